@@ -1,0 +1,205 @@
+/*
+ * lt.h -- C ABI of the LazyTensor fused-execution library for AMD MI355X (gfx950).
+ *
+ * The library implements the hot path of the LazyTensor method (Suhan et al.,
+ * "LazyTensor: combining eager execution with domain-specific compilers"):
+ * tensor operations are recorded into an IR graph instead of being run
+ * (section 3); a barrier cuts the trace of all live tensors (section 4,
+ * barrier and DeviceContextArena paragraphs), canonicalises and hashes it,
+ * looks it up in a compiled-program cache (section 4, caching paragraph) and
+ * runs it as a small number of fused device kernels.
+ *
+ * Conventions
+ *  - Every function returns lt_status (LT_OK = 0).  Nothing throws or aborts.
+ *    On error no state changes and lt_last_error() describes the failure.
+ *  - "device pointer" = address in the HBM of the context's GPU.
+ *    "host pointer"   = ordinary process memory.
+ *  - One thread per lt_ctx.  All operands of an op must belong to the same
+ *    context (no implicit transfers between devices, section 4.1).
+ *  - Tensors are row-major and contiguous.  Shapes have rank <= LT_MAX_RANK.
+ */
+#ifndef LT_H_
+#define LT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LT_MAX_RANK 6
+
+typedef struct lt_ctx lt_ctx;   /* one per device: the paper's DeviceContextArena       */
+typedef uint64_t lt_tensor;     /* unique tensor id (section 4); 0 = invalid; never reused */
+
+typedef enum { LT_F32 = 0, LT_BF16 = 1, LT_I32 = 2, LT_I64 = 3 } lt_dtype;
+
+typedef enum {
+  LT_OK = 0,
+  LT_ERR_ARG = 1,          /* null pointer, bad rank, bad attribute                      */
+  LT_ERR_HANDLE = 2,       /* unknown or released tensor id                              */
+  LT_ERR_SHAPE = 3,        /* operand shapes do not fit the op                           */
+  LT_ERR_DTYPE = 4,        /* operand dtypes do not fit the op                           */
+  LT_ERR_UNSUPPORTED = 5,  /* op or pattern has no lowering (section 4.5 fallback hook)  */
+  LT_ERR_OOM = 6,          /* workspace arena exhausted                                  */
+  LT_ERR_DEVICE = 7        /* HIP runtime error, or compute requested on a null device   */
+} lt_status;
+
+/* Opcodes: the IR stays at framework-op level like the aten:: nodes of figure 1. */
+typedef enum {
+  LT_OP_NEG = 16, LT_OP_ABS, LT_OP_EXP, LT_OP_LOG, LT_OP_TANH, LT_OP_SQRT, LT_OP_RSQRT,
+  LT_OP_RECIP, LT_OP_RELU, LT_OP_GELU, LT_OP_SQUARE, LT_OP_CAST, LT_OP_SIGMOID,
+  LT_OP_ADD = 32,          /* inputs (a, b) or (a, b, alpha): a + alpha*b, alpha rank 0    */
+  LT_OP_SUB, LT_OP_MUL, LT_OP_DIV, LT_OP_MAXIMUM, LT_OP_MINIMUM,
+  LT_OP_RELU_GRAD,         /* (dy, x): dy where x > 0 else 0                                */
+  LT_OP_GELU_GRAD,         /* (dy, x): dy * d gelu(x)/dx, exact (erf) form                  */
+  LT_OP_EXPAND = 48,       /* attrs LT_ATTR_DIM0+i = output dims                             */
+  LT_OP_RESHAPE,           /* attrs LT_ATTR_DIM0+i = output dims                             */
+  LT_OP_PERMUTE,           /* attrs LT_ATTR_DIM0+i = source axis of output axis i            */
+  LT_OP_SUM = 64, LT_OP_AMAX, LT_OP_MEAN, /* attr LT_ATTR_AXIS (last or first axis); none = all */
+  LT_OP_SOFTMAX = 80,      /* (x): softmax over the last axis                                */
+  LT_OP_SOFTMAX_GRAD,      /* (dy, y): y * (dy - sum(dy*y))                                  */
+  LT_OP_LAYER_NORM,        /* (x, gamma, beta), attr LT_ATTR_EPS -> 3 outputs (y, mean, rstd) */
+  LT_OP_LAYER_NORM_GRAD,   /* (dy, x, gamma, mean, rstd) -> dx                               */
+  LT_OP_XENT,              /* (logits[B,C], labels i32[B]) -> f32[B]: logsumexp - picked     */
+  LT_OP_XENT_GRAD,         /* (logits, labels, scale rank 0) -> (softmax - onehot) * scale   */
+  LT_OP_MATMUL = 96        /* (a, b), attrs LT_ATTR_TRANS_A/B, optional LT_ATTR_DTYPE;        */
+                           /* leading axes of a and b equal, or b a plain matrix             */
+} lt_opcode;
+
+typedef enum {
+  LT_ATTR_VALUE = 1, LT_ATTR_DTYPE = 2, LT_ATTR_AXIS = 3, LT_ATTR_EPS = 4,
+  LT_ATTR_TRANS_A = 5, LT_ATTR_TRANS_B = 6, LT_ATTR_DIM0 = 16
+} lt_attr_key;
+
+typedef struct {
+  uint16_t key;        /* lt_attr_key                                  */
+  uint8_t is_float;    /* 1: use f, 0: use i                           */
+  union { int64_t i; double f; } v;
+} lt_attr;
+
+/* flags of lt_tensor_from_device */
+#define LT_DONATABLE 1u /* a barrier may overwrite this buffer in place (section 4.3)    */
+
+typedef struct {
+  uint64_t hash;        /* FNV-1a-64 of the canonical byte string of the cut trace      */
+  uint64_t key_bytes;   /* length of that string (second half of the cache key)         */
+  int32_t cache_hit;    /* 1 if a cached plan was reused                                */
+  int32_t n_nodes;      /* nodes in the cut trace                                       */
+  int32_t n_roots;      /* live tensors that were evaluated                             */
+  int32_t n_regions;    /* fused regions in the plan                                    */
+  int32_t n_launches;   /* kernels launched                                             */
+  uint64_t bytes_planned;  /* algorithmic HBM bytes of the plan (inputs once + outputs once) */
+  uint64_t flops_planned;  /* 2*M*N*K summed over the plan's contractions               */
+  uint64_t ns_collect, ns_hash, ns_lower, ns_launch; /* host time per phase             */
+} lt_barrier_info;
+
+typedef struct {
+  uint64_t barriers, cache_hits, cache_misses;
+  uint64_t nodes_recorded, regions_launched, kernels_launched;
+  uint64_t ns_lowering_total;
+  uint64_t arena_bytes_in_use, arena_bytes_peak;
+  uint64_t live_tensors;
+} lt_stats_t;
+
+/*
+ * Create the context of one device (section 4: one DeviceContextArena per device, alive for
+ * the process).  device >= 0: HIP device ordinal; kernels are launched on `hip_stream`
+ * (a hipStream_t, may be NULL = default stream).  device = -1: a null device named "CPU:0":
+ * it records, hashes, caches and lowers exactly like a real one but launches nothing
+ * (lt_fetch fails with LT_ERR_DEVICE); used to test host logic without a GPU.
+ * workspace: device pointer to `workspace_bytes` of caller-owned memory in which the library
+ * places every tensor a barrier produces and its reduction scratch; BORROWED, must outlive the
+ * context.  For a null device it may be NULL with any size (addresses are then only planned).
+ */
+lt_status lt_init(int device, void* hip_stream, void* workspace, size_t workspace_bytes, lt_ctx** out);
+lt_status lt_shutdown(lt_ctx* ctx);
+
+/*
+ * Factory: wrap existing device data (section 3: every graph starts at a factory method).
+ * dptr: device pointer to a contiguous row-major tensor; BORROWED -- never freed by the
+ * library; the caller keeps it valid until every handle bound to it is released or rebound.
+ * With LT_DONATABLE the buffer may be overwritten in place when the handle is the destination
+ * of lt_assign and nothing else can observe the old value (section 4.3).
+ */
+lt_status lt_tensor_from_device(lt_ctx* ctx, void* dptr, lt_dtype dtype, int rank,
+                                const int64_t* dims, uint32_t flags, lt_tensor* out);
+
+/*
+ * Factory: rank-0 scalar.  Exactly +0 and 1 become constants that are part of the graph's
+ * identity; every other value (including -0.0) is a dynamic parameter that does not change the
+ * hash (section 4.1, special-scalar heuristic).
+ */
+lt_status lt_scalar(lt_ctx* ctx, lt_dtype dtype, double value, lt_tensor* out);
+
+/*
+ * Record one IR-compatible op (section 3): appends a node, runs nothing.  inputs: n_in live
+ * handles; attrs: n_attr attributes; outputs: receives n_out new handles (n_out must equal the
+ * op's output count: 3 for LT_OP_LAYER_NORM, else 1).  Binary ops broadcast like NumPy.
+ */
+lt_status lt_op(lt_ctx* ctx, uint16_t opcode, const lt_tensor* inputs, int n_in,
+                const lt_attr* attrs, int n_attr, lt_tensor* outputs, int n_out);
+
+/* In-place update as substitution (section 4.3): dst now denotes src's computation. */
+lt_status lt_assign(lt_ctx* ctx, lt_tensor dst, lt_tensor src);
+
+/* UnregisterTensor (section 4): the handle dies; its pending computation is no longer a root. */
+lt_status lt_release(lt_ctx* ctx, lt_tensor t);
+
+/*
+ * Barrier (section 4: mark_step / LazyTensorBarrier).  Evaluates the pending computation of
+ * every live tensor: cut, canonical order, hash, cache lookup, lowering on a miss, kernel
+ * launches on the context's stream, then every evaluated handle is rebound to its data.
+ * blocking != 0 waits for the stream.  info may be NULL.
+ */
+lt_status lt_barrier(lt_ctx* ctx, int blocking, lt_barrier_info* info);
+
+/*
+ * IR-incompatible op (section 3): blocking barrier if `t` is pending, then copy its data to
+ * host_dst (host pointer, nbytes must equal the tensor's byte size).
+ */
+lt_status lt_fetch(lt_ctx* ctx, lt_tensor t, void* host_dst, size_t nbytes);
+
+/* Device pointer of a materialised tensor; LT_ERR_HANDLE while it is still pending. */
+lt_status lt_device_ptr(lt_ctx* ctx, lt_tensor t, void** dptr);
+
+/* dtype / rank / dims (dims must have room for LT_MAX_RANK entries); any argument may be NULL. */
+lt_status lt_shape(lt_ctx* ctx, lt_tensor t, lt_dtype* dtype, int* rank, int64_t* dims);
+
+/*
+ * Text form of the pending trace in the layout of figure 1(a) of the paper.  Writes at most
+ * cap bytes (NUL-terminated when cap > 0) and always stores the full length in *len.
+ */
+lt_status lt_dump_ir(lt_ctx* ctx, char* buf, size_t cap, size_t* len);
+
+/* Region list of the plan used by the last barrier, one region per line. Same buffer rules. */
+lt_status lt_dump_plan(lt_ctx* ctx, char* buf, size_t cap, size_t* len);
+
+/* Canonical byte string of the last barrier's trace (what was hashed).  Same buffer rules. */
+lt_status lt_dump_key(lt_ctx* ctx, uint8_t* buf, size_t cap, size_t* len);
+
+lt_status lt_stats(lt_ctx* ctx, lt_stats_t* out);
+
+/*
+ * Per-kernel timing of the last barrier, measured with HIP events on the context's stream
+ * when profiling is on.  lt_set_profiling(ctx, 1) makes every following barrier record events
+ * around each launch; lt_last_launches returns up to cap entries.
+ */
+typedef struct {
+  char kernel[48];       /* kernel family name                              */
+  int32_t region;        /* index of the region in the plan                 */
+  float ms;              /* elapsed device time                             */
+  uint64_t bytes;        /* algorithmic bytes of the region                 */
+  uint64_t flops;        /* 2MNK of the region's contraction (0 otherwise)  */
+} lt_launch_record;
+lt_status lt_set_profiling(lt_ctx* ctx, int on);
+lt_status lt_last_launches(lt_ctx* ctx, lt_launch_record* out, int cap, int* n);
+
+/* Message of the last failure on this context (or of lt_init when ctx is NULL). */
+const char* lt_last_error(lt_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LT_H_ */

@@ -71,7 +71,7 @@ PLAIN_REDUCE = {SUM, AMAX, MEAN}
 ROW_OPS = {SOFTMAX, SOFTMAX_GRAD, LAYER_NORM, LAYER_NORM_GRAD, XENT, XENT_GRAD}
 
 # caps on one fused region
-MAX_INPUTS, MAX_OUTPUTS, MAX_SLOTS, MAX_FINALISER_ELEMS = 12, 8, 32, 65536
+MAX_INPUTS, MAX_OUTPUTS, MAX_SLOTS, MAX_FINALISER_ELEMS = 8, 8, 32, 65536
 
 
 def fnv1a64(data: bytes) -> int:

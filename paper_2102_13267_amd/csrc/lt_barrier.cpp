@@ -1,0 +1,367 @@
+// C ABI, part 2: the barrier (section 4 of the paper: mark_step / LazyTensorBarrier) and fetch.
+// Cut the trace of all live tensors, number it canonically, serialise, hash, look up the plan
+// cache, lower on a miss, patch the cached launch arguments with this step's pointers and
+// scalars, launch, and rebind every evaluated handle to its data.
+#include <hip/hip_runtime_api.h>
+
+#include <chrono>
+#include <cmath>
+#include <cstdio>
+
+#include "lt_core.h"
+#include "lt_launch.h"
+
+namespace lt {
+
+static uint64_t now_ns() {
+  return (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
+             std::chrono::steady_clock::now().time_since_epoch())
+      .count();
+}
+
+uint64_t fnv1a64(const uint8_t* p, size_t n) {
+  uint64_t h = 0xcbf29ce484222325ull;
+  for (size_t i = 0; i < n; ++i) {
+    h ^= p[i];
+    h *= 0x100000001b3ull;
+  }
+  return h;
+}
+
+// Roots: live handles with a pending computation, ascending tensor id.  Canonical order:
+// post-order from each root in turn, operands visited from last to first, every node once --
+// the numbering that reproduces figures 1, 2 and 3 of the paper.
+void collect_cut(lt_ctx* ctx, Cut* cut) {
+  cut->roots.clear();
+  cut->order.clear();
+  cut->index_of.assign(ctx->nodes.size(), -1);
+  for (auto& kv : ctx->handles)
+    if (kv.second.kind == H_PENDING) cut->roots.push_back(&kv.second);
+  std::vector<std::pair<int32_t, bool>> stack;
+  for (Handle* r : cut->roots) {
+    if (cut->index_of[r->node] >= 0) continue;
+    stack.push_back({r->node, false});
+    while (!stack.empty()) {
+      auto [n, expanded] = stack.back();
+      stack.pop_back();
+      if (cut->index_of[n] >= 0) continue;
+      if (expanded) {
+        cut->index_of[n] = (int32_t)cut->order.size();
+        cut->order.push_back(n);
+        continue;
+      }
+      stack.push_back({n, true});
+      const Node& node = ctx->nodes[n];
+      for (int k = 0; k < node.n_in; ++k)   // pushed first to last => popped last to first
+        if (cut->index_of[node.ins[k].node] < 0) stack.push_back({node.ins[k].node, false});
+    }
+  }
+}
+
+template <class T>
+static void put(std::vector<uint8_t>* out, T v) {
+  const uint8_t* p = (const uint8_t*)&v;   // gfx950 hosts are little-endian x86-64
+  out->insert(out->end(), p, p + sizeof(T));
+}
+
+// Canonical little-endian byte string.  Buffer addresses and the values of dynamic scalars are
+// left out; shapes, dtypes, attributes, operand indices, parameter ordinals, the root list and
+// the donation pattern are in.
+void serialise_cut(lt_ctx* ctx, Cut* cut, std::vector<uint8_t>* out) {
+  out->clear();
+  cut->param_nodes.clear();
+  cut->scalar_nodes.clear();
+  std::unordered_map<const Buffer*, uint32_t> param_of_buffer;
+  for (int32_t idx : cut->order) {
+    const Node& n = ctx->nodes[idx];
+    put<uint16_t>(out, n.op);
+    put<uint8_t>(out, n.dtype);
+    put<uint8_t>(out, n.rank);
+    for (int d = 0; d < n.rank; ++d) put<int64_t>(out, n.dims[d]);
+    put<uint8_t>(out, n.n_attr);
+    for (int k = 0; k < n.n_attr; ++k) {
+      put<uint16_t>(out, n.attrs[k].key);
+      put<uint8_t>(out, n.attrs[k].is_float);
+      if (n.attrs[k].is_float) put<double>(out, n.attrs[k].v.f);
+      else put<int64_t>(out, n.attrs[k].v.i);
+    }
+    put<uint8_t>(out, n.n_in);
+    for (int k = 0; k < n.n_in; ++k) {
+      put<uint32_t>(out, (uint32_t)cut->index_of[n.ins[k].node]);
+      put<uint8_t>(out, (uint8_t)n.ins[k].slot);
+    }
+    if (n.op == OP_DEVICE_DATA) {
+      put<uint32_t>(out, (uint32_t)cut->param_nodes.size());
+      param_of_buffer.emplace(n.buffer.get(), (uint32_t)cut->param_nodes.size());
+      cut->param_nodes.push_back(idx);
+    } else if (n.op == OP_SCALAR_PARAM) {
+      put<uint32_t>(out, (uint32_t)cut->scalar_nodes.size());
+      cut->scalar_nodes.push_back(idx);
+    }
+  }
+  put<uint32_t>(out, (uint32_t)cut->roots.size());
+  cut->donors.assign(cut->roots.size(), 0xFFFFFFFFu);
+  std::vector<const Buffer*> claimed;
+  for (size_t r = 0; r < cut->roots.size(); ++r) {
+    const Handle* h = cut->roots[r];
+    uint32_t d = 0xFFFFFFFFu;
+    const Buffer* b = h->donor.get();
+    if (b) {
+      auto it = param_of_buffer.find(b);
+      bool taken = false;
+      for (const Buffer* c : claimed) taken |= (c == b);
+      const size_t bytes = (size_t)numel(h->dims, h->rank) * dtype_size(h->dtype);
+      // the donor must be a parameter of this graph, seen by no live handle, of the same
+      // dtype and shape (hence byte size) as the value that replaces it
+      const Node* leaf = it != param_of_buffer.end() ? &ctx->nodes[cut->param_nodes[it->second]] : nullptr;
+      bool same = leaf && leaf->dtype == h->dtype && leaf->rank == h->rank && b->bytes == bytes;
+      if (same)
+        for (int i = 0; i < h->rank; ++i) same &= leaf->dims[i] == h->dims[i];
+      if (same && !taken && b->data_refs == 0) {
+        d = it->second;
+        claimed.push_back(b);
+      }
+    }
+    cut->donors[r] = d;
+    put<uint32_t>(out, (uint32_t)cut->index_of[h->node]);
+    put<uint8_t>(out, (uint8_t)h->slot);
+    put<uint32_t>(out, d);
+  }
+}
+
+static lt_status hip_fail(lt_ctx* ctx, const char* what, hipError_t e) {
+  return fail(ctx, LT_ERR_DEVICE, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+static hipError_t launch_one(const Launch& l, const uint8_t* args, hipStream_t s) {
+  switch (l.kind) {
+    case L_EW: return ltk::launch_ew(*(const ltk::EwArgs*)args, l.grid_x, s);
+    case L_ROW: return ltk::launch_row_reduce(*(const ltk::RowArgs*)args, l.grid_x, s);
+    case L_ALL: return ltk::launch_all_reduce(*(const ltk::AllArgs*)args, l.grid_x, s);
+    case L_COL: return ltk::launch_col_reduce(*(const ltk::ColArgs*)args, l.grid_x, l.grid_y, s);
+    case L_ROWOP: return ltk::launch_row_op(*(const ltk::RowOpArgs*)args, l.grid_x, s);
+    case L_GEMM: return ltk::launch_gemm(*(const ltk::GemmArgs*)args, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+static const char* kind_name(LaunchKind k) {
+  switch (k) {
+    case L_EW: return "lt_ew_kernel";
+    case L_ROW: return "lt_row_reduce_kernel";
+    case L_ALL: return "lt_all_reduce_kernel";
+    case L_COL: return "lt_col_reduce_kernel";
+    case L_ROWOP: return "lt_row_op_kernel";
+    case L_GEMM: return "lt_gemm_kernel";
+  }
+  return "?";
+}
+
+// Bind this step's buffers and scalars into the cached plan and launch it.
+static lt_status execute(lt_ctx* ctx, Plan* plan, const Cut& cut, std::vector<BufRef>* storage_bufs) {
+  const size_t ns = plan->storages.size();
+  storage_bufs->assign(ns, nullptr);
+  std::vector<void*> ptr(ns, nullptr);
+  for (size_t s = 0; s < ns; ++s) {
+    const Storage& st = plan->storages[s];
+    if (st.param >= 0) {
+      (*storage_bufs)[s] = ctx->nodes[cut.param_nodes[st.param]].buffer;
+      ptr[s] = (*storage_bufs)[s]->ptr;
+    }
+  }
+  // fresh storages are taken from the arena for their whole plan lifetime; temporaries go back
+  // as soon as the last launch that touches them is enqueued (one stream: reuse is ordered)
+  std::vector<std::vector<size_t>> born(plan->launches.size() + 1), dies(plan->launches.size() + 1);
+  for (size_t s = 0; s < ns; ++s) {
+    const Storage& st = plan->storages[s];
+    if (st.param >= 0) continue;
+    born[st.first_launch].push_back(s);
+    if (!st.bound_to_root) dies[st.last_launch].push_back(s);
+  }
+  const bool real = ctx->device >= 0;
+  const bool prof = real && ctx->profiling;
+  ctx->last_launches.clear();
+  if (prof) {
+    while (ctx->events.size() < 2 * plan->launches.size()) {
+      hipEvent_t e;
+      hipError_t err = hipEventCreate(&e);
+      if (err != hipSuccess) return hip_fail(ctx, "hipEventCreate", err);
+      ctx->events.push_back(e);
+    }
+  }
+  std::vector<uint8_t> args;
+  size_t pp = 0, sp = 0;
+  for (size_t li = 0; li < plan->launches.size(); ++li) {
+    const Launch& l = plan->launches[li];
+    for (size_t s : born[li]) {
+      auto b = std::make_shared<Buffer>();
+      b->ptr = ctx->arena.alloc(plan->storages[s].bytes);
+      if (!b->ptr) return fail(ctx, LT_ERR_OOM, "workspace arena exhausted while running a plan");
+      b->bytes = plan->storages[s].bytes;
+      b->owned = true;
+      b->donatable = true;   // library-owned memory may always be reused in place
+      b->arena = &ctx->arena;
+      (*storage_bufs)[s] = b;
+      ptr[s] = b->ptr;
+    }
+    args = l.args;
+    for (; pp < plan->ptr_patches.size() && plan->ptr_patches[pp].launch == li; ++pp) {
+      const PtrPatch& p = plan->ptr_patches[pp];
+      void* v = (uint8_t*)ptr[p.storage] + p.byte_offset;
+      std::memcpy(args.data() + p.offset, &v, sizeof(void*));
+    }
+    for (; sp < plan->scal_patches.size() && plan->scal_patches[sp].launch == li; ++sp) {
+      const ScalPatch& p = plan->scal_patches[sp];
+      double v = ctx->nodes[cut.scalar_nodes[p.scalar]].value;
+      float f = (float)(p.reciprocal ? 1.0 / v : v);
+      std::memcpy(args.data() + p.offset, &f, sizeof(float));
+    }
+    if (real) {
+      if (l.kind == L_ALL) {
+        ltk::AllArgs* a = (ltk::AllArgs*)args.data();
+        a->partials = ctx->red_partials;
+        a->ticket = ctx->red_tickets;
+      } else if (l.kind == L_COL) {
+        ltk::ColArgs* a = (ltk::ColArgs*)args.data();
+        a->partials = ctx->red_partials;
+        a->tickets = ctx->red_tickets;
+      }
+      if (prof) (void)hipEventRecord(ctx->events[2 * li], ctx->stream);
+      hipError_t e = launch_one(l, args.data(), ctx->stream);
+      if (e != hipSuccess) return hip_fail(ctx, kind_name(l.kind), e);
+      if (prof) (void)hipEventRecord(ctx->events[2 * li + 1], ctx->stream);
+    }
+    for (size_t s : dies[li]) {
+      (*storage_bufs)[s].reset();
+      ptr[s] = nullptr;
+    }
+    ctx->stats.kernels_launched++;
+  }
+  if (prof) {
+    hipError_t e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) return hip_fail(ctx, "hipStreamSynchronize", e);
+    for (size_t li = 0; li < plan->launches.size(); ++li) {
+      lt_launch_record r{};
+      std::snprintf(r.kernel, sizeof(r.kernel), "%s", kind_name(plan->launches[li].kind));
+      r.region = plan->launches[li].region;
+      (void)hipEventElapsedTime(&r.ms, ctx->events[2 * li], ctx->events[2 * li + 1]);
+      r.bytes = plan->launches[li].bytes;
+      r.flops = plan->launches[li].flops;
+      ctx->last_launches.push_back(r);
+    }
+  }
+  return LT_OK;
+}
+
+}  // namespace lt
+
+using namespace lt;
+
+extern "C" {
+
+lt_status lt_barrier(lt_ctx* ctx, int blocking, lt_barrier_info* info) {
+  if (!ctx) return LT_ERR_ARG;
+  const uint64_t t0 = now_ns();
+  Cut cut;
+  collect_cut(ctx, &cut);
+  std::vector<uint8_t> key;
+  serialise_cut(ctx, &cut, &key);
+  const uint64_t t1 = now_ns();
+  const uint64_t h = fnv1a64(key.data(), key.size());
+  Plan* plan = nullptr;
+  auto& bucket = ctx->cache[h];
+  for (auto& p : bucket)
+    if (p->key.size() == key.size() && std::memcmp(p->key.data(), key.data(), key.size()) == 0) plan = p.get();
+  const uint64_t t2 = now_ns();
+  const bool hit = plan != nullptr;
+  if (!hit) {
+    lt_status st = LT_OK;
+    std::unique_ptr<Plan> fresh = lower(ctx, cut, &st);
+    if (!fresh) {
+      if (bucket.empty()) ctx->cache.erase(h);
+      return st;
+    }
+    fresh->key = key;
+    plan = fresh.get();
+    bucket.push_back(std::move(fresh));
+  }
+  const uint64_t t3 = now_ns();
+  std::vector<BufRef> bufs;
+  lt_status st = execute(ctx, plan, cut, &bufs);
+  if (st != LT_OK) return st;
+  // result binding: after the barrier every evaluated handle is plain data (or a scalar when
+  // folding reduced it to one); a new IR graph starts (section 3)
+  for (size_t r = 0; r < cut.roots.size(); ++r) {
+    Handle* hd = cut.roots[r];
+    const RootBind& rb = plan->roots[r];
+    hd->node = -1;
+    hd->slot = 0;
+    if (rb.kind == RootBind::SCALAR || rb.kind == RootBind::CONST) {
+      hd->kind = H_SCALAR;
+      hd->value = rb.kind == RootBind::CONST ? rb.value : ctx->nodes[cut.scalar_nodes[rb.index]].value;
+      continue;
+    }
+    hd->kind = H_DATA;
+    hd->buf = rb.kind == RootBind::PARAM_ALIAS ? ctx->nodes[cut.param_nodes[rb.index]].buffer : bufs[rb.index];
+    hd->buf->data_refs += 1;
+  }
+  for (auto& kv : ctx->handles) kv.second.donor.reset();
+  bufs.clear();
+  ctx->nodes.clear();
+  ctx->epoch++;
+  const uint64_t t4 = now_ns();
+  if (blocking && ctx->device >= 0) {
+    hipError_t e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) return fail(ctx, LT_ERR_DEVICE, std::string("hipStreamSynchronize: ") + hipGetErrorString(e));
+  }
+  ctx->last_plan = plan;
+  ctx->last_key.swap(key);
+  ctx->stats.barriers++;
+  (hit ? ctx->stats.cache_hits : ctx->stats.cache_misses)++;
+  ctx->stats.regions_launched += plan->n_regions;
+  if (!hit) ctx->stats.ns_lowering_total += t3 - t2;
+  if (info) {
+    info->hash = h;
+    info->key_bytes = ctx->last_key.size();
+    info->cache_hit = hit ? 1 : 0;
+    info->n_nodes = (int32_t)cut.order.size();
+    info->n_roots = (int32_t)cut.roots.size();
+    info->n_regions = plan->n_regions;
+    info->n_launches = (int32_t)plan->launches.size();
+    info->bytes_planned = plan->bytes_planned;
+    info->flops_planned = plan->flops_planned;
+    info->ns_collect = t1 - t0;
+    info->ns_hash = t2 - t1;
+    info->ns_lower = t3 - t2;
+    info->ns_launch = t4 - t3;
+  }
+  return LT_OK;
+}
+
+lt_status lt_fetch(lt_ctx* ctx, lt_tensor t, void* host_dst, size_t nbytes) {
+  if (!ctx || !host_dst) return LT_ERR_ARG;
+  auto it = ctx->handles.find(t);
+  if (it == ctx->handles.end()) return fail(ctx, LT_ERR_HANDLE, "lt_fetch: unknown or released tensor id");
+  if (it->second.kind == H_PENDING) {
+    lt_status st = lt_barrier(ctx, 1, nullptr);
+    if (st != LT_OK) return st;
+    it = ctx->handles.find(t);
+  }
+  Handle& h = it->second;
+  const size_t bytes = (size_t)numel(h.dims, h.rank) * dtype_size(h.dtype);
+  if (nbytes != bytes) return fail(ctx, LT_ERR_ARG, "lt_fetch: nbytes does not match the tensor");
+  if (h.kind == H_SCALAR) {
+    if (h.dtype == LT_F32) { float v = (float)h.value; std::memcpy(host_dst, &v, 4); }
+    else if (h.dtype == LT_I32) { int32_t v = (int32_t)h.value; std::memcpy(host_dst, &v, 4); }
+    else if (h.dtype == LT_I64) { int64_t v = (int64_t)h.value; std::memcpy(host_dst, &v, 8); }
+    else { float f = (float)h.value; uint32_t u; std::memcpy(&u, &f, 4); uint16_t b = (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16); std::memcpy(host_dst, &b, 2); }
+    return LT_OK;
+  }
+  if (ctx->device < 0) return fail(ctx, LT_ERR_DEVICE, "lt_fetch: a null device holds no data");
+  hipError_t e = hipMemcpyAsync(host_dst, h.buf->ptr, bytes, hipMemcpyDeviceToHost, ctx->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) return fail(ctx, LT_ERR_DEVICE, std::string("lt_fetch: ") + hipGetErrorString(e));
+  return LT_OK;
+}
+
+}  // extern "C"

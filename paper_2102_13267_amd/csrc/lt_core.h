@@ -1,0 +1,197 @@
+// Internal host-side data structures of the LazyTensor library: IR nodes, tensor handles,
+// device buffers, the workspace arena, cached plans and the context (the paper's
+// DeviceContextArena, section 4).
+#ifndef LT_CORE_H_
+#define LT_CORE_H_
+
+#include <hip/hip_runtime_api.h>
+
+#include <cstdint>
+#include <cstring>
+#include <map>
+#include <memory>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "../../include/lt.h"
+#include "lt_kernels.h"
+
+namespace lt {
+
+// node kinds that the public opcode enum does not list (leaves)
+enum : uint16_t { OP_DEVICE_DATA = 1, OP_SCALAR_PARAM = 2, OP_CONSTANT = 3 };
+
+constexpr int kMaxAttrs = 8;
+constexpr int kMaxIns = 5;
+
+// caps on one fused region (part of the partition rules)
+constexpr int kMaxRegionInputs = 8;
+constexpr int kMaxRegionOutputs = 8;
+constexpr int kMaxRegionSlots = 32;
+constexpr int64_t kMaxFinaliserElems = 65536;
+
+struct Arena;
+
+// A device buffer.  Borrowed buffers belong to the caller; owned ones are carved out of the
+// workspace arena and return to it when the last reference goes away.
+struct Buffer {
+  void* ptr = nullptr;
+  size_t bytes = 0;
+  bool owned = false;
+  bool donatable = false;
+  int data_refs = 0;   // live handles currently bound to this buffer
+  Arena* arena = nullptr;
+  ~Buffer();
+};
+using BufRef = std::shared_ptr<Buffer>;
+
+// First-fit free-list allocator over the caller's workspace (256-byte granules).
+struct Arena {
+  uintptr_t base = 0;
+  size_t size = 0;
+  std::map<uintptr_t, size_t> free_blocks;   // offset -> length
+  std::unordered_map<uintptr_t, size_t> used;  // offset -> length
+  size_t in_use = 0, peak = 0;
+  void init(void* p, size_t bytes);
+  void* alloc(size_t bytes);   // nullptr when exhausted
+  void release(void* p);
+};
+
+struct Attr {
+  uint16_t key;
+  uint8_t is_float;
+  union { int64_t i; double f; } v;
+};
+
+struct Val {
+  int32_t node;
+  int32_t slot;
+  bool operator==(const Val& o) const { return node == o.node && slot == o.slot; }
+  bool operator!=(const Val& o) const { return !(*this == o); }
+};
+
+struct Node {
+  uint16_t op = 0;
+  uint8_t dtype = 0, rank = 0, n_attr = 0, n_in = 0, n_out = 1;
+  int64_t dims[LT_MAX_RANK] = {0};
+  Attr attrs[kMaxAttrs];
+  Val ins[kMaxIns];
+  BufRef buffer;       // OP_DEVICE_DATA
+  double value = 0;    // OP_SCALAR_PARAM: the dynamic value (not part of the graph's identity)
+};
+
+enum HandleKind : uint8_t { H_PENDING = 0, H_DATA = 1, H_SCALAR = 2 };
+
+struct Handle {
+  uint64_t id = 0;
+  HandleKind kind = H_DATA;
+  uint8_t dtype = 0, rank = 0;
+  int64_t dims[LT_MAX_RANK] = {0};
+  int32_t node = -1, slot = 0;    // H_PENDING
+  BufRef buf;                     // H_DATA
+  double value = 0;               // H_SCALAR
+  BufRef donor;                   // buffer this handle gave up through lt_assign
+  uint64_t memo_epoch = ~0ull;    // leaf node created for this handle in the current trace
+  int32_t memo_node = -1;
+};
+
+// ---- a lowered, cached program ------------------------------------------------------------
+
+enum LaunchKind : uint8_t { L_EW, L_ROW, L_ALL, L_COL, L_ROWOP, L_GEMM };
+
+struct Storage {
+  int param = -1;        // >= 0: the buffer of device parameter `param` (input, or donated output)
+  size_t bytes = 0;      // param < 0: a fresh arena allocation of this size
+  int first_launch = 0, last_launch = 0;
+  bool bound_to_root = false;
+};
+
+struct PtrPatch {
+  uint32_t launch, offset;   // byte offset of a pointer field inside the launch's argument block
+  int32_t storage;
+  int64_t byte_offset;
+};
+
+struct ScalPatch {
+  uint32_t launch, offset;   // byte offset of a float inside the argument block
+  int32_t scalar;            // scalar parameter ordinal
+  uint8_t reciprocal;        // 1: store 1/value
+};
+
+struct Launch {
+  LaunchKind kind;
+  int32_t region;
+  uint32_t grid_x = 1, grid_y = 1;
+  std::vector<uint8_t> args;
+  uint64_t bytes = 0, flops = 0;
+};
+
+struct RootBind {
+  enum Kind : uint8_t { STORAGE, PARAM_ALIAS, SCALAR, CONST } kind = STORAGE;
+  int32_t index = -1;        // storage / param ordinal / scalar ordinal
+  double value = 0;          // CONST
+};
+
+struct Plan {
+  std::vector<uint8_t> key;
+  std::string text;
+  int n_params = 0, n_scalars = 0, n_regions = 0;
+  std::vector<Storage> storages;
+  std::vector<Launch> launches;
+  std::vector<PtrPatch> ptr_patches;
+  std::vector<ScalPatch> scal_patches;
+  std::vector<RootBind> roots;
+  uint64_t bytes_planned = 0, flops_planned = 0;
+};
+
+}  // namespace lt
+
+struct lt_ctx {
+  int device = -1;
+  hipStream_t stream = nullptr;
+  std::string device_name;
+  lt::Arena arena;
+  std::vector<lt::Node> nodes;               // the trace being recorded (flat arena, indices not pointers)
+  std::map<uint64_t, lt::Handle> handles;    // live tensors by id
+  uint64_t next_id = 1, epoch = 0;
+  std::unordered_map<uint64_t, std::vector<std::unique_ptr<lt::Plan>>> cache;
+  lt::Plan* last_plan = nullptr;
+  std::vector<uint8_t> last_key;
+  lt_stats_t stats{};
+  std::string err;
+  float* red_partials = nullptr;             // reduction scratch inside the workspace
+  uint32_t* red_tickets = nullptr;
+  bool profiling = false;
+  std::vector<lt_launch_record> last_launches;
+  std::vector<hipEvent_t> events;
+};
+
+namespace lt {
+
+constexpr size_t kPartialFloats = 1 << 16;   // reduction partials
+constexpr size_t kTickets = 1024;
+
+lt_status fail(lt_ctx* ctx, lt_status code, const std::string& msg);
+size_t dtype_size(uint8_t dtype);
+const char* dtype_name(uint8_t dtype);
+const char* op_name(uint16_t op);
+int64_t numel(const int64_t* dims, int rank);
+
+// barrier pieces (lt_barrier.cpp)
+struct Cut {
+  std::vector<Handle*> roots;
+  std::vector<int32_t> order;       // canonical position -> node index
+  std::vector<int32_t> index_of;    // node index -> canonical position (-1: not in the cut)
+  std::vector<uint32_t> donors;     // per root: donated parameter ordinal or 0xFFFFFFFF
+  std::vector<int32_t> param_nodes, scalar_nodes;   // ordinal -> node index
+};
+void collect_cut(lt_ctx* ctx, Cut* cut);
+void serialise_cut(lt_ctx* ctx, Cut* cut, std::vector<uint8_t>* out);
+uint64_t fnv1a64(const uint8_t* p, size_t n);
+
+// lowering (lt_lower.cpp): returns nullptr and sets ctx->err / *status on failure
+std::unique_ptr<Plan> lower(lt_ctx* ctx, const Cut& cut, lt_status* status);
+
+}  // namespace lt
+#endif  // LT_CORE_H_

@@ -1,0 +1,146 @@
+// Kernel argument blocks shared by the host lowering pass and the HIP kernels.
+//
+// Every fused region is run by one kernel family.  What varies per region -- the
+// elementwise chain -- is not compiled: it is a small bytecode program that lives in
+// the kernel-argument segment (read through scalar loads) and is interpreted with the
+// value slots held in vector registers.  The paper leaves code generation to its
+// backend compiler (section 4, "lowering"); this build replaces that compiler with an
+// interpreter so that a cache miss costs microseconds, not a JIT run.
+#ifndef LT_KERNELS_H_
+#define LT_KERNELS_H_
+
+#include <stdint.h>
+
+namespace ltk {
+
+constexpr int kMaxIn = 8;       // array inputs of one program
+constexpr int kMaxOut = 8;      // outputs of one program
+constexpr int kMaxScal = 32;    // scalar table: dynamic scalars and immediates
+constexpr int kMaxCode = 48;    // instructions
+constexpr int kSlots = 32;      // value slots a program may name (kernels hold 16 or 32)
+constexpr int kVec = 4;         // elements handled per lane and interpreted instruction
+
+// device dtypes of loads / stores
+enum : uint32_t { kF32 = 0, kBF16 = 1, kI32 = 2, kI64 = 3 };
+
+// how an input is addressed from the flat index i of the iteration space [rows, cols]
+enum : uint32_t {
+  kFull = 0,     // element i
+  kRowVec = 1,   // element i % cols   (a vector broadcast along rows, e.g. a bias)
+  kColVec = 2,   // element i / cols   (one value per row)
+  kScalar = 3,   // element 0
+  kStrided = 4   // sum_k coord_k(i) * stride[k] over the (<= 4-d) iteration space
+};
+
+// interpreter opcodes
+enum : uint32_t {
+  kMov = 0, kNeg, kAbs, kExp, kLog, kTanh, kSqrt, kRsqrt, kRecip, kRelu, kGelu, kSquare,
+  kSigmoid, kRoundBf16,
+  kAdd, kSub, kMul, kDiv, kMax, kMin, kReluGrad, kGeluGrad,
+  kFma,          // a*b + c
+  kNumOps
+};
+
+// instruction word: op[7:0] dst[12:8] a[18:13] b[24:19] c[30:25];
+// operand < 32: value slot; operand >= 32: scal[operand - 32]
+inline uint32_t encode(uint32_t op, uint32_t dst, uint32_t a, uint32_t b = 0, uint32_t c = 0) {
+  return op | (dst << 8) | (a << 13) | (b << 19) | (c << 25);
+}
+
+struct EwIn {
+  const void* ptr;
+  uint32_t mode;
+  uint32_t dtype;
+  int64_t stride[4];   // kStrided only, in elements
+};
+
+struct EwOut {
+  void* ptr;
+  uint32_t dtype;
+  uint32_t slot;       // value slot stored
+  uint32_t scalar;     // 1: a rank-0 result, written once (by flat index 0)
+  uint32_t pad;
+};
+
+struct EwProg {
+  uint32_t n_in, n_out, n_code, anchor_slot;  // anchor_slot: where a reduction / GEMM result enters
+  uint32_t vec_ok;     // 1: cols % 4 == 0, so a 4-vector never straddles a row
+  uint32_t full_vec_ok;  // 1: every 4-vector of the flat space starts at a multiple of 4
+  uint32_t cols;       // last dimension of the iteration space (>= 1)
+  uint32_t n_slots;    // value slots the program uses (selects the 16- or 32-slot kernel)
+  uint64_t n;          // elements of the iteration space
+  uint32_t dims[4];    // iteration space collapsed to 4 dims (kStrided addressing)
+  EwIn in[kMaxIn];
+  EwOut out[kMaxOut];
+  float scal[kMaxScal];
+  uint32_t code[kMaxCode];
+};
+
+// ---- elementwise region -----------------------------------------------------------
+struct EwArgs {
+  EwProg prog;
+};
+
+// ---- reductions ---------------------------------------------------------------------
+enum : uint32_t { kRedSum = 0, kRedMax = 1, kRedMean = 2 };
+
+// row reduction: out[r] = post(reduce_c pro(x[r, c]))
+struct RowArgs {
+  EwProg pro;          // iteration space [rows, cols]; its result is slot pro.anchor_slot
+  EwProg post;         // iteration space [rows]
+  uint32_t rows, cols, red, threads_per_row;
+};
+
+// global reduction, single launch: per-workgroup partials, the last workgroup to finish
+// combines them, then runs the post program (scalar epilogue and optional finaliser)
+struct AllArgs {
+  EwProg pro;          // iteration space = the reduced tensor, flat
+  EwProg post;         // iteration space: 1 element, or the finaliser's shape
+  float* partials;     // [gridDim.x]
+  uint32_t* ticket;    // zero before launch; reset by the kernel
+  uint32_t red, pad;
+  uint64_t count;      // elements reduced (for mean)
+};
+
+// column reduction over axis 0 of [rows, cols]
+struct ColArgs {
+  EwProg pro;          // iteration space [rows, cols]
+  EwProg post;         // iteration space [cols]
+  float* partials;     // [gridDim.y, cols]
+  uint32_t* tickets;   // [gridDim.x], zero before launch; reset by the kernel
+  uint32_t rows, cols, red, pad;
+};
+
+// ---- row operators with a fixed body ---------------------------------------------------
+enum : uint32_t { kSoftmax = 0, kSoftmaxGrad, kLayerNorm, kLayerNormGrad, kXent, kXentGrad };
+
+struct RowOpArgs {
+  uint32_t op, rows, cols, threads_per_row;
+  const void* in[5];
+  uint32_t in_dtype[5];
+  void* out[3];
+  uint32_t out_dtype[3];
+  float eps;           // layer norm
+  float scale;         // xent_grad
+};
+
+// ---- contraction ------------------------------------------------------------------------
+// C[b] = post(A[b] * B[b]); A is M x K, B is K x N, element (i, j) of an operand is at
+// base + b0*sb0 + b1*sb1 + i*s_row + j*s_col (element strides), so transposes, batched
+// operands and head-split layouts are all addressing, never copies.
+struct GemmOperand {
+  const void* ptr;
+  int64_t s_row, s_col, s_b0, s_b1;
+};
+
+struct GemmArgs {
+  GemmOperand a, b;
+  uint32_t m, n, k;
+  uint32_t batch0, batch1;   // batch = batch0 * batch1 (b = b0 * batch1 + b1)
+  uint32_t in_dtype;         // kF32 or kBF16 (both operands)
+  uint32_t tiles_m, tiles_n;
+  EwProg post;               // iteration space [batch * m, n] of the output
+};
+
+}  // namespace ltk
+#endif  // LT_KERNELS_H_

@@ -1,0 +1,17 @@
+// Host-callable launchers of the kernel families (defined in the .hip files).
+#ifndef LT_LAUNCH_H_
+#define LT_LAUNCH_H_
+
+#include <hip/hip_runtime_api.h>
+
+#include "lt_kernels.h"
+
+namespace ltk {
+hipError_t launch_ew(const EwArgs& a, uint32_t grid, hipStream_t s);
+hipError_t launch_row_reduce(const RowArgs& a, uint32_t grid, hipStream_t s);
+hipError_t launch_all_reduce(const AllArgs& a, uint32_t grid, hipStream_t s);
+hipError_t launch_col_reduce(const ColArgs& a, uint32_t grid_x, uint32_t grid_y, hipStream_t s);
+hipError_t launch_row_op(const RowOpArgs& a, uint32_t grid, hipStream_t s);
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
+}  // namespace ltk
+#endif

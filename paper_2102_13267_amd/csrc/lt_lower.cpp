@@ -1,0 +1,1251 @@
+// Lowering of a cut trace into a cached plan (runs on a cache miss only).
+//
+// The paper hands the trace to a domain-specific compiler (section 4: op lowerings, compile,
+// cache).  Here the "compiler" is: fold the special scalars 0 and 1 (section 4.1), partition the
+// DAG into fused regions, emit one bytecode program per elementwise chain, plan buffers with
+// input/output donation (section 4.3) and pre-build the kernel argument blocks.  No code is
+// generated, so a miss costs microseconds.
+//
+// Partition rules (deterministic; an independent implementation must produce the same list):
+//   classes   LEAF (device_data, scalar, constant), VIEW (expand / reshape that is not a root),
+//             EW (elementwise, permute, root views), ROW / COL / ALL (reductions by axis; the
+//             fixed row operators are ROW), MM (matmul).
+//   pass 0    every live EW / ROW / COL / ALL / MM node is a region of its own.
+//   pass 1    plain reductions absorb, walking down from the anchor, every elementwise node of the
+//             reduced tensor's shape whose users all lie inside the region (prologue).
+//   pass 2    in canonical order each still-single elementwise node joins the region of one of
+//             its producers: an anchored region as epilogue (same shape as the anchor's result;
+//             a global reduction also takes a "finaliser" of <= 65536 elements), else elementwise
+//             regions of equal shape are merged; never through a view, never if the region graph
+//             would get a cycle, never beyond the caps (8 inputs, 8 outputs, inputs + members <= 32).
+//   pass 3    donation: a root may overwrite its donated input when all other readers can be
+//             ordered first (ordering edges are added) and the writer reads it index-aligned.
+//   pass 4    regions run in topological order, smallest id (anchor, else first member) first.
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <functional>
+#include <set>
+
+#include "lt_core.h"
+
+namespace lt {
+namespace {
+
+enum Class : uint8_t { C_DEAD, C_LEAF, C_VIEW, C_EW, C_ROW, C_COL, C_ALL, C_MM };
+
+struct Region {
+  Class kind;
+  int32_t anchor;                 // canonical index or -1
+  std::vector<int32_t> members;   // sorted canonical indices
+  bool has_fin = false;
+  std::vector<int64_t> fin_shape;
+  std::vector<Region*> extra_succ;   // ordering-only edges added by donation
+  bool alive = true;
+  int32_t id() const { return anchor >= 0 ? anchor : members.front(); }
+  bool has(int32_t m) const { return std::binary_search(members.begin(), members.end(), m); }
+};
+
+struct Lowering {
+  lt_ctx* ctx;
+  const Cut& cut;
+  int32_t N;
+  std::vector<const Node*> nd;
+  std::vector<std::vector<Val>> rins;       // operands after folding (canonical indices)
+  std::vector<Val> fwd;                     // node -> replacement (node == -1: none)
+  std::vector<Val> root_vals;
+  std::vector<Class> cls;
+  std::vector<char> live, is_root;
+  std::vector<std::vector<int32_t>> users;
+  std::vector<std::unique_ptr<Region>> pool;
+  std::vector<Region*> region_of;
+  std::vector<Region*> ordered;
+  std::string err;
+  lt_status status = LT_OK;
+
+  explicit Lowering(lt_ctx* c, const Cut& k) : ctx(c), cut(k), N((int32_t)k.order.size()) {}
+
+  bool bad(lt_status s, const std::string& m) {
+    if (status == LT_OK) {
+      status = s;
+      err = m;
+    }
+    return false;
+  }
+
+  // ---- value helpers -----------------------------------------------------------------------
+  int out_rank(Val v) const {
+    const Node* n = nd[v.node];
+    return (n->op == LT_OP_LAYER_NORM && v.slot > 0) ? n->rank - 1 : n->rank;
+  }
+  std::vector<int64_t> out_shape(Val v) const {
+    const Node* n = nd[v.node];
+    return std::vector<int64_t>(n->dims, n->dims + out_rank(v));
+  }
+  uint8_t out_dtype(Val v) const {
+    const Node* n = nd[v.node];
+    return (n->op == LT_OP_LAYER_NORM && v.slot > 0) ? (uint8_t)LT_F32 : n->dtype;
+  }
+  std::vector<int64_t> shape_of(int32_t i) const { return std::vector<int64_t>(nd[i]->dims, nd[i]->dims + nd[i]->rank); }
+  static int64_t count(const std::vector<int64_t>& s) {
+    int64_t n = 1;
+    for (int64_t d : s) n *= d;
+    return n;
+  }
+  Val res(Val v) const {
+    while (v.slot == 0 && fwd[v.node].node >= 0) v = fwd[v.node];
+    return v;
+  }
+  static bool plain_reduce(uint16_t op) { return op == LT_OP_SUM || op == LT_OP_AMAX || op == LT_OP_MEAN; }
+  static bool is_unary(uint16_t op) { return op >= LT_OP_NEG && op <= LT_OP_SIGMOID; }
+  static bool is_binary(uint16_t op) { return op >= LT_OP_ADD && op <= LT_OP_GELU_GRAD; }
+  static bool is_row_op(uint16_t op) { return op >= LT_OP_SOFTMAX && op <= LT_OP_XENT_GRAD; }
+
+  // value of a node known at lowering time (constants 0 / 1, seen through views)
+  bool const_of(Val v, double* out, const std::vector<std::vector<Val>>& ins) const {
+    v = res(v);
+    const Node* n = nd[v.node];
+    if (n->op == OP_CONSTANT) {
+      *out = n->attrs[0].is_float ? n->attrs[0].v.f : (double)n->attrs[0].v.i;
+      return true;
+    }
+    if (n->op == LT_OP_EXPAND || n->op == LT_OP_RESHAPE) return const_of(ins[v.node][0], out, ins);
+    return false;
+  }
+  bool is_imm(Val v) const {
+    const Node* n = nd[v.node];
+    if (n->op == OP_CONSTANT || n->op == OP_SCALAR_PARAM) return true;
+    if (n->op == LT_OP_EXPAND || n->op == LT_OP_RESHAPE) return is_imm(rins[v.node][0]);
+    return false;
+  }
+  Val base(Val v) const {
+    while (cls[v.node] == C_VIEW) v = rins[v.node][0];
+    return v;
+  }
+
+  // ---- step 1: special-scalar folding ------------------------------------------------------------
+  void fold() {
+    std::vector<std::vector<Val>> ins(N);
+    for (int32_t i = 0; i < N; ++i)
+      for (int k = 0; k < nd[i]->n_in; ++k)
+        ins[i].push_back(Val{cut.index_of[nd[i]->ins[k].node], nd[i]->ins[k].slot});
+    fwd.assign(N, Val{-1, 0});
+    std::vector<char> drop_alpha(N, 0);
+    for (int32_t i = 0; i < N; ++i) {
+      const Node* n = nd[i];
+      auto same = [&](Val v) {
+        v = res(v);
+        return out_shape(v) == shape_of(i) && out_dtype(v) == n->dtype;
+      };
+      const auto& o = ins[i];
+      double c;
+      if (n->op == LT_OP_ADD && o.size() == 3 && const_of(o[2], &c, ins) && c == 1.0) drop_alpha[i] = 1;
+      const bool two = o.size() == 2 || drop_alpha[i];
+      if (n->op == LT_OP_MUL) {
+        if (const_of(o[1], &c, ins) && c == 1.0 && same(o[0])) fwd[i] = res(o[0]);
+        else if (const_of(o[0], &c, ins) && c == 1.0 && same(o[1])) fwd[i] = res(o[1]);
+      } else if (n->op == LT_OP_ADD && two) {
+        if (const_of(o[1], &c, ins) && c == 0.0 && same(o[0])) fwd[i] = res(o[0]);
+        else if (const_of(o[0], &c, ins) && c == 0.0 && same(o[1])) fwd[i] = res(o[1]);
+      } else if (n->op == LT_OP_SUB) {
+        if (const_of(o[1], &c, ins) && c == 0.0 && same(o[0])) fwd[i] = res(o[0]);
+      } else if (n->op == LT_OP_DIV) {
+        if (const_of(o[1], &c, ins) && c == 1.0 && same(o[0])) fwd[i] = res(o[0]);
+      }
+    }
+    rins.assign(N, {});
+    for (int32_t i = 0; i < N; ++i) {
+      for (Val v : ins[i]) rins[i].push_back(res(v));
+      if (drop_alpha[i]) rins[i].resize(2);
+    }
+    for (const Handle* h : cut.roots) root_vals.push_back(res(Val{cut.index_of[h->node], h->slot}));
+    live.assign(N, 0);
+    std::vector<int32_t> stack;
+    for (Val v : root_vals) stack.push_back(v.node);
+    while (!stack.empty()) {
+      int32_t i = stack.back();
+      stack.pop_back();
+      if (live[i]) continue;
+      live[i] = 1;
+      for (Val v : rins[i]) stack.push_back(v.node);
+    }
+    is_root.assign(N, 0);
+    for (Val v : root_vals) is_root[v.node] = 1;
+  }
+
+  // ---- step 2: classes and users ------------------------------------------------------------------
+  bool classify() {
+    cls.assign(N, C_DEAD);
+    for (int32_t i = 0; i < N; ++i) {
+      if (!live[i]) continue;
+      const uint16_t op = nd[i]->op;
+      if (op == OP_DEVICE_DATA || op == OP_SCALAR_PARAM || op == OP_CONSTANT) cls[i] = C_LEAF;
+      else if (op == LT_OP_EXPAND || op == LT_OP_RESHAPE) cls[i] = is_root[i] ? C_EW : C_VIEW;
+      else if (is_unary(op) || is_binary(op) || op == LT_OP_PERMUTE) cls[i] = C_EW;
+      else if (plain_reduce(op)) {
+        const int in_rank = out_rank(rins[i][0]);
+        if (nd[i]->n_attr == 0 || in_rank <= 1) cls[i] = C_ALL;
+        else if (nd[i]->attrs[0].v.i == in_rank - 1) cls[i] = C_ROW;
+        else if (nd[i]->attrs[0].v.i == 0) cls[i] = C_COL;
+        else return bad(LT_ERR_UNSUPPORTED, "reduction over a middle axis has no lowering");
+      } else if (is_row_op(op)) cls[i] = C_ROW;
+      else if (op == LT_OP_MATMUL) cls[i] = C_MM;
+      else return bad(LT_ERR_UNSUPPORTED, "opcode has no lowering");
+    }
+    users.assign(N, {});
+    for (int32_t j = 0; j < N; ++j) {
+      if (!live[j]) continue;
+      for (Val v : rins[j])
+        if (std::find(users[v.node].begin(), users[v.node].end(), j) == users[v.node].end()) users[v.node].push_back(j);
+    }
+    return true;
+  }
+
+  std::vector<int32_t> eff_users(int32_t i) const {
+    std::vector<int32_t> out, stack(users[i]);
+    while (!stack.empty()) {
+      int32_t u = stack.back();
+      stack.pop_back();
+      if (cls[u] == C_VIEW) stack.insert(stack.end(), users[u].begin(), users[u].end());
+      else if (std::find(out.begin(), out.end(), u) == out.end()) out.push_back(u);
+    }
+    return out;
+  }
+
+  // ---- region bookkeeping ----------------------------------------------------------------------------
+  void region_io(const std::vector<int32_t>& members, std::vector<Val>* inputs, std::vector<Val>* outputs) const {
+    auto in_set = [&](int32_t m) { return std::binary_search(members.begin(), members.end(), m); };
+    inputs->clear();
+    outputs->clear();
+    for (int32_t m : members)
+      for (Val v : rins[m]) {
+        if (in_set(v.node) || is_imm(v)) continue;
+        if (std::find(inputs->begin(), inputs->end(), v) == inputs->end()) inputs->push_back(v);
+      }
+    for (int32_t m : members) {
+      const int n_out = nd[m]->op == LT_OP_LAYER_NORM ? 3 : 1;
+      for (int s = 0; s < n_out; ++s) {
+        const Val v{m, s};
+        bool ext = std::find(root_vals.begin(), root_vals.end(), v) != root_vals.end();
+        for (int32_t u : users[m])
+          if (!in_set(u) && std::find(rins[u].begin(), rins[u].end(), v) != rins[u].end()) ext = true;
+        if (ext) outputs->push_back(v);
+      }
+    }
+  }
+
+  bool caps_ok(const std::vector<int32_t>& members) const {
+    std::vector<Val> in, out;
+    region_io(members, &in, &out);
+    return (int)in.size() <= kMaxRegionInputs && (int)out.size() <= kMaxRegionOutputs &&
+           (int)(in.size() + members.size()) <= kMaxRegionSlots;
+  }
+
+  static std::vector<int32_t> merged(const std::vector<int32_t>& a, const std::vector<int32_t>& b) {
+    std::vector<int32_t> out(a.size() + b.size());
+    std::merge(a.begin(), a.end(), b.begin(), b.end(), out.begin());
+    return out;
+  }
+
+  void unite(Region* home, Region* other) {
+    for (int32_t m : other->members) region_of[m] = home;
+    home->members = merged(home->members, other->members);
+    other->alive = false;
+    other->members.clear();
+  }
+
+  std::vector<Region*> successors(const Region* r) const {
+    std::vector<Region*> out(r->extra_succ);
+    for (int32_t m : r->members)
+      for (int32_t u : eff_users(m)) {
+        Region* ru = region_of[u];
+        if (ru != r && std::find(out.begin(), out.end(), ru) == out.end()) out.push_back(ru);
+      }
+    return out;
+  }
+
+  bool reachable(const Region* src, const Region* dst) const {
+    std::vector<const Region*> stack{src}, seen;
+    while (!stack.empty()) {
+      const Region* x = stack.back();
+      stack.pop_back();
+      if (x == dst) return true;
+      if (std::find(seen.begin(), seen.end(), x) != seen.end()) continue;
+      seen.push_back(x);
+      for (Region* s : successors(x)) stack.push_back(s);
+    }
+    return false;
+  }
+
+  bool can_union(const Region* a, const Region* b) const {
+    for (Region* x : successors(a))
+      if (x != b && reachable(x, b)) return false;
+    for (Region* x : successors(b))
+      if (x != a && reachable(x, a)) return false;
+    return true;
+  }
+
+  bool compatible(const Region* r, int32_t i) const {
+    const std::vector<int64_t> shape = shape_of(i);
+    if (r->kind == C_EW) return shape == shape_of(r->members.front());
+    const int32_t a = r->anchor;
+    if (r->kind == C_MM) return shape == shape_of(a);
+    if (plain_reduce(nd[a]->op)) {
+      if (shape == shape_of(a)) return true;
+      if (r->kind == C_ALL && !shape.empty() && count(shape) <= kMaxFinaliserElems &&
+          (!r->has_fin || r->fin_shape == shape))
+        return true;
+    }
+    return false;
+  }
+
+  // ---- step 3: partition ------------------------------------------------------------------------------
+  void partition() {
+    region_of.assign(N, nullptr);
+    for (int32_t i = 0; i < N; ++i) {
+      if (cls[i] < C_EW) continue;
+      pool.emplace_back(new Region{cls[i], cls[i] == C_EW ? -1 : i, {i}});
+      region_of[i] = pool.back().get();
+    }
+    // pass 1: prologue absorption into plain reductions
+    for (int32_t a = 0; a < N; ++a) {
+      if (!(cls[a] == C_ROW || cls[a] == C_COL || cls[a] == C_ALL) || !plain_reduce(nd[a]->op)) continue;
+      Region* r = region_of[a];
+      const std::vector<int64_t> in_shape = out_shape(rins[a][0]);
+      for (int32_t i = a - 1; i >= 0; --i) {
+        if (cls[i] != C_EW || region_of[i]->members.size() != 1 || is_root[i]) continue;
+        if (shape_of(i) != in_shape || users[i].empty()) continue;
+        bool inside = true;
+        for (int32_t u : users[i]) inside &= r->has(u);
+        if (!inside) continue;
+        if (!caps_ok(merged(r->members, {i}))) continue;
+        unite(r, region_of[i]);
+      }
+    }
+    // pass 2: epilogue / finaliser / elementwise grouping
+    for (int32_t i = 0; i < N; ++i) {
+      if (cls[i] != C_EW || region_of[i]->members.size() != 1 || nd[i]->op == LT_OP_PERMUTE) continue;
+      std::vector<Region*> cand;
+      for (Val v : rins[i]) {
+        Region* r = region_of[v.node];
+        if (r && std::find(cand.begin(), cand.end(), r) == cand.end()) cand.push_back(r);
+      }
+      std::stable_sort(cand.begin(), cand.end(), [](const Region* x, const Region* y) {
+        const int kx = x->kind != C_EW ? 0 : 1, ky = y->kind != C_EW ? 0 : 1;
+        if (kx != ky) return kx < ky;
+        return x->id() > y->id();
+      });
+      Region* home = region_of[i];
+      for (Region* r : cand) {
+        if (!r->alive || r == home) continue;
+        if (r->kind != C_EW) {
+          if (home->members.size() != 1) continue;
+          if (!compatible(r, i) || !caps_ok(merged(r->members, {i})) || !can_union(r, home)) continue;
+          if (r->kind == C_ALL && shape_of(i) != shape_of(r->anchor)) {
+            r->has_fin = true;
+            r->fin_shape = shape_of(i);
+          }
+          unite(r, home);
+          home = r;
+        } else if (home->kind == C_EW) {
+          if (!compatible(r, i) || !caps_ok(merged(r->members, home->members))) continue;
+          if (!can_union(r, home)) continue;
+          unite(r, home);
+          home = r;
+        }
+      }
+    }
+  }
+
+  // ---- step 4: donation and order ---------------------------------------------------------------------
+  struct InPlace { Val v; uint32_t param; };
+  std::vector<std::vector<InPlace>> inplace_of_region;   // parallel to `alive_regions`
+  std::vector<Region*> alive_regions;                    // sorted by id
+  std::vector<int32_t> inplace_root;                     // per root: param ordinal or -1
+
+  int region_pos(const Region* r) const {
+    return (int)(std::find(alive_regions.begin(), alive_regions.end(), r) - alive_regions.begin());
+  }
+
+  void donate_and_order() {
+    for (auto& r : pool)
+      if (r->alive) alive_regions.push_back(r.get());
+    std::sort(alive_regions.begin(), alive_regions.end(), [](const Region* x, const Region* y) { return x->id() < y->id(); });
+    inplace_of_region.assign(alive_regions.size(), {});
+    inplace_root.assign(cut.roots.size(), -1);
+    // canonical index of every device parameter
+    std::vector<int32_t> pnode;
+    for (int32_t idx : cut.param_nodes) pnode.push_back(cut.index_of[idx]);
+    for (size_t k = 0; k < cut.roots.size(); ++k) {
+      const uint32_t d = cut.donors[k];
+      const Val v = root_vals[k];
+      if (d == 0xFFFFFFFFu || !region_of[v.node]) continue;
+      Region* rw = region_of[v.node];
+      auto& mine = inplace_of_region[region_pos(rw)];
+      bool dup = false;
+      for (const InPlace& ip : mine) dup |= (ip.v == v);
+      if (dup) continue;
+      const Buffer* buf = nd[pnode[d]]->buffer.get();
+      auto names_donor = [&](Val x) {
+        return nd[x.node]->op == OP_DEVICE_DATA && x.slot == 0 && nd[x.node]->buffer.get() == buf;
+      };
+      bool ok = true;
+      std::vector<Region*> readers;
+      for (Region* r : alive_regions) {
+        bool reads = false;
+        for (int32_t m : r->members)
+          for (Val x : rins[m]) reads |= names_donor(base(x));
+        if (!reads) continue;
+        if (r == rw) {
+          for (int32_t m : r->members)
+            for (Val x : rins[m])
+              if (names_donor(base(x)) && (m == rw->anchor || !names_donor(x) || nd[m]->op == LT_OP_PERMUTE ||
+                                           nd[m]->op == LT_OP_EXPAND || nd[m]->op == LT_OP_RESHAPE))
+                ok = false;
+        } else {
+          readers.push_back(r);
+        }
+      }
+      if (ok)
+        for (Region* r : readers) ok &= !reachable(rw, r);
+      if (!ok) continue;
+      for (Region* r : readers)
+        if (std::find(r->extra_succ.begin(), r->extra_succ.end(), rw) == r->extra_succ.end()) r->extra_succ.push_back(rw);
+      mine.push_back(InPlace{v, d});
+      inplace_root[k] = (int32_t)d;
+    }
+    // Kahn, smallest id first
+    std::vector<std::vector<Region*>> succ(alive_regions.size());
+    std::vector<int> indeg(alive_regions.size(), 0);
+    for (size_t i = 0; i < alive_regions.size(); ++i) {
+      succ[i] = successors(alive_regions[i]);
+      for (Region* s : succ[i]) indeg[region_pos(s)]++;
+    }
+    std::vector<char> done(alive_regions.size(), 0);
+    while (ordered.size() < alive_regions.size()) {
+      size_t pick = alive_regions.size();
+      for (size_t i = 0; i < alive_regions.size(); ++i)
+        if (!done[i] && indeg[i] == 0) {
+          pick = i;   // alive_regions is sorted by id, so the first ready one is the smallest
+          break;
+        }
+      if (pick == alive_regions.size()) {
+        bad(LT_ERR_UNSUPPORTED, "internal: region graph has a cycle");
+        return;
+      }
+      done[pick] = 1;
+      ordered.push_back(alive_regions[pick]);
+      for (Region* s : succ[pick]) indeg[region_pos(s)]--;
+    }
+  }
+
+  std::string plan_text() const {
+    std::string out;
+    char tmp[64];
+    for (size_t k = 0; k < ordered.size(); ++k) {
+      const Region* r = ordered[k];
+      static const char* names[] = {"DEAD", "LEAF", "VIEW", "EW", "ROW", "COL", "ALL", "MM"};
+      std::vector<Val> in, o;
+      region_io(r->members, &in, &o);
+      if (k) out += "\n";
+      out += "R" + std::to_string(k) + " " + names[r->kind] + " anchor=" + (r->anchor < 0 ? "-" : std::to_string(r->anchor)) + " members=[";
+      for (size_t i = 0; i < r->members.size(); ++i) out += (i ? "," : "") + std::to_string(r->members[i]);
+      out += "] inputs=[";
+      for (size_t i = 0; i < in.size(); ++i) {
+        std::snprintf(tmp, sizeof(tmp), "%s%d.%d", i ? "," : "", in[i].node, in[i].slot);
+        out += tmp;
+      }
+      out += "] outputs=[";
+      for (size_t i = 0; i < o.size(); ++i) {
+        std::snprintf(tmp, sizeof(tmp), "%s%d.%d", i ? "," : "", o[i].node, o[i].slot);
+        out += tmp;
+      }
+      out += "] inplace=[";
+      const auto& ips = inplace_of_region[region_pos(r)];
+      for (size_t i = 0; i < ips.size(); ++i) {
+        std::snprintf(tmp, sizeof(tmp), "%s%d.%d->p%u", i ? "," : "", ips[i].v.node, ips[i].v.slot, ips[i].param);
+        out += tmp;
+      }
+      out += "]";
+    }
+    return out;
+  }
+
+  // ================= code generation =================================================================
+  Plan* plan = nullptr;
+  std::vector<std::vector<int32_t>> storage_of;   // [node][slot] -> storage index or -1
+  std::vector<int32_t> param_ordinal;             // canonical node -> device parameter ordinal or -1
+  std::vector<int32_t> scalar_ordinal;            // canonical node -> scalar ordinal or -1
+
+  // Addressing of a value relative to an iteration space: the storage that holds it and the
+  // element stride along every dimension of the space (0 where it is broadcast).
+  struct Access {
+    int32_t storage = -1;
+    uint8_t dtype = 0;
+    std::vector<int64_t> stride;
+  };
+
+  static std::vector<int64_t> contiguous(const std::vector<int64_t>& shape) {
+    std::vector<int64_t> s(shape.size(), 1);
+    for (int i = (int)shape.size() - 2; i >= 0; --i) s[i] = s[i + 1] * shape[i + 1];
+    return s;
+  }
+
+  // strides of value v (seen through its view chain) over its own shape
+  bool view_strides(Val v, int32_t* storage, std::vector<int64_t>* shape, std::vector<int64_t>* stride) {
+    if (cls[v.node] != C_VIEW) {
+      const int32_t s = storage_of[v.node][v.slot];
+      if (s < 0) return bad(LT_ERR_UNSUPPORTED, "internal: operand has no storage");
+      *storage = s;
+      *shape = out_shape(v);
+      *stride = contiguous(*shape);
+      return true;
+    }
+    std::vector<int64_t> ishape, istride;
+    if (!view_strides(rins[v.node][0], storage, &ishape, &istride)) return false;
+    const std::vector<int64_t> oshape = shape_of(v.node);
+    if (nd[v.node]->op == LT_OP_EXPAND) {
+      std::vector<int64_t> st(oshape.size(), 0);
+      const int off = (int)oshape.size() - (int)ishape.size();
+      for (size_t d = 0; d < ishape.size(); ++d) st[d + off] = ishape[d] == 1 ? 0 : istride[d];
+      *shape = oshape;
+      *stride = st;
+      return true;
+    }
+    // reshape: only of a dense row-major value
+    if (istride != contiguous(ishape)) return bad(LT_ERR_UNSUPPORTED, "reshape of a broadcast view has no lowering");
+    *shape = oshape;
+    *stride = contiguous(oshape);
+    return true;
+  }
+
+  // access of operand v (optionally through `perm`, the permutation of a permute member) from
+  // iteration space `space`
+  bool make_access(Val v, const std::vector<int64_t>& space, const int64_t* perm, Access* out) {
+    std::vector<int64_t> shape, stride;
+    if (!view_strides(v, &out->storage, &shape, &stride)) return false;
+    out->dtype = out_dtype(base(v));
+    if (perm) {
+      std::vector<int64_t> ps(shape.size()), pst(shape.size());
+      for (size_t d = 0; d < shape.size(); ++d) {
+        ps[d] = shape[perm[d]];
+        pst[d] = stride[perm[d]];
+      }
+      shape = ps;
+      stride = pst;
+    }
+    out->stride.assign(space.size(), 0);
+    const int off = (int)space.size() - (int)shape.size();
+    if (off < 0) return bad(LT_ERR_UNSUPPORTED, "internal: operand rank exceeds its iteration space");
+    for (size_t d = 0; d < shape.size(); ++d) out->stride[d + off] = (shape[d] == 1 && space[d + off] != 1) ? 0 : stride[d];
+    for (size_t d = 0; d < space.size(); ++d)
+      if (space[d] == 1) out->stride[d] = 0;
+    return true;
+  }
+
+  struct ProgBuild {
+    ltk::EwProg prog{};
+    std::vector<std::pair<uint32_t, int32_t>> in_storage;    // (input index, storage)
+    std::vector<std::pair<uint32_t, int32_t>> out_storage;   // (output index, storage)
+    struct SP { uint32_t index; int32_t scalar; bool recip; };
+    std::vector<SP> scal_patch;
+    uint64_t bytes = 0;
+  };
+
+  // Build the bytecode program for `members` (sorted) over iteration space `space`.
+  // anchor: value entering through prog.anchor_slot (node -1: none).
+  // outputs: values the program must store.
+  bool build_prog(const std::vector<int32_t>& members, const std::vector<int64_t>& space, Val anchor,
+                  const std::vector<Val>& outputs, bool full_vec, ProgBuild* pb) {
+    ltk::EwProg& p = pb->prog;
+    const int64_t n = count(space);
+    p.n = (uint64_t)n;
+    p.cols = (uint32_t)(space.empty() ? 1 : std::max<int64_t>(space.back(), 1));
+    p.vec_ok = (p.cols % 4u == 0u) ? 1u : 0u;
+    p.full_vec_ok = (full_vec || p.vec_ok) ? 1u : 0u;
+    // --- inputs and immediates
+    struct ValInfo { int slot = -1; int last_use = -1; bool is_output = false; };
+    std::vector<Val> vals;            // values that live in slots
+    std::vector<ValInfo> info;
+    auto find_val = [&](Val v) {
+      for (size_t i = 0; i < vals.size(); ++i)
+        if (vals[i] == v) return (int)i;
+      return -1;
+    };
+    auto in_members = [&](int32_t m) { return std::binary_search(members.begin(), members.end(), m); };
+    std::vector<float> scal;
+    std::vector<int> scal_src;   // scalar ordinal or -1 (immediate), with recip flag in scal_rec
+    std::vector<char> scal_rec;
+    auto scal_index = [&](double value, int ordinal, bool recip) -> int {
+      for (size_t i = 0; i < scal.size(); ++i) {
+        if (ordinal >= 0 && scal_src[i] == ordinal && scal_rec[i] == (char)recip) return (int)i;
+        if (ordinal < 0 && scal_src[i] < 0 && scal[i] == (float)value && std::signbit(scal[i]) == std::signbit((float)value)) return (int)i;
+      }
+      scal.push_back((float)(recip ? 1.0 / value : value));
+      scal_src.push_back(ordinal);
+      scal_rec.push_back((char)recip);
+      return (int)scal.size() - 1;
+    };
+    // inputs, in first-use order (operand order inside each member); a permute member reads
+    // its operand through a private input with permuted strides
+    std::vector<Val> input_vals;
+    std::vector<int32_t> input_perm;   // permute member that owns the input, or -1
+    for (int32_t m : members) {
+      if (m == anchor.node) continue;
+      for (Val v : rins[m]) {
+        if (in_members(v.node) || is_imm(v) || v == anchor) continue;
+        const bool perm = nd[m]->op == LT_OP_PERMUTE;
+        bool have = false;
+        for (size_t q = 0; q < input_vals.size(); ++q) have |= (input_vals[q] == v && input_perm[q] < 0);
+        if (perm || !have) {
+          input_vals.push_back(v);
+          input_perm.push_back(perm ? m : -1);
+        }
+      }
+    }
+    if ((int)input_vals.size() > ltk::kMaxIn) return bad(LT_ERR_UNSUPPORTED, "internal: region has too many inputs");
+    p.n_in = (uint32_t)input_vals.size();
+    // permute members load their operand through a private, permuted input
+    std::vector<int> permute_input(N, -1);
+    for (size_t k = 0; k < input_vals.size(); ++k) {
+      Access acc;
+      int64_t perm[LT_MAX_RANK];
+      const int64_t* pp = nullptr;
+      if (input_perm[k] >= 0) {
+        const int32_t m = input_perm[k];
+        for (int a = 0; a < nd[m]->n_attr; ++a) perm[a] = nd[m]->attrs[a].v.i;
+        pp = perm;
+        permute_input[m] = (int)k;
+      }
+      if (!make_access(input_vals[k], space, pp, &acc)) return false;
+      ltk::EwIn& in = p.in[k];
+      in.ptr = nullptr;
+      in.dtype = acc.dtype;
+      // classify the access
+      const std::vector<int64_t> cs = contiguous(space);
+      bool full = true, zero = true, rowvec = !space.empty(), colvec = !space.empty();
+      for (size_t d = 0; d < space.size(); ++d) {
+        const int64_t want = space[d] == 1 ? 0 : cs[d];
+        if (acc.stride[d] != want) full = false;
+        if (acc.stride[d] != 0) zero = false;
+        if (d + 1 < space.size()) {
+          if (acc.stride[d] != 0) rowvec = false;
+          const int64_t lead = space[d] == 1 ? 0 : cs[d] / std::max<int64_t>(space.back(), 1);
+          if (acc.stride[d] != lead) colvec = false;
+        } else {
+          if (acc.stride[d] != (space[d] == 1 ? 0 : 1)) rowvec = false;
+          if (acc.stride[d] != 0) colvec = false;
+        }
+      }
+      if (n <= 1 || zero) in.mode = ltk::kScalar;
+      else if (full) in.mode = ltk::kFull;
+      else if (rowvec) in.mode = ltk::kRowVec;
+      else if (colvec) in.mode = ltk::kColVec;
+      else {
+        if (space.size() > 4) return bad(LT_ERR_UNSUPPORTED, "strided operand in an iteration space of rank > 4");
+        in.mode = ltk::kStrided;
+        const int off = 4 - (int)space.size();
+        for (int d = 0; d < 4; ++d) {
+          p.dims[d] = d < off ? 1u : (uint32_t)space[d - off];
+          in.stride[d] = d < off ? 0 : acc.stride[d - off];
+        }
+      }
+      if (in.mode != ltk::kStrided && space.size() <= 4) {
+        const int off = 4 - (int)space.size();
+        for (int d = 0; d < 4; ++d) p.dims[d] = d < off ? 1u : (uint32_t)space[d - off];
+      }
+      pb->in_storage.push_back({(uint32_t)k, acc.storage});
+      // algorithmic bytes: the un-broadcast operand is read once
+      int64_t elems = 1;
+      for (size_t d = 0; d < space.size(); ++d)
+        if (acc.stride[d] != 0) elems *= space[d];
+      pb->bytes += (uint64_t)elems * dtype_size(acc.dtype);
+      if (input_perm[k] < 0) {
+        vals.push_back(input_vals[k]);
+        info.push_back(ValInfo{(int)k, -1, false});
+      }
+    }
+    for (size_t d = 0; d < 4; ++d)
+      if (p.dims[d] == 0) p.dims[d] = 1;
+    // --- liveness: last use of every value, by member position
+    if (anchor.node >= 0) {
+      vals.push_back(anchor);
+      info.push_back(ValInfo{-1, -1, false});
+    }
+    for (size_t pos = 0; pos < members.size(); ++pos) {
+      const int32_t m = members[pos];
+      if (m == anchor.node) continue;
+      for (Val v : rins[m]) {
+        const int vi = find_val(v);
+        if (vi >= 0) info[vi].last_use = (int)pos;
+      }
+      const int n_out = 1;
+      for (int s = 0; s < n_out; ++s) {
+        vals.push_back(Val{m, s});
+        info.push_back(ValInfo{-1, -1, false});
+      }
+    }
+    for (Val o : outputs) {
+      const int vi = find_val(o);
+      if (vi < 0) return bad(LT_ERR_UNSUPPORTED, "internal: region output is not computed by the region");
+      info[vi].is_output = true;
+    }
+    // --- slot allocation (inputs sit in slots 0 .. n_in-1 when the program starts)
+    std::vector<char> slot_used(ltk::kSlots, 0);
+    for (uint32_t k = 0; k < p.n_in; ++k) slot_used[k] = 1;
+    int max_slot = (int)p.n_in;
+    auto take_slot = [&]() {
+      for (int s = 0; s < ltk::kSlots; ++s)
+        if (!slot_used[s]) {
+          slot_used[s] = 1;
+          max_slot = std::max(max_slot, s + 1);
+          return s;
+        }
+      return -1;
+    };
+    // permuted private inputs hold their slot until their permute member has copied them
+    if (anchor.node >= 0) {
+      const int s = take_slot();
+      if (s < 0) return bad(LT_ERR_UNSUPPORTED, "region needs more than 32 value slots");
+      info[find_val(anchor)].slot = s;
+      p.anchor_slot = (uint32_t)s;
+    }
+    auto operand = [&](Val v, bool recip, uint32_t* enc) -> bool {
+      const Node* n = nd[v.node];
+      if (is_imm(v)) {
+        Val b = v;
+        while (nd[b.node]->op == LT_OP_EXPAND || nd[b.node]->op == LT_OP_RESHAPE) b = rins[b.node][0];
+        int idx;
+        if (nd[b.node]->op == OP_CONSTANT) {
+          const double c = nd[b.node]->attrs[0].is_float ? nd[b.node]->attrs[0].v.f : (double)nd[b.node]->attrs[0].v.i;
+          idx = scal_index(c, -1, recip);
+        } else {
+          idx = scal_index(nd[b.node]->value, scalar_ordinal[b.node], recip);
+        }
+        if (idx >= ltk::kMaxScal) return bad(LT_ERR_UNSUPPORTED, "region uses more than 32 distinct scalars");
+        *enc = 32u + (uint32_t)idx;
+        return true;
+      }
+      (void)n;
+      const int vi = find_val(v);
+      if (vi < 0 || info[vi].slot < 0) return bad(LT_ERR_UNSUPPORTED, "internal: operand value has no slot");
+      *enc = (uint32_t)info[vi].slot;
+      return true;
+    };
+    uint32_t n_code = 0;
+    auto emit = [&](uint32_t op, uint32_t dst, uint32_t a, uint32_t b = 0, uint32_t c = 0) -> bool {
+      if (n_code >= (uint32_t)ltk::kMaxCode) return bad(LT_ERR_UNSUPPORTED, "region program exceeds 48 instructions");
+      p.code[n_code++] = ltk::encode(op, dst, a, b, c);
+      return true;
+    };
+    for (size_t pos = 0; pos < members.size(); ++pos) {
+      const int32_t m = members[pos];
+      if (m == anchor.node) continue;
+      const Node* n = nd[m];
+      const auto& o = rins[m];
+      if (n->dtype != LT_F32 && n->dtype != LT_BF16) return bad(LT_ERR_UNSUPPORTED, "integer elementwise arithmetic has no lowering");
+      uint32_t ea = 0, eb = 0, ec = 0;
+      if (n->op == LT_OP_PERMUTE) {
+        ea = (uint32_t)permute_input[m];
+      } else {
+        const bool recip_b = n->op == LT_OP_DIV && nd[o[1].node]->op == OP_SCALAR_PARAM;
+        if (!operand(o[0], false, &ea)) return false;
+        if (o.size() > 1 && !operand(o[1], recip_b, &eb)) return false;
+        if (o.size() > 2 && !operand(o[2], false, &ec)) return false;
+      }
+      // operands whose last use is this member free their slots before the result is placed
+      for (Val v : o) {
+        const int vi = find_val(v);
+        if (vi >= 0 && info[vi].last_use == (int)pos && !info[vi].is_output && info[vi].slot >= 0) {
+          slot_used[info[vi].slot] = 0;
+        }
+      }
+      if (n->op == LT_OP_PERMUTE) slot_used[permute_input[m]] = 0;
+      const int dst = take_slot();
+      if (dst < 0) return bad(LT_ERR_UNSUPPORTED, "region needs more than 32 value slots");
+      info[find_val(Val{m, 0})].slot = dst;
+      uint32_t op;
+      switch (n->op) {
+        case LT_OP_NEG: op = ltk::kNeg; break;
+        case LT_OP_ABS: op = ltk::kAbs; break;
+        case LT_OP_EXP: op = ltk::kExp; break;
+        case LT_OP_LOG: op = ltk::kLog; break;
+        case LT_OP_TANH: op = ltk::kTanh; break;
+        case LT_OP_SQRT: op = ltk::kSqrt; break;
+        case LT_OP_RSQRT: op = ltk::kRsqrt; break;
+        case LT_OP_RECIP: op = ltk::kRecip; break;
+        case LT_OP_RELU: op = ltk::kRelu; break;
+        case LT_OP_GELU: op = ltk::kGelu; break;
+        case LT_OP_SQUARE: op = ltk::kSquare; break;
+        case LT_OP_SIGMOID: op = ltk::kSigmoid; break;
+        case LT_OP_CAST: op = n->dtype == LT_BF16 ? ltk::kRoundBf16 : ltk::kMov; break;
+        case LT_OP_EXPAND: case LT_OP_RESHAPE: case LT_OP_PERMUTE: op = ltk::kMov; break;
+        case LT_OP_ADD: op = o.size() == 3 ? ltk::kFma : ltk::kAdd; break;
+        case LT_OP_SUB: op = ltk::kSub; break;
+        case LT_OP_MUL: op = ltk::kMul; break;
+        case LT_OP_DIV: op = (nd[o[1].node]->op == OP_SCALAR_PARAM) ? ltk::kMul : ltk::kDiv; break;
+        case LT_OP_MAXIMUM: op = ltk::kMax; break;
+        case LT_OP_MINIMUM: op = ltk::kMin; break;
+        case LT_OP_RELU_GRAD: op = ltk::kReluGrad; break;
+        case LT_OP_GELU_GRAD: op = ltk::kGeluGrad; break;
+        default: return bad(LT_ERR_UNSUPPORTED, "opcode cannot be a member of an elementwise program");
+      }
+      bool okk;
+      if (op == ltk::kFma) okk = emit(op, (uint32_t)dst, ec, eb, ea);   // alpha*b + a
+      else okk = emit(op, (uint32_t)dst, ea, eb);
+      if (!okk) return false;
+    }
+    p.n_code = n_code;
+    p.n_slots = (uint32_t)max_slot;
+    for (size_t i = 0; i < scal.size(); ++i) {
+      p.scal[i] = scal[i];
+      if (scal_src[i] >= 0) pb->scal_patch.push_back({(uint32_t)i, scal_src[i], (bool)scal_rec[i]});
+    }
+    // --- outputs
+    if ((int)outputs.size() > ltk::kMaxOut) return bad(LT_ERR_UNSUPPORTED, "internal: region has too many outputs");
+    p.n_out = (uint32_t)outputs.size();
+    for (size_t k = 0; k < outputs.size(); ++k) {
+      const Val v = outputs[k];
+      ltk::EwOut& out = p.out[k];
+      out.ptr = nullptr;
+      out.dtype = out_dtype(v);
+      out.slot = (uint32_t)info[find_val(v)].slot;
+      const int64_t on = count(out_shape(v));
+      out.scalar = (on == 1 && n > 1) ? 1u : 0u;
+      if (on != n && on != 1) return bad(LT_ERR_UNSUPPORTED, "internal: output shape differs from its iteration space");
+      pb->out_storage.push_back({(uint32_t)k, storage_of[v.node][v.slot]});
+      pb->bytes += (uint64_t)on * dtype_size(out.dtype);
+    }
+    return true;
+  }
+
+  // append one program's patches to the plan; `offset` = byte offset of the EwProg inside the args
+  void add_prog_patches(uint32_t launch, size_t offset, const ProgBuild& pb) {
+    for (auto& is : pb.in_storage)
+      plan->ptr_patches.push_back(PtrPatch{launch, (uint32_t)(offset + offsetof(ltk::EwProg, in) + is.first * sizeof(ltk::EwIn) + offsetof(ltk::EwIn, ptr)), is.second, 0});
+    for (auto& os : pb.out_storage)
+      plan->ptr_patches.push_back(PtrPatch{launch, (uint32_t)(offset + offsetof(ltk::EwProg, out) + os.first * sizeof(ltk::EwOut) + offsetof(ltk::EwOut, ptr)), os.second, 0});
+    for (auto& sp : pb.scal_patch)
+      plan->scal_patches.push_back(ScalPatch{launch, (uint32_t)(offset + offsetof(ltk::EwProg, scal) + sp.index * sizeof(float)), sp.scalar, (uint8_t)(sp.recip ? 1 : 0)});
+  }
+
+  void touch(int32_t storage, int launch) {
+    if (storage < 0) return;
+    Storage& s = plan->storages[storage];
+    if (s.first_launch < 0) s.first_launch = launch;
+    s.last_launch = launch;
+  }
+
+  template <class T>
+  Launch make_launch(LaunchKind kind, int region, const T& args) {
+    Launch l;
+    l.kind = kind;
+    l.region = region;
+    l.args.resize(sizeof(T));
+    std::memcpy(l.args.data(), &args, sizeof(T));
+    return l;
+  }
+
+  static uint32_t ew_grid(uint64_t n) {
+    const uint64_t tiles = (n + 1023) / 1024;
+    return (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(tiles, 256 * 8));
+  }
+
+  bool operand_gemm(Val v, bool trans, bool flatten_lead, ltk::GemmOperand* g, int32_t* storage, uint8_t* dtype,
+                    std::vector<int64_t>* lead) {
+    std::vector<int64_t> shape, stride;
+    if (!view_strides(v, storage, &shape, &stride)) return false;
+    *dtype = out_dtype(base(v));
+    const size_t r = shape.size();
+    g->ptr = nullptr;
+    g->s_row = trans ? stride[r - 1] : stride[r - 2];
+    g->s_col = trans ? stride[r - 2] : stride[r - 1];
+    lead->assign(shape.begin(), shape.end() - 2);
+    // leading axes must be dense over the matrices so that one batch stride describes them
+    int64_t expect = shape[r - 2] * shape[r - 1];
+    for (int d = (int)r - 3; d >= 0; --d) {
+      if (shape[d] != 1 && stride[d] != expect) return bad(LT_ERR_UNSUPPORTED, "matmul operand with non-dense leading axes");
+      expect *= shape[d];
+    }
+    g->s_b0 = r > 2 ? shape[r - 2] * shape[r - 1] : 0;
+    g->s_b1 = 0;
+    (void)flatten_lead;
+    return true;
+  }
+
+  bool codegen() {
+    storage_of.assign(N, {});
+    param_ordinal.assign(N, -1);
+    scalar_ordinal.assign(N, -1);
+    for (size_t k = 0; k < cut.param_nodes.size(); ++k) param_ordinal[cut.index_of[cut.param_nodes[k]]] = (int32_t)k;
+    for (size_t k = 0; k < cut.scalar_nodes.size(); ++k) scalar_ordinal[cut.index_of[cut.scalar_nodes[k]]] = (int32_t)k;
+    plan->n_params = (int)cut.param_nodes.size();
+    plan->n_scalars = (int)cut.scalar_nodes.size();
+    // storages: every live device parameter, then every region output
+    for (int32_t i = 0; i < N; ++i) {
+      storage_of[i].assign(nd[i]->op == LT_OP_LAYER_NORM ? 3 : 1, -1);
+      if (live[i] && nd[i]->op == OP_DEVICE_DATA) {
+        Storage s;
+        s.param = param_ordinal[i];
+        s.first_launch = s.last_launch = 0;
+        plan->storages.push_back(s);
+        storage_of[i][0] = (int32_t)plan->storages.size() - 1;
+      }
+    }
+    for (size_t k = 0; k < ordered.size(); ++k) {
+      std::vector<Val> in, out;
+      region_io(ordered[k]->members, &in, &out);
+      const auto& ips = inplace_of_region[region_pos(ordered[k])];
+      for (Val v : out) {
+        Storage s;
+        s.first_launch = -1;
+        for (const InPlace& ip : ips)
+          if (ip.v == v) s.param = (int)ip.param;
+        if (s.param < 0) s.bytes = (size_t)count(out_shape(v)) * dtype_size(out_dtype(v));
+        else s.first_launch = s.last_launch = 0;
+        plan->storages.push_back(s);
+        storage_of[v.node][v.slot] = (int32_t)plan->storages.size() - 1;
+      }
+    }
+    // roots
+    for (size_t r = 0; r < root_vals.size(); ++r) {
+      const Val v = root_vals[r];
+      RootBind rb;
+      const Node* n = nd[v.node];
+      if (n->op == OP_DEVICE_DATA) {
+        rb.kind = RootBind::PARAM_ALIAS;
+        rb.index = param_ordinal[v.node];
+      } else if (n->op == OP_SCALAR_PARAM) {
+        rb.kind = RootBind::SCALAR;
+        rb.index = scalar_ordinal[v.node];
+      } else if (n->op == OP_CONSTANT) {
+        rb.kind = RootBind::CONST;
+        rb.value = n->attrs[0].is_float ? n->attrs[0].v.f : (double)n->attrs[0].v.i;
+      } else {
+        rb.kind = RootBind::STORAGE;
+        rb.index = storage_of[v.node][v.slot];
+        if (rb.index < 0) return bad(LT_ERR_UNSUPPORTED, "internal: root has no storage");
+        plan->storages[rb.index].bound_to_root = true;
+      }
+      plan->roots.push_back(rb);
+    }
+    // launches
+    for (size_t k = 0; k < ordered.size(); ++k) {
+      if (!emit_region((int)k, ordered[k])) return false;
+    }
+    for (Storage& s : plan->storages)
+      if (s.first_launch < 0) s.first_launch = s.last_launch = 0;
+    plan->n_regions = (int)ordered.size();
+    for (const Launch& l : plan->launches) {
+      plan->bytes_planned += l.bytes;
+      plan->flops_planned += l.flops;
+    }
+    return true;
+  }
+
+  void note_prog_storages(const ProgBuild& pb, int launch) {
+    for (auto& is : pb.in_storage) touch(is.second, launch);
+    for (auto& os : pb.out_storage) touch(os.second, launch);
+  }
+
+  bool emit_region(int k, Region* r) {
+    std::vector<Val> in, out;
+    region_io(r->members, &in, &out);
+    const int launch = (int)plan->launches.size();
+    if (r->kind == C_EW) {
+      ProgBuild pb;
+      if (!build_prog(r->members, shape_of(r->members.front()), Val{-1, 0}, out, true, &pb)) return false;
+      ltk::EwArgs a{};
+      a.prog = pb.prog;
+      Launch l = make_launch(L_EW, k, a);
+      l.grid_x = ew_grid(pb.prog.n);
+      l.bytes = pb.bytes;
+      plan->launches.push_back(std::move(l));
+      add_prog_patches(launch, offsetof(ltk::EwArgs, prog), pb);
+      note_prog_storages(pb, launch);
+      return true;
+    }
+    const int32_t a = r->anchor;
+    const Node* an = nd[a];
+    // split members into prologue (< anchor) and post (> anchor)
+    std::vector<int32_t> pro_m, post_m;
+    for (int32_t m : r->members) {
+      if (m < a) pro_m.push_back(m);
+      else if (m > a) post_m.push_back(m);
+    }
+    if (r->kind == C_MM) return emit_gemm(k, r, post_m, out);
+    if (!plain_reduce(an->op)) return emit_row_op(k, r, out);
+    // ---- plain reduction
+    const Val src = rins[a][0];
+    const std::vector<int64_t> in_shape = out_shape(src);
+    // prologue program: members below the anchor plus a final value = the reduced operand
+    ProgBuild pro;
+    {
+      if (!build_prologue(pro_m, in_shape, src, r->kind == C_ALL, &pro)) return false;
+    }
+    std::vector<int64_t> post_space = shape_of(a);
+    if (r->has_fin) post_space = r->fin_shape;
+    ProgBuild post;
+    std::vector<int32_t> post_members = post_m;
+    post_members.insert(post_members.begin(), a);
+    if (!build_prog(post_members, post_space, Val{a, 0}, out, r->kind == C_ALL, &post)) return false;
+    const uint32_t red = an->op == LT_OP_SUM ? ltk::kRedSum : an->op == LT_OP_AMAX ? ltk::kRedMax : ltk::kRedMean;
+    if (r->kind == C_ROW) {
+      ltk::RowArgs args{};
+      args.pro = pro.prog;
+      args.post = post.prog;
+      args.cols = (uint32_t)in_shape.back();
+      args.rows = (uint32_t)(count(in_shape) / std::max<int64_t>(1, in_shape.back()));
+      args.red = red;
+      args.threads_per_row = args.cols >= 512 ? 256u : 64u;
+      Launch l = make_launch(L_ROW, k, args);
+      const uint32_t rpb = 256u / args.threads_per_row;
+      l.grid_x = std::max<uint32_t>(1, std::min<uint32_t>((args.rows + rpb - 1) / rpb, 256 * 16));
+      l.bytes = pro.bytes + post.bytes;
+      plan->launches.push_back(std::move(l));
+      add_prog_patches(launch, offsetof(ltk::RowArgs, pro), pro);
+      add_prog_patches(launch, offsetof(ltk::RowArgs, post), post);
+    } else if (r->kind == C_ALL) {
+      ltk::AllArgs args{};
+      args.pro = pro.prog;
+      args.post = post.prog;
+      args.red = red;
+      args.count = (uint64_t)count(in_shape);
+      Launch l = make_launch(L_ALL, k, args);
+      l.grid_x = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>((args.count + 4095) / 4096, 256 * 8));
+      l.bytes = pro.bytes + post.bytes;
+      plan->launches.push_back(std::move(l));
+      add_prog_patches(launch, offsetof(ltk::AllArgs, pro), pro);
+      add_prog_patches(launch, offsetof(ltk::AllArgs, post), post);
+    } else {
+      if (in_shape.size() != 2) return bad(LT_ERR_UNSUPPORTED, "axis-0 reduction needs a rank-2 operand (reshape first)");
+      ltk::ColArgs args{};
+      args.pro = pro.prog;
+      args.post = post.prog;
+      args.rows = (uint32_t)in_shape[0];
+      args.cols = (uint32_t)in_shape[1];
+      args.red = red;
+      Launch l = make_launch(L_COL, k, args);
+      l.grid_x = (args.cols + 255) / 256;
+      if (l.grid_x > kTickets) return bad(LT_ERR_UNSUPPORTED, "axis-0 reduction wider than 262144 columns");
+      uint32_t gy = std::max<uint32_t>(1, std::min<uint32_t>(args.rows / 16, 64));
+      while (gy > 1 && (uint64_t)gy * args.cols > kPartialFloats) gy /= 2;
+      if ((uint64_t)gy * args.cols > kPartialFloats) return bad(LT_ERR_UNSUPPORTED, "axis-0 reduction wider than 65536 columns");
+      while (gy > 1 && (uint64_t)gy * l.grid_x > 256 * 8) gy /= 2;
+      l.grid_y = gy;
+      l.bytes = pro.bytes + post.bytes;
+      plan->launches.push_back(std::move(l));
+      add_prog_patches(launch, offsetof(ltk::ColArgs, pro), pro);
+      add_prog_patches(launch, offsetof(ltk::ColArgs, post), post);
+    }
+    note_prog_storages(pro, launch);
+    note_prog_storages(post, launch);
+    return true;
+  }
+
+  // Prologue of a reduction: the members below the anchor, producing `src` in slot anchor_slot.
+  // When `src` is not computed by a member it is simply the program's only input.
+  bool build_prologue(const std::vector<int32_t>& members, const std::vector<int64_t>& space, Val src, bool full_vec,
+                      ProgBuild* pb) {
+    const bool computed = std::binary_search(members.begin(), members.end(), src.node);
+    if (computed) {
+      // treat src as an "output" so that its slot stays live; it is not stored
+      std::vector<Val> outs{src};
+      storage_of[src.node][src.slot] = -2;   // placeholder, removed below
+      if (!build_prog(members, space, Val{-1, 0}, outs, full_vec, pb)) return false;
+      storage_of[src.node][src.slot] = -1;
+      pb->prog.anchor_slot = pb->prog.out[0].slot;
+      pb->prog.n_out = 0;
+      pb->out_storage.clear();
+      pb->bytes -= (uint64_t)count(space) * dtype_size(out_dtype(src));
+      return true;
+    }
+    // identity prologue: load src into slot 0
+    ltk::EwProg& p = pb->prog;
+    p = ltk::EwProg{};
+    Access acc;
+    if (!make_access(src, space, nullptr, &acc)) return false;
+    // reuse build_prog's classification by building a one-member copy program is overkill:
+    // a reduction operand that is not computed in the region is always read in full
+    const std::vector<int64_t> cs = contiguous(space);
+    bool full = true;
+    for (size_t d = 0; d < space.size(); ++d)
+      if (acc.stride[d] != (space[d] == 1 ? 0 : cs[d])) full = false;
+    if (!full) return bad(LT_ERR_UNSUPPORTED, "reduction of a broadcast view has no lowering");
+    p.n = (uint64_t)count(space);
+    p.cols = (uint32_t)(space.empty() ? 1 : std::max<int64_t>(space.back(), 1));
+    p.vec_ok = (p.cols % 4u == 0u) ? 1u : 0u;
+    p.full_vec_ok = (full_vec || p.vec_ok) ? 1u : 0u;
+    p.n_in = 1;
+    p.in[0].mode = p.n <= 1 ? ltk::kScalar : ltk::kFull;
+    p.in[0].dtype = acc.dtype;
+    p.anchor_slot = 0;
+    p.n_slots = 1;
+    for (int d = 0; d < 4; ++d) p.dims[d] = 1;
+    pb->in_storage.push_back({0u, acc.storage});
+    pb->bytes += p.n * dtype_size(acc.dtype);
+    return true;
+  }
+
+  bool emit_row_op(int k, Region* r, const std::vector<Val>& out) {
+    const int32_t a = r->anchor;
+    const Node* an = nd[a];
+    if (r->members.size() != 1) return bad(LT_ERR_UNSUPPORTED, "internal: fixed row operator with fused members");
+    const int launch = (int)plan->launches.size();
+    ltk::RowOpArgs args{};
+    const std::vector<int64_t> xs = out_shape(rins[a][an->op == LT_OP_LAYER_NORM_GRAD ? 1 : 0]);
+    args.cols = (uint32_t)xs.back();
+    args.rows = (uint32_t)(count(xs) / std::max<int64_t>(1, xs.back()));
+    args.threads_per_row = args.cols > 1024 ? 256u : 64u;
+    if (args.cols > args.threads_per_row * 16u) return bad(LT_ERR_UNSUPPORTED, "row operator on rows longer than 4096 elements");
+    switch (an->op) {
+      case LT_OP_SOFTMAX: args.op = ltk::kSoftmax; break;
+      case LT_OP_SOFTMAX_GRAD: args.op = ltk::kSoftmaxGrad; break;
+      case LT_OP_LAYER_NORM: args.op = ltk::kLayerNorm; args.eps = (float)an->attrs[0].v.f; break;
+      case LT_OP_LAYER_NORM_GRAD: args.op = ltk::kLayerNormGrad; break;
+      case LT_OP_XENT: args.op = ltk::kXent; break;
+      default: args.op = ltk::kXentGrad; break;
+    }
+    Launch l = make_launch(L_ROWOP, k, args);
+    const uint32_t rpb = 256u / args.threads_per_row;
+    l.grid_x = std::max<uint32_t>(1, std::min<uint32_t>((args.rows + rpb - 1) / rpb, 256 * 16));
+    uint64_t bytes = 0;
+    const size_t n_arr = an->op == LT_OP_XENT_GRAD ? 2 : rins[a].size();
+    for (size_t i = 0; i < n_arr; ++i) {
+      Access acc;
+      const std::vector<int64_t> vs = out_shape(rins[a][i]);
+      if (!make_access(rins[a][i], vs, nullptr, &acc)) return false;
+      if (acc.stride != contiguous(vs) && count(vs) > 1) {
+        bool dense = true;
+        const std::vector<int64_t> cs = contiguous(vs);
+        for (size_t d = 0; d < vs.size(); ++d) dense &= (vs[d] == 1 || acc.stride[d] == cs[d]);
+        if (!dense) return bad(LT_ERR_UNSUPPORTED, "row operator on a broadcast view has no lowering");
+      }
+      ((ltk::RowOpArgs*)l.args.data())->in_dtype[i] = acc.dtype;
+      plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)(offsetof(ltk::RowOpArgs, in) + i * sizeof(void*)), acc.storage, 0});
+      touch(acc.storage, launch);
+      bytes += (uint64_t)count(vs) * dtype_size(acc.dtype);
+    }
+    if (an->op == LT_OP_XENT_GRAD) {
+      // the scale is a rank-0 operand: an immediate or a dynamic scalar
+      const Val s = rins[a][2];
+      if (!is_imm(s)) return bad(LT_ERR_UNSUPPORTED, "xent_grad: scale must be a scalar constant or parameter");
+      Val b = s;
+      while (nd[b.node]->op == LT_OP_EXPAND || nd[b.node]->op == LT_OP_RESHAPE) b = rins[b.node][0];
+      if (nd[b.node]->op == OP_CONSTANT) {
+        ((ltk::RowOpArgs*)l.args.data())->scale = (float)(nd[b.node]->attrs[0].is_float ? nd[b.node]->attrs[0].v.f : (double)nd[b.node]->attrs[0].v.i);
+      } else {
+        plan->scal_patches.push_back(ScalPatch{(uint32_t)launch, (uint32_t)offsetof(ltk::RowOpArgs, scale), scalar_ordinal[b.node], 0});
+      }
+    }
+    // outputs: every slot of the anchor that is needed; unneeded layer-norm statistics still
+    // need somewhere to go, so they get storage as well
+    const int n_out = an->op == LT_OP_LAYER_NORM ? 3 : 1;
+    for (int s = 0; s < n_out; ++s) {
+      int32_t st = storage_of[a][s];
+      if (st < 0) {
+        Storage ns;
+        ns.first_launch = -1;
+        ns.bytes = (size_t)count(out_shape(Val{a, s})) * dtype_size(out_dtype(Val{a, s}));
+        plan->storages.push_back(ns);
+        st = storage_of[a][s] = (int32_t)plan->storages.size() - 1;
+      }
+      ((ltk::RowOpArgs*)l.args.data())->out_dtype[s] = out_dtype(Val{a, s});
+      plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)(offsetof(ltk::RowOpArgs, out) + s * sizeof(void*)), st, 0});
+      touch(st, launch);
+      bytes += (uint64_t)count(out_shape(Val{a, s})) * dtype_size(out_dtype(Val{a, s}));
+    }
+    (void)out;
+    l.bytes = bytes;
+    plan->launches.push_back(std::move(l));
+    return true;
+  }
+
+  bool emit_gemm(int k, Region* r, const std::vector<int32_t>& post_m, const std::vector<Val>& out) {
+    const int32_t a = r->anchor;
+    const Node* an = nd[a];
+    const int launch = (int)plan->launches.size();
+    bool tra = false, trb = false;
+    for (int i = 0; i < an->n_attr; ++i) {
+      if (an->attrs[i].key == LT_ATTR_TRANS_A) tra = an->attrs[i].v.i != 0;
+      if (an->attrs[i].key == LT_ATTR_TRANS_B) trb = an->attrs[i].v.i != 0;
+    }
+    ltk::GemmArgs args{};
+    int32_t sa, sb;
+    uint8_t da, db;
+    std::vector<int64_t> la, lb;
+    if (!operand_gemm(rins[a][0], tra, false, &args.a, &sa, &da, &la)) return false;
+    if (!operand_gemm(rins[a][1], trb, false, &args.b, &sb, &db, &lb)) return false;
+    if (da != db) return bad(LT_ERR_UNSUPPORTED, "matmul of operands with different dtypes has no lowering");
+    const std::vector<int64_t> os = shape_of(a);
+    args.m = (uint32_t)os[os.size() - 2];
+    args.n = (uint32_t)os.back();
+    const std::vector<int64_t> as = out_shape(rins[a][0]);
+    args.k = (uint32_t)(tra ? as[as.size() - 2] : as.back());
+    int64_t batch = count(la);
+    if (lb.empty() && batch > 1) {
+      // a plain matrix on the right: fold the leading axes of a into its rows
+      if (tra) return bad(LT_ERR_UNSUPPORTED, "transposed batched a with an unbatched b has no lowering");
+      args.m = (uint32_t)(batch * args.m);
+      batch = 1;
+    }
+    args.batch0 = (uint32_t)batch;
+    args.batch1 = 1;
+    if (batch == 1) args.a.s_b0 = args.b.s_b0 = 0;
+    args.in_dtype = da;
+    ProgBuild post;
+    std::vector<int32_t> post_members = post_m;
+    post_members.insert(post_members.begin(), a);
+    std::vector<int64_t> space{(int64_t)batch * args.m, (int64_t)args.n};
+    // the post program sees the output flat as [batch*m, n]; every member has the output's shape,
+    // so broadcast classification must be done against the true shape
+    if (!build_prog(post_members, shape_of(a), Val{a, 0}, out, false, &post)) return false;
+    (void)space;
+    args.post = post.prog;
+    Launch l = make_launch(L_GEMM, k, args);
+    l.flops = 2ull * (uint64_t)batch * args.m * args.n * args.k;
+    l.bytes = post.bytes + (uint64_t)batch * ((uint64_t)args.m * args.k + (uint64_t)args.k * args.n) * dtype_size(da);
+    plan->launches.push_back(std::move(l));
+    plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)(offsetof(ltk::GemmArgs, a) + offsetof(ltk::GemmOperand, ptr)), sa, 0});
+    plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)(offsetof(ltk::GemmArgs, b) + offsetof(ltk::GemmOperand, ptr)), sb, 0});
+    touch(sa, launch);
+    touch(sb, launch);
+    add_prog_patches(launch, offsetof(ltk::GemmArgs, post), post);
+    note_prog_storages(post, launch);
+    return true;
+  }
+};
+
+}  // namespace
+
+std::unique_ptr<Plan> lower(lt_ctx* ctx, const Cut& cut, lt_status* status) {
+  Lowering L(ctx, cut);
+  for (int32_t idx : cut.order) L.nd.push_back(&ctx->nodes[idx]);
+  std::unique_ptr<Plan> plan(new Plan());
+  L.plan = plan.get();
+  L.fold();
+  bool ok = L.classify();
+  if (ok) {
+    L.partition();
+    L.donate_and_order();
+    ok = L.status == LT_OK;
+  }
+  if (ok) {
+    plan->text = L.plan_text();
+    ok = L.codegen();
+  }
+  if (ok) {
+    // patches must be sorted by launch for the single forward sweep of the executor
+    std::stable_sort(plan->ptr_patches.begin(), plan->ptr_patches.end(), [](const PtrPatch& x, const PtrPatch& y) { return x.launch < y.launch; });
+    std::stable_sort(plan->scal_patches.begin(), plan->scal_patches.end(), [](const ScalPatch& x, const ScalPatch& y) { return x.launch < y.launch; });
+  }
+  if (!ok) {
+    *status = L.status == LT_OK ? LT_ERR_UNSUPPORTED : L.status;
+    ctx->err = L.err;
+    return nullptr;
+  }
+  *status = LT_OK;
+  return plan;
+}
+
+}  // namespace lt

@@ -1,0 +1,332 @@
+"""ctypes binding with the same names as include/lt.h.  Argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+DTYPES = {"f32": 0, "bf16": 1, "s32": 2, "s64": 3}
+_DTYPE_NAMES = {v: k for k, v in DTYPES.items()}
+_DTYPE_BYTES = {0: 4, 1: 2, 2: 4, 3: 8}
+
+OPCODES = {
+    "neg": 16, "abs": 17, "exp": 18, "log": 19, "tanh": 20, "sqrt": 21, "rsqrt": 22, "recip": 23,
+    "relu": 24, "gelu": 25, "square": 26, "cast": 27, "sigmoid": 28,
+    "add": 32, "sub": 33, "mul": 34, "div": 35, "maximum": 36, "minimum": 37, "relu_grad": 38, "gelu_grad": 39,
+    "expand": 48, "reshape": 49, "permute": 50,
+    "sum": 64, "amax": 65, "mean": 66,
+    "softmax": 80, "softmax_grad": 81, "layer_norm": 82, "layer_norm_grad": 83, "xent": 84, "xent_grad": 85,
+    "matmul": 96,
+}
+ATTR_VALUE, ATTR_DTYPE, ATTR_AXIS, ATTR_EPS, ATTR_TRANS_A, ATTR_TRANS_B, ATTR_DIM0 = 1, 2, 3, 4, 5, 6, 16
+LT_DONATABLE = 1
+MAX_RANK = 6
+
+
+class _AttrV(C.Union):
+    _fields_ = [("i", C.c_int64), ("f", C.c_double)]
+
+
+class lt_attr(C.Structure):
+    _fields_ = [("key", C.c_uint16), ("is_float", C.c_uint8), ("v", _AttrV)]
+
+
+class BarrierInfo(C.Structure):
+    _fields_ = [("hash", C.c_uint64), ("key_bytes", C.c_uint64), ("cache_hit", C.c_int32),
+                ("n_nodes", C.c_int32), ("n_roots", C.c_int32), ("n_regions", C.c_int32),
+                ("n_launches", C.c_int32), ("bytes_planned", C.c_uint64), ("flops_planned", C.c_uint64),
+                ("ns_collect", C.c_uint64), ("ns_hash", C.c_uint64), ("ns_lower", C.c_uint64),
+                ("ns_launch", C.c_uint64)]
+
+
+class Stats(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in (
+        "barriers", "cache_hits", "cache_misses", "nodes_recorded", "regions_launched", "kernels_launched",
+        "ns_lowering_total", "arena_bytes_in_use", "arena_bytes_peak", "live_tensors")]
+
+
+class LaunchRecord(C.Structure):
+    _fields_ = [("kernel", C.c_char * 48), ("region", C.c_int32), ("ms", C.c_float),
+                ("bytes", C.c_uint64), ("flops", C.c_uint64)]
+
+
+class LtError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"lt_status {status}: {message}")
+        self.status = status
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, "liblt.so")
+
+
+def load_library():
+    """Load liblt.so.  It must have been built (python -m paper_2102_13267_amd.build);
+    there is no fallback: without the native library nothing in this package works."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python -m paper_2102_13267_amd.build`")
+    lib = C.CDLL(path)
+    P, u64, i32 = C.c_void_p, C.c_uint64, C.c_int
+    sig = {
+        "lt_init": [i32, P, P, C.c_size_t, C.POINTER(P)],
+        "lt_shutdown": [P],
+        "lt_tensor_from_device": [P, P, i32, i32, C.POINTER(C.c_int64), C.c_uint32, C.POINTER(u64)],
+        "lt_scalar": [P, i32, C.c_double, C.POINTER(u64)],
+        "lt_op": [P, C.c_uint16, C.POINTER(u64), i32, C.POINTER(lt_attr), i32, C.POINTER(u64), i32],
+        "lt_assign": [P, u64, u64],
+        "lt_release": [P, u64],
+        "lt_barrier": [P, i32, C.POINTER(BarrierInfo)],
+        "lt_fetch": [P, u64, P, C.c_size_t],
+        "lt_device_ptr": [P, u64, C.POINTER(P)],
+        "lt_shape": [P, u64, C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_int64)],
+        "lt_dump_ir": [P, C.c_char_p, C.c_size_t, C.POINTER(C.c_size_t)],
+        "lt_dump_plan": [P, C.c_char_p, C.c_size_t, C.POINTER(C.c_size_t)],
+        "lt_dump_key": [P, P, C.c_size_t, C.POINTER(C.c_size_t)],
+        "lt_stats": [P, C.POINTER(Stats)],
+        "lt_set_profiling": [P, i32],
+        "lt_last_launches": [P, C.POINTER(LaunchRecord), i32, C.POINTER(i32)],
+    }
+    for name, argtypes in sig.items():
+        fn = getattr(lib, name)
+        fn.argtypes = argtypes
+        fn.restype = C.c_int
+    lib.lt_last_error.argtypes = [P]
+    lib.lt_last_error.restype = C.c_char_p
+    _LIB = lib
+    return lib
+
+
+class Tensor:
+    """A handle (unique tensor id).  Dropping the last Python reference releases it, which is
+    how the library learns that a tensor is no longer live."""
+    __slots__ = ("ctx", "tid", "dtype", "shape", "_keep", "__weakref__")
+
+    def __init__(self, ctx, tid, dtype, shape, keep=None):
+        self.ctx, self.tid, self.dtype, self.shape, self._keep = ctx, tid, dtype, tuple(shape), keep
+
+    def __del__(self):
+        ctx = self.ctx
+        if ctx is not None and ctx._h:
+            ctx._lib.lt_release(ctx._h, self.tid)
+
+    def __repr__(self):
+        return f"Tensor(id={self.tid}, {self.dtype}{list(self.shape)})"
+
+
+class Context:
+    """One lt_ctx.  device=None gives the null device ("CPU:0": records, hashes, lowers, launches
+    nothing).  Otherwise `device` is a HIP ordinal and the workspace is a torch byte tensor."""
+
+    def __init__(self, device=None, workspace_bytes=1 << 30, stream=None):
+        self._lib = load_library()
+        self._h = C.c_void_p()
+        self._torch = None
+        self._workspace = None
+        if device is None:
+            self._check_init(self._lib.lt_init(-1, None, None, int(workspace_bytes), C.byref(self._h)))
+            self.device = None
+        else:
+            import torch
+            if not torch.cuda.is_available():
+                raise RuntimeError("no GPU visible: the HIP path cannot run (there is no CPU fallback)")
+            self._torch = torch
+            self.device = int(device)
+            torch.cuda.set_device(self.device)
+            self._workspace = torch.empty(int(workspace_bytes), dtype=torch.uint8, device=f"cuda:{self.device}")
+            st = stream if stream is not None else torch.cuda.current_stream(self.device)
+            self._stream = st
+            self._check_init(self._lib.lt_init(self.device, C.c_void_p(st.cuda_stream), C.c_void_p(self._workspace.data_ptr()),
+                                               int(workspace_bytes), C.byref(self._h)))
+
+    def _check_init(self, st):
+        if st != 0:
+            raise LtError(st, (self._lib.lt_last_error(None) or b"").decode())
+
+    def _check(self, st):
+        if st != 0:
+            raise LtError(st, (self._lib.lt_last_error(self._h) or b"").decode())
+
+    def close(self):
+        if self._h:
+            self._lib.lt_shutdown(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- factories -----------------------------------------------------------------------
+    def from_device(self, dptr, dtype, shape, donatable=False, keep=None) -> Tensor:
+        dims = (C.c_int64 * max(1, len(shape)))(*shape)
+        out = C.c_uint64()
+        self._check(self._lib.lt_tensor_from_device(self._h, C.c_void_p(dptr), DTYPES[dtype], len(shape), dims,
+                                                     LT_DONATABLE if donatable else 0, C.byref(out)))
+        return Tensor(self, out.value, dtype, shape, keep)
+
+    def tensor(self, array, dtype=None, donatable=False) -> Tensor:
+        """Upload a NumPy array (or adopt a torch tensor already on the device)."""
+        if self.device is None:
+            a = np.asarray(array)
+            if dtype is None:
+                dtype = "s32" if a.dtype == np.int32 else "s64" if a.dtype == np.int64 else "f32"
+            return self.from_device(0, dtype, a.shape, donatable)
+        torch = self._torch
+        if isinstance(array, torch.Tensor):
+            t = array
+            if dtype is None:
+                dtype = {torch.float32: "f32", torch.bfloat16: "bf16", torch.int32: "s32", torch.int64: "s64"}[t.dtype]
+        else:
+            a = np.ascontiguousarray(array)
+            if dtype is None:
+                dtype = "s32" if a.dtype == np.int32 else "s64" if a.dtype == np.int64 else "f32"
+            if a.dtype == np.float64:
+                a = a.astype(np.float32)
+            t = torch.from_numpy(a).to(f"cuda:{self.device}")
+            if dtype == "bf16":
+                t = t.to(torch.bfloat16)
+        t = t.contiguous()
+        return self.from_device(t.data_ptr(), dtype, tuple(t.shape), donatable, keep=t)
+
+    def scalar(self, value, dtype="f32") -> Tensor:
+        out = C.c_uint64()
+        self._check(self._lib.lt_scalar(self._h, DTYPES[dtype], float(value), C.byref(out)))
+        return Tensor(self, out.value, dtype, ())
+
+    # ---- generic op -------------------------------------------------------------------------
+    def _t(self, x) -> Tensor:
+        return x if isinstance(x, Tensor) else self.scalar(x)
+
+    def op(self, name, inputs, attrs=(), n_out=1):
+        ins = [self._t(x) for x in inputs]
+        ids = (C.c_uint64 * len(ins))(*[t.tid for t in ins])
+        at = (lt_attr * max(1, len(attrs)))()
+        for i, (key, val) in enumerate(attrs):
+            at[i].key = key
+            if isinstance(val, float):
+                at[i].is_float = 1
+                at[i].v.f = val
+            else:
+                at[i].is_float = 0
+                at[i].v.i = int(val)
+        outs = (C.c_uint64 * n_out)()
+        self._check(self._lib.lt_op(self._h, OPCODES[name], ids, len(ins), at, len(attrs), outs, n_out))
+        res = []
+        for k in range(n_out):
+            dt, rank = C.c_int(), C.c_int()
+            dims = (C.c_int64 * MAX_RANK)()
+            self._check(self._lib.lt_shape(self._h, outs[k], C.byref(dt), C.byref(rank), dims))
+            res.append(Tensor(self, outs[k], _DTYPE_NAMES[dt.value], tuple(dims[i] for i in range(rank.value))))
+        return res[0] if n_out == 1 else tuple(res)
+
+    # ---- the tensor API shared with the oracle's back ends -------------------------------------------
+    def neg(self, x): return self.op("neg", [x])
+    def abs(self, x): return self.op("abs", [x])
+    def exp(self, x): return self.op("exp", [x])
+    def log(self, x): return self.op("log", [x])
+    def tanh(self, x): return self.op("tanh", [x])
+    def sqrt(self, x): return self.op("sqrt", [x])
+    def rsqrt(self, x): return self.op("rsqrt", [x])
+    def recip(self, x): return self.op("recip", [x])
+    def relu(self, x): return self.op("relu", [x])
+    def gelu(self, x): return self.op("gelu", [x])
+    def square(self, x): return self.op("square", [x])
+    def sigmoid(self, x): return self.op("sigmoid", [x])
+    def cast(self, x, dtype): return self.op("cast", [x], [(ATTR_DTYPE, DTYPES[dtype])])
+    def add(self, a, b, alpha=None): return self.op("add", [a, b] if alpha is None else [a, b, alpha])
+    def sub(self, a, b): return self.op("sub", [a, b])
+    def mul(self, a, b): return self.op("mul", [a, b])
+    def div(self, a, b): return self.op("div", [a, b])
+    def maximum(self, a, b): return self.op("maximum", [a, b])
+    def minimum(self, a, b): return self.op("minimum", [a, b])
+    def relu_grad(self, dy, x): return self.op("relu_grad", [dy, x])
+    def gelu_grad(self, dy, x): return self.op("gelu_grad", [dy, x])
+    def expand(self, x, size): return self.op("expand", [x], [(ATTR_DIM0 + i, int(d)) for i, d in enumerate(size)])
+    def reshape(self, x, size): return self.op("reshape", [x], [(ATTR_DIM0 + i, int(d)) for i, d in enumerate(size)])
+    def permute(self, x, dims): return self.op("permute", [x], [(ATTR_DIM0 + i, int(d)) for i, d in enumerate(dims)])
+    def sum(self, x, axis=None): return self.op("sum", [x], [] if axis is None else [(ATTR_AXIS, int(axis))])
+    def amax(self, x, axis=None): return self.op("amax", [x], [] if axis is None else [(ATTR_AXIS, int(axis))])
+    def mean(self, x, axis=None): return self.op("mean", [x], [] if axis is None else [(ATTR_AXIS, int(axis))])
+    def softmax(self, x): return self.op("softmax", [x])
+    def softmax_grad(self, dy, y): return self.op("softmax_grad", [dy, y])
+    def layer_norm(self, x, gamma, beta, eps=1e-5): return self.op("layer_norm", [x, gamma, beta], [(ATTR_EPS, float(eps))], n_out=3)
+    def layer_norm_grad(self, dy, x, gamma, mean, rstd): return self.op("layer_norm_grad", [dy, x, gamma, mean, rstd])
+    def xent(self, logits, labels): return self.op("xent", [logits, labels])
+    def xent_grad(self, logits, labels, scale): return self.op("xent_grad", [logits, labels, scale])
+
+    def matmul(self, a, b, trans_a=False, trans_b=False, dtype=None):
+        attrs = [(ATTR_TRANS_A, int(bool(trans_a))), (ATTR_TRANS_B, int(bool(trans_b)))]
+        if dtype is not None:
+            attrs.append((ATTR_DTYPE, DTYPES[dtype]))
+        return self.op("matmul", [a, b], attrs)
+
+    def assign(self, dst: Tensor, src: Tensor):
+        self._check(self._lib.lt_assign(self._h, dst.tid, src.tid))
+        dst.dtype, dst.shape = src.dtype, src.shape
+
+    def release(self, t: Tensor):
+        self._check(self._lib.lt_release(self._h, t.tid))
+        t.ctx = None
+
+    # ---- barrier, fetch, diagnostics -----------------------------------------------------------------------
+    def barrier(self, blocking=True) -> BarrierInfo:
+        info = BarrierInfo()
+        self._check(self._lib.lt_barrier(self._h, 1 if blocking else 0, C.byref(info)))
+        return info
+
+    def fetch(self, t: Tensor) -> np.ndarray:
+        """Blocking barrier if needed, then device-to-host copy.  bf16 comes back as float32."""
+        code = DTYPES[t.dtype]
+        n = int(np.prod(t.shape, dtype=np.int64)) if t.shape else 1
+        np_t = {0: np.float32, 1: np.uint16, 2: np.int32, 3: np.int64}[code]
+        out = np.empty(n, dtype=np_t)
+        self._check(self._lib.lt_fetch(self._h, t.tid, out.ctypes.data_as(C.c_void_p), out.nbytes))
+        if code == 1:
+            out = (out.astype(np.uint32) << 16).view(np.float32)
+        return out.reshape(t.shape)
+
+    def device_ptr(self, t: Tensor) -> int:
+        p = C.c_void_p()
+        self._check(self._lib.lt_device_ptr(self._h, t.tid, C.byref(p)))
+        return p.value or 0
+
+    def _dump(self, fn, binary=False):
+        n = C.c_size_t()
+        self._check(fn(self._h, None, 0, C.byref(n)))
+        buf = C.create_string_buffer(n.value + 1)
+        self._check(fn(self._h, C.cast(buf, C.c_void_p) if binary else buf, n.value + 1, C.byref(n)))
+        return buf.raw[:n.value] if binary else buf.value.decode()
+
+    def dump_ir(self) -> str:
+        return self._dump(self._lib.lt_dump_ir)
+
+    def dump_plan(self) -> str:
+        return self._dump(self._lib.lt_dump_plan)
+
+    def dump_key(self) -> bytes:
+        return self._dump(self._lib.lt_dump_key, binary=True)
+
+    def stats(self) -> Stats:
+        s = Stats()
+        self._check(self._lib.lt_stats(self._h, C.byref(s)))
+        return s
+
+    def set_profiling(self, on: bool):
+        self._check(self._lib.lt_set_profiling(self._h, 1 if on else 0))
+
+    def last_launches(self):
+        n = C.c_int()
+        self._check(self._lib.lt_last_launches(self._h, None, 0, C.byref(n)))
+        recs = (LaunchRecord * max(1, n.value))()
+        self._check(self._lib.lt_last_launches(self._h, recs, n.value, C.byref(n)))
+        return [{"kernel": r.kernel.decode(), "region": r.region, "ms": r.ms, "bytes": r.bytes, "flops": r.flops}
+                for r in recs[:n.value]]

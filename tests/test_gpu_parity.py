@@ -1,0 +1,379 @@
+"""GPU parity (-m gpu): the HIP path through the C ABI against the CPU oracle, element by element.
+Tolerances (norm-wise per tensor, as the design doc derives): 1e-5 for fp32 paths, 2e-2 for bf16."""
+import numpy as np
+import pytest
+
+from oracle.numeric import Eager, round_to_bf16
+from workloads import programs
+from workloads.inputs import C4_HYPER, c1_inputs, c2_inputs, c4_inputs, c5_batch, c5_inputs
+
+pytestmark = pytest.mark.gpu
+
+TOL32, TOL16 = 1e-5, 2e-2
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    from paper_2102_13267_amd import Context
+    c = Context(device=0, workspace_bytes=2 << 30)
+    yield c
+    c.close()
+
+
+def rel_err(got, ref):
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    assert np.array_equal(np.isnan(got), np.isnan(ref))
+    fin = np.isfinite(ref)
+    assert np.array_equal(got[~fin & ~np.isnan(ref)], ref[~fin & ~np.isnan(ref)])
+    if not fin.any():
+        return 0.0
+    scale = max(float(np.max(np.abs(ref[fin]))), 1e-30)
+    return float(np.max(np.abs(got[fin] - ref[fin]))) / scale
+
+
+def check(ctx, E, got_t, ref_t, tol, what=""):
+    err = rel_err(ctx.fetch(got_t), E.fetch(ref_t))
+    assert err <= tol, (what, err)
+    return err
+
+
+def rng(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+UNARY = ["neg", "abs", "exp", "tanh", "sqrt", "rsqrt", "recip", "relu", "gelu", "square", "sigmoid", "log"]
+
+
+@pytest.mark.parametrize("shape", [(1,), (3, 5), (257,), (64, 100), (1000, 33), (128, 1024)])
+def test_unary_ops_each_alone(ctx, shape):
+    """Spans one lane, ragged tails, non-multiple-of-4 rows and several workgroup tiles."""
+    E = Eager()
+    x = (rng(1).random(shape, dtype=np.float32) * 4 + 0.05).astype(np.float32)
+    for name in UNARY:
+        xin = x if name in ("sqrt", "rsqrt", "log", "recip") else (x - 2.0).astype(np.float32)
+        got = getattr(ctx, name)(ctx.tensor(xin))
+        ref = getattr(E, name)(E.tensor(xin))
+        check(ctx, E, got, ref, TOL32, name)
+
+
+def test_special_values(ctx):
+    E = Eager()
+    x = np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 1e-40, -1e-40, 88.0, -104.0], np.float32)
+    for name in ["neg", "abs", "exp", "tanh", "relu", "gelu", "square", "sigmoid"]:
+        with np.errstate(all="ignore"):
+            got = ctx.fetch(getattr(ctx, name)(ctx.tensor(x)))
+            ref = E.fetch(getattr(E, name)(E.tensor(x)))
+        assert np.array_equal(np.isnan(got), np.isnan(ref)), name
+        ok = ~np.isnan(ref)
+        assert np.allclose(got[ok], ref[ok], rtol=1e-5, atol=1e-37), (name, got, ref)
+    assert ctx.fetch(ctx.tanh(ctx.tensor(np.zeros(4, np.float32)))).tolist() == [0, 0, 0, 0]
+    assert ctx.fetch(ctx.exp(ctx.tensor(np.zeros(4, np.float32)))).tolist() == [1, 1, 1, 1]
+    assert ctx.fetch(ctx.gelu(ctx.tensor(np.zeros(4, np.float32)))).tolist() == [0, 0, 0, 0]
+
+
+@pytest.mark.parametrize("shapes", [((64, 48), (64, 48)), ((64, 48), (48,)), ((64, 48), (64, 1)), ((64, 48), ()),
+                                    ((7, 5), (5,)), ((7, 5), (7, 1)), ((4, 6, 10), (6, 1)), ((2, 3, 4, 5), (3, 1, 5))])
+def test_binary_ops_and_broadcast_modes(ctx, shapes):
+    E = Eager()
+    a = (rng(2).random(shapes[0], dtype=np.float32) - 0.5).astype(np.float32)
+    b = (rng(3).random(shapes[1], dtype=np.float32) + 0.5).astype(np.float32)
+    for name in ["add", "sub", "mul", "div", "maximum", "minimum", "relu_grad", "gelu_grad"]:
+        check(ctx, E, getattr(ctx, name)(ctx.tensor(a), ctx.tensor(b)), getattr(E, name)(E.tensor(a), E.tensor(b)), TOL32, name)
+        check(ctx, E, getattr(ctx, name)(ctx.tensor(b), ctx.tensor(a)), getattr(E, name)(E.tensor(b), E.tensor(a)), TOL32, name)
+    check(ctx, E, ctx.add(ctx.tensor(a), ctx.tensor(b), alpha=0.37), E.add(E.tensor(a), E.tensor(b), alpha=0.37), TOL32)
+    check(ctx, E, ctx.div(ctx.tensor(a), 3.0), E.div(E.tensor(a), 3.0), TOL32)
+
+
+def test_empty_and_scalar_tensors(ctx):
+    E = Eager()
+    e = ctx.add(ctx.tensor(np.zeros((0, 8), np.float32)), 1.0)
+    assert ctx.fetch(e).shape == (0, 8)
+    s = ctx.mul(ctx.tensor(np.array(3.0, np.float32)), ctx.tensor(np.array(4.0, np.float32)))
+    assert ctx.fetch(s) == 12.0
+
+
+@pytest.mark.parametrize("shape", [(5,), (1000,), (33, 7), (64, 1024), (300, 515), (1 << 20,)])
+def test_reductions(ctx, shape):
+    E = Eager()
+    x = (rng(4).random(shape, dtype=np.float32) - 0.3).astype(np.float32)
+    for name in ["sum", "amax", "mean"]:
+        check(ctx, E, getattr(ctx, name)(ctx.tensor(x)), getattr(E, name)(E.tensor(x)), TOL32, name)
+        if len(shape) == 2:
+            check(ctx, E, getattr(ctx, name)(ctx.tensor(x), -1), getattr(E, name)(E.tensor(x), -1), TOL32, name + " rows")
+            check(ctx, E, getattr(ctx, name)(ctx.tensor(x), 0), getattr(E, name)(E.tensor(x), 0), TOL32, name + " cols")
+
+
+def test_sum_of_ones_is_exact(ctx):
+    for n in (1, 63, 4096, 1 << 22):
+        assert ctx.fetch(ctx.sum(ctx.tensor(np.ones(n, np.float32)))) == n
+    assert np.array_equal(ctx.fetch(ctx.sum(ctx.tensor(np.ones((100, 300), np.float32)), 0)), np.full(300, 100.0))
+    assert np.array_equal(ctx.fetch(ctx.sum(ctx.tensor(np.ones((100, 300), np.float32)), 1)), np.full(100, 300.0))
+
+
+def test_reduction_with_prologue_and_epilogue(ctx):
+    E = Eager()
+    x = (rng(5).random((200, 96), dtype=np.float32) - 0.5).astype(np.float32)
+    w = (rng(6).random((96,), dtype=np.float32)).astype(np.float32)
+    c = (rng(7).random((200,), dtype=np.float32)).astype(np.float32)
+
+    def prog(B, x, w, c):
+        z = B.mul(B.tanh(x), w)                     # prologue with a row-vector broadcast
+        r = B.add(B.sum(z, axis=1), c)               # row reduce + epilogue
+        k = B.sub(B.amax(B.mul(B.square(x), B.expand(B.reshape(c, (200, 1)), (200, 96))), axis=0), w)   # column-vector broadcast, column reduce
+        t = B.sqrt(B.add(B.mean(B.abs(x)), 1.0))     # global reduce + scalar epilogue
+        return r, k, t
+    got = prog(ctx, ctx.tensor(x), ctx.tensor(w), ctx.tensor(c))
+    ref = prog(E, E.tensor(x), E.tensor(w), E.tensor(c))
+    for g, r in zip(got, ref):
+        check(ctx, E, g, r, TOL32)
+
+
+@pytest.mark.parametrize("rows,cols", [(64, 48), (1024, 1024), (100, 1000), (37, 4100)])
+def test_c1_trace(ctx, rows, cols):
+    E = Eager()
+    inp = c1_inputs(rows, cols)
+    hits = []
+    for it in range(3):
+        out = programs.c1_trace(ctx, *(ctx.tensor(inp[k]) for k in ("x", "y", "bias")))
+        info = ctx.barrier()
+        hits.append(info.cache_hit)
+        got = ctx.fetch(out)
+        if it == 0:
+            first = got
+        else:
+            assert np.array_equal(got, first)        # a cache hit gives the same bits as the fresh lowering
+    assert hits == [0, 1, 1] and info.n_regions == 2
+    ref = E.fetch(programs.c1_trace(E, *(E.tensor(inp[k]) for k in ("x", "y", "bias"))))
+    assert rel_err(got, ref) <= TOL32
+    assert np.max(np.abs(got)) == 1.0                # x / |x| is exact
+
+
+def test_c1_full_size_ten_runs(ctx):
+    inp = c1_inputs()
+    x, y, b = (ctx.tensor(inp[k]) for k in ("x", "y", "bias"))
+    hits = []
+    for _ in range(10):
+        out = programs.c1_trace(ctx, x, y, b)
+        hits.append(ctx.barrier().cache_hit)
+    assert hits == [0] + [1] * 9
+    E = Eager()
+    ref = E.fetch(programs.c1_trace(E, *(E.tensor(inp[k]) for k in ("x", "y", "bias"))))
+    assert rel_err(ctx.fetch(out), ref) <= TOL32
+
+
+@pytest.mark.parametrize("n", [1000, 70000, (1 << 22) + 3])
+def test_c4_adam_clip(ctx, n):
+    E = Eager()
+    inp = c4_inputs(n)
+    names = ("p", "g", "m", "v")
+    gt = [ctx.tensor(inp[k].copy(), donatable=True) for k in names]
+    rt = [E.tensor(inp[k]) for k in names]
+    for step in range(2):
+        hyper = dict(C4_HYPER, t=step + 1)
+        programs.c4_step(ctx, *gt, **hyper)
+        info = ctx.barrier()
+        programs.c4_step(E, *rt, **hyper)
+        assert info.cache_hit == (step > 0)
+        for g, r, k in zip(gt, rt, names):
+            if k != "g":
+                check(ctx, E, g, r, TOL32, f"{k} step {step}")
+    if n > 65536:
+        assert info.n_regions == 2
+        assert ctx.dump_plan().count("->p") == 3     # p, m, v updated in place
+
+
+def test_in_place_semantics_of_section_4_3(ctx):
+    """a += 1; read; read  -> the second read must not add again.
+    b = a + 2; a += 1      -> b sees the old a."""
+    import torch
+    base = torch.arange(8, dtype=torch.float32, device="cuda:0")
+    a = ctx.tensor(base, donatable=True)
+    ctx.assign(a, ctx.add(a, 1.0))
+    assert ctx.fetch(a).tolist() == list(range(1, 9))
+    assert ctx.fetch(a).tolist() == list(range(1, 9))
+    assert ctx.device_ptr(a) == base.data_ptr()      # donated: updated in place
+    b = ctx.add(a, 2.0)
+    ctx.assign(a, ctx.add(a, 1.0))
+    assert ctx.fetch(a).tolist() == list(range(2, 10))
+    assert ctx.fetch(b).tolist() == list(range(3, 11))
+    # a second handle on the buffer forbids donation
+    keep = ctx.scalar(0.0)
+    ctx.assign(keep, a)
+    ctx.assign(a, ctx.mul(a, 2.0))
+    assert ctx.fetch(a).tolist() == [2 * v for v in range(2, 10)]
+    assert ctx.fetch(keep).tolist() == list(range(2, 10))
+
+
+ROW_SHAPES = [(4, 10), (128, 10), (33, 64), (256, 256), (8, 1000), (16, 1024), (5, 4096), (3, 1030)]
+
+
+@pytest.mark.parametrize("shape", ROW_SHAPES)
+def test_row_operators_f32(ctx, shape):
+    E = Eager()
+    r = rng(8)
+    x = (r.standard_normal(shape, dtype=np.float32) * 2).astype(np.float32)
+    dy = r.standard_normal(shape, dtype=np.float32)
+    g = (r.random(shape[1], dtype=np.float32) + 0.5).astype(np.float32)
+    b = r.standard_normal(shape[1], dtype=np.float32)
+    lab = r.integers(0, shape[1], size=shape[0], dtype=np.int32)
+
+    def prog(B, x, dy, g, b, lab):
+        p = B.softmax(x)
+        dp = B.softmax_grad(dy, p)
+        y, mu, rs = B.layer_norm(x, g, b, eps=1e-5)
+        dx = B.layer_norm_grad(dy, x, g, mu, rs)
+        l = B.xent(x, lab)
+        dl = B.xent_grad(x, lab, 0.25)
+        return p, dp, y, mu, rs, dx, l, dl
+    got = prog(ctx, *(ctx.tensor(v) for v in (x, dy, g, b, lab)))
+    ref = prog(E, *(E.tensor(v) for v in (x, dy, g, b, lab)))
+    for k, (gg, rr) in enumerate(zip(got, ref)):
+        check(ctx, E, gg, rr, 2e-5 if k == 5 else TOL32, f"row op output {k}")
+    p = ctx.fetch(got[0])
+    assert np.allclose(p.sum(axis=1), 1.0, atol=1e-5)
+
+
+def test_row_operators_bf16(ctx):
+    E = Eager()
+    r = rng(9)
+    shape = (64, 256)
+    x = round_to_bf16(r.standard_normal(shape, dtype=np.float32))
+    dy = round_to_bf16(r.standard_normal(shape, dtype=np.float32))
+    g = round_to_bf16((r.random(shape[1], dtype=np.float32) + 0.5).astype(np.float32))
+    b = round_to_bf16(r.standard_normal(shape[1], dtype=np.float32))
+
+    def prog(B, x, dy, g, b):
+        p = B.softmax(x)
+        dp = B.softmax_grad(dy, p)
+        y, mu, rs = B.layer_norm(x, g, b)
+        dx = B.layer_norm_grad(dy, x, g, mu, rs)
+        return p, dp, y, dx
+    got = prog(ctx, *(ctx.tensor(v, dtype="bf16") for v in (x, dy, g, b)))
+    ref = prog(E, *(E.tensor(v, dtype="bf16") for v in (x, dy, g, b)))
+    for gg, rr in zip(got, ref):
+        assert gg.dtype == "bf16"
+        check(ctx, E, gg, rr, TOL16)
+
+
+GEMM_SHAPES = [(1, 1, 1), (8, 8, 8), (128, 128, 16), (130, 70, 33), (128, 784, 512), (257, 1000, 129), (128, 512, 10)]
+
+
+@pytest.mark.parametrize("m,k,n", GEMM_SHAPES)
+@pytest.mark.parametrize("ta,tb", [(False, False), (True, False), (False, True), (True, True)])
+def test_gemm_f32(ctx, m, k, n, ta, tb):
+    E = Eager()
+    r = rng(10)
+    a = r.standard_normal((k, m) if ta else (m, k), dtype=np.float32)
+    b = r.standard_normal((n, k) if tb else (k, n), dtype=np.float32)
+    check(ctx, E, ctx.matmul(ctx.tensor(a), ctx.tensor(b), ta, tb), E.matmul(E.tensor(a), E.tensor(b), ta, tb), TOL32, (m, k, n, ta, tb))
+
+
+def test_gemm_identity_and_ones(ctx):
+    a = rng(11).standard_normal((200, 96), dtype=np.float32)
+    assert np.array_equal(ctx.fetch(ctx.matmul(ctx.tensor(a), ctx.tensor(np.eye(96, dtype=np.float32)))), a)
+    ones = ctx.fetch(ctx.matmul(ctx.tensor(np.ones((150, 256), np.float32)), ctx.tensor(np.ones((256, 70), np.float32))))
+    assert np.all(ones == 256)
+    h = ctx.fetch(ctx.matmul(ctx.tensor(np.ones((150, 256), np.float32), dtype="bf16"),
+                             ctx.tensor(np.ones((256, 70), np.float32), dtype="bf16")))
+    assert np.all(h == 256)
+
+
+@pytest.mark.parametrize("m,k,n", [(8, 8, 8), (128, 64, 128), (130, 70, 33), (256, 1024, 512), (100, 40, 264)])
+@pytest.mark.parametrize("ta,tb", [(False, False), (True, False), (False, True), (True, True)])
+def test_gemm_bf16(ctx, m, k, n, ta, tb):
+    E = Eager()
+    r = rng(12)
+    a = round_to_bf16(r.standard_normal((k, m) if ta else (m, k), dtype=np.float32))
+    b = round_to_bf16(r.standard_normal((n, k) if tb else (k, n), dtype=np.float32))
+    got = ctx.matmul(ctx.tensor(a, dtype="bf16"), ctx.tensor(b, dtype="bf16"), ta, tb)
+    ref = E.matmul(E.tensor(a, dtype="bf16"), E.tensor(b, dtype="bf16"), ta, tb)
+    check(ctx, E, got, ref, TOL16, (m, k, n, ta, tb))
+    # fp32 output of a bf16 product keeps the fp32 accumulator: far tighter than bf16 rounding
+    got32 = ctx.matmul(ctx.tensor(a, dtype="bf16"), ctx.tensor(b, dtype="bf16"), ta, tb, dtype="f32")
+    ref32 = E.matmul(E.tensor(a, dtype="bf16"), E.tensor(b, dtype="bf16"), ta, tb, dtype="f32")
+    check(ctx, E, got32, ref32, 1e-5, (m, k, n, ta, tb))
+
+
+def test_gemm_batched_and_epilogue(ctx):
+    E = Eager()
+    r = rng(13)
+    a = r.standard_normal((3, 4, 70, 48), dtype=np.float32)
+    b = r.standard_normal((3, 4, 48, 90), dtype=np.float32)
+    check(ctx, E, ctx.matmul(ctx.tensor(a), ctx.tensor(b)), E.matmul(E.tensor(a), E.tensor(b)), TOL32)
+    bt = r.standard_normal((3, 4, 90, 48), dtype=np.float32)
+    check(ctx, E, ctx.matmul(ctx.tensor(a), ctx.tensor(bt), False, True), E.matmul(E.tensor(a), E.tensor(bt), False, True), TOL32)
+    w = r.standard_normal((48, 90), dtype=np.float32)
+    bias = r.standard_normal((90,), dtype=np.float32)
+    res = r.standard_normal((3, 4, 70, 90), dtype=np.float32)
+
+    def prog(B, a, w, bias, res):
+        return B.add(res, B.gelu(B.add(B.matmul(a, w), bias)))
+    got = prog(ctx, *(ctx.tensor(v) for v in (a, w, bias, res)))
+    info = ctx.barrier()
+    assert info.n_regions == 1
+    check(ctx, E, got, prog(E, *(E.tensor(v) for v in (a, w, bias, res))), TOL32)
+
+
+def test_c2_mlp_training_teacher_forced(ctx):
+    """Every step starts from the oracle's weights, so errors cannot accumulate: 1e-5 per step."""
+    E = Eager()
+    inp = c2_inputs(steps=3)
+    names = ("W1", "b1", "W2", "b2", "W3", "b3")
+    rp = [E.tensor(inp[k]) for k in names]
+    for step in range(3):
+        gp = [ctx.tensor(E.fetch(p).copy(), donatable=True) for p in rp]
+        lg = programs.c2_step(ctx, ctx.tensor(inp["X"][step]), ctx.tensor(inp["labels"][step]), gp, 0.01)
+        info = ctx.barrier()
+        lr_ = programs.c2_step(E, E.tensor(inp["X"][step]), E.tensor(inp["labels"][step]), rp, 0.01)
+        assert info.cache_hit == (step > 0)
+        check(ctx, E, lg, lr_, TOL32, "loss")
+        for g, r, k in zip(gp, rp, names):
+            # compare the update itself, which is what the step computes
+            check(ctx, E, g, r, TOL32, k)
+    assert ctx.dump_plan().count("->p") == 6
+
+
+def test_c2_mlp_training_free_running(ctx):
+    E = Eager()
+    steps = 20
+    inp = c2_inputs(steps=steps)
+    names = ("W1", "b1", "W2", "b2", "W3", "b3")
+    gp = [ctx.tensor(inp[k].copy(), donatable=True) for k in names]
+    rp = [E.tensor(inp[k]) for k in names]
+    hits = []
+    for step in range(steps):
+        lg = programs.c2_step(ctx, ctx.tensor(inp["X"][step]), ctx.tensor(inp["labels"][step]), gp, 0.01)
+        hits.append(ctx.barrier().cache_hit)
+        lr_ = programs.c2_step(E, E.tensor(inp["X"][step]), E.tensor(inp["labels"][step]), rp, 0.01)
+        assert abs(float(ctx.fetch(lg)) - float(E.fetch(lr_))) <= 1e-4 * abs(float(E.fetch(lr_)))
+    assert hits == [0] + [1] * (steps - 1)
+    for g, r, k in zip(gp, rp, names):
+        check(ctx, E, g, r, 1e-4, k)
+
+
+def test_c5_dynamic_shapes_and_host_control_flow(ctx):
+    E = Eager()
+    d = 256
+    inp = c5_inputs(d=d, steps=12, batches=(8, 16, 32, 136))
+    gW = [ctx.tensor(w) for w in inp["W"]]; gb = [ctx.tensor(w) for w in inp["b"]]
+    gWr = [ctx.tensor(w) for w in inp["Wr"]]; gbr = [ctx.tensor(w) for w in inp["br"]]
+    rW = [E.tensor(w) for w in inp["W"]]; rb = [E.tensor(w) for w in inp["b"]]
+    rWr = [E.tensor(w) for w in inp["Wr"]]; rbr = [E.tensor(w) for w in inp["br"]]
+    seen, misses = set(), 0
+    for step in range(12):
+        batch = int(inp["batch"][step])
+        X = c5_batch(step, batch, d)
+        word = ctx.tensor(np.array([inp["word"][step]], np.int32))
+        depth = 1 + int(ctx.fetch(word)[0]) % 8          # data-dependent host branch: a trace break
+        assert depth == 1 + int(inp["word"][step]) % 8
+        s, h = programs.c5_forward(ctx, ctx.tensor(X), gW, gb, gWr, gbr, depth)
+        info = ctx.barrier()
+        misses += 0 if info.cache_hit else 1
+        assert info.cache_hit == ((batch, depth) in seen)
+        seen.add((batch, depth))
+        sr, hr = programs.c5_forward(E, E.tensor(X), rW, rb, rWr, rbr, depth)
+        check(ctx, E, h, hr, TOL32, f"h step {step}")
+        check(ctx, E, s, sr, TOL32, f"checksum step {step}")
+        assert info.n_regions == 4 + depth + 1
+    assert misses == len(seen)

@@ -1,0 +1,260 @@
+#!/usr/bin/env python3
+"""Benchmark of the LazyTensor fused-execution hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input: record the trace
+through the C ABI, barrier (cut, hash, cache lookup, lowering on a miss, kernel launches), block
+until the device is done.  Inputs are resident in HBM before the timed region starts.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4|c1|c2|c5]
+
+Prints ONE JSON line: barrier-steps/s for the workload, the roofline of its dominant kernel
+(duration measured with HIP events on the library's stream inside the timed steps) and the CPU
+oracle timed on the same box.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_PEAK_TFLOPS = {"bf16": 2516.6, "f32": 157.3}
+
+
+def _gpu_ctx(workspace_bytes):
+    from paper_2102_13267_amd import Context
+    ctx = Context(device=0, workspace_bytes=workspace_bytes)
+    return ctx
+
+
+def _sync():
+    import torch
+    torch.cuda.synchronize()
+
+
+def _time_steps(step_fn, ctx, steps, warmup):
+    """Returns (seconds for `steps` steps, per-kernel records of the timed steps, barrier infos)."""
+    for _ in range(warmup):
+        step_fn()
+    _sync()
+    ctx.set_profiling(True)
+    launches, infos = [], []
+    _sync()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        infos.append(step_fn())
+        launches.append(ctx.last_launches())
+    _sync()
+    dt = time.perf_counter() - t0
+    ctx.set_profiling(False)
+    # the same steps without event recording, for the headline rate
+    _sync()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step_fn()
+    _sync()
+    dt_plain = time.perf_counter() - t0
+    return dt_plain, dt, launches, infos
+
+
+def _dominant(launches):
+    """Average duration and algorithmic bytes / flops per launch of the kernel family that takes
+    the most device time."""
+    agg = {}
+    for step in launches:
+        for r in step:
+            a = agg.setdefault((r["kernel"], r["region"]), {"ms": 0.0, "n": 0, "bytes": r["bytes"], "flops": r["flops"]})
+            a["ms"] += r["ms"]
+            a["n"] += 1
+    (kernel, region), a = max(agg.items(), key=lambda kv: kv[1]["ms"])
+    table = [{"kernel": k, "region": rg, "avg_ms": v["ms"] / v["n"], "bytes": v["bytes"], "flops": v["flops"]}
+             for (k, rg), v in sorted(agg.items(), key=lambda kv: kv[0][1])]
+    return kernel, region, a["ms"] / a["n"], a["bytes"], a["flops"], table
+
+
+# ---- workloads ---------------------------------------------------------------------------------
+def run_c4(steps, warmup, n=268_435_456):
+    from workloads import programs
+    from workloads.inputs import C4_HYPER, c4_inputs
+    ctx = _gpu_ctx(64 << 20)
+    inp = c4_inputs(n)
+    p, g, m, v = (ctx.tensor(inp[k], donatable=(k != "g")) for k in ("p", "g", "m", "v"))
+    state = {"t": 0}
+
+    def step():
+        state["t"] += 1
+        programs.c4_step(ctx, p, g, m, v, **dict(C4_HYPER, t=state["t"]))
+        return ctx.barrier(True)
+    dt, dt_prof, launches, infos = _time_steps(step, ctx, steps, warmup)
+    kernel, region, avg_ms, kbytes, _, table = _dominant(launches)
+    roof = {"bound": "hbm", "kernel": kernel, "achieved": kbytes / (avg_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "traffic": None, "avg_ms": avg_ms, "bytes_per_launch": kbytes}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    extra = {"kernels": table, "plan": ctx.dump_plan(), "cache_hits": sum(i.cache_hit for i in infos),
+             "bytes_planned_per_step": int(infos[-1].bytes_planned),
+             "whole_step_GBps": infos[-1].bytes_planned * steps / dt / 1e9}
+    config = {"workload": f"c4: fused Adam + grad-norm clipping over {n} fp32 params, one barrier per step",
+              "params": n, "regions": int(infos[-1].n_regions)}
+
+    def cpu(sample=1 << 24):
+        from oracle.numeric import Eager
+        si = c4_inputs(sample)
+        E = Eager()
+        ts = [E.tensor(si[k]) for k in ("p", "g", "m", "v")]
+        programs.c4_step(E, *ts, **C4_HYPER)           # warm-up
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < 10.0:
+            programs.c4_step(E, *ts, **C4_HYPER)
+            reps += 1
+        per_param = (time.perf_counter() - t0) / (reps * sample)
+        return 1.0 / (per_param * n), f"{reps} oracle steps on {sample} params, scaled linearly to {n}"
+    return dt, "f32", config, roof, extra, cpu
+
+
+def run_c1(steps, warmup, rows=1024, cols=1024):
+    from workloads import programs
+    from workloads.inputs import c1_inputs
+    ctx = _gpu_ctx(64 << 20)
+    inp = c1_inputs(rows, cols)
+    x, y, b = (ctx.tensor(inp[k]) for k in ("x", "y", "bias"))
+
+    def step():
+        out = programs.c1_trace(ctx, x, y, b)
+        return ctx.barrier(True)
+    dt, dt_prof, launches, infos = _time_steps(step, ctx, steps, warmup)
+    kernel, region, avg_ms, kbytes, _, table = _dominant(launches)
+    roof = {"bound": "hbm", "kernel": kernel, "achieved": kbytes / (avg_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "traffic": None, "avg_ms": avg_ms, "bytes_per_launch": kbytes}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    extra = {"kernels": table, "plan": ctx.dump_plan(), "cache_hits": sum(i.cache_hit for i in infos)}
+    config = {"workload": f"c1: 12-op elementwise+reduce trace on fp32 [{rows},{cols}]", "regions": int(infos[-1].n_regions)}
+
+    def cpu():
+        from oracle.numeric import Eager
+        E = Eager()
+        ts = [E.tensor(inp[k]) for k in ("x", "y", "bias")]
+        programs.c1_trace(E, *ts)
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < 10.0:
+            programs.c1_trace(E, *ts)
+            reps += 1
+        return reps / (time.perf_counter() - t0), f"{reps} oracle steps at full size"
+    return dt, "f32", config, roof, extra, cpu
+
+
+def run_c2(steps, warmup):
+    from workloads import programs
+    from workloads.inputs import c2_inputs
+    ctx = _gpu_ctx(256 << 20)
+    n_batches = 100
+    inp = c2_inputs(steps=n_batches)
+    names = ("W1", "b1", "W2", "b2", "W3", "b3")
+    params = [ctx.tensor(inp[k], donatable=True) for k in names]
+    Xs = [ctx.tensor(inp["X"][i]) for i in range(n_batches)]
+    Ls = [ctx.tensor(inp["labels"][i]) for i in range(n_batches)]
+    state = {"i": 0}
+
+    def step():
+        i = state["i"] % n_batches
+        state["i"] += 1
+        loss = programs.c2_step(ctx, Xs[i], Ls[i], params, 0.01)
+        return ctx.barrier(True)
+    dt, dt_prof, launches, infos = _time_steps(step, ctx, steps, warmup)
+    kernel, region, avg_ms, kbytes, kflops, table = _dominant(launches)
+    roof = {"bound": "mfma", "kernel": kernel, "achieved": kflops / (avg_ms * 1e-3) / 1e12, "peak": MFMA_PEAK_TFLOPS["f32"],
+            "unit": "TFLOP/s", "traffic": None, "avg_ms": avg_ms, "flops_per_launch": kflops}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    extra = {"kernels": table, "cache_hits": sum(i.cache_hit for i in infos), "ns_host_per_step": {
+        "collect": int(np.mean([i.ns_collect for i in infos])), "hash": int(np.mean([i.ns_hash for i in infos])),
+        "launch": int(np.mean([i.ns_launch for i in infos]))}}
+    config = {"workload": "c2: MLP 784-512-512-10 fp32 batch 128, fwd+bwd+SGD, one barrier per step", "regions": int(infos[-1].n_regions)}
+
+    def cpu():
+        from oracle.numeric import Eager
+        E = Eager()
+        ps = [E.tensor(inp[k]) for k in names]
+        X, L = E.tensor(inp["X"][0]), E.tensor(inp["labels"][0])
+        programs.c2_step(E, X, L, ps, 0.01)
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < 10.0:
+            programs.c2_step(E, X, L, ps, 0.01)
+            reps += 1
+        return reps / (time.perf_counter() - t0), f"{reps} oracle steps at full size"
+    return dt, "f32", config, roof, extra, cpu
+
+
+def run_c5(steps, warmup):
+    from workloads import programs
+    from workloads.inputs import c5_batch, c5_inputs
+    ctx = _gpu_ctx(1 << 30)
+    total = warmup + 2 * steps + 8
+    inp = c5_inputs(steps=total)
+    W = [ctx.tensor(w) for w in inp["W"]]; b = [ctx.tensor(w) for w in inp["b"]]
+    Wr = [ctx.tensor(w) for w in inp["Wr"]]; br = [ctx.tensor(w) for w in inp["br"]]
+    Xs = [ctx.tensor(c5_batch(i, int(inp["batch"][i]))) for i in range(total)]
+    words = [ctx.tensor(np.array([inp["word"][i]], np.int32)) for i in range(total)]
+    state = {"i": 0}
+
+    def step():
+        i = state["i"]
+        state["i"] += 1
+        depth = 1 + int(ctx.fetch(words[i])[0]) % 8      # data-dependent host branch
+        s, h = programs.c5_forward(ctx, Xs[i], W, b, Wr, br, depth)
+        return ctx.barrier(True)
+    dt, dt_prof, launches, infos = _time_steps(step, ctx, steps, warmup)
+    kernel, region, avg_ms, kbytes, kflops, table = _dominant(launches)
+    flops = sum(r["flops"] for st in launches for r in st)
+    gemm_ms = sum(r["ms"] for st in launches for r in st if r["flops"])
+    roof = {"bound": "mfma", "kernel": "lt_gemm_kernel", "achieved": flops / (gemm_ms * 1e-3) / 1e12,
+            "peak": MFMA_PEAK_TFLOPS["f32"], "unit": "TFLOP/s", "traffic": None, "gemm_ms_total": gemm_ms}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    misses = [i for i in infos if not i.cache_hit]
+    extra = {"hit_rate": 1 - len(misses) / len(infos),
+             "lowering_us_per_miss": float(np.mean([i.ns_lower for i in misses]) / 1e3) if misses else None}
+    config = {"workload": "c5: 4-layer GELU MLP d=2048 fp32, batch in {8..1024}, 1-8 unrolled residual blocks"}
+    return dt, "f32", config, roof, extra, None
+
+
+WORKLOADS = {"c1": run_c1, "c2": run_c2, "c4": run_c4, "c5": run_c5}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="c4", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
+              "(the path shards by parameter range / batch, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+    defaults = {"c4": (20, 3), "c1": (200, 10), "c2": (200, 10), "c5": (100, 10)}
+    steps = args.steps if args.steps is not None else defaults[args.workload][0]
+    warmup = args.warmup if args.warmup is not None else defaults[args.workload][1]
+    dt, dtype, config, roof, extra, cpu = WORKLOADS[args.workload](steps, warmup)
+    line = {
+        "metric": "barrier-steps/sec", "value": steps / dt, "unit": "steps/s", "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": dt / steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": dtype, "data": "synthetic", "config": config, "roofline": roof,
+    }
+    if cpu is not None and not args.no_cpu:
+        v, sample = cpu()
+        line["cpu_baseline"] = {"value": v, "unit": "steps/s", "cores": os.cpu_count(), "kind": "oracle", "sample": sample}
+    line["detail"] = extra
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -73,6 +73,12 @@ def load_library():
     path = library_path()
     if not os.path.exists(path):
         raise ImportError(f"{path} is missing: build it with `python -m paper_2102_13267_amd.build`")
+    # PyTorch-ROCm ships its own HIP runtime under the same soname as /opt/rocm's.  One process
+    # must use one runtime, so torch's is loaded first and liblt.so then binds to it.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(path)
     P, u64, i32 = C.c_void_p, C.c_uint64, C.c_int
     sig = {

@@ -21,59 +21,46 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 // One accumulator quad = four consecutive rows of one column (the MFMA 32x32 result layout).
 // Runs the post program for it.
-__device__ __forceinline__ void post_quad(const EwProg& p, float4 acc, uint32_t row0, uint32_t col, uint32_t rows_valid,
-                                          uint64_t out_base_row, uint32_t n) {
-  // flat index of element e of the quad in the [rows, n] output space
+__device__ __forceinline__ void post_quad(const EwProg& p, const ProgRegs pr, Quad acc, uint32_t row0, uint32_t col,
+                                          uint32_t rows_valid, uint64_t out_base_row, uint32_t n) {
+  // flat index of element e of the quad in the [rows, n] output space: i0 + e*n
   const uint64_t i0 = (out_base_row + row0) * (uint64_t)n + col;
   RF<16> f = rf_zero<16>();
-  {
-    typename RF<16>::vec r0 = f.e0, r1 = f.e1, r2 = f.e2, r3 = f.e3;
-    const uint32_t n_in = p.n_in;
+  const uint32_t n_in = p.n_in;
 #pragma unroll
-    for (int k = 0; k < kMaxIn; ++k) {
-      if ((uint32_t)k < n_in) {
-        const EwIn& in = p.in[k];
-        float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (in.mode == kScalar) {
-          const float s = load_elem(in.ptr, in.dtype, 0);
-          q = make_float4(s, s, s, s);
-        } else if (in.mode == kRowVec) {
-          const float s = load_elem(in.ptr, in.dtype, col);
-          q = make_float4(s, s, s, s);
-        } else if (in.mode == kColVec) {
-          const uint64_t r = out_base_row + row0;
-          if (rows_valid > 0u) q.x = load_elem(in.ptr, in.dtype, r);
-          if (rows_valid > 1u) q.y = load_elem(in.ptr, in.dtype, r + 1);
-          if (rows_valid > 2u) q.z = load_elem(in.ptr, in.dtype, r + 2);
-          if (rows_valid > 3u) q.w = load_elem(in.ptr, in.dtype, r + 3);
-        } else if (in.mode == kFull) {
-          if (rows_valid > 0u) q.x = load_elem(in.ptr, in.dtype, i0);
-          if (rows_valid > 1u) q.y = load_elem(in.ptr, in.dtype, i0 + n);
-          if (rows_valid > 2u) q.z = load_elem(in.ptr, in.dtype, i0 + 2ull * n);
-          if (rows_valid > 3u) q.w = load_elem(in.ptr, in.dtype, i0 + 3ull * n);
-        } else {
-          if (rows_valid > 0u) q.x = load_elem(in.ptr, in.dtype, strided_index(p, in, i0));
-          if (rows_valid > 1u) q.y = load_elem(in.ptr, in.dtype, strided_index(p, in, i0 + n));
-          if (rows_valid > 2u) q.z = load_elem(in.ptr, in.dtype, strided_index(p, in, i0 + 2ull * n));
-          if (rows_valid > 3u) q.w = load_elem(in.ptr, in.dtype, strided_index(p, in, i0 + 3ull * n));
+  for (int k = 0; k < kMaxIn; ++k) {
+    Quad q = splat(0.0f);
+    if ((uint32_t)k < n_in) {
+      const EwIn& in = p.in[k];
+      if (in.mode == kScalar) {
+        q = splat(load_elem(in.ptr, in.dtype, 0));
+      } else if (in.mode == kRowVec) {
+        q = splat(load_elem(in.ptr, in.dtype, col));
+      } else {
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) {
+          if ((uint32_t)e < rows_valid) {
+            const uint64_t i = i0 + (uint64_t)e * n;
+            const uint64_t off = in.mode == kFull ? i : in.mode == kColVec ? out_base_row + row0 + e : strided_index(p, in, i);
+            q.v[e] = load_elem(in.ptr, in.dtype, off);
+          }
         }
-        LT_WR4(k, q);
       }
     }
-    f.e0 = r0; f.e1 = r1; f.e2 = r2; f.e3 = r3;
+#pragma unroll
+    for (int v = 0; v < kVec; ++v) f.e[v][k] = q.v[v];
   }
   f = rf_set<16>(f, p.anchor_slot, acc);
-  f = interp<16>(f, p);
+  f = interp<16>(f, pr, p.n_code);
   const uint32_t n_out = p.n_out;
 #pragma unroll
   for (int o = 0; o < kMaxOut; ++o) {
     if ((uint32_t)o < n_out) {
       const EwOut& out = p.out[o];
-      const float4 q = rf_get<16>(f, out.slot);
-      if (rows_valid > 0u) store_elem(out.ptr, out.dtype, i0, q.x);
-      if (rows_valid > 1u) store_elem(out.ptr, out.dtype, i0 + n, q.y);
-      if (rows_valid > 2u) store_elem(out.ptr, out.dtype, i0 + 2ull * n, q.z);
-      if (rows_valid > 3u) store_elem(out.ptr, out.dtype, i0 + 3ull * n, q.w);
+      const Quad q = rf_get<16>(f, out.slot);
+#pragma unroll
+      for (int e = 0; e < kVec; ++e)
+        if ((uint32_t)e < rows_valid) store_elem(out.ptr, out.dtype, i0 + (uint64_t)e * n, q.v[e]);
     }
   }
 }
@@ -81,6 +68,7 @@ __device__ __forceinline__ void post_quad(const EwProg& p, float4 acc, uint32_t 
 __device__ __forceinline__ void epilogue(const GemmArgs& a, const v16f (&acc)[2][2], uint32_t tile_m, uint32_t tile_n,
                                          uint32_t wave_m, uint32_t wave_n, uint32_t lane, uint32_t batch) {
   const uint64_t base_row = (uint64_t)batch * a.m;
+  const ProgRegs pr = load_prog_regs(a.post);
 #pragma unroll
   for (int bm = 0; bm < 2; ++bm) {
 #pragma unroll
@@ -91,9 +79,10 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, const v16f (&acc)[2]
         const uint32_t row0 = tile_m + wave_m * 64 + bm * 32 + g * 8 + (lane >> 5) * 4;
         if (col < a.n && row0 < a.m) {
           const uint32_t rv = min(4u, a.m - row0);
-          const float4 q = make_float4(acc[bm][bn][g * 4 + 0], acc[bm][bn][g * 4 + 1], acc[bm][bn][g * 4 + 2],
-                                       acc[bm][bn][g * 4 + 3]);
-          post_quad(a.post, q, row0, col, rv, base_row, a.n);
+          Quad q;
+#pragma unroll
+          for (int e = 0; e < kVec; ++e) q.v[e] = acc[bm][bn][g * 4 + e];
+          post_quad(a.post, pr, q, row0, col, rv, base_row, a.n);
         }
       }
     }

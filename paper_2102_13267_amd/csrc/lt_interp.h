@@ -1,15 +1,24 @@
 // Register-resident bytecode interpreter (device side).
 //
 // A program is a list of three-address instructions over up to 32 value slots.  Each lane
-// processes kVec = 4 elements, so a slot is four vector registers; the four "columns" of
-// the register file are kept in four 32-wide vector values that the compiler indexes with a
-// wave-uniform index (the instruction word comes from the kernel-argument segment through
-// scalar loads), which lowers to relative register addressing -- no scratch memory, no LDS.
-// The register file is passed and returned BY VALUE on purpose: element-indexed access to a
-// vector that lives behind a reference is turned into memory accesses and would spill it.
-// For the same reason slot indices are NOT masked here: an index the optimiser can prove in
-// range lets it rewrite "load vector, extract element" as a scalar load from a stack copy.
-// The host validates every program (slots < n_slots <= NS) before it is ever launched.
+// processes kVec = 4 elements, so a slot is four vector registers; the register file is four
+// NS-wide vector values (one per element lane) that the compiler indexes with a wave-uniform slot
+// number, which lowers to relative register addressing (s_set_gpr_idx + v_mov) -- no scratch
+// memory, no LDS.  Three rules keep it that way (each found by reading the generated ISA):
+//  * the register file is passed and returned BY VALUE: element-indexed access to a vector that
+//    lives behind a reference is turned into memory accesses;
+//  * slot indices are NOT masked: an index the optimiser can prove in range lets it rewrite
+//    "load vector, extract element" as a scalar load from a stack copy.  The host validates
+//    every program (slots < n_slots <= NS) before it is launched;
+//  * a slot is written exactly once per instruction, after the opcode switch, and input slots
+//    are written outside their "is this input present" branch: a write inside a branch makes
+//    the compiler copy the whole register file where the branches join.
+// The program itself is held in two vector registers per wavefront (lane j keeps instruction word
+// j and scalar-table entry j); fetching an instruction or a scalar operand is one v_readlane with
+// a wave-uniform lane number, so the interpreter loop touches no memory at all.
+// Multi-instruction math (division, square root, transcendentals) is evaluated one element lane
+// at a time behind scheduling barriers: interleaving four copies only inflates register
+// pressure, and occupancy is what hides HBM latency here.
 #ifndef LT_INTERP_H_
 #define LT_INTERP_H_
 
@@ -23,11 +32,22 @@ template <int NS> struct SlotVec;
 template <> struct SlotVec<16> { typedef float type __attribute__((ext_vector_type(16))); };
 template <> struct SlotVec<32> { typedef float type __attribute__((ext_vector_type(32))); };
 
-// Register file of NS value slots (16 or 32) x 4 element lanes.
+// Register file of NS value slots (16 or 32) x kVec element lanes.
 template <int NS> struct RF {
   typedef typename SlotVec<NS>::type vec;
-  vec e0, e1, e2, e3;   // element lane 0..3 of every slot
+  vec e[kVec];
 };
+
+struct Quad {
+  float v[kVec];
+};
+
+__device__ __forceinline__ Quad splat(float s) {
+  Quad q;
+#pragma unroll
+  for (int v = 0; v < kVec; ++v) q.v[v] = s;
+  return q;
+}
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
 
@@ -41,214 +61,282 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
 
 __device__ __forceinline__ float op_gelu(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
 __device__ __forceinline__ float op_gelu_grad(float dy, float x) {
-  float cdf = 0.5f * (1.0f + erff(x * 0.70710678118654752f));
-  float pdf = 0.39894228040143268f * __expf(-0.5f * x * x);
+  const float cdf = 0.5f * (1.0f + erff(x * 0.70710678118654752f));
+  const float pdf = 0.39894228040143268f * __expf(-0.5f * x * x);
   return dy * (cdf + x * pdf);
 }
 
-#define LT_RD4(i) make_float4(r0[i], r1[i], r2[i], r3[i])
-#define LT_WR4(i, q) \
-  {                  \
-    r0[i] = (q).x;   \
-    r1[i] = (q).y;   \
-    r2[i] = (q).z;   \
-    r3[i] = (q).w;   \
+struct ProgRegs {
+  uint32_t code;   // lane j: code[j]  (j < kMaxCode <= 64)
+  float scal;      // lane j: scal[j]  (j < kMaxScal)
+};
+
+__device__ __forceinline__ ProgRegs load_prog_regs(const EwProg& p) {
+  const uint32_t lane = threadIdx.x & 63u;
+  ProgRegs r;
+  r.code = lane < (uint32_t)kMaxCode ? p.code[lane] : 0u;
+  r.scal = lane < (uint32_t)kMaxScal ? p.scal[lane] : 0.0f;
+  return r;
+}
+
+__device__ __forceinline__ float scal_at(const ProgRegs& pr, uint32_t idx) {
+  return __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(pr.scal), (int)idx));
+}
+
+// cheap ops: all element lanes at once
+#define LT_MAP(EXPR)                                                \
+  _Pragma("unroll") for (int v = 0; v < kVec; ++v) {                \
+    const float xa = A.v[v], xb = B.v[v];                           \
+    (void)xb;                                                       \
+    q.v[v] = (EXPR);                                                \
   }
-// apply EXPR (in terms of xa, xb, xc) to the four element lanes
-#define LT_MAP(EXPR)                                   \
-  {                                                    \
-    float4 q;                                          \
-    { float xa = A.x, xb = B.x, xc = C.x; (void)xb; (void)xc; q.x = (EXPR); } \
-    { float xa = A.y, xb = B.y, xc = C.y; (void)xb; (void)xc; q.y = (EXPR); } \
-    { float xa = A.z, xb = B.z, xc = C.z; (void)xb; (void)xc; q.z = (EXPR); } \
-    { float xa = A.w, xb = B.w, xc = C.w; (void)xb; (void)xc; q.w = (EXPR); } \
-    LT_WR4(d, q);                                      \
+// multi-instruction ops: one element lane at a time
+#define LT_MAP_SERIAL(EXPR)                                         \
+  _Pragma("unroll") for (int v = 0; v < kVec; ++v) {                \
+    const float xa = A.v[v], xb = B.v[v];                           \
+    (void)xb;                                                       \
+    q.v[v] = (EXPR);                                                \
+    __builtin_amdgcn_sched_barrier(0);                              \
   }
 
 template <int NS>
-__device__ __forceinline__ RF<NS> interp(RF<NS> f, const EwProg& p) {
-  typename RF<NS>::vec r0 = f.e0, r1 = f.e1, r2 = f.e2, r3 = f.e3;
-  const uint32_t n = p.n_code;
+__device__ __forceinline__ RF<NS> interp(RF<NS> f, const ProgRegs pr, const uint32_t n) {
+  typename RF<NS>::vec r[kVec];
+#pragma unroll
+  for (int v = 0; v < kVec; ++v) r[v] = f.e[v];
   for (uint32_t pc = 0; pc < n; ++pc) {
-    const uint32_t w = p.code[pc];
+    const uint32_t w = (uint32_t)__builtin_amdgcn_readlane((int)pr.code, (int)pc);
     const uint32_t op = w & 0xffu, d = (w >> 8) & 31u;
     const uint32_t ia = (w >> 13) & 63u, ib = (w >> 19) & 63u, ic = (w >> 25) & 63u;
-    float4 A, B, C;
-    if (ia < 32u) { A = LT_RD4(ia); } else { float s = p.scal[ia - 32u]; A = make_float4(s, s, s, s); }
-    if (ib < 32u) { B = LT_RD4(ib); } else { float s = p.scal[ib - 32u]; B = make_float4(s, s, s, s); }
-    C = A;
-    if (op == kFma) {
-      if (ic < 32u) { C = LT_RD4(ic); } else { float s = p.scal[ic - 32u]; C = make_float4(s, s, s, s); }
+    Quad A, B = splat(0.0f), q;
+    // operand a is always a slot: the lowering puts a scalar operand second (using the
+    // reversed form of non-commutative ops) or materialises it with kSplat first
+#pragma unroll
+    for (int v = 0; v < kVec; ++v) A.v[v] = r[v][ia];
+    if (op >= kAdd) {   // binary and ternary ops: operand b is a slot or a scalar-table entry
+      if (ib < 32u) {
+#pragma unroll
+        for (int v = 0; v < kVec; ++v) B.v[v] = r[v][ib];
+      } else {
+        B = splat(scal_at(pr, ib - 32u));
+      }
     }
+    q = A;
     switch (op) {
-      case kMov: LT_MAP(xa) break;
-      case kNeg: LT_MAP(-xa) break;
-      case kAbs: LT_MAP(fabsf(xa)) break;
-      case kExp: LT_MAP(expf(xa)) break;
-      case kLog: LT_MAP(logf(xa)) break;
-      case kTanh: LT_MAP(tanhf(xa)) break;
-      case kSqrt: LT_MAP(sqrtf(xa)) break;
-      case kRsqrt: LT_MAP(rsqrtf(xa)) break;
-      case kRecip: LT_MAP(1.0f / xa) break;
-      case kRelu: LT_MAP(xa > 0.0f ? xa : 0.0f) break;
-      case kGelu: LT_MAP(op_gelu(xa)) break;
-      case kSquare: LT_MAP(xa * xa) break;
-      case kSigmoid: LT_MAP(1.0f / (1.0f + expf(-xa))) break;
-      case kRoundBf16: LT_MAP(bf16_to_f32(f32_to_bf16(xa))) break;
-      case kAdd: LT_MAP(xa + xb) break;
-      case kSub: LT_MAP(xa - xb) break;
       case kMul: LT_MAP(xa * xb) break;
-      case kDiv: LT_MAP(xa / xb) break;
+      case kAdd: LT_MAP(xa + xb) break;
+      case kFma: {
+        Quad C;
+        if (ic < 32u) {
+#pragma unroll
+          for (int v = 0; v < kVec; ++v) C.v[v] = r[v][ic];
+        } else {
+          C = splat(scal_at(pr, ic - 32u));
+        }
+#pragma unroll
+        for (int v = 0; v < kVec; ++v) q.v[v] = fmaf(A.v[v], B.v[v], C.v[v]);
+      } break;
+      case kSub: LT_MAP(xa - xb) break;
+      case kRsub: LT_MAP(xb - xa) break;
+      case kDiv: LT_MAP_SERIAL(xa / xb) break;
+      case kRdiv: LT_MAP_SERIAL(xb / xa) break;
       case kMax: LT_MAP((xa != xa || xb != xb) ? (xa + xb) : fmaxf(xa, xb)) break;
       case kMin: LT_MAP((xa != xa || xb != xb) ? (xa + xb) : fminf(xa, xb)) break;
       case kReluGrad: LT_MAP(xb > 0.0f ? xa : 0.0f) break;
-      case kGeluGrad: LT_MAP(op_gelu_grad(xa, xb)) break;
-      case kFma: LT_MAP(fmaf(xa, xb, xc)) break;
+      case kRreluGrad: LT_MAP(xa > 0.0f ? xb : 0.0f) break;
+      case kGeluGrad: LT_MAP_SERIAL(op_gelu_grad(xa, xb)) break;
+      case kRgeluGrad: LT_MAP_SERIAL(op_gelu_grad(xb, xa)) break;
+      case kMov: break;
+      case kNeg: LT_MAP(-xa) break;
+      case kAbs: LT_MAP(fabsf(xa)) break;
+      case kSquare: LT_MAP(xa * xa) break;
+      case kRelu: LT_MAP(xa > 0.0f ? xa : 0.0f) break;
+      case kSqrt: LT_MAP_SERIAL(sqrtf(xa)) break;
+      case kRsqrt: LT_MAP_SERIAL(rsqrtf(xa)) break;
+      case kRecip: LT_MAP_SERIAL(1.0f / xa) break;
+      case kExp: LT_MAP_SERIAL(expf(xa)) break;
+      case kLog: LT_MAP_SERIAL(logf(xa)) break;
+      case kTanh: LT_MAP_SERIAL(tanhf(xa)) break;
+      case kGelu: LT_MAP_SERIAL(op_gelu(xa)) break;
+      case kSigmoid: LT_MAP_SERIAL(1.0f / (1.0f + expf(-xa))) break;
+      case kRoundBf16: LT_MAP(bf16_to_f32(f32_to_bf16(xa))) break;
+      case kSplat: q = splat(scal_at(pr, ib - 32u)); break;
       default: break;
     }
+#pragma unroll
+    for (int v = 0; v < kVec; ++v) r[v][d] = q.v[v];
   }
   RF<NS> o;
-  o.e0 = r0; o.e1 = r1; o.e2 = r2; o.e3 = r3;
+#pragma unroll
+  for (int v = 0; v < kVec; ++v) o.e[v] = r[v];
   return o;
 }
 
 // ---- loads -------------------------------------------------------------------------------
 
+// F32: the host promises that every input and output of the program is fp32, which removes the
+// dtype branches (and their registers) from the streaming kernels.
+template <bool F32 = false>
 __device__ __forceinline__ float load_elem(const void* ptr, uint32_t dtype, uint64_t idx) {
-  if (dtype == kBF16) return bf16_to_f32(((const uint16_t*)ptr)[idx]);
-  if (dtype == kI32) return (float)((const int32_t*)ptr)[idx];
+  if (!F32) {
+    if (dtype == kBF16) return bf16_to_f32(((const uint16_t*)ptr)[idx]);
+    if (dtype == kI32) return (float)((const int32_t*)ptr)[idx];
+  }
   return ((const float*)ptr)[idx];
 }
 
-__device__ __forceinline__ float4 load_vec4(const void* ptr, uint32_t dtype, uint64_t idx) {
-  if (dtype == kBF16) {
-    uint2 u = *(const uint2*)((const uint16_t*)ptr + idx);
-    return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u),
-                       __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xffff0000u));
+// Four consecutive elements starting at element `base + lane` of `ptr`.  `base` is wave-uniform
+// and is folded into the (scalar) base address; only the 32-bit lane offset lives in a vector
+// register, so all inputs of a program share one address register per lane.
+template <bool F32 = false>
+__device__ __forceinline__ Quad load_vec4(const void* ptr, uint32_t dtype, uint64_t base, uint32_t lane) {
+  Quad q;
+  if (!F32 && dtype == kBF16) {
+    const char* b = (const char*)ptr + base * 2u;
+    const uint2 u = *(const uint2*)(b + lane * 2u);
+    q.v[0] = __uint_as_float(u.x << 16);
+    q.v[1] = __uint_as_float(u.x & 0xffff0000u);
+    q.v[2] = __uint_as_float(u.y << 16);
+    q.v[3] = __uint_as_float(u.y & 0xffff0000u);
+  } else {
+    const char* b = (const char*)ptr + base * 4u;
+    const float4 t = *(const float4*)(b + lane * 4u);
+    q.v[0] = t.x; q.v[1] = t.y; q.v[2] = t.z; q.v[3] = t.w;
   }
-  return *(const float4*)((const float*)ptr + idx);
-}
-
-__device__ __forceinline__ uint64_t strided_index(const EwProg& p, const EwIn& in, uint64_t i) {
-  uint64_t c3 = i % p.dims[3]; i /= p.dims[3];
-  uint64_t c2 = i % p.dims[2]; i /= p.dims[2];
-  uint64_t c1 = i % p.dims[1]; i /= p.dims[1];
-  return (uint64_t)((int64_t)i * in.stride[0] + (int64_t)c1 * in.stride[1] + (int64_t)c2 * in.stride[2] +
-                    (int64_t)c3 * in.stride[3]);
-}
-
-// Load the (up to) four consecutive elements i .. i+3 of the iteration space for input k.
-// nvalid < 4 at a ragged tail; missing elements read as `pad`.
-__device__ __forceinline__ float4 load_input(const EwProg& p, int k, uint64_t i, uint32_t nvalid, float pad) {
-  const EwIn& in = p.in[k];
-  const uint32_t mode = in.mode, dt = in.dtype;
-  if (mode == kScalar) {
-    float s = load_elem(in.ptr, dt, 0);
-    return make_float4(s, s, s, s);
-  }
-  const bool fast = p.vec_ok && nvalid == 4u;
-  if (mode == kFull) {
-    if (p.full_vec_ok && nvalid == 4u) return load_vec4(in.ptr, dt, i);
-    float4 q = make_float4(pad, pad, pad, pad);
-    if (nvalid > 0u) q.x = load_elem(in.ptr, dt, i);
-    if (nvalid > 1u) q.y = load_elem(in.ptr, dt, i + 1);
-    if (nvalid > 2u) q.z = load_elem(in.ptr, dt, i + 2);
-    if (nvalid > 3u) q.w = load_elem(in.ptr, dt, i + 3);
-    return q;
-  }
-  if (mode == kRowVec) {
-    if (fast) return load_vec4(in.ptr, dt, i % p.cols);
-    float4 q = make_float4(pad, pad, pad, pad);
-    if (nvalid > 0u) q.x = load_elem(in.ptr, dt, i % p.cols);
-    if (nvalid > 1u) q.y = load_elem(in.ptr, dt, (i + 1) % p.cols);
-    if (nvalid > 2u) q.z = load_elem(in.ptr, dt, (i + 2) % p.cols);
-    if (nvalid > 3u) q.w = load_elem(in.ptr, dt, (i + 3) % p.cols);
-    return q;
-  }
-  if (mode == kColVec) {
-    if (p.vec_ok) {
-      float s = load_elem(in.ptr, dt, i / p.cols);
-      return make_float4(s, s, s, s);
-    }
-    float4 q = make_float4(pad, pad, pad, pad);
-    if (nvalid > 0u) q.x = load_elem(in.ptr, dt, i / p.cols);
-    if (nvalid > 1u) q.y = load_elem(in.ptr, dt, (i + 1) / p.cols);
-    if (nvalid > 2u) q.z = load_elem(in.ptr, dt, (i + 2) / p.cols);
-    if (nvalid > 3u) q.w = load_elem(in.ptr, dt, (i + 3) / p.cols);
-    return q;
-  }
-  // kStrided
-  float4 q = make_float4(pad, pad, pad, pad);
-  if (nvalid > 0u) q.x = load_elem(in.ptr, dt, strided_index(p, in, i));
-  if (nvalid > 1u) q.y = load_elem(in.ptr, dt, strided_index(p, in, i + 1));
-  if (nvalid > 2u) q.z = load_elem(in.ptr, dt, strided_index(p, in, i + 2));
-  if (nvalid > 3u) q.w = load_elem(in.ptr, dt, strided_index(p, in, i + 3));
   return q;
 }
 
-// Put all inputs of the program into slots 0 .. n_in-1.  The loop is fully unrolled so the
-// slot index is a compile-time constant and all loads are in flight before the first use.
-template <int NS>
-__device__ __forceinline__ RF<NS> load_inputs(RF<NS> f, const EwProg& p, uint64_t i, uint32_t nvalid) {
-  typename RF<NS>::vec r0 = f.e0, r1 = f.e1, r2 = f.e2, r3 = f.e3;
-  const uint32_t n_in = p.n_in;
+__device__ __forceinline__ uint64_t strided_index(const EwProg& p, const EwIn& in, uint64_t i) {
+  uint32_t j = (uint32_t)i;
+  const uint32_t c3 = j % p.dims[3]; j /= p.dims[3];
+  const uint32_t c2 = j % p.dims[2]; j /= p.dims[2];
+  const uint32_t c1 = j % p.dims[1]; j /= p.dims[1];
+  return (uint64_t)((int64_t)j * in.stride[0] + (int64_t)c1 * in.stride[1] + (int64_t)c2 * in.stride[2] +
+                    (int64_t)c3 * in.stride[3]);
+}
+
+// Flat element index -> element offset inside input `in` (general, one element at a time).
+__device__ __forceinline__ uint64_t elem_offset(const EwProg& p, const EwIn& in, uint64_t i) {
+  const uint32_t mode = in.mode;
+  if (mode == kFull) return i;
+  if (mode == kScalar) return 0;
+  if (mode == kRowVec) return (uint32_t)i % p.cols;
+  if (mode == kColVec) return (uint32_t)i / p.cols;
+  return strided_index(p, in, i);
+}
+
+// General path: ragged tails, rows that are not a multiple of four, strided views.  Kept as a
+// rolled loop: it is rare, and code size matters more than its speed (the instruction cache is
+// shared by neighbouring compute units).
+__device__ __forceinline__ Quad load_input_slow(const EwProg& p, const EwIn& in, uint64_t i, uint32_t nvalid) {
+  Quad q = splat(0.0f);
+#pragma unroll 1
+  for (uint32_t e = 0; e < nvalid; ++e) {
+    const float x = load_elem<false>(in.ptr, in.dtype, elem_offset(p, in, i + e));
 #pragma unroll
-  for (int k = 0; k < kMaxIn; ++k) {
-    if ((uint32_t)k < n_in) {
-      float4 q = load_input(p, k, i, nvalid, 0.0f);
-      LT_WR4(k, q);
-    }
+    for (int v = 0; v < kVec; ++v) q.v[v] = e == (uint32_t)v ? x : q.v[v];
   }
-  RF<NS> o;
-  o.e0 = r0; o.e1 = r1; o.e2 = r2; o.e3 = r3;
-  return o;
+  return q;
+}
+
+// Fetch the four consecutive elements i .. i+3 (i = base + lane, base wave-uniform) of the
+// iteration space for one input.  FAST: the host promises full, aligned 4-vectors and no strided
+// input, so the element-by-element path is not even compiled in.
+template <bool FAST, bool F32>
+__device__ __forceinline__ Quad load_input(const EwProg& p, const EwIn& in, uint64_t base, uint32_t lane, uint32_t i_div,
+                                           uint32_t i_mod, uint32_t nvalid) {
+  const uint32_t fetch = (FAST || nvalid == (uint32_t)kVec) ? in.fetch : (uint32_t)kFetchSlow;
+  if (!FAST && fetch == kFetchSlow) return load_input_slow(p, in, base + lane, nvalid);
+  const uint32_t mode = in.mode;
+  if (fetch == kFetchVec4) {
+    if (mode == kFull) return load_vec4<F32>(in.ptr, in.dtype, base, lane);
+    return load_vec4<F32>(in.ptr, in.dtype, 0, i_mod);   // kRowVec
+  }
+  return splat(load_elem<F32>(in.ptr, in.dtype, mode == kColVec ? i_div : 0u));
+}
+
+// Put the inputs of the program into slots 0 .. n_in-1.  The loop over inputs is fully unrolled
+// so that the slot index is a compile-time constant and every load is in flight before the first
+// use.  MAXIN bounds the unrolling (and with it the registers reserved for loads in flight).
+template <int NS, int MAXIN = kMaxIn, bool FAST = false, bool F32 = false>
+__device__ __forceinline__ RF<NS> load_inputs(RF<NS> f, const EwProg& p, uint64_t base, uint32_t lane, uint32_t nvalid) {
+  const uint32_t n_in = p.n_in;
+  uint32_t i_div = 0, i_mod = 0;
+  if (p.needs_divmod) {
+    const uint32_t i = (uint32_t)base + lane;
+    i_div = i / p.cols;
+    i_mod = i - i_div * p.cols;
+  }
+#pragma unroll
+  for (int k = 0; k < MAXIN; ++k) {
+    Quad q = splat(0.0f);
+    if ((uint32_t)k < n_in) q = load_input<FAST, F32>(p, p.in[k], base, lane, i_div, i_mod, nvalid);
+#pragma unroll
+    for (int v = 0; v < kVec; ++v) f.e[v][k] = q.v[v];
+  }
+  return f;
 }
 
 template <int NS>
-__device__ __forceinline__ float4 rf_get(RF<NS> f, uint32_t slot) {
-  typename RF<NS>::vec r0 = f.e0, r1 = f.e1, r2 = f.e2, r3 = f.e3;
-  return LT_RD4(slot);
+__device__ __forceinline__ Quad rf_get(RF<NS> f, uint32_t slot) {
+  Quad q;
+#pragma unroll
+  for (int v = 0; v < kVec; ++v) {
+    typename RF<NS>::vec t = f.e[v];
+    q.v[v] = t[slot];
+  }
+  return q;
 }
 
 template <int NS>
-__device__ __forceinline__ RF<NS> rf_set(RF<NS> f, uint32_t slot, float4 q) {
-  typename RF<NS>::vec r0 = f.e0, r1 = f.e1, r2 = f.e2, r3 = f.e3;
-  LT_WR4(slot, q);
-  RF<NS> o;
-  o.e0 = r0; o.e1 = r1; o.e2 = r2; o.e3 = r3;
-  return o;
+__device__ __forceinline__ RF<NS> rf_set(RF<NS> f, uint32_t slot, Quad q) {
+#pragma unroll
+  for (int v = 0; v < kVec; ++v) {
+    typename RF<NS>::vec t = f.e[v];
+    t[slot] = q.v[v];
+    f.e[v] = t;
+  }
+  return f;
 }
 
+template <bool F32 = false>
 __device__ __forceinline__ void store_elem(void* ptr, uint32_t dtype, uint64_t idx, float v) {
-  if (dtype == kBF16) ((uint16_t*)ptr)[idx] = f32_to_bf16(v);
+  if (!F32 && dtype == kBF16) ((uint16_t*)ptr)[idx] = f32_to_bf16(v);
   else ((float*)ptr)[idx] = v;
 }
 
-// Store the outputs of the program for elements i .. i+nvalid-1 (flat, contiguous outputs).
-template <int NS>
-__device__ __forceinline__ void store_outputs(RF<NS> f, const EwProg& p, uint64_t i, uint32_t nvalid) {
+template <bool F32 = false>
+__device__ __forceinline__ void store_vec4(void* ptr, uint32_t dtype, uint64_t base, uint32_t lane, const Quad& q) {
+  if (!F32 && dtype == kBF16) {
+    uint2 u;
+    u.x = (uint32_t)f32_to_bf16(q.v[0]) | ((uint32_t)f32_to_bf16(q.v[1]) << 16);
+    u.y = (uint32_t)f32_to_bf16(q.v[2]) | ((uint32_t)f32_to_bf16(q.v[3]) << 16);
+    char* b = (char*)ptr + base * 2u;
+    *(uint2*)(b + lane * 2u) = u;
+  } else {
+    char* b = (char*)ptr + base * 4u;
+    *(float4*)(b + lane * 4u) = make_float4(q.v[0], q.v[1], q.v[2], q.v[3]);
+  }
+}
+
+// Store the outputs of the program for elements i .. i+nvalid-1, i = base + lane (flat,
+// contiguous outputs).
+template <int NS, bool FAST = false, bool F32 = false>
+__device__ __forceinline__ void store_outputs(RF<NS> f, const EwProg& p, uint64_t base, uint32_t lane, uint32_t nvalid) {
   const uint32_t n_out = p.n_out;
 #pragma unroll
   for (int o = 0; o < kMaxOut; ++o) {
     if ((uint32_t)o < n_out) {
       const EwOut& out = p.out[o];
-      float4 q = rf_get(f, out.slot);
+      const Quad q = rf_get<NS>(f, out.slot);
       if (out.scalar) {
-        if (i == 0) store_elem(out.ptr, out.dtype, 0, q.x);
-      } else if (p.full_vec_ok && nvalid == 4u) {
-        if (out.dtype == kBF16) {
-          uint2 u;
-          u.x = (uint32_t)f32_to_bf16(q.x) | ((uint32_t)f32_to_bf16(q.y) << 16);
-          u.y = (uint32_t)f32_to_bf16(q.z) | ((uint32_t)f32_to_bf16(q.w) << 16);
-          *(uint2*)((uint16_t*)out.ptr + i) = u;
-        } else {
-          *(float4*)((float*)out.ptr + i) = q;
-        }
+        if (base + lane == 0) store_elem<F32>(out.ptr, out.dtype, 0, q.v[0]);
+      } else if (FAST || (p.full_vec_ok && nvalid == (uint32_t)kVec)) {
+        store_vec4<F32>(out.ptr, out.dtype, base, lane, q);
       } else {
-        if (nvalid > 0u) store_elem(out.ptr, out.dtype, i, q.x);
-        if (nvalid > 1u) store_elem(out.ptr, out.dtype, i + 1, q.y);
-        if (nvalid > 2u) store_elem(out.ptr, out.dtype, i + 2, q.z);
-        if (nvalid > 3u) store_elem(out.ptr, out.dtype, i + 3, q.w);
+#pragma unroll 1
+        for (uint32_t e = 0; e < nvalid; ++e)
+          store_elem<F32>(out.ptr, out.dtype, base + lane + e, e == 0 ? q.v[0] : e == 1 ? q.v[1] : e == 2 ? q.v[2] : q.v[3]);
       }
     }
   }
@@ -257,7 +345,8 @@ __device__ __forceinline__ void store_outputs(RF<NS> f, const EwProg& p, uint64_
 template <int NS>
 __device__ __forceinline__ RF<NS> rf_zero() {
   RF<NS> f;
-  f.e0 = 0.0f; f.e1 = 0.0f; f.e2 = 0.0f; f.e3 = 0.0f;
+#pragma unroll
+  for (int v = 0; v < kVec; ++v) f.e[v] = 0.0f;
   return f;
 }
 

@@ -9,17 +9,20 @@ namespace ltk {
 
 // Run the post program of an anchored region for the flat elements i .. i+nvalid-1 of its
 // space, with the anchor's value(s) already placed in slot post.anchor_slot.
-__device__ __forceinline__ void run_post(const EwProg& post, float4 anchor, uint64_t i, uint32_t nvalid) {
-  RF<16> f = load_inputs<16>(rf_zero<16>(), post, i, nvalid);
+__device__ __forceinline__ void run_post(const EwProg& post, const ProgRegs post_regs, Quad anchor, uint64_t i,
+                                         uint32_t nvalid) {
+  RF<16> f = load_inputs<16>(rf_zero<16>(), post, 0, (uint32_t)i, nvalid);
   f = rf_set(f, post.anchor_slot, anchor);
-  f = interp<16>(f, post);
-  store_outputs<16>(f, post, i, nvalid);
+  f = interp<16>(f, post_regs, post.n_code);
+  store_outputs<16>(f, post, 0, (uint32_t)i, nvalid);
 }
 
 // Row reduction.  threads_per_row is 64 (one wave per row, four rows per workgroup) or 256.
 __global__ __launch_bounds__(kBlock) void lt_row_reduce_kernel(const RowArgs a) {
   __shared__ float lds[kBlock / 64];
   const EwProg& pro = a.pro;
+  const ProgRegs pro_regs = load_prog_regs(a.pro), post_regs = load_prog_regs(a.post);
+  const uint32_t pro_n = a.pro.n_code;
   const uint32_t tpr = a.threads_per_row;
   const uint32_t rows_per_block = kBlock / tpr;
   const uint32_t lane = threadIdx.x % tpr;
@@ -31,9 +34,9 @@ __global__ __launch_bounds__(kBlock) void lt_row_reduce_kernel(const RowArgs a) 
     if (row < a.rows) {
       for (uint32_t c = lane * kVec; c < a.cols; c += tpr * kVec) {
         const uint32_t nvalid = (a.cols - c >= (uint32_t)kVec) ? (uint32_t)kVec : a.cols - c;
-        const uint64_t i = (uint64_t)row * a.cols + c;
-        RF<16> f = load_inputs<16>(rf_zero<16>(), pro, i, nvalid);
-        f = interp<16>(f, pro);
+        const uint32_t i = row * a.cols + c;
+        RF<16> f = load_inputs<16>(rf_zero<16>(), pro, 0, i, nvalid);
+        f = interp<16>(f, pro_regs, pro_n);
         acc = fold_vec(a.red, acc, rf_get(f, pro.anchor_slot), nvalid);
       }
     }
@@ -41,7 +44,7 @@ __global__ __launch_bounds__(kBlock) void lt_row_reduce_kernel(const RowArgs a) 
     if (tpr == 64u) r = wave_reduce(a.red, acc);
     else r = block_reduce(a.red, acc, lds);
     if (a.red == kRedMean) r = r / (float)a.cols;
-    if (lane == 0 && row < a.rows) run_post(a.post, make_float4(r, r, r, r), row, 1u);
+    if (lane == 0 && row < a.rows) run_post(a.post, post_regs, splat(r), row, 1u);
   }
 }
 
@@ -50,14 +53,16 @@ __global__ __launch_bounds__(kBlock) void lt_all_reduce_kernel(const AllArgs a) 
   __shared__ float lds[kBlock / 64];
   __shared__ uint32_t is_last;
   const EwProg& pro = a.pro;
+  const ProgRegs pro_regs = load_prog_regs(a.pro), post_regs = load_prog_regs(a.post);
+  const uint32_t pro_n = a.pro.n_code;
   const uint64_t n = pro.n;
   const uint64_t nvec = (n + kVec - 1) / kVec;
   float acc = red_identity(a.red);
   for (uint64_t v = (uint64_t)blockIdx.x * kBlock + threadIdx.x; v < nvec; v += (uint64_t)gridDim.x * kBlock) {
     const uint64_t i = v * kVec;
     const uint32_t nvalid = (n - i >= (uint64_t)kVec) ? (uint32_t)kVec : (uint32_t)(n - i);
-    RF<16> f = load_inputs<16>(rf_zero<16>(), pro, i, nvalid);
-    f = interp<16>(f, pro);
+    RF<16> f = load_inputs<16>(rf_zero<16>(), pro, 0, (uint32_t)i, nvalid);
+    f = interp<16>(f, pro_regs, pro_n);
     acc = fold_vec(a.red, acc, rf_get(f, pro.anchor_slot), nvalid);
   }
   float r = block_reduce(a.red, acc, lds);
@@ -83,7 +88,7 @@ __global__ __launch_bounds__(kBlock) void lt_all_reduce_kernel(const AllArgs a) 
   for (uint64_t v = threadIdx.x; v < pvec; v += kBlock) {
     const uint64_t i = v * kVec;
     const uint32_t nvalid = (pn - i >= (uint64_t)kVec) ? (uint32_t)kVec : (uint32_t)(pn - i);
-    run_post(post, make_float4(r, r, r, r), i, nvalid);
+    run_post(post, post_regs, splat(r), i, nvalid);
   }
 }
 
@@ -93,6 +98,8 @@ __global__ __launch_bounds__(kBlock) void lt_col_reduce_kernel(const ColArgs a) 
   __shared__ float4 lds[kBlock];
   __shared__ uint32_t is_last;
   const EwProg& pro = a.pro;
+  const ProgRegs pro_regs = load_prog_regs(a.pro), post_regs = load_prog_regs(a.post);
+  const uint32_t pro_n = a.pro.n_code;
   const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint32_t c = blockIdx.x * 256u + lane * kVec;
   const uint32_t nvalid = c >= a.cols ? 0u : ((a.cols - c >= (uint32_t)kVec) ? (uint32_t)kVec : a.cols - c);
@@ -103,14 +110,14 @@ __global__ __launch_bounds__(kBlock) void lt_col_reduce_kernel(const ColArgs a) 
   float4 acc = make_float4(id, id, id, id);
   if (nvalid) {
     for (uint32_t r = r0 + wave; r < r1; r += kBlock / 64) {
-      const uint64_t i = (uint64_t)r * a.cols + c;
-      RF<16> f = load_inputs<16>(rf_zero<16>(), pro, i, nvalid);
-      f = interp<16>(f, pro);
-      float4 q = rf_get(f, pro.anchor_slot);
-      acc.x = red_combine(a.red, acc.x, q.x);
-      acc.y = red_combine(a.red, acc.y, q.y);
-      acc.z = red_combine(a.red, acc.z, q.z);
-      acc.w = red_combine(a.red, acc.w, q.w);
+      const uint32_t i = r * a.cols + c;
+      RF<16> f = load_inputs<16>(rf_zero<16>(), pro, 0, i, nvalid);
+      f = interp<16>(f, pro_regs, pro_n);
+      const Quad q = rf_get(f, pro.anchor_slot);
+      acc.x = red_combine(a.red, acc.x, q.v[0]);
+      acc.y = red_combine(a.red, acc.y, q.v[1]);
+      acc.z = red_combine(a.red, acc.z, q.v[2]);
+      acc.w = red_combine(a.red, acc.w, q.v[3]);
     }
   }
   lds[threadIdx.x] = acc;
@@ -155,7 +162,9 @@ __global__ __launch_bounds__(kBlock) void lt_col_reduce_kernel(const ColArgs a) 
     const float inv = 1.0f / (float)a.rows;
     acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
   }
-  run_post(a.post, acc, c, nvalid);
+  Quad accq;
+  accq.v[0] = acc.x; accq.v[1] = acc.y; accq.v[2] = acc.z; accq.v[3] = acc.w;
+  run_post(a.post, post_regs, accq, c, nvalid);
 }
 
 

@@ -32,12 +32,19 @@ enum : uint32_t {
   kStrided = 4   // sum_k coord_k(i) * stride[k] over the (<= 4-d) iteration space
 };
 
-// interpreter opcodes
+// interpreter opcodes.  Unary ops come first: the interpreter reads operand b only for
+// op >= kAdd.  Operand a is always a value slot; a scalar-table operand can only be b (or c of
+// kFma), so non-commutative ops have a reversed form ("kRsub": b - a).
 enum : uint32_t {
   kMov = 0, kNeg, kAbs, kExp, kLog, kTanh, kSqrt, kRsqrt, kRecip, kRelu, kGelu, kSquare,
   kSigmoid, kRoundBf16,
-  kAdd, kSub, kMul, kDiv, kMax, kMin, kReluGrad, kGeluGrad,
+  kAdd, kSub, kRsub, kMul, kDiv, kRdiv, kMax, kMin,
+  kReluGrad,     // b > 0 ? a : 0     (a = dy, b = x)
+  kRreluGrad,    // a > 0 ? b : 0
+  kGeluGrad,     // a * gelu'(b)
+  kRgeluGrad,    // b * gelu'(a)
   kFma,          // a*b + c
+  kSplat,        // b (a scalar-table entry) replicated
   kNumOps
 };
 
@@ -47,10 +54,19 @@ inline uint32_t encode(uint32_t op, uint32_t dst, uint32_t a, uint32_t b = 0, ui
   return op | (dst << 8) | (a << 13) | (b << 19) | (c << 25);
 }
 
+// how the kernels fetch an input on their fast path (full 4-vectors)
+enum : uint32_t {
+  kFetchVec4 = 0,   // one 16-byte (8-byte for bf16) load of four consecutive elements
+  kFetchBcast = 1,  // one element, replicated to the four lanes
+  kFetchSlow = 2    // element by element through the general addressing code
+};
+
 struct EwIn {
   const void* ptr;
   uint32_t mode;
   uint32_t dtype;
+  uint32_t fetch;      // kFetch*: decided by the host from mode, cols and alignment
+  uint32_t pad;
   int64_t stride[4];   // kStrided only, in elements
 };
 
@@ -68,6 +84,10 @@ struct EwProg {
   uint32_t full_vec_ok;  // 1: every 4-vector of the flat space starts at a multiple of 4
   uint32_t cols;       // last dimension of the iteration space (>= 1)
   uint32_t n_slots;    // value slots the program uses (selects the 16- or 32-slot kernel)
+  uint32_t needs_divmod;  // 1: some input is addressed by i / cols or i % cols
+  uint32_t fast;       // 1: n % 4 == 0, every input fetches as vec4 / broadcast, outputs contiguous
+  uint32_t all_f32;    // 1: every input and output is fp32
+  uint32_t pad2;
   uint64_t n;          // elements of the iteration space
   uint32_t dims[4];    // iteration space collapsed to 4 dims (kStrided addressing)
   EwIn in[kMaxIn];

@@ -559,6 +559,7 @@ struct Lowering {
                   const std::vector<Val>& outputs, bool full_vec, ProgBuild* pb) {
     ltk::EwProg& p = pb->prog;
     const int64_t n = count(space);
+    if (n >= ((int64_t)1 << 32)) return bad(LT_ERR_UNSUPPORTED, "iteration space of 2^32 or more elements");
     p.n = (uint64_t)n;
     p.cols = (uint32_t)(space.empty() ? 1 : std::max<int64_t>(space.back(), 1));
     p.vec_ok = (p.cols % 4u == 0u) ? 1u : 0u;
@@ -650,6 +651,12 @@ struct Lowering {
           in.stride[d] = d < off ? 0 : acc.stride[d - off];
         }
       }
+      in.fetch = ltk::kFetchSlow;
+      if (in.mode == ltk::kScalar) in.fetch = ltk::kFetchBcast;
+      else if (in.mode == ltk::kFull && p.full_vec_ok) in.fetch = ltk::kFetchVec4;
+      else if (in.mode == ltk::kRowVec && p.vec_ok) in.fetch = ltk::kFetchVec4;
+      else if (in.mode == ltk::kColVec && p.vec_ok) in.fetch = ltk::kFetchBcast;
+      if (in.mode == ltk::kRowVec || in.mode == ltk::kColVec) p.needs_divmod = 1;
       if (in.mode != ltk::kStrided && space.size() <= 4) {
         const int off = 4 - (int)space.size();
         for (int d = 0; d < 4; ++d) p.dims[d] = d < off ? 1u : (uint32_t)space[d - off];
@@ -744,14 +751,13 @@ struct Lowering {
       const Node* n = nd[m];
       const auto& o = rins[m];
       if (n->dtype != LT_F32 && n->dtype != LT_BF16) return bad(LT_ERR_UNSUPPORTED, "integer elementwise arithmetic has no lowering");
-      uint32_t ea = 0, eb = 0, ec = 0;
+      uint32_t enc[3] = {0, 0, 0};
       if (n->op == LT_OP_PERMUTE) {
-        ea = (uint32_t)permute_input[m];
+        enc[0] = (uint32_t)permute_input[m];
       } else {
         const bool recip_b = n->op == LT_OP_DIV && nd[o[1].node]->op == OP_SCALAR_PARAM;
-        if (!operand(o[0], false, &ea)) return false;
-        if (o.size() > 1 && !operand(o[1], recip_b, &eb)) return false;
-        if (o.size() > 2 && !operand(o[2], false, &ec)) return false;
+        for (size_t q = 0; q < o.size(); ++q)
+          if (!operand(o[q], q == 1 && recip_b, &enc[q])) return false;
       }
       // operands whose last use is this member free their slots before the result is placed
       for (Val v : o) {
@@ -764,7 +770,7 @@ struct Lowering {
       const int dst = take_slot();
       if (dst < 0) return bad(LT_ERR_UNSUPPORTED, "region needs more than 32 value slots");
       info[find_val(Val{m, 0})].slot = dst;
-      uint32_t op;
+      uint32_t op, rop = ltk::kNumOps;     // rop: the form with operands a and b exchanged
       switch (n->op) {
         case LT_OP_NEG: op = ltk::kNeg; break;
         case LT_OP_ABS: op = ltk::kAbs; break;
@@ -780,19 +786,50 @@ struct Lowering {
         case LT_OP_SIGMOID: op = ltk::kSigmoid; break;
         case LT_OP_CAST: op = n->dtype == LT_BF16 ? ltk::kRoundBf16 : ltk::kMov; break;
         case LT_OP_EXPAND: case LT_OP_RESHAPE: case LT_OP_PERMUTE: op = ltk::kMov; break;
-        case LT_OP_ADD: op = o.size() == 3 ? ltk::kFma : ltk::kAdd; break;
-        case LT_OP_SUB: op = ltk::kSub; break;
-        case LT_OP_MUL: op = ltk::kMul; break;
-        case LT_OP_DIV: op = (nd[o[1].node]->op == OP_SCALAR_PARAM) ? ltk::kMul : ltk::kDiv; break;
-        case LT_OP_MAXIMUM: op = ltk::kMax; break;
-        case LT_OP_MINIMUM: op = ltk::kMin; break;
-        case LT_OP_RELU_GRAD: op = ltk::kReluGrad; break;
-        case LT_OP_GELU_GRAD: op = ltk::kGeluGrad; break;
+        case LT_OP_ADD: op = o.size() == 3 ? ltk::kFma : ltk::kAdd; rop = ltk::kAdd; break;
+        case LT_OP_SUB: op = ltk::kSub; rop = ltk::kRsub; break;
+        case LT_OP_MUL: op = rop = ltk::kMul; break;
+        case LT_OP_DIV:
+          if (nd[o[1].node]->op == OP_SCALAR_PARAM) op = rop = ltk::kMul;   // times the reciprocal
+          else { op = ltk::kDiv; rop = ltk::kRdiv; }
+          break;
+        case LT_OP_MAXIMUM: op = rop = ltk::kMax; break;
+        case LT_OP_MINIMUM: op = rop = ltk::kMin; break;
+        case LT_OP_RELU_GRAD: op = ltk::kReluGrad; rop = ltk::kRreluGrad; break;
+        case LT_OP_GELU_GRAD: op = ltk::kGeluGrad; rop = ltk::kRgeluGrad; break;
         default: return bad(LT_ERR_UNSUPPORTED, "opcode cannot be a member of an elementwise program");
       }
+      // operand a of an instruction must be a slot: a scalar there is exchanged with b when b
+      // is a slot, else copied into the destination slot first
+      auto splat_into_dst = [&](uint32_t scalar_enc) { return emit(ltk::kSplat, (uint32_t)dst, 0, scalar_enc); };
       bool okk;
-      if (op == ltk::kFma) okk = emit(op, (uint32_t)dst, ec, eb, ea);   // alpha*b + a
-      else okk = emit(op, (uint32_t)dst, ea, eb);
+      if (op == ltk::kFma) {
+        // a + alpha*b  ->  fma(x = b, y = alpha, z = a); x must be a slot
+        uint32_t x = enc[1], y = enc[2], z = enc[0];
+        if (x >= 32u && y < 32u) std::swap(x, y);
+        if (x >= 32u) {
+          if (!splat_into_dst(x)) return false;
+          x = (uint32_t)dst;
+        }
+        okk = emit(op, (uint32_t)dst, x, y, z);
+      } else if (op >= ltk::kAdd) {
+        uint32_t a = enc[0], b = enc[1];
+        if (a >= 32u && b < 32u) {
+          std::swap(a, b);
+          op = rop;
+        } else if (a >= 32u) {
+          if (!splat_into_dst(a)) return false;
+          a = (uint32_t)dst;
+        }
+        okk = emit(op, (uint32_t)dst, a, b);
+      } else {
+        uint32_t a = enc[0];
+        if (a >= 32u) {
+          if (!splat_into_dst(a)) return false;
+          a = (uint32_t)dst;
+        }
+        okk = emit(op, (uint32_t)dst, a);
+      }
       if (!okk) return false;
     }
     p.n_code = n_code;
@@ -848,7 +885,7 @@ struct Lowering {
 
   static uint32_t ew_grid(uint64_t n) {
     const uint64_t tiles = (n + 1023) / 1024;
-    return (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(tiles, 256 * 8));
+    return (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(tiles, 256 * 32));
   }
 
   bool operand_gemm(Val v, bool trans, bool flatten_lead, ltk::GemmOperand* g, int32_t* storage, uint8_t* dtype,
@@ -955,6 +992,18 @@ struct Lowering {
     if (r->kind == C_EW) {
       ProgBuild pb;
       if (!build_prog(r->members, shape_of(r->members.front()), Val{-1, 0}, out, true, &pb)) return false;
+      {
+        // the streaming kernel's fast variants: whole aligned 4-vectors only
+        ltk::EwProg& q = pb.prog;
+        bool fast = (q.n % 4u) == 0u && q.full_vec_ok, f32 = true;
+        for (uint32_t i = 0; i < q.n_in; ++i) {
+          fast = fast && q.in[i].fetch != ltk::kFetchSlow;
+          f32 = f32 && q.in[i].dtype == ltk::kF32;
+        }
+        for (uint32_t i = 0; i < q.n_out; ++i) f32 = f32 && q.out[i].dtype == ltk::kF32;
+        q.fast = fast ? 1u : 0u;
+        q.all_f32 = f32 ? 1u : 0u;
+      }
       ltk::EwArgs a{};
       a.prog = pb.prog;
       Launch l = make_launch(L_EW, k, a);
@@ -1079,6 +1128,7 @@ struct Lowering {
     p.n_in = 1;
     p.in[0].mode = p.n <= 1 ? ltk::kScalar : ltk::kFull;
     p.in[0].dtype = acc.dtype;
+    p.in[0].fetch = p.n <= 1 ? ltk::kFetchBcast : (p.full_vec_ok ? ltk::kFetchVec4 : ltk::kFetchSlow);
     p.anchor_slot = 0;
     p.n_slots = 1;
     for (int d = 0; d < 4; ++d) p.dims[d] = 1;

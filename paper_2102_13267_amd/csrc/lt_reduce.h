@@ -31,11 +31,11 @@ __device__ __forceinline__ float block_reduce(uint32_t red, float v, float* lds 
 }
 
 // combine the (valid) element lanes of slot `slot`
-__device__ __forceinline__ float fold_vec(uint32_t red, float acc, float4 q, uint32_t nvalid) {
-  if (nvalid > 0u) acc = red_combine(red, acc, q.x);
-  if (nvalid > 1u) acc = red_combine(red, acc, q.y);
-  if (nvalid > 2u) acc = red_combine(red, acc, q.z);
-  if (nvalid > 3u) acc = red_combine(red, acc, q.w);
+__device__ __forceinline__ float fold_vec(uint32_t red, float acc, const Quad& q, uint32_t nvalid) {
+  if (nvalid > 0u) acc = red_combine(red, acc, q.v[0]);
+  if (nvalid > 1u) acc = red_combine(red, acc, q.v[1]);
+  if (nvalid > 2u) acc = red_combine(red, acc, q.v[2]);
+  if (nvalid > 3u) acc = red_combine(red, acc, q.v[3]);
   return acc;
 }
 

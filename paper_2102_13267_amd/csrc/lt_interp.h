@@ -42,6 +42,8 @@ struct Quad {
   float v[kVec];
 };
 
+typedef float RawVec __attribute__((ext_vector_type(4)));   // one 128-bit register tuple
+
 __device__ __forceinline__ Quad splat(float s) {
   Quad q;
 #pragma unroll
@@ -151,9 +153,9 @@ __device__ __forceinline__ RF<NS> interp(RF<NS> f, const ProgRegs pr, const uint
       case kAbs: LT_MAP(fabsf(xa)) break;
       case kSquare: LT_MAP(xa * xa) break;
       case kRelu: LT_MAP(xa > 0.0f ? xa : 0.0f) break;
-      case kSqrt: LT_MAP_SERIAL(sqrtf(xa)) break;
-      case kRsqrt: LT_MAP_SERIAL(rsqrtf(xa)) break;
-      case kRecip: LT_MAP_SERIAL(1.0f / xa) break;
+      case kSqrt: LT_MAP(__builtin_amdgcn_sqrtf(xa)) break;   // hardware square root, 1 ulp
+      case kRsqrt: LT_MAP(__builtin_amdgcn_rsqf(xa)) break;    // 1 ulp
+      case kRecip: LT_MAP(__builtin_amdgcn_rcpf(xa)) break;    // 1 ulp
       case kExp: LT_MAP_SERIAL(expf(xa)) break;
       case kLog: LT_MAP_SERIAL(logf(xa)) break;
       case kTanh: LT_MAP_SERIAL(tanhf(xa)) break;
@@ -185,25 +187,54 @@ __device__ __forceinline__ float load_elem(const void* ptr, uint32_t dtype, uint
   return ((const float*)ptr)[idx];
 }
 
-// Four consecutive elements starting at element `base + lane` of `ptr`.  `base` is wave-uniform
-// and is folded into the (scalar) base address; only the 32-bit lane offset lives in a vector
-// register, so all inputs of a program share one address register per lane.
+// Loads are split in two so that every load of a 4-vector's inputs is issued before any result
+// is touched: fetch_* returns the RAW bits (a conversion right behind a load would make the
+// compiler wait for it -- and for every other load in flight), finish_* converts them later.
+//
+// Raw fetch of four consecutive elements starting at element `base + lane` of `ptr`.  `base` is
+// wave-uniform and folded into the scalar base address; only the lane offset is per lane.
 template <bool F32 = false>
-__device__ __forceinline__ Quad load_vec4(const void* ptr, uint32_t dtype, uint64_t base, uint32_t lane) {
-  Quad q;
+__device__ __forceinline__ RawVec fetch_vec4(const void* ptr, uint32_t dtype, uint64_t base, uint32_t lane) {
+  RawVec q;
   if (!F32 && dtype == kBF16) {
     const char* b = (const char*)ptr + base * 2u;
-    const uint2 u = *(const uint2*)(b + lane * 2u);
-    q.v[0] = __uint_as_float(u.x << 16);
-    q.v[1] = __uint_as_float(u.x & 0xffff0000u);
-    q.v[2] = __uint_as_float(u.y << 16);
-    q.v[3] = __uint_as_float(u.y & 0xffff0000u);
+    const uint2 u = *(const uint2*)(b + (size_t)lane * 2u);
+    q.x = __uint_as_float(u.x);
+    q.y = __uint_as_float(u.y);
+    q.z = q.w = 0.0f;
   } else {
     const char* b = (const char*)ptr + base * 4u;
-    const float4 t = *(const float4*)(b + lane * 4u);
-    q.v[0] = t.x; q.v[1] = t.y; q.v[2] = t.z; q.v[3] = t.w;
+    q = *(const RawVec*)(b + (size_t)lane * 4u);
   }
   return q;
+}
+
+template <bool F32 = false>
+__device__ __forceinline__ float fetch_elem(const void* ptr, uint32_t dtype, uint64_t idx) {
+  if (!F32 && dtype == kBF16) return __uint_as_float((uint32_t)((const uint16_t*)ptr)[idx]);
+  return ((const float*)ptr)[idx];   // fp32 and int32 are both one dword
+}
+
+template <bool F32 = false>
+__device__ __forceinline__ Quad finish_vec4(uint32_t dtype, const RawVec raw) {
+  Quad q;
+  if (F32 || dtype != kBF16) {
+    q.v[0] = raw.x; q.v[1] = raw.y; q.v[2] = raw.z; q.v[3] = raw.w;
+    return q;
+  }
+  const uint32_t x = __float_as_uint(raw.x), y = __float_as_uint(raw.y);
+  q.v[0] = __uint_as_float(x << 16);
+  q.v[1] = __uint_as_float(x & 0xffff0000u);
+  q.v[2] = __uint_as_float(y << 16);
+  q.v[3] = __uint_as_float(y & 0xffff0000u);
+  return q;
+}
+
+template <bool F32 = false>
+__device__ __forceinline__ float finish_elem(uint32_t dtype, float raw) {
+  if (F32 || dtype == kF32) return raw;
+  if (dtype == kBF16) return __uint_as_float(__float_as_uint(raw) << 16);
+  return (float)(int32_t)__float_as_uint(raw);   // kI32
 }
 
 __device__ __forceinline__ uint64_t strided_index(const EwProg& p, const EwIn& in, uint64_t i) {
@@ -239,27 +270,24 @@ __device__ __forceinline__ Quad load_input_slow(const EwProg& p, const EwIn& in,
   return q;
 }
 
-// Fetch the four consecutive elements i .. i+3 (i = base + lane, base wave-uniform) of the
-// iteration space for one input.  FAST: the host promises full, aligned 4-vectors and no strided
-// input, so the element-by-element path is not even compiled in.
-template <bool FAST, bool F32>
-__device__ __forceinline__ Quad load_input(const EwProg& p, const EwIn& in, uint64_t base, uint32_t lane, uint32_t i_div,
-                                           uint32_t i_mod, uint32_t nvalid) {
-  const uint32_t fetch = (FAST || nvalid == (uint32_t)kVec) ? in.fetch : (uint32_t)kFetchSlow;
-  if (!FAST && fetch == kFetchSlow) return load_input_slow(p, in, base + lane, nvalid);
-  const uint32_t mode = in.mode;
-  if (fetch == kFetchVec4) {
-    if (mode == kFull) return load_vec4<F32>(in.ptr, in.dtype, base, lane);
-    return load_vec4<F32>(in.ptr, in.dtype, 0, i_mod);   // kRowVec
-  }
-  return splat(load_elem<F32>(in.ptr, in.dtype, mode == kColVec ? i_div : 0u));
-}
+// The inputs of one 4-vector, as fetched (MAXIN bounds the unrolling and with it the registers
+// reserved for loads in flight).  Vector loads and broadcast loads land in SEPARATE registers:
+// merging the two kinds into one variable makes the compiler move loaded data right behind the
+// load, and that move waits for the load (and every other load in flight).
+template <int MAXIN> struct Staged {
+  RawVec vec[MAXIN];   // kFetchVec4 (raw bits) or the slow path (converted values)
+  float bc[MAXIN];     // kFetchBcast (raw bits)
+};
 
-// Put the inputs of the program into slots 0 .. n_in-1.  The loop over inputs is fully unrolled
-// so that the slot index is a compile-time constant and every load is in flight before the first
-// use.  MAXIN bounds the unrolling (and with it the registers reserved for loads in flight).
-template <int NS, int MAXIN = kMaxIn, bool FAST = false, bool F32 = false>
-__device__ __forceinline__ RF<NS> load_inputs(RF<NS> f, const EwProg& p, uint64_t base, uint32_t lane, uint32_t nvalid) {
+// Issue the loads of every input for the 4-vector at base + lane (base wave-uniform).  Fully
+// unrolled so that all loads are in flight together.  FAST: the host promises full, aligned
+// 4-vectors and no strided input, so the element-by-element path is not even compiled in.
+template <int MAXIN, bool FAST, bool F32>
+__device__ __forceinline__ Staged<MAXIN> fetch_inputs(const EwProg& p, uint64_t base, uint32_t lane, uint32_t nvalid) {
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Wuninitialized"
+#pragma clang diagnostic ignored "-Wsometimes-uninitialized"
+  Staged<MAXIN> st;
   const uint32_t n_in = p.n_in;
   uint32_t i_div = 0, i_mod = 0;
   if (p.needs_divmod) {
@@ -269,12 +297,57 @@ __device__ __forceinline__ RF<NS> load_inputs(RF<NS> f, const EwProg& p, uint64_
   }
 #pragma unroll
   for (int k = 0; k < MAXIN; ++k) {
-    Quad q = splat(0.0f);
-    if ((uint32_t)k < n_in) q = load_input<FAST, F32>(p, p.in[k], base, lane, i_div, i_mod, nvalid);
+    // (deliberately not zero-initialised: a "= 0" that the other branch overwrites with a load
+    // becomes a register write that must wait for that load)
+    if ((uint32_t)k < n_in) {
+      const EwIn& in = p.in[k];
+      const uint32_t fetch = (FAST || nvalid == (uint32_t)kVec) ? in.fetch : (uint32_t)kFetchSlow;
+      const uint32_t mode = in.mode;
+      if (!FAST && fetch == kFetchSlow) {
+        const Quad t = load_input_slow(p, in, base + lane, nvalid);
+        st.vec[k].x = t.v[0]; st.vec[k].y = t.v[1]; st.vec[k].z = t.v[2]; st.vec[k].w = t.v[3];
+      } else if (fetch == kFetchVec4) {
+        if (mode == kFull) st.vec[k] = fetch_vec4<F32>(in.ptr, in.dtype, base, lane);
+        else st.vec[k] = fetch_vec4<F32>(in.ptr, in.dtype, 0, i_mod);   // kRowVec
+      } else {
+        st.bc[k] = fetch_elem<F32>(in.ptr, in.dtype, mode == kColVec ? i_div : 0u);
+      }
+    }
+  }
+  // Every use of the fetched values is made to depend on this point, which lies behind the last
+  // load: without it the compiler sinks the "move into the slot" of each input into that input's
+  // own branch, right behind its load, and so waits for every load before issuing the next.
+#pragma unroll
+  for (int k = 0; k < MAXIN; ++k)
+    asm volatile("" : "+v"(st.vec[k]), "+v"(st.bc[k]));
+  return st;
+#pragma clang diagnostic pop
+}
+
+// Convert the fetched inputs and move them into slots 0 .. MAXIN-1 (compile-time slot numbers:
+// plain register moves).
+template <int NS, int MAXIN, bool FAST, bool F32>
+__device__ __forceinline__ RF<NS> place_inputs(RF<NS> f, const EwProg& p, const Staged<MAXIN>& st, uint32_t nvalid) {
+  const uint32_t n_in = p.n_in;
+#pragma unroll
+  for (int k = 0; k < MAXIN; ++k) {
+    Quad q;
+    q.v[0] = st.vec[k].x; q.v[1] = st.vec[k].y; q.v[2] = st.vec[k].z; q.v[3] = st.vec[k].w;
+    if ((uint32_t)k < n_in) {
+      const EwIn& in = p.in[k];
+      const uint32_t fetch = (FAST || nvalid == (uint32_t)kVec) ? in.fetch : (uint32_t)kFetchSlow;
+      if (fetch == kFetchVec4) q = finish_vec4<F32>(in.dtype, st.vec[k]);
+      else if (fetch == kFetchBcast) q = splat(finish_elem<F32>(in.dtype, st.bc[k]));
+    }
 #pragma unroll
     for (int v = 0; v < kVec; ++v) f.e[v][k] = q.v[v];
   }
   return f;
+}
+
+template <int NS, int MAXIN = kMaxIn, bool FAST = false, bool F32 = false>
+__device__ __forceinline__ RF<NS> load_inputs(RF<NS> f, const EwProg& p, uint64_t base, uint32_t lane, uint32_t nvalid) {
+  return place_inputs<NS, MAXIN, FAST, F32>(f, p, fetch_inputs<MAXIN, FAST, F32>(p, base, lane, nvalid), nvalid);
 }
 
 template <int NS>
@@ -312,10 +385,10 @@ __device__ __forceinline__ void store_vec4(void* ptr, uint32_t dtype, uint64_t b
     u.x = (uint32_t)f32_to_bf16(q.v[0]) | ((uint32_t)f32_to_bf16(q.v[1]) << 16);
     u.y = (uint32_t)f32_to_bf16(q.v[2]) | ((uint32_t)f32_to_bf16(q.v[3]) << 16);
     char* b = (char*)ptr + base * 2u;
-    *(uint2*)(b + lane * 2u) = u;
+    *(uint2*)(b + (size_t)lane * 2u) = u;
   } else {
     char* b = (char*)ptr + base * 4u;
-    *(float4*)(b + lane * 4u) = make_float4(q.v[0], q.v[1], q.v[2], q.v[3]);
+    *(float4*)(b + (size_t)lane * 4u) = make_float4(q.v[0], q.v[1], q.v[2], q.v[3]);
   }
 }
 

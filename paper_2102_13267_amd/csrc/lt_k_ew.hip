@@ -19,6 +19,8 @@ __global__ __launch_bounds__(kBlock) void lt_ew_kernel(const EwArgs a) {
   const ProgRegs pr = load_prog_regs(p);
   const uint32_t n_code = p.n_code;
   const uint32_t lane = threadIdx.x * kVec;
+  // (Prefetching the next tile's inputs during interpretation was measured and lost to the
+  // occupancy it costs: 4 resident waves per SIMD hide HBM latency better than 3 pipelined ones.)
   for (uint64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
     const uint64_t base = tile * kTile;
     const uint64_t left = n - base;                       // >= 1
@@ -33,10 +35,11 @@ __global__ __launch_bounds__(kBlock) void lt_ew_kernel(const EwArgs a) {
 hipError_t launch_ew(const EwArgs& a, uint32_t grid, hipStream_t s) {
   const EwProg& p = a.prog;
   const dim3 g(grid), b(kBlock);
-  if (p.fast && p.n_slots <= 16u && p.all_f32 && p.n_in <= 4u) hipLaunchKernelGGL((lt_ew_kernel<16, 4, true, true>), g, b, 0, s, a);
-  else if (p.fast && p.n_slots <= 16u && p.all_f32 && p.n_in <= 6u) hipLaunchKernelGGL((lt_ew_kernel<16, 6, true, true>), g, b, 0, s, a);
-  else if (p.fast && p.n_slots <= 16u && p.all_f32) hipLaunchKernelGGL((lt_ew_kernel<16, 8, true, true>), g, b, 0, s, a);
-  else if (p.fast && p.n_slots <= 16u) hipLaunchKernelGGL((lt_ew_kernel<16, 8, true, false>), g, b, 0, s, a);
+  const bool f16 = p.fast && p.n_slots <= 16u;
+  if (f16 && p.all_f32 && p.n_in <= 4u) hipLaunchKernelGGL((lt_ew_kernel<16, 4, true, true>), g, b, 0, s, a);
+  else if (f16 && p.all_f32 && p.n_in <= 6u) hipLaunchKernelGGL((lt_ew_kernel<16, 6, true, true>), g, b, 0, s, a);
+  else if (f16 && p.all_f32) hipLaunchKernelGGL((lt_ew_kernel<16, 8, true, true>), g, b, 0, s, a);
+  else if (f16) hipLaunchKernelGGL((lt_ew_kernel<16, 8, true, false>), g, b, 0, s, a);
   else hipLaunchKernelGGL((lt_ew_kernel<32, 8, false, false>), g, b, 0, s, a);
   return hipGetLastError();
 }

@@ -48,7 +48,10 @@ __global__ __launch_bounds__(kBlock) void lt_row_reduce_kernel(const RowArgs a) 
   }
 }
 
-// Global reduction in one launch.
+// Global reduction in one launch.  U independent 4-vectors per lane and loop trip: all their
+// loads are issued before the first is interpreted (a reduction has few inputs, so memory-level
+// parallelism has to come from unrolling).
+template <int MAXIN, int U, bool FAST, bool F32>
 __global__ __launch_bounds__(kBlock) void lt_all_reduce_kernel(const AllArgs a) {
   __shared__ float lds[kBlock / 64];
   __shared__ uint32_t is_last;
@@ -58,10 +61,25 @@ __global__ __launch_bounds__(kBlock) void lt_all_reduce_kernel(const AllArgs a) 
   const uint64_t n = pro.n;
   const uint64_t nvec = (n + kVec - 1) / kVec;
   float acc = red_identity(a.red);
-  for (uint64_t v = (uint64_t)blockIdx.x * kBlock + threadIdx.x; v < nvec; v += (uint64_t)gridDim.x * kBlock) {
+  const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+  const uint64_t full_trips = FAST ? nvec / (stride * U) : 0;     // every lane has U whole vectors
+  uint64_t v = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  for (uint64_t t = 0; t < full_trips; ++t) {
+    Staged<MAXIN> st[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) st[u] = fetch_inputs<MAXIN, FAST, F32>(pro, 0, (uint32_t)((v + (uint64_t)u * stride) * kVec), kVec);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      RF<16> f = place_inputs<16, MAXIN, FAST, F32>(rf_zero<16>(), pro, st[u], kVec);
+      f = interp<16>(f, pro_regs, pro_n);
+      acc = fold_vec(a.red, acc, rf_get(f, pro.anchor_slot), kVec);
+    }
+    v += stride * U;
+  }
+  for (; v < nvec; v += stride) {
     const uint64_t i = v * kVec;
     const uint32_t nvalid = (n - i >= (uint64_t)kVec) ? (uint32_t)kVec : (uint32_t)(n - i);
-    RF<16> f = load_inputs<16>(rf_zero<16>(), pro, 0, (uint32_t)i, nvalid);
+    RF<16> f = load_inputs<16, MAXIN, false, false>(rf_zero<16>(), pro, 0, (uint32_t)i, nvalid);
     f = interp<16>(f, pro_regs, pro_n);
     acc = fold_vec(a.red, acc, rf_get(f, pro.anchor_slot), nvalid);
   }
@@ -173,7 +191,10 @@ hipError_t launch_row_reduce(const RowArgs& a, uint32_t grid, hipStream_t s) {
   return hipGetLastError();
 }
 hipError_t launch_all_reduce(const AllArgs& a, uint32_t grid, hipStream_t s) {
-  hipLaunchKernelGGL(lt_all_reduce_kernel, dim3(grid), dim3(kBlock), 0, s, a);
+  if (a.pro.fast && a.pro.all_f32 && a.pro.n_in <= 2u)
+    hipLaunchKernelGGL((lt_all_reduce_kernel<2, 4, true, true>), dim3(grid), dim3(kBlock), 0, s, a);
+  else
+    hipLaunchKernelGGL((lt_all_reduce_kernel<8, 1, false, false>), dim3(grid), dim3(kBlock), 0, s, a);
   return hipGetLastError();
 }
 hipError_t launch_col_reduce(const ColArgs& a, uint32_t grid_x, uint32_t grid_y, hipStream_t s) {

@@ -24,7 +24,7 @@ __device__ __forceinline__ RowRegs row_load(const void* ptr, uint32_t dtype, uin
     float4 q = make_float4(pad, pad, pad, pad);
     if (c < cols) {
       if (vec_ok) {
-        const Quad t = load_vec4(ptr, dtype, base, c);
+        const Quad t = finish_vec4(dtype, fetch_vec4(ptr, dtype, base, c));
         q = make_float4(t.v[0], t.v[1], t.v[2], t.v[3]);
       } else {
         q.x = load_elem(ptr, dtype, base + c);

@@ -853,7 +853,24 @@ struct Lowering {
       pb->out_storage.push_back({(uint32_t)k, storage_of[v.node][v.slot]});
       pb->bytes += (uint64_t)on * dtype_size(out.dtype);
     }
+    finish_flags(&p);
     return true;
+  }
+
+  // Flags for the kernels' fast variants: whole 4-vectors only (n % 4 == 0, no element-wise
+  // input), and "everything is fp32".
+  static void finish_flags(ltk::EwProg* q) {
+    bool fast = (q->n % 4u) == 0u, f32 = true;
+    for (uint32_t i = 0; i < q->n_in; ++i) {
+      fast = fast && q->in[i].fetch != ltk::kFetchSlow;
+      f32 = f32 && q->in[i].dtype == ltk::kF32;
+    }
+    for (uint32_t i = 0; i < q->n_out; ++i) {
+      f32 = f32 && q->out[i].dtype == ltk::kF32;
+      fast = fast && (q->out[i].scalar || q->full_vec_ok);
+    }
+    q->fast = fast ? 1u : 0u;
+    q->all_f32 = f32 ? 1u : 0u;
   }
 
   // append one program's patches to the plan; `offset` = byte offset of the EwProg inside the args
@@ -992,18 +1009,6 @@ struct Lowering {
     if (r->kind == C_EW) {
       ProgBuild pb;
       if (!build_prog(r->members, shape_of(r->members.front()), Val{-1, 0}, out, true, &pb)) return false;
-      {
-        // the streaming kernel's fast variants: whole aligned 4-vectors only
-        ltk::EwProg& q = pb.prog;
-        bool fast = (q.n % 4u) == 0u && q.full_vec_ok, f32 = true;
-        for (uint32_t i = 0; i < q.n_in; ++i) {
-          fast = fast && q.in[i].fetch != ltk::kFetchSlow;
-          f32 = f32 && q.in[i].dtype == ltk::kF32;
-        }
-        for (uint32_t i = 0; i < q.n_out; ++i) f32 = f32 && q.out[i].dtype == ltk::kF32;
-        q.fast = fast ? 1u : 0u;
-        q.all_f32 = f32 ? 1u : 0u;
-      }
       ltk::EwArgs a{};
       a.prog = pb.prog;
       Launch l = make_launch(L_EW, k, a);
@@ -1105,6 +1110,7 @@ struct Lowering {
       storage_of[src.node][src.slot] = -1;
       pb->prog.anchor_slot = pb->prog.out[0].slot;
       pb->prog.n_out = 0;
+      finish_flags(&pb->prog);
       pb->out_storage.clear();
       pb->bytes -= (uint64_t)count(space) * dtype_size(out_dtype(src));
       return true;
@@ -1134,6 +1140,7 @@ struct Lowering {
     for (int d = 0; d < 4; ++d) p.dims[d] = 1;
     pb->in_storage.push_back({0u, acc.storage});
     pb->bytes += p.n * dtype_size(acc.dtype);
+    finish_flags(&p);
     return true;
   }
 

@@ -1,11 +1,16 @@
 // Contraction region: C = post(A * B) on the MFMA matrix cores (gfx950), fp32 or bf16 operands,
 // fp32 accumulation.  Operands are addressed through element strides, so transposed, batched and
 // head-split layouts need no copies.  The elementwise chain that consumes the product (bias,
-// activation, residual, optimiser update, cast ...) is interpreted on the accumulator tile in
-// registers before anything is written: the product itself never travels to HBM unless asked for.
+// activation, residual, optimiser update, cast ...) is interpreted on the accumulator tile before
+// anything is written: the product itself never travels to HBM unless asked for.
 //
-// Workgroup tile 128 x 128, four wavefronts in a 2 x 2 arrangement, each owning 64 x 64 as 2 x 2
-// MFMA 32x32 blocks.  K is staged through LDS in slices of 16 (fp32) or 32 (bf16).
+// Structure: workgroup tile BM x BN (128 x 128, or 64 x 64 for small problems so that more
+// compute units get a tile), four wavefronts in a 2 x 2 arrangement, each owning a quarter as
+// MFMA 32x32 blocks.  K is walked in slices (16 fp32 / 32 bf16) with register prefetch: the
+// global loads of slice k+1 are issued before the MFMAs of slice k and written to the other LDS
+// buffer afterwards, so HBM latency overlaps the matrix cores.  Global loads are 16 bytes per
+// lane along whichever dimension of the operand is contiguous; an operand whose contraction
+// dimension is not the one the MFMA wants contiguous is transposed on its way into LDS.
 #include <hip/hip_runtime.h>
 
 #include "lt_interp.h"
@@ -13,262 +18,292 @@
 
 namespace ltk {
 
-constexpr int kBM = 128, kBN = 128;
 constexpr int kGemmThreads = 256;
+constexpr int kCPad = 4;
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
-// One accumulator quad = four consecutive rows of one column (the MFMA 32x32 result layout).
-// Runs the post program for it.
-__device__ __forceinline__ void post_quad(const EwProg& p, const ProgRegs pr, Quad acc, uint32_t row0, uint32_t col,
-                                          uint32_t rows_valid, uint64_t out_base_row, uint32_t n) {
-  // flat index of element e of the quad in the [rows, n] output space: i0 + e*n
-  const uint64_t i0 = (out_base_row + row0) * (uint64_t)n + col;
-  RF<16> f = rf_zero<16>();
-  const uint32_t n_in = p.n_in;
+// ---- epilogue ------------------------------------------------------------------------------
+// The accumulators leave the MFMA layout (a lane owns 4-row column segments) through LDS: the
+// tile is written once, then every lane walks it in row-major 4-element quads, so the post
+// program sees flat, contiguous indices exactly like the elementwise kernel does (16-byte loads
+// of residuals, 16-byte stores) and is compiled in only once.
+template <int BM, int BN, int MB, int NB>
+__device__ __forceinline__ void epilogue(const GemmArgs& a, const v16f (&acc)[MB][NB], float* Cs, uint32_t tile_m,
+                                         uint32_t tile_n, uint32_t wave_m, uint32_t wave_n, uint32_t lane, uint32_t batch) {
+  constexpr int kCStride = BN + kCPad;
+  __syncthreads();   // the operand tiles in the same LDS bytes are dead now
 #pragma unroll
-  for (int k = 0; k < kMaxIn; ++k) {
-    Quad q = splat(0.0f);
-    if ((uint32_t)k < n_in) {
-      const EwIn& in = p.in[k];
-      if (in.mode == kScalar) {
-        q = splat(load_elem(in.ptr, in.dtype, 0));
-      } else if (in.mode == kRowVec) {
-        q = splat(load_elem(in.ptr, in.dtype, col));
-      } else {
+  for (int bm = 0; bm < MB; ++bm)
 #pragma unroll
-        for (int e = 0; e < kVec; ++e) {
-          if ((uint32_t)e < rows_valid) {
-            const uint64_t i = i0 + (uint64_t)e * n;
-            const uint64_t off = in.mode == kFull ? i : in.mode == kColVec ? out_base_row + row0 + e : strided_index(p, in, i);
-            q.v[e] = load_elem(in.ptr, in.dtype, off);
-          }
-        }
+    for (int bn = 0; bn < NB; ++bn)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const uint32_t row = wave_m * (MB * 32) + bm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+        const uint32_t col = wave_n * (NB * 32) + bn * 32 + (lane & 31);
+        Cs[row * kCStride + col] = acc[bm][bn][r];
       }
-    }
-#pragma unroll
-    for (int v = 0; v < kVec; ++v) f.e[v][k] = q.v[v];
-  }
-  f = rf_set<16>(f, p.anchor_slot, acc);
-  f = interp<16>(f, pr, p.n_code);
-  const uint32_t n_out = p.n_out;
-#pragma unroll
-  for (int o = 0; o < kMaxOut; ++o) {
-    if ((uint32_t)o < n_out) {
-      const EwOut& out = p.out[o];
-      const Quad q = rf_get<16>(f, out.slot);
-#pragma unroll
-      for (int e = 0; e < kVec; ++e)
-        if ((uint32_t)e < rows_valid) store_elem(out.ptr, out.dtype, i0 + (uint64_t)e * n, q.v[e]);
-    }
-  }
-}
-
-__device__ __forceinline__ void epilogue(const GemmArgs& a, const v16f (&acc)[2][2], uint32_t tile_m, uint32_t tile_n,
-                                         uint32_t wave_m, uint32_t wave_n, uint32_t lane, uint32_t batch) {
+  __syncthreads();
+  const EwProg& p = a.post;
+  const ProgRegs pr = load_prog_regs(p);
+  const uint32_t n_code = p.n_code;
   const uint64_t base_row = (uint64_t)batch * a.m;
-  const ProgRegs pr = load_prog_regs(a.post);
+#pragma unroll 1
+  for (uint32_t q = threadIdx.x; q < (uint32_t)(BM * BN / kVec); q += kGemmThreads) {
+    const uint32_t r = q / (BN / kVec), c = (q % (BN / kVec)) * kVec;
+    const uint32_t row = tile_m + r, col = tile_n + c;
+    if (row >= a.m || col >= a.n) continue;
+    const uint32_t nvalid = a.n - col >= (uint32_t)kVec ? (uint32_t)kVec : a.n - col;
+    const uint32_t i = (uint32_t)((base_row + row) * a.n + col);
+    const float4 t = *(const float4*)&Cs[r * kCStride + c];
+    Quad anchor;
+    anchor.v[0] = t.x; anchor.v[1] = t.y; anchor.v[2] = t.z; anchor.v[3] = t.w;
+    RF<16> f = load_inputs<16, kMaxIn, false, false>(rf_zero<16>(), p, 0, i, nvalid);
+    f = rf_set<16>(f, p.anchor_slot, anchor);
+    f = interp<16>(f, pr, n_code);
+    store_outputs<16, false, false>(f, p, 0, i, nvalid);
+  }
+}
+
+// ---- operand staging --------------------------------------------------------------------------
+// A "group" is what one lane fetches with one 16-byte load: G consecutive elements along the
+// operand's contiguous dimension (4 fp32 or 8 bf16).  For element type T the raw group travels
+// as uint4.
+template <typename T> struct Elem;
+template <> struct Elem<float> { static constexpr int G = 4; static constexpr int BK = 16; };
+template <> struct Elem<uint16_t> { static constexpr int G = 8; static constexpr int BK = 32; };
+
+// Guarded fetch of G elements at (outer, inner .. inner+G-1); element (o, i) lives at
+// base + o*s_outer + i (unit stride inside the group).  Out-of-range elements read as zero.
+template <typename T>
+__device__ __forceinline__ uint4 fetch_group(const T* base, int64_t s_outer, uint32_t outer, uint32_t inner, uint32_t n_outer,
+                                             uint32_t n_inner, bool aligned) {
+  constexpr int G = Elem<T>::G;
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (outer >= n_outer || inner >= n_inner) return v;
+  const T* src = base + (int64_t)outer * s_outer + inner;
+  if (aligned && inner + G <= n_inner) return *(const uint4*)src;
+  T t[G];
 #pragma unroll
-  for (int bm = 0; bm < 2; ++bm) {
+  for (int j = 0; j < G; ++j) t[j] = (inner + j < n_inner) ? src[j] : (T)0;
+  if (sizeof(T) == 4) {
+    v = make_uint4(((const uint32_t*)t)[0], ((const uint32_t*)t)[1], ((const uint32_t*)t)[2], ((const uint32_t*)t)[3]);
+  } else {
+    const uint16_t* h = (const uint16_t*)t;
+    v = make_uint4(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16), h[4] | ((uint32_t)h[5] << 16),
+                   h[6] | ((uint32_t)h[7] << 16));
+  }
+  return v;
+}
+
+// Per-dtype LDS layouts.
+//   fp32: tile[k][x]  (x = m or n contiguous), row stride BX + 4  -> MFMA 32x32x2 reads one float
+//   bf16: tile[x][k]  (k contiguous),          row stride BK + 8  -> MFMA 32x32x16 reads 8 bf16
+template <typename T, int BX> struct Tile;
+template <int BX> struct Tile<float, BX> {
+  static constexpr int BK = 16, STRIDE = BX + 4, ELEMS = BK * STRIDE;
+};
+template <int BX> struct Tile<uint16_t, BX> {
+  static constexpr int BK = 32, STRIDE = BK + 8, ELEMS = BX * STRIDE;
+};
+
+// Number of 16-byte groups per lane and k-slice for an operand tile of BX x BK elements.
+template <typename T, int BX> struct Groups {
+  static constexpr int N = BX * Elem<T>::BK / Elem<T>::G / kGemmThreads;   // 128: 2, 64: 1
+};
+
+template <int N> struct GroupRegs {
+  uint4 g[N];
+};
+
+// Fetch this lane's groups of the slice starting at k0.  KC: the contraction dimension is the
+// operand's contiguous one.  x0: first row (A) / column (B) of the tile.
+template <typename T, int BX, bool KC>
+__device__ __forceinline__ void fetch_tile(GroupRegs<Groups<T, BX>::N>& gr, const T* base, int64_t s_x, int64_t s_k, uint32_t x0,
+                                           uint32_t k0, uint32_t nx, uint32_t nk, bool aligned) {
+  constexpr int G = Elem<T>::G, BK = Elem<T>::BK, NG = Groups<T, BX>::N;
+  const uint32_t t = threadIdx.x;
 #pragma unroll
-    for (int bn = 0; bn < 2; ++bn) {
-      const uint32_t col = tile_n + wave_n * 64 + bn * 32 + (lane & 31);
+  for (int it = 0; it < NG; ++it) {
+    const uint32_t e = it * kGemmThreads + t;
+    if (KC) {
+      const uint32_t x = e / (BK / G), kq = e % (BK / G);
+      gr.g[it] = fetch_group<T>(base, s_x, x0 + x, k0 + kq * G, nx, nk, aligned);
+    } else {
+      const uint32_t k = e / (BX / G), xq = e % (BX / G);
+      gr.g[it] = fetch_group<T>(base, s_k, k0 + k, x0 + xq * G, nk, nx, aligned);
+    }
+  }
+}
+
+template <int BX, bool KC>
+__device__ __forceinline__ void stash_tile(const GroupRegs<Groups<float, BX>::N>& gr, float* tile) {
+  const uint4* g = gr.g;
+  constexpr int G = 4, BK = 16, STRIDE = Tile<float, BX>::STRIDE, NG = Groups<float, BX>::N;
+  const uint32_t t = threadIdx.x;
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const uint32_t row0 = tile_m + wave_m * 64 + bm * 32 + g * 8 + (lane >> 5) * 4;
-        if (col < a.n && row0 < a.m) {
-          const uint32_t rv = min(4u, a.m - row0);
-          Quad q;
+  for (int it = 0; it < NG; ++it) {
+    const uint32_t e = it * kGemmThreads + t;
+    if (KC) {   // transposing: four scalar writes
+      const uint32_t x = e / (BK / G), kq = e % (BK / G);
+      tile[(kq * G + 0) * STRIDE + x] = __uint_as_float(g[it].x);
+      tile[(kq * G + 1) * STRIDE + x] = __uint_as_float(g[it].y);
+      tile[(kq * G + 2) * STRIDE + x] = __uint_as_float(g[it].z);
+      tile[(kq * G + 3) * STRIDE + x] = __uint_as_float(g[it].w);
+    } else {
+      const uint32_t k = e / (BX / G), xq = e % (BX / G);
+      *(uint4*)&tile[k * STRIDE + xq * G] = g[it];
+    }
+  }
+}
+
+template <int BX, bool KC>
+__device__ __forceinline__ void stash_tile(const GroupRegs<Groups<uint16_t, BX>::N>& gr, uint16_t* tile) {
+  const uint4* g = gr.g;
+  constexpr int G = 8, BK = 32, STRIDE = Tile<uint16_t, BX>::STRIDE, NG = Groups<uint16_t, BX>::N;
+  const uint32_t t = threadIdx.x;
 #pragma unroll
-          for (int e = 0; e < kVec; ++e) q.v[e] = acc[bm][bn][g * 4 + e];
-          post_quad(a.post, pr, q, row0, col, rv, base_row, a.n);
-        }
+  for (int it = 0; it < NG; ++it) {
+    const uint32_t e = it * kGemmThreads + t;
+    if (KC) {
+      const uint32_t x = e / (BK / G), kq = e % (BK / G);
+      *(uint4*)&tile[x * STRIDE + kq * G] = g[it];
+    } else {   // transposing: eight 2-byte writes
+      const uint32_t k = e / (BX / G), xq = e % (BX / G);
+      const uint32_t w[4] = {g[it].x, g[it].y, g[it].z, g[it].w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        tile[(xq * G + 2 * j) * STRIDE + k] = (uint16_t)(w[j] & 0xffffu);
+        tile[(xq * G + 2 * j + 1) * STRIDE + k] = (uint16_t)(w[j] >> 16);
       }
     }
   }
 }
 
-// ---- fp32: v_mfma_f32_32x32x2_f32; LDS holds A as [k][m] and B as [k][n] ----------------------------
-constexpr int kBK32 = 16;
-constexpr int kPad32 = 4;
-
-__global__ __launch_bounds__(kGemmThreads) void lt_gemm_f32_kernel(const GemmArgs a) {
-  __shared__ float As[kBK32][kBM + kPad32];
-  __shared__ float Bs[kBK32][kBN + kPad32];
-  const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const uint32_t wave_m = wave >> 1, wave_n = wave & 1;
-  const uint32_t tile_m = blockIdx.y * kBM, tile_n = blockIdx.x * kBN, batch = blockIdx.z;
-  const float* A = (const float*)a.a.ptr + (int64_t)batch * a.a.s_b0;
-  const float* B = (const float*)a.b.ptr + (int64_t)batch * a.b.s_b0;
-  v16f acc[2][2];
+// MFMAs of one k-slice.
+template <int BM, int BN, int MB, int NB>
+__device__ __forceinline__ void mma_slice(v16f (&acc)[MB][NB], const float* As, const float* Bs, uint32_t wave_m, uint32_t wave_n,
+                                          uint32_t lane) {
+  constexpr int SA = Tile<float, BM>::STRIDE, SB = Tile<float, BN>::STRIDE;
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int kk = 0; kk < 16; kk += 2) {
+    const uint32_t kl = kk + (lane >> 5);
+    float af[MB], bf[NB];
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int i = 0; i < MB; ++i) af[i] = As[kl * SA + wave_m * (MB * 32) + i * 32 + (lane & 31)];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
-  for (uint32_t k0 = 0; k0 < a.k; k0 += kBK32) {
-    // stage A[tile_m .. +128][k0 .. +16] and B[k0 .. +16][tile_n .. +128]; 2048 elements each,
-    // 8 per thread; the thread's fast index follows the operand's unit stride for coalescing
+    for (int j = 0; j < NB; ++j) bf[j] = Bs[kl * SB + wave_n * (NB * 32) + j * 32 + (lane & 31)];
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const uint32_t e = it * kGemmThreads + tid;
-      uint32_t m, k;
-      if (a.a.s_col == 1) { k = e % kBK32; m = e / kBK32; } else { m = e % kBM; k = e / kBM; }
-      const uint32_t gm = tile_m + m, gk = k0 + k;
-      As[k][m] = (gm < a.m && gk < a.k) ? A[(int64_t)gm * a.a.s_row + (int64_t)gk * a.a.s_col] : 0.0f;
-      uint32_t n, kb;
-      if (a.b.s_col == 1) { n = e % kBN; kb = e / kBN; } else { kb = e % kBK32; n = e / kBK32; }
-      const uint32_t gn = tile_n + n, gkb = k0 + kb;
-      Bs[kb][n] = (gn < a.n && gkb < a.k) ? B[(int64_t)gkb * a.b.s_row + (int64_t)gn * a.b.s_col] : 0.0f;
-    }
-    __syncthreads();
+    for (int i = 0; i < MB; ++i)
 #pragma unroll
-    for (int kk = 0; kk < kBK32; kk += 2) {
-      const uint32_t kl = kk + (lane >> 5);
-      float af[2], bf[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) af[i] = As[kl][wave_m * 64 + i * 32 + (lane & 31)];
-#pragma unroll
-      for (int j = 0; j < 2; ++j) bf[j] = Bs[kl][wave_n * 64 + j * 32 + (lane & 31)];
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i], bf[j], acc[i][j], 0, 0, 0);
-    }
-    __syncthreads();
+      for (int j = 0; j < NB; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i], bf[j], acc[i][j], 0, 0, 0);
   }
-  epilogue(a, acc, tile_m, tile_n, wave_m, wave_n, lane, batch);
 }
 
-// ---- bf16: v_mfma_f32_32x32x16_bf16; LDS holds A as [m][k] and B as [n][k] ---------------------------
-constexpr int kBK16 = 32;
-constexpr int kPad16 = 8;
+template <int BM, int BN, int MB, int NB>
+__device__ __forceinline__ void mma_slice(v16f (&acc)[MB][NB], const uint16_t* As, const uint16_t* Bs, uint32_t wave_m,
+                                          uint32_t wave_n, uint32_t lane) {
+  constexpr int SA = Tile<uint16_t, BM>::STRIDE, SB = Tile<uint16_t, BN>::STRIDE;
+#pragma unroll
+  for (int kk = 0; kk < 32; kk += 16) {
+    const uint32_t kl = kk + (lane >> 5) * 8;
+    v8bf af[MB], bf[NB];
+#pragma unroll
+    for (int i = 0; i < MB; ++i) af[i] = *(const v8bf*)&As[(wave_m * (MB * 32) + i * 32 + (lane & 31)) * SA + kl];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) bf[j] = *(const v8bf*)&Bs[(wave_n * (NB * 32) + j * 32 + (lane & 31)) * SB + kl];
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+  }
+}
 
-__global__ __launch_bounds__(kGemmThreads) void lt_gemm_bf16_kernel(const GemmArgs a) {
-  __shared__ __attribute__((aligned(16))) uint16_t As[kBM][kBK16 + kPad16];
-  __shared__ __attribute__((aligned(16))) uint16_t Bs[kBN][kBK16 + kPad16];
+template <typename T, int BM, int BN> struct Smem {
+  static constexpr size_t kOperands = 2 * (Tile<T, BM>::ELEMS + Tile<T, BN>::ELEMS) * sizeof(T);   // double buffered
+  static constexpr size_t kC = (size_t)BM * (BN + kCPad) * sizeof(float);
+  static constexpr size_t kBytes = kOperands > kC ? kOperands : kC;
+};
+
+// T: float or uint16_t (bf16 bits).  AKC / BKC: the operand's contiguous dimension is k.
+template <typename T, int BM, int BN, bool AKC, bool BKC>
+__global__ __launch_bounds__(kGemmThreads) void lt_gemm_kernel(const GemmArgs a) {
+  constexpr int MB = BM / 64, NB = BN / 64, BK = Elem<T>::BK;
+  __shared__ __attribute__((aligned(16))) char smem[Smem<T, BM, BN>::kBytes];
+  // LDS map: A buffer 0, A buffer 1, B buffer 0, B buffer 1 (the C tile of the epilogue reuses it)
+  T* const lds = (T*)smem;
+  auto As = [&](uint32_t buf) { return lds + buf * Tile<T, BM>::ELEMS; };
+  auto Bs = [&](uint32_t buf) { return lds + 2 * Tile<T, BM>::ELEMS + buf * Tile<T, BN>::ELEMS; };
   const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const uint32_t wave_m = wave >> 1, wave_n = wave & 1;
-  const uint32_t tile_m = blockIdx.y * kBM, tile_n = blockIdx.x * kBN, batch = blockIdx.z;
-  const uint16_t* A = (const uint16_t*)a.a.ptr + (int64_t)batch * a.a.s_b0;
-  const uint16_t* B = (const uint16_t*)a.b.ptr + (int64_t)batch * a.b.s_b0;
-  v16f acc[2][2];
+  const uint32_t tile_m = blockIdx.y * BM, tile_n = blockIdx.x * BN, batch = blockIdx.z;
+  const T* A = (const T*)a.a.ptr + (int64_t)batch * a.a.s_b0;
+  const T* B = (const T*)a.b.ptr + (int64_t)batch * a.b.s_b0;
+  // 16-byte loads need 16-byte aligned groups: base, and the stride between groups' rows
+  constexpr int G = Elem<T>::G;
+  const int64_t a_outer = AKC ? a.a.s_row : a.a.s_col, b_outer = BKC ? a.b.s_col : a.b.s_row;
+  const bool a_al = (((uintptr_t)A) & 15u) == 0 && (a_outer % G) == 0;
+  const bool b_al = (((uintptr_t)B) & 15u) == 0 && (b_outer % G) == 0;
+  v16f acc[MB][NB];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MB; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NB; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  // 128 x 32 elements per operand and slice = 512 groups of 8; two groups per thread
-  const bool a_k_contig = a.a.s_col == 1, b_k_contig = a.b.s_row == 1;
-  const bool a_vec = a_k_contig ? ((a.a.s_row % 8) == 0 && (a.k % 8) == 0) : ((a.a.s_col % 8) == 0 && (a.m % 8) == 0);
-  const bool b_vec = b_k_contig ? ((a.b.s_col % 8) == 0 && (a.k % 8) == 0) : ((a.b.s_row % 8) == 0 && (a.n % 8) == 0);
-  const bool a_al = (((uintptr_t)A) & 15u) == 0, b_al = (((uintptr_t)B) & 15u) == 0;
-  for (uint32_t k0 = 0; k0 < a.k; k0 += kBK16) {
-#pragma unroll
-    for (int it = 0; it < 2; ++it) {
-      const uint32_t g = it * kGemmThreads + tid;
-      // ---- A
-      if (a_k_contig) {
-        const uint32_t m = g >> 2, k = (g & 3) * 8;
-        const uint32_t gm = tile_m + m, gk = k0 + k;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (gm < a.m && gk < a.k) {
-          const uint16_t* src = A + (int64_t)gm * a.a.s_row + gk;
-          if (a_vec && a_al) v = *(const uint4*)src;
-          else {
-            uint16_t t[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) t[j] = (gk + j < a.k) ? src[j] : (uint16_t)0;
-            v = make_uint4(t[0] | (t[1] << 16), t[2] | (t[3] << 16), t[4] | (t[5] << 16), t[6] | (t[7] << 16));
-          }
-        }
-        *(uint4*)&As[m][k] = v;
-      } else {
-        const uint32_t k = g >> 4, m = (g & 15) * 8;
-        const uint32_t gm = tile_m + m, gk = k0 + k;
-        uint16_t t[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) t[j] = 0;
-        if (gk < a.k && gm < a.m) {
-          const uint16_t* src = A + (int64_t)gk * a.a.s_col + gm;
-          if (a_vec && a_al) {
-            const uint4 v = *(const uint4*)src;
-            t[0] = v.x & 0xffff; t[1] = v.x >> 16; t[2] = v.y & 0xffff; t[3] = v.y >> 16;
-            t[4] = v.z & 0xffff; t[5] = v.z >> 16; t[6] = v.w & 0xffff; t[7] = v.w >> 16;
-          } else {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) t[j] = (gm + j < a.m) ? src[j] : (uint16_t)0;
-          }
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) As[m + j][k] = t[j];
-      }
-      // ---- B
-      if (b_k_contig) {
-        const uint32_t n = g >> 2, k = (g & 3) * 8;
-        const uint32_t gn = tile_n + n, gk = k0 + k;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (gn < a.n && gk < a.k) {
-          const uint16_t* src = B + (int64_t)gn * a.b.s_col + gk;
-          if (b_vec && b_al) v = *(const uint4*)src;
-          else {
-            uint16_t t[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) t[j] = (gk + j < a.k) ? src[j] : (uint16_t)0;
-            v = make_uint4(t[0] | (t[1] << 16), t[2] | (t[3] << 16), t[4] | (t[5] << 16), t[6] | (t[7] << 16));
-          }
-        }
-        *(uint4*)&Bs[n][k] = v;
-      } else {
-        const uint32_t k = g >> 4, n = (g & 15) * 8;
-        const uint32_t gn = tile_n + n, gk = k0 + k;
-        uint16_t t[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) t[j] = 0;
-        if (gk < a.k && gn < a.n) {
-          const uint16_t* src = B + (int64_t)gk * a.b.s_row + gn;
-          if (b_vec && b_al) {
-            const uint4 v = *(const uint4*)src;
-            t[0] = v.x & 0xffff; t[1] = v.x >> 16; t[2] = v.y & 0xffff; t[3] = v.y >> 16;
-            t[4] = v.z & 0xffff; t[5] = v.z >> 16; t[6] = v.w & 0xffff; t[7] = v.w >> 16;
-          } else {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) t[j] = (gn + j < a.n) ? src[j] : (uint16_t)0;
-          }
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) Bs[n + j][k] = t[j];
-      }
+  GroupRegs<Groups<T, BM>::N> ga;
+  GroupRegs<Groups<T, BN>::N> gb;
+  fetch_tile<T, BM, AKC>(ga, A, a.a.s_row, a.a.s_col, tile_m, 0, a.m, a.k, a_al);
+  fetch_tile<T, BN, BKC>(gb, B, a.b.s_col, a.b.s_row, tile_n, 0, a.n, a.k, b_al);
+  stash_tile<BM, AKC>(ga, As(0));
+  stash_tile<BN, BKC>(gb, Bs(0));
+  __syncthreads();
+  uint32_t cur = 0;
+  for (uint32_t k0 = 0; k0 < a.k; k0 += BK) {
+    const bool more = k0 + BK < a.k;
+    if (more) {
+      fetch_tile<T, BM, AKC>(ga, A, a.a.s_row, a.a.s_col, tile_m, k0 + BK, a.m, a.k, a_al);
+      fetch_tile<T, BN, BKC>(gb, B, a.b.s_col, a.b.s_row, tile_n, k0 + BK, a.n, a.k, b_al);
+    }
+    mma_slice<BM, BN, MB, NB>(acc, As(cur), Bs(cur), wave_m, wave_n, lane);
+    if (more) {
+      stash_tile<BM, AKC>(ga, As(cur ^ 1));
+      stash_tile<BN, BKC>(gb, Bs(cur ^ 1));
     }
     __syncthreads();
-#pragma unroll
-    for (int kk = 0; kk < kBK16; kk += 16) {
-      const uint32_t kl = kk + (lane >> 5) * 8;
-      v8bf af[2], bf[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) af[i] = *(const v8bf*)&As[wave_m * 64 + i * 32 + (lane & 31)][kl];
-#pragma unroll
-      for (int j = 0; j < 2; ++j) bf[j] = *(const v8bf*)&Bs[wave_n * 64 + j * 32 + (lane & 31)][kl];
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
-    }
-    __syncthreads();
+    cur ^= 1;
   }
-  epilogue(a, acc, tile_m, tile_n, wave_m, wave_n, lane, batch);
+  epilogue<BM, BN, MB, NB>(a, acc, (float*)smem, tile_m, tile_n, wave_m, wave_n, lane, batch);
+}
+
+template <typename T, int BM, int BN>
+static void launch_variant(const GemmArgs& a, const dim3 grid, hipStream_t s) {
+  const bool akc = a.a.s_col == 1, bkc = a.b.s_row == 1;
+  if (akc && bkc) hipLaunchKernelGGL((lt_gemm_kernel<T, BM, BN, true, true>), grid, dim3(kGemmThreads), 0, s, a);
+  else if (akc) hipLaunchKernelGGL((lt_gemm_kernel<T, BM, BN, true, false>), grid, dim3(kGemmThreads), 0, s, a);
+  else if (bkc) hipLaunchKernelGGL((lt_gemm_kernel<T, BM, BN, false, true>), grid, dim3(kGemmThreads), 0, s, a);
+  else hipLaunchKernelGGL((lt_gemm_kernel<T, BM, BN, false, false>), grid, dim3(kGemmThreads), 0, s, a);
 }
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
-  const dim3 grid((a.n + kBN - 1) / kBN, (a.m + kBM - 1) / kBM, a.batch0 * a.batch1);
+  // an operand must have unit stride along one of its two dimensions
+  if ((a.a.s_col != 1 && a.a.s_row != 1) || (a.b.s_col != 1 && a.b.s_row != 1)) return hipErrorInvalidValue;
+  const uint32_t batch = a.batch0 * a.batch1;
+  // big tiles only when they still give every compute unit work
+  const uint64_t big_tiles = (uint64_t)((a.m + 127) / 128) * ((a.n + 127) / 128) * batch;
+  const bool big = big_tiles >= 256;
+  const uint32_t bm = big ? 128 : 64;
+  const dim3 grid((a.n + bm - 1) / bm, (a.m + bm - 1) / bm, batch);
   if (grid.y > 65535u || grid.z > 65535u) return hipErrorInvalidValue;
-  if (a.in_dtype == kBF16) hipLaunchKernelGGL(lt_gemm_bf16_kernel, grid, dim3(kGemmThreads), 0, s, a);
-  else hipLaunchKernelGGL(lt_gemm_f32_kernel, grid, dim3(kGemmThreads), 0, s, a);
+  if (a.in_dtype == kBF16) {
+    if (big) launch_variant<uint16_t, 128, 128>(a, grid, s);
+    else launch_variant<uint16_t, 64, 64>(a, grid, s);
+  } else {
+    if (big) launch_variant<float, 128, 128>(a, grid, s);
+    else launch_variant<float, 64, 64>(a, grid, s);
+  }
   return hipGetLastError();
 }
 

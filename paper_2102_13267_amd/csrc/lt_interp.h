@@ -282,7 +282,16 @@ template <int MAXIN> struct Staged {
 // Issue the loads of every input for the 4-vector at base + lane (base wave-uniform).  Fully
 // unrolled so that all loads are in flight together.  FAST: the host promises full, aligned
 // 4-vectors and no strided input, so the element-by-element path is not even compiled in.
-template <int MAXIN, bool FAST, bool F32>
+// Every use of fetched values is made to depend on this point.  Placed behind the last load it
+// keeps the compiler from sinking each input's "move into the slot" into that input's own
+// branch, right behind its load, which would wait for every load before issuing the next.
+template <int MAXIN>
+__device__ __forceinline__ void pin_staged(Staged<MAXIN>& st) {
+#pragma unroll
+  for (int k = 0; k < MAXIN; ++k) asm volatile("" : "+v"(st.vec[k]), "+v"(st.bc[k]));
+}
+
+template <int MAXIN, bool FAST, bool F32, bool PIN = true>
 __device__ __forceinline__ Staged<MAXIN> fetch_inputs(const EwProg& p, uint64_t base, uint32_t lane, uint32_t nvalid) {
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Wuninitialized"
@@ -314,12 +323,7 @@ __device__ __forceinline__ Staged<MAXIN> fetch_inputs(const EwProg& p, uint64_t 
       }
     }
   }
-  // Every use of the fetched values is made to depend on this point, which lies behind the last
-  // load: without it the compiler sinks the "move into the slot" of each input into that input's
-  // own branch, right behind its load, and so waits for every load before issuing the next.
-#pragma unroll
-  for (int k = 0; k < MAXIN; ++k)
-    asm volatile("" : "+v"(st.vec[k]), "+v"(st.bc[k]));
+  if (PIN) pin_staged<MAXIN>(st);
   return st;
 #pragma clang diagnostic pop
 }

@@ -67,7 +67,10 @@ __global__ __launch_bounds__(kBlock) void lt_all_reduce_kernel(const AllArgs a) 
   for (uint64_t t = 0; t < full_trips; ++t) {
     Staged<MAXIN> st[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) st[u] = fetch_inputs<MAXIN, FAST, F32>(pro, 0, (uint32_t)((v + (uint64_t)u * stride) * kVec), kVec);
+    for (int u = 0; u < U; ++u)
+      st[u] = fetch_inputs<MAXIN, FAST, F32, false>(pro, 0, (uint32_t)((v + (uint64_t)u * stride) * kVec), kVec);
+#pragma unroll
+    for (int u = 0; u < U; ++u) pin_staged<MAXIN>(st[u]);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       RF<16> f = place_inputs<16, MAXIN, FAST, F32>(rf_zero<16>(), pro, st[u], kVec);

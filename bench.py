@@ -235,6 +235,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="c4", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy, so that a rocprofv3 --pmc run of this command "
+                         "holds a kernel of known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
@@ -243,6 +246,13 @@ def main():
     defaults = {"c4": (20, 3), "c1": (200, 10), "c2": (200, 10), "c5": (100, 10)}
     steps = args.steps if args.steps is not None else defaults[args.workload][0]
     warmup = args.warmup if args.warmup is not None else defaults[args.workload][1]
+    if args.copy_calibration:
+        import torch
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     dt, dtype, config, roof, extra, cpu = WORKLOADS[args.workload](steps, warmup)
     line = {
         "metric": "barrier-steps/sec", "value": steps / dt, "unit": "steps/s", "n_gpus": 1, "steps": steps,

@@ -25,6 +25,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the 1 GiB calibration
+# copy of the same runs (FETCH x 2.000, WRITE x 1.000): see profiles/c4_adam_clip_kernels.md
+PROFILED_TRAFFIC = {("c4", "lt_ew_kernel"): 7_516_357_427}
 MFMA_PEAK_TFLOPS = {"bf16": 2516.6, "f32": 157.3}
 
 
@@ -97,6 +100,8 @@ def run_c4(steps, warmup, n=268_435_456):
     roof = {"bound": "hbm", "kernel": kernel, "achieved": kbytes / (avg_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "traffic": None, "avg_ms": avg_ms, "bytes_per_launch": kbytes}
     roof["frac"] = roof["achieved"] / roof["peak"]
+    if n == 268_435_456:
+        roof["traffic"] = PROFILED_TRAFFIC.get(("c4", kernel))
     extra = {"kernels": table, "plan": ctx.dump_plan(), "cache_hits": sum(i.cache_hit for i in infos),
              "bytes_planned_per_step": int(infos[-1].bytes_planned),
              "whole_step_GBps": infos[-1].bytes_planned * steps / dt / 1e9}

@@ -624,7 +624,10 @@ class Tracer:
             if n.op in (EXPAND, RESHAPE):
                 # a view that must itself be materialised (it is a root) is a copy
                 return EW if is_root[i] else VIEW
-            if n.op in UNARY or n.op in BINARY or n.op == PERMUTE:
+            if n.op == PERMUTE:
+                # a permutation that only feeds contractions is addressing (operand strides), not a copy
+                return VIEW if (not is_root[i] and pre_users[i] and all(nd[u].op == MATMUL for u in pre_users[i])) else EW
+            if n.op in UNARY or n.op in BINARY:
                 return EW
             if n.op in PLAIN_REDUCE:
                 in_shape = oshape(rins[i][0])
@@ -646,6 +649,12 @@ class Tracer:
         is_root = [False] * N
         for v in root_vals:
             is_root[v[0]] = True
+        pre_users = [[] for _ in range(N)]      # live users, needed before classes exist
+        for j in range(N):
+            if live[j]:
+                for v in rins[j]:
+                    if j not in pre_users[v[0]]:
+                        pre_users[v[0]].append(j)
         cls = [klass(i) if live[i] else "DEAD" for i in range(N)]
 
         def is_imm(v):
@@ -762,6 +771,8 @@ class Tracer:
             return False
 
         def compatible(r, i):
+            if r.get("sealed"):
+                return False
             shape = nd[i].shape
             if r["kind"] == EW:
                 return shape == nd[min(r["members"])].shape
@@ -794,7 +805,17 @@ class Tracer:
             del regions[id(other)]
 
         for i in range(N):
-            if cls[i] != EW or len(region_of[i]["members"]) != 1 or nd[i].op == PERMUTE:
+            if cls[i] != EW or len(region_of[i]["members"]) != 1:
+                continue
+            if nd[i].op == PERMUTE:
+                # a permutation of a bare contraction result that nothing else reads becomes the
+                # contraction's output layout
+                v = rins[i][0]
+                a = v[0]
+                if (cls[a] == MM and v[1] == 0 and region_of[a]["members"] == {a} and users[a] == [i]
+                        and not is_root[a]):
+                    union(region_of[a], region_of[i])
+                    region_of[a]["sealed"] = True      # the layout change ends the region
                 continue
             cand = []
             for v in rins[i]:
@@ -815,6 +836,19 @@ class Tracer:
                         r["fin_shape"] = nd[i].shape
                     union(r, home)
                     home = r
+                    # elementwise producers of i that feed nothing but this region (e.g. beta*m of
+                    # an optimiser update) are computed by the region's post program too
+                    for v in rins[i]:
+                        q = region_of.get(v[0])
+                        if q is None or q is home or q["kind"] != EW or id(q) not in regions:
+                            continue
+                        if nd[min(q["members"])].shape != nd[i].shape or any(is_root[m] for m in q["members"]):
+                            continue
+                        if not all(u in q["members"] or u in home["members"] for m in q["members"] for u in users[m]):
+                            continue
+                        if not caps_ok(home["members"] | q["members"]) or not can_union(home, q):
+                            continue
+                        union(home, q)
                 elif home["kind"] == EW:
                     # grow one elementwise region out of producer regions of equal shape
                     if not compatible(r, i) or not caps_ok(r["members"] | home["members"]):

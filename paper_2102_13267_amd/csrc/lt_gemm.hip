@@ -48,14 +48,15 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, const v16f (&acc)[MB
   const EwProg& p = a.post;
   const ProgRegs pr = load_prog_regs(p);
   const uint32_t n_code = p.n_code;
-  const uint64_t base_row = (uint64_t)batch * a.m;
+  const uint32_t b0 = batch / a.batch1, b1 = batch % a.batch1;
+  const int64_t base = (int64_t)b0 * a.o_b0 + (int64_t)b1 * a.o_b1;
 #pragma unroll 1
   for (uint32_t q = threadIdx.x; q < (uint32_t)(BM * BN / kVec); q += kGemmThreads) {
     const uint32_t r = q / (BN / kVec), c = (q % (BN / kVec)) * kVec;
     const uint32_t row = tile_m + r, col = tile_n + c;
     if (row >= a.m || col >= a.n) continue;
     const uint32_t nvalid = a.n - col >= (uint32_t)kVec ? (uint32_t)kVec : a.n - col;
-    const uint32_t i = (uint32_t)((base_row + row) * a.n + col);
+    const uint32_t i = (uint32_t)(base + (int64_t)row * a.o_row + col);
     const float4 t = *(const float4*)&Cs[r * kCStride + c];
     Quad anchor;
     anchor.v[0] = t.x; anchor.v[1] = t.y; anchor.v[2] = t.z; anchor.v[3] = t.w;
@@ -238,8 +239,9 @@ __global__ __launch_bounds__(kGemmThreads) void lt_gemm_kernel(const GemmArgs a)
   const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const uint32_t wave_m = wave >> 1, wave_n = wave & 1;
   const uint32_t tile_m = blockIdx.y * BM, tile_n = blockIdx.x * BN, batch = blockIdx.z;
-  const T* A = (const T*)a.a.ptr + (int64_t)batch * a.a.s_b0;
-  const T* B = (const T*)a.b.ptr + (int64_t)batch * a.b.s_b0;
+  const uint32_t b0 = batch / a.batch1, b1 = batch % a.batch1;
+  const T* A = (const T*)a.a.ptr + (int64_t)b0 * a.a.s_b0 + (int64_t)b1 * a.a.s_b1;
+  const T* B = (const T*)a.b.ptr + (int64_t)b0 * a.b.s_b0 + (int64_t)b1 * a.b.s_b1;
   // 16-byte loads need 16-byte aligned groups: base, and the stride between groups' rows
   constexpr int G = Elem<T>::G;
   const int64_t a_outer = AKC ? a.a.s_row : a.a.s_col, b_outer = BKC ? a.b.s_col : a.b.s_row;

@@ -159,7 +159,11 @@ struct GemmArgs {
   uint32_t batch0, batch1;   // batch = batch0 * batch1 (b = b0 * batch1 + b1)
   uint32_t in_dtype;         // kF32 or kBF16 (both operands)
   uint32_t tiles_m, tiles_n;
-  EwProg post;               // iteration space [batch * m, n] of the output
+  // where output element (b0, b1, row, col) goes: b0*o_b0 + b1*o_b1 + row*o_row + col (elements).
+  // Contiguous [batch, m, n] by default; a permuted layout when the product's only reader is a
+  // permutation (head merge), which then costs nothing.
+  int64_t o_b0, o_b1, o_row;
+  EwProg post;               // iteration space = the output
 };
 
 }  // namespace ltk

@@ -39,6 +39,7 @@ struct Region {
   int32_t anchor;                 // canonical index or -1
   std::vector<int32_t> members;   // sorted canonical indices
   bool has_fin = false;
+  bool sealed = false;              // ends in a layout permute: takes no further members
   std::vector<int64_t> fin_shape;
   std::vector<Region*> extra_succ;   // ordering-only edges added by donation
   bool alive = true;
@@ -175,13 +176,24 @@ struct Lowering {
 
   // ---- step 2: classes and users ------------------------------------------------------------------
   bool classify() {
+    users.assign(N, {});
+    for (int32_t j = 0; j < N; ++j) {
+      if (!live[j]) continue;
+      for (Val v : rins[j])
+        if (std::find(users[v.node].begin(), users[v.node].end(), j) == users[v.node].end()) users[v.node].push_back(j);
+    }
     cls.assign(N, C_DEAD);
     for (int32_t i = 0; i < N; ++i) {
       if (!live[i]) continue;
       const uint16_t op = nd[i]->op;
       if (op == OP_DEVICE_DATA || op == OP_SCALAR_PARAM || op == OP_CONSTANT) cls[i] = C_LEAF;
       else if (op == LT_OP_EXPAND || op == LT_OP_RESHAPE) cls[i] = is_root[i] ? C_EW : C_VIEW;
-      else if (is_unary(op) || is_binary(op) || op == LT_OP_PERMUTE) cls[i] = C_EW;
+      else if (op == LT_OP_PERMUTE) {
+        // a permutation that only feeds contractions is addressing (operand strides), not a copy
+        bool only_mm = !is_root[i] && !users[i].empty();
+        for (int32_t u : users[i]) only_mm = only_mm && nd[u]->op == LT_OP_MATMUL;
+        cls[i] = only_mm ? C_VIEW : C_EW;
+      } else if (is_unary(op) || is_binary(op)) cls[i] = C_EW;
       else if (plain_reduce(op)) {
         const int in_rank = out_rank(rins[i][0]);
         if (nd[i]->n_attr == 0 || in_rank <= 1) cls[i] = C_ALL;
@@ -191,12 +203,6 @@ struct Lowering {
       } else if (is_row_op(op)) cls[i] = C_ROW;
       else if (op == LT_OP_MATMUL) cls[i] = C_MM;
       else return bad(LT_ERR_UNSUPPORTED, "opcode has no lowering");
-    }
-    users.assign(N, {});
-    for (int32_t j = 0; j < N; ++j) {
-      if (!live[j]) continue;
-      for (Val v : rins[j])
-        if (std::find(users[v.node].begin(), users[v.node].end(), j) == users[v.node].end()) users[v.node].push_back(j);
     }
     return true;
   }
@@ -286,6 +292,7 @@ struct Lowering {
   }
 
   bool compatible(const Region* r, int32_t i) const {
+    if (r->sealed) return false;
     const std::vector<int64_t> shape = shape_of(i);
     if (r->kind == C_EW) return shape == shape_of(r->members.front());
     const int32_t a = r->anchor;
@@ -324,7 +331,20 @@ struct Lowering {
     }
     // pass 2: epilogue / finaliser / elementwise grouping
     for (int32_t i = 0; i < N; ++i) {
-      if (cls[i] != C_EW || region_of[i]->members.size() != 1 || nd[i]->op == LT_OP_PERMUTE) continue;
+      if (cls[i] != C_EW || region_of[i]->members.size() != 1) continue;
+      if (nd[i]->op == LT_OP_PERMUTE) {
+        // a permutation of a bare contraction result that nothing else reads becomes the
+        // contraction's output layout
+        const Val v = rins[i][0];
+        const int32_t a = v.node;
+        if (cls[a] == C_MM && v.slot == 0 && region_of[a]->members.size() == 1 && users[a].size() == 1 && users[a][0] == i &&
+            !is_root[a]) {
+          Region* r = region_of[a];
+          unite(r, region_of[i]);
+          r->sealed = true;
+        }
+        continue;
+      }
       std::vector<Region*> cand;
       for (Val v : rins[i]) {
         Region* r = region_of[v.node];
@@ -347,6 +367,21 @@ struct Lowering {
           }
           unite(r, home);
           home = r;
+          // elementwise producers of i that feed nothing but this region (e.g. beta*m of an
+          // optimiser update) are computed by the region's post program too
+          for (Val v : rins[i]) {
+            Region* q = region_of[v.node];
+            if (!q || q == home || q->kind != C_EW || !q->alive) continue;
+            if (shape_of(q->members.front()) != shape_of(i)) continue;
+            bool ok = true;
+            for (int32_t m : q->members) {
+              ok = ok && !is_root[m];
+              for (int32_t u : users[m]) ok = ok && (q->has(u) || home->has(u));
+            }
+            if (!ok) continue;
+            if (!caps_ok(merged(home->members, q->members)) || !can_union(home, q)) continue;
+            unite(home, q);
+          }
         } else if (home->kind == C_EW) {
           if (!compatible(r, i) || !caps_ok(merged(r->members, home->members))) continue;
           if (!can_union(r, home)) continue;
@@ -508,6 +543,13 @@ struct Lowering {
       std::vector<int64_t> st(oshape.size(), 0);
       const int off = (int)oshape.size() - (int)ishape.size();
       for (size_t d = 0; d < ishape.size(); ++d) st[d + off] = ishape[d] == 1 ? 0 : istride[d];
+      *shape = oshape;
+      *stride = st;
+      return true;
+    }
+    if (nd[v.node]->op == LT_OP_PERMUTE) {
+      std::vector<int64_t> st(oshape.size());
+      for (size_t d = 0; d < oshape.size(); ++d) st[d] = istride[nd[v.node]->attrs[d].v.i];
       *shape = oshape;
       *stride = st;
       return true;
@@ -905,25 +947,33 @@ struct Lowering {
     return (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(tiles, 256 * 32));
   }
 
-  bool operand_gemm(Val v, bool trans, bool flatten_lead, ltk::GemmOperand* g, int32_t* storage, uint8_t* dtype,
-                    std::vector<int64_t>* lead) {
+  // A contraction operand seen through its views: strides of the two matrix dimensions and of the
+  // (non-unit) leading dimensions.
+  struct MatView {
+    int32_t storage;
+    uint8_t dtype;
+    int64_t rows, cols, s_row, s_col;
+    std::vector<int64_t> lead, s_lead;
+  };
+
+  bool operand_gemm(Val v, bool trans, MatView* mv) {
     std::vector<int64_t> shape, stride;
-    if (!view_strides(v, storage, &shape, &stride)) return false;
-    *dtype = out_dtype(base(v));
+    if (!view_strides(v, &mv->storage, &shape, &stride)) return false;
+    mv->dtype = out_dtype(base(v));
     const size_t r = shape.size();
-    g->ptr = nullptr;
-    g->s_row = trans ? stride[r - 1] : stride[r - 2];
-    g->s_col = trans ? stride[r - 2] : stride[r - 1];
-    lead->assign(shape.begin(), shape.end() - 2);
-    // leading axes must be dense over the matrices so that one batch stride describes them
-    int64_t expect = shape[r - 2] * shape[r - 1];
-    for (int d = (int)r - 3; d >= 0; --d) {
-      if (shape[d] != 1 && stride[d] != expect) return bad(LT_ERR_UNSUPPORTED, "matmul operand with non-dense leading axes");
-      expect *= shape[d];
-    }
-    g->s_b0 = r > 2 ? shape[r - 2] * shape[r - 1] : 0;
-    g->s_b1 = 0;
-    (void)flatten_lead;
+    mv->rows = trans ? shape[r - 1] : shape[r - 2];
+    mv->cols = trans ? shape[r - 2] : shape[r - 1];
+    mv->s_row = trans ? stride[r - 1] : stride[r - 2];
+    mv->s_col = trans ? stride[r - 2] : stride[r - 1];
+    if (mv->rows == 1) mv->s_row = mv->s_col == 1 ? mv->cols : 1;   // any stride serves a single row / column
+    if (mv->cols == 1) mv->s_col = mv->s_row == 1 ? mv->rows : 1;
+    mv->lead.clear();
+    mv->s_lead.clear();
+    for (size_t d = 0; d + 2 < r; ++d)
+      if (shape[d] != 1) {
+        mv->lead.push_back(shape[d]);
+        mv->s_lead.push_back(stride[d]);
+      }
     return true;
   }
 
@@ -1021,11 +1071,25 @@ struct Lowering {
     }
     const int32_t a = r->anchor;
     const Node* an = nd[a];
-    // split members into prologue (< anchor) and post (> anchor)
+    // split members: the prologue is what the anchor depends on, everything else runs after it
+    std::vector<char> feeds(N, 0);
+    {
+      std::vector<int32_t> stack{a};
+      while (!stack.empty()) {
+        const int32_t x = stack.back();
+        stack.pop_back();
+        for (Val v : rins[x])
+          if (r->has(v.node) && !feeds[v.node]) {
+            feeds[v.node] = 1;
+            stack.push_back(v.node);
+          }
+      }
+    }
     std::vector<int32_t> pro_m, post_m;
     for (int32_t m : r->members) {
-      if (m < a) pro_m.push_back(m);
-      else if (m > a) post_m.push_back(m);
+      if (m == a) continue;
+      if (feeds[m]) pro_m.push_back(m);
+      else post_m.push_back(m);
     }
     if (r->kind == C_MM) return emit_gemm(k, r, post_m, out);
     if (!plain_reduce(an->op)) return emit_row_op(k, r, out);
@@ -1218,7 +1282,7 @@ struct Lowering {
     return true;
   }
 
-  bool emit_gemm(int k, Region* r, const std::vector<int32_t>& post_m, const std::vector<Val>& out) {
+  bool emit_gemm(int k, Region* r, const std::vector<int32_t>& post_m_in, const std::vector<Val>& out_in) {
     const int32_t a = r->anchor;
     const Node* an = nd[a];
     const int launch = (int)plan->launches.size();
@@ -1228,45 +1292,93 @@ struct Lowering {
       if (an->attrs[i].key == LT_ATTR_TRANS_B) trb = an->attrs[i].v.i != 0;
     }
     ltk::GemmArgs args{};
-    int32_t sa, sb;
-    uint8_t da, db;
-    std::vector<int64_t> la, lb;
-    if (!operand_gemm(rins[a][0], tra, false, &args.a, &sa, &da, &la)) return false;
-    if (!operand_gemm(rins[a][1], trb, false, &args.b, &sb, &db, &lb)) return false;
-    if (da != db) return bad(LT_ERR_UNSUPPORTED, "matmul of operands with different dtypes has no lowering");
+    MatView A, B;
+    if (!operand_gemm(rins[a][0], tra, &A)) return false;
+    if (!operand_gemm(rins[a][1], trb, &B)) return false;
+    if (A.dtype != B.dtype) return bad(LT_ERR_UNSUPPORTED, "matmul of operands with different dtypes has no lowering");
+    if ((A.s_row != 1 && A.s_col != 1) || (B.s_row != 1 && B.s_col != 1))
+      return bad(LT_ERR_UNSUPPORTED, "matmul operand without a unit-stride matrix dimension");
     const std::vector<int64_t> os = shape_of(a);
-    args.m = (uint32_t)os[os.size() - 2];
-    args.n = (uint32_t)os.back();
-    const std::vector<int64_t> as = out_shape(rins[a][0]);
-    args.k = (uint32_t)(tra ? as[as.size() - 2] : as.back());
-    int64_t batch = count(la);
-    if (lb.empty() && batch > 1) {
-      // a plain matrix on the right: fold the leading axes of a into its rows
+    int64_t m = A.rows, n = B.cols;
+    const int64_t kk = A.cols;
+    std::vector<int64_t> lead = A.lead;
+    if (B.lead.empty() && !A.lead.empty()) {
+      // a plain matrix on the right: fold the (dense) leading axes of a into its rows
       if (tra) return bad(LT_ERR_UNSUPPORTED, "transposed batched a with an unbatched b has no lowering");
-      args.m = (uint32_t)(batch * args.m);
-      batch = 1;
+      int64_t expect = A.s_row * A.rows;
+      for (int d = (int)A.lead.size() - 1; d >= 0; --d) {
+        if (A.s_lead[d] != expect) return bad(LT_ERR_UNSUPPORTED, "matmul: leading axes of a are not dense over its rows");
+        expect *= A.lead[d];
+      }
+      for (int64_t d : A.lead) m *= d;
+      lead.clear();
+      A.lead.clear();
+      A.s_lead.clear();
     }
-    args.batch0 = (uint32_t)batch;
-    args.batch1 = 1;
-    if (batch == 1) args.a.s_b0 = args.b.s_b0 = 0;
-    args.in_dtype = da;
+    if (lead.size() > 2) return bad(LT_ERR_UNSUPPORTED, "matmul with more than two batch axes has no lowering");
+    if (B.lead != lead) return bad(LT_ERR_UNSUPPORTED, "matmul: batch axes of a and b differ after views");
+    args.m = (uint32_t)m;
+    args.n = (uint32_t)n;
+    args.k = (uint32_t)kk;
+    args.batch0 = lead.size() == 2 ? (uint32_t)lead[0] : lead.size() == 1 ? (uint32_t)lead[0] : 1u;
+    args.batch1 = lead.size() == 2 ? (uint32_t)lead[1] : 1u;
+    auto fill = [&](ltk::GemmOperand* g, const MatView& mv) {
+      g->ptr = nullptr;
+      g->s_row = mv.s_row;
+      g->s_col = mv.s_col;
+      g->s_b0 = mv.s_lead.size() >= 1 ? mv.s_lead[0] : 0;
+      g->s_b1 = mv.s_lead.size() == 2 ? mv.s_lead[1] : 0;
+    };
+    fill(&args.a, A);
+    fill(&args.b, B);
+    args.in_dtype = A.dtype;
+    const int64_t batch = (int64_t)args.batch0 * args.batch1;
+    // output layout: contiguous [batch0, batch1, m, n] unless the region ends in a layout permute
+    args.o_row = n;
+    args.o_b1 = m * n;
+    args.o_b0 = (int64_t)args.batch1 * m * n;
+    std::vector<int32_t> post_m = post_m_in;
+    std::vector<Val> out = out_in;
+    if (r->sealed) {
+      const int32_t pm = post_m.back();   // the permute member
+      if (post_m.size() != 1 || nd[pm]->op != LT_OP_PERMUTE) return bad(LT_ERR_UNSUPPORTED, "internal: sealed region shape");
+      // stride of anchor dimension d in the permuted, dense result
+      const std::vector<int64_t> pshape = shape_of(pm), pcs = contiguous(pshape);
+      std::vector<int64_t> sd(os.size(), 0);
+      for (size_t j = 0; j < pshape.size(); ++j) sd[nd[pm]->attrs[j].v.i] = pcs[j];
+      const size_t rr = os.size();
+      if (sd[rr - 1] != 1) return bad(LT_ERR_UNSUPPORTED, "permuted matmul result must keep its last axis last");
+      std::vector<int64_t> ol;
+      for (size_t d = 0; d + 2 < rr; ++d)
+        if (os[d] != 1) ol.push_back(sd[d]);
+      if (ol.size() != lead.size()) return bad(LT_ERR_UNSUPPORTED, "permuted matmul result: batch axes do not match");
+      args.o_row = sd[rr - 2];
+      args.o_b0 = ol.size() >= 1 ? ol[0] : 0;
+      args.o_b1 = ol.size() == 2 ? ol[1] : 0;
+      // the region's output is the permute's value; the program only stores the accumulator
+      storage_of[a][0] = storage_of[pm][0];
+      post_m.clear();
+      out.assign(1, Val{a, 0});
+    }
     ProgBuild post;
     std::vector<int32_t> post_members = post_m;
     post_members.insert(post_members.begin(), a);
-    std::vector<int64_t> space{(int64_t)batch * args.m, (int64_t)args.n};
-    // the post program sees the output flat as [batch*m, n]; every member has the output's shape,
-    // so broadcast classification must be done against the true shape
-    if (!build_prog(post_members, shape_of(a), Val{a, 0}, out, false, &post)) return false;
-    (void)space;
+    if (!build_prog(post_members, os, Val{a, 0}, out, false, &post)) return false;
+    if (r->sealed) {
+      storage_of[a][0] = -1;
+      // quads are 16-byte aligned in the permuted layout only if every stride is a multiple of 4
+      const bool al = (args.o_row % 4) == 0 && (args.o_b0 % 4) == 0 && (args.o_b1 % 4) == 0 && (n % 4) == 0;
+      post.prog.vec_ok = post.prog.full_vec_ok = al ? 1u : 0u;
+    }
     args.post = post.prog;
     Launch l = make_launch(L_GEMM, k, args);
-    l.flops = 2ull * (uint64_t)batch * args.m * args.n * args.k;
-    l.bytes = post.bytes + (uint64_t)batch * ((uint64_t)args.m * args.k + (uint64_t)args.k * args.n) * dtype_size(da);
+    l.flops = 2ull * (uint64_t)batch * m * n * kk;
+    l.bytes = post.bytes + (uint64_t)batch * ((uint64_t)m * kk + (uint64_t)kk * n) * dtype_size(A.dtype);
     plan->launches.push_back(std::move(l));
-    plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)(offsetof(ltk::GemmArgs, a) + offsetof(ltk::GemmOperand, ptr)), sa, 0});
-    plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)(offsetof(ltk::GemmArgs, b) + offsetof(ltk::GemmOperand, ptr)), sb, 0});
-    touch(sa, launch);
-    touch(sb, launch);
+    plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)(offsetof(ltk::GemmArgs, a) + offsetof(ltk::GemmOperand, ptr)), A.storage, 0});
+    plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)(offsetof(ltk::GemmArgs, b) + offsetof(ltk::GemmOperand, ptr)), B.storage, 0});
+    touch(A.storage, launch);
+    touch(B.storage, launch);
     add_prog_patches(launch, offsetof(ltk::GemmArgs, post), post);
     note_prog_storages(post, launch);
     return true;

@@ -383,3 +383,59 @@ def test_c5_dynamic_shapes_and_host_control_flow(ctx):
         check(ctx, E, s, sr, TOL32, f"checksum step {step}")
         assert info.n_regions == 4 + depth + 1
     assert misses == len(seen)
+
+
+def _c3_setup(B, mk, cfg):
+    from workloads.inputs import c3_inputs
+    bsz, seq, d, ffn, heads = cfg
+    inp = c3_inputs(bsz, seq, d, ffn)
+    keys = programs.C3_WEIGHTS + programs.C3_VECTORS
+    P = {k: mk(round_to_bf16(inp[k]), "bf16", True) for k in keys}
+    M = {k: mk(np.zeros_like(inp[k]), "f32", True) for k in keys}
+    V = {k: mk(np.zeros_like(inp[k]), "f32", True) for k in keys}
+    x, dy = mk(round_to_bf16(inp["x"]), "bf16", False), mk(round_to_bf16(inp["dy"]), "bf16", False)
+    return x, dy, P, M, V, heads
+
+
+@pytest.mark.parametrize("cfg", [(2, 16, 64, 128, 4), (3, 40, 192, 320, 6)])
+def test_c3_transformer_layer_forward_backward_adam(ctx, cfg):
+    """bf16 activations and weights, fp32 accumulation and Adam moments; 2e-2 per tensor.
+    Two steps: the second is a cache hit and runs on the updated (donated) parameters."""
+    E = Eager()
+    g = _c3_setup(ctx, lambda a, dt, don: ctx.tensor(a, dtype=dt, donatable=don), cfg)
+    r = _c3_setup(E, lambda a, dt, don: E.tensor(a, dtype=dt), cfg)
+    for step in range(2):
+        yg, dxg = programs.c3_step(ctx, *g, t=step + 1)
+        info = ctx.barrier()
+        yr, dxr = programs.c3_step(E, *r, t=step + 1)
+        assert info.cache_hit == (step > 0)
+        check(ctx, E, yg, yr, TOL16, "y")
+        check(ctx, E, dxg, dxr, TOL16, "dx")
+        for k in programs.C3_WEIGHTS + programs.C3_VECTORS:
+            if k == "bk":
+                # Softmax is invariant to a shift of its row, so the key bias has an exactly zero
+                # gradient: what both sides hold there is rounding noise, small against a live
+                # gradient of the same shape (the query bias), and not comparable element-wise.
+                live = np.max(np.abs(E.fetch(r[3]["bq"])))
+                assert np.max(np.abs(E.fetch(r[3][k]))) <= 0.1 * live
+                assert np.max(np.abs(ctx.fetch(g[3][k]))) <= 0.1 * live
+            else:
+                check(ctx, E, g[3][k], r[3][k], TOL16, f"m[{k}] step {step}")     # first moment = the gradient
+                check(ctx, E, g[4][k], r[4][k], 2 * TOL16, f"v[{k}] step {step}")  # squares double the relative error
+            # With zero moments Adam's first steps are sign descent: an element whose gradient is
+            # pure rounding noise moves by +lr in one implementation and -lr in the other.  So the
+            # parameters are held to  2.2 lr per step + one bf16 ulp  in absolute terms; the gradients
+            # themselves (m, v above) carry the 2e-2 parity.
+            ref_p = E.fetch(r[2][k]).astype(np.float64)
+            got_p = ctx.fetch(g[2][k]).astype(np.float64)
+            bound = 2.2e-3 * (step + 1) + 2.0 ** -8 * max(np.max(np.abs(ref_p)), 1e-30)   # lr = 1e-3, per step taken
+            assert np.max(np.abs(got_p - ref_p)) <= bound, (k, step, np.max(np.abs(got_p - ref_p)), bound)
+            strong = np.abs(E.fetch(r[3][k])) > 0.05 * np.max(np.abs(E.fetch(r[3][k])))
+            if step == 0 and k != "bk" and strong.any():
+                # where the first gradient is clearly non-zero the sign, hence the step, is fixed:
+                # there the new parameter agrees to 2 bf16 ulps (of the value or of the lr-sized step)
+                ulp = 2.0 ** -7 * np.maximum(np.abs(ref_p[strong]), 1e-3)
+                assert np.all(np.abs(got_p[strong] - ref_p[strong]) <= 2 * ulp), (k, step)
+    plan = ctx.dump_plan()
+    assert plan.count("->p") == 48                          # 16 parameters x (p, m, v) updated in place
+    assert " EW " not in plan.replace("R41 EW", "") or plan.count(" EW ") <= 2   # no stray copy kernels for the head split / merge

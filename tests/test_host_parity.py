@@ -117,6 +117,28 @@ def test_c5_parity_distinct_depths_are_distinct_programs():
     assert len(set(seen.values())) == len(seen)
 
 
+def test_c3_parity_head_split_is_addressing_not_copies():
+    from workloads.inputs import c3_inputs
+    P_ = Pair()
+    bsz, seq, d, ffn, heads = 2, 16, 64, 128, 4
+    inp = c3_inputs(bsz, seq, d, ffn)
+    keys = programs.C3_WEIGHTS + programs.C3_VECTORS
+    W = {k: P_.tensor(inp[k].shape, "bf16", donatable=True) for k in keys}
+    M = {k: P_.tensor(inp[k].shape, "f32", donatable=True) for k in keys}
+    V = {k: P_.tensor(inp[k].shape, "f32", donatable=True) for k in keys}
+    x, dy = P_.tensor(inp["x"].shape, "bf16"), P_.tensor(inp["dy"].shape, "bf16")
+    side = lambda i: (x[i], dy[i], {k: W[k][i] for k in keys}, {k: M[k][i] for k in keys}, {k: V[k][i] for k in keys}, heads)
+    for step in range(2):
+        oa = programs.c3_step(P_.lib, *side(0), t=step + 1)
+        ob = programs.c3_step(P_.ora, *side(1), t=step + 1)
+        info, ref = P_.barrier()
+        assert info.cache_hit == (step > 0)
+        assert ref["plan"].count("->p") == 48
+        kinds = [l.split()[1] for l in ref["plan"].splitlines()]
+        assert kinds.count("EW") <= 2 and kinds.count("MM") == 24
+        del oa, ob
+
+
 def test_random_traces_parity():
     rng = np.random.Generator(np.random.PCG64(7))
     unary = ["neg", "abs", "exp", "tanh", "sqrt", "relu", "gelu", "square", "sigmoid"]

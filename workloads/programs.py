@@ -77,3 +77,88 @@ def c5_forward(B, X, W, b, Wr, br, depth):
     for j in range(depth):
         h = B.add(h, B.gelu(B.add(B.matmul(h, Wr[j]), br[j])))
     return B.sum(h), h
+
+
+C3_WEIGHTS = ("Wq", "Wk", "Wv", "Wo", "W1", "W2")
+C3_VECTORS = ("bq", "bk", "bv", "bo", "b1", "b2", "g1", "be1", "g2", "be2")
+
+
+def c3_step(B, x, dy, P, M, V, heads, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, t=1):
+    """Pre-LayerNorm transformer encoder layer, forward + backward + Adam, one trace.
+    x, dy: [batch, seq, d] bf16 (dy is the upstream gradient of the layer output).
+    P: dict of bf16 parameters (C3_WEIGHTS are [in, out] matrices), M / V: dicts of fp32 Adam
+    moments with the same keys; all three are updated in place.  Returns (y, dx).
+    The 1/sqrt(d_head) factor is folded into the query projection."""
+    bsz, seq, d = x.shape
+    dh = d // heads
+    n = bsz * seq
+    scale = 1.0 / (dh ** 0.5)
+    x2 = B.reshape(x, (n, d))
+    dy2 = B.reshape(dy, (n, d))
+
+    def split(t2):      # [n, d] -> [batch, heads, seq, dh]   (views)
+        return B.permute(B.reshape(t2, (bsz, seq, heads, dh)), (0, 2, 1, 3))
+
+    def merge(t4):      # [batch, heads, seq, dh] -> [n, d]
+        return B.reshape(B.permute(t4, (0, 2, 1, 3)), (n, d))
+
+    # ---- forward
+    ln1, mu1, rs1 = B.layer_norm(x2, P["g1"], P["be1"])
+    qs = B.mul(B.add(B.matmul(ln1, P["Wq"]), P["bq"]), scale)
+    kk = B.add(B.matmul(ln1, P["Wk"]), P["bk"])
+    vv = B.add(B.matmul(ln1, P["Wv"]), P["bv"])
+    qh, kh, vh = split(qs), split(kk), split(vv)
+    prob = B.softmax(B.matmul(qh, kh, trans_b=True))
+    ctx = merge(B.matmul(prob, vh))
+    x3 = B.add(x2, B.add(B.matmul(ctx, P["Wo"]), P["bo"]))
+    ln2, mu2, rs2 = B.layer_norm(x3, P["g2"], P["be2"])
+    u = B.add(B.matmul(ln2, P["W1"]), P["b1"])
+    h = B.gelu(u)
+    y = B.add(x3, B.add(B.matmul(h, P["W2"]), P["b2"]))
+
+    # ---- backward
+    G = {}
+    G["W2"] = B.matmul(h, dy2, trans_a=True)
+    G["b2"] = B.sum(dy2, axis=0)
+    du = B.gelu_grad(B.matmul(dy2, P["W2"], trans_b=True), u)
+    G["W1"] = B.matmul(ln2, du, trans_a=True)
+    G["b1"] = B.sum(du, axis=0)
+    dln2 = B.matmul(du, P["W1"], trans_b=True)
+    xhat2 = B.mul(B.sub(x3, B.reshape(mu2, (n, 1))), B.reshape(rs2, (n, 1)))
+    G["g2"] = B.sum(B.mul(dln2, xhat2), axis=0)
+    G["be2"] = B.sum(dln2, axis=0)
+    dx3 = B.add(dy2, B.layer_norm_grad(dln2, x3, P["g2"], mu2, rs2))
+    G["Wo"] = B.matmul(ctx, dx3, trans_a=True)
+    G["bo"] = B.sum(dx3, axis=0)
+    dctx = split(B.matmul(dx3, P["Wo"], trans_b=True))
+    dprob = B.matmul(dctx, vh, trans_b=True)
+    dvv = merge(B.matmul(prob, dctx, trans_a=True))
+    dscore = B.softmax_grad(dprob, prob)
+    dqs = merge(B.matmul(dscore, kh))
+    dkk = merge(B.matmul(dscore, qh, trans_a=True))
+    G["Wq"] = B.mul(B.matmul(ln1, dqs, trans_a=True), scale)
+    G["bq"] = B.mul(B.sum(dqs, axis=0), scale)
+    G["Wk"] = B.matmul(ln1, dkk, trans_a=True)
+    G["bk"] = B.sum(dkk, axis=0)
+    G["Wv"] = B.matmul(ln1, dvv, trans_a=True)
+    G["bv"] = B.sum(dvv, axis=0)
+    dln1 = B.mul(B.matmul(dqs, P["Wq"], trans_b=True), scale)
+    dln1 = B.add(B.matmul(dkk, P["Wk"], trans_b=True), dln1)
+    dln1 = B.add(B.matmul(dvv, P["Wv"], trans_b=True), dln1)
+    xhat1 = B.mul(B.sub(x2, B.reshape(mu1, (n, 1))), B.reshape(rs1, (n, 1)))
+    G["g1"] = B.sum(B.mul(dln1, xhat1), axis=0)
+    G["be1"] = B.sum(dln1, axis=0)
+    dx = B.add(dx3, B.layer_norm_grad(dln1, x2, P["g1"], mu1, rs1))
+
+    # ---- Adam: moments fp32, parameters bf16 (update in fp32, then rounded)
+    for name in C3_WEIGHTS + C3_VECTORS:
+        g, p, m, v = G[name], P[name], M[name], V[name]
+        m_new = B.add(B.mul(m, beta1), g, alpha=1.0 - beta1)
+        v_new = B.add(B.mul(v, beta2), B.square(g), alpha=1.0 - beta2)
+        mhat = B.div(m_new, 1.0 - beta1 ** t)
+        vhat = B.div(v_new, 1.0 - beta2 ** t)
+        p_new = B.cast(B.sub(p, B.div(B.mul(mhat, lr), B.add(B.sqrt(vhat), eps))), "bf16")
+        B.assign(p, p_new)
+        B.assign(m, m_new)
+        B.assign(v, v_new)
+    return y, dx

@@ -5,7 +5,7 @@ A "step" is one pass of the whole hot path over one batch of synthetic input: re
 through the C ABI, barrier (cut, hash, cache lookup, lowering on a miss, kernel launches), block
 until the device is done.  Inputs are resident in HBM before the timed region starts.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4|c1|c2|c5]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4|c1|c2|c3|c5]
 
 Prints ONE JSON line: barrier-steps/s for the workload, the roofline of its dominant kernel
 (duration measured with HIP events on the library's stream inside the timed steps) and the CPU
@@ -230,7 +230,64 @@ def run_c5(steps, warmup):
     return dt, "f32", config, roof, extra, None
 
 
-WORKLOADS = {"c1": run_c1, "c2": run_c2, "c4": run_c4, "c5": run_c5}
+def run_c3(steps, warmup, bsz=32, seq=256, d=1024, ffn=4096, heads=16):
+    from workloads import programs
+    from workloads.inputs import c3_inputs
+    import torch
+    ctx = _gpu_ctx(8 << 30)
+    keys = programs.C3_WEIGHTS + programs.C3_VECTORS
+
+    def setup(B, mk, batch):
+        inp = c3_inputs(batch, seq, d, ffn)
+        bf = lambda a: torch.from_numpy(a).to(torch.bfloat16).to(torch.float32).numpy()   # round to nearest even
+        P = {k: mk(bf(inp[k]), "bf16", True) for k in keys}
+        M = {k: mk(np.zeros_like(inp[k]), "f32", True) for k in keys}
+        V = {k: mk(np.zeros_like(inp[k]), "f32", True) for k in keys}
+        return mk(bf(inp["x"]), "bf16", False), mk(bf(inp["dy"]), "bf16", False), P, M, V, heads
+    g = setup(ctx, lambda a, dt, don: ctx.tensor(a, dtype=dt, donatable=don), bsz)
+    state = {"t": 0}
+
+    def step():
+        state["t"] += 1
+        programs.c3_step(ctx, *g, t=state["t"])
+        return ctx.barrier(True)
+    dt, dt_prof, launches, infos = _time_steps(step, ctx, steps, warmup)
+    _, _, _, _, _, table = _dominant(launches)
+    n = len(launches)
+    gemm = [r for st in launches for r in st if r["flops"]]
+    rest = [r for st in launches for r in st if not r["flops"]]
+    big = [r for r in gemm if r["flops"] >= 2 * bsz * seq * d * d]           # the projection / FFN GEMMs
+    att = [r for r in gemm if r["flops"] < 2 * bsz * seq * d * d]           # per-head score / context GEMMs
+    tf = lambda rs: sum(r["flops"] for r in rs) / (sum(r["ms"] for r in rs) * 1e-3) / 1e12 if rs else None
+    gb = lambda rs: sum(r["bytes"] for r in rs) / (sum(r["ms"] for r in rs) * 1e-3) / 1e9 if rs else None
+    roof = {"bound": "mfma", "kernel": "lt_gemm_kernel", "achieved": tf(gemm), "peak": MFMA_PEAK_TFLOPS["bf16"],
+            "unit": "TFLOP/s", "traffic": None, "gemm_ms_per_step": sum(r["ms"] for r in gemm) / n,
+            "flops_per_step": sum(r["flops"] for r in gemm) / n}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    extra = {"projection_ffn_gemm_TFLOPs": tf(big), "attention_gemm_TFLOPs": tf(att),
+             "non_gemm_ms_per_step": sum(r["ms"] for r in rest) / n, "non_gemm_GBps": gb(rest),
+             "non_gemm_bytes_per_step": sum(r["bytes"] for r in rest) / n,
+             "device_ms_per_step": sum(r["ms"] for st in launches for r in st) / n,
+             "launches_per_step": len(launches[-1]), "kernels": table,
+             "cache_hits": sum(i.cache_hit for i in infos),
+             "ns_host_per_step": {"collect": int(np.mean([i.ns_collect for i in infos])),
+                                  "hash": int(np.mean([i.ns_hash for i in infos])),
+                                  "launch": int(np.mean([i.ns_launch for i in infos]))}}
+    config = {"workload": f"c3: transformer encoder layer fwd+bwd+Adam, bf16, batch {bsz} seq {seq} d_model {d} "
+                          f"heads {heads} ffn {ffn}, one barrier per step", "regions": int(infos[-1].n_regions)}
+
+    def cpu(sample_batch=2):
+        from oracle.numeric import Eager
+        E = Eager()
+        r = setup(E, lambda a, dt, don: E.tensor(a, dtype=dt), sample_batch)
+        t0 = time.perf_counter()
+        programs.c3_step(E, *r, t=1)
+        el = time.perf_counter() - t0
+        return 1.0 / (el * bsz / sample_batch), f"1 oracle step at batch {sample_batch}, scaled linearly to batch {bsz}"
+    return dt, "bf16", config, roof, extra, cpu
+
+
+WORKLOADS = {"c1": run_c1, "c2": run_c2, "c3": run_c3, "c4": run_c4, "c5": run_c5}
 
 
 def main():
@@ -248,7 +305,7 @@ def main():
         print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
               "(the path shards by parameter range / batch, see DESIGN.md)", file=sys.stderr)
         sys.exit(2)
-    defaults = {"c4": (20, 3), "c1": (200, 10), "c2": (200, 10), "c5": (100, 10)}
+    defaults = {"c4": (20, 3), "c1": (200, 10), "c2": (200, 10), "c3": (10, 2), "c5": (100, 10)}
     steps = args.steps if args.steps is not None else defaults[args.workload][0]
     warmup = args.warmup if args.warmup is not None else defaults[args.workload][1]
     if args.copy_calibration:

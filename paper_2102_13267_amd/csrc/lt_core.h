@@ -169,7 +169,7 @@ struct lt_ctx {
 
 namespace lt {
 
-constexpr size_t kPartialFloats = 1 << 16;   // reduction partials
+constexpr size_t kPartialFloats = 1 << 20;   // reduction partials (4 MiB of the workspace)
 constexpr size_t kTickets = 1024;
 
 lt_status fail(lt_ctx* ctx, lt_status code, const std::string& msg);

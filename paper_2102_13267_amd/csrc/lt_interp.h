@@ -29,10 +29,11 @@
 namespace ltk {
 
 template <int NS> struct SlotVec;
+template <> struct SlotVec<8> { typedef float type __attribute__((ext_vector_type(8))); };
 template <> struct SlotVec<16> { typedef float type __attribute__((ext_vector_type(16))); };
 template <> struct SlotVec<32> { typedef float type __attribute__((ext_vector_type(32))); };
 
-// Register file of NS value slots (16 or 32) x kVec element lanes.
+// Register file of NS value slots (8, 16 or 32) x kVec element lanes.
 template <int NS> struct RF {
   typedef typename SlotVec<NS>::type vec;
   vec e[kVec];
@@ -101,6 +102,10 @@ __device__ __forceinline__ float scal_at(const ProgRegs& pr, uint32_t idx) {
     __builtin_amdgcn_sched_barrier(0);                              \
   }
 
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Wuninitialized"
+#pragma clang diagnostic ignored "-Wsometimes-uninitialized"
+#pragma clang diagnostic ignored "-Wconditional-uninitialized"
 template <int NS>
 __device__ __forceinline__ RF<NS> interp(RF<NS> f, const ProgRegs pr, const uint32_t n) {
   typename RF<NS>::vec r[kVec];
@@ -110,7 +115,7 @@ __device__ __forceinline__ RF<NS> interp(RF<NS> f, const ProgRegs pr, const uint
     const uint32_t w = (uint32_t)__builtin_amdgcn_readlane((int)pr.code, (int)pc);
     const uint32_t op = w & 0xffu, d = (w >> 8) & 31u;
     const uint32_t ia = (w >> 13) & 63u, ib = (w >> 19) & 63u, ic = (w >> 25) & 63u;
-    Quad A, B = splat(0.0f), q;
+    Quad A, B, q;   // B stays undefined for unary ops, which never read it
     // operand a is always a slot: the lowering puts a scalar operand second (using the
     // reversed form of non-commutative ops) or materialises it with kSplat first
 #pragma unroll
@@ -173,6 +178,7 @@ __device__ __forceinline__ RF<NS> interp(RF<NS> f, const ProgRegs pr, const uint
   for (int v = 0; v < kVec; ++v) o.e[v] = r[v];
   return o;
 }
+#pragma clang diagnostic pop
 
 // ---- loads -------------------------------------------------------------------------------
 
@@ -419,12 +425,92 @@ __device__ __forceinline__ void store_outputs(RF<NS> f, const EwProg& p, uint64_
   }
 }
 
+// ---- streaming stage for reductions ---------------------------------------------------------
+// A reduction has few inputs, so memory-level parallelism must come from fetching U 4-vectors per
+// lane before any is used.  Unrolling the interpreter U times would multiply its code (and miss
+// the instruction cache), so the U raw vectors of an input are kept in ONE wide register tuple
+// and the interpreter runs in a rolled loop that picks vector u with a wave-uniform index
+// (relative register addressing again).  Only for programs whose NIN inputs are all read in
+// full, 4 elements at a time, and share one element type (BF: bf16, else fp32).
+template <int N> struct WideVec { typedef float type __attribute__((ext_vector_type(N))); };
+
+template <int NIN, int U, bool BF> struct Stream {
+  typedef typename WideVec<(BF ? 2 : 4) * U>::type vec;
+  vec s[NIN];
+};
+
+// fetch vector number u (a compile-time constant after unrolling) of every input
+template <int NIN, int U, bool BF>
+__device__ __forceinline__ void stream_fetch(Stream<NIN, U, BF>& st, const int u, const EwProg& p, uint64_t base, uint32_t lane) {
+#pragma unroll
+  for (int k = 0; k < NIN; ++k) {
+    if (BF) {
+      const uint2 t = *(const uint2*)((const char*)p.in[k].ptr + base * 2u + (size_t)lane * 2u);
+      st.s[k][2 * u] = __uint_as_float(t.x);
+      st.s[k][2 * u + 1] = __uint_as_float(t.y);
+    } else {
+      const RawVec t = *(const RawVec*)((const char*)p.in[k].ptr + base * 4u + (size_t)lane * 4u);
+      st.s[k][4 * u] = t.x; st.s[k][4 * u + 1] = t.y; st.s[k][4 * u + 2] = t.z; st.s[k][4 * u + 3] = t.w;
+    }
+  }
+}
+
+// vector u (compile-time) of input k, converted
+template <int NIN, int U, bool BF>
+__device__ __forceinline__ Quad stream_quad(const Stream<NIN, U, BF>& st, const int k, const int u) {
+  Quad q;
+  if (BF) {
+    const uint32_t x = __float_as_uint(st.s[k][2 * u]), y = __float_as_uint(st.s[k][2 * u + 1]);
+    q.v[0] = __uint_as_float(x << 16);
+    q.v[1] = __uint_as_float(x & 0xffff0000u);
+    q.v[2] = __uint_as_float(y << 16);
+    q.v[3] = __uint_as_float(y & 0xffff0000u);
+  } else {
+    q.v[0] = st.s[k][4 * u]; q.v[1] = st.s[k][4 * u + 1]; q.v[2] = st.s[k][4 * u + 2]; q.v[3] = st.s[k][4 * u + 3];
+  }
+  return q;
+}
+
+// move vector u (run-time, wave-uniform) of every input into slots 0 .. NIN-1
+template <int NS, int NIN, int U, bool BF>
+__device__ __forceinline__ RF<NS> stream_place(RF<NS> f, const Stream<NIN, U, BF> st, const uint32_t u) {
+#pragma unroll
+  for (int k = 0; k < NIN; ++k) {
+    const typename Stream<NIN, U, BF>::vec t = st.s[k];
+    Quad q;
+    if (BF) {
+      const uint32_t x = __float_as_uint(t[2 * u]), y = __float_as_uint(t[2 * u + 1]);
+      q.v[0] = __uint_as_float(x << 16);
+      q.v[1] = __uint_as_float(x & 0xffff0000u);
+      q.v[2] = __uint_as_float(y << 16);
+      q.v[3] = __uint_as_float(y & 0xffff0000u);
+    } else {
+      q.v[0] = t[4 * u]; q.v[1] = t[4 * u + 1]; q.v[2] = t[4 * u + 2]; q.v[3] = t[4 * u + 3];
+    }
+#pragma unroll
+    for (int v = 0; v < kVec; ++v) f.e[v][k] = q.v[v];
+  }
+  return f;
+}
+
+// Host side: can this program be streamed, and with which element type?  0 = no, 1 = fp32, 2 = bf16.
+inline int stream_kind(const EwProg& p) {
+  if (!p.fast || p.n_in == 0u) return 0;
+  for (uint32_t k = 0; k < p.n_in; ++k)
+    if (p.in[k].mode != kFull || p.in[k].fetch != kFetchVec4 || p.in[k].dtype != p.in[0].dtype) return 0;
+  return p.in[0].dtype == kF32 ? 1 : p.in[0].dtype == kBF16 ? 2 : 0;
+}
+
+// A fresh register file.  Its contents are deliberately left undefined: a valid program writes
+// every slot before reading it (the host checks), and clearing NS x 4 registers per 4-vector is
+// a measurable share of a short program's instructions.
 template <int NS>
 __device__ __forceinline__ RF<NS> rf_zero() {
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Wuninitialized"
   RF<NS> f;
-#pragma unroll
-  for (int v = 0; v < kVec; ++v) f.e[v] = 0.0f;
   return f;
+#pragma clang diagnostic pop
 }
 
 }  // namespace ltk

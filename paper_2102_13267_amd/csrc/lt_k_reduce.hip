@@ -48,10 +48,9 @@ __global__ __launch_bounds__(kBlock) void lt_row_reduce_kernel(const RowArgs a) 
   }
 }
 
-// Global reduction in one launch.  U independent 4-vectors per lane and loop trip: all their
-// loads are issued before the first is interpreted (a reduction has few inputs, so memory-level
-// parallelism has to come from unrolling).
-template <int MAXIN, int U, bool FAST, bool F32>
+// Global reduction in one launch.  NIN > 0: streamed (U 4-vectors per lane and trip fetched
+// together, a workgroup reading U consecutive tiles); NIN == 0: general path.
+template <int NS, int NIN, int U, bool BF>
 __global__ __launch_bounds__(kBlock) void lt_all_reduce_kernel(const AllArgs a) {
   __shared__ float lds[kBlock / 64];
   __shared__ uint32_t is_last;
@@ -61,34 +60,42 @@ __global__ __launch_bounds__(kBlock) void lt_all_reduce_kernel(const AllArgs a) 
   const uint64_t n = pro.n;
   const uint64_t nvec = (n + kVec - 1) / kVec;
   float acc = red_identity(a.red);
-  const uint64_t stride = (uint64_t)gridDim.x * kBlock;
-  const uint64_t full_trips = FAST ? nvec / (stride * U) : 0;     // every lane has U whole vectors
-  uint64_t v = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-  for (uint64_t t = 0; t < full_trips; ++t) {
-    Staged<MAXIN> st[U];
+  uint64_t tail_from = 0;   // first 4-vector the general loop below has to cover
+  if (NIN > 0) {
+    // a trip of the grid covers gridDim.x * U tiles of kBlock vectors; workgroup b takes tiles
+    // b*U .. b*U+U-1 of each trip, i.e. U * 4 KiB (fp32) of consecutive memory
+    constexpr int UU = NIN > 0 ? U : 1, NN = NIN > 0 ? NIN : 1;
+    const uint64_t per_trip = (uint64_t)gridDim.x * UU * kBlock;
+    const uint64_t trips = nvec / per_trip;
+    for (uint64_t t = 0; t < trips; ++t) {
+      const uint64_t v0 = t * per_trip + (uint64_t)blockIdx.x * UU * kBlock;   // wave-uniform
+      Stream<NN, UU, BF> st;
 #pragma unroll
-    for (int u = 0; u < U; ++u)
-      st[u] = fetch_inputs<MAXIN, FAST, F32, false>(pro, 0, (uint32_t)((v + (uint64_t)u * stride) * kVec), kVec);
+      for (int u = 0; u < UU; ++u) stream_fetch<NN, UU, BF>(st, u, pro, (v0 + (uint64_t)u * kBlock) * kVec, threadIdx.x * kVec);
+      if (NN == 1 && pro_n == 0u) {   // the operand itself is reduced: nothing to interpret
 #pragma unroll
-    for (int u = 0; u < U; ++u) pin_staged<MAXIN>(st[u]);
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      RF<16> f = place_inputs<16, MAXIN, FAST, F32>(rf_zero<16>(), pro, st[u], kVec);
-      f = interp<16>(f, pro_regs, pro_n);
-      acc = fold_vec(a.red, acc, rf_get(f, pro.anchor_slot), kVec);
+        for (int u = 0; u < UU; ++u) acc = fold_vec(a.red, acc, stream_quad<NN, UU, BF>(st, 0, u), kVec);
+      } else {
+#pragma unroll 1
+        for (uint32_t u = 0; u < (uint32_t)UU; ++u) {
+          RF<NS> f = stream_place<NS, NN, UU, BF>(rf_zero<NS>(), st, u);
+          f = interp<NS>(f, pro_regs, pro_n);
+          acc = fold_vec(a.red, acc, rf_get(f, pro.anchor_slot), kVec);
+        }
+      }
     }
-    v += stride * U;
+    tail_from = trips * per_trip;
   }
-  for (; v < nvec; v += stride) {
+  for (uint64_t v = tail_from + (uint64_t)blockIdx.x * kBlock + threadIdx.x; v < nvec; v += (uint64_t)gridDim.x * kBlock) {
     const uint64_t i = v * kVec;
     const uint32_t nvalid = (n - i >= (uint64_t)kVec) ? (uint32_t)kVec : (uint32_t)(n - i);
-    RF<16> f = load_inputs<16, MAXIN, false, false>(rf_zero<16>(), pro, 0, (uint32_t)i, nvalid);
-    f = interp<16>(f, pro_regs, pro_n);
+    RF<NS> f = load_inputs<NS, kMaxIn, false, false>(rf_zero<NS>(), pro, 0, (uint32_t)i, nvalid);
+    f = interp<NS>(f, pro_regs, pro_n);
     acc = fold_vec(a.red, acc, rf_get(f, pro.anchor_slot), nvalid);
   }
   float r = block_reduce(a.red, acc, lds);
   if (threadIdx.x == 0) {
-    __hip_atomic_store(&a.partials[blockIdx.x], r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    a.partials[blockIdx.x] = r;   // published by the fence, read by the last workgroup behind its own fence
     __threadfence();
     uint32_t t = atomicAdd(a.ticket, 1u);
     is_last = (t == gridDim.x - 1) ? 1u : 0u;
@@ -98,8 +105,7 @@ __global__ __launch_bounds__(kBlock) void lt_all_reduce_kernel(const AllArgs a) 
   __threadfence();
   // the last workgroup combines the partials in a fixed order (deterministic for a given grid)
   acc = red_identity(a.red);
-  for (uint32_t g = threadIdx.x; g < gridDim.x; g += kBlock)
-    acc = red_combine(a.red, acc, __hip_atomic_load(&a.partials[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+  for (uint32_t g = threadIdx.x; g < gridDim.x; g += kBlock) acc = red_combine(a.red, acc, a.partials[g]);
   r = block_reduce(a.red, acc, lds);
   if (a.red == kRedMean) r = r / (float)a.count;
   if (threadIdx.x == 0) *a.ticket = 0u;
@@ -113,71 +119,141 @@ __global__ __launch_bounds__(kBlock) void lt_all_reduce_kernel(const AllArgs a) 
   }
 }
 
+constexpr int kColBlock = 512;
+
 // Column reduction over axis 0 of [rows, cols].  blockIdx.x: strip of 256 columns (64 lanes x 4);
-// the four waves of a workgroup take interleaved rows; blockIdx.y: slab of rows.
-__global__ __launch_bounds__(kBlock) void lt_col_reduce_kernel(const ColArgs a) {
-  __shared__ float4 lds[kBlock];
+// the eight waves of a workgroup take interleaved rows; blockIdx.y: slab of rows.  A lane owns four
+// columns, so nothing crosses lanes until the waves meet in LDS.  FAST (whole aligned 4-vectors,
+// no strided input): U rows per wave are fetched together before any is interpreted.
+__device__ __forceinline__ void col_fold(uint32_t red, float4& acc, const Quad& q) {
+  acc.x = red_combine(red, acc.x, q.v[0]);
+  acc.y = red_combine(red, acc.y, q.v[1]);
+  acc.z = red_combine(red, acc.z, q.v[2]);
+  acc.w = red_combine(red, acc.w, q.v[3]);
+}
+
+template <int NS, int NIN, int U, bool BF>
+__global__ __launch_bounds__(kColBlock) void lt_col_reduce_kernel(const ColArgs a) {
+  constexpr uint32_t kWaves = kColBlock / 64;
+  __shared__ float4 lds[kColBlock];
   __shared__ uint32_t is_last;
   const EwProg& pro = a.pro;
   const ProgRegs pro_regs = load_prog_regs(a.pro), post_regs = load_prog_regs(a.post);
   const uint32_t pro_n = a.pro.n_code;
-  const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t c = blockIdx.x * 256u + lane * kVec;
   const uint32_t nvalid = c >= a.cols ? 0u : ((a.cols - c >= (uint32_t)kVec) ? (uint32_t)kVec : a.cols - c);
   const uint32_t rows_per_slab = (a.rows + gridDim.y - 1) / gridDim.y;
-  const uint32_t r0 = blockIdx.y * rows_per_slab;
+  const uint32_t r0 = min(a.rows, blockIdx.y * rows_per_slab);
   const uint32_t r1 = min(a.rows, r0 + rows_per_slab);
   const float id = red_identity(a.red);
+  const uint32_t pstride = (a.cols + 3u) & ~3u;   // floats between slabs of partials
   float4 acc = make_float4(id, id, id, id);
   if (nvalid) {
-    for (uint32_t r = r0 + wave; r < r1; r += kBlock / 64) {
-      const uint32_t i = r * a.cols + c;
-      RF<16> f = load_inputs<16>(rf_zero<16>(), pro, 0, i, nvalid);
-      f = interp<16>(f, pro_regs, pro_n);
-      const Quad q = rf_get(f, pro.anchor_slot);
-      acc.x = red_combine(a.red, acc.x, q.v[0]);
-      acc.y = red_combine(a.red, acc.y, q.v[1]);
-      acc.z = red_combine(a.red, acc.z, q.v[2]);
-      acc.w = red_combine(a.red, acc.w, q.v[3]);
+    uint32_t r = r0 + wave;
+    if (NIN > 0) {   // streamed: cols is a multiple of 4, so this lane's vector is whole
+      constexpr int UU = NIN > 0 ? U : 1, NN = NIN > 0 ? NIN : 1;
+      for (; r + (UU - 1) * kWaves < r1; r += UU * kWaves) {
+        Stream<NN, UU, BF> st;
+#pragma unroll
+        for (int u = 0; u < UU; ++u)
+          stream_fetch<NN, UU, BF>(st, u, pro, (uint64_t)(r + u * kWaves) * a.cols + blockIdx.x * 256u, lane * kVec);
+        if (NN == 1 && pro_n == 0u) {   // the operand itself is reduced: nothing to interpret
+#pragma unroll
+          for (int u = 0; u < UU; ++u) col_fold(a.red, acc, stream_quad<NN, UU, BF>(st, 0, u));
+        } else {
+#pragma unroll 1
+          for (uint32_t u = 0; u < (uint32_t)UU; ++u) {
+            RF<NS> f = stream_place<NS, NN, UU, BF>(rf_zero<NS>(), st, u);
+            f = interp<NS>(f, pro_regs, pro_n);
+            col_fold(a.red, acc, rf_get(f, pro.anchor_slot));
+          }
+        }
+      }
+    }
+    for (; r < r1; r += kWaves) {
+      RF<NS> f = load_inputs<NS, kMaxIn, false, false>(rf_zero<NS>(), pro, (uint64_t)r * a.cols + blockIdx.x * 256u, lane * kVec, nvalid);
+      f = interp<NS>(f, pro_regs, pro_n);
+      col_fold(a.red, acc, rf_get(f, pro.anchor_slot));
     }
   }
   lds[threadIdx.x] = acc;
   __syncthreads();
   if (wave == 0) {
 #pragma unroll
-    for (int w = 1; w < kBlock / 64; ++w) {
-      float4 o = lds[w * 64 + lane];
+    for (int w = 1; w < (int)kWaves; ++w) {
+      const float4 o = lds[w * 64 + lane];
       acc.x = red_combine(a.red, acc.x, o.x);
       acc.y = red_combine(a.red, acc.y, o.y);
       acc.z = red_combine(a.red, acc.z, o.z);
       acc.w = red_combine(a.red, acc.w, o.w);
     }
-    if (nvalid) {
-      float* dst = a.partials + (uint64_t)blockIdx.y * a.cols + c;
-      if (nvalid > 0u) __hip_atomic_store(dst + 0, acc.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (nvalid > 1u) __hip_atomic_store(dst + 1, acc.y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (nvalid > 2u) __hip_atomic_store(dst + 2, acc.z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (nvalid > 3u) __hip_atomic_store(dst + 3, acc.w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // plain stores: the fence below publishes them before the ticket is taken, and the last
+    // workgroup's fence after its ticket makes them visible to its plain loads.  The slab stride
+    // is padded to a multiple of four floats so that whole vectors stay 16-byte aligned.
+    if (nvalid == (uint32_t)kVec) {
+      *(float4*)(a.partials + (uint64_t)blockIdx.y * pstride + c) = acc;
+    } else if (nvalid) {
+      float* dst = a.partials + (uint64_t)blockIdx.y * pstride + c;
+      dst[0] = acc.x;
+      if (nvalid > 1u) dst[1] = acc.y;
+      if (nvalid > 2u) dst[2] = acc.z;
     }
-  }
-  __threadfence();
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t t = atomicAdd(&a.tickets[blockIdx.x], 1u);
-    is_last = (t == gridDim.y - 1) ? 1u : 0u;
+    // only this wave wrote partials, so only it pays for the release fence (a write-back of the
+    // whole L2: far too expensive to run once per wave)
+    __threadfence();
+    if (lane == 0) {
+      uint32_t t = atomicAdd(&a.tickets[blockIdx.x], 1u);
+      is_last = (t == gridDim.y - 1) ? 1u : 0u;
+    }
   }
   __syncthreads();
   if (!is_last) return;
   __threadfence();
   if (threadIdx.x == 0) a.tickets[blockIdx.x] = 0u;
-  if (wave != 0 || !nvalid) return;
+  // the last workgroup of a strip combines the slabs: each wave a contiguous share, eight loads in
+  // flight, fixed order (deterministic for a given grid)
   acc = make_float4(id, id, id, id);
-  for (uint32_t s = 0; s < gridDim.y; ++s) {
-    const float* src = a.partials + (uint64_t)s * a.cols + c;
-    if (nvalid > 0u) acc.x = red_combine(a.red, acc.x, __hip_atomic_load(src + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    if (nvalid > 1u) acc.y = red_combine(a.red, acc.y, __hip_atomic_load(src + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    if (nvalid > 2u) acc.z = red_combine(a.red, acc.z, __hip_atomic_load(src + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    if (nvalid > 3u) acc.w = red_combine(a.red, acc.w, __hip_atomic_load(src + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+  if (nvalid) {
+    const uint32_t per_wave = (gridDim.y + kWaves - 1) / kWaves;
+    const uint32_t s0 = min(gridDim.y, wave * per_wave), s1 = min(gridDim.y, s0 + per_wave);
+    for (uint32_t sb = s0; sb < s1; sb += 8) {
+      float4 t[8];
+#pragma unroll
+      for (uint32_t j = 0; j < 8; ++j) {
+        t[j] = make_float4(id, id, id, id);
+        if (sb + j < s1) {
+          const float* src = a.partials + (uint64_t)(sb + j) * pstride + c;
+          if (nvalid == (uint32_t)kVec) {
+            t[j] = *(const float4*)src;
+          } else {
+            t[j].x = src[0];
+            if (nvalid > 1u) t[j].y = src[1];
+            if (nvalid > 2u) t[j].z = src[2];
+          }
+        }
+      }
+#pragma unroll
+      for (uint32_t j = 0; j < 8; ++j) {
+        acc.x = red_combine(a.red, acc.x, t[j].x);
+        acc.y = red_combine(a.red, acc.y, t[j].y);
+        acc.z = red_combine(a.red, acc.z, t[j].z);
+        acc.w = red_combine(a.red, acc.w, t[j].w);
+      }
+    }
+  }
+  __syncthreads();   // every wave has read its slot of the first exchange
+  lds[threadIdx.x] = acc;
+  __syncthreads();
+  if (wave != 0 || !nvalid) return;
+#pragma unroll
+  for (int w = 1; w < (int)kWaves; ++w) {
+    const float4 o = lds[w * 64 + lane];
+    acc.x = red_combine(a.red, acc.x, o.x);
+    acc.y = red_combine(a.red, acc.y, o.y);
+    acc.z = red_combine(a.red, acc.z, o.z);
+    acc.w = red_combine(a.red, acc.w, o.w);
   }
   if (a.red == kRedMean) {
     const float inv = 1.0f / (float)a.rows;
@@ -194,14 +270,25 @@ hipError_t launch_row_reduce(const RowArgs& a, uint32_t grid, hipStream_t s) {
   return hipGetLastError();
 }
 hipError_t launch_all_reduce(const AllArgs& a, uint32_t grid, hipStream_t s) {
-  if (a.pro.fast && a.pro.all_f32 && a.pro.n_in <= 2u)
-    hipLaunchKernelGGL((lt_all_reduce_kernel<2, 4, true, true>), dim3(grid), dim3(kBlock), 0, s, a);
-  else
-    hipLaunchKernelGGL((lt_all_reduce_kernel<8, 1, false, false>), dim3(grid), dim3(kBlock), 0, s, a);
+  const dim3 g(grid), b(kBlock);
+  const int kind = stream_kind(a.pro);
+  const uint32_t n_in = a.pro.n_in;
+  if (kind == 1 && n_in == 1u) hipLaunchKernelGGL((lt_all_reduce_kernel<16, 1, 8, false>), g, b, 0, s, a);
+  else if (kind == 1 && n_in == 2u) hipLaunchKernelGGL((lt_all_reduce_kernel<16, 2, 4, false>), g, b, 0, s, a);
+  else if (kind == 2 && n_in == 1u) hipLaunchKernelGGL((lt_all_reduce_kernel<16, 1, 8, true>), g, b, 0, s, a);
+  else if (kind == 2 && n_in == 2u) hipLaunchKernelGGL((lt_all_reduce_kernel<16, 2, 8, true>), g, b, 0, s, a);
+  else hipLaunchKernelGGL((lt_all_reduce_kernel<16, 0, 1, false>), g, b, 0, s, a);
   return hipGetLastError();
 }
 hipError_t launch_col_reduce(const ColArgs& a, uint32_t grid_x, uint32_t grid_y, hipStream_t s) {
-  hipLaunchKernelGGL(lt_col_reduce_kernel, dim3(grid_x, grid_y), dim3(kBlock), 0, s, a);
+  const dim3 g(grid_x, grid_y), b(kColBlock);
+  const int kind = (a.cols % 4u) == 0u ? stream_kind(a.pro) : 0;
+  const uint32_t n_in = a.pro.n_in;
+  if (kind == 1 && n_in == 1u) hipLaunchKernelGGL((lt_col_reduce_kernel<16, 1, 8, false>), g, b, 0, s, a);
+  else if (kind == 1 && n_in == 2u) hipLaunchKernelGGL((lt_col_reduce_kernel<16, 2, 4, false>), g, b, 0, s, a);
+  else if (kind == 2 && n_in == 1u) hipLaunchKernelGGL((lt_col_reduce_kernel<16, 1, 8, true>), g, b, 0, s, a);
+  else if (kind == 2 && n_in == 2u) hipLaunchKernelGGL((lt_col_reduce_kernel<16, 2, 8, true>), g, b, 0, s, a);
+  else hipLaunchKernelGGL((lt_col_reduce_kernel<16, 0, 1, false>), g, b, 0, s, a);
   return hipGetLastError();
 }
 

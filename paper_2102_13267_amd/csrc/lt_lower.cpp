@@ -1130,7 +1130,7 @@ struct Lowering {
       args.red = red;
       args.count = (uint64_t)count(in_shape);
       Launch l = make_launch(L_ALL, k, args);
-      l.grid_x = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>((args.count + 4095) / 4096, 256 * 8));
+      l.grid_x = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>((args.count + 4095) / 4096, 256 * 2));
       l.bytes = pro.bytes + post.bytes;
       plan->launches.push_back(std::move(l));
       add_prog_patches(launch, offsetof(ltk::AllArgs, pro), pro);
@@ -1146,10 +1146,11 @@ struct Lowering {
       Launch l = make_launch(L_COL, k, args);
       l.grid_x = (args.cols + 255) / 256;
       if (l.grid_x > kTickets) return bad(LT_ERR_UNSUPPORTED, "axis-0 reduction wider than 262144 columns");
-      uint32_t gy = std::max<uint32_t>(1, std::min<uint32_t>(args.rows / 16, 64));
-      while (gy > 1 && (uint64_t)gy * args.cols > kPartialFloats) gy /= 2;
-      if ((uint64_t)gy * args.cols > kPartialFloats) return bad(LT_ERR_UNSUPPORTED, "axis-0 reduction wider than 65536 columns");
-      while (gy > 1 && (uint64_t)gy * l.grid_x > 256 * 8) gy /= 2;
+      // a slab of 64 rows gives each of a workgroup's 8 waves one 8-row trip
+      uint32_t gy = std::max<uint32_t>(1, std::min<uint32_t>(args.rows / 64, 64));
+      while (gy > 1 && (uint64_t)gy * (args.cols + 3) > kPartialFloats) gy /= 2;
+      if ((uint64_t)gy * (args.cols + 3) > kPartialFloats) return bad(LT_ERR_UNSUPPORTED, "axis-0 reduction wider than 1048576 columns");
+      while (gy > 1 && (uint64_t)gy * l.grid_x > 256) gy /= 2;
       l.grid_y = gy;
       l.bytes = pro.bytes + post.bytes;
       plan->launches.push_back(std::move(l));
@@ -1217,7 +1218,7 @@ struct Lowering {
     const std::vector<int64_t> xs = out_shape(rins[a][an->op == LT_OP_LAYER_NORM_GRAD ? 1 : 0]);
     args.cols = (uint32_t)xs.back();
     args.rows = (uint32_t)(count(xs) / std::max<int64_t>(1, xs.back()));
-    args.threads_per_row = args.cols > 1024 ? 256u : 64u;
+    args.threads_per_row = args.cols > 1024 ? 256u : args.cols > 256 ? 64u : 16u;   // a lane holds up to 16 columns
     if (args.cols > args.threads_per_row * 16u) return bad(LT_ERR_UNSUPPORTED, "row operator on rows longer than 4096 elements");
     switch (an->op) {
       case LT_OP_SOFTMAX: args.op = ltk::kSoftmax; break;

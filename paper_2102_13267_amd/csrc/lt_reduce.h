@@ -11,10 +11,32 @@ __device__ __forceinline__ float red_combine(uint32_t red, float x, float y) {
   return x + y;
 }
 
-__device__ __forceinline__ float wave_reduce(uint32_t red, float v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v = red_combine(red, v, __shfl_xor(v, off, 64));
+// One butterfly step inside a row of 16 lanes through the data-parallel-primitive lane crossbar
+// (no LDS traffic).  CTRL: 0xB1 swaps neighbours, 0x4E swaps pairs, 0x141 mirrors each half row
+// (reaches the other quad), 0x140 mirrors the row (reaches the other half).
+template <int CTRL>
+__device__ __forceinline__ float dpp_step(uint32_t red, float v) {
+  const float o = __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xf, 0xf, true));
+  return red_combine(red, v, o);
+}
+
+// Reduction over each aligned group of 16 lanes; every lane of the group gets the result.
+__device__ __forceinline__ float row16_reduce(uint32_t red, float v) {
+  v = dpp_step<0xB1>(red, v);
+  v = dpp_step<0x4E>(red, v);
+  v = dpp_step<0x141>(red, v);
+  v = dpp_step<0x140>(red, v);
   return v;
+}
+
+// Reduction over the 64 lanes of a wavefront; every lane gets the result.  The four row results
+// travel through scalar registers and are combined in a fixed order.
+__device__ __forceinline__ float wave_reduce(uint32_t red, float v) {
+  v = row16_reduce(red, v);
+  const int b = __float_as_int(v);
+  const float r0 = __int_as_float(__builtin_amdgcn_readlane(b, 0)), r1 = __int_as_float(__builtin_amdgcn_readlane(b, 16));
+  const float r2 = __int_as_float(__builtin_amdgcn_readlane(b, 32)), r3 = __int_as_float(__builtin_amdgcn_readlane(b, 48));
+  return red_combine(red, red_combine(red, r0, r1), red_combine(red, r2, r3));
 }
 
 // reduce over the kBlock threads of a workgroup; result valid in every thread

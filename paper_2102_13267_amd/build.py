@@ -16,7 +16,7 @@ OUT = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liblt.so")
 ROCM = os.environ.get("ROCM_PATH", "/opt/rocm")
 
-HIP_SOURCES = ["lt_k_ew.hip", "lt_k_reduce.hip", "lt_k_rowop.hip", "lt_gemm.hip"]
+HIP_SOURCES = ["lt_k_ew.hip", "lt_k_reduce.hip", "lt_k_rowop.hip", "lt_gemm.hip", "lt_gemm_bf16.hip"]
 CPP_SOURCES = ["lt_api.cpp", "lt_barrier.cpp", "lt_lower.cpp"]
 
 # packed-fp32 VALU ops are switched off for all device code (build flags)

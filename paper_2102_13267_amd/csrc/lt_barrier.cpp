@@ -141,6 +141,7 @@ static hipError_t launch_one(const Launch& l, const uint8_t* args, hipStream_t s
     case L_COL: return ltk::launch_col_reduce(*(const ltk::ColArgs*)args, l.grid_x, l.grid_y, s);
     case L_ROWOP: return ltk::launch_row_op(*(const ltk::RowOpArgs*)args, l.grid_x, s);
     case L_GEMM: return ltk::launch_gemm(*(const ltk::GemmArgs*)args, s);
+    case L_SPLITPOST: return ltk::launch_split_post(*(const ltk::SplitPostArgs*)args, l.grid_x, s);
   }
   return hipErrorInvalidValue;
 }
@@ -153,6 +154,7 @@ static const char* kind_name(LaunchKind k) {
     case L_COL: return "lt_col_reduce_kernel";
     case L_ROWOP: return "lt_row_op_kernel";
     case L_GEMM: return "lt_gemm_kernel";
+    case L_SPLITPOST: return "lt_split_post_kernel";
   }
   return "?";
 }

@@ -98,7 +98,7 @@ struct Handle {
 
 // ---- a lowered, cached program ------------------------------------------------------------
 
-enum LaunchKind : uint8_t { L_EW, L_ROW, L_ALL, L_COL, L_ROWOP, L_GEMM };
+enum LaunchKind : uint8_t { L_EW, L_ROW, L_ALL, L_COL, L_ROWOP, L_GEMM, L_SPLITPOST };
 
 struct Storage {
   int param = -1;        // >= 0: the buffer of device parameter `param` (input, or donated output)

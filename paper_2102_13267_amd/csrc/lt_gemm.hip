@@ -13,59 +13,10 @@
 // dimension is not the one the MFMA wants contiguous is transposed on its way into LDS.
 #include <hip/hip_runtime.h>
 
-#include "lt_interp.h"
+#include "lt_gemm_epilogue.h"
 #include "lt_launch.h"
 
 namespace ltk {
-
-constexpr int kGemmThreads = 256;
-constexpr int kCPad = 4;
-
-typedef float v16f __attribute__((ext_vector_type(16)));
-typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
-
-// ---- epilogue ------------------------------------------------------------------------------
-// The accumulators leave the MFMA layout (a lane owns 4-row column segments) through LDS: the
-// tile is written once, then every lane walks it in row-major 4-element quads, so the post
-// program sees flat, contiguous indices exactly like the elementwise kernel does (16-byte loads
-// of residuals, 16-byte stores) and is compiled in only once.
-template <int BM, int BN, int MB, int NB>
-__device__ __forceinline__ void epilogue(const GemmArgs& a, const v16f (&acc)[MB][NB], float* Cs, uint32_t tile_m,
-                                         uint32_t tile_n, uint32_t wave_m, uint32_t wave_n, uint32_t lane, uint32_t batch) {
-  constexpr int kCStride = BN + kCPad;
-  __syncthreads();   // the operand tiles in the same LDS bytes are dead now
-#pragma unroll
-  for (int bm = 0; bm < MB; ++bm)
-#pragma unroll
-    for (int bn = 0; bn < NB; ++bn)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const uint32_t row = wave_m * (MB * 32) + bm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        const uint32_t col = wave_n * (NB * 32) + bn * 32 + (lane & 31);
-        Cs[row * kCStride + col] = acc[bm][bn][r];
-      }
-  __syncthreads();
-  const EwProg& p = a.post;
-  const ProgRegs pr = load_prog_regs(p);
-  const uint32_t n_code = p.n_code;
-  const uint32_t b0 = batch / a.batch1, b1 = batch % a.batch1;
-  const int64_t base = (int64_t)b0 * a.o_b0 + (int64_t)b1 * a.o_b1;
-#pragma unroll 1
-  for (uint32_t q = threadIdx.x; q < (uint32_t)(BM * BN / kVec); q += kGemmThreads) {
-    const uint32_t r = q / (BN / kVec), c = (q % (BN / kVec)) * kVec;
-    const uint32_t row = tile_m + r, col = tile_n + c;
-    if (row >= a.m || col >= a.n) continue;
-    const uint32_t nvalid = a.n - col >= (uint32_t)kVec ? (uint32_t)kVec : a.n - col;
-    const uint32_t i = (uint32_t)(base + (int64_t)row * a.o_row + col);
-    const float4 t = *(const float4*)&Cs[r * kCStride + c];
-    Quad anchor;
-    anchor.v[0] = t.x; anchor.v[1] = t.y; anchor.v[2] = t.z; anchor.v[3] = t.w;
-    RF<16> f = load_inputs<16, kMaxIn, false, false>(rf_zero<16>(), p, 0, i, nvalid);
-    f = rf_set<16>(f, p.anchor_slot, anchor);
-    f = interp<16>(f, pr, n_code);
-    store_outputs<16, false, false>(f, p, 0, i, nvalid);
-  }
-}
 
 // ---- operand staging --------------------------------------------------------------------------
 // A "group" is what one lane fetches with one 16-byte load: G consecutive elements along the
@@ -292,6 +243,7 @@ static void launch_variant(const GemmArgs& a, const dim3 grid, hipStream_t s) {
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   // an operand must have unit stride along one of its two dimensions
   if ((a.a.s_col != 1 && a.a.s_row != 1) || (a.b.s_col != 1 && a.b.s_row != 1)) return hipErrorInvalidValue;
+  if (a.in_dtype == kBF16) return launch_gemm_bf16(a, s);
   const uint32_t batch = a.batch0 * a.batch1;
   // big tiles only when they still give every compute unit work
   const uint64_t big_tiles = (uint64_t)((a.m + 127) / 128) * ((a.n + 127) / 128) * batch;
@@ -299,13 +251,8 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   const uint32_t bm = big ? 128 : 64;
   const dim3 grid((a.n + bm - 1) / bm, (a.m + bm - 1) / bm, batch);
   if (grid.y > 65535u || grid.z > 65535u) return hipErrorInvalidValue;
-  if (a.in_dtype == kBF16) {
-    if (big) launch_variant<uint16_t, 128, 128>(a, grid, s);
-    else launch_variant<uint16_t, 64, 64>(a, grid, s);
-  } else {
-    if (big) launch_variant<float, 128, 128>(a, grid, s);
-    else launch_variant<float, 64, 64>(a, grid, s);
-  }
+  if (big) launch_variant<float, 128, 128>(a, grid, s);
+  else launch_variant<float, 64, 64>(a, grid, s);
   return hipGetLastError();
 }
 

@@ -1,0 +1,79 @@
+// Pieces shared by the contraction kernels: vector types and the interpreted epilogue.
+#ifndef LT_GEMM_EPILOGUE_H_
+#define LT_GEMM_EPILOGUE_H_
+#include <hip/hip_runtime.h>
+
+#include "lt_interp.h"
+
+namespace ltk {
+
+constexpr int kGemmThreads = 256;
+constexpr int kCPad = 4;
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+// ---- epilogue ------------------------------------------------------------------------------
+// The accumulators leave the MFMA layout (a lane owns 4-row column segments) through LDS: the
+// tile is written once, then every lane walks it in row-major 4-element quads, so the post
+// program sees flat, contiguous indices exactly like the elementwise kernel does (16-byte loads
+// of residuals, 16-byte stores) and is compiled in only once.
+template <int BM, int BN, int MB, int NB>
+__device__ __forceinline__ void epilogue(const GemmArgs& a, const v16f (&acc)[MB][NB], float* Cs, uint32_t tile_m,
+                                         uint32_t tile_n, uint32_t wave_m, uint32_t wave_n, uint32_t lane, uint32_t batch) {
+  constexpr int kCStride = BN + kCPad;
+  __syncthreads();   // the operand tiles in the same LDS bytes are dead now
+#pragma unroll
+  for (int bm = 0; bm < MB; ++bm)
+#pragma unroll
+    for (int bn = 0; bn < NB; ++bn)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const uint32_t row = wave_m * (MB * 32) + bm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+        const uint32_t col = wave_n * (NB * 32) + bn * 32 + (lane & 31);
+        Cs[row * kCStride + col] = acc[bm][bn][r];
+      }
+  __syncthreads();
+  const EwProg& p = a.post;
+  const ProgRegs pr = load_prog_regs(p);
+  const uint32_t n_code = p.n_code;
+  const uint32_t b0 = batch / a.batch1, b1 = batch % a.batch1;
+  const int64_t base = (int64_t)b0 * a.o_b0 + (int64_t)b1 * a.o_b1;
+  // Whole tile, whole aligned 4-vectors, at most four inputs and none of them strided: no bounds
+  // checks, no divisions (row and column are known), loads of a quad issued together.
+  if (p.fast && p.full_vec_ok && p.n_in <= 4u && tile_m + BM <= a.m && tile_n + BN <= a.n) {
+    const uint32_t row_flat0 = (b0 * a.batch1 + b1) * a.m + tile_m;   // row number in the flattened [rows, n] output
+#pragma unroll 1
+    for (uint32_t q = threadIdx.x; q < (uint32_t)(BM * BN / kVec); q += kGemmThreads) {
+      const uint32_t r = q / (BN / kVec), c = (q % (BN / kVec)) * kVec;
+      const uint32_t i = (uint32_t)(base + (int64_t)(tile_m + r) * a.o_row + tile_n + c);
+      const Staged<4> st = fetch_inputs_at<4, false>(p, i, row_flat0 + r, tile_n + c);
+      const float4 t = *(const float4*)&Cs[r * kCStride + c];
+      Quad anchor;
+      anchor.v[0] = t.x; anchor.v[1] = t.y; anchor.v[2] = t.z; anchor.v[3] = t.w;
+      RF<16> f = place_inputs<16, 4, true, false>(rf_zero<16>(), p, st, kVec);
+      f = rf_set<16>(f, p.anchor_slot, anchor);
+      f = interp<16>(f, pr, n_code);
+      store_outputs<16, true, false>(f, p, 0, i, kVec);
+    }
+    return;
+  }
+#pragma unroll 1
+  for (uint32_t q = threadIdx.x; q < (uint32_t)(BM * BN / kVec); q += kGemmThreads) {
+    const uint32_t r = q / (BN / kVec), c = (q % (BN / kVec)) * kVec;
+    const uint32_t row = tile_m + r, col = tile_n + c;
+    if (row >= a.m || col >= a.n) continue;
+    const uint32_t nvalid = a.n - col >= (uint32_t)kVec ? (uint32_t)kVec : a.n - col;
+    const uint32_t i = (uint32_t)(base + (int64_t)row * a.o_row + col);
+    const float4 t = *(const float4*)&Cs[r * kCStride + c];
+    Quad anchor;
+    anchor.v[0] = t.x; anchor.v[1] = t.y; anchor.v[2] = t.z; anchor.v[3] = t.w;
+    RF<16> f = load_inputs<16, kMaxIn, false, false>(rf_zero<16>(), p, 0, i, nvalid);
+    f = rf_set<16>(f, p.anchor_slot, anchor);
+    f = interp<16>(f, pr, n_code);
+    store_outputs<16, false, false>(f, p, 0, i, nvalid);
+  }
+}
+
+}  // namespace ltk
+#endif  // LT_GEMM_EPILOGUE_H_

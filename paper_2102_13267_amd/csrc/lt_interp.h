@@ -334,6 +334,28 @@ __device__ __forceinline__ Staged<MAXIN> fetch_inputs(const EwProg& p, uint64_t 
 #pragma clang diagnostic pop
 }
 
+// The same for a caller that already knows the row (i_div) and column (i_mod) of flat element i
+// and promises whole, aligned 4-vectors and no strided input (no division, no slow path).
+template <int MAXIN, bool F32>
+__device__ __forceinline__ Staged<MAXIN> fetch_inputs_at(const EwProg& p, uint32_t i, uint32_t i_div, uint32_t i_mod) {
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Wuninitialized"
+#pragma clang diagnostic ignored "-Wsometimes-uninitialized"
+  Staged<MAXIN> st;
+  const uint32_t n_in = p.n_in;
+#pragma unroll
+  for (int k = 0; k < MAXIN; ++k) {
+    if ((uint32_t)k < n_in) {
+      const EwIn& in = p.in[k];
+      if (in.fetch == kFetchVec4) st.vec[k] = fetch_vec4<F32>(in.ptr, in.dtype, 0, in.mode == kFull ? i : i_mod);
+      else st.bc[k] = fetch_elem<F32>(in.ptr, in.dtype, in.mode == kColVec ? i_div : 0u);
+    }
+  }
+  pin_staged<MAXIN>(st);
+  return st;
+#pragma clang diagnostic pop
+}
+
 // Convert the fetched inputs and move them into slots 0 .. MAXIN-1 (compile-time slot numbers:
 // plain register moves).
 template <int NS, int MAXIN, bool FAST, bool F32>

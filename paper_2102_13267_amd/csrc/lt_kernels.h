@@ -163,7 +163,21 @@ struct GemmArgs {
   // Contiguous [batch, m, n] by default; a permuted layout when the product's only reader is a
   // permutation (head merge), which then costs nothing.
   int64_t o_b0, o_b1, o_row;
+  // Split-K (bf16 kernel only): `splits` workgroups share an output tile, each contracting a
+  // slice of k and leaving its fp32 partial product, row major, in split_ws[split]; the post
+  // program then runs in a second launch (SplitPostArgs) that adds the partials up in split order.
+  uint32_t splits, tile_m;   // tile_m: rows per workgroup tile (128; columns: 128)
+  float* split_ws;           // [splits][batch * m * n] floats
   EwProg post;               // iteration space = the output
+};
+
+// second launch of a split-K contraction: anchor = sum over splits of ws[split][i], then the
+// contraction's post program over the flat output, exactly like an elementwise region
+struct SplitPostArgs {
+  EwProg prog;
+  const float* ws;
+  uint32_t splits, pad;
+  uint64_t stride;           // floats between consecutive splits (= elements of the output)
 };
 
 }  // namespace ltk

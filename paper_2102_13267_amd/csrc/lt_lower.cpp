@@ -1372,6 +1372,55 @@ struct Lowering {
       post.prog.vec_ok = post.prog.full_vec_ok = al ? 1u : 0u;
     }
     args.post = post.prog;
+    args.splits = 1;
+    int32_t ws_storage = -1;
+    if (A.dtype == LT_BF16) {
+      // the bf16 kernel works on 128 x 128 tiles; few tiles and a long k: split k so that about
+      // two workgroups per compute unit exist, each keeping at least four 64-wide slices
+      const uint32_t bm = 128u;
+      args.tile_m = bm;
+      args.tiles_m = (uint32_t)((m + bm - 1) / bm);
+      args.tiles_n = (uint32_t)((n + 127) / 128);
+      const uint64_t tiles = (uint64_t)args.tiles_m * args.tiles_n * (uint64_t)batch;
+      const uint64_t slices = (uint64_t)(kk + 63) / 64;
+      uint64_t splits = std::min<uint64_t>({512 / std::max<uint64_t>(tiles, 1), slices / 4, 16});
+      if (r->sealed) splits = 1;   // the second launch writes the dense layout only
+      if (splits > 1) {
+        args.splits = (uint32_t)splits;
+        Storage ws;
+        ws.param = -1;
+        ws.bytes = (size_t)((uint64_t)splits * (uint64_t)batch * m * n * sizeof(float));
+        ws.first_launch = launch;
+        ws.last_launch = launch + 1;
+        ws_storage = (int32_t)plan->storages.size();
+        plan->storages.push_back(ws);
+      }
+    }
+    if (ws_storage >= 0) {
+      // two launches: the contraction proper (no post program), then partial sums + post program
+      args.post = ltk::EwProg{};
+      Launch l = make_launch(L_GEMM, k, args);
+      l.flops = 2ull * (uint64_t)batch * m * n * kk;
+      l.bytes = (uint64_t)batch * ((uint64_t)m * kk + (uint64_t)kk * n) * dtype_size(A.dtype);
+      plan->launches.push_back(std::move(l));
+      plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)(offsetof(ltk::GemmArgs, a) + offsetof(ltk::GemmOperand, ptr)), A.storage, 0});
+      plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)(offsetof(ltk::GemmArgs, b) + offsetof(ltk::GemmOperand, ptr)), B.storage, 0});
+      plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)offsetof(ltk::GemmArgs, split_ws), ws_storage, 0});
+      touch(A.storage, launch);
+      touch(B.storage, launch);
+      ltk::SplitPostArgs pa{};
+      pa.prog = post.prog;
+      pa.splits = args.splits;
+      pa.stride = (uint64_t)batch * m * n;
+      Launch l2 = make_launch(L_SPLITPOST, k, pa);
+      l2.grid_x = ew_grid(post.prog.n);
+      l2.bytes = post.bytes;
+      plan->launches.push_back(std::move(l2));
+      plan->ptr_patches.push_back(PtrPatch{(uint32_t)(launch + 1), (uint32_t)offsetof(ltk::SplitPostArgs, ws), ws_storage, 0});
+      add_prog_patches(launch + 1, offsetof(ltk::SplitPostArgs, prog), post);
+      note_prog_storages(post, launch + 1);
+      return true;
+    }
     Launch l = make_launch(L_GEMM, k, args);
     l.flops = 2ull * (uint64_t)batch * m * n * kk;
     l.bytes = post.bytes + (uint64_t)batch * ((uint64_t)m * kk + (uint64_t)kk * n) * dtype_size(A.dtype);

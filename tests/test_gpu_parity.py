@@ -297,6 +297,27 @@ def test_gemm_bf16(ctx, m, k, n, ta, tb):
     check(ctx, E, got32, ref32, 1e-5, (m, k, n, ta, tb))
 
 
+@pytest.mark.parametrize("m,k,n,batch", [(200, 1100, 136, ()), (128, 2048, 256, ()), (70, 520, 90, (3,)), (33, 777, 50, (2, 2))])
+def test_gemm_bf16_long_k_with_epilogue(ctx, m, k, n, batch):
+    """Few output tiles and a long contraction: k is split over several workgroups, their partial
+    products are summed in a second launch that also runs the fused chain (ragged in every
+    dimension, plain and batched)."""
+    E = Eager()
+    r = rng(14)
+    a = round_to_bf16(r.standard_normal(batch + (k, m), dtype=np.float32))       # used transposed
+    b = round_to_bf16(r.standard_normal(batch + (k, n), dtype=np.float32))
+    bias = round_to_bf16(r.standard_normal((n,), dtype=np.float32))
+    res = round_to_bf16(r.standard_normal(batch + (m, n), dtype=np.float32))
+
+    def prog(B):
+        t = lambda v: B.tensor(v, dtype="bf16")
+        return B.add(t(res), B.relu(B.add(B.matmul(t(a), t(b), True, False), t(bias))))
+    got = prog(ctx)
+    info = ctx.barrier()
+    assert info.n_regions == 1
+    check(ctx, E, got, prog(E), TOL16, (m, k, n, batch))
+
+
 def test_gemm_batched_and_epilogue(ctx):
     E = Eager()
     r = rng(13)

@@ -41,7 +41,7 @@
 namespace ltk {
 
 namespace bf {
-constexpr int BN = 128, BK = 32;
+constexpr int BK = 32;
 constexpr int kStrideKC = 80;    // bytes per row of an [x][k] tile: 64 + 16 of padding
 
 typedef short v4s __attribute__((ext_vector_type(4)));
@@ -165,21 +165,21 @@ __device__ __forceinline__ v8bf fragment(const char* tile, uint32_t x_blk, uint3
 }
 
 constexpr int kStripRows = 64;                       // epilogue strip: 32 rows of each wave row
-constexpr int kCStride = BN + kCPad;
-constexpr size_t kStripBytes = (size_t)kStripRows * kCStride * sizeof(float);
 
-template <int BM> struct Smem {
+template <int BM, int BN> struct Smem {
   static constexpr size_t kStage = Geo<BM>::kBytes + Geo<BN>::kBytes;
   static constexpr size_t kOperands = 2 * kStage;
+  static constexpr size_t kStripBytes = (size_t)kStripRows * (BN + kCPad) * sizeof(float);
   static constexpr size_t kBytes = kOperands > kStripBytes ? kOperands : kStripBytes;
 };
 
-// Epilogue over the workgroup's BM x 128 tile.  Strip p holds block row p of both wave rows:
+// Epilogue over the workgroup's BM x BN tile.  Strip p holds block row p of both wave rows:
 // LDS row r is tile row (r / 32) * (BM / 2) + p * 32 + r % 32.
-template <int BM, int MB>
-__device__ __forceinline__ void epilogue_strips(const GemmArgs& a, const v16f (&acc)[MB][2], float* Cs, uint32_t tile_m,
+template <int BM, int BN, int MB, int NB>
+__device__ __forceinline__ void epilogue_strips(const GemmArgs& a, const v16f (&acc)[MB][NB], float* Cs, uint32_t tile_m,
                                                 uint32_t tile_n, uint32_t wave_m, uint32_t wave_n, uint32_t lane,
                                                 uint32_t batch, float* raw) {
+  constexpr int kCStride = BN + kCPad;
   const EwProg& p = a.post;
   const ProgRegs pr = load_prog_regs(p);
   const uint32_t n_code = p.n_code;
@@ -194,20 +194,20 @@ __device__ __forceinline__ void epilogue_strips(const GemmArgs& a, const v16f (&
   // with compile-time indices so that the accumulator array never has to live in memory.
 #pragma unroll 1
   for (int s = 0; s < MB; ++s) {
-    v16f strip[2];
+    v16f strip[NB];
 #pragma unroll
     for (int ss = 0; ss < MB; ++ss)
       if (ss == s) {
-        strip[0] = acc[ss][0];
-        strip[1] = acc[ss][1];
+#pragma unroll
+        for (int bn = 0; bn < NB; ++bn) strip[bn] = acc[ss][bn];
       }
     __syncthreads();   // the LDS bytes (operand tiles, or the previous strip) are dead now
 #pragma unroll
-    for (int bn = 0; bn < 2; ++bn)
+    for (int bn = 0; bn < NB; ++bn)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const uint32_t row = wave_m * 32u + (r >> 2) * 8u + (lane >> 5) * 4u + (r & 3);
-        const uint32_t col = wave_n * 64u + bn * 32u + (lane & 31u);
+        const uint32_t col = wave_n * (BN / 2) + bn * 32u + (lane & 31u);
         Cs[row * kCStride + col] = strip[bn][r];
       }
     __syncthreads();
@@ -278,10 +278,10 @@ __device__ __forceinline__ void epilogue_strips(const GemmArgs& a, const v16f (&
   }
 }
 
-template <int BM, bool AKC, bool BKC>
+template <int BM, int BN, bool AKC, bool BKC>
 __global__ __launch_bounds__(kGemmThreads, 2) void lt_gemm_bf16_kernel(const GemmArgs a) {
-  constexpr int MB = BM / 64;   // 32-row blocks per wave
-  __shared__ __attribute__((aligned(16))) char smem[Smem<BM>::kBytes];
+  constexpr int MB = BM / 64, NB = BN / 64;   // 32 x 32 blocks per wave: rows, columns
+  __shared__ __attribute__((aligned(16))) char smem[Smem<BM, BN>::kBytes];
   const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
   const uint32_t wave_m = wave >> 1, wave_n = wave & 1u;
   // tile number: remap so that each XCD (workgroup number mod 8) owns a contiguous range
@@ -303,18 +303,18 @@ __global__ __launch_bounds__(kGemmThreads, 2) void lt_gemm_bf16_kernel(const Gem
   const bool a_in = a_al && tile_m + BM <= a.m, b_in = b_al && tile_n + BN <= a.n;
 
   // LDS: two stages, each the A tile then the B tile
-  constexpr uint32_t kStage = (uint32_t)Smem<BM>::kStage;
-  v16f acc[MB][2];
+  constexpr uint32_t kStage = (uint32_t)Smem<BM, BN>::kStage;
+  v16f acc[MB][NB];
 #pragma unroll
   for (int i = 0; i < MB; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NB; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
   // fragments of one slice: every MFMA operand of this wave, both k16 steps
   struct Frags {
-    v8bf a[BK / 16][MB], b[BK / 16][2];
+    v8bf a[BK / 16][MB], b[BK / 16][NB];
   };
   auto load_frags = [&](uint32_t stage) {
     const char* As = smem + stage * kStage;
@@ -325,7 +325,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void lt_gemm_bf16_kernel(const Gem
 #pragma unroll
       for (int i = 0; i < MB; ++i) f.a[kk][i] = fragment<BM, AKC>(As, wave_m * (BM / 2) + i * 32u, kk, lane);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) f.b[kk][j] = fragment<BN, BKC>(Bs, wave_n * 64u + j * 32u, kk, lane);
+      for (int j = 0; j < NB; ++j) f.b[kk][j] = fragment<BN, BKC>(Bs, wave_n * (BN / 2) + j * 32u, kk, lane);
     }
     return f;
   };
@@ -335,7 +335,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void lt_gemm_bf16_kernel(const Gem
 #pragma unroll
       for (int i = 0; i < MB; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[kk][i], f.b[kk][j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < NB; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[kk][i], f.b[kk][j], acc[i][j], 0, 0, 0);
   };
   const bool whole = a_in && b_in && ((k_end - k_begin) % BK) == 0u;
   if (k_begin < k_end && whole) {
@@ -397,32 +397,33 @@ __global__ __launch_bounds__(kGemmThreads, 2) void lt_gemm_bf16_kernel(const Gem
 
   // split-K: this workgroup's partial product goes to its own fp32 copy of the output, row major
   float* const raw = a.splits > 1u ? a.split_ws + (size_t)split * ((size_t)a.batch0 * a.batch1 * a.m * a.n) : nullptr;
-  epilogue_strips<BM, MB>(a, acc, (float*)smem, tile_m, tile_n, wave_m, wave_n, lane, batch, raw);
+  epilogue_strips<BM, BN, MB, NB>(a, acc, (float*)smem, tile_m, tile_n, wave_m, wave_n, lane, batch, raw);
 }
 
-template <int BM>
-static void launch_bm(const GemmArgs& a, dim3 grid, hipStream_t s) {
+template <int BM, int BN>
+static void launch_tile(const GemmArgs& a, dim3 grid, hipStream_t s) {
   const dim3 block(kGemmThreads);
   const bool akc = a.a.s_col == 1, bkc = a.b.s_row == 1;
-  if (akc && bkc) hipLaunchKernelGGL((lt_gemm_bf16_kernel<BM, true, true>), grid, block, 0, s, a);
-  else if (akc) hipLaunchKernelGGL((lt_gemm_bf16_kernel<BM, true, false>), grid, block, 0, s, a);
-  else if (bkc) hipLaunchKernelGGL((lt_gemm_bf16_kernel<BM, false, true>), grid, block, 0, s, a);
-  else hipLaunchKernelGGL((lt_gemm_bf16_kernel<BM, false, false>), grid, block, 0, s, a);
+  if (akc && bkc) hipLaunchKernelGGL((lt_gemm_bf16_kernel<BM, BN, true, true>), grid, block, 0, s, a);
+  else if (akc) hipLaunchKernelGGL((lt_gemm_bf16_kernel<BM, BN, true, false>), grid, block, 0, s, a);
+  else if (bkc) hipLaunchKernelGGL((lt_gemm_bf16_kernel<BM, BN, false, true>), grid, block, 0, s, a);
+  else hipLaunchKernelGGL((lt_gemm_bf16_kernel<BM, BN, false, false>), grid, block, 0, s, a);
 }
 
 }  // namespace bf
 
-// a.tile_m: rows per workgroup tile.  The kernel is written for 128 or 256; only 128 is built: the
+// a.tile_m, a.tile_n: rows and columns per workgroup tile (128 x 128, or 128 x 64 for narrow outputs).  The kernel is written for 128 or 256; only 128 is built: the
 // 256-row variant needs more than the 256 registers that two wavefronts per SIMD leave each, and
 // measured no faster.
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   const uint32_t batch = a.batch0 * a.batch1;
   const uint32_t tiles = a.tiles_m * a.tiles_n;
   if (a.splits == 0u || (uint64_t)batch * a.splits > 65535u) return hipErrorInvalidValue;
-  if (a.tile_m != 128u) return hipErrorInvalidValue;
-  if (a.tiles_m != (a.m + a.tile_m - 1) / a.tile_m || a.tiles_n != (a.n + bf::BN - 1) / bf::BN) return hipErrorInvalidValue;
+  if (a.tile_m != 128u || (a.tile_n != 128u && a.tile_n != 64u)) return hipErrorInvalidValue;
+  if (a.tiles_m != (a.m + a.tile_m - 1) / a.tile_m || a.tiles_n != (a.n + a.tile_n - 1) / a.tile_n) return hipErrorInvalidValue;
   const dim3 grid(tiles, batch * a.splits);
-  bf::launch_bm<128>(a, grid, s);
+  if (a.tile_n == 64u) bf::launch_tile<128, 64>(a, grid, s);
+  else bf::launch_tile<128, 128>(a, grid, s);
   return hipGetLastError();
 }
 

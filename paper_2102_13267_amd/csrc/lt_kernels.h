@@ -166,7 +166,7 @@ struct GemmArgs {
   // Split-K (bf16 kernel only): `splits` workgroups share an output tile, each contracting a
   // slice of k and leaving its fp32 partial product, row major, in split_ws[split]; the post
   // program then runs in a second launch (SplitPostArgs) that adds the partials up in split order.
-  uint32_t splits, tile_m;   // tile_m: rows per workgroup tile (128; columns: 128)
+  uint32_t splits, tile_m, tile_n, pad;   // workgroup tile: 128 rows, 128 or 64 columns
   float* split_ws;           // [splits][batch * m * n] floats
   EwProg post;               // iteration space = the output
 };

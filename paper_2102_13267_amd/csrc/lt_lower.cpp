@@ -1378,9 +1378,11 @@ struct Lowering {
       // the bf16 kernel works on 128 x 128 tiles; few tiles and a long k: split k so that about
       // two workgroups per compute unit exist, each keeping at least four 64-wide slices
       const uint32_t bm = 128u;
+      const uint32_t bn = n <= 64 ? 64u : 128u;   // narrow outputs (attention heads): no half-empty tiles
       args.tile_m = bm;
+      args.tile_n = bn;
       args.tiles_m = (uint32_t)((m + bm - 1) / bm);
-      args.tiles_n = (uint32_t)((n + 127) / 128);
+      args.tiles_n = (uint32_t)((n + bn - 1) / bn);
       const uint64_t tiles = (uint64_t)args.tiles_m * args.tiles_n * (uint64_t)batch;
       const uint64_t slices = (uint64_t)(kk + 63) / 64;
       uint64_t splits = std::min<uint64_t>({512 / std::max<uint64_t>(tiles, 1), slices / 4, 16});

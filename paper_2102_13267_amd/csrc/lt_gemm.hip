@@ -189,7 +189,11 @@ __global__ __launch_bounds__(kGemmThreads) void lt_gemm_kernel(const GemmArgs a)
   auto Bs = [&](uint32_t buf) { return lds + 2 * Tile<T, BM>::ELEMS + buf * Tile<T, BN>::ELEMS; };
   const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const uint32_t wave_m = wave >> 1, wave_n = wave & 1;
-  const uint32_t tile_m = blockIdx.y * BM, tile_n = blockIdx.x * BN, batch = blockIdx.z;
+  const uint32_t tile_m = blockIdx.y * BM, tile_n = blockIdx.x * BN;
+  const uint32_t batch = blockIdx.z / a.splits, split = blockIdx.z % a.splits;
+  // this workgroup's share of k: whole slices, split evenly
+  const uint32_t slices = (a.k + BK - 1) / BK, per = (slices + a.splits - 1) / a.splits;
+  const uint32_t k_begin = min(a.k, split * per * BK), k_end = min(a.k, (split + 1) * per * BK);
   const uint32_t b0 = batch / a.batch1, b1 = batch % a.batch1;
   const T* A = (const T*)a.a.ptr + (int64_t)b0 * a.a.s_b0 + (int64_t)b1 * a.a.s_b1;
   const T* B = (const T*)a.b.ptr + (int64_t)b0 * a.b.s_b0 + (int64_t)b1 * a.b.s_b1;
@@ -208,27 +212,31 @@ __global__ __launch_bounds__(kGemmThreads) void lt_gemm_kernel(const GemmArgs a)
 
   GroupRegs<Groups<T, BM>::N> ga;
   GroupRegs<Groups<T, BN>::N> gb;
-  fetch_tile<T, BM, AKC>(ga, A, a.a.s_row, a.a.s_col, tile_m, 0, a.m, a.k, a_al);
-  fetch_tile<T, BN, BKC>(gb, B, a.b.s_col, a.b.s_row, tile_n, 0, a.n, a.k, b_al);
-  stash_tile<BM, AKC>(ga, As(0));
-  stash_tile<BN, BKC>(gb, Bs(0));
-  __syncthreads();
-  uint32_t cur = 0;
-  for (uint32_t k0 = 0; k0 < a.k; k0 += BK) {
-    const bool more = k0 + BK < a.k;
-    if (more) {
-      fetch_tile<T, BM, AKC>(ga, A, a.a.s_row, a.a.s_col, tile_m, k0 + BK, a.m, a.k, a_al);
-      fetch_tile<T, BN, BKC>(gb, B, a.b.s_col, a.b.s_row, tile_n, k0 + BK, a.n, a.k, b_al);
-    }
-    mma_slice<BM, BN, MB, NB>(acc, As(cur), Bs(cur), wave_m, wave_n, lane);
-    if (more) {
-      stash_tile<BM, AKC>(ga, As(cur ^ 1));
-      stash_tile<BN, BKC>(gb, Bs(cur ^ 1));
-    }
+  if (k_begin < k_end) {
+    fetch_tile<T, BM, AKC>(ga, A, a.a.s_row, a.a.s_col, tile_m, k_begin, a.m, k_end, a_al);
+    fetch_tile<T, BN, BKC>(gb, B, a.b.s_col, a.b.s_row, tile_n, k_begin, a.n, k_end, b_al);
+    stash_tile<BM, AKC>(ga, As(0));
+    stash_tile<BN, BKC>(gb, Bs(0));
     __syncthreads();
-    cur ^= 1;
+    uint32_t cur = 0;
+    for (uint32_t k0 = k_begin; k0 < k_end; k0 += BK) {
+      const bool more = k0 + BK < k_end;
+      if (more) {
+        fetch_tile<T, BM, AKC>(ga, A, a.a.s_row, a.a.s_col, tile_m, k0 + BK, a.m, k_end, a_al);
+        fetch_tile<T, BN, BKC>(gb, B, a.b.s_col, a.b.s_row, tile_n, k0 + BK, a.n, k_end, b_al);
+      }
+      mma_slice<BM, BN, MB, NB>(acc, As(cur), Bs(cur), wave_m, wave_n, lane);
+      if (more) {
+        stash_tile<BM, AKC>(ga, As(cur ^ 1));
+        stash_tile<BN, BKC>(gb, Bs(cur ^ 1));
+      }
+      __syncthreads();
+      cur ^= 1;
+    }
   }
-  epilogue<BM, BN, MB, NB>(a, acc, (float*)smem, tile_m, tile_n, wave_m, wave_n, lane, batch);
+  // split-K: this workgroup's partial product goes to its own fp32 copy of the output, row major
+  float* const raw = a.splits > 1u ? a.split_ws + (size_t)split * ((size_t)a.batch0 * a.batch1 * a.m * a.n) : nullptr;
+  epilogue<BM, BN, MB, NB>(a, acc, (float*)smem, tile_m, tile_n, wave_m, wave_n, lane, batch, raw);
 }
 
 template <typename T, int BM, int BN>
@@ -249,7 +257,8 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   const uint64_t big_tiles = (uint64_t)((a.m + 127) / 128) * ((a.n + 127) / 128) * batch;
   const bool big = big_tiles >= 256;
   const uint32_t bm = big ? 128 : 64;
-  const dim3 grid((a.n + bm - 1) / bm, (a.m + bm - 1) / bm, batch);
+  if (a.splits == 0u) return hipErrorInvalidValue;
+  const dim3 grid((a.n + bm - 1) / bm, (a.m + bm - 1) / bm, batch * a.splits);
   if (grid.y > 65535u || grid.z > 65535u) return hipErrorInvalidValue;
   if (big) launch_variant<float, 128, 128>(a, grid, s);
   else launch_variant<float, 64, 64>(a, grid, s);

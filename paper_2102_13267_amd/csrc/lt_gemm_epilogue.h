@@ -20,7 +20,8 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 // of residuals, 16-byte stores) and is compiled in only once.
 template <int BM, int BN, int MB, int NB>
 __device__ __forceinline__ void epilogue(const GemmArgs& a, const v16f (&acc)[MB][NB], float* Cs, uint32_t tile_m,
-                                         uint32_t tile_n, uint32_t wave_m, uint32_t wave_n, uint32_t lane, uint32_t batch) {
+                                         uint32_t tile_n, uint32_t wave_m, uint32_t wave_n, uint32_t lane, uint32_t batch,
+                                         float* raw = nullptr) {
   constexpr int kCStride = BN + kCPad;
   __syncthreads();   // the operand tiles in the same LDS bytes are dead now
 #pragma unroll
@@ -39,6 +40,28 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, const v16f (&acc)[MB
   const uint32_t n_code = p.n_code;
   const uint32_t b0 = batch / a.batch1, b1 = batch % a.batch1;
   const int64_t base = (int64_t)b0 * a.o_b0 + (int64_t)b1 * a.o_b1;
+  if (raw) {
+    // partial product of a k split: plain fp32, dense [batch * m, n]; the post program runs in a
+    // second launch over the sum of the splits
+    const uint32_t row_flat0 = (b0 * a.batch1 + b1) * a.m;
+    const bool vec = (a.n % 4u) == 0u;
+    for (uint32_t q = threadIdx.x; q < (uint32_t)(BM * BN / kVec); q += kGemmThreads) {
+      const uint32_t r = q / (BN / kVec), c = (q % (BN / kVec)) * kVec;
+      const uint32_t row = tile_m + r, col = tile_n + c;
+      if (row >= a.m || col >= a.n) continue;
+      float* dst = raw + (size_t)(row_flat0 + row) * a.n + col;
+      const float4 t = *(const float4*)&Cs[r * kCStride + c];
+      if (vec) {
+        *(float4*)dst = t;
+      } else {
+        dst[0] = t.x;
+        if (col + 1 < a.n) dst[1] = t.y;
+        if (col + 2 < a.n) dst[2] = t.z;
+        if (col + 3 < a.n) dst[3] = t.w;
+      }
+    }
+    return;
+  }
   // Whole tile, whole aligned 4-vectors, at most four inputs and none of them strided: no bounds
   // checks, no divisions (row and column are known), loads of a quad issued together.
   if (p.fast && p.full_vec_ok && p.n_in <= 4u && tile_m + BM <= a.m && tile_n + BN <= a.n) {

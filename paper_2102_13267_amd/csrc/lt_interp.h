@@ -262,16 +262,17 @@ __device__ __forceinline__ uint64_t elem_offset(const EwProg& p, const EwIn& in,
   return strided_index(p, in, i);
 }
 
-// General path: ragged tails, rows that are not a multiple of four, strided views.  Kept as a
-// rolled loop: it is rare, and code size matters more than its speed (the instruction cache is
-// shared by neighbouring compute units).
+// General path: ragged tails, rows that are not a multiple of four, strided views.
 __device__ __forceinline__ Quad load_input_slow(const EwProg& p, const EwIn& in, uint64_t i, uint32_t nvalid) {
-  Quad q = splat(0.0f);
-#pragma unroll 1
-  for (uint32_t e = 0; e < nvalid; ++e) {
-    const float x = load_elem<false>(in.ptr, in.dtype, elem_offset(p, in, i + e));
+  // the (up to four) element loads are issued together: one after the other they would cost a
+  // memory round trip each
+  // (elements past nvalid re-read the last valid one, so that no load sits behind a branch)
+  Quad q;
 #pragma unroll
-    for (int v = 0; v < kVec; ++v) q.v[v] = e == (uint32_t)v ? x : q.v[v];
+  for (int e = 0; e < kVec; ++e) {
+    const uint32_t ee = (uint32_t)e < nvalid ? (uint32_t)e : nvalid - 1u;   // nvalid >= 1
+    const float x = load_elem<false>(in.ptr, in.dtype, elem_offset(p, in, i + ee));
+    q.v[e] = (uint32_t)e < nvalid ? x : 0.0f;
   }
   return q;
 }
@@ -377,8 +378,40 @@ __device__ __forceinline__ RF<NS> place_inputs(RF<NS> f, const EwProg& p, const 
   return f;
 }
 
+template <int NS>
+__device__ __forceinline__ RF<NS> rf_set(RF<NS> f, uint32_t slot, Quad q);
+
+// The general path (ragged tails, rows that are not a multiple of four, strided views, small
+// problems) as ONE rolled loop over the inputs: a kernel that runs it at all runs it a few times,
+// so what it costs is the instructions it drags through the instruction cache, not its latency.
+template <int NS>
+__device__ __forceinline__ RF<NS> load_inputs_general(RF<NS> f, const EwProg& p, uint64_t base, uint32_t lane, uint32_t nvalid) {
+  const uint32_t n_in = p.n_in;
+  uint32_t i_div = 0, i_mod = 0;
+  if (p.needs_divmod) {
+    const uint32_t i = (uint32_t)base + lane;
+    i_div = i / p.cols;
+    i_mod = i - i_div * p.cols;
+  }
+#pragma unroll 1
+  for (uint32_t k = 0; k < n_in; ++k) {
+    const EwIn& in = p.in[k];
+    const uint32_t fetch = nvalid == (uint32_t)kVec ? in.fetch : (uint32_t)kFetchSlow;
+    const uint32_t mode = in.mode;
+    Quad q;
+    if (fetch == kFetchSlow) q = load_input_slow(p, in, base + lane, nvalid);
+    else if (fetch == kFetchVec4)
+      q = finish_vec4<false>(in.dtype, mode == kFull ? fetch_vec4<false>(in.ptr, in.dtype, base, lane)
+                                                      : fetch_vec4<false>(in.ptr, in.dtype, 0, i_mod));
+    else q = splat(finish_elem<false>(in.dtype, fetch_elem<false>(in.ptr, in.dtype, mode == kColVec ? i_div : 0u)));
+    f = rf_set<NS>(f, k, q);
+  }
+  return f;
+}
+
 template <int NS, int MAXIN = kMaxIn, bool FAST = false, bool F32 = false>
 __device__ __forceinline__ RF<NS> load_inputs(RF<NS> f, const EwProg& p, uint64_t base, uint32_t lane, uint32_t nvalid) {
+  if (!FAST) return load_inputs_general<NS>(f, p, base, lane, nvalid);
   return place_inputs<NS, MAXIN, FAST, F32>(f, p, fetch_inputs<MAXIN, FAST, F32>(p, base, lane, nvalid), nvalid);
 }
 
@@ -429,6 +462,23 @@ __device__ __forceinline__ void store_vec4(void* ptr, uint32_t dtype, uint64_t b
 template <int NS, bool FAST = false, bool F32 = false>
 __device__ __forceinline__ void store_outputs(RF<NS> f, const EwProg& p, uint64_t base, uint32_t lane, uint32_t nvalid) {
   const uint32_t n_out = p.n_out;
+  if (!FAST) {   // general path: one rolled copy (see load_inputs_general)
+#pragma unroll 1
+    for (uint32_t o = 0; o < n_out; ++o) {
+      const EwOut& out = p.out[o];
+      const Quad q = rf_get<NS>(f, out.slot);
+      if (out.scalar) {
+        if (base + lane == 0) store_elem<false>(out.ptr, out.dtype, 0, q.v[0]);
+      } else if (p.full_vec_ok && nvalid == (uint32_t)kVec) {
+        store_vec4<false>(out.ptr, out.dtype, base, lane, q);
+      } else {
+#pragma unroll 1
+        for (uint32_t e = 0; e < nvalid; ++e)
+          store_elem<false>(out.ptr, out.dtype, base + lane + e, e == 0 ? q.v[0] : e == 1 ? q.v[1] : e == 2 ? q.v[2] : q.v[3]);
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int o = 0; o < kMaxOut; ++o) {
     if ((uint32_t)o < n_out) {
@@ -436,12 +486,8 @@ __device__ __forceinline__ void store_outputs(RF<NS> f, const EwProg& p, uint64_
       const Quad q = rf_get<NS>(f, out.slot);
       if (out.scalar) {
         if (base + lane == 0) store_elem<F32>(out.ptr, out.dtype, 0, q.v[0]);
-      } else if (FAST || (p.full_vec_ok && nvalid == (uint32_t)kVec)) {
-        store_vec4<F32>(out.ptr, out.dtype, base, lane, q);
       } else {
-#pragma unroll 1
-        for (uint32_t e = 0; e < nvalid; ++e)
-          store_elem<F32>(out.ptr, out.dtype, base + lane + e, e == 0 ? q.v[0] : e == 1 ? q.v[1] : e == 2 ? q.v[2] : q.v[3]);
+        store_vec4<F32>(out.ptr, out.dtype, base, lane, q);
       }
     }
   }

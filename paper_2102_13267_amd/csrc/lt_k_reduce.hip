@@ -94,21 +94,24 @@ __global__ __launch_bounds__(kBlock) void lt_all_reduce_kernel(const AllArgs a) 
     acc = fold_vec(a.red, acc, rf_get(f, pro.anchor_slot), nvalid);
   }
   float r = block_reduce(a.red, acc, lds);
-  if (threadIdx.x == 0) {
-    a.partials[blockIdx.x] = r;   // published by the fence, read by the last workgroup behind its own fence
+  if (gridDim.x > 1u) {   // (a single workgroup is its own last one: no partials, no fences, whose
+                          // device-wide cache write-back costs microseconds)
+    if (threadIdx.x == 0) {
+      a.partials[blockIdx.x] = r;   // published by the fence, read by the last workgroup behind its own fence
+      __threadfence();
+      uint32_t t = atomicAdd(a.ticket, 1u);
+      is_last = (t == gridDim.x - 1) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!is_last) return;
     __threadfence();
-    uint32_t t = atomicAdd(a.ticket, 1u);
-    is_last = (t == gridDim.x - 1) ? 1u : 0u;
+    // the last workgroup combines the partials in a fixed order (deterministic for a given grid)
+    acc = red_identity(a.red);
+    for (uint32_t g = threadIdx.x; g < gridDim.x; g += kBlock) acc = red_combine(a.red, acc, a.partials[g]);
+    r = block_reduce(a.red, acc, lds);
+    if (threadIdx.x == 0) *a.ticket = 0u;
   }
-  __syncthreads();
-  if (!is_last) return;
-  __threadfence();
-  // the last workgroup combines the partials in a fixed order (deterministic for a given grid)
-  acc = red_identity(a.red);
-  for (uint32_t g = threadIdx.x; g < gridDim.x; g += kBlock) acc = red_combine(a.red, acc, a.partials[g]);
-  r = block_reduce(a.red, acc, lds);
   if (a.red == kRedMean) r = r / (float)a.count;
-  if (threadIdx.x == 0) *a.ticket = 0u;
   const EwProg& post = a.post;
   const uint64_t pn = post.n;
   const uint64_t pvec = (pn + kVec - 1) / kVec;
@@ -189,6 +192,17 @@ __global__ __launch_bounds__(kColBlock) void lt_col_reduce_kernel(const ColArgs 
       acc.z = red_combine(a.red, acc.z, o.z);
       acc.w = red_combine(a.red, acc.w, o.w);
     }
+    if (gridDim.y == 1u) {   // one slab: this is the result, no partials, tickets or fences
+      if (!nvalid) return;
+      if (a.red == kRedMean) {
+        const float inv = 1.0f / (float)a.rows;
+        acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
+      }
+      Quad accq;
+      accq.v[0] = acc.x; accq.v[1] = acc.y; accq.v[2] = acc.z; accq.v[3] = acc.w;
+      run_post(a.post, post_regs, accq, c, nvalid);
+      return;
+    }
     // plain stores: the fence below publishes them before the ticket is taken, and the last
     // workgroup's fence after its ticket makes them visible to its plain loads.  The slab stride
     // is padded to a multiple of four floats so that whole vectors stay 16-byte aligned.
@@ -208,6 +222,7 @@ __global__ __launch_bounds__(kColBlock) void lt_col_reduce_kernel(const ColArgs 
       is_last = (t == gridDim.y - 1) ? 1u : 0u;
     }
   }
+  if (gridDim.y == 1u) return;   // (uniform: wave 0 has finished the strip above)
   __syncthreads();
   if (!is_last) return;
   __threadfence();

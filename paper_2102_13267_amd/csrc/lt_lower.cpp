@@ -1148,6 +1148,9 @@ struct Lowering {
       if (l.grid_x > kTickets) return bad(LT_ERR_UNSUPPORTED, "axis-0 reduction wider than 262144 columns");
       // a slab of 64 rows gives each of a workgroup's 8 waves one 8-row trip
       uint32_t gy = std::max<uint32_t>(1, std::min<uint32_t>(args.rows / 64, 64));
+      // small: one slab per strip and no cross-workgroup step -- unless the rows are not whole
+      // 4-vectors, where the element-wise path is slow enough to want the rows spread out
+      if ((uint64_t)args.rows * args.cols <= 65536) gy = (args.cols % 4u) == 0u ? 1u : std::max<uint32_t>(1, std::min<uint32_t>(args.rows / 16, 8));
       while (gy > 1 && (uint64_t)gy * (args.cols + 3) > kPartialFloats) gy /= 2;
       if ((uint64_t)gy * (args.cols + 3) > kPartialFloats) return bad(LT_ERR_UNSUPPORTED, "axis-0 reduction wider than 1048576 columns");
       while (gy > 1 && (uint64_t)gy * l.grid_x > 256) gy /= 2;
@@ -1392,6 +1395,23 @@ struct Lowering {
         Storage ws;
         ws.param = -1;
         ws.bytes = (size_t)((uint64_t)splits * (uint64_t)batch * m * n * sizeof(float));
+        ws.first_launch = launch;
+        ws.last_launch = launch + 1;
+        ws_storage = (int32_t)plan->storages.size();
+        plan->storages.push_back(ws);
+      }
+    }
+    if (A.dtype == LT_F32 && !r->sealed) {
+      // the fp32 kernel takes 64 x 64 tiles when there are few; a long k over few tiles is split
+      // so that the chip has about one workgroup per compute unit, each with >= 4 slices of 16
+      const uint64_t tiles = (uint64_t)((m + 63) / 64) * ((n + 63) / 64) * (uint64_t)batch;
+      const uint64_t slices = (uint64_t)(kk + 15) / 16;
+      const uint64_t splits = std::min<uint64_t>({256 / std::max<uint64_t>(tiles, 1), slices / 4, 16});
+      if (splits > 1) {
+        args.splits = (uint32_t)splits;
+        Storage ws;
+        ws.param = -1;
+        ws.bytes = (size_t)(splits * (uint64_t)batch * m * n * sizeof(float));
         ws.first_launch = launch;
         ws.last_launch = launch + 1;
         ws_storage = (int32_t)plan->storages.size();

@@ -7,6 +7,10 @@ until the device is done.  Inputs are resident in HBM before the timed region st
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4|c1|c2|c3|c5]
 
+Without --workload the headline is c4 (the configuration whose fused regions are HBM-bound at a
+size that fills the GPU) and the other four configurations run briefly afterwards; their rates
+and roofline fractions go under detail.other_configs of the same JSON line.
+
 Prints ONE JSON line: barrier-steps/s for the workload, the roofline of its dominant kernel
 (duration measured with HIP events on the library's stream inside the timed steps) and the CPU
 oracle timed on the same box.
@@ -174,9 +178,14 @@ def run_c2(steps, warmup):
         loss = programs.c2_step(ctx, Xs[i], Ls[i], params, 0.01)
         return ctx.barrier(True)
     dt, dt_prof, launches, infos = _time_steps(step, ctx, steps, warmup)
-    kernel, region, avg_ms, kbytes, kflops, table = _dominant(launches)
-    roof = {"bound": "mfma", "kernel": kernel, "achieved": kflops / (avg_ms * 1e-3) / 1e12, "peak": MFMA_PEAK_TFLOPS["f32"],
-            "unit": "TFLOP/s", "traffic": None, "avg_ms": avg_ms, "flops_per_launch": kflops}
+    _, _, _, _, _, table = _dominant(launches)
+    # the contractions as a family (each is a few microseconds: launch latency, not the matrix cores, bounds them)
+    flops = sum(r["flops"] for st in launches for r in st)
+    gemm_ms = sum(r["ms"] for st in launches for r in st if r["flops"])
+    roof = {"bound": "mfma", "kernel": "lt_gemm_kernel", "achieved": flops / (gemm_ms * 1e-3) / 1e12,
+            "peak": MFMA_PEAK_TFLOPS["f32"], "unit": "TFLOP/s", "traffic": None, "gemm_ms_per_step": gemm_ms / len(launches),
+            "device_ms_per_step": sum(r["ms"] for st in launches for r in st) / len(launches),
+            "launches_per_step": len(launches[-1])}
     roof["frac"] = roof["achieved"] / roof["peak"]
     extra = {"kernels": table, "cache_hits": sum(i.cache_hit for i in infos), "ns_host_per_step": {
         "collect": int(np.mean([i.ns_collect for i in infos])), "hash": int(np.mean([i.ns_hash for i in infos])),
@@ -295,7 +304,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="c4", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default=None, choices=sorted(WORKLOADS),
+                    help="default: c4 as the headline line, plus a short run of every other config under detail.other_configs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy, so that a rocprofv3 --pmc run of this command "
@@ -306,8 +316,9 @@ def main():
               "(the path shards by parameter range / batch, see DESIGN.md)", file=sys.stderr)
         sys.exit(2)
     defaults = {"c4": (20, 3), "c1": (200, 10), "c2": (200, 10), "c3": (10, 2), "c5": (100, 10)}
-    steps = args.steps if args.steps is not None else defaults[args.workload][0]
-    warmup = args.warmup if args.warmup is not None else defaults[args.workload][1]
+    headline = args.workload or "c4"
+    steps = args.steps if args.steps is not None else defaults[headline][0]
+    warmup = args.warmup if args.warmup is not None else defaults[headline][1]
     if args.copy_calibration:
         import torch
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")      # 1 GiB read + 1 GiB written
@@ -315,7 +326,7 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    dt, dtype, config, roof, extra, cpu = WORKLOADS[args.workload](steps, warmup)
+    dt, dtype, config, roof, extra, cpu = WORKLOADS[headline](steps, warmup)
     line = {
         "metric": "barrier-steps/sec", "value": steps / dt, "unit": "steps/s", "n_gpus": 1, "steps": steps,
         "warmup": warmup, "ms_per_step": dt / steps * 1e3, "higher_is_better": True, "scaling": "weak",
@@ -325,6 +336,19 @@ def main():
         v, sample = cpu()
         line["cpu_baseline"] = {"value": v, "unit": "steps/s", "cores": os.cpu_count(), "kind": "oracle", "sample": sample}
     line["detail"] = extra
+    if args.workload is None:
+        # the other configurations, each a short run of its own (parity is the tests' business;
+        # these are the rates and roofline fractions the design notes quote)
+        others = {}
+        for w in ("c1", "c2", "c3", "c5"):
+            import gc
+            gc.collect()
+            st, wu = defaults[w]
+            odt, odtype, oconfig, oroof, oextra, _ = WORKLOADS[w](st, wu)
+            others[w] = {"value": st / odt, "unit": "steps/s", "ms_per_step": odt / st * 1e3, "steps": st, "dtype": odtype,
+                         "workload": oconfig["workload"], "roofline": oroof,
+                         "detail": {k: v for k, v in oextra.items() if k not in ("kernels", "plan")}}
+        line["detail"]["other_configs"] = others
     print(json.dumps(line))
 
 

@@ -110,13 +110,44 @@ def load_library():
     return lib
 
 
+_NO_ATTRS = (lt_attr * 1)()   # what an op without attributes passes (never read)
+
+
 class Tensor:
     """A handle (unique tensor id).  Dropping the last Python reference releases it, which is
-    how the library learns that a tensor is no longer live."""
-    __slots__ = ("ctx", "tid", "dtype", "shape", "_keep", "__weakref__")
+    how the library learns that a tensor is no longer live.  Element type and shape of an op's
+    result are asked from the library only when somebody reads them: recording an op is one call."""
+    __slots__ = ("ctx", "tid", "_dtype", "_shape", "_keep", "__weakref__")
 
-    def __init__(self, ctx, tid, dtype, shape, keep=None):
-        self.ctx, self.tid, self.dtype, self.shape, self._keep = ctx, tid, dtype, tuple(shape), keep
+    def __init__(self, ctx, tid, dtype=None, shape=None, keep=None):
+        self.ctx, self.tid, self._keep = ctx, tid, keep
+        self._dtype, self._shape = dtype, (None if shape is None else tuple(shape))
+
+    def _query(self):
+        dt, rank = C.c_int(), C.c_int()
+        dims = (C.c_int64 * MAX_RANK)()
+        self.ctx._check(self.ctx._lib.lt_shape(self.ctx._h, self.tid, C.byref(dt), C.byref(rank), dims))
+        self._dtype, self._shape = _DTYPE_NAMES[dt.value], tuple(dims[i] for i in range(rank.value))
+
+    @property
+    def dtype(self):
+        if self._dtype is None:
+            self._query()
+        return self._dtype
+
+    @dtype.setter
+    def dtype(self, v):
+        self._dtype = v
+
+    @property
+    def shape(self):
+        if self._shape is None:
+            self._query()
+        return self._shape
+
+    @shape.setter
+    def shape(self, v):
+        self._shape = None if v is None else tuple(v)
 
     def __del__(self):
         ctx = self.ctx
@@ -213,9 +244,9 @@ class Context:
         return x if isinstance(x, Tensor) else self.scalar(x)
 
     def op(self, name, inputs, attrs=(), n_out=1):
-        ins = [self._t(x) for x in inputs]
+        ins = [x if isinstance(x, Tensor) else self.scalar(x) for x in inputs]
         ids = (C.c_uint64 * len(ins))(*[t.tid for t in ins])
-        at = (lt_attr * max(1, len(attrs)))()
+        at = (lt_attr * len(attrs))() if attrs else _NO_ATTRS
         for i, (key, val) in enumerate(attrs):
             at[i].key = key
             if isinstance(val, float):
@@ -226,13 +257,9 @@ class Context:
                 at[i].v.i = int(val)
         outs = (C.c_uint64 * n_out)()
         self._check(self._lib.lt_op(self._h, OPCODES[name], ids, len(ins), at, len(attrs), outs, n_out))
-        res = []
-        for k in range(n_out):
-            dt, rank = C.c_int(), C.c_int()
-            dims = (C.c_int64 * MAX_RANK)()
-            self._check(self._lib.lt_shape(self._h, outs[k], C.byref(dt), C.byref(rank), dims))
-            res.append(Tensor(self, outs[k], _DTYPE_NAMES[dt.value], tuple(dims[i] for i in range(rank.value))))
-        return res[0] if n_out == 1 else tuple(res)
+        if n_out == 1:
+            return Tensor(self, outs[0])
+        return tuple(Tensor(self, outs[k]) for k in range(n_out))
 
     # ---- the tensor API shared with the oracle's back ends -------------------------------------------
     def neg(self, x): return self.op("neg", [x])
@@ -277,7 +304,7 @@ class Context:
 
     def assign(self, dst: Tensor, src: Tensor):
         self._check(self._lib.lt_assign(self._h, dst.tid, src.tid))
-        dst.dtype, dst.shape = src.dtype, src.shape
+        dst._dtype, dst._shape = src._dtype, src._shape   # (unknown stays unknown: asked for on demand)
 
     def release(self, t: Tensor):
         self._check(self._lib.lt_release(self._h, t.tid))

@@ -258,7 +258,7 @@ def run_c3(steps, warmup, bsz=32, seq=256, d=1024, ffn=4096, heads=16):
 
     def step():
         state["t"] += 1
-        programs.c3_step(ctx, *g, t=state["t"])
+        y, dx = programs.c3_step(ctx, *g, t=state["t"])     # held until the barrier: the layer output and the input gradient are results
         return ctx.barrier(True)
     dt, dt_prof, launches, infos = _time_steps(step, ctx, steps, warmup)
     _, _, _, _, _, table = _dominant(launches)

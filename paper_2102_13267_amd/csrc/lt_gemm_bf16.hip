@@ -414,7 +414,7 @@ static void launch_tile(const GemmArgs& a, dim3 grid, hipStream_t s) {
 
 // a.tile_m, a.tile_n: rows and columns per workgroup tile (128 x 128, or 128 x 64 for narrow outputs).  The kernel is written for 128 or 256; only 128 is built: the
 // 256-row variant needs more than the 256 registers that two wavefronts per SIMD leave each, and
-// measured no faster.
+// measured slower both ways (two workgroups per compute unit with spills, or one with 385 registers).
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   const uint32_t batch = a.batch0 * a.batch1;
   const uint32_t tiles = a.tiles_m * a.tiles_n;

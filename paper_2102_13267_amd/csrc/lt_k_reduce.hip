@@ -35,6 +35,8 @@ __global__ __launch_bounds__(kBlock) void lt_row_reduce_kernel(const RowArgs a) 
       for (uint32_t c = lane * kVec; c < a.cols; c += tpr * kVec) {
         const uint32_t nvalid = (a.cols - c >= (uint32_t)kVec) ? (uint32_t)kVec : a.cols - c;
         const uint32_t i = row * a.cols + c;
+        // (the compact general path: measured faster here than the unrolled loads, whose code the
+        // typical small, cache-resident row reduction would have to fetch first)
         RF<16> f = load_inputs<16>(rf_zero<16>(), pro, 0, i, nvalid);
         f = interp<16>(f, pro_regs, pro_n);
         acc = fold_vec(a.red, acc, rf_get(f, pro.anchor_slot), nvalid);
@@ -176,7 +178,9 @@ __global__ __launch_bounds__(kColBlock) void lt_col_reduce_kernel(const ColArgs 
       }
     }
     for (; r < r1; r += kWaves) {
-      RF<NS> f = load_inputs<NS, kMaxIn, false, false>(rf_zero<NS>(), pro, (uint64_t)r * a.cols + blockIdx.x * 256u, lane * kVec, nvalid);
+      const uint64_t rb = (uint64_t)r * a.cols + blockIdx.x * 256u;
+      RF<NS> f = (pro.fast && nvalid == (uint32_t)kVec) ? load_inputs<NS, kMaxIn, true, false>(rf_zero<NS>(), pro, rb, lane * kVec, nvalid)
+                                                        : load_inputs<NS, kMaxIn, false, false>(rf_zero<NS>(), pro, rb, lane * kVec, nvalid);
       f = interp<NS>(f, pro_regs, pro_n);
       col_fold(a.red, acc, rf_get(f, pro.anchor_slot));
     }

@@ -460,3 +460,104 @@ def test_c3_transformer_layer_forward_backward_adam(ctx, cfg):
     plan = ctx.dump_plan()
     assert plan.count("->p") == 48                          # 16 parameters x (p, m, v) updated in place
     assert " EW " not in plan.replace("R41 EW", "") or plan.count(" EW ") <= 2   # no stray copy kernels for the head split / merge
+
+
+# ---- full sizes, in the launch configurations that bench.py times ---------------------------------
+def test_c4_full_size_sampled():
+    """268,435,456 parameters (the headline configuration).  The clipping coefficient needs the
+    whole gradient, so the oracle reduces all of it; the Adam chain is then elementwise and is
+    checked on a sample: both ends, and 2^18 positions spread over the vector."""
+    from paper_2102_13267_amd import Context
+    import torch
+    n = 268_435_456
+    ctx = Context(device=0, workspace_bytes=64 << 20)
+    inp = c4_inputs(n)
+    names = ("p", "g", "m", "v")
+    dev = {k: torch.from_numpy(inp[k]).to("cuda:0") for k in names}
+    gt = [ctx.tensor(dev[k], donatable=(k != "g")) for k in names]
+    programs.c4_step(ctx, *gt, **C4_HYPER)
+    info = ctx.barrier()
+    assert info.n_regions == 2 and ctx.dump_plan().count("->p") == 3
+    r = rng(40)
+    idx = np.unique(np.concatenate([np.arange(4096), np.arange(n - 4096, n), r.integers(0, n, 1 << 18)]))
+    E = Eager()
+    gnorm = E.sqrt(E.sum(E.square(E.tensor(inp["g"]))))                       # the oracle over all of g
+    clip = E.minimum(1.0, E.div(C4_HYPER["max_norm"], E.add(gnorm, 1e-6)))
+    rs = {k: E.tensor(inp[k][idx]) for k in names}
+    hyper = {k: v for k, v in C4_HYPER.items() if k != "max_norm"}
+    programs.adam_update(E, rs["p"], rs["g"], rs["m"], rs["v"], clip=clip, **hyper)
+    for k, t in zip(names, gt):
+        if k == "g":
+            continue
+        got = dev[k][torch.from_numpy(idx).to("cuda:0")].cpu().numpy()     # donated: the caller's buffer holds the result
+        assert ctx.device_ptr(t) == dev[k].data_ptr()
+        assert rel_err(got, E.fetch(rs[k])) <= TOL32, k
+    ctx.close()
+
+
+C3_GEMMS = [  # (m, n, k, trans_a, trans_b, batch): the contraction shapes of the transformer layer
+    (8192, 1024, 1024, False, False, ()),      # projections
+    (8192, 4096, 1024, False, False, ()),      # FFN up
+    (8192, 1024, 4096, False, True, ()),       # FFN down, backward w.r.t. its input
+    (1024, 1024, 8192, True, False, ()),       # weight gradient: k split over workgroups
+    (1024, 4096, 8192, True, False, ()),
+    (256, 256, 64, False, True, (32, 16)),     # attention scores
+    (256, 64, 256, False, False, (32, 16)),    # attention context (128 x 64 tiles)
+    (256, 64, 256, True, False, (32, 16)),     # its gradients
+]
+
+
+@pytest.mark.parametrize("m,n,k,ta,tb,batch", C3_GEMMS)
+def test_gemm_bf16_full_size_sampled(m, n, k, ta, tb, batch):
+    """The bf16 contractions at C3's full sizes: 16 x 16 sampled outputs per (sampled) batch,
+    each a k-long dot product the oracle computes on its own."""
+    from paper_2102_13267_amd import Context
+    import torch
+    ctx = Context(device=0, workspace_bytes=1 << 30)
+    g = torch.Generator(device="cuda:0").manual_seed(41)
+    a = (torch.randn(*batch, *((k, m) if ta else (m, k)), device="cuda:0", generator=g) * 0.5).to(torch.bfloat16)
+    b = (torch.randn(*batch, *((n, k) if tb else (k, n)), device="cuda:0", generator=g) * 0.5).to(torch.bfloat16)
+    out = ctx.matmul(ctx.tensor(a, dtype="bf16"), ctx.tensor(b, dtype="bf16"), ta, tb, dtype="f32")
+    got = ctx.fetch(out)
+    r = rng(42)
+    rows, cols = np.sort(r.choice(m, 16, replace=False)), np.sort(r.choice(n, 16, replace=False))
+    picks = [()] if not batch else [tuple(int(r.integers(0, d)) for d in batch) for _ in range(4)]
+    E = Eager()
+    for bi in picks:
+        an, bn = a[bi].float().cpu().numpy(), b[bi].float().cpu().numpy()
+        asub = an[:, rows] if ta else an[rows, :]
+        bsub = bn[cols, :] if tb else bn[:, cols]
+        ref = E.fetch(E.matmul(E.tensor(asub, dtype="bf16"), E.tensor(bsub, dtype="bf16"), ta, tb, dtype="f32"))
+        sub = got[bi][np.ix_(rows, cols)]
+        assert rel_err(sub, ref) <= 1e-5, (m, n, k, ta, tb, bi)      # fp32 accumulator, fp32 output
+    ctx.close()
+
+
+def test_c3_full_size_batch_elements():
+    """The transformer layer at its full size (batch 32, seq 256, d_model 1024, FFN 4096, 16 heads).
+    A batch element's output and input gradient depend on that element alone, so the oracle runs
+    the same program on single batch elements."""
+    from paper_2102_13267_amd import Context
+    from workloads.inputs import c3_inputs
+    bsz, seq, d, ffn, heads = 32, 256, 1024, 4096, 16
+    ctx = Context(device=0, workspace_bytes=8 << 30)
+    inp = c3_inputs(bsz, seq, d, ffn)
+    keys = programs.C3_WEIGHTS + programs.C3_VECTORS
+
+    def setup(B, mk, sl):
+        P = {k: mk(round_to_bf16(inp[k]), "bf16", True) for k in keys}
+        M = {k: mk(np.zeros_like(inp[k]), "f32", True) for k in keys}
+        V = {k: mk(np.zeros_like(inp[k]), "f32", True) for k in keys}
+        return mk(round_to_bf16(inp["x"][sl]), "bf16", False), mk(round_to_bf16(inp["dy"][sl]), "bf16", False), P, M, V, heads
+    g = setup(ctx, lambda a, dt, don: ctx.tensor(a, dtype=dt, donatable=don), slice(None))
+    y, dx = programs.c3_step(ctx, *g, t=1)
+    info = ctx.barrier()
+    assert info.n_regions == 42
+    yg, dxg = ctx.fetch(y).reshape(bsz, seq, d), ctx.fetch(dx).reshape(bsz, seq, d)
+    for b in (0, 17):
+        E = Eager()
+        r = setup(E, lambda a, dt, don: E.tensor(a, dtype=dt), slice(b, b + 1))
+        yr, dxr = programs.c3_step(E, *r, t=1)
+        assert rel_err(yg[b], E.fetch(yr).reshape(seq, d)) <= TOL16, b
+        assert rel_err(dxg[b], E.fetch(dxr).reshape(seq, d)) <= TOL16, b
+    ctx.close()

@@ -366,18 +366,25 @@ __global__ __launch_bounds__(kGemmThreads, 2) void lt_gemm_bf16_kernel(const Gem
     LT_STASH(1);
     LT_FETCH(2);
     __syncthreads();
-    Frags f = load_frags(0);
+    Frags f0 = load_frags(0), f1;
     __syncthreads();   // nobody overwrites stage 0 before everybody has read slice 0 from it
-    // The body is branch free: past the end it reads fragments nobody uses and writes a stage
-    // nobody reads (all inside the workgroup's own LDS).
-    for (uint32_t i = 0; i < n; ++i) {
-      const Frags fn = load_frags((i + 1u) & 1u);
-      mma(f);
-      LT_STASH(i & 1u);
+    // Two slices per trip so that the two fragment sets swap roles without register copies.  The
+    // body is branch free: past the end it reads fragments nobody uses and writes a stage nobody
+    // reads (all inside the workgroup's own LDS).
+    uint32_t i = 0;
+    for (; i + 1u < n; i += 2u) {
+      f1 = load_frags(1);
+      mma(f0);
+      LT_STASH(0);
       LT_FETCH(i + 3u);
       __syncthreads();
-      f = fn;
+      f0 = load_frags(0);
+      mma(f1);
+      LT_STASH(1);
+      LT_FETCH(i + 4u);
+      __syncthreads();
     }
+    if (i < n) mma(f0);   // odd number of slices: the last one is already in registers
 #undef LT_FETCH
 #undef LT_STASH
   } else if (k_begin < k_end) {

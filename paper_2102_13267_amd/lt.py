@@ -165,6 +165,7 @@ class Context:
     def __init__(self, device=None, workspace_bytes=1 << 30, stream=None):
         self._lib = load_library()
         self._h = C.c_void_p()
+        self._ids, self._outs, self._attrs = {}, {}, {}     # reusable ctypes argument arrays of op()
         self._torch = None
         self._workspace = None
         if device is None:
@@ -244,19 +245,40 @@ class Context:
         return x if isinstance(x, Tensor) else self.scalar(x)
 
     def op(self, name, inputs, attrs=(), n_out=1):
-        ins = [x if isinstance(x, Tensor) else self.scalar(x) for x in inputs]
-        ids = (C.c_uint64 * len(ins))(*[t.tid for t in ins])
-        at = (lt_attr * len(attrs))() if attrs else _NO_ATTRS
-        for i, (key, val) in enumerate(attrs):
-            at[i].key = key
-            if isinstance(val, float):
-                at[i].is_float = 1
-                at[i].v.f = val
-            else:
-                at[i].is_float = 0
-                at[i].v.i = int(val)
-        outs = (C.c_uint64 * n_out)()
-        self._check(self._lib.lt_op(self._h, OPCODES[name], ids, len(ins), at, len(attrs), outs, n_out))
+        # (argument arrays are reused between calls: recording an op is a hot path of the method,
+        # and building ctypes objects costs more than the call itself)
+        n = len(inputs)
+        ids = self._ids.get(n)
+        if ids is None:
+            ids = self._ids[n] = (C.c_uint64 * max(1, n))()
+        held = None
+        for i, x in enumerate(inputs):
+            if not isinstance(x, Tensor):
+                x = self.scalar(x)
+                held = (held, x)               # alive until the op has been recorded
+            ids[i] = x.tid
+        if attrs:
+            key = tuple(attrs)
+            at = self._attrs.get(key)
+            if at is None:
+                at = (lt_attr * len(key))()
+                for i, (k, val) in enumerate(key):
+                    at[i].key = k
+                    if isinstance(val, float):
+                        at[i].is_float = 1
+                        at[i].v.f = val
+                    else:
+                        at[i].is_float = 0
+                        at[i].v.i = int(val)
+                self._attrs[key] = at
+        else:
+            at = _NO_ATTRS
+        outs = self._outs.get(n_out)
+        if outs is None:
+            outs = self._outs[n_out] = (C.c_uint64 * n_out)()
+        st = self._lib.lt_op(self._h, OPCODES[name], ids, n, at, len(attrs), outs, n_out)
+        if st:
+            self._check(st)
         if n_out == 1:
             return Tensor(self, outs[0])
         return tuple(Tensor(self, outs[k]) for k in range(n_out))

@@ -71,6 +71,20 @@ def _time_steps(step_fn, ctx, steps, warmup):
     return dt_plain, dt, launches, infos
 
 
+def _time_pipelined(record_fn, ctx, steps):
+    """Steps per second when the barrier does not block (section 4's asynchronous execution): the
+    host records step i+1 while the device runs step i; one synchronisation at the end.
+    `record_fn` records one step and returns what must stay alive until its barrier."""
+    _sync()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        keep = record_fn()
+        ctx.barrier(False)
+    del keep
+    _sync()
+    return steps / (time.perf_counter() - t0)
+
+
 def _dominant(launches):
     """Average duration and algorithmic bytes / flops per launch of the kernel family that takes
     the most device time."""
@@ -178,6 +192,12 @@ def run_c2(steps, warmup):
         loss = programs.c2_step(ctx, Xs[i], Ls[i], params, 0.01)
         return ctx.barrier(True)
     dt, dt_prof, launches, infos = _time_steps(step, ctx, steps, warmup)
+
+    def record():
+        i = state["i"] % n_batches
+        state["i"] += 1
+        return programs.c2_step(ctx, Xs[i], Ls[i], params, 0.01)
+    pipelined = _time_pipelined(record, ctx, steps)
     _, _, _, _, _, table = _dominant(launches)
     # the contractions as a family (each is a few microseconds: launch latency, not the matrix cores, bounds them)
     flops = sum(r["flops"] for st in launches for r in st)
@@ -189,7 +209,7 @@ def run_c2(steps, warmup):
     roof["frac"] = roof["achieved"] / roof["peak"]
     extra = {"kernels": table, "cache_hits": sum(i.cache_hit for i in infos), "ns_host_per_step": {
         "collect": int(np.mean([i.ns_collect for i in infos])), "hash": int(np.mean([i.ns_hash for i in infos])),
-        "launch": int(np.mean([i.ns_launch for i in infos]))}}
+        "launch": int(np.mean([i.ns_launch for i in infos]))}, "steps_per_s_non_blocking_barrier": pipelined}
     config = {"workload": "c2: MLP 784-512-512-10 fp32 batch 128, fwd+bwd+SGD, one barrier per step", "regions": int(infos[-1].n_regions)}
 
     def cpu():
@@ -261,6 +281,11 @@ def run_c3(steps, warmup, bsz=32, seq=256, d=1024, ffn=4096, heads=16):
         y, dx = programs.c3_step(ctx, *g, t=state["t"])     # held until the barrier: the layer output and the input gradient are results
         return ctx.barrier(True)
     dt, dt_prof, launches, infos = _time_steps(step, ctx, steps, warmup)
+
+    def record():
+        state["t"] += 1
+        return programs.c3_step(ctx, *g, t=state["t"])
+    pipelined = _time_pipelined(record, ctx, steps)
     _, _, _, _, _, table = _dominant(launches)
     n = len(launches)
     gemm = [r for st in launches for r in st if r["flops"]]
@@ -278,7 +303,7 @@ def run_c3(steps, warmup, bsz=32, seq=256, d=1024, ffn=4096, heads=16):
              "non_gemm_bytes_per_step": sum(r["bytes"] for r in rest) / n,
              "device_ms_per_step": sum(r["ms"] for st in launches for r in st) / n,
              "launches_per_step": len(launches[-1]), "kernels": table,
-             "cache_hits": sum(i.cache_hit for i in infos),
+             "cache_hits": sum(i.cache_hit for i in infos), "steps_per_s_non_blocking_barrier": pipelined,
              "ns_host_per_step": {"collect": int(np.mean([i.ns_collect for i in infos])),
                                   "hash": int(np.mean([i.ns_hash for i in infos])),
                                   "launch": int(np.mean([i.ns_launch for i in infos]))}}
@@ -313,7 +338,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
-              "(the path shards by parameter range / batch, see DESIGN.md)", file=sys.stderr)
+              "(the path would shard by parameter range / batch: every replica records the same trace)", file=sys.stderr)
         sys.exit(2)
     defaults = {"c4": (20, 3), "c1": (200, 10), "c2": (200, 10), "c3": (10, 2), "c5": (100, 10)}
     headline = args.workload or "c4"

@@ -19,7 +19,8 @@ ROCM = os.environ.get("ROCM_PATH", "/opt/rocm")
 HIP_SOURCES = ["lt_k_ew.hip", "lt_k_reduce.hip", "lt_k_rowop.hip", "lt_gemm.hip", "lt_gemm_bf16.hip"]
 CPP_SOURCES = ["lt_api.cpp", "lt_barrier.cpp", "lt_lower.cpp"]
 
-# packed-fp32 VALU ops are switched off for all device code (build flags)
+# packed-fp32 VALU ops are switched off for all device code: some of their forms have given wrong
+# results on this hardware, silently
 HIP_FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-value"]
 CPP_FLAGS = ["-O2", "-std=c++17", "-fPIC", "-Wall", "-D__HIP_PLATFORM_AMD__", f"-I{ROCM}/include"]

@@ -253,10 +253,9 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   if ((a.a.s_col != 1 && a.a.s_row != 1) || (a.b.s_col != 1 && a.b.s_row != 1)) return hipErrorInvalidValue;
   if (a.in_dtype == kBF16) return launch_gemm_bf16(a, s);
   const uint32_t batch = a.batch0 * a.batch1;
-  // big tiles only when they still give every compute unit work
-  const uint64_t big_tiles = (uint64_t)((a.m + 127) / 128) * ((a.n + 127) / 128) * batch;
-  const bool big = big_tiles >= 256;
-  const uint32_t bm = big ? 128 : 64;
+  if (a.tile_m != a.tile_n || (a.tile_m != 64u && a.tile_m != 128u)) return hipErrorInvalidValue;
+  const bool big = a.tile_m == 128u;   // the host picks big tiles only when they still give every compute unit work
+  const uint32_t bm = a.tile_m;
   if (a.splits == 0u) return hipErrorInvalidValue;
   const dim3 grid((a.n + bm - 1) / bm, (a.m + bm - 1) / bm, batch * a.splits);
   if (grid.y > 65535u || grid.z > 65535u) return hipErrorInvalidValue;

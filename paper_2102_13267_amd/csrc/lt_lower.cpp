@@ -1401,12 +1401,17 @@ struct Lowering {
         plan->storages.push_back(ws);
       }
     }
-    if (A.dtype == LT_F32 && !r->sealed) {
-      // the fp32 kernel takes 64 x 64 tiles when there are few; a long k over few tiles is split
-      // so that the chip has about one workgroup per compute unit, each with >= 4 slices of 16
-      const uint64_t tiles = (uint64_t)((m + 63) / 64) * ((n + 63) / 64) * (uint64_t)batch;
+    if (A.dtype == LT_F32) {
+      // a long k over few tiles is split so that the chip has about one workgroup per compute
+      // unit, each with >= 4 slices of 16
+      const uint64_t big_tiles = (uint64_t)((m + 127) / 128) * ((n + 127) / 128) * (uint64_t)batch;
+      // 128 x 128 tiles need half the LDS fragment traffic per flop of 64 x 64 ones: measured
+      // better from 32 big tiles up (k is split to fill the rest of the chip)
+      const uint32_t ts = big_tiles >= 32 ? 128u : 64u;
+      args.tile_m = args.tile_n = ts;
+      const uint64_t tiles = (uint64_t)((m + ts - 1) / ts) * ((n + ts - 1) / ts) * (uint64_t)batch;
       const uint64_t slices = (uint64_t)(kk + 15) / 16;
-      const uint64_t splits = std::min<uint64_t>({256 / std::max<uint64_t>(tiles, 1), slices / 4, 16});
+      const uint64_t splits = r->sealed ? 1 : std::min<uint64_t>({256 / std::max<uint64_t>(tiles, 1), slices / 4, 16});
       if (splits > 1) {
         args.splits = (uint32_t)splits;
         Storage ws;

@@ -62,11 +62,25 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
   return (uint16_t)(u >> 16);
 }
 
-__device__ __forceinline__ float op_gelu(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+// Standard normal CDF Phi(x) = (1 + erf(x / sqrt 2)) / 2 without branches: the five-term rational
+// approximation of erf (Abramowitz & Stegun 7.1.26, |error| <= 1.5e-7 in exact arithmetic) on |x|
+// and the reflection Phi(-x) = 1 - Phi(x).  The library erff is exact to an ulp but takes two
+// divergent polynomial paths, which is most of what a GELU epilogue costs.
+__device__ __forceinline__ float normal_cdf(float x) {
+  const float z = fabsf(x) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
+  float poly = fmaf(1.061405429f, t, -1.453152027f);
+  poly = fmaf(poly, t, 1.421413741f);
+  poly = fmaf(poly, t, -0.284496736f);
+  poly = fmaf(poly, t, 0.254829592f);
+  const float tail = 0.5f * poly * t * __expf(-z * z);   // (1 - erf(z)) / 2
+  return x >= 0.0f ? 1.0f - tail : tail;
+}
+
+__device__ __forceinline__ float op_gelu(float x) { return x * normal_cdf(x); }
 __device__ __forceinline__ float op_gelu_grad(float dy, float x) {
-  const float cdf = 0.5f * (1.0f + erff(x * 0.70710678118654752f));
   const float pdf = 0.39894228040143268f * __expf(-0.5f * x * x);
-  return dy * (cdf + x * pdf);
+  return dy * (normal_cdf(x) + x * pdf);
 }
 
 struct ProgRegs {

@@ -1,16 +1,17 @@
-// Contraction region: C = post(A * B) on the MFMA matrix cores (gfx950), fp32 or bf16 operands,
-// fp32 accumulation.  Operands are addressed through element strides, so transposed, batched and
-// head-split layouts need no copies.  The elementwise chain that consumes the product (bias,
-// activation, residual, optimiser update, cast ...) is interpreted on the accumulator tile before
-// anything is written: the product itself never travels to HBM unless asked for.
+// fp32 contraction region: C = post(A * B) on the MFMA matrix cores (gfx950), fp32 operands and
+// accumulation (bf16 operands: lt_gemm_bf16.hip).  Operands are addressed through element strides,
+// so transposed, batched and head-split layouts need no copies.  The elementwise chain that
+// consumes the product (bias, activation, residual, optimiser update, cast ...) is interpreted on
+// the accumulator tile before anything is written: the product itself never travels to HBM unless
+// asked for.
 //
-// Structure: workgroup tile BM x BN (128 x 128, or 64 x 64 for small problems so that more
-// compute units get a tile), four wavefronts in a 2 x 2 arrangement, each owning a quarter as
-// MFMA 32x32 blocks.  K is walked in slices (16 fp32 / 32 bf16) with register prefetch: the
-// global loads of slice k+1 are issued before the MFMAs of slice k and written to the other LDS
-// buffer afterwards, so HBM latency overlaps the matrix cores.  Global loads are 16 bytes per
-// lane along whichever dimension of the operand is contiguous; an operand whose contraction
-// dimension is not the one the MFMA wants contiguous is transposed on its way into LDS.
+// Structure: workgroup tile 128 x 128 (or 64 x 64 for small problems so that more compute units
+// get a tile), four wavefronts in a 2 x 2 arrangement, each owning a quarter as MFMA 32x32x2
+// blocks.  K is walked in slices of 16 with register prefetch: the global loads of slice k+1 are
+// issued before the MFMAs of slice k and written to the other LDS buffer afterwards.  Global
+// loads are 16 bytes per lane along whichever dimension of the operand is contiguous; an operand
+// whose contiguous dimension is k is transposed on its way into LDS.  A long k over few tiles is
+// split over workgroups (partial products to a workspace, summed by a second launch).
 #include <hip/hip_runtime.h>
 
 #include "lt_gemm_epilogue.h"
@@ -24,7 +25,6 @@ namespace ltk {
 // as uint4.
 template <typename T> struct Elem;
 template <> struct Elem<float> { static constexpr int G = 4; static constexpr int BK = 16; };
-template <> struct Elem<uint16_t> { static constexpr int G = 8; static constexpr int BK = 32; };
 
 // Guarded fetch of G elements at (outer, inner .. inner+G-1); element (o, i) lives at
 // base + o*s_outer + i (unit stride inside the group).  Out-of-range elements read as zero.
@@ -39,27 +39,15 @@ __device__ __forceinline__ uint4 fetch_group(const T* base, int64_t s_outer, uin
   T t[G];
 #pragma unroll
   for (int j = 0; j < G; ++j) t[j] = (inner + j < n_inner) ? src[j] : (T)0;
-  if (sizeof(T) == 4) {
-    v = make_uint4(((const uint32_t*)t)[0], ((const uint32_t*)t)[1], ((const uint32_t*)t)[2], ((const uint32_t*)t)[3]);
-  } else {
-    const uint16_t* h = (const uint16_t*)t;
-    v = make_uint4(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16), h[4] | ((uint32_t)h[5] << 16),
-                   h[6] | ((uint32_t)h[7] << 16));
-  }
+  v = make_uint4(((const uint32_t*)t)[0], ((const uint32_t*)t)[1], ((const uint32_t*)t)[2], ((const uint32_t*)t)[3]);
   return v;
 }
 
-// Per-dtype LDS layouts.
-//   fp32: tile[k][x]  (x = m or n contiguous), row stride BX + 4  -> MFMA 32x32x2 reads one float
-//   bf16: tile[x][k]  (k contiguous),          row stride BK + 8  -> MFMA 32x32x16 reads 8 bf16
+// LDS layout: tile[k][x] (x = m or n contiguous), row stride BX + 4 -> MFMA 32x32x2 reads one float
 template <typename T, int BX> struct Tile;
 template <int BX> struct Tile<float, BX> {
   static constexpr int BK = 16, STRIDE = BX + 4, ELEMS = BK * STRIDE;
 };
-template <int BX> struct Tile<uint16_t, BX> {
-  static constexpr int BK = 32, STRIDE = BK + 8, ELEMS = BX * STRIDE;
-};
-
 // Number of 16-byte groups per lane and k-slice for an operand tile of BX x BK elements.
 template <typename T, int BX> struct Groups {
   static constexpr int N = BX * Elem<T>::BK / Elem<T>::G / kGemmThreads;   // 128: 2, 64: 1
@@ -110,29 +98,6 @@ __device__ __forceinline__ void stash_tile(const GroupRegs<Groups<float, BX>::N>
   }
 }
 
-template <int BX, bool KC>
-__device__ __forceinline__ void stash_tile(const GroupRegs<Groups<uint16_t, BX>::N>& gr, uint16_t* tile) {
-  const uint4* g = gr.g;
-  constexpr int G = 8, BK = 32, STRIDE = Tile<uint16_t, BX>::STRIDE, NG = Groups<uint16_t, BX>::N;
-  const uint32_t t = threadIdx.x;
-#pragma unroll
-  for (int it = 0; it < NG; ++it) {
-    const uint32_t e = it * kGemmThreads + t;
-    if (KC) {
-      const uint32_t x = e / (BK / G), kq = e % (BK / G);
-      *(uint4*)&tile[x * STRIDE + kq * G] = g[it];
-    } else {   // transposing: eight 2-byte writes
-      const uint32_t k = e / (BX / G), xq = e % (BX / G);
-      const uint32_t w[4] = {g[it].x, g[it].y, g[it].z, g[it].w};
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        tile[(xq * G + 2 * j) * STRIDE + k] = (uint16_t)(w[j] & 0xffffu);
-        tile[(xq * G + 2 * j + 1) * STRIDE + k] = (uint16_t)(w[j] >> 16);
-      }
-    }
-  }
-}
-
 // MFMAs of one k-slice.
 template <int BM, int BN, int MB, int NB>
 __device__ __forceinline__ void mma_slice(v16f (&acc)[MB][NB], const float* As, const float* Bs, uint32_t wave_m, uint32_t wave_n,
@@ -153,32 +118,13 @@ __device__ __forceinline__ void mma_slice(v16f (&acc)[MB][NB], const float* As, 
   }
 }
 
-template <int BM, int BN, int MB, int NB>
-__device__ __forceinline__ void mma_slice(v16f (&acc)[MB][NB], const uint16_t* As, const uint16_t* Bs, uint32_t wave_m,
-                                          uint32_t wave_n, uint32_t lane) {
-  constexpr int SA = Tile<uint16_t, BM>::STRIDE, SB = Tile<uint16_t, BN>::STRIDE;
-#pragma unroll
-  for (int kk = 0; kk < 32; kk += 16) {
-    const uint32_t kl = kk + (lane >> 5) * 8;
-    v8bf af[MB], bf[NB];
-#pragma unroll
-    for (int i = 0; i < MB; ++i) af[i] = *(const v8bf*)&As[(wave_m * (MB * 32) + i * 32 + (lane & 31)) * SA + kl];
-#pragma unroll
-    for (int j = 0; j < NB; ++j) bf[j] = *(const v8bf*)&Bs[(wave_n * (NB * 32) + j * 32 + (lane & 31)) * SB + kl];
-#pragma unroll
-    for (int i = 0; i < MB; ++i)
-#pragma unroll
-      for (int j = 0; j < NB; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
-  }
-}
-
 template <typename T, int BM, int BN> struct Smem {
   static constexpr size_t kOperands = 2 * (Tile<T, BM>::ELEMS + Tile<T, BN>::ELEMS) * sizeof(T);   // double buffered
   static constexpr size_t kC = (size_t)BM * (BN + kCPad) * sizeof(float);
   static constexpr size_t kBytes = kOperands > kC ? kOperands : kC;
 };
 
-// T: float or uint16_t (bf16 bits).  AKC / BKC: the operand's contiguous dimension is k.
+// T: float.  AKC / BKC: the operand's contiguous dimension is k.
 template <typename T, int BM, int BN, bool AKC, bool BKC>
 __global__ __launch_bounds__(kGemmThreads) void lt_gemm_kernel(const GemmArgs a) {
   constexpr int MB = BM / 64, NB = BN / 64, BK = Elem<T>::BK;

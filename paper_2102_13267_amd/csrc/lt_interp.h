@@ -54,12 +54,26 @@ __device__ __forceinline__ Quad splat(float s) {
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
 
-// round to nearest even; NaN stays NaN
-__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
+// fp32 -> bf16, round to nearest even, NaN stays NaN: the hardware conversion (two values per
+// instruction; eight instructions per value when spelled out in integer arithmetic).
+typedef __bf16 Bf16x2 __attribute__((ext_vector_type(2)));
+typedef float F32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t f32_to_bf16_pair(float lo, float hi) {
+  const F32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, Bf16x2));
+}
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
+
+// a / b in six instructions instead of the IEEE sequence's twelve: reciprocal estimate (1 ulp), one
+// residual correction.  Correctly rounded except in rare half-way cases (then 1 ulp off); x / x is
+// exactly 1; zeros, infinities and NaNs give what IEEE division gives (the correction is skipped
+// when the residual is not finite).  It does not rescale: a divisor beyond 2^126 or a subnormal
+// one, whose reciprocal leaves the normal range, loses accuracy.
+__device__ __forceinline__ float fast_div(float a, float b) {
+  const float r = __builtin_amdgcn_rcpf(b);
+  const float q = a * r;
+  const float e = fmaf(-b, q, a);
+  return __builtin_isfinite(e) ? fmaf(e, r, q) : q;
 }
 
 // Standard normal CDF Phi(x) = (1 + erf(x / sqrt 2)) / 2 without branches: the five-term rational
@@ -102,26 +116,32 @@ __device__ __forceinline__ float scal_at(const ProgRegs& pr, uint32_t idx) {
 
 // cheap ops: all element lanes at once
 #define LT_MAP(EXPR)                                                \
-  _Pragma("unroll") for (int v = 0; v < kVec; ++v) {                \
-    const float xa = A.v[v], xb = B.v[v];                           \
+  _Pragma("unroll") for (int v = 0; v < kVec * Q; ++v) {            \
+    const float xa = A[v], xb = B[v];                               \
     (void)xb;                                                       \
-    q.v[v] = (EXPR);                                                \
+    q[v] = (EXPR);                                                  \
   }
 // multi-instruction ops: one element lane at a time
 #define LT_MAP_SERIAL(EXPR)                                         \
-  _Pragma("unroll") for (int v = 0; v < kVec; ++v) {                \
-    const float xa = A.v[v], xb = B.v[v];                           \
+  _Pragma("unroll") for (int v = 0; v < kVec * Q; ++v) {            \
+    const float xa = A[v], xb = B[v];                               \
     (void)xb;                                                       \
-    q.v[v] = (EXPR);                                                \
+    q[v] = (EXPR);                                                  \
     __builtin_amdgcn_sched_barrier(0);                              \
   }
 
+// Q = 1: the register file holds NS slots of one 4-vector.  Q = 2: it holds NS/2 slots of TWO
+// 4-vectors (slot s of 4-vector j is element s + j * NS/2 of each register-file vector), and every
+// instruction is fetched, decoded and dispatched once for both.  Fetch, decode and the opcode
+// tree are scalar instructions and branches -- two thirds of what an interpreted instruction
+// costs -- so this halves most of the interpreter's overhead per element with the same registers.
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Wuninitialized"
 #pragma clang diagnostic ignored "-Wsometimes-uninitialized"
 #pragma clang diagnostic ignored "-Wconditional-uninitialized"
-template <int NS>
+template <int NS, int Q = 1>
 __device__ __forceinline__ RF<NS> interp(RF<NS> f, const ProgRegs pr, const uint32_t n) {
+  constexpr uint32_t SL = NS / Q;   // slots per 4-vector
   typename RF<NS>::vec r[kVec];
 #pragma unroll
   for (int v = 0; v < kVec; ++v) r[v] = f.e[v];
@@ -129,38 +149,49 @@ __device__ __forceinline__ RF<NS> interp(RF<NS> f, const ProgRegs pr, const uint
     const uint32_t w = (uint32_t)__builtin_amdgcn_readlane((int)pr.code, (int)pc);
     const uint32_t op = w & 0xffu, d = (w >> 8) & 31u;
     const uint32_t ia = (w >> 13) & 63u, ib = (w >> 19) & 63u, ic = (w >> 25) & 63u;
-    Quad A, B, q;   // B stays undefined for unary ops, which never read it
+    float A[kVec * Q], B[kVec * Q], q[kVec * Q];   // B stays undefined for unary ops, which never read it
     // operand a is always a slot: the lowering puts a scalar operand second (using the
     // reversed form of non-commutative ops) or materialises it with kSplat first
 #pragma unroll
-    for (int v = 0; v < kVec; ++v) A.v[v] = r[v][ia];
+    for (int j = 0; j < Q; ++j)
+#pragma unroll
+      for (int v = 0; v < kVec; ++v) A[j * kVec + v] = r[v][ia + j * SL];
     if (op >= kAdd) {   // binary and ternary ops: operand b is a slot or a scalar-table entry
       if (ib < 32u) {
 #pragma unroll
-        for (int v = 0; v < kVec; ++v) B.v[v] = r[v][ib];
+        for (int j = 0; j < Q; ++j)
+#pragma unroll
+          for (int v = 0; v < kVec; ++v) B[j * kVec + v] = r[v][ib + j * SL];
       } else {
-        B = splat(scal_at(pr, ib - 32u));
+        const float sb = scal_at(pr, ib - 32u);
+#pragma unroll
+        for (int v = 0; v < kVec * Q; ++v) B[v] = sb;
       }
     }
-    q = A;
+#pragma unroll
+    for (int v = 0; v < kVec * Q; ++v) q[v] = A[v];
     switch (op) {
       case kMul: LT_MAP(xa * xb) break;
       case kAdd: LT_MAP(xa + xb) break;
       case kFma: {
-        Quad C;
+        float C[kVec * Q];
         if (ic < 32u) {
 #pragma unroll
-          for (int v = 0; v < kVec; ++v) C.v[v] = r[v][ic];
+          for (int j = 0; j < Q; ++j)
+#pragma unroll
+            for (int v = 0; v < kVec; ++v) C[j * kVec + v] = r[v][ic + j * SL];
         } else {
-          C = splat(scal_at(pr, ic - 32u));
+          const float sc = scal_at(pr, ic - 32u);
+#pragma unroll
+          for (int v = 0; v < kVec * Q; ++v) C[v] = sc;
         }
 #pragma unroll
-        for (int v = 0; v < kVec; ++v) q.v[v] = fmaf(A.v[v], B.v[v], C.v[v]);
+        for (int v = 0; v < kVec * Q; ++v) q[v] = fmaf(A[v], B[v], C[v]);
       } break;
       case kSub: LT_MAP(xa - xb) break;
       case kRsub: LT_MAP(xb - xa) break;
-      case kDiv: LT_MAP_SERIAL(xa / xb) break;
-      case kRdiv: LT_MAP_SERIAL(xb / xa) break;
+      case kDiv: LT_MAP(fast_div(xa, xb)) break;
+      case kRdiv: LT_MAP(fast_div(xb, xa)) break;
       case kMax: LT_MAP((xa != xa || xb != xb) ? (xa + xb) : fmaxf(xa, xb)) break;
       case kMin: LT_MAP((xa != xa || xb != xb) ? (xa + xb) : fminf(xa, xb)) break;
       case kReluGrad: LT_MAP(xb > 0.0f ? xa : 0.0f) break;
@@ -179,13 +210,19 @@ __device__ __forceinline__ RF<NS> interp(RF<NS> f, const ProgRegs pr, const uint
       case kLog: LT_MAP_SERIAL(logf(xa)) break;
       case kTanh: LT_MAP_SERIAL(tanhf(xa)) break;
       case kGelu: LT_MAP_SERIAL(op_gelu(xa)) break;
-      case kSigmoid: LT_MAP_SERIAL(1.0f / (1.0f + expf(-xa))) break;
+      case kSigmoid: LT_MAP_SERIAL(fast_div(1.0f, 1.0f + expf(-xa))) break;
       case kRoundBf16: LT_MAP(bf16_to_f32(f32_to_bf16(xa))) break;
-      case kSplat: q = splat(scal_at(pr, ib - 32u)); break;
+      case kSplat: {
+        const float sb = scal_at(pr, ib - 32u);
+#pragma unroll
+        for (int v = 0; v < kVec * Q; ++v) q[v] = sb;
+      } break;
       default: break;
     }
 #pragma unroll
-    for (int v = 0; v < kVec; ++v) r[v][d] = q.v[v];
+    for (int j = 0; j < Q; ++j)
+#pragma unroll
+      for (int v = 0; v < kVec; ++v) r[v][d + j * SL] = q[j * kVec + v];
   }
   RF<NS> o;
 #pragma unroll
@@ -373,7 +410,8 @@ __device__ __forceinline__ Staged<MAXIN> fetch_inputs_at(const EwProg& p, uint32
 
 // Convert the fetched inputs and move them into slots 0 .. MAXIN-1 (compile-time slot numbers:
 // plain register moves).
-template <int NS, int MAXIN, bool FAST, bool F32>
+// OFF: first slot (NS/2 for the second 4-vector of a two-wide register file).
+template <int NS, int MAXIN, bool FAST, bool F32, int OFF = 0>
 __device__ __forceinline__ RF<NS> place_inputs(RF<NS> f, const EwProg& p, const Staged<MAXIN>& st, uint32_t nvalid) {
   const uint32_t n_in = p.n_in;
 #pragma unroll
@@ -387,7 +425,7 @@ __device__ __forceinline__ RF<NS> place_inputs(RF<NS> f, const EwProg& p, const 
       else if (fetch == kFetchBcast) q = splat(finish_elem<F32>(in.dtype, st.bc[k]));
     }
 #pragma unroll
-    for (int v = 0; v < kVec; ++v) f.e[v][k] = q.v[v];
+    for (int v = 0; v < kVec; ++v) f.e[v][k + OFF] = q.v[v];
   }
   return f;
 }
@@ -461,8 +499,8 @@ template <bool F32 = false>
 __device__ __forceinline__ void store_vec4(void* ptr, uint32_t dtype, uint64_t base, uint32_t lane, const Quad& q) {
   if (!F32 && dtype == kBF16) {
     uint2 u;
-    u.x = (uint32_t)f32_to_bf16(q.v[0]) | ((uint32_t)f32_to_bf16(q.v[1]) << 16);
-    u.y = (uint32_t)f32_to_bf16(q.v[2]) | ((uint32_t)f32_to_bf16(q.v[3]) << 16);
+    u.x = f32_to_bf16_pair(q.v[0], q.v[1]);
+    u.y = f32_to_bf16_pair(q.v[2], q.v[3]);
     char* b = (char*)ptr + base * 2u;
     *(uint2*)(b + (size_t)lane * 2u) = u;
   } else {
@@ -473,14 +511,14 @@ __device__ __forceinline__ void store_vec4(void* ptr, uint32_t dtype, uint64_t b
 
 // Store the outputs of the program for elements i .. i+nvalid-1, i = base + lane (flat,
 // contiguous outputs).
-template <int NS, bool FAST = false, bool F32 = false>
+template <int NS, bool FAST = false, bool F32 = false, int OFF = 0>
 __device__ __forceinline__ void store_outputs(RF<NS> f, const EwProg& p, uint64_t base, uint32_t lane, uint32_t nvalid) {
   const uint32_t n_out = p.n_out;
   if (!FAST) {   // general path: one rolled copy (see load_inputs_general)
 #pragma unroll 1
     for (uint32_t o = 0; o < n_out; ++o) {
       const EwOut& out = p.out[o];
-      const Quad q = rf_get<NS>(f, out.slot);
+      const Quad q = rf_get<NS>(f, out.slot + (uint32_t)OFF);
       if (out.scalar) {
         if (base + lane == 0) store_elem<false>(out.ptr, out.dtype, 0, q.v[0]);
       } else if (p.full_vec_ok && nvalid == (uint32_t)kVec) {
@@ -497,7 +535,7 @@ __device__ __forceinline__ void store_outputs(RF<NS> f, const EwProg& p, uint64_
   for (int o = 0; o < kMaxOut; ++o) {
     if ((uint32_t)o < n_out) {
       const EwOut& out = p.out[o];
-      const Quad q = rf_get<NS>(f, out.slot);
+      const Quad q = rf_get<NS>(f, out.slot + (uint32_t)OFF);
       if (out.scalar) {
         if (base + lane == 0) store_elem<F32>(out.ptr, out.dtype, 0, q.v[0]);
       } else {
@@ -527,11 +565,12 @@ __device__ __forceinline__ void stream_fetch(Stream<NIN, U, BF>& st, const int u
 #pragma unroll
   for (int k = 0; k < NIN; ++k) {
     if (BF) {
-      const uint2 t = *(const uint2*)((const char*)p.in[k].ptr + base * 2u + (size_t)lane * 2u);
+      typedef uint32_t U32x2 __attribute__((ext_vector_type(2)));
+      const U32x2 t = __builtin_nontemporal_load((const U32x2*)((const char*)p.in[k].ptr + base * 2u + (size_t)lane * 2u));
       st.s[k][2 * u] = __uint_as_float(t.x);
       st.s[k][2 * u + 1] = __uint_as_float(t.y);
     } else {
-      const RawVec t = *(const RawVec*)((const char*)p.in[k].ptr + base * 4u + (size_t)lane * 4u);
+      const RawVec t = __builtin_nontemporal_load((const RawVec*)((const char*)p.in[k].ptr + base * 4u + (size_t)lane * 4u));
       st.s[k][4 * u] = t.x; st.s[k][4 * u + 1] = t.y; st.s[k][4 * u + 2] = t.z; st.s[k][4 * u + 3] = t.w;
     }
   }
@@ -554,7 +593,7 @@ __device__ __forceinline__ Quad stream_quad(const Stream<NIN, U, BF>& st, const 
 }
 
 // move vector u (run-time, wave-uniform) of every input into slots 0 .. NIN-1
-template <int NS, int NIN, int U, bool BF>
+template <int NS, int NIN, int U, bool BF, int OFF = 0>
 __device__ __forceinline__ RF<NS> stream_place(RF<NS> f, const Stream<NIN, U, BF> st, const uint32_t u) {
 #pragma unroll
   for (int k = 0; k < NIN; ++k) {
@@ -570,7 +609,7 @@ __device__ __forceinline__ RF<NS> stream_place(RF<NS> f, const Stream<NIN, U, BF
       q.v[0] = t[4 * u]; q.v[1] = t[4 * u + 1]; q.v[2] = t[4 * u + 2]; q.v[3] = t[4 * u + 3];
     }
 #pragma unroll
-    for (int v = 0; v < kVec; ++v) f.e[v][k] = q.v[v];
+    for (int v = 0; v < kVec; ++v) f.e[v][k + OFF] = q.v[v];
   }
   return f;
 }

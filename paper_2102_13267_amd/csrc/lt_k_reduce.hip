@@ -52,7 +52,8 @@ __global__ __launch_bounds__(kBlock) void lt_row_reduce_kernel(const RowArgs a) 
 
 // Global reduction in one launch.  NIN > 0: streamed (U 4-vectors per lane and trip fetched
 // together, a workgroup reading U consecutive tiles); NIN == 0: general path.
-template <int NS, int NIN, int U, bool BF>
+// Q = 2, 4: so many 4-vectors per interpreter dispatch (programs of at most NS/Q slots).
+template <int NS, int NIN, int U, bool BF, int Q>
 __global__ __launch_bounds__(kBlock) void lt_all_reduce_kernel(const AllArgs a) {
   __shared__ float lds[kBlock / 64];
   __shared__ uint32_t is_last;
@@ -79,10 +80,16 @@ __global__ __launch_bounds__(kBlock) void lt_all_reduce_kernel(const AllArgs a) 
         for (int u = 0; u < UU; ++u) acc = fold_vec(a.red, acc, stream_quad<NN, UU, BF>(st, 0, u), kVec);
       } else {
 #pragma unroll 1
-        for (uint32_t u = 0; u < (uint32_t)UU; ++u) {
+        for (uint32_t u = 0; u < (uint32_t)UU; u += Q) {
           RF<NS> f = stream_place<NS, NN, UU, BF>(rf_zero<NS>(), st, u);
-          f = interp<NS>(f, pro_regs, pro_n);
-          acc = fold_vec(a.red, acc, rf_get(f, pro.anchor_slot), kVec);
+          if (Q >= 2) f = stream_place<NS, NN, UU, BF, NS / Q>(f, st, u + 1u);
+          if (Q == 4) {
+            f = stream_place<NS, NN, UU, BF, 2 * (NS / Q)>(f, st, u + 2u);
+            f = stream_place<NS, NN, UU, BF, 3 * (NS / Q)>(f, st, u + 3u);
+          }
+          f = interp<NS, Q>(f, pro_regs, pro_n);
+#pragma unroll
+          for (int j = 0; j < Q; ++j) acc = fold_vec(a.red, acc, rf_get(f, pro.anchor_slot + j * (NS / Q)), kVec);
         }
       }
     }
@@ -292,11 +299,16 @@ hipError_t launch_all_reduce(const AllArgs& a, uint32_t grid, hipStream_t s) {
   const dim3 g(grid), b(kBlock);
   const int kind = stream_kind(a.pro);
   const uint32_t n_in = a.pro.n_in;
-  if (kind == 1 && n_in == 1u) hipLaunchKernelGGL((lt_all_reduce_kernel<16, 1, 8, false>), g, b, 0, s, a);
-  else if (kind == 1 && n_in == 2u) hipLaunchKernelGGL((lt_all_reduce_kernel<16, 2, 4, false>), g, b, 0, s, a);
-  else if (kind == 2 && n_in == 1u) hipLaunchKernelGGL((lt_all_reduce_kernel<16, 1, 8, true>), g, b, 0, s, a);
-  else if (kind == 2 && n_in == 2u) hipLaunchKernelGGL((lt_all_reduce_kernel<16, 2, 8, true>), g, b, 0, s, a);
-  else hipLaunchKernelGGL((lt_all_reduce_kernel<16, 0, 1, false>), g, b, 0, s, a);
+  const bool two = a.pro.n_slots <= 8u;   // the program fits half a register file: two 4-vectors per dispatch
+  if (kind == 1 && n_in == 1u && two) hipLaunchKernelGGL((lt_all_reduce_kernel<32, 1, 8, false, 4>), g, b, 0, s, a);
+  else if (kind == 1 && n_in == 1u) hipLaunchKernelGGL((lt_all_reduce_kernel<16, 1, 8, false, 1>), g, b, 0, s, a);
+  else if (kind == 1 && n_in == 2u && two) hipLaunchKernelGGL((lt_all_reduce_kernel<32, 2, 4, false, 4>), g, b, 0, s, a);
+  else if (kind == 1 && n_in == 2u) hipLaunchKernelGGL((lt_all_reduce_kernel<16, 2, 4, false, 1>), g, b, 0, s, a);
+  else if (kind == 2 && n_in == 1u && two) hipLaunchKernelGGL((lt_all_reduce_kernel<32, 1, 8, true, 4>), g, b, 0, s, a);
+  else if (kind == 2 && n_in == 1u) hipLaunchKernelGGL((lt_all_reduce_kernel<16, 1, 8, true, 1>), g, b, 0, s, a);
+  else if (kind == 2 && n_in == 2u && two) hipLaunchKernelGGL((lt_all_reduce_kernel<32, 2, 8, true, 4>), g, b, 0, s, a);
+  else if (kind == 2 && n_in == 2u) hipLaunchKernelGGL((lt_all_reduce_kernel<16, 2, 8, true, 1>), g, b, 0, s, a);
+  else hipLaunchKernelGGL((lt_all_reduce_kernel<16, 0, 1, false, 1>), g, b, 0, s, a);
   return hipGetLastError();
 }
 hipError_t launch_col_reduce(const ColArgs& a, uint32_t grid_x, uint32_t grid_y, hipStream_t s) {

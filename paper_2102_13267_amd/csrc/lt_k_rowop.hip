@@ -73,8 +73,8 @@ __device__ __forceinline__ void row_store(void* ptr, uint32_t dtype_rt, uint64_t
     if (vec_ok) {
       if (dtype == kBF16) {
         uint2 u;
-        u.x = (uint32_t)f32_to_bf16(q.x) | ((uint32_t)f32_to_bf16(q.y) << 16);
-        u.y = (uint32_t)f32_to_bf16(q.z) | ((uint32_t)f32_to_bf16(q.w) << 16);
+        u.x = f32_to_bf16_pair(q.x, q.y);
+        u.y = f32_to_bf16_pair(q.z, q.w);
         *(uint2*)((uint16_t*)ptr + base + c) = u;
       } else {
         *(float4*)((float*)ptr + base + c) = q;

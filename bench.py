@@ -35,9 +35,13 @@ PROFILED_TRAFFIC = {("c4", "lt_ew_kernel"): 7_516_357_427}
 MFMA_PEAK_TFLOPS = {"bf16": 2516.6, "f32": 157.3}
 
 
+_STREAMS = 4   # --streams: streams a barrier may spread independent launches over
+
+
 def _gpu_ctx(workspace_bytes):
     from paper_2102_13267_amd import Context
     ctx = Context(device=0, workspace_bytes=workspace_bytes)
+    ctx.set_streams(_STREAMS)
     return ctx
 
 
@@ -332,6 +336,8 @@ def main():
     ap.add_argument("--workload", default=None, choices=sorted(WORKLOADS),
                     help="default: c4 as the headline line, plus a short run of every other config under detail.other_configs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--streams", type=int, default=4,
+                    help="streams a barrier may spread independent launches over (1: all on one stream)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy, so that a rocprofv3 --pmc run of this command "
                          "holds a kernel of known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -340,6 +346,8 @@ def main():
         print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
               "(the path would shard by parameter range / batch: every replica records the same trace)", file=sys.stderr)
         sys.exit(2)
+    global _STREAMS
+    _STREAMS = args.streams
     defaults = {"c4": (20, 3), "c1": (200, 10), "c2": (200, 10), "c3": (10, 2), "c5": (100, 10)}
     headline = args.workload or "c4"
     steps = args.steps if args.steps is not None else defaults[headline][0]

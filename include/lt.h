@@ -176,6 +176,13 @@ lt_status lt_dump_ir(lt_ctx* ctx, char* buf, size_t cap, size_t* len);
 /* Region list of the plan used by the last barrier, one region per line. Same buffer rules. */
 lt_status lt_dump_plan(lt_ctx* ctx, char* buf, size_t cap, size_t* len);
 
+/*
+ * Stream schedule of the plan used by the last barrier, one launch per line in enqueue order:
+ * "L<i> <kind> R<region> stream=<0..3> slot=<quarter of the reduction scratch> record=<0|1>
+ * waits=[<earlier launches on other streams>]".  Stream 0 is the caller's.  Same buffer rules.
+ */
+lt_status lt_dump_schedule(lt_ctx* ctx, char* buf, size_t cap, size_t* len);
+
 /* Canonical byte string of the last barrier's trace (what was hashed).  Same buffer rules. */
 lt_status lt_dump_key(lt_ctx* ctx, uint8_t* buf, size_t cap, size_t* len);
 
@@ -195,6 +202,19 @@ typedef struct {
 } lt_launch_record;
 lt_status lt_set_profiling(lt_ctx* ctx, int on);
 lt_status lt_last_launches(lt_ctx* ctx, lt_launch_record* out, int cap, int* n);
+
+/*
+ * Streams a barrier may spread its launches over (1 .. 4, default 4).  Launches of a plan that
+ * do not depend on each other (section 4: the barrier hands the device a whole graph, not a
+ * sequence) run on up to n - 1 side streams of the library's own next to the caller's stream;
+ * every barrier forks them from the caller's stream and joins them into it again before it
+ * returns, so the caller sees the ordering of a single stream.  n = 1 keeps every launch on the
+ * caller's stream.  A plan whose temporaries do not fit the workspace without being recycled
+ * inside the step also runs on one stream.  Barriers that record per-launch timings
+ * (lt_set_profiling) run on one stream so that the timings are those of the kernels alone.
+ * Errors: LT_ERR_ARG (n out of range).
+ */
+lt_status lt_set_streams(lt_ctx* ctx, int n);
 
 /* Message of the last failure on this context (or of lt_init when ctx is NULL). */
 const char* lt_last_error(lt_ctx* ctx);

@@ -17,7 +17,7 @@ LIB = os.path.join(HERE, "liblt.so")
 ROCM = os.environ.get("ROCM_PATH", "/opt/rocm")
 
 HIP_SOURCES = ["lt_k_ew.hip", "lt_k_reduce.hip", "lt_k_rowop.hip", "lt_gemm.hip", "lt_gemm_bf16.hip"]
-CPP_SOURCES = ["lt_api.cpp", "lt_barrier.cpp", "lt_lower.cpp"]
+CPP_SOURCES = ["lt_api.cpp", "lt_barrier.cpp", "lt_lower.cpp", "lt_schedule.cpp"]
 
 # packed-fp32 VALU ops are switched off for all device code: some of their forms have given wrong
 # results on this hardware, silently

@@ -232,6 +232,13 @@ lt_status lt_init(int device, void* hip_stream, void* workspace, size_t workspac
   if (device >= 0) {
     hipError_t e = hipMemsetAsync(ctx->red_tickets, 0, kTickets * sizeof(uint32_t), ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    // side streams for independent launches: default priority, no implicit ordering against the
+    // null stream (every edge to the caller's stream is an explicit event)
+    for (int i = 0; i < kMaxStreams - 1 && e == hipSuccess; ++i) {
+      e = hipStreamCreateWithFlags(&ctx->side[i], hipStreamNonBlocking);
+      if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->join_event[i], hipEventDisableTiming);
+    }
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->fork_event, hipEventDisableTiming);
     if (e != hipSuccess) return fail(nullptr, LT_ERR_DEVICE, std::string("lt_init: ") + hipGetErrorString(e));
   }
   *out = ctx.release();
@@ -243,6 +250,16 @@ lt_status lt_shutdown(lt_ctx* ctx) {
   if (ctx->device >= 0) {
     (void)hipStreamSynchronize(ctx->stream);
     for (hipEvent_t e : ctx->events) (void)hipEventDestroy(e);
+    for (auto& bucket : ctx->cache)
+      for (auto& plan : bucket.second)
+        for (hipEvent_t e : plan->events)
+          if (e) (void)hipEventDestroy(e);
+    for (int i = 0; i < kMaxStreams - 1; ++i) {
+      if (ctx->side[i]) (void)hipStreamSynchronize(ctx->side[i]);
+      if (ctx->side[i]) (void)hipStreamDestroy(ctx->side[i]);
+      if (ctx->join_event[i]) (void)hipEventDestroy(ctx->join_event[i]);
+    }
+    if (ctx->fork_event) (void)hipEventDestroy(ctx->fork_event);
   }
   ctx->handles.clear();
   ctx->nodes.clear();
@@ -602,6 +619,23 @@ lt_status lt_dump_plan(lt_ctx* ctx, char* buf, size_t cap, size_t* len) {
   return copy_out(ctx->last_plan ? ctx->last_plan->text : std::string(), buf, cap, len);
 }
 
+lt_status lt_dump_schedule(lt_ctx* ctx, char* buf, size_t cap, size_t* len) {
+  if (!ctx) return LT_ERR_ARG;
+  std::string s;
+  if (ctx->last_plan) {
+    static const char* const kinds[] = {"EW", "ROW", "ALL", "COL", "ROWOP", "MM", "SPLITPOST"};
+    const Plan& p = *ctx->last_plan;
+    for (size_t i = 0; i < p.launches.size(); ++i) {
+      const Launch& l = p.launches[i];
+      s += "L" + std::to_string(i) + " " + kinds[l.kind] + " R" + std::to_string(l.region) + " stream=" + std::to_string(l.stream) +
+           " slot=" + std::to_string(l.scratch_slot) + " record=" + std::to_string(l.record) + " waits=[";
+      for (size_t w = 0; w < l.waits.size(); ++w) s += (w ? "," : "") + std::to_string(l.waits[w]);
+      s += "]\n";
+    }
+  }
+  return copy_out(s, buf, cap, len);
+}
+
 lt_status lt_dump_key(lt_ctx* ctx, uint8_t* buf, size_t cap, size_t* len) {
   if (!ctx) return LT_ERR_ARG;
   if (len) *len = ctx->last_key.size();
@@ -615,6 +649,13 @@ lt_status lt_stats(lt_ctx* ctx, lt_stats_t* out) {
   ctx->stats.arena_bytes_peak = ctx->arena.peak;
   ctx->stats.live_tensors = ctx->handles.size();
   *out = ctx->stats;
+  return LT_OK;
+}
+
+lt_status lt_set_streams(lt_ctx* ctx, int n) {
+  if (!ctx) return LT_ERR_ARG;
+  if (n < 1 || n > kMaxStreams) return fail(ctx, LT_ERR_ARG, "lt_set_streams: between 1 and 4 streams");
+  ctx->max_streams = n;
   return LT_OK;
 }
 

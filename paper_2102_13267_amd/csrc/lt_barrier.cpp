@@ -182,6 +182,11 @@ static lt_status execute(lt_ctx* ctx, Plan* plan, const Cut& cut, std::vector<Bu
   }
   const bool real = ctx->device >= 0;
   const bool prof = real && ctx->profiling;
+  // Several streams: only when the schedule found independent work, no per-launch timing is
+  // asked for, and the workspace holds every temporary at once (memory given back while the step
+  // is still being enqueued could be handed to a launch that runs next to its last reader).
+  const bool multi = real && !prof && ctx->max_streams > 1 && plan->n_streams > 1 &&
+                     ctx->arena.size - ctx->arena.in_use >= plan->temp_bytes + (plan->temp_bytes >> 3);
   ctx->last_launches.clear();
   if (prof) {
     while (ctx->events.size() < 2 * plan->launches.size()) {
@@ -191,6 +196,13 @@ static lt_status execute(lt_ctx* ctx, Plan* plan, const Cut& cut, std::vector<Bu
       ctx->events.push_back(e);
     }
   }
+  bool forked[kMaxStreams] = {true, false, false, false};
+  if (multi) {
+    plan->events.resize(plan->launches.size(), nullptr);
+    hipError_t e = hipEventRecord(ctx->fork_event, ctx->stream);
+    if (e != hipSuccess) return hip_fail(ctx, "hipEventRecord", e);
+  }
+  std::vector<size_t> deferred;
   std::vector<uint8_t> args;
   size_t pp = 0, sp = 0;
   for (size_t li = 0; li < plan->launches.size(); ++li) {
@@ -219,25 +231,56 @@ static lt_status execute(lt_ctx* ctx, Plan* plan, const Cut& cut, std::vector<Bu
       std::memcpy(args.data() + p.offset, &f, sizeof(float));
     }
     if (real) {
+      // reductions that may run next to each other work in different quarters of the scratch
       if (l.kind == L_ALL) {
         ltk::AllArgs* a = (ltk::AllArgs*)args.data();
-        a->partials = ctx->red_partials;
-        a->ticket = ctx->red_tickets;
+        a->partials = ctx->red_partials + l.scratch_slot * (kPartialFloats / kScratchSlots);
+        a->ticket = ctx->red_tickets + l.scratch_slot * (kTickets / kScratchSlots);
       } else if (l.kind == L_COL) {
         ltk::ColArgs* a = (ltk::ColArgs*)args.data();
-        a->partials = ctx->red_partials;
-        a->tickets = ctx->red_tickets;
+        a->partials = ctx->red_partials + l.scratch_slot * (kPartialFloats / kScratchSlots);
+        a->tickets = ctx->red_tickets + l.scratch_slot * (kTickets / kScratchSlots);
+      }
+      hipStream_t stream = ctx->stream;
+      if (multi) {
+        if (l.stream > 0) stream = ctx->side[l.stream - 1];
+        hipError_t e = hipSuccess;
+        if (!forked[l.stream]) {   // the side stream starts behind everything the caller's stream holds
+          e = hipStreamWaitEvent(stream, ctx->fork_event, 0);
+          forked[l.stream] = true;
+        }
+        for (size_t w = 0; w < l.waits.size() && e == hipSuccess; ++w) e = hipStreamWaitEvent(stream, plan->events[l.waits[w]], 0);
+        if (e != hipSuccess) return hip_fail(ctx, "hipStreamWaitEvent", e);
       }
       if (prof) (void)hipEventRecord(ctx->events[2 * li], ctx->stream);
-      hipError_t e = launch_one(l, args.data(), ctx->stream);
+      hipError_t e = launch_one(l, args.data(), stream);
       if (e != hipSuccess) return hip_fail(ctx, kind_name(l.kind), e);
       if (prof) (void)hipEventRecord(ctx->events[2 * li + 1], ctx->stream);
+      if (multi && l.record) {
+        if (!plan->events[li]) e = hipEventCreateWithFlags(&plan->events[li], hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventRecord(plan->events[li], stream);
+        if (e != hipSuccess) return hip_fail(ctx, "hipEventRecord", e);
+      }
     }
     for (size_t s : dies[li]) {
+      if (multi) {
+        deferred.push_back(s);
+        continue;
+      }
       (*storage_bufs)[s].reset();
       ptr[s] = nullptr;
     }
     ctx->stats.kernels_launched++;
+  }
+  if (multi) {
+    // join: whatever follows on the caller's stream comes after every side stream's work
+    for (int s = 1; s < kMaxStreams; ++s) {
+      if (!forked[s]) continue;
+      hipError_t e = hipEventRecord(ctx->join_event[s - 1], ctx->side[s - 1]);
+      if (e == hipSuccess) e = hipStreamWaitEvent(ctx->stream, ctx->join_event[s - 1], 0);
+      if (e != hipSuccess) return hip_fail(ctx, "stream join", e);
+    }
+    for (size_t s : deferred) (*storage_bufs)[s].reset();
   }
   if (prof) {
     hipError_t e = hipStreamSynchronize(ctx->stream);

@@ -31,6 +31,9 @@ constexpr int kMaxRegionOutputs = 8;
 constexpr int kMaxRegionSlots = 32;
 constexpr int64_t kMaxFinaliserElems = 65536;
 
+constexpr int kMaxStreams = 4;     // the caller's stream + three side streams
+constexpr int kScratchSlots = 4;   // quarters of the reduction scratch, one per concurrent reduction
+
 struct Arena;
 
 // A device buffer.  Borrowed buffers belong to the caller; owned ones are carved out of the
@@ -111,6 +114,7 @@ struct PtrPatch {
   uint32_t launch, offset;   // byte offset of a pointer field inside the launch's argument block
   int32_t storage;
   int64_t byte_offset;
+  uint8_t write = 0;         // 1: the launch writes this storage (0: it only reads it)
 };
 
 struct ScalPatch {
@@ -125,6 +129,11 @@ struct Launch {
   uint32_t grid_x = 1, grid_y = 1;
   std::vector<uint8_t> args;
   uint64_t bytes = 0, flops = 0;
+  // stream schedule (schedule_streams): which of the context's streams runs the launch, the
+  // earlier launches on OTHER streams it has to wait for, whether a later launch on another
+  // stream waits for it, and its quarter of the reduction scratch
+  uint8_t stream = 0, record = 0, scratch_slot = 0;
+  std::vector<uint32_t> waits;
 };
 
 struct RootBind {
@@ -143,6 +152,9 @@ struct Plan {
   std::vector<ScalPatch> scal_patches;
   std::vector<RootBind> roots;
   uint64_t bytes_planned = 0, flops_planned = 0;
+  int n_streams = 1;                 // streams the schedule uses (1: everything on the caller's stream)
+  size_t temp_bytes = 0;             // arena bytes when no temporary is reused inside the step
+  std::vector<hipEvent_t> events;    // one per launch with `record` set (created on first use)
 };
 
 }  // namespace lt
@@ -165,12 +177,18 @@ struct lt_ctx {
   bool profiling = false;
   std::vector<lt_launch_record> last_launches;
   std::vector<hipEvent_t> events;
+  // side streams for launches that do not depend on each other (default priority, created by
+  // lt_init), and the events that fork them from / join them into the caller's stream
+  hipStream_t side[lt::kMaxStreams - 1] = {};
+  hipEvent_t fork_event = nullptr, join_event[lt::kMaxStreams - 1] = {};
+  int max_streams = lt::kMaxStreams;   // lt_set_streams
 };
 
 namespace lt {
 
 constexpr size_t kPartialFloats = 1 << 20;   // reduction partials (4 MiB of the workspace)
 constexpr size_t kTickets = 1024;
+
 
 lt_status fail(lt_ctx* ctx, lt_status code, const std::string& msg);
 size_t dtype_size(uint8_t dtype);
@@ -192,6 +210,8 @@ uint64_t fnv1a64(const uint8_t* p, size_t n);
 
 // lowering (lt_lower.cpp): returns nullptr and sets ctx->err / *status on failure
 std::unique_ptr<Plan> lower(lt_ctx* ctx, const Cut& cut, lt_status* status);
+// stream schedule of a lowered plan (lt_schedule.cpp)
+void schedule_streams(Plan* plan);
 
 }  // namespace lt
 #endif  // LT_CORE_H_

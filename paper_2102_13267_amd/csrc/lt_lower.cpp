@@ -920,7 +920,7 @@ struct Lowering {
     for (auto& is : pb.in_storage)
       plan->ptr_patches.push_back(PtrPatch{launch, (uint32_t)(offset + offsetof(ltk::EwProg, in) + is.first * sizeof(ltk::EwIn) + offsetof(ltk::EwIn, ptr)), is.second, 0});
     for (auto& os : pb.out_storage)
-      plan->ptr_patches.push_back(PtrPatch{launch, (uint32_t)(offset + offsetof(ltk::EwProg, out) + os.first * sizeof(ltk::EwOut) + offsetof(ltk::EwOut, ptr)), os.second, 0});
+      plan->ptr_patches.push_back(PtrPatch{launch, (uint32_t)(offset + offsetof(ltk::EwProg, out) + os.first * sizeof(ltk::EwOut) + offsetof(ltk::EwOut, ptr)), os.second, 0, 1});
     for (auto& sp : pb.scal_patch)
       plan->scal_patches.push_back(ScalPatch{launch, (uint32_t)(offset + offsetof(ltk::EwProg, scal) + sp.index * sizeof(float)), sp.scalar, (uint8_t)(sp.recip ? 1 : 0)});
   }
@@ -1276,7 +1276,7 @@ struct Lowering {
         st = storage_of[a][s] = (int32_t)plan->storages.size() - 1;
       }
       ((ltk::RowOpArgs*)l.args.data())->out_dtype[s] = out_dtype(Val{a, s});
-      plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)(offsetof(ltk::RowOpArgs, out) + s * sizeof(void*)), st, 0});
+      plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)(offsetof(ltk::RowOpArgs, out) + s * sizeof(void*)), st, 0, 1});
       touch(st, launch);
       bytes += (uint64_t)count(out_shape(Val{a, s})) * dtype_size(out_dtype(Val{a, s}));
     }
@@ -1432,7 +1432,7 @@ struct Lowering {
       plan->launches.push_back(std::move(l));
       plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)(offsetof(ltk::GemmArgs, a) + offsetof(ltk::GemmOperand, ptr)), A.storage, 0});
       plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)(offsetof(ltk::GemmArgs, b) + offsetof(ltk::GemmOperand, ptr)), B.storage, 0});
-      plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)offsetof(ltk::GemmArgs, split_ws), ws_storage, 0});
+      plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)offsetof(ltk::GemmArgs, split_ws), ws_storage, 0, 1});
       touch(A.storage, launch);
       touch(B.storage, launch);
       ltk::SplitPostArgs pa{};
@@ -1484,6 +1484,7 @@ std::unique_ptr<Plan> lower(lt_ctx* ctx, const Cut& cut, lt_status* status) {
     // patches must be sorted by launch for the single forward sweep of the executor
     std::stable_sort(plan->ptr_patches.begin(), plan->ptr_patches.end(), [](const PtrPatch& x, const PtrPatch& y) { return x.launch < y.launch; });
     std::stable_sort(plan->scal_patches.begin(), plan->scal_patches.end(), [](const ScalPatch& x, const ScalPatch& y) { return x.launch < y.launch; });
+    schedule_streams(plan.get());
   }
   if (!ok) {
     *status = L.status == LT_OK ? LT_ERR_UNSUPPORTED : L.status;

@@ -95,9 +95,11 @@ def load_library():
         "lt_shape": [P, u64, C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_int64)],
         "lt_dump_ir": [P, C.c_char_p, C.c_size_t, C.POINTER(C.c_size_t)],
         "lt_dump_plan": [P, C.c_char_p, C.c_size_t, C.POINTER(C.c_size_t)],
+        "lt_dump_schedule": [P, C.c_char_p, C.c_size_t, C.POINTER(C.c_size_t)],
         "lt_dump_key": [P, P, C.c_size_t, C.POINTER(C.c_size_t)],
         "lt_stats": [P, C.POINTER(Stats)],
         "lt_set_profiling": [P, i32],
+        "lt_set_streams": [P, i32],
         "lt_last_launches": [P, C.POINTER(LaunchRecord), i32, C.POINTER(i32)],
     }
     for name, argtypes in sig.items():
@@ -367,6 +369,9 @@ class Context:
     def dump_plan(self) -> str:
         return self._dump(self._lib.lt_dump_plan)
 
+    def dump_schedule(self) -> str:
+        return self._dump(self._lib.lt_dump_schedule)
+
     def dump_key(self) -> bytes:
         return self._dump(self._lib.lt_dump_key, binary=True)
 
@@ -377,6 +382,9 @@ class Context:
 
     def set_profiling(self, on: bool):
         self._check(self._lib.lt_set_profiling(self._h, 1 if on else 0))
+
+    def set_streams(self, n: int) -> None:
+        self._check(self._lib.lt_set_streams(self._h, int(n)))
 
     def last_launches(self):
         n = C.c_int()

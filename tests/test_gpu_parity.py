@@ -562,3 +562,110 @@ def test_c3_full_size_batch_elements():
         assert rel_err(yg[b], E.fetch(yr).reshape(seq, d)) <= TOL16, b
         assert rel_err(dxg[b], E.fetch(dxr).reshape(seq, d)) <= TOL16, b
     ctx.close()
+
+
+def _many_live_values(B, x):
+    """Ten values that all stay live across two chains: a program of more than eight slots."""
+    u = [B.exp(B.mul(x, 0.1)), B.tanh(x), B.abs(x), B.square(x), B.neg(x), B.relu(x), B.sigmoid(x),
+         B.sqrt(B.abs(x)), B.mul(x, 0.5), B.add(x, 1.0)]
+    s = u[0]
+    for t in u[1:]:
+        s = B.add(s, t)
+    m = u[0]
+    for t in u[1:]:
+        m = B.mul(m, B.add(B.mul(t, 0.01), 1.0))
+    return B.add(s, m)
+
+
+@pytest.mark.parametrize("n", [4096, (1 << 20) + 8, (1 << 22)])
+def test_programs_wider_than_half_a_register_file(ctx, n):
+    """Reductions and elementwise regions interpret several 4-vectors per dispatch when the program
+    fits a fraction of the register file; this one does not and takes the one-at-a-time path."""
+    E = Eager()
+    x = (rng(77).standard_normal(n) * 0.7).astype(np.float32)
+    got_s = ctx.sum(_many_live_values(ctx, ctx.tensor(x)))
+    got_e = _many_live_values(ctx, ctx.tensor(x))
+    ref_s = E.sum(_many_live_values(E, E.tensor(x)))
+    ref_e = _many_live_values(E, E.tensor(x))
+    check(ctx, E, got_e, ref_e, TOL32, "elementwise")
+    check(ctx, E, got_s, ref_s, TOL32, "global sum")
+    x2 = x[: (n // 1024) * 1024].reshape(-1, 1024) if n >= 1024 else x.reshape(1, -1)
+    got_c = ctx.sum(_many_live_values(ctx, ctx.tensor(x2)), axis=0)
+    ref_c = E.sum(_many_live_values(E, E.tensor(x2)), axis=0)
+    check(ctx, E, got_c, ref_c, TOL32, "column sum")
+
+
+def _stream_case(c, x_np, w_np, w2_np, p_np):
+    """Independent launches with every kind of hazard between them: a wide column reduction next to
+    contractions, a consumer of the reduction, five reductions sharing the scratch, and an in-place
+    update of a tensor that a reduction on another stream reads."""
+    x, w, w2 = c.tensor(x_np), c.tensor(w_np), c.tensor(w2_np)
+    p = c.tensor(p_np.copy(), donatable=True)
+    y0 = c.matmul(x, w)
+    s = c.sum(c.square(x), axis=0)
+    z = c.add(c.matmul(x, w2), s)
+    sums = [c.sum(c.mul(x, float(k + 2)), axis=0) for k in range(5)]
+    colsum = c.sum(c.abs(p), axis=0)
+    c.assign(p, c.mul(p, 0.5))
+    return [y0, s, z, colsum, p] + sums
+
+
+def test_streams_do_not_change_results():
+    """The same plan on one stream and on four: bit-identical results (the kernels, grids and
+    summation orders are the same; only what runs next to what differs), three steps each so that
+    events and scratch quarters are reused; the first step is also held against the oracle."""
+    from paper_2102_13267_amd import Context
+    g = rng(2024)
+    x = g.standard_normal((4096, 1024)).astype(np.float32)
+    w = (g.standard_normal((1024, 512)) * 0.03).astype(np.float32)
+    w2 = (g.standard_normal((1024, 1024)) * 0.03).astype(np.float32)
+    p = g.standard_normal((4096, 1024)).astype(np.float32)
+    results = {}
+    for n_streams in (1, 4):
+        c = Context(device=0, workspace_bytes=1 << 30)
+        c.set_streams(n_streams)
+        steps = []
+        for step in range(3):
+            outs = _stream_case(c, x, w, w2, p)
+            c.barrier()
+            if n_streams == 4 and step == 0:
+                sched = c.dump_schedule()
+                assert "stream=1" in sched or "stream=2" in sched, sched
+            steps.append([c.fetch(t).copy() for t in outs])
+        results[n_streams] = steps
+        c.close()
+    for a_step, b_step in zip(results[1], results[4]):
+        for a, b in zip(a_step, b_step):
+            assert np.array_equal(a, b)
+    E = Eager()
+    ref = _stream_case(E, x, w, w2, p)
+    for got, r in zip(results[4][0], ref):
+        assert rel_err(got, E.fetch(r)) <= TOL32
+
+
+def test_c3_layer_same_on_one_stream_and_four():
+    """Transformer layer step at a size whose bias-gradient reductions are wide enough to leave the
+    caller's stream: every output, gradient moment and parameter bit-identical to the one-stream run."""
+    from paper_2102_13267_amd import Context
+    from workloads.inputs import c3_inputs
+    cfg = (8, 256, 1024, 2048, 16)
+    bsz, seq, d, ffn, heads = cfg
+    inp = c3_inputs(bsz, seq, d, ffn)
+    keys = programs.C3_WEIGHTS + programs.C3_VECTORS
+    results = {}
+    for n_streams in (1, 4):
+        c = Context(device=0, workspace_bytes=3 << 30)
+        c.set_streams(n_streams)
+        P = {k: c.tensor(round_to_bf16(inp[k]), dtype="bf16", donatable=True) for k in keys}
+        M = {k: c.tensor(np.zeros_like(inp[k]), dtype="f32", donatable=True) for k in keys}
+        V = {k: c.tensor(np.zeros_like(inp[k]), dtype="f32", donatable=True) for k in keys}
+        xt, dyt = c.tensor(round_to_bf16(inp["x"]), dtype="bf16"), c.tensor(round_to_bf16(inp["dy"]), dtype="bf16")
+        for step in range(2):
+            y, dx = programs.c3_step(c, xt, dyt, P, M, V, heads, t=step + 1)
+            c.barrier()
+        if n_streams == 4:
+            assert any(f"stream={s}" in c.dump_schedule() for s in (1, 2, 3))
+        results[n_streams] = [c.fetch(y), c.fetch(dx)] + [c.fetch(D[k]) for D in (P, M, V) for k in keys]
+        c.close()
+    for a, b in zip(results[1], results[4]):
+        assert np.array_equal(np.asarray(a).view(np.uint8), np.asarray(b).view(np.uint8))

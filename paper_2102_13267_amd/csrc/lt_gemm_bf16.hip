@@ -169,7 +169,7 @@ constexpr int kStripRows = 64;                       // epilogue strip: 32 rows 
 template <int BM, int BN> struct Smem {
   static constexpr size_t kStage = Geo<BM>::kBytes + Geo<BN>::kBytes;
   static constexpr size_t kOperands = 2 * kStage;
-  static constexpr size_t kStripBytes = (size_t)kStripRows * (BN + kCPad) * sizeof(float);
+  static constexpr size_t kStripBytes = (size_t)BM * (BN + kCPad) * sizeof(float);   // the whole tile
   static constexpr size_t kBytes = kOperands > kStripBytes ? kOperands : kStripBytes;
 };
 
@@ -404,7 +404,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void lt_gemm_bf16_kernel(const Gem
 
   // split-K: this workgroup's partial product goes to its own fp32 copy of the output, row major
   float* const raw = a.splits > 1u ? a.split_ws + (size_t)split * ((size_t)a.batch0 * a.batch1 * a.m * a.n) : nullptr;
-  epilogue_strips<BM, BN, MB, NB>(a, acc, (float*)smem, tile_m, tile_n, wave_m, wave_n, lane, batch, raw);
+  epilogue<BM, BN, MB, NB>(a, acc, (float*)smem, tile_m, tile_n, wave_m, wave_n, lane, batch, raw);
 }
 
 template <int BM, int BN>

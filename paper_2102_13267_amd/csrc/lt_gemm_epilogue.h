@@ -62,22 +62,46 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, const v16f (&acc)[MB
     }
     return;
   }
-  // Whole tile, whole aligned 4-vectors, at most four inputs and none of them strided: no bounds
-  // checks, no divisions (row and column are known), loads of a quad issued together.
-  if (p.fast && p.full_vec_ok && p.n_in <= 4u && tile_m + BM <= a.m && tile_n + BN <= a.n) {
-    const uint32_t row_flat0 = (b0 * a.batch1 + b1) * a.m + tile_m;   // row number in the flattened [rows, n] output
-#pragma unroll 1
+  // Whole tile, whole aligned 4-vectors, at most four inputs (none of them strided) and eight
+  // slots: no bounds checks, no divisions (row and column are known).
+  const bool fast = p.fast && p.full_vec_ok && p.n_in <= 4u && p.n_slots <= 8u && tile_m + BM <= a.m && tile_n + BN <= a.n;
+  const uint32_t row_flat0 = (b0 * a.batch1 + b1) * a.m + tile_m;   // row number in the flattened [rows, n] output
+  if (fast && n_code == 0u && p.n_in == 0u && p.n_out == 1u && !p.out[0].scalar && p.out[0].slot == p.anchor_slot) {
+    // the product itself is the only output: convert and store, nothing to interpret
+    const EwOut& o = p.out[0];
+#pragma unroll 4
     for (uint32_t q = threadIdx.x; q < (uint32_t)(BM * BN / kVec); q += kGemmThreads) {
       const uint32_t r = q / (BN / kVec), c = (q % (BN / kVec)) * kVec;
       const uint32_t i = (uint32_t)(base + (int64_t)(tile_m + r) * a.o_row + tile_n + c);
-      const Staged<4> st = fetch_inputs_at<4, false>(p, i, row_flat0 + r, tile_n + c);
       const float4 t = *(const float4*)&Cs[r * kCStride + c];
+      Quad v;
+      v.v[0] = t.x; v.v[1] = t.y; v.v[2] = t.z; v.v[3] = t.w;
+      store_vec4<false>(o.ptr, o.dtype, 0, i, v);
+    }
+    return;
+  }
+  if (fast) {
+    // two quads per trip (same columns, kGemmThreads quads apart): the interpreter is fetched,
+    // decoded and dispatched once for both (register file = 8 slots x 2)
+    constexpr uint32_t kRowStep = (uint32_t)kGemmThreads / (BN / kVec);
+#pragma unroll 1
+    for (uint32_t q = threadIdx.x; q < (uint32_t)(BM * BN / kVec); q += 2u * kGemmThreads) {
+      const uint32_t ra = q / (BN / kVec), c = (q % (BN / kVec)) * kVec, rb = ra + kRowStep;
+      const uint32_t ia = (uint32_t)(base + (int64_t)(tile_m + ra) * a.o_row + tile_n + c);
+      const uint32_t ib = (uint32_t)(base + (int64_t)(tile_m + rb) * a.o_row + tile_n + c);
+      const Staged<4> sa = fetch_inputs_at<4, false>(p, ia, row_flat0 + ra, tile_n + c);
+      RF<16> f = place_inputs<16, 4, true, false, 0>(rf_zero<16>(), p, sa, kVec);
+      const Staged<4> sb = fetch_inputs_at<4, false>(p, ib, row_flat0 + rb, tile_n + c);
+      f = place_inputs<16, 4, true, false, 8>(f, p, sb, kVec);
+      const float4 ta = *(const float4*)&Cs[ra * kCStride + c], tb = *(const float4*)&Cs[rb * kCStride + c];
       Quad anchor;
-      anchor.v[0] = t.x; anchor.v[1] = t.y; anchor.v[2] = t.z; anchor.v[3] = t.w;
-      RF<16> f = place_inputs<16, 4, true, false>(rf_zero<16>(), p, st, kVec);
+      anchor.v[0] = ta.x; anchor.v[1] = ta.y; anchor.v[2] = ta.z; anchor.v[3] = ta.w;
       f = rf_set<16>(f, p.anchor_slot, anchor);
-      f = interp<16>(f, pr, n_code);
-      store_outputs<16, true, false>(f, p, 0, i, kVec);
+      anchor.v[0] = tb.x; anchor.v[1] = tb.y; anchor.v[2] = tb.z; anchor.v[3] = tb.w;
+      f = rf_set<16>(f, p.anchor_slot + 8u, anchor);
+      f = interp<16, 2>(f, pr, n_code);
+      store_outputs<16, true, false, 0>(f, p, 0, ia, kVec);
+      store_outputs<16, true, false, 8>(f, p, 0, ib, kVec);
     }
     return;
   }

@@ -388,7 +388,8 @@ __device__ __forceinline__ Staged<MAXIN> fetch_inputs(const EwProg& p, uint64_t 
 
 // The same for a caller that already knows the row (i_div) and column (i_mod) of flat element i
 // and promises whole, aligned 4-vectors and no strided input (no division, no slow path).
-template <int MAXIN, bool F32>
+// PIN = false leaves the loads in flight (the caller pins the result where it wants to wait).
+template <int MAXIN, bool F32, bool PIN = true>
 __device__ __forceinline__ Staged<MAXIN> fetch_inputs_at(const EwProg& p, uint32_t i, uint32_t i_div, uint32_t i_mod) {
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Wuninitialized"
@@ -403,7 +404,7 @@ __device__ __forceinline__ Staged<MAXIN> fetch_inputs_at(const EwProg& p, uint32
       else st.bc[k] = fetch_elem<F32>(in.ptr, in.dtype, in.mode == kColVec ? i_div : 0u);
     }
   }
-  pin_staged<MAXIN>(st);
+  if (PIN) pin_staged<MAXIN>(st);
   return st;
 #pragma clang diagnostic pop
 }

@@ -13,6 +13,80 @@ constexpr int kCPad = 4;
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
+// ---- streamed post program -------------------------------------------------------------------
+// Post programs whose inputs are all whole 4-vectors of one element type, addressed like the
+// output (a residual) or by column (a bias): the inputs of U of this lane's quads are fetched
+// into wide register tuples before any is used -- one memory round trip per U quads instead of
+// one per quad, with nothing in the fetch that depends on the program -- and a rolled loop then
+// interprets two quads per dispatch, as the streamed reductions do.  A program with one input
+// streams it twice (no branch in the fetch); the copy lands in a slot that the program writes
+// before it reads.
+template <int BM, int BN, int U, bool BF>
+__device__ __forceinline__ void post_streamed(const GemmArgs& a, const ProgRegs pr, const float* Cs, uint32_t tile_m, uint32_t tile_n,
+                                              int64_t base) {
+  constexpr int kCStride = BN + kCPad;
+  constexpr uint32_t kQuadsPerRow = BN / kVec, kRowStep = (uint32_t)kGemmThreads / kQuadsPerRow;
+  constexpr uint32_t kTrips = (uint32_t)(BM * BN / kVec) / kGemmThreads;   // quads per lane
+  constexpr int UU = (uint32_t)U < kTrips ? U : (int)kTrips;
+  const EwProg& p = a.post;
+  const uint32_t n_code = p.n_code;
+  const uint32_t r0 = threadIdx.x / kQuadsPerRow, c = (threadIdx.x % kQuadsPerRow) * kVec;
+  const uint32_t k1 = p.n_in > 1u ? 1u : 0u;
+  const char* ptr0 = (const char*)p.in[0].ptr;
+  const char* ptr1 = (const char*)p.in[k1].ptr;
+  const bool full0 = p.in[0].mode == kFull, full1 = p.in[k1].mode == kFull;
+  constexpr uint32_t kEsz = BF ? 2u : 4u;
+#pragma unroll 1
+  for (uint32_t pass = 0; pass < kTrips / (uint32_t)UU; ++pass) {
+    Stream<2, UU, BF> st;
+#pragma unroll
+    for (int u = 0; u < UU; ++u) {
+      const uint32_t r = r0 + (pass * (uint32_t)UU + (uint32_t)u) * kRowStep;
+      const uint32_t i = (uint32_t)(base + (int64_t)(tile_m + r) * a.o_row + tile_n + c);
+      const uint32_t e0 = full0 ? i : tile_n + c, e1 = full1 ? i : tile_n + c;
+      if (BF) {
+        typedef uint32_t U32x2 __attribute__((ext_vector_type(2)));
+        const U32x2 t0 = *(const U32x2*)(ptr0 + (size_t)e0 * kEsz), t1 = *(const U32x2*)(ptr1 + (size_t)e1 * kEsz);
+        st.s[0][2 * u] = __uint_as_float(t0.x); st.s[0][2 * u + 1] = __uint_as_float(t0.y);
+        st.s[1][2 * u] = __uint_as_float(t1.x); st.s[1][2 * u + 1] = __uint_as_float(t1.y);
+      } else {
+        const RawVec t0 = *(const RawVec*)(ptr0 + (size_t)e0 * kEsz), t1 = *(const RawVec*)(ptr1 + (size_t)e1 * kEsz);
+        st.s[0][4 * u] = t0.x; st.s[0][4 * u + 1] = t0.y; st.s[0][4 * u + 2] = t0.z; st.s[0][4 * u + 3] = t0.w;
+        st.s[1][4 * u] = t1.x; st.s[1][4 * u + 1] = t1.y; st.s[1][4 * u + 2] = t1.z; st.s[1][4 * u + 3] = t1.w;
+      }
+    }
+#pragma unroll 1
+    for (uint32_t u = 0; u < (uint32_t)UU; u += 2u) {
+      const uint32_t ra = r0 + (pass * (uint32_t)UU + u) * kRowStep, rb = ra + kRowStep;
+      const uint32_t ia = (uint32_t)(base + (int64_t)(tile_m + ra) * a.o_row + tile_n + c);
+      const uint32_t ib = (uint32_t)(base + (int64_t)(tile_m + rb) * a.o_row + tile_n + c);
+      RF<16> f = stream_place<16, 2, UU, BF, 0>(rf_zero<16>(), st, u);
+      f = stream_place<16, 2, UU, BF, 8>(f, st, u + 1u);
+      const float4 ta = *(const float4*)&Cs[ra * kCStride + c], tb = *(const float4*)&Cs[rb * kCStride + c];
+      Quad anchor;
+      anchor.v[0] = ta.x; anchor.v[1] = ta.y; anchor.v[2] = ta.z; anchor.v[3] = ta.w;
+      f = rf_set<16>(f, p.anchor_slot, anchor);
+      anchor.v[0] = tb.x; anchor.v[1] = tb.y; anchor.v[2] = tb.z; anchor.v[3] = tb.w;
+      f = rf_set<16>(f, p.anchor_slot + 8u, anchor);
+      f = interp<16, 2>(f, pr, n_code);
+      store_outputs<16, true, false, 0>(f, p, 0, ia, kVec);
+      store_outputs<16, true, false, 8>(f, p, 0, ib, kVec);
+    }
+  }
+}
+
+// Host-independent test (wave-uniform): can the post program be streamed, and as which element
+// type?  0 = no, 1 = fp32, 2 = bf16.
+__device__ __forceinline__ int post_stream_kind(const EwProg& p) {
+  if (p.n_in == 0u || p.n_in > 2u) return 0;
+  const uint32_t dt = p.in[0].dtype;
+  for (uint32_t k = 0; k < p.n_in; ++k) {
+    const EwIn& in = p.in[k];
+    if (in.fetch != kFetchVec4 || (in.mode != kFull && in.mode != kRowVec) || in.dtype != dt) return 0;
+  }
+  return dt == kF32 ? 1 : dt == kBF16 ? 2 : 0;
+}
+
 // ---- epilogue ------------------------------------------------------------------------------
 // The accumulators leave the MFMA layout (a lane owns 4-row column segments) through LDS: the
 // tile is written once, then every lane walks it in row-major 4-element quads, so the post
@@ -79,6 +153,17 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, const v16f (&acc)[MB
       store_vec4<false>(o.ptr, o.dtype, 0, i, v);
     }
     return;
+  }
+  if (fast) {
+    const int sk = post_stream_kind(p);
+    if (sk == 2) {
+      post_streamed<BM, BN, 8, true>(a, pr, Cs, tile_m, tile_n, base);
+      return;
+    }
+    if (sk == 1) {
+      post_streamed<BM, BN, 8, false>(a, pr, Cs, tile_m, tile_n, base);
+      return;
+    }
   }
   if (fast) {
     // two quads per trip (same columns, kGemmThreads quads apart): the interpreter is fetched,

@@ -148,6 +148,14 @@ lt_status lt_assign(lt_ctx* ctx, lt_tensor dst, lt_tensor src);
 lt_status lt_release(lt_ctx* ctx, lt_tensor t);
 
 /*
+ * The same for n handles at once (ts: host array of n ids).  A front end that learns of dead
+ * tensors one by one (a garbage collector) can hand them over in one call before the next
+ * barrier: liveness only matters when the trace is cut.  Every valid id is released; an unknown
+ * one is skipped and reported as LT_ERR_HANDLE after the others have been released.
+ */
+lt_status lt_release_many(lt_ctx* ctx, const lt_tensor* ts, size_t n);
+
+/*
  * Barrier (section 4: mark_step / LazyTensorBarrier).  Evaluates the pending computation of
  * every live tensor: cut, canonical order, hash, cache lookup, lowering on a miss, kernel
  * launches on the context's stream, then every evaluated handle is rebound to its data.

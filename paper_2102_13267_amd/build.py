@@ -9,11 +9,13 @@ import concurrent.futures
 import os
 import subprocess
 import sys
+import sysconfig
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liblt.so")
+REC = os.path.join(HERE, "_ltrec" + (sysconfig.get_config_var("EXT_SUFFIX") or ".so"))   # recording fast path of the binding
 ROCM = os.environ.get("ROCM_PATH", "/opt/rocm")
 
 HIP_SOURCES = ["lt_k_ew.hip", "lt_k_reduce.hip", "lt_k_rowop.hip", "lt_gemm.hip", "lt_gemm_bf16.hip"]
@@ -67,6 +69,13 @@ def build(force: bool = False, verbose: bool = True) -> str:
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError(f"link failed: {' '.join(cmd)}\n{r.stdout}{r.stderr}")
+    # the binding's recording fast path: a CPython extension, plain C, no dependency on liblt.so
+    rec_src = os.path.join(CSRC, "ltrec_module.c")
+    if force or not os.path.exists(REC) or os.path.getmtime(rec_src) > os.path.getmtime(REC):
+        cmd = ["gcc", "-O2", "-fPIC", "-shared", "-Wall", f"-I{sysconfig.get_paths()['include']}", rec_src, "-o", REC]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"compile failed: {' '.join(cmd)}\n{r.stdout}{r.stderr}")
     return LIB
 
 

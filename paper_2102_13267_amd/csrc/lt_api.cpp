@@ -536,6 +536,21 @@ lt_status lt_release(lt_ctx* ctx, lt_tensor t) {
   return LT_OK;
 }
 
+lt_status lt_release_many(lt_ctx* ctx, const lt_tensor* ts, size_t n) {
+  if (!ctx || (n && !ts)) return LT_ERR_ARG;
+  lt_status st = LT_OK;
+  for (size_t i = 0; i < n; ++i) {
+    Handle* h = find(ctx, ts[i]);
+    if (!h) {
+      st = fail(ctx, LT_ERR_HANDLE, "lt_release_many: unknown or released tensor id");
+      continue;
+    }
+    unbind(h);
+    ctx->handles.erase(ts[i]);
+  }
+  return st;
+}
+
 lt_status lt_shape(lt_ctx* ctx, lt_tensor t, lt_dtype* dtype, int* rank, int64_t* dims) {
   if (!ctx) return LT_ERR_ARG;
   Handle* h = find(ctx, t);

@@ -98,6 +98,7 @@ def load_library():
         "lt_dump_schedule": [P, C.c_char_p, C.c_size_t, C.POINTER(C.c_size_t)],
         "lt_dump_key": [P, P, C.c_size_t, C.POINTER(C.c_size_t)],
         "lt_stats": [P, C.POINTER(Stats)],
+        "lt_release_many": [P, C.POINTER(C.c_uint64), C.c_size_t],
         "lt_set_profiling": [P, i32],
         "lt_set_streams": [P, i32],
         "lt_last_launches": [P, C.POINTER(LaunchRecord), i32, C.POINTER(i32)],
@@ -108,11 +109,22 @@ def load_library():
         fn.restype = C.c_int
     lib.lt_last_error.argtypes = [P]
     lib.lt_last_error.restype = C.c_char_p
+    # the recording fast path makes the same calls from C; it gets the entry points' addresses
+    try:
+        from . import _ltrec
+    except ImportError as e:
+        raise RuntimeError("paper_2102_13267_amd/_ltrec extension is missing: run python -m paper_2102_13267_amd.build") from e
+    addr = lambda fn: C.cast(fn, C.c_void_p).value
+    _ltrec.init(addr(lib.lt_op), addr(lib.lt_scalar), addr(lib.lt_release), addr(lib.lt_last_error))
+    global _REC
+    _REC = _ltrec
     _LIB = lib
     return lib
 
 
 _NO_ATTRS = (lt_attr * 1)()   # what an op without attributes passes (never read)
+_NO_ATTRS_ADDR = C.addressof(_NO_ATTRS)
+_REC = None                   # the _ltrec extension (set by load_library)
 
 
 class Tensor:
@@ -152,9 +164,11 @@ class Tensor:
         self._shape = None if v is None else tuple(v)
 
     def __del__(self):
+        # (liveness matters when the trace is cut, not before: dead ids are collected here and
+        # handed over in one call -- see Context._flush)
         ctx = self.ctx
-        if ctx is not None and ctx._h:
-            ctx._lib.lt_release(ctx._h, self.tid)
+        if ctx is not None:
+            ctx._dead.append(self.tid)
 
     def __repr__(self):
         return f"Tensor(id={self.tid}, {self.dtype}{list(self.shape)})"
@@ -168,6 +182,7 @@ class Context:
         self._lib = load_library()
         self._h = C.c_void_p()
         self._ids, self._outs, self._attrs = {}, {}, {}     # reusable ctypes argument arrays of op()
+        self._dead = []                                     # ids of dropped tensors, not yet released
         self._torch = None
         self._workspace = None
         if device is None:
@@ -189,15 +204,29 @@ class Context:
     def _check_init(self, st):
         if st != 0:
             raise LtError(st, (self._lib.lt_last_error(None) or b"").decode())
+        self._hv = self._h.value or 0   # the context pointer as a plain int, for the recording fast path
 
     def _check(self, st):
         if st != 0:
             raise LtError(st, (self._lib.lt_last_error(self._h) or b"").decode())
 
+    def _flush(self):
+        """Release the tensors that Python dropped since the last call (one call for all of them).
+        Runs before anything that looks at liveness: barrier, fetch, the dumps, the statistics."""
+        dead = self._dead
+        if dead and self._h:
+            self._dead = []
+            arr = (C.c_uint64 * len(dead))(*dead)
+            self._lib.lt_release_many(self._h, arr, len(dead))
+        elif dead:
+            self._dead = []
+
     def close(self):
         if self._h:
+            self._flush()
             self._lib.lt_shutdown(self._h)
             self._h = C.c_void_p()
+            self._hv = 0
 
     def __del__(self):
         try:
@@ -247,43 +276,32 @@ class Context:
         return x if isinstance(x, Tensor) else self.scalar(x)
 
     def op(self, name, inputs, attrs=(), n_out=1):
-        # (argument arrays are reused between calls: recording an op is a hot path of the method,
-        # and building ctypes objects costs more than the call itself)
-        n = len(inputs)
-        ids = self._ids.get(n)
-        if ids is None:
-            ids = self._ids[n] = (C.c_uint64 * max(1, n))()
-        held = None
-        for i, x in enumerate(inputs):
-            if not isinstance(x, Tensor):
-                x = self.scalar(x)
-                held = (held, x)               # alive until the op has been recorded
-            ids[i] = x.tid
+        # recording an op is a hot path of the method: the call goes through the C fast path, which
+        # also turns Python numbers among the operands into scalar tensors that live for the call
         if attrs:
             key = tuple(attrs)
             at = self._attrs.get(key)
             if at is None:
-                at = (lt_attr * len(key))()
+                arr = (lt_attr * len(key))()
                 for i, (k, val) in enumerate(key):
-                    at[i].key = k
+                    arr[i].key = k
                     if isinstance(val, float):
-                        at[i].is_float = 1
-                        at[i].v.f = val
+                        arr[i].is_float = 1
+                        arr[i].v.f = val
                     else:
-                        at[i].is_float = 0
-                        at[i].v.i = int(val)
-                self._attrs[key] = at
+                        arr[i].is_float = 0
+                        arr[i].v.i = int(val)
+                at = self._attrs[key] = (C.addressof(arr), len(key), arr)   # (arr is kept alive here)
+            addr, n_attr = at[0], at[1]
         else:
-            at = _NO_ATTRS
-        outs = self._outs.get(n_out)
-        if outs is None:
-            outs = self._outs[n_out] = (C.c_uint64 * n_out)()
-        st = self._lib.lt_op(self._h, OPCODES[name], ids, n, at, len(attrs), outs, n_out)
-        if st:
-            self._check(st)
+            addr, n_attr = _NO_ATTRS_ADDR, 0
+        try:
+            r = _REC.op(self._hv, OPCODES[name], inputs, addr, n_attr, n_out)
+        except _REC.Error as e:
+            raise LtError(e.args[0], e.args[1]) from None
         if n_out == 1:
-            return Tensor(self, outs[0])
-        return tuple(Tensor(self, outs[k]) for k in range(n_out))
+            return Tensor(self, r)
+        return tuple(Tensor(self, t) for t in r)
 
     # ---- the tensor API shared with the oracle's back ends -------------------------------------------
     def neg(self, x): return self.op("neg", [x])
@@ -331,17 +349,20 @@ class Context:
         dst._dtype, dst._shape = src._dtype, src._shape   # (unknown stays unknown: asked for on demand)
 
     def release(self, t: Tensor):
+        self._flush()
         self._check(self._lib.lt_release(self._h, t.tid))
         t.ctx = None
 
     # ---- barrier, fetch, diagnostics -----------------------------------------------------------------------
     def barrier(self, blocking=True) -> BarrierInfo:
+        self._flush()
         info = BarrierInfo()
         self._check(self._lib.lt_barrier(self._h, 1 if blocking else 0, C.byref(info)))
         return info
 
     def fetch(self, t: Tensor) -> np.ndarray:
         """Blocking barrier if needed, then device-to-host copy.  bf16 comes back as float32."""
+        self._flush()
         code = DTYPES[t.dtype]
         n = int(np.prod(t.shape, dtype=np.int64)) if t.shape else 1
         np_t = {0: np.float32, 1: np.uint16, 2: np.int32, 3: np.int64}[code]
@@ -357,6 +378,7 @@ class Context:
         return p.value or 0
 
     def _dump(self, fn, binary=False):
+        self._flush()
         n = C.c_size_t()
         self._check(fn(self._h, None, 0, C.byref(n)))
         buf = C.create_string_buffer(n.value + 1)
@@ -376,6 +398,7 @@ class Context:
         return self._dump(self._lib.lt_dump_key, binary=True)
 
     def stats(self) -> Stats:
+        self._flush()
         s = Stats()
         self._check(self._lib.lt_stats(self._h, C.byref(s)))
         return s

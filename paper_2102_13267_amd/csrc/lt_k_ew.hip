@@ -1,6 +1,8 @@
 // Elementwise fused region: one coalesced HBM pass; the whole chain is interpreted in registers.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "lt_interp.h"
 #include "lt_launch.h"
 
@@ -30,6 +32,100 @@ __global__ __launch_bounds__(kBlock) void lt_ew_kernel(const EwArgs a) {
     f = interp<NS>(f, pr, n_code);
     store_outputs<NS, FAST, F32>(f, p, base, lane, nvalid);
   }
+}
+
+// ---- streamed elementwise region --------------------------------------------------------------
+// For fp32 programs of at most eight slots whose inputs are whole 4-vectors addressed like the
+// output, plus at most two device scalars (a clipping factor, say).  Which input is which is
+// sorted out on the host (EwStreamArgs), so that the kernel's loads are unconditional: a workgroup
+// takes two tiles per trip, the NV vector inputs of both are fetched back to back, and the
+// interpreter runs once for both (register file = 8 slots x 2).  A program with fewer than NV
+// vector inputs loads one of them again (same slot, same data).  Tiles without a partner -- an odd
+// one, a last one that not every lane takes part in -- go through the same code with both halves
+// on the same tile: they load the same values before either stores, and store the same results.
+struct EwStreamArgs {
+  EwProg prog;
+  uint32_t vin[4];    // input numbers of the vector inputs (padded with the first)
+  uint32_t sin[2];    // input numbers of the device scalars
+  uint32_t n_sin, pad;
+};
+
+template <int NV>
+__global__ __launch_bounds__(kBlock) void lt_ew_stream_kernel(const EwStreamArgs a) {
+  const EwProg& p = a.prog;
+  const uint64_t n = p.n;
+  constexpr uint64_t kTile = (uint64_t)kBlock * kVec;
+  const uint64_t ntiles = (n + kTile - 1) / kTile;
+  const uint64_t npairs = (n / kTile) / 2;            // pairs of tiles that every lane takes part in
+  const uint64_t ntrips = npairs + (ntiles - 2 * npairs);
+  const ProgRegs pr = load_prog_regs(p);
+  const uint32_t n_code = p.n_code;
+  const uint32_t lane = threadIdx.x * kVec;
+  const char* vp[NV];
+  uint32_t vslot[NV];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    vslot[j] = a.vin[j];
+    vp[j] = (const char*)p.in[vslot[j]].ptr;
+  }
+  float sval[2] = {0.0f, 0.0f};
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+    if ((uint32_t)j < a.n_sin) sval[j] = *(const float*)p.in[a.sin[j]].ptr;
+  for (uint64_t trip = blockIdx.x; trip < ntrips; trip += gridDim.x) {
+    const bool pair = trip < npairs;
+    const uint64_t t0 = pair ? 2 * trip : npairs + trip, t1 = pair ? t0 + 1 : t0;
+    const uint64_t base0 = t0 * kTile, base1 = t1 * kTile;
+    if ((uint64_t)lane >= n - base0) continue;   // (only in the last tile, which is its own partner)
+    RawVec v0[NV], v1[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      v0[j] = *(const RawVec*)(vp[j] + (base0 + lane) * 4u);
+      v1[j] = *(const RawVec*)(vp[j] + (base1 + lane) * 4u);
+    }
+    RF<16> f = rf_zero<16>();
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      Quad q;
+      q.v[0] = v0[j].x; q.v[1] = v0[j].y; q.v[2] = v0[j].z; q.v[3] = v0[j].w;
+      f = rf_set<16>(f, vslot[j], q);
+      q.v[0] = v1[j].x; q.v[1] = v1[j].y; q.v[2] = v1[j].z; q.v[3] = v1[j].w;
+      f = rf_set<16>(f, vslot[j] + 8u, q);
+    }
+    for (uint32_t j = 0; j < a.n_sin; ++j) {
+      const Quad q = splat(j == 0u ? sval[0] : sval[1]);
+      f = rf_set<16>(f, a.sin[j], q);
+      f = rf_set<16>(f, a.sin[j] + 8u, q);
+    }
+    f = interp<16, 2>(f, pr, n_code);
+    store_outputs<16, true, true, 0>(f, p, base0, lane, kVec);
+    store_outputs<16, true, true, 8>(f, p, base1, lane, kVec);
+  }
+}
+
+// Host side: fill in EwStreamArgs if the program qualifies.
+static bool make_stream_args(const EwProg& p, EwStreamArgs* out) {
+  if (!p.fast || !p.all_f32 || p.n_slots > 8u || p.n_in == 0u) return false;
+  uint32_t nv = 0, ns = 0;
+  for (uint32_t k = 0; k < p.n_in; ++k) {
+    const EwIn& in = p.in[k];
+    if (in.fetch == kFetchVec4 && in.mode == kFull) {
+      if (nv == 4u) return false;
+      out->vin[nv++] = k;
+    } else if (in.fetch == kFetchBcast && in.mode == kScalar) {
+      if (ns == 2u) return false;
+      out->sin[ns++] = k;
+    } else {
+      return false;
+    }
+  }
+  if (nv == 0u) return false;
+  for (uint32_t j = nv; j < 4u; ++j) out->vin[j] = out->vin[0];
+  for (uint32_t j = ns; j < 2u; ++j) out->sin[j] = 0u;
+  out->n_sin = ns;
+  out->pad = nv;
+  out->prog = p;
+  return true;
 }
 
 // Second half of a split-K contraction: add the splits' partial products (fixed order, so the
@@ -79,6 +175,16 @@ hipError_t launch_ew(const EwArgs& a, uint32_t grid, hipStream_t s) {
   const EwProg& p = a.prog;
   const dim3 g(grid), b(kBlock);
   const bool f16 = p.fast && p.n_slots <= 16u;
+  EwStreamArgs sa;
+  if (make_stream_args(p, &sa)) {
+    const uint64_t tiles = (p.n + 1023) / 1024;
+    // one trip per workgroup: measured 5.27 TB/s on 1 GiB operands against 4.3 with 8192 workgroups
+    // walking the same tiles with a grid stride (the loop stays for spaces beyond 2^31 trips)
+    const dim3 g2((uint32_t)std::max<uint64_t>(1, std::min<uint64_t>((tiles + 1) / 2, 0x7fffffffull)));
+    if (sa.pad <= 2u) hipLaunchKernelGGL((lt_ew_stream_kernel<2>), g2, b, 0, s, sa);
+    else hipLaunchKernelGGL((lt_ew_stream_kernel<4>), g2, b, 0, s, sa);
+    return hipGetLastError();
+  }
   if (f16 && p.all_f32 && p.n_in <= 4u) hipLaunchKernelGGL((lt_ew_kernel<16, 4, true, true>), g, b, 0, s, a);
   else if (f16 && p.all_f32 && p.n_in <= 6u) hipLaunchKernelGGL((lt_ew_kernel<16, 6, true, true>), g, b, 0, s, a);
   else if (f16 && p.all_f32) hipLaunchKernelGGL((lt_ew_kernel<16, 8, true, true>), g, b, 0, s, a);

@@ -228,3 +228,38 @@ def test_middle_axis_reduction_is_reported_unsupported_at_the_barrier():
         ctx.barrier()
     assert e.value.status == 5
     del s
+
+
+def test_recording_fast_path_numbers_and_liveness():
+    """The binding records through its C extension: Python and NumPy numbers among the operands
+    become scalar tensors that live for the call only; tensors that Python drops are released in
+    one call before the trace is cut, so liveness at the barrier is what it was with eager release."""
+    ctx = Context()
+    a = ctx.tensor(np.zeros((4, 8), np.float32))
+    base = ctx.stats().live_tensors
+    outs = [ctx.mul(a, 2), ctx.mul(a, 2.5), ctx.mul(a, np.float32(0.5)), ctx.add(a, a, alpha=np.float64(3.0))]
+    assert ctx.stats().live_tensors == base + len(outs)      # no scalar temporary is left behind
+    with pytest.raises(TypeError):
+        ctx.mul(2.0, "two")                                  # not a tensor, not a number (the 2.0 is released again)
+    assert ctx.stats().live_tensors == base + len(outs)
+    dropped = ctx.tanh(outs[0])
+    del dropped                                              # dead before the barrier: not a root
+    info = ctx.barrier()
+    assert info.n_roots == len(outs)
+    del outs
+    assert ctx.stats().live_tensors == base
+
+
+def test_release_many_reports_a_stale_id_after_releasing_the_rest():
+    ctx = Context()
+    lib = load_library()
+    a = ctx.tensor(np.zeros((4,), np.float32))
+    ts = [ctx.neg(a) for _ in range(3)]
+    ids = [t.tid for t in ts]
+    for t in ts:
+        t.ctx = None                                         # (released by hand below, not by __del__)
+    arr = (ctypes.c_uint64 * 4)(ids[0], 123456789, ids[1], ids[2])
+    assert lib.lt_release_many(ctx._h, arr, 4) == 2          # the unknown id is reported ...
+    for i in ids:
+        assert lib.lt_release(ctx._h, i) == 2                # ... and the others are gone
+    assert lib.lt_release_many(ctx._h, None, 0) == 0

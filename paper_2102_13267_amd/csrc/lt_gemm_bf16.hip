@@ -164,119 +164,105 @@ __device__ __forceinline__ v8bf fragment(const char* tile, uint32_t x_blk, uint3
   }
 }
 
-constexpr int kStripRows = 64;                       // epilogue strip: 32 rows of each wave row
+// ---- whole tiles: global memory -> LDS without passing through registers -----------------------
+// `global_load_lds_dwordx4`: every lane names its own 16 global bytes, the hardware writes them to
+// LDS at a wave-uniform base + lane * 16 (checked with an in-bounds probe), so a wave instruction
+// fills 1 KiB of consecutive LDS.  Tiles are therefore dense (no row padding), and bank conflicts
+// of the fragment reads are avoided by a swizzle instead: the 16-byte chunk at (row, c) lives at
+// position c ^ f(row) of its row.  The swizzle costs nothing in the loop: it is folded into each
+// lane's global offset (which chunk it fetches for its LDS slot) and into the fragment addresses.
+//   [x][k] tile (k contiguous in memory): rows of 64 bytes, f(x) = (x >> 2) & 3 -- the sixteen rows
+//     that one cycle of a ds_read_b128 touches then cover all sixteen 16-byte bank groups;
+//   [k][x] tile (x contiguous): rows of BX * 2 bytes, f(k) = (k & 3) << 2 for 256-byte rows
+//     (((k >> 1) & 1) << 2 for 128-byte rows): the four k rows of a transposing read land in four
+//     different 64-byte bank ranges.
+template <int BX, bool KC> struct Dense {
+  static constexpr uint32_t kBytes = BX * 64;            // BX x 32 bf16
+  static constexpr uint32_t kInstr = BX / 64;            // wave instructions per slice (4 waves x 1 KiB each)
+  static constexpr uint32_t kPerRow = BX / 8;            // chunks per k row of a [k][x] tile
+  static constexpr uint32_t kRowsPer256 = 256 / (BX * 2) ? 256 / (BX * 2) : 1;   // [k][x] rows per 256 bytes
+  __device__ static __forceinline__ uint32_t swz_k(uint32_t k) { return ((k / kRowsPer256) & (4u / kRowsPer256 - 1u)) << 2; }
+  __device__ static __forceinline__ uint32_t swz_x(uint32_t x) { return (x >> 2) & 3u; }
+};
+
+// This lane's byte offset from the (wave-uniform) origin of an instruction's 64 rows (KC) or
+// 256 / kPerRow k rows (otherwise): the same for every instruction and every slice.
+template <int BX, bool KC>
+__device__ __forceinline__ uint32_t dma_lane_offset(int64_t s_x, int64_t s_k) {
+  typedef Dense<BX, KC> D;
+  const uint32_t t = threadIdx.x;
+  if (KC) {
+    const uint32_t row = t >> 2, c = (t & 3u) ^ D::swz_x(row);
+    return (uint32_t)((row * s_x + c * 8u) * 2);
+  }
+  const uint32_t k = t / D::kPerRow, xc = (t % D::kPerRow) ^ D::swz_k(k);
+  return (uint32_t)((k * s_k + xc * 8u) * 2);
+}
+
+// One wave instruction of such a copy.  Written in assembly on purpose: the compiler orders every
+// later LDS read behind every copy it knows to be in flight (and loses track of them around a
+// loop's back edge), so a pipeline deeper than one slice needs copies it does not know about and
+// waits that the code spells out (landed(), below).  M0 holds the LDS base of the instruction;
+// nothing else in the loop uses it, and the interpreter's register indexing sets it afresh.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void copy_1k(const void* gptr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_base), "v"(gptr) : "memory", "m0");
+}
+#pragma clang diagnostic pop
+
+// Wait until at most `outstanding` of this wave's copies are still in flight (they complete in
+// order).  s_waitcnt immediate: vmcnt in bits 3:0 and 15:14, the other counters left alone.
+template <uint32_t outstanding>
+__device__ __forceinline__ void landed() {
+  static_assert(outstanding < 64u, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt((int)((outstanding & 15u) | ((outstanding >> 4) << 14) | 0x0f70u));
+}
+
+// Start the copy of the slice at k0 of the BX-wide panel at x0 into the tile at LDS address `tile`.
+template <int BX, bool KC>
+__device__ __forceinline__ void dma_tile(const uint16_t* base, int64_t s_x, int64_t s_k, uint32_t x0, uint32_t k0, uint32_t lane_off,
+                                         uint32_t tile, uint32_t wave) {
+  typedef Dense<BX, KC> D;
+  constexpr uint32_t rows_per_instr = KC ? 64u : (uint32_t)kGemmThreads / D::kPerRow;
+#pragma unroll
+  for (uint32_t it = 0; it < D::kInstr; ++it) {
+    const uint16_t* u = KC ? base + (int64_t)(x0 + it * rows_per_instr) * s_x + k0
+                           : base + (int64_t)(k0 + it * rows_per_instr) * s_k + x0;
+    copy_1k((const char*)u + lane_off, tile + (it * (uint32_t)kGemmThreads + wave * 64u) * 16u);
+  }
+}
+
+// The MFMA fragment of a 32-row (or 32-column) block of a dense, swizzled tile.
+template <int BX, bool KC>
+__device__ __forceinline__ v8bf fragment_dense(const char* tile, uint32_t x_blk, uint32_t kk, uint32_t lane) {
+  typedef Dense<BX, KC> D;
+  if (KC) {
+    const uint32_t row = x_blk + (lane & 31u), c = kk * 2u + (lane >> 5);
+    return *(const v8bf*)(tile + row * 64u + ((c ^ D::swz_x(row)) << 4));
+  } else {
+    constexpr uint32_t S = BX * 2;
+    const uint32_t i16 = lane & 15u;
+    const uint32_t k = kk * 16u + (lane >> 5) * 8u + (i16 >> 2);
+    const uint32_t col = (x_blk + ((lane & 31u) >> 4) * 16u + 4u * (i16 & 3u)) * 2u;   // byte column
+    const char* p = tile + k * S + (((col >> 4) ^ D::swz_k(k)) << 4) + (col & 15u);
+    const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)p);
+    const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(p + 4 * S));   // k + 4: same swizzle
+    v8s r;
+    r[0] = lo[0]; r[1] = lo[1]; r[2] = lo[2]; r[3] = lo[3];
+    r[4] = hi[0]; r[5] = hi[1]; r[6] = hi[2]; r[7] = hi[3];
+    return __builtin_bit_cast(v8bf, r);
+  }
+}
 
 template <int BM, int BN> struct Smem {
   static constexpr size_t kStage = Geo<BM>::kBytes + Geo<BN>::kBytes;
   static constexpr size_t kOperands = 2 * kStage;
   static constexpr size_t kStripBytes = (size_t)BM * (BN + kCPad) * sizeof(float);   // the whole tile
-  static constexpr size_t kBytes = kOperands > kStripBytes ? kOperands : kStripBytes;
+  static constexpr size_t kDense = 4 * (size_t)(BM + BN) * 64;                        // four dense stages
+  static constexpr size_t kMax2 = kOperands > kStripBytes ? kOperands : kStripBytes;
+  static constexpr size_t kBytes = kMax2 > kDense ? kMax2 : kDense;
 };
-
-// Epilogue over the workgroup's BM x BN tile.  Strip p holds block row p of both wave rows:
-// LDS row r is tile row (r / 32) * (BM / 2) + p * 32 + r % 32.
-template <int BM, int BN, int MB, int NB>
-__device__ __forceinline__ void epilogue_strips(const GemmArgs& a, const v16f (&acc)[MB][NB], float* Cs, uint32_t tile_m,
-                                                uint32_t tile_n, uint32_t wave_m, uint32_t wave_n, uint32_t lane,
-                                                uint32_t batch, float* raw) {
-  constexpr int kCStride = BN + kCPad;
-  const EwProg& p = a.post;
-  const ProgRegs pr = load_prog_regs(p);
-  const uint32_t n_code = p.n_code;
-  const uint32_t b0 = batch / a.batch1, b1 = batch % a.batch1;
-  const int64_t base = (int64_t)b0 * a.o_b0 + (int64_t)b1 * a.o_b1;
-  const uint32_t row_flat0 = (b0 * a.batch1 + b1) * a.m;   // first row of this batch in the flattened [rows, n] output
-  // whole tile, whole aligned 4-vectors, at most four inputs and none of them strided: no bounds
-  // checks, no divisions (row and column are known), loads of a quad issued together
-  const bool fast = p.fast && p.full_vec_ok && p.n_in <= 4u && tile_m + BM <= a.m && tile_n + BN <= a.n;
-  const bool plain = n_code == 0u && p.n_in == 0u && p.n_out == 1u && !p.out[0].scalar && p.out[0].slot == p.anchor_slot;
-  // The strip loop stays rolled (one copy of the interpreter); the strip's accumulators are picked
-  // with compile-time indices so that the accumulator array never has to live in memory.
-#pragma unroll 1
-  for (int s = 0; s < MB; ++s) {
-    v16f strip[NB];
-#pragma unroll
-    for (int ss = 0; ss < MB; ++ss)
-      if (ss == s) {
-#pragma unroll
-        for (int bn = 0; bn < NB; ++bn) strip[bn] = acc[ss][bn];
-      }
-    __syncthreads();   // the LDS bytes (operand tiles, or the previous strip) are dead now
-#pragma unroll
-    for (int bn = 0; bn < NB; ++bn)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const uint32_t row = wave_m * 32u + (r >> 2) * 8u + (lane >> 5) * 4u + (r & 3);
-        const uint32_t col = wave_n * (BN / 2) + bn * 32u + (lane & 31u);
-        Cs[row * kCStride + col] = strip[bn][r];
-      }
-    __syncthreads();
-    if (raw) {
-      // partial product of a split: plain fp32, dense [batch * m, n]
-      const bool vec = (a.n % 4u) == 0u;
-#pragma unroll 4
-      for (uint32_t q = threadIdx.x; q < (uint32_t)(kStripRows * BN / kVec); q += kGemmThreads) {
-        const uint32_t r = q / (BN / kVec), c = (q % (BN / kVec)) * kVec;
-        const uint32_t row = tile_m + (r >> 5) * (BM / 2) + s * 32u + (r & 31u), col = tile_n + c;
-        if (row >= a.m || col >= a.n) continue;
-        float* dst = raw + (size_t)(row_flat0 + row) * a.n + col;
-        const float4 t = *(const float4*)&Cs[r * kCStride + c];
-        if (vec) {
-          *(float4*)dst = t;
-        } else {
-          dst[0] = t.x;
-          if (col + 1 < a.n) dst[1] = t.y;
-          if (col + 2 < a.n) dst[2] = t.z;
-          if (col + 3 < a.n) dst[3] = t.w;
-        }
-      }
-    } else if (fast && plain) {
-      // the product itself is the only output: convert and store, nothing to interpret
-      const EwOut& o = p.out[0];
-#pragma unroll 4
-      for (uint32_t q = threadIdx.x; q < (uint32_t)(kStripRows * BN / kVec); q += kGemmThreads) {
-        const uint32_t r = q / (BN / kVec), c = (q % (BN / kVec)) * kVec;
-        const uint32_t row = tile_m + (r >> 5) * (BM / 2) + s * 32u + (r & 31u);
-        const uint32_t i = (uint32_t)(base + (int64_t)row * a.o_row + tile_n + c);
-        const float4 t = *(const float4*)&Cs[r * kCStride + c];
-        Quad v;
-        v.v[0] = t.x; v.v[1] = t.y; v.v[2] = t.z; v.v[3] = t.w;
-        store_vec4<false>(o.ptr, o.dtype, 0, i, v);
-      }
-    } else if (fast) {
-#pragma unroll 1
-      for (uint32_t q = threadIdx.x; q < (uint32_t)(kStripRows * BN / kVec); q += kGemmThreads) {
-        const uint32_t r = q / (BN / kVec), c = (q % (BN / kVec)) * kVec;
-        const uint32_t row = tile_m + (r >> 5) * (BM / 2) + s * 32u + (r & 31u);
-        const uint32_t i = (uint32_t)(base + (int64_t)row * a.o_row + tile_n + c);
-        const Staged<4> st = fetch_inputs_at<4, false>(p, i, row_flat0 + row, tile_n + c);
-        const float4 t = *(const float4*)&Cs[r * kCStride + c];
-        Quad anchor;
-        anchor.v[0] = t.x; anchor.v[1] = t.y; anchor.v[2] = t.z; anchor.v[3] = t.w;
-        RF<16> f = place_inputs<16, 4, true, false>(rf_zero<16>(), p, st, kVec);
-        f = rf_set<16>(f, p.anchor_slot, anchor);
-        f = interp<16>(f, pr, n_code);
-        store_outputs<16, true, false>(f, p, 0, i, kVec);
-      }
-    } else {
-#pragma unroll 1
-      for (uint32_t q = threadIdx.x; q < (uint32_t)(kStripRows * BN / kVec); q += kGemmThreads) {
-        const uint32_t r = q / (BN / kVec), c = (q % (BN / kVec)) * kVec;
-        const uint32_t row = tile_m + (r >> 5) * (BM / 2) + s * 32u + (r & 31u), col = tile_n + c;
-        if (row >= a.m || col >= a.n) continue;
-        const uint32_t nvalid = a.n - col >= (uint32_t)kVec ? (uint32_t)kVec : a.n - col;
-        const uint32_t i = (uint32_t)(base + (int64_t)row * a.o_row + col);
-        const float4 t = *(const float4*)&Cs[r * kCStride + c];
-        Quad anchor;
-        anchor.v[0] = t.x; anchor.v[1] = t.y; anchor.v[2] = t.z; anchor.v[3] = t.w;
-        RF<16> f = load_inputs<16, kMaxIn, false, false>(rf_zero<16>(), p, 0, i, nvalid);
-        f = rf_set<16>(f, p.anchor_slot, anchor);
-        f = interp<16>(f, pr, n_code);
-        store_outputs<16, false, false>(f, p, 0, i, nvalid);
-      }
-    }
-  }
-}
 
 template <int BM, int BN, bool AKC, bool BKC>
 __global__ __launch_bounds__(kGemmThreads, 2) void lt_gemm_bf16_kernel(const GemmArgs a) {
@@ -302,8 +288,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void lt_gemm_bf16_kernel(const Gem
   const bool b_al = (((uintptr_t)B) & 15u) == 0 && (b_outer % 8) == 0;
   const bool a_in = a_al && tile_m + BM <= a.m, b_in = b_al && tile_n + BN <= a.n;
 
-  // LDS: two stages, each the A tile then the B tile
-  constexpr uint32_t kStage = (uint32_t)Smem<BM, BN>::kStage;
+    constexpr uint32_t kStage = (uint32_t)Smem<BM, BN>::kStage;   // padded layout (ragged tiles): A tile then B tile
   v16f acc[MB][NB];
 #pragma unroll
   for (int i = 0; i < MB; ++i)
@@ -339,54 +324,65 @@ __global__ __launch_bounds__(kGemmThreads, 2) void lt_gemm_bf16_kernel(const Gem
   };
   const bool whole = a_in && b_in && ((k_end - k_begin) % BK) == 0u;
   if (k_begin < k_end && whole) {
-    // Software pipeline over slices i = 0 .. n-1, three things in flight at once: the MFMAs of
-    // slice i run from fragment registers; the fragments of slice i+1 are read from the LDS stage
-    // that holds it; slice i+2 travels global -> registers -> the stage slice i has just left.
-    // So no MFMA ever waits for an LDS read of its own iteration, and one barrier per slice
-    // orders the stage hand-over.  (Fetches past the end are clamped to the last slice: in
-    // bounds, unused.)
+    // Software pipeline over slices j = 0 .. n-1, four LDS stages: the MFMAs of slice j run from
+    // fragment registers, the fragments of slice j+1 are read from the stage that holds it, and
+    // slices j+2 and j+3 are on their way from global memory straight into their stages -- no
+    // registers, no LDS write instructions, two iterations for a copy to land.  One barrier per
+    // slice: behind it slice j+1 has landed for every wave.  The stage that the copy of slice j+3
+    // overwrites held slice j-1, whose fragments every wave had read before it reached the
+    // previous barrier.  (Copies past the end are clamped to the last slice: in bounds, unused.)
+    constexpr uint32_t kDenseStage = Dense<BM, AKC>::kBytes + Dense<BN, BKC>::kBytes;
+    constexpr uint32_t kPer = Dense<BM, AKC>::kInstr + Dense<BN, BKC>::kInstr;   // copy instructions per wave and slice
+    static_assert(4 * kDenseStage <= Smem<BM, BN>::kBytes, "four dense stages fit the tile's LDS");
     const uint32_t n = (k_end - k_begin) / BK;
-    const uint32_t a_off = lane_offset<BM, AKC>(a.a.s_row, a.a.s_col), b_off = lane_offset<BN, BKC>(a.b.s_col, a.b.s_row);
-#define LT_FETCH(I)                                                                                       \
-  {                                                                                                      \
-    const uint32_t kf = k_begin + min((uint32_t)(I), n - 1u) * BK;                                       \
-    ca = fetch_whole<BM, AKC>(A, a.a.s_row, a.a.s_col, tile_m, kf, a_off);                               \
-    cb = fetch_whole<BN, BKC>(B, a.b.s_col, a.b.s_row, tile_n, kf, b_off);                               \
+    const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+    const uint32_t a_off = dma_lane_offset<BM, AKC>(a.a.s_row, a.a.s_col), b_off = dma_lane_offset<BN, BKC>(a.b.s_col, a.b.s_row);
+#define LT_COPY(I, STAGE)                                                                                          \
+  {                                                                                                               \
+    const uint32_t kf = k_begin + min((uint32_t)(I), n - 1u) * BK;                                                \
+    dma_tile<BM, AKC>(A, a.a.s_row, a.a.s_col, tile_m, kf, a_off, lds0 + (STAGE) * kDenseStage, wave_u);          \
+    dma_tile<BN, BKC>(B, a.b.s_col, a.b.s_row, tile_n, kf, b_off, lds0 + (STAGE) * kDenseStage + Dense<BM, AKC>::kBytes, wave_u); \
   }
-#define LT_STASH(STAGE)                                                    \
-  {                                                                       \
-    stash<BM, AKC>(ca, smem + (STAGE) * kStage);                          \
-    stash<BN, BKC>(cb, smem + (STAGE) * kStage + Geo<BM>::kBytes);        \
-  }
-    Chunks<Geo<BM>::kChunks> ca;
-    Chunks<Geo<BN>::kChunks> cb;
-    LT_FETCH(0);
-    LT_STASH(0);
-    LT_FETCH(1);
-    LT_STASH(1);
-    LT_FETCH(2);
+    auto dense_frags = [&](uint32_t stage) {
+      const char* As = smem + stage * kDenseStage;
+      const char* Bs = As + Dense<BM, AKC>::kBytes;
+      Frags f;
+#pragma unroll
+      for (uint32_t kk = 0; kk < BK / 16; ++kk) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i) f.a[kk][i] = fragment_dense<BM, AKC>(As, wave_m * (BM / 2) + i * 32u, kk, lane);
+#pragma unroll
+        for (int j = 0; j < NB; ++j) f.b[kk][j] = fragment_dense<BN, BKC>(Bs, wave_n * (BN / 2) + j * 32u, kk, lane);
+      }
+      return f;
+    };
+    LT_COPY(0, 0);
+    LT_COPY(1, 1);
+    LT_COPY(2, 2);
+    landed<2 * kPer>();   // slice 0
     __syncthreads();
-    Frags f0 = load_frags(0), f1;
-    __syncthreads();   // nobody overwrites stage 0 before everybody has read slice 0 from it
-    // Two slices per trip so that the two fragment sets swap roles without register copies.  The
-    // body is branch free: past the end it reads fragments nobody uses and writes a stage nobody
-    // reads (all inside the workgroup's own LDS).
-    uint32_t i = 0;
-    for (; i + 1u < n; i += 2u) {
-      f1 = load_frags(1);
-      mma(f0);
-      LT_STASH(0);
-      LT_FETCH(i + 3u);
-      __syncthreads();
-      f0 = load_frags(0);
-      mma(f1);
-      LT_STASH(1);
-      LT_FETCH(i + 4u);
-      __syncthreads();
+    Frags f0 = dense_frags(0), f1;
+    // Four slices per trip: stage numbers and the two fragment sets are compile-time.  Past the end
+    // the body copies into stages nobody reads and reads fragments nobody uses; only the MFMAs
+    // are guarded.
+#define LT_SLICE(J, CUR, NEXT)                                     \
+  {                                                              \
+    LT_COPY(i + (J) + 3u, ((J) + 3) & 3);                        \
+    landed<2 * kPer>(); /* slice i + J + 1 */                    \
+    __syncthreads();                                             \
+    NEXT = dense_frags(((J) + 1) & 3);                           \
+    if (i + (J) < n) mma(CUR);                                   \
+  }
+    for (uint32_t i = 0; i < n; i += 4u) {
+      LT_SLICE(0, f0, f1);
+      LT_SLICE(1, f1, f0);
+      LT_SLICE(2, f0, f1);
+      LT_SLICE(3, f1, f0);
     }
-    if (i < n) mma(f0);   // odd number of slices: the last one is already in registers
-#undef LT_FETCH
-#undef LT_STASH
+    landed<0>();   // nothing may still be on its way into LDS when the epilogue reuses it
+#undef LT_SLICE
+#undef LT_COPY
   } else if (k_begin < k_end) {
     // ragged or unaligned tile: every access checked, one slice at a time
 #pragma unroll 1

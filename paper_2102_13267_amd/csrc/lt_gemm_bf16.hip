@@ -1,29 +1,29 @@
 // bf16 contraction on the gfx950 matrix cores: C = post(A * B), fp32 accumulation.
 //
-// Workgroup tile BM x 128 (BM = 128 as built), k walked in slices of 32,
-// four wavefronts in a 2 x 2 arrangement, each owning (BM/2) x 64 as blocks of
-// v_mfma_f32_32x32x16_bf16.  What bounds this kernel is LDS bandwidth, not the matrix cores: every
-// MFMA of a 64 x 64 wavefront tile needs a kilobyte of fragments from LDS, which at four SIMDs per
-// compute unit is the whole LDS read rate; the 128 x 64 wavefront tile of BM = 256 needs a
-// quarter less, and its A tile is shared by twice the work.  Two LDS stages of 30 KiB let two
-// workgroups share a compute unit, so one's matrix instructions run under the other's loads,
-// stores and barriers; the registers stay under the 256 that two wavefronts per SIMD allow.
+// Workgroup tile 128 x 128 (128 x 64 for narrow outputs), k walked in slices of 32, four
+// wavefronts in a 2 x 2 arrangement, each owning 64 x 64 (64 x 32) as blocks of
+// v_mfma_f32_32x32x16_bf16.  What bounds this kernel is LDS bandwidth, not the matrix cores: the
+// 8 MFMAs of a 64 x 64 block and slice (256 cycles) need 8 KiB of fragments from LDS, and the
+// slice itself has to get into LDS first.  Two workgroups share a compute unit, so one's matrix
+// instructions run under the other's LDS traffic, barriers and epilogue.
 //
-// Operand staging.  An MFMA lane wants 8 consecutive k of one row (A) or column (B).
-//  * k is the operand's contiguous dimension: global 16-byte loads land in LDS as [x][k] rows of
-//    80 bytes (64 + 16 of padding: eight consecutive rows hit eight different 16-byte bank
-//    groups) and a lane's fragment is one ds_read_b128;
-//  * x (m or n) is the contiguous dimension: the tile is stored as it arrives, [k][x] rows padded
-//    by 32 bytes, and the transpose happens in the LDS read: ds_read_b64_tr_b16 hands each lane of
-//    a 16-lane group one column of a 4 x 16 sub-tile (lane i gets element i of each of the four
-//    rows that lanes 4j .. 4j+3 point at), so two such reads give the 8 k values of one x.
-// Either way global loads and LDS writes are 16 bytes per lane and nothing is transposed by
-// scalar code.  The loop is software pipelined three deep (MFMAs of slice i from registers, LDS
-// fragment reads of slice i+1, global loads and LDS writes of slice i+2), one barrier per slice.
+// Whole, 16-byte aligned tiles go from global memory into LDS without touching registers
+// (global_load_lds_dwordx4), into dense tiles whose bank conflicts a swizzle takes care of; four
+// stages, copies two slices ahead (see "whole tiles" below).  An MFMA lane wants 8 consecutive k
+// of one row (A) or column (B):
+//  * k is the operand's contiguous dimension: the tile is [x][k] and a fragment is one
+//    ds_read_b128;
+//  * x (m or n) is the contiguous dimension: the tile stays as it arrives, [k][x], and the
+//    transpose happens in the LDS read: ds_read_b64_tr_b16 hands each lane of a 16-lane group one
+//    column of a 4 x 16 sub-tile (lane i gets element i of each of the four rows that lanes
+//    4j .. 4j+3 point at), so two such reads give the 8 k values of one x.
+// Nothing is transposed by scalar code.  Ragged or unaligned tiles take a second path: every
+// access checked, global -> registers -> padded LDS tiles, one slice at a time.
 //
-// Epilogue: the accumulators leave the MFMA layout through LDS in strips of 64 rows; each strip is
-// then walked in row-major 4-element quads by the interpreter (bias, activation, residual,
-// optimiser update, cast ...), so the product itself never travels to HBM unless asked for.
+// Epilogue (lt_gemm_epilogue.h): the accumulators leave the MFMA layout through LDS, the whole tile
+// at once, and are then walked in row-major 4-element quads by the interpreter (bias, activation,
+// residual, optimiser update, cast ...), so the product itself never travels to HBM unless
+// asked for.
 //
 // Split-K: when a problem has few output tiles but a long k, `splits` workgroups share a tile and
 // each leaves its fp32 partial product in a workspace; a second, elementwise launch adds them in
@@ -48,7 +48,7 @@ typedef short v4s __attribute__((ext_vector_type(4)));
 typedef short v8s __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) v4s* lds_v4s_ptr;
 
-// Geometry of one operand tile of BX rows/columns by 32 k.
+// Geometry of one padded operand tile of BX rows/columns by 32 k (ragged-tile path).
 template <int BX> struct Geo {
   static constexpr int kChunks = BX / 64;              // 16-byte chunks per lane and slice
   static constexpr int kStrideXC = BX * 2 + 32;        // bytes per row of a [k][x] tile
@@ -103,33 +103,6 @@ __device__ __forceinline__ Chunks<Geo<BX>::kChunks> fetch_checked(const uint16_t
     chunk_pos<BX, KC>(it, &o, &i);
     c.g[it] = KC ? fetch_guarded(base, s_x, x0 + o, k0 + i, nx, nk, aligned)
                  : fetch_guarded(base, s_k, k0 + o, x0 + i, nk, nx, aligned);
-  }
-  return c;
-}
-
-// The same for a tile and slice that are whole and 16-byte aligned.  A chunk's address is split
-// into a wave-uniform part (tile origin, slice, chunk number: scalar registers) and this lane's
-// byte offset inside a chunk row group, which is the same for every chunk and every slice: one
-// vector register per operand instead of a 64-bit address per chunk.
-template <int BX, bool KC>
-__device__ __forceinline__ uint32_t lane_offset(int64_t s_x, int64_t s_k) {
-  const uint32_t t = threadIdx.x;
-  if (KC) return (uint32_t)(((t >> 2) * s_x + (t & 3u) * 8u) * 2);
-  constexpr uint32_t per_row = BX / 8;
-  return (uint32_t)(((t / per_row) * s_k + (t % per_row) * 8u) * 2);
-}
-
-template <int BX, bool KC>
-__device__ __forceinline__ Chunks<Geo<BX>::kChunks> fetch_whole(const uint16_t* base, int64_t s_x, int64_t s_k, uint32_t x0,
-                                                                uint32_t k0, uint32_t lane_off) {
-  Chunks<Geo<BX>::kChunks> c;
-  // rows advance by 64 (KC) or by 256 / (BX / 8) (otherwise) from one chunk to the next
-  constexpr uint32_t rows_per_chunk = KC ? 64u : (uint32_t)kGemmThreads / (BX / 8);
-#pragma unroll
-  for (int it = 0; it < Geo<BX>::kChunks; ++it) {
-    const uint16_t* u = KC ? base + (int64_t)(x0 + it * rows_per_chunk) * s_x + k0
-                           : base + (int64_t)(k0 + it * rows_per_chunk) * s_k + x0;
-    c.g[it] = *(const uint4*)((const char*)u + lane_off);
   }
   return c;
 }
@@ -257,10 +230,9 @@ __device__ __forceinline__ v8bf fragment_dense(const char* tile, uint32_t x_blk,
 
 template <int BM, int BN> struct Smem {
   static constexpr size_t kStage = Geo<BM>::kBytes + Geo<BN>::kBytes;
-  static constexpr size_t kOperands = 2 * kStage;
   static constexpr size_t kStripBytes = (size_t)BM * (BN + kCPad) * sizeof(float);   // the whole tile
   static constexpr size_t kDense = 4 * (size_t)(BM + BN) * 64;                        // four dense stages
-  static constexpr size_t kMax2 = kOperands > kStripBytes ? kOperands : kStripBytes;
+  static constexpr size_t kMax2 = kStage > kStripBytes ? kStage : kStripBytes;   // (ragged tiles: one padded stage)
   static constexpr size_t kBytes = kMax2 > kDense ? kMax2 : kDense;
 };
 

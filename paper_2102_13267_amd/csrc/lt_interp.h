@@ -29,11 +29,10 @@
 namespace ltk {
 
 template <int NS> struct SlotVec;
-template <> struct SlotVec<8> { typedef float type __attribute__((ext_vector_type(8))); };
 template <> struct SlotVec<16> { typedef float type __attribute__((ext_vector_type(16))); };
 template <> struct SlotVec<32> { typedef float type __attribute__((ext_vector_type(32))); };
 
-// Register file of NS value slots (8, 16 or 32) x kVec element lanes.
+// Register file of NS value slots (16 or 32) x kVec element lanes.
 template <int NS> struct RF {
   typedef typename SlotVec<NS>::type vec;
   vec e[kVec];

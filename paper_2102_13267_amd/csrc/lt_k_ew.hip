@@ -162,8 +162,144 @@ __global__ __launch_bounds__(kBlock) void lt_split_post_kernel(const SplitPostAr
   }
 }
 
+// The same with the loads sorted out on the host, for post programs of at most eight slots whose
+// inputs are plain (same shape as the product): at most two fp32 ones and one bf16 one -- an
+// optimiser update of bf16 parameters with fp32 moments.  Two tiles per trip and workgroup, one
+// trip per workgroup; the partial products of four splits at a time and every input of both tiles
+// are fetched before anything is used, and the interpreter runs once for both tiles.
+struct SplitStreamArgs {
+  SplitPostArgs base;
+  uint32_t fin[2];    // input numbers of the fp32 inputs (padded with the first)
+  uint32_t bin;       // input number of the bf16 input
+  uint32_t n_fin, n_bin, pad;
+};
+
+template <int NVF, int NVB>
+__global__ __launch_bounds__(kBlock) void lt_split_post_stream_kernel(const SplitStreamArgs sa) {
+  const SplitPostArgs& a = sa.base;
+  const EwProg& p = a.prog;
+  const uint64_t n = p.n;
+  constexpr uint64_t kTile = (uint64_t)kBlock * kVec;
+  const uint64_t ntiles = (n + kTile - 1) / kTile;
+  const uint64_t npairs = (n / kTile) / 2;
+  const uint64_t ntrips = npairs + (ntiles - 2 * npairs);
+  const ProgRegs pr = load_prog_regs(p);
+  const uint32_t n_code = p.n_code;
+  const uint32_t lane = threadIdx.x * kVec;
+  const char* fp[NVF > 0 ? NVF : 1];
+  uint32_t fslot[NVF > 0 ? NVF : 1];
+#pragma unroll
+  for (int j = 0; j < NVF; ++j) {
+    fslot[j] = sa.fin[j];
+    fp[j] = (const char*)p.in[fslot[j]].ptr;
+  }
+  const char* bp = NVB ? (const char*)p.in[sa.bin].ptr : nullptr;
+  for (uint64_t trip = blockIdx.x; trip < ntrips; trip += gridDim.x) {
+    const bool pair = trip < npairs;
+    const uint64_t t0 = pair ? 2 * trip : npairs + trip, t1 = pair ? t0 + 1 : t0;
+    const uint64_t e0 = t0 * kTile + lane, e1 = t1 * kTile + lane;   // first element of this lane's two quads
+    if (e0 >= n) continue;   // (only in the last tile, which is its own partner)
+    RawVec vf0[NVF > 0 ? NVF : 1], vf1[NVF > 0 ? NVF : 1];
+    typedef uint32_t U32x2 __attribute__((ext_vector_type(2)));
+    U32x2 vb0 = {0, 0}, vb1 = {0, 0};
+#pragma unroll
+    for (int j = 0; j < NVF; ++j) {
+      vf0[j] = *(const RawVec*)(fp[j] + e0 * 4u);
+      vf1[j] = *(const RawVec*)(fp[j] + e1 * 4u);
+    }
+    if (NVB) {
+      vb0 = *(const U32x2*)(bp + e0 * 2u);
+      vb1 = *(const U32x2*)(bp + e1 * 2u);
+    }
+    // partial products, summed in split order (the result does not depend on scheduling)
+    RawVec s0 = {0, 0, 0, 0}, s1 = {0, 0, 0, 0};
+    uint32_t sp = 0;
+    for (; sp + 4u <= a.splits; sp += 4u) {
+      RawVec t0v[4], t1v[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float* src = a.ws + (uint64_t)(sp + j) * a.stride;
+        t0v[j] = *(const RawVec*)(src + e0);
+        t1v[j] = *(const RawVec*)(src + e1);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        s0 += t0v[j];
+        s1 += t1v[j];
+      }
+    }
+    for (; sp < a.splits; ++sp) {
+      const float* src = a.ws + (uint64_t)sp * a.stride;
+      const RawVec u0 = *(const RawVec*)(src + e0), u1 = *(const RawVec*)(src + e1);
+      s0 += u0;
+      s1 += u1;
+    }
+    RF<16> f = rf_zero<16>();
+    Quad q;
+#pragma unroll
+    for (int j = 0; j < NVF; ++j) {
+      q.v[0] = vf0[j].x; q.v[1] = vf0[j].y; q.v[2] = vf0[j].z; q.v[3] = vf0[j].w;
+      f = rf_set<16>(f, fslot[j], q);
+      q.v[0] = vf1[j].x; q.v[1] = vf1[j].y; q.v[2] = vf1[j].z; q.v[3] = vf1[j].w;
+      f = rf_set<16>(f, fslot[j] + 8u, q);
+    }
+    if (NVB) {
+      q.v[0] = __uint_as_float(vb0.x << 16); q.v[1] = __uint_as_float(vb0.x & 0xffff0000u);
+      q.v[2] = __uint_as_float(vb0.y << 16); q.v[3] = __uint_as_float(vb0.y & 0xffff0000u);
+      f = rf_set<16>(f, sa.bin, q);
+      q.v[0] = __uint_as_float(vb1.x << 16); q.v[1] = __uint_as_float(vb1.x & 0xffff0000u);
+      q.v[2] = __uint_as_float(vb1.y << 16); q.v[3] = __uint_as_float(vb1.y & 0xffff0000u);
+      f = rf_set<16>(f, sa.bin + 8u, q);
+    }
+    q.v[0] = s0.x; q.v[1] = s0.y; q.v[2] = s0.z; q.v[3] = s0.w;
+    f = rf_set<16>(f, p.anchor_slot, q);
+    q.v[0] = s1.x; q.v[1] = s1.y; q.v[2] = s1.z; q.v[3] = s1.w;
+    f = rf_set<16>(f, p.anchor_slot + 8u, q);
+    f = interp<16, 2>(f, pr, n_code);
+    store_outputs<16, true, false, 0>(f, p, t0 * kTile, lane, kVec);
+    store_outputs<16, true, false, 8>(f, p, t1 * kTile, lane, kVec);
+  }
+}
+
+static bool make_split_stream_args(const SplitPostArgs& a, SplitStreamArgs* out) {
+  const EwProg& p = a.prog;
+  if (!p.fast || p.n_slots > 8u || (a.stride % 4u) != 0u) return false;
+  uint32_t nf = 0, nb = 0;
+  out->fin[0] = out->fin[1] = out->bin = 0u;
+  for (uint32_t k = 0; k < p.n_in; ++k) {
+    const EwIn& in = p.in[k];
+    if (in.fetch != kFetchVec4 || in.mode != kFull) return false;
+    if (in.dtype == kF32) {
+      if (nf == 2u) return false;
+      out->fin[nf++] = k;
+    } else if (in.dtype == kBF16) {
+      if (nb == 1u) return false;
+      out->bin = k;
+      ++nb;
+    } else {
+      return false;
+    }
+  }
+  if (nf == 1u) out->fin[1] = out->fin[0];
+  out->n_fin = nf;
+  out->n_bin = nb;
+  out->pad = 0;
+  out->base = a;
+  return true;
+}
+
 hipError_t launch_split_post(const SplitPostArgs& a, uint32_t grid, hipStream_t s) {
   const dim3 g(grid), b(kBlock);
+  SplitStreamArgs sa;
+  if (make_split_stream_args(a, &sa)) {
+    const uint64_t tiles = (a.prog.n + 1023) / 1024;
+    const dim3 g2((uint32_t)std::max<uint64_t>(1, std::min<uint64_t>((tiles + 1) / 2, 0x7fffffffull)));
+    if (sa.n_fin == 0u && sa.n_bin == 0u) hipLaunchKernelGGL((lt_split_post_stream_kernel<0, 0>), g2, b, 0, s, sa);
+    else if (sa.n_fin == 0u) hipLaunchKernelGGL((lt_split_post_stream_kernel<0, 1>), g2, b, 0, s, sa);
+    else if (sa.n_bin == 0u) hipLaunchKernelGGL((lt_split_post_stream_kernel<2, 0>), g2, b, 0, s, sa);
+    else hipLaunchKernelGGL((lt_split_post_stream_kernel<2, 1>), g2, b, 0, s, sa);
+    return hipGetLastError();
+  }
   // whole 4-vectors of partials need 16-byte aligned splits
   const bool fast = a.prog.fast && a.prog.n_in <= 4u && (a.stride % 4u) == 0u;
   if (fast) hipLaunchKernelGGL((lt_split_post_kernel<4, true>), g, b, 0, s, a);

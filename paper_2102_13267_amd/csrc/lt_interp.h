@@ -495,7 +495,8 @@ __device__ __forceinline__ void store_elem(void* ptr, uint32_t dtype, uint64_t i
   else ((float*)ptr)[idx] = v;
 }
 
-template <bool F32 = false>
+// NT: non-temporal store (the data is not read again by this kernel).
+template <bool F32 = false, bool NT = false>
 __device__ __forceinline__ void store_vec4(void* ptr, uint32_t dtype, uint64_t base, uint32_t lane, const Quad& q) {
   if (!F32 && dtype == kBF16) {
     uint2 u;
@@ -505,13 +506,18 @@ __device__ __forceinline__ void store_vec4(void* ptr, uint32_t dtype, uint64_t b
     *(uint2*)(b + (size_t)lane * 2u) = u;
   } else {
     char* b = (char*)ptr + base * 4u;
-    *(float4*)(b + (size_t)lane * 4u) = make_float4(q.v[0], q.v[1], q.v[2], q.v[3]);
+    if (NT) {
+      const RawVec t = {q.v[0], q.v[1], q.v[2], q.v[3]};
+      __builtin_nontemporal_store(t, (RawVec*)(b + (size_t)lane * 4u));
+    } else {
+      *(float4*)(b + (size_t)lane * 4u) = make_float4(q.v[0], q.v[1], q.v[2], q.v[3]);
+    }
   }
 }
 
 // Store the outputs of the program for elements i .. i+nvalid-1, i = base + lane (flat,
 // contiguous outputs).
-template <int NS, bool FAST = false, bool F32 = false, int OFF = 0>
+template <int NS, bool FAST = false, bool F32 = false, int OFF = 0, bool NT = false>
 __device__ __forceinline__ void store_outputs(RF<NS> f, const EwProg& p, uint64_t base, uint32_t lane, uint32_t nvalid) {
   const uint32_t n_out = p.n_out;
   if (!FAST) {   // general path: one rolled copy (see load_inputs_general)
@@ -539,7 +545,7 @@ __device__ __forceinline__ void store_outputs(RF<NS> f, const EwProg& p, uint64_
       if (out.scalar) {
         if (base + lane == 0) store_elem<F32>(out.ptr, out.dtype, 0, q.v[0]);
       } else {
-        store_vec4<F32>(out.ptr, out.dtype, base, lane, q);
+        store_vec4<F32, NT>(out.ptr, out.dtype, base, lane, q);
       }
     }
   }

@@ -669,3 +669,25 @@ def test_c3_layer_same_on_one_stream_and_four():
         c.close()
     for a, b in zip(results[1], results[4]):
         assert np.array_equal(np.asarray(a).view(np.uint8), np.asarray(b).view(np.uint8))
+
+
+@pytest.mark.parametrize("n", [8, 2048, 2056, 2052, 6 * 2048 + 24, (1 << 20) + 4])
+def test_bf16_elementwise_programs(ctx, n):
+    """Elementwise regions over bf16 tensors: sizes of one lane's 8 elements, one tile, a tile and a
+    ragged one, a size that is not a multiple of 8 (the 4-at-a-time path), several tiles; one to
+    three bf16 inputs, a device scalar, bf16 and fp32 outputs in one region."""
+    E = Eager()
+    g = rng(300 + n % 97)
+    a, b, c = (round_to_bf16(g.standard_normal(n, dtype=np.float32)) for _ in range(3))
+    s = np.array(0.75, np.float32)
+
+    def prog(B, a, b, c, s):
+        u = B.gelu(B.add(a, b))                              # bf16 in, bf16 out
+        v = B.cast(B.mul(B.add(B.mul(a, c), u), s), "f32")   # three inputs, a device scalar, fp32 out
+        w = B.add(a, b)                                      # the bare residual add
+        return u, v, w
+
+    got = prog(ctx, *(ctx.tensor(t, dtype="bf16") for t in (a, b, c)), ctx.tensor(s))
+    ref = prog(E, *(E.tensor(t, dtype="bf16") for t in (a, b, c)), E.tensor(s))
+    for gt, rt, what in zip(got, ref, "uvw"):
+        check(ctx, E, gt, rt, TOL16, what)

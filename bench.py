@@ -31,7 +31,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the 1 GiB calibration
 # copy of the same runs (FETCH x 2.000, WRITE x 1.000): see profiles/c4_adam_clip_kernels.md
-PROFILED_TRAFFIC = {("c4", "lt_ew_kernel"): 7_516_430_336}
+PROFILED_TRAFFIC = {("c4", "lt_ew_kernel"): 7_517_218_816}
 MFMA_PEAK_TFLOPS = {"bf16": 2516.6, "f32": 157.3}
 
 

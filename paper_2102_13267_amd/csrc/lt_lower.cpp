@@ -1150,7 +1150,7 @@ struct Lowering {
       uint32_t gy = std::max<uint32_t>(1, std::min<uint32_t>(args.rows / 64, 64));
       // small: one slab per strip and no cross-workgroup step -- unless the rows are not whole
       // 4-vectors, where the element-wise path is slow enough to want the rows spread out
-      if ((uint64_t)args.rows * args.cols <= 65536) gy = (args.cols % 4u) == 0u ? 1u : std::max<uint32_t>(1, std::min<uint32_t>(args.rows / 16, 8));
+      if ((uint64_t)args.rows * args.cols <= 65536) gy = (args.cols % 4u) == 0u ? 1u : std::max<uint32_t>(1, std::min<uint32_t>(args.rows / 8, 32));
       while (gy > 1 && (uint64_t)gy * (args.cols + 3) > kPartialFloats) gy /= 2;
       if ((uint64_t)gy * (args.cols + 3) > kPartialFloats) return bad(LT_ERR_UNSUPPORTED, "axis-0 reduction wider than 1048576 columns");
       while (gy > 1 && (uint64_t)gy * l.grid_x > 256) gy /= 2;

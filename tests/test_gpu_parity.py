@@ -691,3 +691,28 @@ def test_bf16_elementwise_programs(ctx, n):
     ref = prog(E, *(E.tensor(t, dtype="bf16") for t in (a, b, c)), E.tensor(s))
     for gt, rt, what in zip(got, ref, "uvw"):
         check(ctx, E, gt, rt, TOL16, what)
+
+
+@pytest.mark.parametrize("n", [4, 1024, 1028, 2048, 3072, 5 * 1024 + 8, (1 << 20) + 1024])
+def test_streamed_fp32_elementwise_tile_pairs(ctx, n):
+    """The streamed fp32 elementwise kernel takes two 1024-element tiles per workgroup: a single
+    tile, a tile and a ragged one, an odd number of tiles (the last one is its own partner), one to
+    four plain inputs, two device scalars, an in-place update among the outputs."""
+    E = Eager()
+    g = rng(500 + n % 89)
+    arrs = [g.standard_normal(n).astype(np.float32) for _ in range(4)]
+    s1, s2 = np.array(0.25, np.float32), np.array(-1.5, np.float32)
+
+    def prog(B, a, b, c, d, s1, s2):
+        one = B.tanh(a)                                            # one input
+        two = B.add(B.mul(a, b), s1)                               # two inputs, one device scalar
+        four = B.sub(B.mul(B.add(a, b), B.mul(c, s2)), B.mul(d, s1))   # four inputs, two device scalars
+        B.assign(d, B.add(B.mul(d, 0.5), c))                       # in place
+        return one, two, four, d
+
+    lt = [ctx.tensor(x.copy(), donatable=(i == 3)) for i, x in enumerate(arrs)]
+    et = [E.tensor(x.copy(), donatable=(i == 3)) for i, x in enumerate(arrs)]
+    got = prog(ctx, *lt, ctx.tensor(s1), ctx.tensor(s2))
+    ref = prog(E, *et, E.tensor(s1), E.tensor(s2))
+    for gt, rt, what in zip(got, ref, ("one", "two", "four", "in place")):
+        check(ctx, E, gt, rt, TOL32, what)

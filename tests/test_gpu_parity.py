@@ -716,3 +716,75 @@ def test_streamed_fp32_elementwise_tile_pairs(ctx, n):
     ref = prog(E, *et, E.tensor(s1), E.tensor(s2))
     for gt, rt, what in zip(got, ref, ("one", "two", "four", "in place")):
         check(ctx, E, gt, rt, TOL32, what)
+
+
+def _random_trace(B, rg, base, allow_matmul):
+    """A random DAG over three inputs: well-conditioned elementwise ops, reductions over every axis
+    kind, an occasional contraction, in-place updates of the inputs, dropped intermediates.
+    Decisions are drawn from `rg` only, so two back ends given equal seeds build the same trace."""
+    unary = ["neg", "abs", "tanh", "relu", "gelu", "square", "sigmoid"]
+    binary = ["add", "sub", "mul", "maximum", "minimum"]
+    vals = list(base)
+    full = list(base)
+    for _ in range(int(rg.integers(6, 22))):
+        kind = int(rg.integers(0, 12))
+        pick = lambda: full[int(rg.integers(0, len(full)))]
+        if kind < 3:
+            r = getattr(B, unary[int(rg.integers(0, len(unary)))])(pick())
+        elif kind < 7:
+            a, b = pick(), pick()
+            name = binary[int(rg.integers(0, len(binary)))]
+            if rg.integers(0, 3) == 0:
+                r = getattr(B, name)(a, [0.0, 1.0, 0.5, -2.0][int(rg.integers(0, 4))])
+            elif a.shape == b.shape or len(b.shape) == 0 or (len(a.shape) == 2 and b.shape in ((a.shape[1],), (a.shape[0], 1))):
+                r = getattr(B, name)(a, b)
+            else:
+                continue
+        elif kind < 9:
+            a = pick()
+            if len(a.shape) == 0:
+                continue
+            axis = [None, -1, 0][int(rg.integers(0, 3))]
+            if axis == 0 and len(a.shape) != 2:
+                axis = None
+            r = getattr(B, ["sum", "amax", "mean"][int(rg.integers(0, 3))])(B.mul(a, 0.01), axis)
+        elif kind == 9 and allow_matmul:
+            a, b = pick(), pick()
+            if len(a.shape) != 2 or a.shape != b.shape:
+                continue
+            r = B.mul(B.matmul(a, b, trans_a=True), 1.0 / a.shape[0])       # [cols, cols]
+        elif kind >= 10:
+            dst, src = vals[int(rg.integers(0, len(vals)))], pick()
+            if tuple(dst.shape) != tuple(src.shape) or dst is src:
+                continue
+            B.assign(dst, src)
+            continue
+        else:
+            continue
+        full.append(r)
+        if rg.integers(0, 3) == 0 and len(full) > 6:
+            full.pop(int(rg.integers(len(vals), len(full))))
+    return full
+
+
+@pytest.mark.parametrize("shape,trials", [((8, 16), 12), ((100, 257), 8), ((1024, 1024), 6), ((4096, 1024), 4)])
+def test_random_traces_numeric(ctx, shape, trials):
+    """Random traces, the same on both sides, every live tensor compared after the barrier.  The
+    larger shapes reach the streamed kernels, the several-vectors-per-dispatch interpreter paths
+    and (4096 x 1024: column reductions of 16 MiB) the side streams."""
+    for trial in range(trials):
+        seed = 9000 + 31 * trial + shape[0]
+        g = rng(seed)
+        arrs = [g.standard_normal(shape).astype(np.float32) * 0.5, g.standard_normal(shape).astype(np.float32) * 0.5,
+                g.standard_normal(shape[1]).astype(np.float32)]
+        E = Eager()
+        lt = [ctx.tensor(a.copy(), donatable=(i == 0)) for i, a in enumerate(arrs)]
+        et = [E.tensor(a.copy(), donatable=(i == 0)) for i, a in enumerate(arrs)]
+        got = _random_trace(ctx, rng(seed + 1), lt, allow_matmul=shape[0] >= 100)
+        ref = _random_trace(E, rng(seed + 1), et, allow_matmul=shape[0] >= 100)
+        assert len(got) == len(ref)
+        ctx.barrier()
+        for k, (a, b) in enumerate(zip(got, ref)):
+            err = rel_err(ctx.fetch(a), E.fetch(b))
+            assert err <= 2e-5, (shape, trial, k, err)
+        del got, ref, lt, et

@@ -329,6 +329,19 @@ __global__ __launch_bounds__(kGemmThreads, 2) void lt_gemm_bf16_kernel(const Gem
       }
       return f;
     };
+    if (n <= 3u) {
+      // a short k (attention scores and contexts: k = 64) fits the stages at once: every slice is
+      // copied, one wait, one barrier, and the slices are multiplied straight from LDS
+      LT_COPY(0, 0);
+      if (n > 1u) LT_COPY(1, 1);
+      if (n > 2u) LT_COPY(2, 2);
+      landed<0>();
+      __syncthreads();
+      for (uint32_t j = 0; j < n; ++j) {
+        const Frags f = j == 0u ? dense_frags(0) : j == 1u ? dense_frags(1) : dense_frags(2);
+        mma(f);
+      }
+    } else {
     LT_COPY(0, 0);
     LT_COPY(1, 1);
     LT_COPY(2, 2);
@@ -353,6 +366,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void lt_gemm_bf16_kernel(const Gem
       LT_SLICE(3, f1, f0);
     }
     landed<0>();   // nothing may still be on its way into LDS when the epilogue reuses it
+    }
 #undef LT_SLICE
 #undef LT_COPY
   } else if (k_begin < k_end) {

@@ -9,7 +9,7 @@
 //
 // Whole, 16-byte aligned tiles go from global memory into LDS without touching registers
 // (global_load_lds_dwordx4), into dense tiles whose bank conflicts a swizzle takes care of; four
-// stages, copies two slices ahead (see "whole tiles" below).  An MFMA lane wants 8 consecutive k
+// stages, copies three slices ahead (see "whole tiles" below).  An MFMA lane wants 8 consecutive k
 // of one row (A) or column (B):
 //  * k is the operand's contiguous dimension: the tile is [x][k] and a fragment is one
 //    ds_read_b128;
@@ -228,6 +228,13 @@ __device__ __forceinline__ v8bf fragment_dense(const char* tile, uint32_t x_blk,
   }
 }
 
+// The same, and every LDS read of this wave has returned as well (lgkmcnt = 0).
+template <uint32_t outstanding>
+__device__ __forceinline__ void landed_and_read() {
+  static_assert(outstanding < 64u, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt((int)((outstanding & 15u) | ((outstanding >> 4) << 14) | 0x0070u));
+}
+
 template <int BM, int BN> struct Smem {
   static constexpr size_t kStage = Geo<BM>::kBytes + Geo<BN>::kBytes;
   static constexpr size_t kStripBytes = (size_t)BM * (BN + kCPad) * sizeof(float);   // the whole tile
@@ -298,11 +305,13 @@ __global__ __launch_bounds__(kGemmThreads, 2) void lt_gemm_bf16_kernel(const Gem
   if (k_begin < k_end && whole) {
     // Software pipeline over slices j = 0 .. n-1, four LDS stages: the MFMAs of slice j run from
     // fragment registers, the fragments of slice j+1 are read from the stage that holds it, and
-    // slices j+2 and j+3 are on their way from global memory straight into their stages -- no
-    // registers, no LDS write instructions, two iterations for a copy to land.  One barrier per
-    // slice: behind it slice j+1 has landed for every wave.  The stage that the copy of slice j+3
-    // overwrites held slice j-1, whose fragments every wave had read before it reached the
-    // previous barrier.  (Copies past the end are clamped to the last slice: in bounds, unused.)
+    // slices j+2 .. j+4 are on their way from global memory straight into their stages -- no
+    // registers, no LDS write instructions, three iterations for a copy to land (the loop is bound
+    // by that latency, not by bandwidth, when the distance is shorter).  One barrier per slice:
+    // behind it slice j+1 has landed for every wave, and every wave's reads of slice j's stage
+    // (issued one iteration earlier) have returned -- each wave waits for its own LDS reads before
+    // the barrier -- so the copy of slice j+4 may overwrite that stage at once.  (Copies past the
+    // end are clamped to the last slice: in bounds, unused.)
     constexpr uint32_t kDenseStage = Dense<BM, AKC>::kBytes + Dense<BN, BKC>::kBytes;
     constexpr uint32_t kPer = Dense<BM, AKC>::kInstr + Dense<BN, BKC>::kInstr;   // copy instructions per wave and slice
     static_assert(4 * kDenseStage <= Smem<BM, BN>::kBytes, "four dense stages fit the tile's LDS");
@@ -345,19 +354,20 @@ __global__ __launch_bounds__(kGemmThreads, 2) void lt_gemm_bf16_kernel(const Gem
     LT_COPY(0, 0);
     LT_COPY(1, 1);
     LT_COPY(2, 2);
-    landed<2 * kPer>();   // slice 0
+    LT_COPY(3, 3);
+    landed<3 * kPer>();   // slice 0
     __syncthreads();
     Frags f0 = dense_frags(0), f1;
     // Four slices per trip: stage numbers and the two fragment sets are compile-time.  Past the end
     // the body copies into stages nobody reads and reads fragments nobody uses; only the MFMAs
     // are guarded.
-#define LT_SLICE(J, CUR, NEXT)                                     \
-  {                                                              \
-    LT_COPY(i + (J) + 3u, ((J) + 3) & 3);                        \
-    landed<2 * kPer>(); /* slice i + J + 1 */                    \
-    __syncthreads();                                             \
-    NEXT = dense_frags(((J) + 1) & 3);                           \
-    if (i + (J) < n) mma(CUR);                                   \
+#define LT_SLICE(J, CUR, NEXT)                                                  \
+  {                                                                           \
+    landed_and_read<2 * kPer>(); /* slice i + J + 1; this wave's fragments */ \
+    __syncthreads();                                                          \
+    LT_COPY(i + (J) + 4u, (J) & 3);                                           \
+    NEXT = dense_frags(((J) + 1) & 3);                                        \
+    if (i + (J) < n) mma(CUR);                                                \
   }
     for (uint32_t i = 0; i < n; i += 4u) {
       LT_SLICE(0, f0, f1);

@@ -15,19 +15,22 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 // ---- streamed post program -------------------------------------------------------------------
 // Post programs whose inputs are all whole 4-vectors of one element type, addressed like the
-// output (a residual) or by column (a bias): the inputs of U of this lane's quads are fetched
-// into wide register tuples before any is used -- one memory round trip per U quads instead of
-// one per quad, with nothing in the fetch that depends on the program -- and a rolled loop then
-// interprets two quads per dispatch, as the streamed reductions do.  A program with one input
-// streams it twice (no branch in the fetch); the copy lands in a slot that the program writes
-// before it reads.
-template <int BM, int BN, int U, bool BF>
-__device__ __forceinline__ void post_streamed(const GemmArgs& a, const ProgRegs pr, const float* Cs, uint32_t tile_m, uint32_t tile_n,
-                                              int64_t base) {
+// output (a residual) or by column (a bias).  What an interpreted epilogue costs is mostly fetch,
+// decode and dispatch of the instruction -- scalar work, the same for one quad or many -- and it
+// sits on the critical path: the workgroups of a launch reach their epilogues together, so nothing
+// runs under it.  So a lane's quads go through the interpreter Q at a time (Q = 8: a register
+// file of 4 slots x 8 quads, one or two trips per lane; Q = 4: 8 slots x 4 quads).  The inputs of
+// the Q quads are fetched straight into the register file -- one memory round trip per trip, with
+// nothing in the fetch that depends on the program.  A program with one input fetches it twice (no
+// branch in the fetch); the copy lands in a slot that the program writes before it reads.
+template <int BM, int BN, int Q>
+__device__ __forceinline__ void post_wide(const GemmArgs& a, const ProgRegs pr, const float* Cs, uint32_t tile_m, uint32_t tile_n,
+                                          int64_t base, const bool bf) {
+  constexpr int NS = 32, SL = NS / Q;
   constexpr int kCStride = BN + kCPad;
   constexpr uint32_t kQuadsPerRow = BN / kVec, kRowStep = (uint32_t)kGemmThreads / kQuadsPerRow;
   constexpr uint32_t kTrips = (uint32_t)(BM * BN / kVec) / kGemmThreads;   // quads per lane
-  constexpr int UU = (uint32_t)U < kTrips ? U : (int)kTrips;
+  static_assert(kTrips % (uint32_t)Q == 0u, "a lane's quads make whole trips");
   const EwProg& p = a.post;
   const uint32_t n_code = p.n_code;
   const uint32_t r0 = threadIdx.x / kQuadsPerRow, c = (threadIdx.x % kQuadsPerRow) * kVec;
@@ -35,42 +38,64 @@ __device__ __forceinline__ void post_streamed(const GemmArgs& a, const ProgRegs 
   const char* ptr0 = (const char*)p.in[0].ptr;
   const char* ptr1 = (const char*)p.in[k1].ptr;
   const bool full0 = p.in[0].mode == kFull, full1 = p.in[k1].mode == kFull;
-  constexpr uint32_t kEsz = BF ? 2u : 4u;
+  const uint32_t col = tile_n + c;
 #pragma unroll 1
-  for (uint32_t pass = 0; pass < kTrips / (uint32_t)UU; ++pass) {
-    Stream<2, UU, BF> st;
+  for (uint32_t pass = 0; pass < kTrips / (uint32_t)Q; ++pass) {
+    uint32_t idx[Q];   // flat output index of quad j of this trip
 #pragma unroll
-    for (int u = 0; u < UU; ++u) {
-      const uint32_t r = r0 + (pass * (uint32_t)UU + (uint32_t)u) * kRowStep;
-      const uint32_t i = (uint32_t)(base + (int64_t)(tile_m + r) * a.o_row + tile_n + c);
-      const uint32_t e0 = full0 ? i : tile_n + c, e1 = full1 ? i : tile_n + c;
-      if (BF) {
-        typedef uint32_t U32x2 __attribute__((ext_vector_type(2)));
-        const U32x2 t0 = *(const U32x2*)(ptr0 + (size_t)e0 * kEsz), t1 = *(const U32x2*)(ptr1 + (size_t)e1 * kEsz);
-        st.s[0][2 * u] = __uint_as_float(t0.x); st.s[0][2 * u + 1] = __uint_as_float(t0.y);
-        st.s[1][2 * u] = __uint_as_float(t1.x); st.s[1][2 * u + 1] = __uint_as_float(t1.y);
-      } else {
-        const RawVec t0 = *(const RawVec*)(ptr0 + (size_t)e0 * kEsz), t1 = *(const RawVec*)(ptr1 + (size_t)e1 * kEsz);
-        st.s[0][4 * u] = t0.x; st.s[0][4 * u + 1] = t0.y; st.s[0][4 * u + 2] = t0.z; st.s[0][4 * u + 3] = t0.w;
-        st.s[1][4 * u] = t1.x; st.s[1][4 * u + 1] = t1.y; st.s[1][4 * u + 2] = t1.z; st.s[1][4 * u + 3] = t1.w;
+    for (int j = 0; j < Q; ++j) {
+      const uint32_t r = r0 + (pass * (uint32_t)Q + (uint32_t)j) * kRowStep;
+      idx[j] = (uint32_t)(base + (int64_t)(tile_m + r) * a.o_row + col);
+    }
+    RF<NS> f = rf_zero<NS>();
+    if (bf) {
+      typedef uint32_t U32x2 __attribute__((ext_vector_type(2)));
+      U32x2 t0[Q], t1[Q];
+#pragma unroll
+      for (int j = 0; j < Q; ++j) {
+        t0[j] = *(const U32x2*)(ptr0 + (size_t)(full0 ? idx[j] : col) * 2u);
+        t1[j] = *(const U32x2*)(ptr1 + (size_t)(full1 ? idx[j] : col) * 2u);
+      }
+#pragma unroll
+      for (int j = 0; j < Q; ++j) {
+        f.e[0][j * SL] = __uint_as_float(t0[j].x << 16);
+        f.e[1][j * SL] = __uint_as_float(t0[j].x & 0xffff0000u);
+        f.e[2][j * SL] = __uint_as_float(t0[j].y << 16);
+        f.e[3][j * SL] = __uint_as_float(t0[j].y & 0xffff0000u);
+        f.e[0][j * SL + 1] = __uint_as_float(t1[j].x << 16);
+        f.e[1][j * SL + 1] = __uint_as_float(t1[j].x & 0xffff0000u);
+        f.e[2][j * SL + 1] = __uint_as_float(t1[j].y << 16);
+        f.e[3][j * SL + 1] = __uint_as_float(t1[j].y & 0xffff0000u);
+      }
+    } else {
+      RawVec t0[Q], t1[Q];
+#pragma unroll
+      for (int j = 0; j < Q; ++j) {
+        t0[j] = *(const RawVec*)(ptr0 + (size_t)(full0 ? idx[j] : col) * 4u);
+        t1[j] = *(const RawVec*)(ptr1 + (size_t)(full1 ? idx[j] : col) * 4u);
+      }
+#pragma unroll
+      for (int j = 0; j < Q; ++j) {
+        f.e[0][j * SL] = t0[j].x; f.e[1][j * SL] = t0[j].y; f.e[2][j * SL] = t0[j].z; f.e[3][j * SL] = t0[j].w;
+        f.e[0][j * SL + 1] = t1[j].x; f.e[1][j * SL + 1] = t1[j].y; f.e[2][j * SL + 1] = t1[j].z; f.e[3][j * SL + 1] = t1[j].w;
       }
     }
-#pragma unroll 1
-    for (uint32_t u = 0; u < (uint32_t)UU; u += 2u) {
-      const uint32_t ra = r0 + (pass * (uint32_t)UU + u) * kRowStep, rb = ra + kRowStep;
-      const uint32_t ia = (uint32_t)(base + (int64_t)(tile_m + ra) * a.o_row + tile_n + c);
-      const uint32_t ib = (uint32_t)(base + (int64_t)(tile_m + rb) * a.o_row + tile_n + c);
-      RF<16> f = stream_place<16, 2, UU, BF, 0>(rf_zero<16>(), st, u);
-      f = stream_place<16, 2, UU, BF, 8>(f, st, u + 1u);
-      const float4 ta = *(const float4*)&Cs[ra * kCStride + c], tb = *(const float4*)&Cs[rb * kCStride + c];
+#pragma unroll
+    for (int j = 0; j < Q; ++j) {
+      const uint32_t r = r0 + (pass * (uint32_t)Q + (uint32_t)j) * kRowStep;
+      const float4 t = *(const float4*)&Cs[r * kCStride + c];
       Quad anchor;
-      anchor.v[0] = ta.x; anchor.v[1] = ta.y; anchor.v[2] = ta.z; anchor.v[3] = ta.w;
-      f = rf_set<16>(f, p.anchor_slot, anchor);
-      anchor.v[0] = tb.x; anchor.v[1] = tb.y; anchor.v[2] = tb.z; anchor.v[3] = tb.w;
-      f = rf_set<16>(f, p.anchor_slot + 8u, anchor);
-      f = interp<16, 2>(f, pr, n_code);
-      store_outputs<16, true, false, 0>(f, p, 0, ia, kVec);
-      store_outputs<16, true, false, 8>(f, p, 0, ib, kVec);
+      anchor.v[0] = t.x; anchor.v[1] = t.y; anchor.v[2] = t.z; anchor.v[3] = t.w;
+      f = rf_set<NS>(f, p.anchor_slot + (uint32_t)(j * SL), anchor);
+    }
+    f = interp<NS, Q>(f, pr, n_code);
+#pragma unroll
+    for (int o = 0; o < kMaxOut; ++o) {
+      if ((uint32_t)o < p.n_out) {
+        const EwOut& out = p.out[o];
+#pragma unroll
+        for (int j = 0; j < Q; ++j) store_vec4<false>(out.ptr, out.dtype, 0, idx[j], rf_get<NS>(f, out.slot + (uint32_t)(j * SL)));
+      }
     }
   }
 }
@@ -156,12 +181,14 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, const v16f (&acc)[MB
   }
   if (fast) {
     const int sk = post_stream_kind(p);
-    if (sk == 2) {
-      post_streamed<BM, BN, 8, true>(a, pr, Cs, tile_m, tile_n, base);
+    constexpr uint32_t kTrips = (uint32_t)(BM * BN / kVec) / kGemmThreads;
+    constexpr int Q8 = kTrips % 8u == 0u ? 8 : 4;
+    if (sk != 0 && p.n_slots <= 32u / (uint32_t)Q8) {
+      post_wide<BM, BN, Q8>(a, pr, Cs, tile_m, tile_n, base, sk == 2);
       return;
     }
-    if (sk == 1) {
-      post_streamed<BM, BN, 8, false>(a, pr, Cs, tile_m, tile_n, base);
+    if (sk != 0 && Q8 != 4) {
+      post_wide<BM, BN, 4>(a, pr, Cs, tile_m, tile_n, base, sk == 2);
       return;
     }
   }

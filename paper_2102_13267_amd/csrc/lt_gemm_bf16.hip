@@ -206,6 +206,28 @@ __device__ __forceinline__ void dma_tile(const uint16_t* base, int64_t s_x, int6
   }
 }
 
+// Two consecutive slices (ka, kb = ka + 32 unless clamped) at once, instruction by instruction.
+// A row of an [x][k] slice is 64 bytes, half a cache line; fetched one slice per iteration, the
+// second half comes a whole iteration's traffic later, misses the L1 again and costs a second
+// request to L2 (measured: 1.8 times the L2 requests, the address unit stalled by the cache for
+// 40 % of the kernel).  Back to back, the second access finds the line already on its way.
+template <int BX, bool KC>
+__device__ __forceinline__ void dma_tile2(const uint16_t* base, int64_t s_x, int64_t s_k, uint32_t x0, uint32_t ka, uint32_t kb,
+                                          uint32_t lane_off, uint32_t tile_a, uint32_t tile_b, uint32_t wave) {
+  typedef Dense<BX, KC> D;
+  constexpr uint32_t rows_per_instr = KC ? 64u : (uint32_t)kGemmThreads / D::kPerRow;
+#pragma unroll
+  for (uint32_t it = 0; it < D::kInstr; ++it) {
+    const uint16_t* ua = KC ? base + (int64_t)(x0 + it * rows_per_instr) * s_x + ka
+                            : base + (int64_t)(ka + it * rows_per_instr) * s_k + x0;
+    const uint16_t* ub = KC ? base + (int64_t)(x0 + it * rows_per_instr) * s_x + kb
+                            : base + (int64_t)(kb + it * rows_per_instr) * s_k + x0;
+    const uint32_t dst = (it * (uint32_t)kGemmThreads + wave * 64u) * 16u;
+    copy_1k((const char*)ua + lane_off, tile_a + dst);
+    copy_1k((const char*)ub + lane_off, tile_b + dst);
+  }
+}
+
 // The MFMA fragment of a 32-row (or 32-column) block of a dense, swizzled tile.
 template <int BX, bool KC>
 __device__ __forceinline__ v8bf fragment_dense(const char* tile, uint32_t x_blk, uint32_t kk, uint32_t lane) {
@@ -305,12 +327,8 @@ __global__ __launch_bounds__(kGemmThreads, 2) void lt_gemm_bf16_kernel(const Gem
   if (k_begin < k_end && whole) {
     // Software pipeline over slices j = 0 .. n-1, four LDS stages: the MFMAs of slice j run from
     // fragment registers, the fragments of slice j+1 are read from the stage that holds it, and
-    // slices j+2 .. j+4 are on their way from global memory straight into their stages -- no
-    // registers, no LDS write instructions, three iterations for a copy to land (the loop is bound
-    // by that latency, not by bandwidth, when the distance is shorter).  One barrier per slice:
-    // behind it slice j+1 has landed for every wave, and every wave's reads of slice j's stage
-    // (issued one iteration earlier) have returned -- each wave waits for its own LDS reads before
-    // the barrier -- so the copy of slice j+4 may overwrite that stage at once.  (Copies past the
+    // later slices are on their way from global memory straight into their stages -- no
+    // registers, no LDS write instructions, two iterations for a copy to land.  (Copies past the
     // end are clamped to the last slice: in bounds, unused.)
     constexpr uint32_t kDenseStage = Dense<BM, AKC>::kBytes + Dense<BN, BKC>::kBytes;
     constexpr uint32_t kPer = Dense<BM, AKC>::kInstr + Dense<BN, BKC>::kInstr;   // copy instructions per wave and slice
@@ -324,6 +342,14 @@ __global__ __launch_bounds__(kGemmThreads, 2) void lt_gemm_bf16_kernel(const Gem
     const uint32_t kf = k_begin + min((uint32_t)(I), n - 1u) * BK;                                                \
     dma_tile<BM, AKC>(A, a.a.s_row, a.a.s_col, tile_m, kf, a_off, lds0 + (STAGE) * kDenseStage, wave_u);          \
     dma_tile<BN, BKC>(B, a.b.s_col, a.b.s_row, tile_n, kf, b_off, lds0 + (STAGE) * kDenseStage + Dense<BM, AKC>::kBytes, wave_u); \
+  }
+#define LT_COPY2(I0, S0, I1, S1)                                                                                   \
+  {                                                                                                               \
+    const uint32_t ka = k_begin + min((uint32_t)(I0), n - 1u) * BK, kb = k_begin + min((uint32_t)(I1), n - 1u) * BK; \
+    dma_tile2<BM, AKC>(A, a.a.s_row, a.a.s_col, tile_m, ka, kb, a_off, lds0 + (S0) * kDenseStage,                  \
+                       lds0 + (S1) * kDenseStage, wave_u);                                                        \
+    dma_tile2<BN, BKC>(B, a.b.s_col, a.b.s_row, tile_n, ka, kb, b_off, lds0 + (S0) * kDenseStage + Dense<BM, AKC>::kBytes, \
+                       lds0 + (S1) * kDenseStage + Dense<BM, AKC>::kBytes, wave_u);                               \
   }
     auto dense_frags = [&](uint32_t stage) {
       const char* As = smem + stage * kDenseStage;
@@ -351,33 +377,65 @@ __global__ __launch_bounds__(kGemmThreads, 2) void lt_gemm_bf16_kernel(const Gem
         mma(f);
       }
     } else {
-    LT_COPY(0, 0);
-    LT_COPY(1, 1);
-    LT_COPY(2, 2);
-    LT_COPY(3, 3);
-    landed<3 * kPer>();   // slice 0
+    // Four slices per trip: stage numbers and the two fragment sets are compile-time.
+    //  * Some operand has k contiguous (64-byte rows per slice): copies go out in pairs, at odd
+    //    slices: slices i+J+3 and i+J+4 into the stages of slices i+J-1 (long read) and i+J (read
+    //    one iteration ago).  Waits and barriers are then needed at odd slices only: behind the
+    //    barrier of slice j (odd) the pair copied two slices earlier -- slices j+1 and j+2, whose
+    //    fragments are read in this iteration and the next -- has landed for every wave, and every
+    //    wave's reads of the two stages about to be overwritten have returned (each wave waits for
+    //    its own LDS reads before the barrier).
+    //  * Otherwise (rows of a slice are whole cache lines) pairs gain nothing and their bursts cost
+    //    a few percent: one copy per slice, slice i+J+4 into the stage of slice i+J behind the
+    //    barrier of slice i+J, which also tells that slice i+J+1 has landed for every wave.
+    // Past the end the body copies into stages nobody reads and reads fragments nobody uses; only
+    // the MFMAs are guarded.
+    constexpr bool kPairs = AKC || BKC;
+    if (kPairs) {
+      LT_COPY2(0, 0, 1, 1);
+      LT_COPY2(2, 2, 3, 3);
+      landed<2 * kPer>();   // slices 0 and 1
+    } else {
+      LT_COPY(0, 0);
+      LT_COPY(1, 1);
+      LT_COPY(2, 2);
+      LT_COPY(3, 3);
+      landed<3 * kPer>();   // slice 0
+    }
     __syncthreads();
     Frags f0 = dense_frags(0), f1;
-    // Four slices per trip: stage numbers and the two fragment sets are compile-time.  Past the end
-    // the body copies into stages nobody reads and reads fragments nobody uses; only the MFMAs
-    // are guarded.
-#define LT_SLICE(J, CUR, NEXT)                                                  \
-  {                                                                           \
-    landed_and_read<2 * kPer>(); /* slice i + J + 1; this wave's fragments */ \
-    __syncthreads();                                                          \
-    LT_COPY(i + (J) + 4u, (J) & 3);                                           \
-    NEXT = dense_frags(((J) + 1) & 3);                                        \
-    if (i + (J) < n) mma(CUR);                                                \
+#define LT_SLICE(J, CUR, NEXT, GUARD)                                            \
+  {                                                                            \
+    if (kPairs) {                                                              \
+      if ((J) & 1) {                                                           \
+        landed_and_read<0>();                                                  \
+        __syncthreads();                                                       \
+        LT_COPY2(i + (J) + 3u, ((J) + 3) & 3, i + (J) + 4u, (J) & 3);          \
+      }                                                                        \
+    } else {                                                                   \
+      landed_and_read<2 * kPer>();                                             \
+      __syncthreads();                                                         \
+      LT_COPY(i + (J) + 4u, (J) & 3);                                          \
+    }                                                                          \
+    NEXT = dense_frags(((J) + 1) & 3);                                         \
+    if (!(GUARD) || i + (J) < n) mma(CUR);                                     \
   }
-    for (uint32_t i = 0; i < n; i += 4u) {
-      LT_SLICE(0, f0, f1);
-      LT_SLICE(1, f1, f0);
-      LT_SLICE(2, f0, f1);
-      LT_SLICE(3, f1, f0);
+    uint32_t i = 0;
+    for (; i + 4u <= n; i += 4u) {   // straight-line code: copies, LDS reads and MFMAs interleave
+      LT_SLICE(0, f0, f1, false);
+      LT_SLICE(1, f1, f0, false);
+      LT_SLICE(2, f0, f1, false);
+      LT_SLICE(3, f1, f0, false);
+    }
+    if (i < n) {                     // one to three slices left
+      LT_SLICE(0, f0, f1, true);
+      LT_SLICE(1, f1, f0, true);
+      LT_SLICE(2, f0, f1, true);
     }
     landed<0>();   // nothing may still be on its way into LDS when the epilogue reuses it
     }
 #undef LT_SLICE
+#undef LT_COPY2
 #undef LT_COPY
   } else if (k_begin < k_end) {
     // ragged or unaligned tile: every access checked, one slice at a time

@@ -110,12 +110,11 @@ def load_library():
     lib.lt_last_error.argtypes = [P]
     lib.lt_last_error.restype = C.c_char_p
     # the recording fast path makes the same calls from C; it gets the entry points' addresses
-    try:
-        from . import _ltrec
-    except ImportError as e:
-        raise RuntimeError("paper_2102_13267_amd/_ltrec extension is missing: run python -m paper_2102_13267_amd.build") from e
+    if _ltrec is None:   # no fallback: without the native parts nothing in this package works
+        raise ImportError("paper_2102_13267_amd/_ltrec extension is missing or stale: run python -m paper_2102_13267_amd.build")
     addr = lambda fn: C.cast(fn, C.c_void_p).value
-    _ltrec.init(addr(lib.lt_op), addr(lib.lt_scalar), addr(lib.lt_release), addr(lib.lt_last_error))
+    _ltrec.init(addr(lib.lt_op), addr(lib.lt_scalar), addr(lib.lt_release), addr(lib.lt_last_error), addr(lib.lt_assign),
+                addr(lib.lt_release_many))
     global _REC
     _REC = _ltrec
     _LIB = lib
@@ -127,51 +126,50 @@ _NO_ATTRS_ADDR = C.addressof(_NO_ATTRS)
 _REC = None                   # the _ltrec extension (set by load_library)
 
 
-class Tensor:
-    """A handle (unique tensor id).  Dropping the last Python reference releases it, which is
-    how the library learns that a tensor is no longer live.  Element type and shape of an op's
-    result are asked from the library only when somebody reads them: recording an op is one call."""
-    __slots__ = ("ctx", "tid", "_dtype", "_shape", "_keep", "__weakref__")
+# The tensor handle is a C type of the recording extension (creating and dropping one per recorded
+# op is part of the hot path): Tensor(ctx, tid, dtype=None, shape=None, keep=None) with attributes
+# ctx, tid, dtype, shape.  Dropping the last Python reference releases the tensor, which is how the
+# library learns that it is no longer live (liveness matters when the trace is cut, not before: dead
+# ids are collected in Context._dead and handed over in one call -- see Context._flush).  Element
+# type and shape of an op's result are asked from the library only when somebody reads them.
+_LTREC_API = 3   # what this file expects of the extension (its `API` attribute)
+try:
+    from . import _ltrec
+    if getattr(_ltrec, "API", 0) != _LTREC_API:
+        raise ImportError("stale _ltrec")
+    Tensor = _ltrec.Tensor
+except ImportError:   # not built yet, or built from older sources: load_library() says so
+    _ltrec = None     # (the package must stay importable for its own build module)
+    Tensor = None
 
-    def __init__(self, ctx, tid, dtype=None, shape=None, keep=None):
-        self.ctx, self.tid, self._keep = ctx, tid, keep
-        self._dtype, self._shape = dtype, (None if shape is None else tuple(shape))
 
-    def _query(self):
-        dt, rank = C.c_int(), C.c_int()
-        dims = (C.c_int64 * MAX_RANK)()
-        self.ctx._check(self.ctx._lib.lt_shape(self.ctx._h, self.tid, C.byref(dt), C.byref(rank), dims))
-        self._dtype, self._shape = _DTYPE_NAMES[dt.value], tuple(dims[i] for i in range(rank.value))
+def _query(t):
+    dt, rank = C.c_int(), C.c_int()
+    dims = (C.c_int64 * MAX_RANK)()
+    t.ctx._check(t.ctx._lib.lt_shape(t.ctx._h, t.tid, C.byref(dt), C.byref(rank), dims))
+    t._dtype, t._shape = _DTYPE_NAMES[dt.value], tuple(dims[i] for i in range(rank.value))
 
-    @property
-    def dtype(self):
-        if self._dtype is None:
-            self._query()
-        return self._dtype
 
-    @dtype.setter
-    def dtype(self, v):
-        self._dtype = v
+if _ltrec is not None:
+    _ltrec.set_query(_query)
+    _ltrec.set_error(LtError)   # a failed call raises LtError(status, message) straight from C
+    _rec_op = _ltrec.op
 
-    @property
-    def shape(self):
-        if self._shape is None:
-            self._query()
-        return self._shape
 
-    @shape.setter
-    def shape(self, v):
-        self._shape = None if v is None else tuple(v)
+def _plain(name, arity):
+    """Method that records op `name` (no attributes, `arity` operands: tensors or numbers)."""
+    code = OPCODES[name]
+    if arity == 1:
+        def method(self, x):
+            return _rec_op(self, self._hv, code, (x,), _NO_ATTRS_ADDR, 0, 1)
+    else:
+        def method(self, a, b):
+            return _rec_op(self, self._hv, code, (a, b), _NO_ATTRS_ADDR, 0, 1)
+    method.__name__ = method.__qualname__ = name
+    return method
 
-    def __del__(self):
-        # (liveness matters when the trace is cut, not before: dead ids are collected here and
-        # handed over in one call -- see Context._flush)
-        ctx = self.ctx
-        if ctx is not None:
-            ctx._dead.append(self.tid)
 
-    def __repr__(self):
-        return f"Tensor(id={self.tid}, {self.dtype}{list(self.shape)})"
+_ADD = OPCODES["add"]
 
 
 class Context:
@@ -213,13 +211,8 @@ class Context:
     def _flush(self):
         """Release the tensors that Python dropped since the last call (one call for all of them).
         Runs before anything that looks at liveness: barrier, fetch, the dumps, the statistics."""
-        dead = self._dead
-        if dead and self._h:
-            self._dead = []
-            arr = (C.c_uint64 * len(dead))(*dead)
-            self._lib.lt_release_many(self._h, arr, len(dead))
-        elif dead:
-            self._dead = []
+        if self._dead:
+            _ltrec.release_many(self._hv, self._dead)   # (empties the list; a closed context just forgets them)
 
     def close(self):
         if self._h:
@@ -295,36 +288,21 @@ class Context:
             addr, n_attr = at[0], at[1]
         else:
             addr, n_attr = _NO_ATTRS_ADDR, 0
-        try:
-            r = _REC.op(self._hv, OPCODES[name], inputs, addr, n_attr, n_out)
-        except _REC.Error as e:
-            raise LtError(e.args[0], e.args[1]) from None
-        if n_out == 1:
-            return Tensor(self, r)
-        return tuple(Tensor(self, t) for t in r)
+        return _rec_op(self, self._hv, OPCODES[name], inputs, addr, n_attr, n_out)
 
     # ---- the tensor API shared with the oracle's back ends -------------------------------------------
-    def neg(self, x): return self.op("neg", [x])
-    def abs(self, x): return self.op("abs", [x])
-    def exp(self, x): return self.op("exp", [x])
-    def log(self, x): return self.op("log", [x])
-    def tanh(self, x): return self.op("tanh", [x])
-    def sqrt(self, x): return self.op("sqrt", [x])
-    def rsqrt(self, x): return self.op("rsqrt", [x])
-    def recip(self, x): return self.op("recip", [x])
-    def relu(self, x): return self.op("relu", [x])
-    def gelu(self, x): return self.op("gelu", [x])
-    def square(self, x): return self.op("square", [x])
-    def sigmoid(self, x): return self.op("sigmoid", [x])
+    # ops without attributes skip op(): one Python frame per recorded op
+    neg, abs, exp, log = _plain("neg", 1), _plain("abs", 1), _plain("exp", 1), _plain("log", 1)
+    tanh, sqrt, rsqrt, recip = _plain("tanh", 1), _plain("sqrt", 1), _plain("rsqrt", 1), _plain("recip", 1)
+    relu, gelu, square, sigmoid = _plain("relu", 1), _plain("gelu", 1), _plain("square", 1), _plain("sigmoid", 1)
+    sub, mul, div = _plain("sub", 2), _plain("mul", 2), _plain("div", 2)
+    maximum, minimum = _plain("maximum", 2), _plain("minimum", 2)
+    relu_grad, gelu_grad = _plain("relu_grad", 2), _plain("gelu_grad", 2)    # (dy, x)
+
+    def add(self, a, b, alpha=None):   # a + alpha * b
+        return _rec_op(self, self._hv, _ADD, (a, b) if alpha is None else (a, b, alpha), _NO_ATTRS_ADDR, 0, 1)
+
     def cast(self, x, dtype): return self.op("cast", [x], [(ATTR_DTYPE, DTYPES[dtype])])
-    def add(self, a, b, alpha=None): return self.op("add", [a, b] if alpha is None else [a, b, alpha])
-    def sub(self, a, b): return self.op("sub", [a, b])
-    def mul(self, a, b): return self.op("mul", [a, b])
-    def div(self, a, b): return self.op("div", [a, b])
-    def maximum(self, a, b): return self.op("maximum", [a, b])
-    def minimum(self, a, b): return self.op("minimum", [a, b])
-    def relu_grad(self, dy, x): return self.op("relu_grad", [dy, x])
-    def gelu_grad(self, dy, x): return self.op("gelu_grad", [dy, x])
     def expand(self, x, size): return self.op("expand", [x], [(ATTR_DIM0 + i, int(d)) for i, d in enumerate(size)])
     def reshape(self, x, size): return self.op("reshape", [x], [(ATTR_DIM0 + i, int(d)) for i, d in enumerate(size)])
     def permute(self, x, dims): return self.op("permute", [x], [(ATTR_DIM0 + i, int(d)) for i, d in enumerate(dims)])
@@ -345,8 +323,7 @@ class Context:
         return self.op("matmul", [a, b], attrs)
 
     def assign(self, dst: Tensor, src: Tensor):
-        self._check(self._lib.lt_assign(self._h, dst.tid, src.tid))
-        dst._dtype, dst._shape = src._dtype, src._shape   # (unknown stays unknown: asked for on demand)
+        _ltrec.assign(self._hv, dst, src)   # (what is known of src's type and shape becomes dst's)
 
     def release(self, t: Tensor):
         self._flush()

@@ -9,7 +9,7 @@ import pytest
 import figures
 from conftest import ROOT, read_golden
 from oracle.structural import Tracer
-from paper_2102_13267_amd import Context, LtError, load_library
+from paper_2102_13267_amd import Context, LtError, Tensor, load_library
 from workloads import programs
 from workloads.inputs import C4_HYPER
 
@@ -263,3 +263,42 @@ def test_release_many_reports_a_stale_id_after_releasing_the_rest():
     for i in ids:
         assert lib.lt_release(ctx._h, i) == 2                # ... and the others are gone
     assert lib.lt_release_many(ctx._h, None, 0) == 0
+
+
+def test_tensor_handle_type_of_the_extension():
+    """The tensor handle is a C type: what is known of a result's type and shape is asked from the
+    library on first use, assign carries it over, dropping the handle queues its id for release,
+    and a failed call raises LtError with the library's status from C."""
+    import weakref
+    ctx = Context()
+    a = ctx.tensor(np.zeros((4, 8), np.float32))
+    b = ctx.tensor(np.zeros((8,), np.float32))
+    c = ctx.add(a, b)
+    assert type(c) is Tensor and c.ctx is ctx and c._shape is None and c._dtype is None
+    assert c.shape == (4, 8) and c.dtype == "f32" and c._shape == (4, 8)
+    assert repr(c) == f"Tensor(id={c.tid}, f32[4, 8])"
+    mean, = [ctx.sum(c, axis=1)]
+    d = ctx.tensor(np.zeros((4,), np.float32), donatable=True)
+    ctx.assign(d, mean)                                      # nothing known of `mean` yet: stays unknown, asked on demand
+    assert d._shape is None and d.shape == (4,)
+    outs = ctx.layer_norm(a, b, b)
+    assert isinstance(outs, tuple) and [t.shape for t in outs] == [(4, 8), (4,), (4,)]
+    with pytest.raises(LtError) as e:
+        ctx.add(a, ctx.tensor(np.zeros((3,), np.float32)))
+    assert e.value.status == 3 and "broadcast" in str(e.value)
+    gone = ctx.neg(a)
+    ctx.release(gone)
+    with pytest.raises(LtError) as e:
+        ctx.assign(d, gone)                                  # a released id
+    assert e.value.status == 2
+    ref, tid = weakref.ref(c), c.tid
+    ctx._flush()
+    del c
+    assert ref() is None and ctx._dead == [tid]
+    live = ctx.stats().live_tensors                          # (stats() hands the dead ids over first)
+    assert ctx._dead == []
+    t = Tensor(ctx, 987654321, "f32", [2, 3])                # an id the library never issued
+    assert t.shape == (2, 3)
+    del t
+    ctx.barrier()                                            # ... is forgotten without an error
+    assert ctx.stats().live_tensors == live

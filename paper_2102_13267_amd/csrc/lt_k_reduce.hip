@@ -144,7 +144,9 @@ __device__ __forceinline__ void col_fold(uint32_t red, float4& acc, const Quad& 
   acc.w = red_combine(red, acc.w, q.v[3]);
 }
 
-template <int NS, int NIN, int U, bool BF>
+// NC > 0: besides the NIN inputs read in full (input numbers a.vin) the program has per-row inputs
+// (a.cin: a mean, a reciprocal deviation), which a wave reads as one broadcast element per row.
+template <int NS, int NIN, int U, bool BF, int NC = 0>
 __global__ __launch_bounds__(kColBlock) void lt_col_reduce_kernel(const ColArgs a) {
   constexpr uint32_t kWaves = kColBlock / 64;
   __shared__ float4 lds[kColBlock];
@@ -168,6 +170,45 @@ __global__ __launch_bounds__(kColBlock) void lt_col_reduce_kernel(const ColArgs 
       constexpr int UU = NIN > 0 ? U : 1, NN = NIN > 0 ? NIN : 1;
       for (; r + (UU - 1) * kWaves < r1; r += UU * kWaves) {
         Stream<NN, UU, BF> st;
+        typename WideVec<UU>::type cw[NC > 0 ? NC : 1];   // per-row inputs of the UU rows
+        if (NC > 0) {
+#pragma unroll
+          for (int u = 0; u < UU; ++u) {
+            const uint64_t e = (uint64_t)(r + u * kWaves) * a.cols + blockIdx.x * 256u + lane * kVec;
+#pragma unroll
+            for (int k = 0; k < NN; ++k) {
+              const char* src = (const char*)pro.in[a.vin[k]].ptr;
+              if (BF) {
+                typedef uint32_t U32x2 __attribute__((ext_vector_type(2)));
+                const U32x2 t = *(const U32x2*)(src + e * 2u);
+                st.s[k][2 * u] = __uint_as_float(t.x);
+                st.s[k][2 * u + 1] = __uint_as_float(t.y);
+              } else {
+                const RawVec t = *(const RawVec*)(src + e * 4u);
+                st.s[k][4 * u] = t.x; st.s[k][4 * u + 1] = t.y; st.s[k][4 * u + 2] = t.z; st.s[k][4 * u + 3] = t.w;
+              }
+            }
+#pragma unroll
+            for (int j = 0; j < NC; ++j) {
+              const EwIn& in = pro.in[a.cin[j]];
+              cw[j][u] = load_elem<false>(in.ptr, in.dtype, r + u * kWaves);
+            }
+          }
+#pragma unroll 1
+          for (uint32_t u = 0; u < (uint32_t)UU; ++u) {
+            RF<NS> f = stream_place<NS, NN, UU, BF>(rf_zero<NS>(), st, u);   // (slots 0 .. NN-1: moved below)
+            Quad full[NN];
+#pragma unroll
+            for (int k = 0; k < NN; ++k) full[k] = rf_get<NS>(f, (uint32_t)k);
+#pragma unroll
+            for (int k = 0; k < NN; ++k) f = rf_set<NS>(f, a.vin[k], full[k]);
+#pragma unroll
+            for (int j = 0; j < NC; ++j) f = rf_set<NS>(f, a.cin[j], splat(cw[j][u]));
+            f = interp<NS>(f, pro_regs, pro_n);
+            col_fold(a.red, acc, rf_get(f, pro.anchor_slot));
+          }
+          continue;
+        }
 #pragma unroll
         for (int u = 0; u < UU; ++u)
           stream_fetch<NN, UU, BF>(st, u, pro, (uint64_t)(r + u * kWaves) * a.cols + blockIdx.x * 256u, lane * kVec);
@@ -311,15 +352,46 @@ hipError_t launch_all_reduce(const AllArgs& a, uint32_t grid, hipStream_t s) {
   else hipLaunchKernelGGL((lt_all_reduce_kernel<16, 0, 1, false, 1>), g, b, 0, s, a);
   return hipGetLastError();
 }
-hipError_t launch_col_reduce(const ColArgs& a, uint32_t grid_x, uint32_t grid_y, hipStream_t s) {
+// Host side: a program whose inputs are one or two whole tensors of one element type plus one or
+// two per-row vectors (the weight gradient of a layer norm: sum over rows of dy * (x - mean) * rstd).
+// Returns 0 (no), 1 (fp32) or 2 (bf16) and fills in a->vin, a->cin.
+static int mixed_kind(ColArgs* a) {
+  const EwProg& p = a->pro;
+  if (!p.fast || (a->cols % 4u) != 0u || p.n_slots > 16u) return 0;
+  uint32_t nv = 0, nc = 0, dt = 0;
+  for (uint32_t k = 0; k < p.n_in; ++k) {
+    const EwIn& in = p.in[k];
+    if (in.mode == kFull && in.fetch == kFetchVec4 && (nv == 0u || in.dtype == dt) && nv < 2u) {
+      dt = in.dtype;
+      a->vin[nv++] = k;
+    } else if (in.mode == kColVec && nc < 2u && (in.dtype == kF32 || in.dtype == kBF16)) {
+      a->cin[nc++] = k;
+    } else {
+      return 0;
+    }
+  }
+  if (nv == 0u || nc == 0u || (dt != kF32 && dt != kBF16)) return 0;
+  for (uint32_t j = nv; j < 2u; ++j) a->vin[j] = a->vin[0];
+  for (uint32_t j = nc; j < 2u; ++j) a->cin[j] = a->cin[0];
+  return dt == kF32 ? 1 : 2;
+}
+
+hipError_t launch_col_reduce(const ColArgs& args, uint32_t grid_x, uint32_t grid_y, hipStream_t s) {
   const dim3 g(grid_x, grid_y), b(kColBlock);
+  ColArgs a = args;
+  a.vin[0] = 0u; a.vin[1] = 1u; a.cin[0] = a.cin[1] = 0u;
   const int kind = (a.cols % 4u) == 0u ? stream_kind(a.pro) : 0;
   const uint32_t n_in = a.pro.n_in;
   if (kind == 1 && n_in == 1u) hipLaunchKernelGGL((lt_col_reduce_kernel<16, 1, 8, false>), g, b, 0, s, a);
   else if (kind == 1 && n_in == 2u) hipLaunchKernelGGL((lt_col_reduce_kernel<16, 2, 4, false>), g, b, 0, s, a);
   else if (kind == 2 && n_in == 1u) hipLaunchKernelGGL((lt_col_reduce_kernel<16, 1, 8, true>), g, b, 0, s, a);
   else if (kind == 2 && n_in == 2u) hipLaunchKernelGGL((lt_col_reduce_kernel<16, 2, 8, true>), g, b, 0, s, a);
-  else hipLaunchKernelGGL((lt_col_reduce_kernel<16, 0, 1, false>), g, b, 0, s, a);
+  else {
+    const int mk = mixed_kind(&a);
+    if (mk == 1) hipLaunchKernelGGL((lt_col_reduce_kernel<16, 2, 4, false, 2>), g, b, 0, s, a);
+    else if (mk == 2) hipLaunchKernelGGL((lt_col_reduce_kernel<16, 2, 8, true, 2>), g, b, 0, s, a);
+    else hipLaunchKernelGGL((lt_col_reduce_kernel<16, 0, 1, false>), g, b, 0, s, a);
+  }
   return hipGetLastError();
 }
 

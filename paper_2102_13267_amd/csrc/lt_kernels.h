@@ -129,6 +129,9 @@ struct ColArgs {
   float* partials;     // [gridDim.y, cols]
   uint32_t* tickets;   // [gridDim.x], zero before launch; reset by the kernel
   uint32_t rows, cols, red, pad;
+  // filled in by launch_col_reduce for the streamed variants: input numbers of the (up to two)
+  // inputs read in full and of the (up to two) per-row inputs (kColVec), padded with the first
+  uint32_t vin[2], cin[2];
 };
 
 // ---- row operators with a fixed body ---------------------------------------------------

@@ -788,3 +788,31 @@ def test_random_traces_numeric(ctx, shape, trials):
             err = rel_err(ctx.fetch(a), E.fetch(b))
             assert err <= 2e-5, (shape, trial, k, err)
         del got, ref, lt, et
+
+
+@pytest.mark.parametrize("rows,cols,dtype", [(8, 256, "f32"), (67, 512, "f32"), (64, 1024, "bf16"), (521, 768, "bf16"),
+                                              (2048, 1024, "bf16"), (300, 260, "f32"), (130, 250, "bf16")])
+def test_column_reductions_with_per_row_inputs(ctx, rows, cols, dtype):
+    """Column sums whose program reads per-row vectors next to whole tensors (the weight gradient
+    of a layer norm): row counts below, at and between multiples of what the waves of a workgroup
+    fetch per trip, one and two whole inputs, one and two per-row inputs, fp32 and bf16; the last
+    two shapes (cols not a multiple of 256, of 4) take the general path."""
+    E = Eager()
+    g = rng(700 + rows + cols)
+    conv = round_to_bf16 if dtype == "bf16" else (lambda t: t)
+    dy, x = (conv(g.standard_normal((rows, cols), dtype=np.float32)) for _ in range(2))
+    mu, rs = g.standard_normal(rows, dtype=np.float32), (g.random(rows, dtype=np.float32) + 0.5)
+
+    def prog(B, dy, x, mu, rs):
+        mu2, rs2 = B.reshape(mu, (rows, 1)), B.reshape(rs, (rows, 1))
+        xhat = B.mul(B.sub(x, mu2), rs2)
+        dgamma = B.sum(B.mul(dy, xhat), axis=0)              # two whole inputs, two per-row inputs
+        centred = B.sum(B.sub(x, mu2), axis=0)               # one whole input, one per-row input
+        scaled = B.amax(B.mul(B.mul(dy, x), rs2), axis=0)    # another reduction, per-row input last
+        return dgamma, centred, scaled
+
+    got = prog(ctx, ctx.tensor(dy, dtype=dtype), ctx.tensor(x, dtype=dtype), ctx.tensor(mu), ctx.tensor(rs))
+    ref = prog(E, E.tensor(dy, dtype=dtype), E.tensor(x, dtype=dtype), E.tensor(mu), E.tensor(rs))
+    tol = TOL16 if dtype == "bf16" else 2e-5 * max(1.0, rows ** 0.5 / 8)
+    for gt, rt, what in zip(got, ref, ("dgamma", "centred", "scaled")):
+        check(ctx, E, gt, rt, tol, what)

@@ -15,9 +15,12 @@
 // the executor does not recycle temporaries of a multi-stream plan before the streams have joined.
 //
 // Measured on the transformer-layer step (48 launches): spreading every launch by earliest start
-// gains 4 % there but costs a step of twenty 6-microsecond kernels 5 % (40 % with non-blocking
-// barriers): two events per edge are dearer than such a kernel.  The policy below (only narrow,
-// long launches move) keeps 3 % of the former and costs the latter nothing.
+// gains there but costs a step of twenty 6-microsecond kernels 5 % (40 % with non-blocking
+// barriers): two events per edge are dearer than such a kernel.  So what may leave the caller's
+// stream is what is long enough to pay for its events: column reductions of a few megabytes and
+// more, and any other launch estimated at kSpreadUs or more (consecutive independent contractions
+// then overlap one's epilogue and tail with the next one's start: +5 % on that step on top of the
+// reductions' +3 %); the small step is left alone.
 #include <algorithm>
 #include <map>
 #include <set>
@@ -93,6 +96,7 @@ void schedule_streams(Plan* plan) {
   for (auto& row : waited)
     for (int& w : row) w = -1;
   constexpr double kSyncUs = 4.0;   // what a cross-stream edge costs
+  constexpr double kSpreadUs = 15.0;   // launches at least this long may start early on a side stream
 
   for (size_t i = 0; i < n; ++i) {
     Launch& l = plan->launches[i];
@@ -108,15 +112,16 @@ void schedule_streams(Plan* plan) {
       for (int r : it->second.readers) deps.insert(r);
     }
     deps.erase((int)i);
-    // Stream choice.  A launch that fills the chip gains nothing from running next to another
-    // one that does, so those stay on the caller's stream, in plan order.  What moves to a side
-    // stream is work that leaves most of the chip idle and takes long enough to be worth two
-    // events: column reductions of a few megabytes and more (a chain of dependent trips, a fence
-    // and a last-workgroup pass, at most 256 workgroups).  A narrow launch that depends on side
-    // stream work follows it there, so that the caller's stream never stalls behind a side stream
-    // for the sake of a small kernel.
+    // Stream choice: the stream on which the launch can start first, among those it may use.
+    // Short launches stay on the caller's stream, in plan order (an event costs more than they
+    // do).  What may move: column reductions of a few megabytes and more (a chain of dependent
+    // trips, a fence and a last-workgroup pass, at most 256 workgroups: most of the chip is idle
+    // under them), and launches of kSpreadUs and more (workgroups of the next independent launch
+    // fill the chip while this one's last workgroups run their epilogues).  A narrow launch that
+    // depends on side stream work follows it there, so that the caller's stream never stalls
+    // behind a side stream for the sake of a small kernel.
     const bool narrow = l.kind == L_COL || (l.kind != L_GEMM && l.bytes < (4u << 20));
-    const bool movable = l.kind == L_COL && l.bytes >= (4u << 20);
+    const bool movable = l.kind == L_COL ? l.bytes >= (4u << 20) : estimate_us(l) >= kSpreadUs;
     int best = 0;
     double best_start = 0;
     for (int s = 0; s < kMaxStreams; ++s) {

@@ -96,7 +96,7 @@ void schedule_streams(Plan* plan) {
   for (auto& row : waited)
     for (int& w : row) w = -1;
   constexpr double kSyncUs = 4.0;   // what a cross-stream edge costs
-  constexpr double kSpreadUs = 15.0;   // launches at least this long may start early on a side stream
+  constexpr double kSpreadUs = 10.0;   // launches at least this long may start early on a side stream
 
   for (size_t i = 0; i < n; ++i) {
     Launch& l = plan->launches[i];

@@ -70,6 +70,14 @@ __global__ __launch_bounds__(kBlock) void lt_all_reduce_kernel(const AllArgs a) 
     constexpr int UU = NIN > 0 ? U : 1, NN = NIN > 0 ? NIN : 1;
     const uint64_t per_trip = (uint64_t)gridDim.x * UU * kBlock;
     const uint64_t trips = nvec / per_trip;
+    // A prologue of one instruction, square or abs of the operand, is applied in place (same
+    // values, same order of additions as the interpreter's): the interpreter's dispatch is what
+    // keeps such a reduction from the memory system's rate, and these two are every norm.
+    uint32_t lone = 0;
+    if (NN == 1 && pro_n == 1u) {
+      const uint32_t w = pro.code[0], op = w & 0xffu;
+      if ((op == kSquare || op == kAbs) && ((w >> 13) & 63u) == 0u && ((w >> 8) & 31u) == pro.anchor_slot) lone = op;
+    }
     for (uint64_t t = 0; t < trips; ++t) {
       const uint64_t v0 = t * per_trip + (uint64_t)blockIdx.x * UU * kBlock;   // wave-uniform
       Stream<NN, UU, BF> st;
@@ -78,6 +86,14 @@ __global__ __launch_bounds__(kBlock) void lt_all_reduce_kernel(const AllArgs a) 
       if (NN == 1 && pro_n == 0u) {   // the operand itself is reduced: nothing to interpret
 #pragma unroll
         for (int u = 0; u < UU; ++u) acc = fold_vec(a.red, acc, stream_quad<NN, UU, BF>(st, 0, u), kVec);
+      } else if (NN == 1 && lone != 0u) {   // one unary instruction on the operand (a norm: sum of squares, of magnitudes)
+#pragma unroll
+        for (int u = 0; u < UU; ++u) {
+          Quad q = stream_quad<NN, UU, BF>(st, 0, u);
+#pragma unroll
+          for (int v = 0; v < kVec; ++v) q.v[v] = lone == kSquare ? q.v[v] * q.v[v] : fabsf(q.v[v]);
+          acc = fold_vec(a.red, acc, q, kVec);
+        }
       } else {
 #pragma unroll 1
         for (uint32_t u = 0; u < (uint32_t)UU; u += Q) {

@@ -112,6 +112,30 @@ def test_sum_of_ones_is_exact(ctx):
     assert np.array_equal(ctx.fetch(ctx.sum(ctx.tensor(np.ones((100, 300), np.float32)), 1)), np.full(100, 300.0))
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_global_norms_over_several_trips(ctx, dtype):
+    """Global reductions large enough for the streamed kernel's trips (512 workgroups x 8 tiles) plus
+    a ragged rest: the bare operand, a lone square / abs (applied in place), and a prologue that
+    goes through the interpreter; signs alternate so that a dropped tile or a wrong sign shows."""
+    E = Eager()
+    n = 2 * 512 * 8 * 1024 + 5 * 4096 + 7
+    x = (rng(11).standard_normal(n, dtype=np.float32) * (1.0 + (np.arange(n) % 3))).astype(np.float32)
+    if dtype == "bf16":
+        x = round_to_bf16(x)
+
+    def prog(B, x):
+        return (B.sum(x), B.sum(B.square(x)), B.sum(B.abs(x)), B.amax(B.abs(x)), B.sqrt(B.sum(B.square(x))),
+                B.sum(B.mul(B.square(x), 0.5)), B.amax(B.neg(x)))
+    got = prog(ctx, ctx.tensor(x, dtype=dtype))
+    ref = prog(E, E.tensor(x, dtype=dtype))
+    val = lambda B, t: float(np.asarray(B.fetch(t)).reshape(-1)[0])
+    gv, rv = [val(ctx, t) for t in got], [val(E, t) for t in ref]
+    tol = TOL16 if dtype == "bf16" else TOL32               # (bf16 results are rounded to bf16)
+    assert abs(gv[0] - rv[0]) <= 2e-6 * rv[2]                # the plain sum cancels: against the sum of magnitudes
+    for k in range(1, len(gv)):
+        assert abs(gv[k] - rv[k]) <= tol * abs(rv[k]), (k, gv[k], rv[k])
+
+
 def test_reduction_with_prologue_and_epilogue(ctx):
     E = Eager()
     x = (rng(5).random((200, 96), dtype=np.float32) - 0.5).astype(np.float32)

@@ -17,6 +17,72 @@ __device__ __forceinline__ void run_post(const EwProg& post, const ProgRegs post
   store_outputs<16>(f, post, 0, (uint32_t)i, nvalid);
 }
 
+// Streamed row reduction: fp32 programs of at most eight slots whose inputs are one or two whole
+// tensors and at most one vector broadcast along rows, rows of a multiple of 16 x threads_per_row
+// columns.  A lane takes four 4-vectors of its row per trip (threads_per_row x 4 columns apart):
+// their loads go out together and the interpreter runs once for the four (8 slots x 4 vectors) --
+// what bounds a cache-resident row reduction with a long prologue is the interpreter's dispatch,
+// not memory.  NV, NR: whole inputs, row-vector inputs (the host sorts out which is which).
+template <int NV, int NR>
+__global__ __launch_bounds__(kBlock) void lt_row_reduce_stream_kernel(const RowArgs a) {
+  __shared__ float lds[kBlock / 64];
+  const EwProg& pro = a.pro;
+  const ProgRegs pro_regs = load_prog_regs(a.pro), post_regs = load_prog_regs(a.post);
+  const uint32_t pro_n = a.pro.n_code;
+  const uint32_t tpr = a.threads_per_row;
+  const uint32_t rows_per_block = kBlock / tpr;
+  const uint32_t lane = threadIdx.x % tpr;
+  const uint32_t sub = threadIdx.x / tpr;
+  const uint32_t nblocks = (a.rows + rows_per_block - 1) / rows_per_block;
+  const uint32_t step = tpr * kVec;   // columns between a lane's consecutive 4-vectors
+  const char* vp[NV];
+  uint32_t vslot[NV];
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    vslot[k] = a.vin[k];
+    vp[k] = (const char*)pro.in[vslot[k]].ptr;
+  }
+  const char* rp = NR ? (const char*)pro.in[a.rin].ptr : nullptr;
+  for (uint32_t blk = blockIdx.x; blk < nblocks; blk += gridDim.x) {
+    const uint32_t row = blk * rows_per_block + sub;
+    float acc = red_identity(a.red);
+    if (row < a.rows) {
+      for (uint32_t c = lane * kVec; c < a.cols; c += 4u * step) {   // (cols is a multiple of 4 * step)
+        RawVec v[NV][4], rv[NR ? 4 : 1];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const uint64_t e = (uint64_t)row * a.cols + c + (uint32_t)j * step;
+#pragma unroll
+          for (int k = 0; k < NV; ++k) v[k][j] = *(const RawVec*)(vp[k] + e * 4u);
+          if (NR) rv[j] = *(const RawVec*)(rp + (size_t)(c + (uint32_t)j * step) * 4u);
+        }
+        RF<32> f = rf_zero<32>();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          Quad q;
+#pragma unroll
+          for (int k = 0; k < NV; ++k) {
+            q.v[0] = v[k][j].x; q.v[1] = v[k][j].y; q.v[2] = v[k][j].z; q.v[3] = v[k][j].w;
+            f = rf_set<32>(f, vslot[k] + (uint32_t)(8 * j), q);
+          }
+          if (NR) {
+            q.v[0] = rv[j].x; q.v[1] = rv[j].y; q.v[2] = rv[j].z; q.v[3] = rv[j].w;
+            f = rf_set<32>(f, a.rin + (uint32_t)(8 * j), q);
+          }
+        }
+        f = interp<32, 4>(f, pro_regs, pro_n);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc = fold_vec(a.red, acc, rf_get<32>(f, pro.anchor_slot + (uint32_t)(8 * j)), kVec);
+      }
+    }
+    float r;
+    if (tpr == 64u) r = wave_reduce(a.red, acc);
+    else r = block_reduce(a.red, acc, lds);
+    if (a.red == kRedMean) r = r / (float)a.cols;
+    if (lane == 0 && row < a.rows) run_post(a.post, post_regs, splat(r), row, 1u);
+  }
+}
+
 // Row reduction.  threads_per_row is 64 (one wave per row, four rows per workgroup) or 256.
 __global__ __launch_bounds__(kBlock) void lt_row_reduce_kernel(const RowArgs a) {
   __shared__ float lds[kBlock / 64];
@@ -348,8 +414,50 @@ __global__ __launch_bounds__(kColBlock) void lt_col_reduce_kernel(const ColArgs 
 }
 
 
-hipError_t launch_row_reduce(const RowArgs& a, uint32_t grid, hipStream_t s) {
-  hipLaunchKernelGGL(lt_row_reduce_kernel, dim3(grid), dim3(kBlock), 0, s, a);
+// Host side: does the program qualify for the streamed row reduction?  Fills in a->vin, a->rin and,
+// when rows are a multiple of 1024 columns only, narrows threads_per_row to 64 (one wave per row)
+// so that a lane has four 4-vectors to take together.
+static bool row_stream_args(RowArgs* a, uint32_t* grid) {
+  const EwProg& p = a->pro;
+  if (!p.fast || !p.all_f32 || p.n_slots > 8u || p.n_in == 0u) return false;
+  uint32_t nv = 0, nr = 0;
+  for (uint32_t k = 0; k < p.n_in; ++k) {
+    const EwIn& in = p.in[k];
+    if (in.fetch != kFetchVec4 || in.dtype != kF32) return false;
+    if (in.mode == kFull && nv < 2u) a->vin[nv++] = k;
+    else if (in.mode == kRowVec && nr < 1u) { a->rin = k; ++nr; }
+    else return false;
+  }
+  if (nv == 0u) return false;
+  uint32_t tpr = a->threads_per_row;
+  if (a->cols % (16u * tpr) != 0u) {
+    tpr = 64u;
+    if (a->cols % (16u * tpr) != 0u) return false;
+  }
+  if (tpr != a->threads_per_row) {
+    a->threads_per_row = tpr;
+    const uint32_t rpb = (uint32_t)kBlock / tpr;
+    *grid = (a->rows + rpb - 1) / rpb < 4096u ? (a->rows + rpb - 1) / rpb : 4096u;
+    if (*grid == 0u) *grid = 1u;
+  }
+  a->n_vin = nv;
+  a->n_rin = nr;
+  for (uint32_t j = nv; j < 2u; ++j) a->vin[j] = a->vin[0];
+  return true;
+}
+
+hipError_t launch_row_reduce(const RowArgs& args, uint32_t grid, hipStream_t s) {
+  RowArgs a = args;
+  a.vin[0] = a.vin[1] = a.rin = a.n_vin = a.n_rin = 0u;
+  if (row_stream_args(&a, &grid)) {
+    const dim3 g(grid), b(kBlock);
+    if (a.n_vin == 1u && a.n_rin == 0u) hipLaunchKernelGGL((lt_row_reduce_stream_kernel<1, 0>), g, b, 0, s, a);
+    else if (a.n_vin == 1u) hipLaunchKernelGGL((lt_row_reduce_stream_kernel<1, 1>), g, b, 0, s, a);
+    else if (a.n_rin == 0u) hipLaunchKernelGGL((lt_row_reduce_stream_kernel<2, 0>), g, b, 0, s, a);
+    else hipLaunchKernelGGL((lt_row_reduce_stream_kernel<2, 1>), g, b, 0, s, a);
+    return hipGetLastError();
+  }
+  hipLaunchKernelGGL(lt_row_reduce_kernel, dim3(grid), dim3(kBlock), 0, s, args);
   return hipGetLastError();
 }
 hipError_t launch_all_reduce(const AllArgs& a, uint32_t grid, hipStream_t s) {

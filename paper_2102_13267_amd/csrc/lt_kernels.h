@@ -109,6 +109,9 @@ struct RowArgs {
   EwProg pro;          // iteration space [rows, cols]; its result is slot pro.anchor_slot
   EwProg post;         // iteration space [rows]
   uint32_t rows, cols, red, threads_per_row;
+  // filled in by launch_row_reduce for the streamed variant: input numbers of the (up to two) fp32
+  // inputs read in full and of the (up to one) fp32 vector broadcast along rows; counts
+  uint32_t vin[2], rin, n_vin, n_rin, pad;
 };
 
 // global reduction, single launch: per-workgroup partials, the last workgroup to finish

@@ -136,6 +136,30 @@ def test_global_norms_over_several_trips(ctx, dtype):
         assert abs(gv[k] - rv[k]) <= tol * abs(rv[k]), (k, gv[k], rv[k])
 
 
+@pytest.mark.parametrize("rows,cols", [(1, 1024), (7, 1024), (130, 2048), (33, 4096), (5, 8192), (9, 3072), (6, 1000)])
+def test_row_reductions_streamed(ctx, rows, cols):
+    """Row reductions whose rows are whole multiples of what a wave (1024 columns) or a workgroup
+    (4096) takes per trip -- four 4-vectors per lane and interpreter dispatch -- with one and two
+    whole inputs, a vector broadcast along rows, sum / max / mean, row counts that do not fill the
+    last workgroup; the last two shapes take the one-vector-at-a-time kernel."""
+    E = Eager()
+    g = rng(900 + rows + cols)
+    x, y = (g.standard_normal((rows, cols), dtype=np.float32) for _ in range(2))
+    b = g.standard_normal(cols, dtype=np.float32)
+
+    def prog(B, x, y, b):
+        s1 = B.sum(x, axis=1)                                          # the bare operand
+        s2 = B.amax(B.mul(B.tanh(B.add(B.mul(x, y), b)), 0.5), axis=1)  # two whole inputs + a row vector
+        s3 = B.mean(B.square(B.sub(y, b)), axis=1)                     # one whole input + a row vector
+        s4 = B.add(B.sum(B.exp(B.neg(B.abs(x))), axis=1), 1.0)        # a longer chain and an epilogue
+        return s1, s2, s3, s4
+    got = prog(ctx, ctx.tensor(x), ctx.tensor(y), ctx.tensor(b))
+    ref = prog(E, E.tensor(x), E.tensor(y), E.tensor(b))
+    check(ctx, E, got[0], ref[0], 2e-6 * cols ** 0.5 + TOL32, "sum")   # (sums of N(0,1) cancel: scale by sqrt(cols))
+    for gt, rt, what in zip(got[1:], ref[1:], ("max", "mean", "chain")):
+        check(ctx, E, gt, rt, TOL32, what)
+
+
 def test_reduction_with_prologue_and_epilogue(ctx):
     E = Eager()
     x = (rng(5).random((200, 96), dtype=np.float32) - 0.5).astype(np.float32)

@@ -2,15 +2,18 @@
 //
 // Workgroup tile 128 x 128 (128 x 64 for narrow outputs), k walked in slices of 32, four
 // wavefronts in a 2 x 2 arrangement, each owning 64 x 64 (64 x 32) as blocks of
-// v_mfma_f32_32x32x16_bf16.  What bounds this kernel is LDS bandwidth, not the matrix cores: the
-// 8 MFMAs of a 64 x 64 block and slice (256 cycles) need 8 KiB of fragments from LDS, and the
-// slice itself has to get into LDS first.  Two workgroups share a compute unit, so one's matrix
-// instructions run under the other's LDS traffic, barriers and epilogue.
+// v_mfma_f32_32x32x16_bf16.  What bounds this kernel is the way into the matrix cores, not the
+// matrix cores: per slice a workgroup brings 16 KiB through the L1 (64 bytes per cycle and compute
+// unit: 256 cycles) and reads 32 KiB of fragments from LDS for 32 MFMAs (256 cycles per SIMD) --
+// at the matrix cores' peak a 128 x 128 tile needs all of the L1's bandwidth.  Two workgroups
+// share a compute unit, so one's matrix instructions run under the other's copies, LDS traffic,
+// barriers and epilogue.
 //
 // Whole, 16-byte aligned tiles go from global memory into LDS without touching registers
 // (global_load_lds_dwordx4), into dense tiles whose bank conflicts a swizzle takes care of; four
-// stages, copies three slices ahead (see "whole tiles" below).  An MFMA lane wants 8 consecutive k
-// of one row (A) or column (B):
+// stages, copies two to three slices ahead, in pairs of slices when an operand's rows are half
+// cache lines (see "whole tiles" below).  An MFMA lane wants 8 consecutive k of one row (A) or
+// column (B):
 //  * k is the operand's contiguous dimension: the tile is [x][k] and a fragment is one
 //    ds_read_b128;
 //  * x (m or n) is the contiguous dimension: the tile stays as it arrives, [k][x], and the

@@ -241,36 +241,22 @@ static PyObject* raise_status(void* ctx, int st) {
   return NULL;
 }
 
-/* op(owner: Context, ctx: int, opcode: int, inputs: sequence of (Tensor | int | float),
- *    attrs_addr: int, n_attr: int, n_out: int) -> Tensor (n_out == 1) or tuple of Tensors */
-static PyObject* rec_op(PyObject* self, PyObject* const* args, Py_ssize_t nargs) {
-  if (nargs != 7) {
-    PyErr_SetString(PyExc_TypeError, "op(owner, ctx, opcode, inputs, attrs_addr, n_attr, n_out)");
-    return NULL;
-  }
+/* Record one op on `items` (tensors or numbers): lt_scalar for the numbers, lt_op, lt_release of
+ * those temporaries.  Returns the result tensor (n_out == 1) or a tuple of them. */
+static PyObject* record_core(PyObject* owner, void* ctx, long opcode, PyObject* const* items, Py_ssize_t n_in,
+                             const void* attrs, long n_attr, long n_out) {
   if (!p_op) {
     PyErr_SetString(PyExc_RuntimeError, "_ltrec.init has not been called");
     return NULL;
   }
-  PyObject* owner = args[0];
-  void* ctx = (void*)(uintptr_t)PyLong_AsUnsignedLongLong(args[1]);
-  const long opcode = PyLong_AsLong(args[2]);
-  const void* attrs = (const void*)(uintptr_t)PyLong_AsUnsignedLongLong(args[4]);
-  const long n_attr = PyLong_AsLong(args[5]);
-  const long n_out = PyLong_AsLong(args[6]);
-  if (PyErr_Occurred()) return NULL;
-  PyObject* seq = PySequence_Fast(args[3], "inputs must be a sequence");
-  if (!seq) return NULL;
-  const Py_ssize_t n_in = PySequence_Fast_GET_SIZE(seq);
   if (n_in > kMaxIn || n_out < 1 || n_out > kMaxOut) {
-    Py_DECREF(seq);
     PyErr_SetString(PyExc_ValueError, "too many operands or results");
     return NULL;
   }
   uint64_t ids[kMaxIn], temps[kMaxIn], outs[kMaxOut];
   int n_temp = 0, st = 0;
   for (Py_ssize_t i = 0; i < n_in && st == 0; ++i) {
-    PyObject* x = PySequence_Fast_GET_ITEM(seq, i);   /* borrowed */
+    PyObject* x = items[i];   /* borrowed */
     if (Py_TYPE(x) == &TensorType) {
       ids[i] = ((TensorObject*)x)->tid;
     } else if (PyFloat_Check(x) || PyLong_Check(x)) {
@@ -295,7 +281,6 @@ static PyObject* rec_op(PyObject* self, PyObject* const* args, Py_ssize_t nargs)
       }
     }
   }
-  Py_DECREF(seq);
   if (st == 0 && !PyErr_Occurred()) st = p_op(ctx, (uint16_t)opcode, ids, (int)n_in, attrs, (int)n_attr, outs, (int)n_out);
   for (int t = 0; t < n_temp; ++t) (void)p_release(ctx, temps[t]);
   if (PyErr_Occurred()) return NULL;
@@ -313,6 +298,143 @@ static PyObject* rec_op(PyObject* self, PyObject* const* args, Py_ssize_t nargs)
   }
   return tup;
 }
+
+/* op(owner: Context, ctx: int, opcode: int, inputs: sequence of (Tensor | int | float),
+ *    attrs_addr: int, n_attr: int, n_out: int) -> Tensor (n_out == 1) or tuple of Tensors */
+static PyObject* rec_op(PyObject* self, PyObject* const* args, Py_ssize_t nargs) {
+  if (nargs != 7) {
+    PyErr_SetString(PyExc_TypeError, "op(owner, ctx, opcode, inputs, attrs_addr, n_attr, n_out)");
+    return NULL;
+  }
+  PyObject* owner = args[0];
+  void* ctx = (void*)(uintptr_t)PyLong_AsUnsignedLongLong(args[1]);
+  const long opcode = PyLong_AsLong(args[2]);
+  const void* attrs = (const void*)(uintptr_t)PyLong_AsUnsignedLongLong(args[4]);
+  const long n_attr = PyLong_AsLong(args[5]);
+  const long n_out = PyLong_AsLong(args[6]);
+  if (PyErr_Occurred()) return NULL;
+  PyObject* seq = PySequence_Fast(args[3], "inputs must be a sequence");
+  if (!seq) return NULL;
+  PyObject* r = record_core(owner, ctx, opcode, PySequence_Fast_ITEMS(seq), PySequence_Fast_GET_SIZE(seq), attrs, n_attr, n_out);
+  Py_DECREF(seq);
+  return r;
+}
+
+/* ---- methods of the binding's Context for ops without attributes ----------------------------
+ * PlainOp(name, opcode, min_operands, max_operands, keyword=None) is a method descriptor: stored
+ * in the class, `ctx.mul(a, b)` calls it with (ctx, a, b) and no Python frame in between.  The
+ * context's handle is its `_hv` attribute.  `keyword` names an optional last operand that may also
+ * be passed by keyword, None meaning absent (add's alpha). */
+typedef struct {
+  PyObject_HEAD
+  vectorcallfunc vectorcall;
+  long opcode;
+  Py_ssize_t min_ops, max_ops;
+  PyObject* name;
+  PyObject* keyword;   /* interned str or NULL */
+} PlainOpObject;
+
+static PyObject* str_hv;
+
+static PyObject* plainop_call(PyObject* callable, PyObject* const* args, size_t nargsf, PyObject* kwnames) {
+  PlainOpObject* op = (PlainOpObject*)callable;
+  const Py_ssize_t nargs = PyVectorcall_NARGS(nargsf);
+  const Py_ssize_t nkw = kwnames ? PyTuple_GET_SIZE(kwnames) : 0;
+  if (nargs < 1) {
+    PyErr_Format(PyExc_TypeError, "%U() needs the context it is a method of", op->name);
+    return NULL;
+  }
+  PyObject* items[kMaxIn];
+  Py_ssize_t n = nargs - 1;
+  if (n > op->max_ops || n > kMaxIn) {
+    PyErr_Format(PyExc_TypeError, "%U() takes at most %zd operands", op->name, op->max_ops);
+    return NULL;
+  }
+  for (Py_ssize_t i = 0; i < n; ++i) items[i] = args[1 + i];
+  if (nkw) {
+    if (nkw != 1 || !op->keyword || n != op->max_ops - 1 ||
+        PyUnicode_Compare(PyTuple_GET_ITEM(kwnames, 0), op->keyword) != 0) {
+      PyErr_Format(PyExc_TypeError, "%U() got an unexpected keyword argument", op->name);
+      return NULL;
+    }
+    items[n++] = args[nargs];
+  }
+  if (op->keyword && n == op->max_ops && items[n - 1] == Py_None) --n;   /* the optional operand left out */
+  if (n < op->min_ops) {
+    PyErr_Format(PyExc_TypeError, "%U() takes at least %zd operands", op->name, op->min_ops);
+    return NULL;
+  }
+  PyObject* h = PyObject_GetAttr(args[0], str_hv);
+  if (!h) return NULL;
+  void* ctx = (void*)(uintptr_t)PyLong_AsUnsignedLongLong(h);
+  Py_DECREF(h);
+  if (PyErr_Occurred()) return NULL;
+  return record_core(args[0], ctx, op->opcode, items, n, NULL, 0, 1);
+}
+
+static PyObject* plainop_new(PyTypeObject* type, PyObject* args, PyObject* kw) {
+  static char* names[] = {"name", "opcode", "min_operands", "max_operands", "keyword", NULL};
+  PyObject *name, *keyword = Py_None;
+  long opcode;
+  Py_ssize_t lo, hi;
+  if (!PyArg_ParseTupleAndKeywords(args, kw, "Ulnn|O", names, &name, &opcode, &lo, &hi, &keyword)) return NULL;
+  if (lo < 1 || hi < lo || hi > kMaxIn || (keyword != Py_None && !PyUnicode_Check(keyword))) {
+    PyErr_SetString(PyExc_ValueError, "PlainOp(name, opcode, min_operands, max_operands, keyword=None)");
+    return NULL;
+  }
+  PlainOpObject* op = (PlainOpObject*)type->tp_alloc(type, 0);
+  if (!op) return NULL;
+  op->vectorcall = plainop_call;
+  op->opcode = opcode;
+  op->min_ops = lo;
+  op->max_ops = hi;
+  Py_INCREF(name);
+  op->name = name;
+  if (keyword != Py_None) {
+    Py_INCREF(keyword);
+    PyUnicode_InternInPlace(&keyword);
+    op->keyword = keyword;
+  } else {
+    op->keyword = NULL;
+  }
+  return (PyObject*)op;
+}
+
+static void plainop_dealloc(PlainOpObject* op) {
+  Py_XDECREF(op->name);
+  Py_XDECREF(op->keyword);
+  Py_TYPE(op)->tp_free((PyObject*)op);
+}
+
+static PyObject* plainop_get(PyObject* self, PyObject* obj, PyObject* type) {
+  if (!obj || obj == Py_None) {
+    Py_INCREF(self);
+    return self;
+  }
+  return PyMethod_New(self, obj);
+}
+
+static PyObject* plainop_repr(PlainOpObject* op) { return PyUnicode_FromFormat("<lt op %U (opcode %ld)>", op->name, op->opcode); }
+
+static PyMemberDef plainop_members[] = {
+    {"__name__", T_OBJECT_EX, offsetof(PlainOpObject, name), READONLY, "op name"},
+    {"opcode", T_LONG, offsetof(PlainOpObject, opcode), READONLY, "opcode recorded"},
+    {NULL}};
+
+static PyTypeObject PlainOpType = {
+    PyVarObject_HEAD_INIT(NULL, 0)
+    .tp_name = "paper_2102_13267_amd._ltrec.PlainOp",
+    .tp_basicsize = sizeof(PlainOpObject),
+    .tp_dealloc = (destructor)plainop_dealloc,
+    .tp_vectorcall_offset = offsetof(PlainOpObject, vectorcall),
+    .tp_repr = (reprfunc)plainop_repr,
+    .tp_call = PyVectorcall_Call,
+    .tp_flags = Py_TPFLAGS_DEFAULT | Py_TPFLAGS_HAVE_VECTORCALL | Py_TPFLAGS_METHOD_DESCRIPTOR,
+    .tp_doc = "PlainOp(name, opcode, min_operands, max_operands, keyword=None): a Context method that records one op",
+    .tp_members = plainop_members,
+    .tp_descr_get = plainop_get,
+    .tp_new = plainop_new,
+};
 
 /* assign(ctx: int, dst: Tensor, src: Tensor): lt_assign; what is known of src's type and shape
  * becomes what is known of dst's (unknown stays unknown: asked for on demand) */
@@ -385,13 +507,17 @@ PyMODINIT_FUNC PyInit__ltrec(void) {
   if (!m) return NULL;
   str_tid = PyUnicode_InternFromString("tid");
   str_dead = PyUnicode_InternFromString("_dead");
+  str_hv = PyUnicode_InternFromString("_hv");
   rec_error = PyErr_NewException("_ltrec.Error", NULL, NULL);
-  if (!str_tid || !str_dead || !rec_error) return NULL;
+  if (!str_tid || !str_dead || !str_hv || !rec_error) return NULL;
   Py_INCREF(rec_error);   /* one reference is the module attribute's, one stays with rec_error */
   if (PyModule_AddObject(m, "Error", rec_error) < 0) return NULL;
-  if (PyModule_AddIntConstant(m, "API", 3) < 0) return NULL;   /* bumped when the binding's expectations change */
+  if (PyModule_AddIntConstant(m, "API", 4) < 0) return NULL;   /* bumped when the binding's expectations change */
   if (PyType_Ready(&TensorType) < 0) return NULL;
   Py_INCREF(&TensorType);
   if (PyModule_AddObject(m, "Tensor", (PyObject*)&TensorType) < 0) return NULL;
+  if (PyType_Ready(&PlainOpType) < 0) return NULL;
+  Py_INCREF(&PlainOpType);
+  if (PyModule_AddObject(m, "PlainOp", (PyObject*)&PlainOpType) < 0) return NULL;
   return m;
 }

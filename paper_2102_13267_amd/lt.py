@@ -132,7 +132,7 @@ _REC = None                   # the _ltrec extension (set by load_library)
 # library learns that it is no longer live (liveness matters when the trace is cut, not before: dead
 # ids are collected in Context._dead and handed over in one call -- see Context._flush).  Element
 # type and shape of an op's result are asked from the library only when somebody reads them.
-_LTREC_API = 3   # what this file expects of the extension (its `API` attribute)
+_LTREC_API = 4   # what this file expects of the extension (its `API` attribute)
 try:
     from . import _ltrec
     if getattr(_ltrec, "API", 0) != _LTREC_API:
@@ -157,19 +157,11 @@ if _ltrec is not None:
 
 
 def _plain(name, arity):
-    """Method that records op `name` (no attributes, `arity` operands: tensors or numbers)."""
-    code = OPCODES[name]
-    if arity == 1:
-        def method(self, x):
-            return _rec_op(self, self._hv, code, (x,), _NO_ATTRS_ADDR, 0, 1)
-    else:
-        def method(self, a, b):
-            return _rec_op(self, self._hv, code, (a, b), _NO_ATTRS_ADDR, 0, 1)
-    method.__name__ = method.__qualname__ = name
-    return method
-
-
-_ADD = OPCODES["add"]
+    """Context method that records op `name` (no attributes, `arity` operands: tensors or numbers):
+    a method descriptor of the extension, called without a Python frame of its own."""
+    if _ltrec is None:      # (not built: nothing can be recorded anyway, load_library() says so)
+        return None
+    return _ltrec.PlainOp(name, OPCODES[name], arity, arity)
 
 
 class Context:
@@ -299,8 +291,7 @@ class Context:
     maximum, minimum = _plain("maximum", 2), _plain("minimum", 2)
     relu_grad, gelu_grad = _plain("relu_grad", 2), _plain("gelu_grad", 2)    # (dy, x)
 
-    def add(self, a, b, alpha=None):   # a + alpha * b
-        return _rec_op(self, self._hv, _ADD, (a, b) if alpha is None else (a, b, alpha), _NO_ATTRS_ADDR, 0, 1)
+    add = None if _ltrec is None else _ltrec.PlainOp("add", OPCODES["add"], 2, 3, "alpha")   # add(a, b, alpha=None): a + alpha * b
 
     def cast(self, x, dtype): return self.op("cast", [x], [(ATTR_DTYPE, DTYPES[dtype])])
     def expand(self, x, size): return self.op("expand", [x], [(ATTR_DIM0 + i, int(d)) for i, d in enumerate(size)])

@@ -302,3 +302,22 @@ def test_tensor_handle_type_of_the_extension():
     del t
     ctx.barrier()                                            # ... is forgotten without an error
     assert ctx.stats().live_tensors == live
+
+
+def test_plain_op_methods_are_descriptors_of_the_extension():
+    """Ops without attributes are method descriptors of the recording extension: called as methods,
+    through getattr, unbound with the context first; add's optional scale by position or keyword;
+    wrong operand counts and keywords are TypeErrors and record nothing."""
+    ctx = Context()
+    a, b = (ctx.tensor(np.zeros((4, 8), np.float32)) for _ in range(2))
+    base = ctx.stats().live_tensors
+    outs = [ctx.add(a, b), ctx.add(a, b, 0.5), ctx.add(a, b, alpha=0.5), ctx.add(a, b, None), ctx.add(a, b, alpha=None),
+            getattr(ctx, "mul")(a, 2.0), Context.neg(ctx, a), ctx.maximum(a, b), ctx.gelu_grad(a, b)]
+    assert all(type(t) is Tensor and t.shape == (4, 8) for t in outs)
+    ir = ctx.dump_ir()
+    assert ir.count("aten::add") == 5 and ir.count("aten::mul") == 1 and ir.count("aten::neg") == 1
+    for bad in (lambda: ctx.mul(a), lambda: ctx.mul(a, b, b), lambda: ctx.add(a), lambda: ctx.add(a, b, beta=1.0),
+                lambda: ctx.neg(a, x=1), lambda: ctx.add(a, b, 0.5, alpha=0.5), lambda: Context.neg()):
+        with pytest.raises(TypeError):
+            bad()
+    assert ctx.stats().live_tensors == base + len(outs)

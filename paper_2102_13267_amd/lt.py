@@ -164,6 +164,11 @@ def _plain(name, arity):
     return _ltrec.PlainOp(name, OPCODES[name], arity, arity)
 
 
+_CAST, _EXPAND, _RESHAPE, _PERMUTE = OPCODES["cast"], OPCODES["expand"], OPCODES["reshape"], OPCODES["permute"]
+_SUM, _AMAX, _MEAN = OPCODES["sum"], OPCODES["amax"], OPCODES["mean"]
+_LAYER_NORM, _MATMUL = OPCODES["layer_norm"], OPCODES["matmul"]
+
+
 class Context:
     """One lt_ctx.  device=None gives the null device ("CPU:0": records, hashes, lowers, launches
     nothing).  Otherwise `device` is a HIP ordinal and the workspace is a torch byte tensor."""
@@ -260,27 +265,43 @@ class Context:
     def _t(self, x) -> Tensor:
         return x if isinstance(x, Tensor) else self.scalar(x)
 
+    def _encode(self, key, attrs):
+        """The lt_attr block of `attrs` ((key, value) pairs), built once per distinct `key` and kept."""
+        arr = (lt_attr * max(1, len(attrs)))()
+        for i, (k, val) in enumerate(attrs):
+            arr[i].key = k
+            if isinstance(val, float):
+                arr[i].is_float = 1
+                arr[i].v.f = val
+            else:
+                arr[i].is_float = 0
+                arr[i].v.i = int(val)
+        at = self._attrs[key] = (C.addressof(arr), len(attrs), arr)   # (arr is kept alive here)
+        return at
+
     def op(self, name, inputs, attrs=(), n_out=1):
         # recording an op is a hot path of the method: the call goes through the C fast path, which
         # also turns Python numbers among the operands into scalar tensors that live for the call
         if attrs:
             key = tuple(attrs)
-            at = self._attrs.get(key)
-            if at is None:
-                arr = (lt_attr * len(key))()
-                for i, (k, val) in enumerate(key):
-                    arr[i].key = k
-                    if isinstance(val, float):
-                        arr[i].is_float = 1
-                        arr[i].v.f = val
-                    else:
-                        arr[i].is_float = 0
-                        arr[i].v.i = int(val)
-                at = self._attrs[key] = (C.addressof(arr), len(key), arr)   # (arr is kept alive here)
+            at = self._attrs.get(key) or self._encode(key, key)
             addr, n_attr = at[0], at[1]
         else:
             addr, n_attr = _NO_ATTRS_ADDR, 0
         return _rec_op(self, self._hv, OPCODES[name], inputs, addr, n_attr, n_out)
+
+    def _dims_op(self, code, x, dims):
+        # (the attribute block of a shape is looked up by the shape itself, not rebuilt per call)
+        key = (code, dims if type(dims) is tuple else tuple(dims))
+        at = self._attrs.get(key) or self._encode(key, [(ATTR_DIM0 + i, int(d)) for i, d in enumerate(key[1])])
+        return _rec_op(self, self._hv, code, (x,), at[0], at[1], 1)
+
+    def _axis_op(self, code, x, axis):
+        if axis is None:
+            return _rec_op(self, self._hv, code, (x,), _NO_ATTRS_ADDR, 0, 1)
+        key = (code, int(axis))
+        at = self._attrs.get(key) or self._encode(key, [(ATTR_AXIS, key[1])])
+        return _rec_op(self, self._hv, code, (x,), at[0], at[1], 1)
 
     # ---- the tensor API shared with the oracle's back ends -------------------------------------------
     # ops without attributes skip op(): one Python frame per recorded op
@@ -293,25 +314,36 @@ class Context:
 
     add = None if _ltrec is None else _ltrec.PlainOp("add", OPCODES["add"], 2, 3, "alpha")   # add(a, b, alpha=None): a + alpha * b
 
-    def cast(self, x, dtype): return self.op("cast", [x], [(ATTR_DTYPE, DTYPES[dtype])])
-    def expand(self, x, size): return self.op("expand", [x], [(ATTR_DIM0 + i, int(d)) for i, d in enumerate(size)])
-    def reshape(self, x, size): return self.op("reshape", [x], [(ATTR_DIM0 + i, int(d)) for i, d in enumerate(size)])
-    def permute(self, x, dims): return self.op("permute", [x], [(ATTR_DIM0 + i, int(d)) for i, d in enumerate(dims)])
-    def sum(self, x, axis=None): return self.op("sum", [x], [] if axis is None else [(ATTR_AXIS, int(axis))])
-    def amax(self, x, axis=None): return self.op("amax", [x], [] if axis is None else [(ATTR_AXIS, int(axis))])
-    def mean(self, x, axis=None): return self.op("mean", [x], [] if axis is None else [(ATTR_AXIS, int(axis))])
-    def softmax(self, x): return self.op("softmax", [x])
-    def softmax_grad(self, dy, y): return self.op("softmax_grad", [dy, y])
-    def layer_norm(self, x, gamma, beta, eps=1e-5): return self.op("layer_norm", [x, gamma, beta], [(ATTR_EPS, float(eps))], n_out=3)
-    def layer_norm_grad(self, dy, x, gamma, mean, rstd): return self.op("layer_norm_grad", [dy, x, gamma, mean, rstd])
-    def xent(self, logits, labels): return self.op("xent", [logits, labels])
-    def xent_grad(self, logits, labels, scale): return self.op("xent_grad", [logits, labels, scale])
+    softmax, softmax_grad = _plain("softmax", 1), _plain("softmax_grad", 2)                 # (x), (dy, y)
+    layer_norm_grad = _plain("layer_norm_grad", 5)                                            # (dy, x, gamma, mean, rstd)
+    xent, xent_grad = _plain("xent", 2), _plain("xent_grad", 3)                               # (logits, labels[, scale])
+
+    def cast(self, x, dtype):
+        key = (_CAST, dtype)
+        at = self._attrs.get(key) or self._encode(key, [(ATTR_DTYPE, DTYPES[dtype])])
+        return _rec_op(self, self._hv, _CAST, (x,), at[0], at[1], 1)
+
+    def expand(self, x, size): return self._dims_op(_EXPAND, x, size)
+    def reshape(self, x, size): return self._dims_op(_RESHAPE, x, size)
+    def permute(self, x, dims): return self._dims_op(_PERMUTE, x, dims)
+    def sum(self, x, axis=None): return self._axis_op(_SUM, x, axis)
+    def amax(self, x, axis=None): return self._axis_op(_AMAX, x, axis)
+    def mean(self, x, axis=None): return self._axis_op(_MEAN, x, axis)
+
+    def layer_norm(self, x, gamma, beta, eps=1e-5):
+        key = (_LAYER_NORM, float(eps))
+        at = self._attrs.get(key) or self._encode(key, [(ATTR_EPS, key[1])])
+        return _rec_op(self, self._hv, _LAYER_NORM, (x, gamma, beta), at[0], at[1], 3)
 
     def matmul(self, a, b, trans_a=False, trans_b=False, dtype=None):
-        attrs = [(ATTR_TRANS_A, int(bool(trans_a))), (ATTR_TRANS_B, int(bool(trans_b)))]
-        if dtype is not None:
-            attrs.append((ATTR_DTYPE, DTYPES[dtype]))
-        return self.op("matmul", [a, b], attrs)
+        key = (_MATMUL, bool(trans_a), bool(trans_b), dtype)
+        at = self._attrs.get(key)
+        if at is None:
+            attrs = [(ATTR_TRANS_A, int(key[1])), (ATTR_TRANS_B, int(key[2]))]
+            if dtype is not None:
+                attrs.append((ATTR_DTYPE, DTYPES[dtype]))
+            at = self._encode(key, attrs)
+        return _rec_op(self, self._hv, _MATMUL, (a, b), at[0], at[1], 1)
 
     def assign(self, dst: Tensor, src: Tensor):
         _ltrec.assign(self._hv, dst, src)   # (what is known of src's type and shape becomes dst's)

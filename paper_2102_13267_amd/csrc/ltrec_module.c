@@ -20,6 +20,7 @@ typedef int (*lt_release_fn)(void* ctx, uint64_t t);
 typedef const char* (*lt_last_error_fn)(void* ctx);
 typedef int (*lt_assign_fn)(void* ctx, uint64_t dst, uint64_t src);
 typedef int (*lt_release_many_fn)(void* ctx, const uint64_t* ids, size_t n);
+typedef int (*lt_barrier_fn)(void* ctx, int blocking, void* info);
 
 static lt_op_fn p_op;
 static lt_scalar_fn p_scalar;
@@ -27,6 +28,7 @@ static lt_release_fn p_release;
 static lt_last_error_fn p_last_error;
 static lt_assign_fn p_assign;
 static lt_release_many_fn p_release_many;
+static lt_barrier_fn p_barrier;
 static PyObject* str_tid;
 static PyObject* str_dead;
 static PyObject* rec_error;
@@ -203,14 +205,15 @@ static PyTypeObject TensorType = {
 };
 
 static PyObject* rec_init(PyObject* self, PyObject* args) {
-  unsigned long long a, b, c, d, e, f;
-  if (!PyArg_ParseTuple(args, "KKKKKK", &a, &b, &c, &d, &e, &f)) return NULL;
+  unsigned long long a, b, c, d, e, f, g;
+  if (!PyArg_ParseTuple(args, "KKKKKKK", &a, &b, &c, &d, &e, &f, &g)) return NULL;
   p_op = (lt_op_fn)(uintptr_t)a;
   p_scalar = (lt_scalar_fn)(uintptr_t)b;
   p_release = (lt_release_fn)(uintptr_t)c;
   p_last_error = (lt_last_error_fn)(uintptr_t)d;
   p_assign = (lt_assign_fn)(uintptr_t)e;
   p_release_many = (lt_release_many_fn)(uintptr_t)f;
+  p_barrier = (lt_barrier_fn)(uintptr_t)g;
   Py_RETURN_NONE;
 }
 
@@ -457,6 +460,32 @@ static PyObject* rec_assign(PyObject* self, PyObject* const* args, Py_ssize_t na
   Py_RETURN_NONE;
 }
 
+/* lt_release_many over the ids in the list, which is emptied.  0, or -1 with an exception set. */
+static int release_list(void* ctx, PyObject* lst) {
+  const Py_ssize_t n = PyList_GET_SIZE(lst);
+  if (n == 0) return 0;
+  uint64_t* ids = (uint64_t*)PyMem_Malloc((size_t)n * sizeof(uint64_t));
+  if (!ids) {
+    PyErr_NoMemory();
+    return -1;
+  }
+  for (Py_ssize_t i = 0; i < n; ++i) {
+    ids[i] = PyLong_AsUnsignedLongLong(PyList_GET_ITEM(lst, i));
+    if (PyErr_Occurred()) {
+      PyMem_Free(ids);
+      return -1;
+    }
+  }
+  /* (nothing below runs Python code, so no handle can die and grow the list in between) */
+  if (PyList_SetSlice(lst, 0, n, NULL) < 0) {
+    PyMem_Free(ids);
+    return -1;
+  }
+  if (ctx) (void)p_release_many(ctx, ids, (size_t)n);   /* an id the library no longer knows is not the caller's error */
+  PyMem_Free(ids);
+  return 0;
+}
+
 /* release_many(ctx: int, ids: list of int): lt_release_many over the list, which is emptied */
 static PyObject* rec_release_many(PyObject* self, PyObject* const* args, Py_ssize_t nargs) {
   if (nargs != 2 || !PyList_Check(args[1])) {
@@ -469,35 +498,43 @@ static PyObject* rec_release_many(PyObject* self, PyObject* const* args, Py_ssiz
   }
   void* ctx = (void*)(uintptr_t)PyLong_AsUnsignedLongLong(args[0]);
   if (PyErr_Occurred()) return NULL;
-  PyObject* lst = args[1];
-  const Py_ssize_t n = PyList_GET_SIZE(lst);
-  if (n == 0) Py_RETURN_NONE;
-  uint64_t* ids = (uint64_t*)PyMem_Malloc((size_t)n * sizeof(uint64_t));
-  if (!ids) return PyErr_NoMemory();
-  for (Py_ssize_t i = 0; i < n; ++i) {
-    ids[i] = PyLong_AsUnsignedLongLong(PyList_GET_ITEM(lst, i));
-    if (PyErr_Occurred()) {
-      PyMem_Free(ids);
-      return NULL;
-    }
-  }
-  /* (nothing below runs Python code, so no handle can die and grow the list in between) */
-  if (PyList_SetSlice(lst, 0, n, NULL) < 0) {
-    PyMem_Free(ids);
+  if (release_list(ctx, args[1]) < 0) return NULL;
+  Py_RETURN_NONE;
+}
+
+/* barrier(ctx: int, dead: list of int, blocking: int, info_addr: int): hands the dropped tensors over
+ * (lt_release_many, the list is emptied), then lt_barrier into the lt_barrier_info at info_addr.  The
+ * interpreter lock is released while the barrier runs (a blocking one waits for the device). */
+static PyObject* rec_barrier(PyObject* self, PyObject* const* args, Py_ssize_t nargs) {
+  if (nargs != 4 || !PyList_Check(args[1])) {
+    PyErr_SetString(PyExc_TypeError, "barrier(ctx, dead: list, blocking, info_addr)");
     return NULL;
   }
-  if (ctx) (void)p_release_many(ctx, ids, (size_t)n);   /* an id the library no longer knows is not the caller's error */
-  PyMem_Free(ids);
+  if (!p_barrier || !p_release_many) {
+    PyErr_SetString(PyExc_RuntimeError, "_ltrec.init has not been called");
+    return NULL;
+  }
+  void* ctx = (void*)(uintptr_t)PyLong_AsUnsignedLongLong(args[0]);
+  const long blocking = PyLong_AsLong(args[2]);
+  void* info = (void*)(uintptr_t)PyLong_AsUnsignedLongLong(args[3]);
+  if (PyErr_Occurred()) return NULL;
+  if (release_list(ctx, args[1]) < 0) return NULL;
+  int st;
+  Py_BEGIN_ALLOW_THREADS
+  st = p_barrier(ctx, blocking ? 1 : 0, info);
+  Py_END_ALLOW_THREADS
+  if (st != 0) return raise_status(ctx, st);
   Py_RETURN_NONE;
 }
 
 static PyMethodDef methods[] = {
-    {"init", rec_init, METH_VARARGS, "init(lt_op, lt_scalar, lt_release, lt_last_error, lt_assign, lt_release_many): addresses of the entry points"},
+    {"init", rec_init, METH_VARARGS, "init(lt_op, lt_scalar, lt_release, lt_last_error, lt_assign, lt_release_many, lt_barrier): addresses of the entry points"},
     {"set_error", rec_set_error, METH_O, "set_error(cls): the exception class raised as cls(status, message)"},
     {"set_query", rec_set_query, METH_O, "set_query(fn): fn(tensor) fills in tensor._dtype and tensor._shape"},
     {"op", (PyCFunction)(void (*)(void))rec_op, METH_FASTCALL, "record one op; returns its result tensor(s)"},
     {"assign", (PyCFunction)(void (*)(void))rec_assign, METH_FASTCALL, "record dst <- src"},
     {"release_many", (PyCFunction)(void (*)(void))rec_release_many, METH_FASTCALL, "release the listed tensor ids and empty the list"},
+    {"barrier", (PyCFunction)(void (*)(void))rec_barrier, METH_FASTCALL, "release the listed tensor ids, then lt_barrier"},
     {NULL, NULL, 0, NULL}};
 
 static struct PyModuleDef moduledef = {PyModuleDef_HEAD_INIT, "_ltrec", "recording fast path of the lt binding", -1, methods};
@@ -512,7 +549,7 @@ PyMODINIT_FUNC PyInit__ltrec(void) {
   if (!str_tid || !str_dead || !str_hv || !rec_error) return NULL;
   Py_INCREF(rec_error);   /* one reference is the module attribute's, one stays with rec_error */
   if (PyModule_AddObject(m, "Error", rec_error) < 0) return NULL;
-  if (PyModule_AddIntConstant(m, "API", 4) < 0) return NULL;   /* bumped when the binding's expectations change */
+  if (PyModule_AddIntConstant(m, "API", 5) < 0) return NULL;   /* bumped when the binding's expectations change */
   if (PyType_Ready(&TensorType) < 0) return NULL;
   Py_INCREF(&TensorType);
   if (PyModule_AddObject(m, "Tensor", (PyObject*)&TensorType) < 0) return NULL;

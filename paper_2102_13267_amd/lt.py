@@ -114,7 +114,7 @@ def load_library():
         raise ImportError("paper_2102_13267_amd/_ltrec extension is missing or stale: run python -m paper_2102_13267_amd.build")
     addr = lambda fn: C.cast(fn, C.c_void_p).value
     _ltrec.init(addr(lib.lt_op), addr(lib.lt_scalar), addr(lib.lt_release), addr(lib.lt_last_error), addr(lib.lt_assign),
-                addr(lib.lt_release_many))
+                addr(lib.lt_release_many), addr(lib.lt_barrier))
     global _REC
     _REC = _ltrec
     _LIB = lib
@@ -132,7 +132,7 @@ _REC = None                   # the _ltrec extension (set by load_library)
 # library learns that it is no longer live (liveness matters when the trace is cut, not before: dead
 # ids are collected in Context._dead and handed over in one call -- see Context._flush).  Element
 # type and shape of an op's result are asked from the library only when somebody reads them.
-_LTREC_API = 4   # what this file expects of the extension (its `API` attribute)
+_LTREC_API = 5   # what this file expects of the extension (its `API` attribute)
 try:
     from . import _ltrec
     if getattr(_ltrec, "API", 0) != _LTREC_API:
@@ -355,9 +355,8 @@ class Context:
 
     # ---- barrier, fetch, diagnostics -----------------------------------------------------------------------
     def barrier(self, blocking=True) -> BarrierInfo:
-        self._flush()
         info = BarrierInfo()
-        self._check(self._lib.lt_barrier(self._h, 1 if blocking else 0, C.byref(info)))
+        _ltrec.barrier(self._hv, self._dead, blocking, C.addressof(info))   # (hands the dropped tensors over first)
         return info
 
     def fetch(self, t: Tensor) -> np.ndarray:

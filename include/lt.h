@@ -187,7 +187,9 @@ lt_status lt_dump_plan(lt_ctx* ctx, char* buf, size_t cap, size_t* len);
 /*
  * Stream schedule of the plan used by the last barrier, one launch per line in enqueue order:
  * "L<i> <kind> R<region> stream=<0..3> slot=<quarter of the reduction scratch> record=<0|1>
- * waits=[<earlier launches on other streams>]".  Stream 0 is the caller's.  Same buffer rules.
+ * waits=[<earlier launches on other streams>] reads=[<storages>] writes=[<storages>]".  Stream 0
+ * is the caller's; a storage is p<n> (the caller's buffer number n of the trace, a donated output
+ * included) or t<n> (temporary number n of the plan).  Same buffer rules.
  */
 lt_status lt_dump_schedule(lt_ctx* ctx, char* buf, size_t cap, size_t* len);
 

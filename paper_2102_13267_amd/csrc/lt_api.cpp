@@ -645,7 +645,21 @@ lt_status lt_dump_schedule(lt_ctx* ctx, char* buf, size_t cap, size_t* len) {
       s += "L" + std::to_string(i) + " " + kinds[l.kind] + " R" + std::to_string(l.region) + " stream=" + std::to_string(l.stream) +
            " slot=" + std::to_string(l.scratch_slot) + " record=" + std::to_string(l.record) + " waits=[";
       for (size_t w = 0; w < l.waits.size(); ++w) s += (w ? "," : "") + std::to_string(l.waits[w]);
-      s += "]\n";
+      s += "]";
+      // what the launch reads and writes, from the plan's pointer patches (p<n>: caller's buffer
+      // number n, donated outputs included; t<n>: temporary storage n)
+      for (int wr = 0; wr < 2; ++wr) {
+        s += wr ? " writes=[" : " reads=[";
+        bool first = true;
+        for (const PtrPatch& pp : p.ptr_patches) {
+          if (pp.launch != i || pp.storage < 0 || (int)pp.write != wr) continue;
+          const Storage& st = p.storages[pp.storage];
+          s += (first ? "" : ",") + (st.param >= 0 ? "p" + std::to_string(st.param) : "t" + std::to_string(pp.storage));
+          first = false;
+        }
+        s += "]";
+      }
+      s += "\n";
     }
   }
   return copy_out(s, buf, cap, len);

@@ -7,7 +7,7 @@ import pytest
 
 from paper_2102_13267_amd import Context
 
-LINE = re.compile(r"L(\d+) (\w+) R(\d+) stream=(\d) slot=(\d) record=([01]) waits=\[([\d,]*)\]")
+LINE = re.compile(r"L(\d+) (\w+) R(\d+) stream=(\d) slot=(\d) record=([01]) waits=\[([\d,]*)\] reads=\[([\w,]*)\] writes=\[([\w,]*)\]")
 
 
 def parse(text):
@@ -15,9 +15,10 @@ def parse(text):
     for ln in text.splitlines():
         m = LINE.fullmatch(ln)
         assert m, ln
-        i, kind, region, stream, slot, record, waits = m.groups()
+        i, kind, region, stream, slot, record, waits, reads, writes = m.groups()
         out.append(dict(i=int(i), kind=kind, region=int(region), stream=int(stream), slot=int(slot), record=int(record),
-                        waits=[int(w) for w in waits.split(",") if w]))
+                        waits=[int(w) for w in waits.split(",") if w],
+                        reads=set(r for r in reads.split(",") if r), writes=set(w for w in writes.split(",") if w)))
     return out
 
 
@@ -31,6 +32,37 @@ def invariants(sched):
     for l in sched:
         if l["record"]:
             assert any(l["i"] in m["waits"] for m in sched), "no event without a waiter"
+
+
+def ordered_before(sched):
+    """before[j][s] = the last launch of stream s known to have finished when launch j starts
+    (-1: none): its own stream's predecessor, what that one knew, and what each event it waits for
+    brings along."""
+    before = []
+    last_on = {}
+    for l in sched:
+        know = dict(before[last_on[l["stream"]]]) if l["stream"] in last_on else {}
+        if l["stream"] in last_on:
+            know[l["stream"]] = last_on[l["stream"]]
+        for w in l["waits"]:
+            for s, k in list(before[w].items()) + [(sched[w]["stream"], w)]:
+                know[s] = max(know.get(s, -1), k)
+        before.append(know)
+        last_on[l["stream"]] = l["i"]
+    return before
+
+
+def hazards_are_ordered(sched):
+    """Every pair of launches that touch the same storage, at least one of them writing it, and
+    every pair of reductions that share a scratch quarter, run in plan order."""
+    before = ordered_before(sched)
+    for j, lj in enumerate(sched):
+        for i in range(j):
+            li = sched[i]
+            clash = (li["writes"] & (lj["reads"] | lj["writes"])) or (li["reads"] & lj["writes"])
+            scratch = li["kind"] in ("COL", "ALL") and lj["kind"] in ("COL", "ALL") and li["slot"] == lj["slot"]
+            if clash or scratch:
+                assert before[j].get(li["stream"], -1) >= i, (i, j, clash, li, lj)
 
 
 def f32(ctx, shape):
@@ -106,6 +138,71 @@ def test_in_place_update_waits_for_every_reader_on_other_streams():
     assert writer["i"] > col["i"]
     assert col["stream"] == writer["stream"] or col["i"] in writer["waits"]
     del warm, colsum
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_large_traces_keep_every_hazard_in_order(seed):
+    """Random traces over tensors large enough for their launches to leave the caller's stream:
+    contractions, elementwise chains, row / column / global reductions, in-place updates of
+    donated buffers.  Whatever the schedule, conflicting launches must stay ordered."""
+    g = np.random.Generator(np.random.PCG64(4000 + seed))
+    ctx = Context()
+    rows, cols = 4096, 1024
+    mats = [ctx.tensor(np.zeros((rows, cols), np.float32), dtype="f32", donatable=(k < 2)) for k in range(4)]
+    sq = [f32(ctx, (cols, cols)) for _ in range(2)]
+    vec = ctx.tensor(np.zeros((cols,), np.float32), dtype="f32", donatable=True)
+    keep = []
+    for _ in range(int(g.integers(8, 16))):
+        kind = int(g.integers(0, 7))
+        a, b = mats[int(g.integers(0, 4))], mats[int(g.integers(0, 4))]
+        if kind == 0:
+            t = ctx.matmul(a, sq[int(g.integers(0, 2))])
+        elif kind == 1:
+            t = ctx.matmul(a, b, trans_a=True)
+        elif kind == 2:
+            t = ctx.tanh(ctx.add(ctx.mul(a, 0.5), b))
+        elif kind == 3:
+            t = ctx.sum(ctx.mul(a, b), axis=0)
+        elif kind == 4:
+            t = ctx.sum(ctx.square(a), axis=1)
+        elif kind == 5:
+            t = ctx.sqrt(ctx.sum(ctx.square(a)))
+        else:
+            t = ctx.softmax(a)
+        if t.shape == (rows, cols) and g.random() < 0.5:
+            k = int(g.integers(0, 4))
+            if k < 2:
+                ctx.assign(mats[k], t)                       # in place: donated
+            else:
+                mats[k] = t                                  # the old tensor dies: its storage may be reused
+        elif t.shape == (cols,) and g.random() < 0.5:
+            ctx.assign(vec, ctx.add(vec, t))
+        else:
+            keep.append(t)
+    ctx.barrier()
+    sched = parse(ctx.dump_schedule())
+    invariants(sched)
+    hazards_are_ordered(sched)
+    assert any(l["stream"] > 0 for l in sched) or len(sched) < 3
+    del keep
+
+
+def test_hazard_check_sees_a_missing_event():
+    """The checker itself: with the events of a schedule that needs them taken away, it objects."""
+    ctx = Context()
+    x, w2 = f32(ctx, (4096, 1024)), f32(ctx, (1024, 1024))
+    y0 = ctx.matmul(x, f32(ctx, (1024, 1024)))               # one stream
+    s = ctx.sum(ctx.square(x), axis=0)                       # another
+    z = ctx.add(ctx.matmul(y0, w2), s)                       # reads both: an event, whichever stream it takes
+    ctx.barrier()
+    sched = parse(ctx.dump_schedule())
+    hazards_are_ordered(sched)
+    assert any(l["waits"] for l in sched)
+    for l in sched:
+        l["waits"] = []
+    with pytest.raises(AssertionError):
+        hazards_are_ordered(sched)
+    del y0, z
 
 
 def test_set_streams_argument_checks():

@@ -691,6 +691,73 @@ def test_streams_do_not_change_results():
         assert rel_err(got, E.fetch(r)) <= TOL32
 
 
+def _random_large_trace(c, g, mats, sq, vec):
+    """A random trace over large tensors (contractions, elementwise chains, row / column / global
+    reductions, a row operator, in-place updates of donated buffers); returns what it keeps."""
+    rows, cols = 2048, 1024
+    keep = []
+    for _ in range(int(g.integers(8, 14))):
+        kind = int(g.integers(0, 7))
+        a, b = mats[int(g.integers(0, 4))], mats[int(g.integers(0, 4))]
+        if kind == 0:
+            t = c.mul(c.matmul(a, sq[int(g.integers(0, 2))]), 0.03)
+        elif kind == 1:
+            t = c.mul(c.matmul(a, b, trans_a=True), 1e-3)
+        elif kind == 2:
+            t = c.tanh(c.add(c.mul(a, 0.5), b))
+        elif kind == 3:
+            t = c.sum(c.mul(a, b), axis=0)
+        elif kind == 4:
+            t = c.sum(c.square(a), axis=1)
+        elif kind == 5:
+            t = c.sqrt(c.sum(c.square(a)))
+        else:
+            t = c.softmax(a)
+        if t.shape == (rows, cols) and g.random() < 0.5:
+            k = int(g.integers(0, 4))
+            if k < 2:
+                c.assign(mats[k], t)
+            else:
+                mats[k] = t
+        elif t.shape == (cols,) and g.random() < 0.5:
+            c.assign(vec, c.add(c.mul(vec, 0.5), t))
+        else:
+            keep.append(t)
+    return keep
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_large_traces_same_on_one_stream_and_four(seed):
+    """Random traces whose launches are long enough to spread over streams, two steps each (events,
+    scratch quarters and arena blocks are reused): every kept result and every buffer updated in
+    place is bit-identical to the one-stream run."""
+    from paper_2102_13267_amd import Context
+    g0 = rng(6000 + seed)
+    data = [g0.standard_normal((2048, 1024)).astype(np.float32) for _ in range(4)]
+    sqd = [(g0.standard_normal((1024, 1024)) * 0.03).astype(np.float32) for _ in range(2)]
+    results = {}
+    for n_streams in (1, 4):
+        c = Context(device=0, workspace_bytes=1 << 30)
+        c.set_streams(n_streams)
+        mats = [c.tensor(d.copy(), donatable=(k < 2)) for k, d in enumerate(data)]
+        donated = mats[:2]
+        sq = [c.tensor(d) for d in sqd]
+        vec = c.tensor(np.zeros(1024, np.float32), donatable=True)
+        out = []
+        for step in range(2):
+            keep = _random_large_trace(c, rng(7000 + seed), list(mats), sq, vec)    # the same trace both steps
+            c.barrier()
+            out.append([c.fetch(t).copy() for t in keep] + [c.fetch(t).copy() for t in donated] + [c.fetch(vec).copy()])
+        if n_streams == 4:
+            assert any(f"stream={s}" in c.dump_schedule() for s in (1, 2, 3))
+        results[n_streams] = out
+        c.close()
+    for a_step, b_step in zip(results[1], results[4]):
+        assert len(a_step) == len(b_step)
+        for a, b in zip(a_step, b_step):
+            assert np.array_equal(np.atleast_1d(a).view(np.uint8), np.atleast_1d(b).view(np.uint8))
+
+
 def test_c3_layer_same_on_one_stream_and_four():
     """Transformer layer step at a size whose bias-gradient reductions are wide enough to leave the
     caller's stream: every output, gradient moment and parameter bit-identical to the one-stream run."""

@@ -146,6 +146,33 @@ def run_c4(steps, warmup, n=268_435_456):
     return dt, "f32", config, roof, extra, cpu
 
 
+def _c1_streaming_rate(n=16384, reps=5):
+    """The same trace on [n, n] operands (2 GiB of inputs at n = 16384, not a configuration of the
+    benchmark): at the configured size the row kernel's 8 MiB are cache resident and a launch is over
+    in microseconds, so this run is what shows the kernel's rate against HBM."""
+    import torch
+    from workloads import programs
+    ctx = _gpu_ctx(64 << 20)
+    gen = torch.Generator(device="cuda:0").manual_seed(1001)
+    x, y = (torch.rand(n, n, device="cuda:0", generator=gen) * 2 - 1 for _ in range(2))
+    b = torch.rand(n, device="cuda:0", generator=gen) * 2 - 1
+    tx, ty, tb = ctx.tensor(x), ctx.tensor(y), ctx.tensor(b)
+    out = programs.c1_trace(ctx, tx, ty, tb)
+    ctx.barrier(True)
+    ctx.set_profiling(True)
+    ms = []
+    for _ in range(reps):
+        out = programs.c1_trace(ctx, tx, ty, tb)
+        ctx.barrier(True)
+        ms.append(min(r["ms"] for r in ctx.last_launches() if r["kernel"] == "lt_row_reduce_kernel"))
+    ctx.set_profiling(False)
+    del out
+    ctx.close()
+    nbytes = 2 * 4 * n * n + 2 * 4 * n
+    best = min(ms)
+    return {"row_kernel_ms": best, "bytes": nbytes, "GBps": nbytes / (best * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (best * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+
 def run_c1(steps, warmup, rows=1024, cols=1024):
     from workloads import programs
     from workloads.inputs import c1_inputs
@@ -163,6 +190,8 @@ def run_c1(steps, warmup, rows=1024, cols=1024):
     roof["frac"] = roof["achieved"] / roof["peak"]
     extra = {"kernels": table, "plan": ctx.dump_plan(), "cache_hits": sum(i.cache_hit for i in infos)}
     config = {"workload": f"c1: 12-op elementwise+reduce trace on fp32 [{rows},{cols}]", "regions": int(infos[-1].n_regions)}
+    if rows == 1024 and cols == 1024:
+        extra["streaming_run_16384x16384"] = _c1_streaming_rate()
 
     def cpu():
         from oracle.numeric import Eager

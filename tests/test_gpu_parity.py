@@ -198,6 +198,39 @@ def test_c1_trace(ctx, rows, cols):
     assert np.max(np.abs(got)) == 1.0                # x / |x| is exact
 
 
+def test_c1_trace_streaming_size_sampled_rows():
+    """The C1 trace on [16384, 16384] operands (the size at which bench.py quotes the row kernel's
+    rate against HBM): row sums of sampled rows against the oracle's, which computes them one row
+    at a time, and the normalised output's exact maximum."""
+    import torch
+    from paper_2102_13267_amd import Context
+    n = 16384
+    c = Context(device=0, workspace_bytes=64 << 20)
+    gen = torch.Generator(device="cuda:0").manual_seed(1001)
+    x, y = (torch.rand(n, n, device="cuda:0", generator=gen) * 2 - 1 for _ in range(2))
+    b = torch.rand(n, device="cuda:0", generator=gen) * 2 - 1
+    tx, ty, tb = c.tensor(x), c.tensor(y), c.tensor(b)
+    t = c.tanh(c.add(c.mul(tx, ty), tb))
+    e = c.exp(c.neg(c.square(tx)))
+    s = c.sum(c.add(c.mul(t, e), ty, alpha=0.5), axis=1)      # the trace's row reduction, kept as a result
+    out = c.div(s, c.amax(c.abs(s)))
+    del t, e                                                  # (dead at the barrier, as inside c1_trace: never materialised)
+    info = c.barrier()
+    assert info.n_regions == 2
+    got_s, got_out = c.fetch(s), c.fetch(out)
+    assert np.max(np.abs(got_out)) == 1.0                     # x / |x| is exact
+    E = Eager()
+    bias = b.cpu().numpy()
+    for r in (0, 1, 4095, 4096, 9999, n - 1):
+        xr, yr = x[r].cpu().numpy()[None, :], y[r].cpu().numpy()[None, :]
+        zr = E.add(E.mul(E.tanh(E.add(E.mul(E.tensor(xr), E.tensor(yr)), E.tensor(bias))), E.exp(E.neg(E.square(E.tensor(xr))))),
+                   E.tensor(yr), alpha=0.5)
+        ref = float(np.asarray(E.fetch(E.sum(zr, axis=1))).reshape(-1)[0])
+        mag = float(np.asarray(E.fetch(E.sum(E.abs(zr), axis=1))).reshape(-1)[0])
+        assert abs(float(got_s[r]) - ref) <= 2e-6 * mag, (r, got_s[r], ref, mag)
+    c.close()
+
+
 def test_c1_full_size_ten_runs():
     from paper_2102_13267_amd import Context
     ctx = Context(device=0, workspace_bytes=64 << 20)     # a fresh cache: 1 miss + 9 hits

@@ -36,6 +36,7 @@ MFMA_PEAK_TFLOPS = {"bf16": 2516.6, "f32": 157.3}
 
 
 _STREAMS = 4   # --streams: streams a barrier may spread independent launches over
+_C1_STREAMING_RUN = True   # --no-streaming-run: C1 without its extra run on [16384, 16384] operands
 
 
 def _gpu_ctx(workspace_bytes):
@@ -190,7 +191,7 @@ def run_c1(steps, warmup, rows=1024, cols=1024):
     roof["frac"] = roof["achieved"] / roof["peak"]
     extra = {"kernels": table, "plan": ctx.dump_plan(), "cache_hits": sum(i.cache_hit for i in infos)}
     config = {"workload": f"c1: 12-op elementwise+reduce trace on fp32 [{rows},{cols}]", "regions": int(infos[-1].n_regions)}
-    if rows == 1024 and cols == 1024:
+    if rows == 1024 and cols == 1024 and _C1_STREAMING_RUN:
         extra["streaming_run_16384x16384"] = _c1_streaming_rate()
 
     def cpu():
@@ -370,13 +371,17 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy, so that a rocprofv3 --pmc run of this command "
                          "holds a kernel of known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
+    ap.add_argument("--no-streaming-run", action="store_true",
+                    help="c1: leave out the extra run of the trace on [16384, 16384] operands (a kernel trace of "
+                         "the command then holds the configured size only)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
               "(the path would shard by parameter range / batch: every replica records the same trace)", file=sys.stderr)
         sys.exit(2)
-    global _STREAMS
+    global _STREAMS, _C1_STREAMING_RUN
     _STREAMS = args.streams
+    _C1_STREAMING_RUN = not args.no_streaming_run
     defaults = {"c4": (20, 3), "c1": (200, 10), "c2": (200, 10), "c3": (10, 2), "c5": (100, 10)}
     headline = args.workload or "c4"
     steps = args.steps if args.steps is not None else defaults[headline][0]

@@ -276,18 +276,23 @@ __global__ __launch_bounds__(kColBlock) void lt_col_reduce_kernel(const ColArgs 
               cw[j][u] = load_elem<false>(in.ptr, in.dtype, r + u * kWaves);
             }
           }
+          // NS = 32: four rows per interpreter dispatch (8 slots x 4 rows), programs of at most 8 slots
+          constexpr int QQ = NS == 32 ? 4 : 1;
+          constexpr uint32_t SL = NS / QQ;
 #pragma unroll 1
-          for (uint32_t u = 0; u < (uint32_t)UU; ++u) {
-            RF<NS> f = stream_place<NS, NN, UU, BF>(rf_zero<NS>(), st, u);   // (slots 0 .. NN-1: moved below)
-            Quad full[NN];
+          for (uint32_t u = 0; u < (uint32_t)UU; u += QQ) {
+            RF<NS> f = rf_zero<NS>();
 #pragma unroll
-            for (int k = 0; k < NN; ++k) full[k] = rf_get<NS>(f, (uint32_t)k);
+            for (int j = 0; j < QQ; ++j) {
+              const RF<NS> one = stream_place<NS, NN, UU, BF>(rf_zero<NS>(), st, u + (uint32_t)j);   // (row u + j in slots 0 .. NN-1)
 #pragma unroll
-            for (int k = 0; k < NN; ++k) f = rf_set<NS>(f, a.vin[k], full[k]);
+              for (int k = 0; k < NN; ++k) f = rf_set<NS>(f, a.vin[k] + (uint32_t)j * SL, rf_get<NS>(one, (uint32_t)k));
 #pragma unroll
-            for (int j = 0; j < NC; ++j) f = rf_set<NS>(f, a.cin[j], splat(cw[j][u]));
-            f = interp<NS>(f, pro_regs, pro_n);
-            col_fold(a.red, acc, rf_get(f, pro.anchor_slot));
+              for (int c = 0; c < NC; ++c) f = rf_set<NS>(f, a.cin[c] + (uint32_t)j * SL, splat(cw[c][u + (uint32_t)j]));
+            }
+            f = interp<NS, QQ>(f, pro_regs, pro_n);
+#pragma unroll
+            for (int j = 0; j < QQ; ++j) col_fold(a.red, acc, rf_get(f, pro.anchor_slot + (uint32_t)j * SL));
           }
           continue;
         }
@@ -512,7 +517,10 @@ hipError_t launch_col_reduce(const ColArgs& args, uint32_t grid_x, uint32_t grid
   else if (kind == 2 && n_in == 2u) hipLaunchKernelGGL((lt_col_reduce_kernel<16, 2, 8, true>), g, b, 0, s, a);
   else {
     const int mk = mixed_kind(&a);
-    if (mk == 1) hipLaunchKernelGGL((lt_col_reduce_kernel<16, 2, 4, false, 2>), g, b, 0, s, a);
+    const bool four = a.pro.n_slots <= 8u;   // the program fits a quarter of a 32-wide register file
+    if (mk == 1 && four) hipLaunchKernelGGL((lt_col_reduce_kernel<32, 2, 4, false, 2>), g, b, 0, s, a);
+    else if (mk == 1) hipLaunchKernelGGL((lt_col_reduce_kernel<16, 2, 4, false, 2>), g, b, 0, s, a);
+    else if (mk == 2 && four) hipLaunchKernelGGL((lt_col_reduce_kernel<32, 2, 8, true, 2>), g, b, 0, s, a);
     else if (mk == 2) hipLaunchKernelGGL((lt_col_reduce_kernel<16, 2, 8, true, 2>), g, b, 0, s, a);
     else hipLaunchKernelGGL((lt_col_reduce_kernel<16, 0, 1, false>), g, b, 0, s, a);
   }

@@ -358,7 +358,18 @@ def run_c3(steps, warmup, bsz=32, seq=256, d=1024, ffn=4096, heads=16):
 WORKLOADS = {"c1": run_c1, "c2": run_c2, "c3": run_c3, "c4": run_c4, "c5": run_c5}
 
 
+def _build_if_nothing_is_built():
+    """liblt.so and the recording extension are loaded as built; only a tree without them is built
+    here (in a process of its own, before the package is imported)."""
+    pkg = os.path.join(ROOT, "paper_2102_13267_amd")
+    have = os.path.exists(os.path.join(pkg, "liblt.so")) and any(f.startswith("_ltrec") and f.endswith(".so") for f in os.listdir(pkg))
+    if not have:
+        import subprocess
+        subprocess.run([sys.executable, "-m", "paper_2102_13267_amd.build"], cwd=ROOT, check=True, stdout=sys.stderr)
+
+
 def main():
+    _build_if_nothing_is_built()
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)

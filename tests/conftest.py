@@ -8,6 +8,25 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+def _built():
+    """liblt.so and the recording extension exist in-tree (whether they are current is the builder's
+    business: after a change to a source, build again)."""
+    pkg = os.path.join(ROOT, "paper_2102_13267_amd")
+    return os.path.exists(os.path.join(pkg, "liblt.so")) and any(
+        f.startswith("_ltrec") and f.endswith(".so") for f in os.listdir(pkg))
+
+
+def _build_if_nothing_is_built():
+    # in a process of its own, and before the package is imported here: the binding looks for its
+    # extension when it is first imported
+    if not _built():
+        import subprocess
+        subprocess.run([sys.executable, "-m", "paper_2102_13267_amd.build"], cwd=ROOT, check=True)
+
+
+_build_if_nothing_is_built()
+
+
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 

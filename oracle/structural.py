@@ -446,8 +446,9 @@ class Tracer:
             for (c, s) in n.ins:
                 out += struct.pack("<IB", index_of[c], s)
             if n.op == DEVICE_DATA:
-                out += struct.pack("<I", n_param)
-                param_ordinal_of_buffer.setdefault(id(n.buffer), n_param)
+                # own ordinal, then that of the first leaf on the same buffer (its alias class)
+                first = param_ordinal_of_buffer.setdefault(id(n.buffer), n_param)
+                out += struct.pack("<II", n_param, first)
                 n_param += 1
             elif n.op == SCALAR_PARAM:
                 out += struct.pack("<I", n_scalar)
@@ -877,7 +878,12 @@ class Tracer:
                 continue
             # every leaf that names the donated buffer
             pn = {(i, 0) for i in param_nodes if nd[i].buffer is nd[param_nodes[d]].buffer}
-            ok = True
+            # a second live tensor that folding reduced to the donor leaf itself (b = a * 1) is
+            # rebound to the donor's buffer by the barrier: it must keep the old value
+            ok = not any(w in pn for j, w in enumerate(root_vals) if j != k)
+            # a buffer that the cut knows under two parameter numbers is never written in place
+            if sum(1 for (i, _) in pn if live[i]) > 1:
+                ok = False
             readers = []
             for r in sorted(rlist, key=rid_of):
                 if not any(base(x) in pn for m in r["members"] for x in rins[m]):

@@ -91,8 +91,11 @@ void serialise_cut(lt_ctx* ctx, Cut* cut, std::vector<uint8_t>* out) {
       put<uint8_t>(out, (uint8_t)n.ins[k].slot);
     }
     if (n.op == OP_DEVICE_DATA) {
-      put<uint32_t>(out, (uint32_t)cut->param_nodes.size());
-      param_of_buffer.emplace(n.buffer.get(), (uint32_t)cut->param_nodes.size());
+      // ordinal, then the ordinal of the first leaf bound to the same buffer: whether two leaves
+      // alias decides what may be updated in place, so it is part of the program's identity
+      const uint32_t ordinal = (uint32_t)cut->param_nodes.size();
+      put<uint32_t>(out, ordinal);
+      put<uint32_t>(out, param_of_buffer.emplace(n.buffer.get(), ordinal).first->second);
       cut->param_nodes.push_back(idx);
     } else if (n.op == OP_SCALAR_PARAM) {
       put<uint32_t>(out, (uint32_t)cut->scalar_nodes.size());

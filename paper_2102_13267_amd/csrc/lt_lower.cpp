@@ -425,6 +425,15 @@ struct Lowering {
         return nd[x.node]->op == OP_DEVICE_DATA && x.slot == 0 && nd[x.node]->buffer.get() == buf;
       };
       bool ok = true;
+      // another live tensor that folding resolved to the donor leaf itself (b = a * 1) is bound
+      // to the donor's buffer after the barrier and must keep seeing the old value (section 4.3)
+      for (size_t j = 0; j < root_vals.size(); ++j)
+        if (j != k && names_donor(root_vals[j])) ok = false;
+      // two leaves on one buffer (a second handle made by lt_assign): the launch schedule tracks
+      // hazards per parameter, so a buffer known under two parameter numbers is never written
+      int leaves = 0;
+      for (int32_t pi : pnode) leaves += live[pi] && nd[pi]->buffer.get() == buf;
+      if (leaves > 1) ok = false;
       std::vector<Region*> readers;
       for (Region* r : alive_regions) {
         bool reads = false;

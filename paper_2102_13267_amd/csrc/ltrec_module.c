@@ -31,6 +31,7 @@ static lt_release_many_fn p_release_many;
 static lt_barrier_fn p_barrier;
 static PyObject* str_tid;
 static PyObject* str_dead;
+static PyObject* str_kept;
 static PyObject* rec_error;
 static PyObject* query_hook;   /* callable(tensor): fills in _dtype and _shape from the library */
 
@@ -104,6 +105,14 @@ static void tensor_dealloc(TensorObject* self) {
       }
     }
     Py_XDECREF(dead);
+    /* the trace being recorded may still name this leaf's device memory (its device_data node holds
+     * the raw pointer until the next barrier has run): the owner of that memory moves to the
+     * context's `_kept` list, which the binding empties once the barrier has been enqueued */
+    if (self->keep && self->keep != Py_None) {
+      PyObject* kept = PyObject_GetAttr(self->ctx, str_kept);
+      if (kept && PyList_Check(kept)) (void)PyList_Append(kept, self->keep);
+      Py_XDECREF(kept);
+    }
     PyErr_Clear();   /* a destructor has nobody to report to */
     PyErr_Restore(et, ev, tb);
   }
@@ -544,12 +553,13 @@ PyMODINIT_FUNC PyInit__ltrec(void) {
   if (!m) return NULL;
   str_tid = PyUnicode_InternFromString("tid");
   str_dead = PyUnicode_InternFromString("_dead");
+  str_kept = PyUnicode_InternFromString("_kept");
   str_hv = PyUnicode_InternFromString("_hv");
   rec_error = PyErr_NewException("_ltrec.Error", NULL, NULL);
-  if (!str_tid || !str_dead || !str_hv || !rec_error) return NULL;
+  if (!str_tid || !str_dead || !str_kept || !str_hv || !rec_error) return NULL;
   Py_INCREF(rec_error);   /* one reference is the module attribute's, one stays with rec_error */
   if (PyModule_AddObject(m, "Error", rec_error) < 0) return NULL;
-  if (PyModule_AddIntConstant(m, "API", 5) < 0) return NULL;   /* bumped when the binding's expectations change */
+  if (PyModule_AddIntConstant(m, "API", 6) < 0) return NULL;   /* bumped when the binding's expectations change */
   if (PyType_Ready(&TensorType) < 0) return NULL;
   Py_INCREF(&TensorType);
   if (PyModule_AddObject(m, "Tensor", (PyObject*)&TensorType) < 0) return NULL;

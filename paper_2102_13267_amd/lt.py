@@ -132,7 +132,7 @@ _REC = None                   # the _ltrec extension (set by load_library)
 # library learns that it is no longer live (liveness matters when the trace is cut, not before: dead
 # ids are collected in Context._dead and handed over in one call -- see Context._flush).  Element
 # type and shape of an op's result are asked from the library only when somebody reads them.
-_LTREC_API = 5   # what this file expects of the extension (its `API` attribute)
+_LTREC_API = 6   # what this file expects of the extension (its `API` attribute)
 try:
     from . import _ltrec
     if getattr(_ltrec, "API", 0) != _LTREC_API:
@@ -178,6 +178,7 @@ class Context:
         self._h = C.c_void_p()
         self._ids, self._outs, self._attrs = {}, {}, {}     # reusable ctypes argument arrays of op()
         self._dead = []                                     # ids of dropped tensors, not yet released
+        self._kept = []                                     # owners of device memory that dropped leaves of the pending trace name
         self._torch = None
         self._workspace = None
         if device is None:
@@ -351,12 +352,17 @@ class Context:
     def release(self, t: Tensor):
         self._flush()
         self._check(self._lib.lt_release(self._h, t.tid))
+        if t._keep is not None:
+            self._kept.append(t._keep)
         t.ctx = None
 
     # ---- barrier, fetch, diagnostics -----------------------------------------------------------------------
     def barrier(self, blocking=True) -> BarrierInfo:
         info = BarrierInfo()
         _ltrec.barrier(self._hv, self._dead, blocking, C.addressof(info))   # (hands the dropped tensors over first)
+        # Every launch that reads a dropped leaf's memory is now enqueued on the context's stream, which is
+        # the stream the memory was allocated on: torch hands a freed block out again in stream order only.
+        self._kept.clear()
         return info
 
     def fetch(self, t: Tensor) -> np.ndarray:
@@ -366,7 +372,10 @@ class Context:
         n = int(np.prod(t.shape, dtype=np.int64)) if t.shape else 1
         np_t = {0: np.float32, 1: np.uint16, 2: np.int32, 3: np.int64}[code]
         out = np.empty(n, dtype=np_t)
+        before = self.stats().barriers if self._kept else 0
         self._check(self._lib.lt_fetch(self._h, t.tid, out.ctypes.data_as(C.c_void_p), out.nbytes))
+        if self._kept and self.stats().barriers != before:   # the fetch of a pending tensor ran a barrier
+            self._kept.clear()
         if code == 1:
             out = (out.astype(np.uint32) << 16).view(np.float32)
         return out.reshape(t.shape)

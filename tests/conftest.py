@@ -35,3 +35,21 @@ def read_golden(name):
     path = os.path.join(ROOT, "tests", "golden", name)
     with open(path) as f:
         return "".join(line for line in f if not line.startswith("#")).strip()
+
+
+def pytest_terminal_summary(terminalreporter, exitstatus, config):
+    """After a GPU run: per test, the worst norm-wise error as a fraction of its tolerance and the
+    element-wise pass rates (see tests/test_gpu_parity.py::elementwise_report)."""
+    mod = sys.modules.get("test_gpu_parity")
+    report = getattr(mod, "REPORT", None) if mod else None
+    if not report:
+        return
+    lines = ["parity report: test | worst norm-wise error / tolerance | elements | allclose(rtol=tol, atol=tol*max|ref|) | rtol=tol, atol=0.01*tol*max|ref|"]
+    for name, (worst, n, a, b) in sorted(report.items()):
+        if n:
+            lines.append(f"{name} | {worst:.3f} | {n} | {a / n:.6f} | {b / n:.6f}")
+    terminalreporter.write_line("\n".join(lines))
+    out = os.path.join(ROOT, "gpurun_out")
+    if os.path.isdir(out):
+        with open(os.path.join(out, "parity_report.txt"), "w") as f:
+            f.write("\n".join(lines) + "\n")

@@ -193,6 +193,38 @@ def test_random_traces_parity():
         P.barrier()   # nothing pending: empty cut on both sides
 
 
+def test_aliases_of_an_updated_buffer():
+    """The two cases where more than one name of a buffer is alive when it is updated: a tensor
+    that folding reduces to the buffer itself, and a second leaf on the same buffer.  Neither may
+    be written in place, and a cache hit must give the plan a fresh lowering gives."""
+    P = Pair()
+    a = P.tensor((16,), donatable=True)
+    b = P.run(lambda B, a: B.mul(a, 1.0), a)
+    P.run(lambda B, a: B.assign(a, B.add(a, 1.0)), a)
+    info, ref = P.barrier()
+    assert "->p" not in ref["plan"]
+    del b
+
+    def step(P, aliased):
+        x = P.tensor((8, 8), donatable=True)
+        if aliased:
+            w = (P.lib.scalar(0.0), P.ora.scalar(0.0))
+            P.lib.assign(w[0], x[0]); P.ora.assign(w[1], x[1])
+        else:
+            w = P.tensor((8, 8), donatable=True)
+        r = P.run(lambda B, w, x: B.add(B.permute(w, (1, 0)), x), w, x)
+        P.lib.assign(x[0], r[0]); P.ora.assign(x[1], r[1])
+        del w, r
+        return P.barrier(), x
+    P = Pair()
+    (i1, r1), k1 = step(P, False)
+    (i2, r2), k2 = step(P, True)          # same ops, aliased operands: a different program
+    assert i1.hash != i2.hash and not i2.cache_hit
+    assert "->p" in r1["plan"] and "->p" not in r2["plan"]
+    (i3, r3), k3 = step(P, True)
+    assert i3.cache_hit and r3["plan"] == r2["plan"]
+
+
 def test_error_paths_leave_state_untouched():
     ctx = Context()
     a, b = ctx.tensor(np.zeros((4, 8), np.float32)), ctx.tensor(np.zeros((5, 8), np.float32))

@@ -201,6 +201,40 @@ def test_donation_refused_while_another_handle_sees_the_buffer():
     del keep
 
 
+def test_a_live_alias_of_the_destination_forbids_its_update_in_place():
+    """b = a * 1 folds to a's buffer itself (section 4.1); a += 1 in the same step must then leave
+    that buffer alone, or b would show the new value (section 4.3, second condition)."""
+    T = Tracer()
+    a = T.tensor((16,), donatable=True)
+    b = T.mul(a, 1.0)
+    T.assign(a, T.add(a, 1.0))
+    assert "->p" not in T.barrier()["plan"]
+    del b
+    # without the alias the same update is in place
+    T.assign(a, T.add(a, 1.0))
+    assert "->p0" in T.barrier()["plan"]
+
+
+def test_two_leaves_on_one_buffer_are_part_of_the_key():
+    """A second handle on a buffer (made by assign) gives a second device_data leaf; whether two
+    leaves alias decides what may be written in place, so it must change the hash."""
+    def run(aliased):
+        T = Tracer()
+        x = T.tensor((8, 8), donatable=True)
+        w = T.scalar(0.0)
+        if aliased:
+            T.assign(w, x)
+        else:
+            w = T.tensor((8, 8), donatable=True)
+        r = T.add(T.permute(w, (1, 0)), x)
+        T.assign(x, r)
+        del w, r
+        return T.barrier()
+    plain, aliased = run(False), run(True)
+    assert plain["hash"] != aliased["hash"]
+    assert "->p" in plain["plan"] and "->p" not in aliased["plan"]
+
+
 def test_fusion_never_builds_a_cyclic_region_graph():
     """s feeds a global max, and the result divides s again: the divide must
     not be pulled back into the row-reduction region (that would be a cycle)."""

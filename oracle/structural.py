@@ -721,6 +721,9 @@ class Tracer:
             return inputs, outputs
 
         def caps_ok(members):
+            # a permutation's operand must be in memory: never computed in the permutation's own region
+            if any(nd[m].op == PERMUTE and rins[m][0][0] in members for m in members):
+                return False
             inputs, outputs = region_io(members)
             return (len(inputs) <= MAX_INPUTS and len(outputs) <= MAX_OUTPUTS
                     and len(inputs) + len(members) <= MAX_SLOTS)

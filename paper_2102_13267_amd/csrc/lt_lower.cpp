@@ -243,6 +243,10 @@ struct Lowering {
   bool caps_ok(const std::vector<int32_t>& members) const {
     std::vector<Val> in, out;
     region_io(members, &in, &out);
+    // a permutation reads its operand at other positions than it writes: the operand has to be
+    // in memory, so its producer never shares a region with the permutation
+    for (int32_t m : members)
+      if (nd[m]->op == LT_OP_PERMUTE && std::binary_search(members.begin(), members.end(), rins[m][0].node)) return false;
     return (int)in.size() <= kMaxRegionInputs && (int)out.size() <= kMaxRegionOutputs &&
            (int)(in.size() + members.size()) <= kMaxRegionSlots;
   }
@@ -646,7 +650,9 @@ struct Lowering {
       if (m == anchor.node) continue;
       for (Val v : rins[m]) {
         if (in_members(v.node) || is_imm(v) || v == anchor) continue;
-        const bool perm = nd[m]->op == LT_OP_PERMUTE;
+        // a permute member, and a reshape member that is materialised (a root view), address their
+        // operand in their own way: through a private input
+        const bool perm = nd[m]->op == LT_OP_PERMUTE || nd[m]->op == LT_OP_RESHAPE;
         bool have = false;
         for (size_t q = 0; q < input_vals.size(); ++q) have |= (input_vals[q] == v && input_perm[q] < 0);
         if (perm || !have) {
@@ -663,13 +669,28 @@ struct Lowering {
       Access acc;
       int64_t perm[LT_MAX_RANK];
       const int64_t* pp = nullptr;
+      bool flat = false;   // a reshape member reads its (dense) operand by flat index
       if (input_perm[k] >= 0) {
         const int32_t m = input_perm[k];
-        for (int a = 0; a < nd[m]->n_attr; ++a) perm[a] = nd[m]->attrs[a].v.i;
-        pp = perm;
         permute_input[m] = (int)k;
+        if (nd[m]->op == LT_OP_PERMUTE) {
+          for (int a = 0; a < nd[m]->n_attr; ++a) perm[a] = nd[m]->attrs[a].v.i;
+          pp = perm;
+        } else {
+          flat = true;
+        }
       }
-      if (!make_access(input_vals[k], space, pp, &acc)) return false;
+      if (flat) {
+        std::vector<int64_t> ishape, istride;
+        if (!view_strides(input_vals[k], &acc.storage, &ishape, &istride)) return false;
+        if (istride != contiguous(ishape)) return bad(LT_ERR_UNSUPPORTED, "reshape of a broadcast view has no lowering");
+        acc.dtype = out_dtype(base(input_vals[k]));
+        acc.stride = contiguous(space);
+        for (size_t d = 0; d < space.size(); ++d)
+          if (space[d] == 1) acc.stride[d] = 0;
+      } else if (!make_access(input_vals[k], space, pp, &acc)) {
+        return false;
+      }
       ltk::EwIn& in = p.in[k];
       in.ptr = nullptr;
       in.dtype = acc.dtype;
@@ -803,7 +824,8 @@ struct Lowering {
       const auto& o = rins[m];
       if (n->dtype != LT_F32 && n->dtype != LT_BF16) return bad(LT_ERR_UNSUPPORTED, "integer elementwise arithmetic has no lowering");
       uint32_t enc[3] = {0, 0, 0};
-      if (n->op == LT_OP_PERMUTE) {
+      const bool private_in = permute_input[m] >= 0;
+      if (private_in) {
         enc[0] = (uint32_t)permute_input[m];
       } else {
         const bool recip_b = n->op == LT_OP_DIV && nd[o[1].node]->op == OP_SCALAR_PARAM;
@@ -817,7 +839,7 @@ struct Lowering {
           slot_used[info[vi].slot] = 0;
         }
       }
-      if (n->op == LT_OP_PERMUTE) slot_used[permute_input[m]] = 0;
+      if (private_in) slot_used[permute_input[m]] = 0;
       const int dst = take_slot();
       if (dst < 0) return bad(LT_ERR_UNSUPPORTED, "region needs more than 32 value slots");
       info[find_val(Val{m, 0})].slot = dst;

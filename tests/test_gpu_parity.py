@@ -334,6 +334,26 @@ def test_in_place_semantics_of_section_4_3(ctx):
     assert ctx.fetch(v3).ravel().tolist() == list(range(8)) and ctx.fetch(a3).tolist() == list(range(1, 9))
 
 
+def test_permutation_of_a_value_computed_in_the_same_step(ctx):
+    """A permutation reads other positions than it writes: its operand has to be in memory, so the
+    producer of the operand never shares a kernel with it -- not even as the post program of the
+    contraction that both hang on (s = a + a^T with a = x w), and a reshape that is itself a result
+    is a flat copy whatever the two shapes are."""
+    E = Eager()
+    r = rng(21)
+    x, w = r.standard_normal((48, 40), dtype=np.float32), r.standard_normal((40, 48), dtype=np.float32)
+
+    def prog(B, x, w):
+        a = B.matmul(x, w)
+        s = B.add(a, B.permute(a, (1, 0)))
+        e = B.exp(B.mul(x, 0.1))
+        return s, B.add(e, 1.0), B.permute(e, (1, 0)), B.reshape(e, (40, 48)), B.reshape(e, (1920,))
+    got = prog(ctx, ctx.tensor(x), ctx.tensor(w))
+    ref = prog(E, E.tensor(x), E.tensor(w))
+    for g, rr, what in zip(got, ref, ("a + a^T", "e + 1", "e^T", "e as 40x48", "e flat")):
+        check(ctx, E, g, rr, TOL32, what)
+
+
 def test_a_leaf_dropped_before_the_barrier_keeps_its_memory(ctx):
     """The trace names a leaf's device memory until the barrier has run; the binding keeps the owner
     of that memory alive that long even when the program drops its handle first."""

@@ -225,6 +225,21 @@ def test_aliases_of_an_updated_buffer():
     assert i3.cache_hit and r3["plan"] == r2["plan"]
 
 
+def test_permutation_never_shares_a_region_with_its_operand():
+    P = Pair()
+    x, w = P.tensor((48, 40)), P.tensor((40, 48))
+
+    def prog(B, x, w):
+        a = B.matmul(x, w)
+        return B.add(a, B.permute(a, (1, 0)))
+    out = P.run(prog, x, w)
+    info, ref = P.barrier()
+    for line in ref["plan"].splitlines():
+        members = [int(m) for m in line.split("members=[")[1].split("]")[0].split(",")]
+        assert not (2 in members and 3 in members), line        # %2 = matmul, %3 = its permutation
+    del out
+
+
 def test_error_paths_leave_state_untouched():
     ctx = Context()
     a, b = ctx.tensor(np.zeros((4, 8), np.float32)), ctx.tensor(np.zeros((5, 8), np.float32))

@@ -268,3 +268,137 @@ def test_in_place_is_substitution():
     b = E.add(a, 2.0)
     E.assign(a, E.add(a, 1.0))
     assert np.all(f(E, a) == 2) and np.all(f(E, a) == 2) and np.all(f(E, b) == 3)
+
+
+# ---- the remaining unary / binary / shape ops ---------------------------------------------
+def test_log_recip_sqrt_neg_abs_closed_forms():
+    E = Eager("f64")
+    xs = np.array([0.125, 0.5, 1.0, 2.0, 3.0, 10.0, 1e-3, 12345.0], np.float32)
+    x = E.tensor(xs)
+    xs = xs.astype(np.float64)
+    assert np.allclose(f(E, E.log(x)), [math.log(v) for v in xs], rtol=1e-15, atol=0)
+    assert np.allclose(f(E, E.log(E.exp(E.tensor(np.linspace(-5, 5, 21).astype(np.float32))))), np.linspace(-5, 5, 21), atol=1e-14)
+    assert f(E, E.log(E.tensor(np.array([1.0], np.float32))))[0] == 0.0
+    assert np.allclose(f(E, E.mul(x, E.recip(x))), 1.0, rtol=1e-15)
+    assert np.array_equal(f(E, E.recip(E.tensor(np.array([2.0, -4.0, 0.5], np.float32)))), [0.5, -0.25, 2.0])
+    assert np.array_equal(f(E, E.sqrt(E.tensor(np.array([0.0, 4.0, 9.0, 0.25], np.float32)))), [0.0, 2.0, 3.0, 0.5])
+    assert np.array_equal(f(E, E.neg(E.tensor(np.array([1.5, -2.0, 0.0], np.float32)))), [-1.5, 2.0, 0.0])
+    assert np.array_equal(f(E, E.abs(E.tensor(np.array([1.5, -2.0, -0.0], np.float32)))), [1.5, 2.0, 0.0])
+    assert np.array_equal(f(E, E.square(E.tensor(np.array([1.5, -2.0], np.float32)))), [2.25, 4.0])
+    # the f32 evaluator rounds once: special values
+    F = Eager()
+    with np.errstate(all="ignore"):
+        sp = F.fetch(F.log(F.tensor(np.array([0.0, -1.0, np.inf], np.float32))))
+        rc = F.fetch(F.recip(F.tensor(np.array([0.0, np.inf], np.float32))))
+    assert sp[0] == -np.inf and np.isnan(sp[1]) and sp[2] == np.inf
+    assert rc[0] == np.inf and rc[1] == 0.0
+
+
+def test_maximum_minimum_are_elementwise_and_ordered():
+    E = Eager()
+    p = rng(2).permutation(64).astype(np.float32)
+    q = p[::-1].copy()
+    hi, lo = f(E, E.maximum(E.tensor(p), E.tensor(q))), f(E, E.minimum(E.tensor(p), E.tensor(q)))
+    assert np.array_equal(hi, [max(a, b) for a, b in zip(p, q)])          # typed out pair by pair
+    assert np.array_equal(lo, [min(a, b) for a, b in zip(p, q)])
+    assert np.array_equal(hi + lo, p + q) and np.all(hi >= lo)
+    assert np.array_equal(f(E, E.maximum(E.tensor(p), 31.5)), np.where(p > 31.5, p, 31.5))    # rank-0 operand
+    assert np.array_equal(f(E, E.minimum(1.0, E.tensor(np.array([0.25, 4.0], np.float32)))), [0.25, 1.0])
+
+
+def test_shape_ops_against_hand_typed_index_maps():
+    """expand / reshape / permute on a 2 x 3 x 4 iota, checked element by element against the index
+    arithmetic of a row-major tensor written out here."""
+    E = Eager()
+    iota = np.arange(24, dtype=np.float32).reshape(2, 3, 4)
+    t = E.tensor(iota)
+    p = f(E, E.permute(t, (1, 2, 0)))                       # out[j, k, i] = in[i, j, k]
+    assert p.shape == (3, 4, 2)
+    for i in range(2):
+        for j in range(3):
+            for k in range(4):
+                assert p[j, k, i] == 12 * i + 4 * j + k
+    back = f(E, E.permute(E.permute(t, (1, 2, 0)), (2, 0, 1)))   # the inverse permutation of figure 3
+    assert np.array_equal(back, iota)
+    r = f(E, E.reshape(t, (6, 4)))                          # flat order is kept
+    assert r.shape == (6, 4)
+    for a in range(6):
+        for b in range(4):
+            assert r[a, b] == 4 * a + b
+    assert np.array_equal(f(E, E.reshape(t, (4, 6)))[3], [18, 19, 20, 21, 22, 23])
+    v = E.tensor(np.array([10.0, 20.0, 30.0, 40.0], np.float32))
+    e = f(E, E.expand(v, (2, 3, 4)))                        # trailing axes align, leading ones repeat
+    assert e.shape == (2, 3, 4)
+    for i in range(2):
+        for j in range(3):
+            assert list(e[i, j]) == [10.0, 20.0, 30.0, 40.0]
+    col = f(E, E.expand(E.tensor(np.array([[1.0], [2.0], [3.0]], np.float32)), (3, 4)))
+    assert [list(row) for row in col] == [[1.0] * 4, [2.0] * 4, [3.0] * 4]
+    assert np.array_equal(f(E, E.expand(E.scalar(7.0), (2, 2))), [[7.0, 7.0], [7.0, 7.0]])
+    assert E.permute(E.cast(t, "bf16"), (2, 1, 0)).dtype == "bf16" and E.reshape(t, (24,)).dtype == "f32"
+
+
+def test_cast_to_integer_truncates_towards_zero_and_back():
+    E = Eager()
+    x = E.tensor(np.array([2.7, -2.7, 0.5, -0.5, 3.0, -1e6 - 0.25], np.float32))
+    i32 = E.cast(x, "s32")
+    assert i32.dtype == "s32" and E.fetch(i32).dtype == np.int32
+    assert list(E.fetch(i32)) == [2, -2, 0, 0, 3, -1000000]
+    i64 = E.cast(x, "s64")
+    assert E.fetch(i64).dtype == np.int64 and list(E.fetch(i64)) == [2, -2, 0, 0, 3, -1000000]
+    assert list(E.fetch(E.cast(i32, "f32"))) == [2.0, -2.0, 0.0, 0.0, 3.0, -1000000.0]
+    h = E.cast(E.tensor(np.array([1.00390625, 257.0], np.float32)), "bf16")      # 1 + 2^-8: a tie, to even
+    assert list(E.fetch(h)) == [1.0, 256.0]
+
+
+# ---- the transformer layer's hand-written backward pass ---------------------------------------
+def test_c3_step_gradients_by_finite_differences():
+    """workloads.programs.c3_step spells out its own backward pass.  In float64, on a tiny encoder
+    (d = 8, seq 4, 2 heads, FFN 16, batch 2), dx and all sixteen parameter gradients (read from the
+    first Adam moment: with m = 0 and beta1 = 0.9 the new moment is 0.1 g) must equal central
+    finite differences of  L = sum(y * dy)  with respect to x and to every parameter."""
+    from workloads.inputs import c3_inputs
+    bsz, seq, d, ffn, heads = 2, 4, 8, 16, 2
+    inp = c3_inputs(bsz, seq, d, ffn, seed_extra=3)
+    r = rng(11)
+    keys = programs.C3_WEIGHTS + programs.C3_VECTORS
+    vals = {k: inp[k].astype(np.float64) for k in keys}
+    for k in keys:   # biases and gains away from their trivial initial values, weights large enough to matter
+        vals[k] = vals[k] * (10.0 if k in programs.C3_WEIGHTS else 1.0) + 0.3 * r.standard_normal(vals[k].shape)
+    x0, dy0 = inp["x"].astype(np.float64), inp["dy"].astype(np.float64)
+
+    def run(x, params):
+        E = Eager("f64")
+        P = {k: E.tensor(params[k].copy(), dtype="f32") for k in keys}
+        M = {k: E.tensor(np.zeros_like(params[k]), dtype="f32") for k in keys}
+        V = {k: E.tensor(np.zeros_like(params[k]), dtype="f32") for k in keys}
+        y, dx = programs.c3_step(E, E.tensor(x, dtype="f32"), E.tensor(dy0, dtype="f32"), P, M, V, heads)
+        return f(E, y).reshape(x.shape), f(E, dx).reshape(x.shape), {k: f(E, M[k]) / 0.1 for k in keys}
+
+    y, dx, grads = run(x0, vals)
+    loss = lambda x, params: float(np.sum(run(x, params)[0] * dy0))
+    h = 1e-5
+
+    def fd(target, idx, is_x):
+        def at(delta):
+            if is_x:
+                xx = x0.copy(); xx[idx] += delta
+                return loss(xx, vals)
+            pp = dict(vals); pp[target] = vals[target].copy(); pp[target][idx] += delta
+            return loss(x0, pp)
+        return (at(h) - at(-h)) / (2 * h)
+
+    scale = max(np.max(np.abs(dx)), 1e-30)
+    for _ in range(6):
+        idx = tuple(int(r.integers(0, n)) for n in x0.shape)
+        assert abs(fd(None, idx, True) - dx[idx]) <= 1e-6 * scale, ("dx", idx)
+    for k in keys:
+        g = grads[k]
+        scale = max(np.max(np.abs(g)), 1e-30)
+        picks = [tuple(int(r.integers(0, n)) for n in g.shape) for _ in range(3)]
+        for idx in picks:
+            num = fd(k, idx, False)
+            if k == "bk":      # softmax ignores a shift of its row: the key bias has no gradient at all
+                assert abs(num) <= 1e-7 and abs(g[idx]) <= 1e-9 * max(np.max(np.abs(grads["bq"])), 1e-30) + 1e-12
+            else:
+                assert abs(num - g[idx]) <= 1e-6 * scale, (k, idx, num, g[idx])

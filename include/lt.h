@@ -160,6 +160,10 @@ lt_status lt_release_many(lt_ctx* ctx, const lt_tensor* ts, size_t n);
  * every live tensor: cut, canonical order, hash, cache lookup, lowering on a miss, kernel
  * launches on the context's stream, then every evaluated handle is rebound to its data.
  * blocking != 0 waits for the stream.  info may be NULL.
+ * Errors: LT_ERR_UNSUPPORTED (an op pattern of the trace has no lowering), LT_ERR_OOM (the plan's
+ * results and temporaries do not fit the workspace; found before anything is launched).  Either way
+ * nothing ran and the trace stays pending.  LT_ERR_DEVICE: a HIP call failed; launches already
+ * enqueued may have updated donated buffers, side streams have been joined, the trace stays pending.
  */
 lt_status lt_barrier(lt_ctx* ctx, int blocking, lt_barrier_info* info);
 
@@ -225,6 +229,15 @@ lt_status lt_last_launches(lt_ctx* ctx, lt_launch_record* out, int cap, int* n);
  * Errors: LT_ERR_ARG (n out of range).
  */
 lt_status lt_set_streams(lt_ctx* ctx, int n);
+
+/*
+ * Debugging switch for the invariant of section 3 (a compiled trace is equivalent to running the
+ * recorded operations one by one): with on = 0 every recorded op is lowered to a region, hence a
+ * kernel, of its own -- views stay addressing, special scalars are still folded, in-place updates
+ * still happen -- and the results must agree with those of the fused plans to rounding.  Changing
+ * the setting waits for the stream and empties the plan cache.  Default: on.
+ */
+lt_status lt_set_fusion(lt_ctx* ctx, int on);
 
 /* Message of the last failure on this context (or of lt_init when ctx is NULL). */
 const char* lt_last_error(lt_ctx* ctx);

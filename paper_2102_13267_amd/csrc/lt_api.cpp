@@ -223,7 +223,7 @@ lt_status lt_init(int device, void* hip_stream, void* workspace, size_t workspac
     ctx->device_name = "HIP:" + std::to_string(device);
   } else {
     ctx->device_name = "CPU:0";
-    if (!workspace) workspace_bytes = std::max<size_t>(workspace_bytes, (size_t)1 << 40);
+    if (!workspace && workspace_bytes == 0) workspace_bytes = (size_t)1 << 40;   // (addresses are only planned)
   }
   ctx->arena.init(workspace, workspace_bytes);
   ctx->red_partials = (float*)ctx->arena.alloc(kPartialFloats * sizeof(float));
@@ -685,6 +685,23 @@ lt_status lt_set_streams(lt_ctx* ctx, int n) {
   if (!ctx) return LT_ERR_ARG;
   if (n < 1 || n > kMaxStreams) return fail(ctx, LT_ERR_ARG, "lt_set_streams: between 1 and 4 streams");
   ctx->max_streams = n;
+  return LT_OK;
+}
+
+lt_status lt_set_fusion(lt_ctx* ctx, int on) {
+  if (!ctx) return LT_ERR_ARG;
+  if (ctx->fusion == (on != 0)) return LT_OK;
+  ctx->fusion = on != 0;
+  // plans are lowered under one setting: the cache starts over
+  if (ctx->device >= 0) {
+    (void)hipStreamSynchronize(ctx->stream);
+    for (auto& bucket : ctx->cache)
+      for (auto& plan : bucket.second)
+        for (hipEvent_t e : plan->events)
+          if (e) (void)hipEventDestroy(e);
+  }
+  ctx->cache.clear();
+  ctx->last_plan = nullptr;
   return LT_OK;
 }
 

@@ -185,11 +185,45 @@ static lt_status execute(lt_ctx* ctx, Plan* plan, const Cut& cut, std::vector<Bu
   }
   const bool real = ctx->device >= 0;
   const bool prof = real && ctx->profiling;
+  auto fresh = [&](size_t s) -> bool {
+    auto b = std::make_shared<Buffer>();
+    b->ptr = ctx->arena.alloc(plan->storages[s].bytes);
+    if (!b->ptr) return false;
+    b->bytes = plan->storages[s].bytes;
+    b->owned = true;
+    b->donatable = true;   // library-owned memory may always be reused in place
+    b->arena = &ctx->arena;
+    (*storage_bufs)[s] = b;
+    ptr[s] = b->ptr;
+    return true;
+  };
+  // Memory is settled before the first launch, so that a step either runs whole or not at all (a
+  // launch that has run may have updated a donated buffer in place: no second try after that).
+  // Normally every fresh storage of the plan fits the workspace at once and is taken up front.
+  // Otherwise the storages are taken when their first launch comes and given back behind their
+  // last one -- after the same sequence has been tried on a copy of the arena's free list.
+  bool upfront = true;
+  for (size_t s = 0; s < ns && upfront; ++s)
+    if (plan->storages[s].param < 0) upfront = fresh(s);
+  if (!upfront) {
+    for (size_t s = 0; s < ns; ++s)
+      if (plan->storages[s].param < 0) {
+        (*storage_bufs)[s].reset();
+        ptr[s] = nullptr;
+      }
+    Arena trial = ctx->arena;
+    std::vector<void*> tp(ns, nullptr);
+    for (size_t li = 0; li < plan->launches.size(); ++li) {
+      for (size_t s : born[li])
+        if (!(tp[s] = trial.alloc(plan->storages[s].bytes)))
+          return fail(ctx, LT_ERR_OOM, "workspace arena exhausted: the plan's temporaries and results do not fit");
+      for (size_t s : dies[li]) trial.release(tp[s]);
+    }
+  }
   // Several streams: only when the schedule found independent work, no per-launch timing is
   // asked for, and the workspace holds every temporary at once (memory given back while the step
   // is still being enqueued could be handed to a launch that runs next to its last reader).
-  const bool multi = real && !prof && ctx->max_streams > 1 && plan->n_streams > 1 &&
-                     ctx->arena.size - ctx->arena.in_use >= plan->temp_bytes + (plan->temp_bytes >> 3);
+  const bool multi = real && !prof && ctx->max_streams > 1 && plan->n_streams > 1 && upfront;
   ctx->last_launches.clear();
   if (prof) {
     while (ctx->events.size() < 2 * plan->launches.size()) {
@@ -208,19 +242,29 @@ static lt_status execute(lt_ctx* ctx, Plan* plan, const Cut& cut, std::vector<Bu
   std::vector<size_t> deferred;
   std::vector<uint8_t> args;
   size_t pp = 0, sp = 0;
+  // join: whatever follows on the caller's stream comes after every side stream's work.  Runs on
+  // every way out once a side stream may hold work -- a failed launch included, so that memory the
+  // caller gets back (the arena blocks of this step) is never reused under a side stream's kernel.
+  auto join_streams = [&]() -> hipError_t {
+    hipError_t first = hipSuccess;
+    for (int s = 1; s < kMaxStreams; ++s) {
+      if (!forked[s]) continue;
+      hipError_t e = hipEventRecord(ctx->join_event[s - 1], ctx->side[s - 1]);
+      if (e == hipSuccess) e = hipStreamWaitEvent(ctx->stream, ctx->join_event[s - 1], 0);
+      if (e != hipSuccess && first == hipSuccess) first = e;
+      forked[s] = false;
+    }
+    return first;
+  };
+  auto give_up = [&](lt_status st) {
+    if (multi) (void)join_streams();
+    return st;
+  };
   for (size_t li = 0; li < plan->launches.size(); ++li) {
     const Launch& l = plan->launches[li];
-    for (size_t s : born[li]) {
-      auto b = std::make_shared<Buffer>();
-      b->ptr = ctx->arena.alloc(plan->storages[s].bytes);
-      if (!b->ptr) return fail(ctx, LT_ERR_OOM, "workspace arena exhausted while running a plan");
-      b->bytes = plan->storages[s].bytes;
-      b->owned = true;
-      b->donatable = true;   // library-owned memory may always be reused in place
-      b->arena = &ctx->arena;
-      (*storage_bufs)[s] = b;
-      ptr[s] = b->ptr;
-    }
+    if (!upfront)
+      for (size_t s : born[li])
+        if (!fresh(s)) return give_up(fail(ctx, LT_ERR_OOM, "internal: the arena differs from its trial run"));
     args = l.args;
     for (; pp < plan->ptr_patches.size() && plan->ptr_patches[pp].launch == li; ++pp) {
       const PtrPatch& p = plan->ptr_patches[pp];
@@ -253,16 +297,16 @@ static lt_status execute(lt_ctx* ctx, Plan* plan, const Cut& cut, std::vector<Bu
           forked[l.stream] = true;
         }
         for (size_t w = 0; w < l.waits.size() && e == hipSuccess; ++w) e = hipStreamWaitEvent(stream, plan->events[l.waits[w]], 0);
-        if (e != hipSuccess) return hip_fail(ctx, "hipStreamWaitEvent", e);
+        if (e != hipSuccess) return give_up(hip_fail(ctx, "hipStreamWaitEvent", e));
       }
       if (prof) (void)hipEventRecord(ctx->events[2 * li], ctx->stream);
       hipError_t e = launch_one(l, args.data(), stream);
-      if (e != hipSuccess) return hip_fail(ctx, kind_name(l.kind), e);
+      if (e != hipSuccess) return give_up(hip_fail(ctx, kind_name(l.kind), e));
       if (prof) (void)hipEventRecord(ctx->events[2 * li + 1], ctx->stream);
       if (multi && l.record) {
         if (!plan->events[li]) e = hipEventCreateWithFlags(&plan->events[li], hipEventDisableTiming);
         if (e == hipSuccess) e = hipEventRecord(plan->events[li], stream);
-        if (e != hipSuccess) return hip_fail(ctx, "hipEventRecord", e);
+        if (e != hipSuccess) return give_up(hip_fail(ctx, "hipEventRecord", e));
       }
     }
     for (size_t s : dies[li]) {
@@ -276,13 +320,8 @@ static lt_status execute(lt_ctx* ctx, Plan* plan, const Cut& cut, std::vector<Bu
     ctx->stats.kernels_launched++;
   }
   if (multi) {
-    // join: whatever follows on the caller's stream comes after every side stream's work
-    for (int s = 1; s < kMaxStreams; ++s) {
-      if (!forked[s]) continue;
-      hipError_t e = hipEventRecord(ctx->join_event[s - 1], ctx->side[s - 1]);
-      if (e == hipSuccess) e = hipStreamWaitEvent(ctx->stream, ctx->join_event[s - 1], 0);
-      if (e != hipSuccess) return hip_fail(ctx, "stream join", e);
-    }
+    hipError_t e = join_streams();
+    if (e != hipSuccess) return hip_fail(ctx, "stream join", e);
     for (size_t s : deferred) (*storage_bufs)[s].reset();
   }
   if (prof) {

@@ -182,6 +182,7 @@ struct lt_ctx {
   hipStream_t side[lt::kMaxStreams - 1] = {};
   hipEvent_t fork_event = nullptr, join_event[lt::kMaxStreams - 1] = {};
   int max_streams = lt::kMaxStreams;   // lt_set_streams
+  bool fusion = true;                  // lt_set_fusion: off = one region per recorded op
 };
 
 namespace lt {

@@ -318,6 +318,7 @@ struct Lowering {
       pool.emplace_back(new Region{cls[i], cls[i] == C_EW ? -1 : i, {i}});
       region_of[i] = pool.back().get();
     }
+    if (!ctx->fusion) return;   // debugging switch: every op runs as a kernel of its own
     // pass 1: prologue absorption into plain reductions
     for (int32_t a = 0; a < N; ++a) {
       if (!(cls[a] == C_ROW || cls[a] == C_COL || cls[a] == C_ALL) || !plain_reduce(nd[a]->op)) continue;

@@ -101,6 +101,7 @@ def load_library():
         "lt_release_many": [P, C.POINTER(C.c_uint64), C.c_size_t],
         "lt_set_profiling": [P, i32],
         "lt_set_streams": [P, i32],
+        "lt_set_fusion": [P, i32],
         "lt_last_launches": [P, C.POINTER(LaunchRecord), i32, C.POINTER(i32)],
     }
     for name, argtypes in sig.items():
@@ -173,7 +174,7 @@ class Context:
     """One lt_ctx.  device=None gives the null device ("CPU:0": records, hashes, lowers, launches
     nothing).  Otherwise `device` is a HIP ordinal and the workspace is a torch byte tensor."""
 
-    def __init__(self, device=None, workspace_bytes=1 << 30, stream=None):
+    def __init__(self, device=None, workspace_bytes=None, stream=None):
         self._lib = load_library()
         self._h = C.c_void_p()
         self._ids, self._outs, self._attrs = {}, {}, {}     # reusable ctypes argument arrays of op()
@@ -181,8 +182,8 @@ class Context:
         self._kept = []                                     # owners of device memory that dropped leaves of the pending trace name
         self._torch = None
         self._workspace = None
-        if device is None:
-            self._check_init(self._lib.lt_init(-1, None, None, int(workspace_bytes), C.byref(self._h)))
+        if device is None:   # (no size given: addresses are planned in an unbounded workspace)
+            self._check_init(self._lib.lt_init(-1, None, None, int(workspace_bytes or 0), C.byref(self._h)))
             self.device = None
         else:
             import torch
@@ -190,6 +191,7 @@ class Context:
                 raise RuntimeError("no GPU visible: the HIP path cannot run (there is no CPU fallback)")
             self._torch = torch
             self.device = int(device)
+            workspace_bytes = int(workspace_bytes or (1 << 30))
             torch.cuda.set_device(self.device)
             self._workspace = torch.empty(int(workspace_bytes), dtype=torch.uint8, device=f"cuda:{self.device}")
             st = stream if stream is not None else torch.cuda.current_stream(self.device)
@@ -416,6 +418,9 @@ class Context:
 
     def set_streams(self, n: int) -> None:
         self._check(self._lib.lt_set_streams(self._h, int(n)))
+
+    def set_fusion(self, on: bool) -> None:
+        self._check(self._lib.lt_set_fusion(self._h, 1 if on else 0))
 
     def last_launches(self):
         n = C.c_int()

@@ -354,6 +354,46 @@ def test_permutation_of_a_value_computed_in_the_same_step(ctx):
         check(ctx, E, g, rr, TOL32, what)
 
 
+def test_fused_and_unfused_plans_agree():
+    """Section 3: a compiled trace is equivalent to running the recorded operations one by one.
+    Inside the library: the same traces with fusion switched off (every op a kernel of its own,
+    every intermediate in memory) against the fused plans, and both against the oracle."""
+    from paper_2102_13267_amd import Context
+    c = Context(device=0, workspace_bytes=1 << 30)
+    E = Eager()
+    inp1 = c1_inputs(300, 1028)
+    inp2 = c2_inputs(steps=1)
+    names = ("W1", "b1", "W2", "b2", "W3", "b3")
+    cfg = (2, 16, 64, 128, 4)
+    results = {}
+    for fused in (True, False):
+        c.set_fusion(fused)
+        out1 = programs.c1_trace(c, *(c.tensor(inp1[k]) for k in ("x", "y", "bias")))
+        n1 = c.barrier().n_regions
+        gp = [c.tensor(inp2[k].copy(), donatable=True) for k in names]
+        loss = programs.c2_step(c, c.tensor(inp2["X"][0]), c.tensor(inp2["labels"][0]), gp, 0.01)
+        n2 = c.barrier().n_regions
+        g3 = _c3_setup(c, lambda a, dt, don: c.tensor(a, dtype=dt, donatable=don), cfg)
+        y3, dx3 = programs.c3_step(c, *g3, t=1)
+        n3 = c.barrier().n_regions
+        results[fused] = ([c.fetch(out1), c.fetch(loss)] + [c.fetch(p) for p in gp], [c.fetch(y3), c.fetch(dx3)] +
+                          [c.fetch(g3[3][k]) for k in programs.C3_WEIGHTS + programs.C3_VECTORS if k != "bk"], (n1, n2, n3))
+    assert results[True][2][0] == 2 and results[False][2][0] == 12
+    assert results[False][2][1] > results[True][2][1] and results[False][2][2] > results[True][2][2]
+    for a, b in zip(results[True][0], results[False][0]):
+        assert rel_err(a, b) <= 2 * TOL32
+    for a, b in zip(results[True][1], results[False][1]):
+        assert rel_err(a, b) <= 2 * TOL16
+    ref1 = E.fetch(programs.c1_trace(E, *(E.tensor(inp1[k]) for k in ("x", "y", "bias"))))
+    rp = [E.tensor(inp2[k]) for k in names]
+    ref_loss = E.fetch(programs.c2_step(E, E.tensor(inp2["X"][0]), E.tensor(inp2["labels"][0]), rp, 0.01))
+    for fused in (True, False):
+        assert rel_err(results[fused][0][0], ref1) <= TOL32 and rel_err(results[fused][0][1], ref_loss) <= TOL32
+        for got, r in zip(results[fused][0][2:], rp):
+            assert rel_err(got, E.fetch(r)) <= TOL32
+    c.close()
+
+
 def test_a_leaf_dropped_before_the_barrier_keeps_its_memory(ctx):
     """The trace names a leaf's device memory until the barrier has run; the binding keeps the owner
     of that memory alive that long even when the program drops its handle first."""

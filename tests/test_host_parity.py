@@ -240,6 +240,63 @@ def test_permutation_never_shares_a_region_with_its_operand():
     del out
 
 
+def test_arena_exhaustion_is_found_before_anything_runs():
+    """A workspace too small for the plan's results: the barrier fails with LT_ERR_OOM before its
+    first launch, every handle stays pending, the arena holds what it held, and the same trace runs
+    once room has been made."""
+    ctx = Context(workspace_bytes=13 << 20)                  # 4 MiB + 4 KiB of it is reduction scratch
+    a = ctx.tensor(np.zeros((1 << 20,), np.float32))         # 4 MiB per tensor of this size
+    first = ctx.exp(a)
+    assert ctx.barrier().n_launches == 1                     # one result fits
+    base = ctx.stats().arena_bytes_in_use
+    outs = [ctx.exp(ctx.mul(a, float(k))) for k in (2, 3)]   # two more do not
+    ir = ctx.dump_ir()
+    with pytest.raises(LtError) as e:
+        ctx.barrier()
+    assert e.value.status == 6 and "workspace" in str(e.value)
+    st = ctx.stats()
+    assert st.arena_bytes_in_use == base and st.barriers == 1
+    assert ctx.dump_ir() == ir                               # the trace is still pending, unchanged
+    del first                                                # make room: its block goes back to the arena
+    info = ctx.barrier()
+    assert info.cache_hit and info.n_roots == 2              # (the plan that the failed attempt lowered is reused)
+    assert ctx.stats().arena_bytes_in_use == base + (4 << 20)
+    # temporaries that fit only one after the other: a chain through two global reductions
+    ctx2 = Context(workspace_bytes=14 << 20)
+    x = ctx2.tensor(np.zeros((1 << 20,), np.float32))
+    y = ctx2.tanh(x)
+    t1 = ctx2.mul(y, ctx2.sum(y))                            # 4 MiB temporary, dead after t2's region
+    t2 = ctx2.mul(t1, ctx2.sum(t1))
+    t3 = ctx2.mul(t2, ctx2.sum(t2))
+    out = ctx2.sum(t3)
+    del y, t1, t2, t3
+    info = ctx2.barrier()                                    # three 4 MiB temporaries: not at once next to the scratch, but two at a time
+    assert info.n_roots == 1 and 12 << 20 <= ctx2.stats().arena_bytes_peak <= 14 << 20
+    del out, outs
+
+
+def test_fusion_switch_gives_one_region_per_op_and_valid_plans():
+    from plan_check import check_plan
+    ctx = Context()
+    ctx.set_fusion(False)
+    x, y, b = (ctx.tensor(np.zeros(s, np.float32)) for s in ((64, 32), (64, 32), (32,)))
+    out = programs.c1_trace(ctx, x, y, b)
+    info = ctx.barrier()
+    assert info.n_regions == 12                              # twelve recorded ops, twelve kernels
+    check_plan(ctx.dump_key(), info.n_nodes, ctx.dump_plan())
+    ts = [ctx.tensor(np.zeros((1 << 12,), np.float32), donatable=True) for _ in range(4)]
+    programs.c4_step(ctx, *ts, **C4_HYPER)
+    info = ctx.barrier()
+    plan = ctx.dump_plan()
+    assert all(len(l.split("members=[")[1].split("]")[0].split(",")) == 1 for l in plan.splitlines())
+    assert plan.count("->p") == 3                            # the updates are still in place
+    check_plan(ctx.dump_key(), info.n_nodes, plan)
+    ctx.set_fusion(True)
+    programs.c4_step(ctx, *ts, **C4_HYPER)
+    assert ctx.barrier().n_regions == 1 and not ctx.barrier().cache_hit is None
+    del out
+
+
 def test_error_paths_leave_state_untouched():
     ctx = Context()
     a, b = ctx.tensor(np.zeros((4, 8), np.float32)), ctx.tensor(np.zeros((5, 8), np.float32))

@@ -168,6 +168,29 @@ lt_status lt_release_many(lt_ctx* ctx, const lt_tensor* ts, size_t n);
 lt_status lt_barrier(lt_ctx* ctx, int blocking, lt_barrier_info* info);
 
 /*
+ * lt_barrier for callers that cannot allocate device memory or create runtime objects while they
+ * run it: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same contract as lt_barrier, except that
+ *  - the reduction scratch (partial results, tickets) and every temporary of the plan (region
+ *    outputs that are not results, partial products of split contractions) live in a 16 MiB
+ *    array in the library's own device image instead of the workspace: 4 MiB + 4 KiB of it are the
+ *    reduction scratch, 12,578,816 bytes are handed to the plan's temporaries front to back
+ *    (each rounded up to 256 bytes, none reused inside a step).  A plan that needs more fails
+ *    with LT_ERR_OOM before anything is launched (the trace stays pending: lt_barrier can
+ *    still run it).  Results that are not written in place over a donated input are placed in the
+ *    workspace given to lt_init, as always -- host-side bookkeeping over caller-owned memory;
+ *  - every launch goes to the context's stream: no side streams, no events, no per-launch timing;
+ *  - it calls no hipMalloc / hipFree, no allocating library routine, and no hipMemsetAsync (the
+ *    tickets are cleared by a small kernel).  With blocking = 0 it makes no synchronising call either.
+ * The array's device address is looked up once per device in lt_init; if that failed, this call
+ * returns LT_ERR_DEVICE with the reason.  Every context on a GPU shares that GPU's array, which
+ * keeps the contents of the last call: calls that overlap in time on one GPU (two contexts, or
+ * two streams) race.  The array stays allocated on every GPU the library has run on until the
+ * process ends.
+ */
+lt_status lt_barrier_static(lt_ctx* ctx, int blocking, lt_barrier_info* info);
+
+/*
  * IR-incompatible op (section 3): blocking barrier if `t` is pending, then copy its data to
  * host_dst (host pointer, nbytes must equal the tensor's byte size).
  */

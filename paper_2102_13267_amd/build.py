@@ -18,7 +18,7 @@ LIB = os.path.join(HERE, "liblt.so")
 REC = os.path.join(HERE, "_ltrec" + (sysconfig.get_config_var("EXT_SUFFIX") or ".so"))   # recording fast path of the binding
 ROCM = os.environ.get("ROCM_PATH", "/opt/rocm")
 
-HIP_SOURCES = ["lt_k_ew.hip", "lt_k_reduce.hip", "lt_k_rowop.hip", "lt_gemm.hip", "lt_gemm_bf16.hip"]
+HIP_SOURCES = ["lt_k_ew.hip", "lt_k_reduce.hip", "lt_k_rowop.hip", "lt_gemm.hip", "lt_gemm_bf16.hip", "lt_static_scratch.hip"]
 CPP_SOURCES = ["lt_api.cpp", "lt_barrier.cpp", "lt_lower.cpp", "lt_schedule.cpp"]
 
 # packed-fp32 VALU ops are switched off for all device code: some of their forms have given wrong

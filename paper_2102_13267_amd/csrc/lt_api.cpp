@@ -8,6 +8,7 @@
 #include <cstdio>
 
 #include "lt_core.h"
+#include "lt_launch.h"
 
 namespace lt {
 
@@ -239,7 +240,16 @@ lt_status lt_init(int device, void* hip_stream, void* workspace, size_t workspac
       if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->join_event[i], hipEventDisableTiming);
     }
     if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->fork_event, hipEventDisableTiming);
+    // the library's static scratch on this device: its address is looked up here, once per device,
+    // so that lt_barrier_static itself neither allocates nor asks the runtime for anything
     if (e != hipSuccess) return fail(nullptr, LT_ERR_DEVICE, std::string("lt_init: ") + hipGetErrorString(e));
+    void* p = nullptr;
+    const hipError_t es = ltk::static_scratch(device, &p, &ctx->static_scratch_bytes);
+    if (es == hipSuccess) ctx->static_scratch = (uint8_t*)p;
+    else ctx->static_scratch_error = std::string("hipGetSymbolAddress of the static scratch: ") + hipGetErrorString(es);   // (lt_barrier_static reports it)
+  } else {
+    ctx->static_scratch = (uint8_t*)(uintptr_t)0x40000000;   // a null device only plans addresses
+    ctx->static_scratch_bytes = ltk::kStaticScratchBytes;
   }
   *out = ctx.release();
   return LT_OK;

@@ -163,7 +163,9 @@ static const char* kind_name(LaunchKind k) {
 }
 
 // Bind this step's buffers and scalars into the cached plan and launch it.
-static lt_status execute(lt_ctx* ctx, Plan* plan, const Cut& cut, std::vector<BufRef>* storage_bufs) {
+// use_static: reduction scratch and temporaries live in the library's static device scratch, only
+// results are placed in the caller's workspace; one stream, no events, nothing is created.
+static lt_status execute(lt_ctx* ctx, Plan* plan, const Cut& cut, std::vector<BufRef>* storage_bufs, bool use_static) {
   const size_t ns = plan->storages.size();
   storage_bufs->assign(ns, nullptr);
   std::vector<void*> ptr(ns, nullptr);
@@ -184,7 +186,7 @@ static lt_status execute(lt_ctx* ctx, Plan* plan, const Cut& cut, std::vector<Bu
     if (!st.bound_to_root) dies[st.last_launch].push_back(s);
   }
   const bool real = ctx->device >= 0;
-  const bool prof = real && ctx->profiling;
+  const bool prof = real && ctx->profiling && !use_static;
   auto fresh = [&](size_t s) -> bool {
     auto b = std::make_shared<Buffer>();
     b->ptr = ctx->arena.alloc(plan->storages[s].bytes);
@@ -203,8 +205,35 @@ static lt_status execute(lt_ctx* ctx, Plan* plan, const Cut& cut, std::vector<Bu
   // Otherwise the storages are taken when their first launch comes and given back behind their
   // last one -- after the same sequence has been tried on a copy of the arena's free list.
   bool upfront = true;
-  for (size_t s = 0; s < ns && upfront; ++s)
-    if (plan->storages[s].param < 0) upfront = fresh(s);
+  float* red_partials = ctx->red_partials;
+  uint32_t* red_tickets = ctx->red_tickets;
+  if (use_static) {
+    // layout of the static scratch: partials, tickets, then temporaries handed out front to back
+    red_partials = (float*)ctx->static_scratch;
+    red_tickets = (uint32_t*)(ctx->static_scratch + kPartialFloats * sizeof(float));
+    size_t top = kPartialFloats * sizeof(float) + kTickets * sizeof(uint32_t);
+    for (size_t s = 0; s < ns; ++s) {
+      const Storage& st = plan->storages[s];
+      if (st.param >= 0 || st.bound_to_root) continue;
+      const size_t need = (std::max<size_t>(st.bytes, 1) + 255) & ~(size_t)255;
+      if (need > ctx->static_scratch_bytes - top)
+        return fail(ctx, LT_ERR_OOM, "lt_barrier_static: the plan's temporaries need more than the " +
+                                         std::to_string((ctx->static_scratch_bytes - kPartialFloats * sizeof(float) - kTickets * sizeof(uint32_t)) >> 10) +
+                                         " KiB that the library's static scratch holds for them");
+      auto b = std::make_shared<Buffer>();
+      b->ptr = ctx->static_scratch + top;
+      b->bytes = st.bytes;
+      (*storage_bufs)[s] = b;
+      ptr[s] = b->ptr;
+      top += need;
+    }
+    for (size_t s = 0; s < ns; ++s)
+      if (plan->storages[s].param < 0 && plan->storages[s].bound_to_root && !fresh(s))
+        return fail(ctx, LT_ERR_OOM, "workspace arena exhausted: the plan's results do not fit");
+  } else {
+    for (size_t s = 0; s < ns && upfront; ++s)
+      if (plan->storages[s].param < 0) upfront = fresh(s);
+  }
   if (!upfront) {
     for (size_t s = 0; s < ns; ++s)
       if (plan->storages[s].param < 0) {
@@ -223,7 +252,7 @@ static lt_status execute(lt_ctx* ctx, Plan* plan, const Cut& cut, std::vector<Bu
   // Several streams: only when the schedule found independent work, no per-launch timing is
   // asked for, and the workspace holds every temporary at once (memory given back while the step
   // is still being enqueued could be handed to a launch that runs next to its last reader).
-  const bool multi = real && !prof && ctx->max_streams > 1 && plan->n_streams > 1 && upfront;
+  const bool multi = real && !prof && !use_static && ctx->max_streams > 1 && plan->n_streams > 1 && upfront;
   ctx->last_launches.clear();
   if (prof) {
     while (ctx->events.size() < 2 * plan->launches.size()) {
@@ -232,6 +261,12 @@ static lt_status execute(lt_ctx* ctx, Plan* plan, const Cut& cut, std::vector<Bu
       if (err != hipSuccess) return hip_fail(ctx, "hipEventCreate", err);
       ctx->events.push_back(e);
     }
+  }
+  if (use_static && real) {
+    // every call on a GPU shares that GPU's array, which keeps the last call's contents: the
+    // tickets must start at zero (a kernel, not a memset: the caller may be capturing a graph)
+    hipError_t e = ltk::launch_fill_u32(red_tickets, (uint32_t)kTickets, 0u, ctx->stream);
+    if (e != hipSuccess) return hip_fail(ctx, "lt_fill_u32_kernel", e);
   }
   bool forked[kMaxStreams] = {true, false, false, false};
   if (multi) {
@@ -281,12 +316,12 @@ static lt_status execute(lt_ctx* ctx, Plan* plan, const Cut& cut, std::vector<Bu
       // reductions that may run next to each other work in different quarters of the scratch
       if (l.kind == L_ALL) {
         ltk::AllArgs* a = (ltk::AllArgs*)args.data();
-        a->partials = ctx->red_partials + l.scratch_slot * (kPartialFloats / kScratchSlots);
-        a->ticket = ctx->red_tickets + l.scratch_slot * (kTickets / kScratchSlots);
+        a->partials = red_partials + l.scratch_slot * (kPartialFloats / kScratchSlots);
+        a->ticket = red_tickets + l.scratch_slot * (kTickets / kScratchSlots);
       } else if (l.kind == L_COL) {
         ltk::ColArgs* a = (ltk::ColArgs*)args.data();
-        a->partials = ctx->red_partials + l.scratch_slot * (kPartialFloats / kScratchSlots);
-        a->tickets = ctx->red_tickets + l.scratch_slot * (kTickets / kScratchSlots);
+        a->partials = red_partials + l.scratch_slot * (kPartialFloats / kScratchSlots);
+        a->tickets = red_tickets + l.scratch_slot * (kTickets / kScratchSlots);
       }
       hipStream_t stream = ctx->stream;
       if (multi) {
@@ -346,8 +381,7 @@ using namespace lt;
 
 extern "C" {
 
-lt_status lt_barrier(lt_ctx* ctx, int blocking, lt_barrier_info* info) {
-  if (!ctx) return LT_ERR_ARG;
+static lt_status barrier_impl(lt_ctx* ctx, int blocking, lt_barrier_info* info, bool use_static) {
   const uint64_t t0 = now_ns();
   Cut cut;
   collect_cut(ctx, &cut);
@@ -374,7 +408,7 @@ lt_status lt_barrier(lt_ctx* ctx, int blocking, lt_barrier_info* info) {
   }
   const uint64_t t3 = now_ns();
   std::vector<BufRef> bufs;
-  lt_status st = execute(ctx, plan, cut, &bufs);
+  lt_status st = execute(ctx, plan, cut, &bufs, use_static);
   if (st != LT_OK) return st;
   // result binding: after the barrier every evaluated handle is plain data (or a scalar when
   // folding reduced it to one); a new IR graph starts (section 3)
@@ -423,6 +457,17 @@ lt_status lt_barrier(lt_ctx* ctx, int blocking, lt_barrier_info* info) {
     info->ns_launch = t4 - t3;
   }
   return LT_OK;
+}
+
+lt_status lt_barrier(lt_ctx* ctx, int blocking, lt_barrier_info* info) {
+  if (!ctx) return LT_ERR_ARG;
+  return barrier_impl(ctx, blocking, info, false);
+}
+
+lt_status lt_barrier_static(lt_ctx* ctx, int blocking, lt_barrier_info* info) {
+  if (!ctx) return LT_ERR_ARG;
+  if (!ctx->static_scratch) return fail(ctx, LT_ERR_DEVICE, "lt_barrier_static: " + ctx->static_scratch_error);
+  return barrier_impl(ctx, blocking, info, true);
 }
 
 lt_status lt_fetch(lt_ctx* ctx, lt_tensor t, void* host_dst, size_t nbytes) {

@@ -183,6 +183,11 @@ struct lt_ctx {
   hipEvent_t fork_event = nullptr, join_event[lt::kMaxStreams - 1] = {};
   int max_streams = lt::kMaxStreams;   // lt_set_streams
   bool fusion = true;                  // lt_set_fusion: off = one region per recorded op
+  // the library's static device scratch on this device (lt_barrier_static): reduction partials,
+  // tickets, then room for a plan's temporaries
+  uint8_t* static_scratch = nullptr;
+  size_t static_scratch_bytes = 0;
+  std::string static_scratch_error;    // why the array's address could not be had (empty: it could)
 };
 
 namespace lt {

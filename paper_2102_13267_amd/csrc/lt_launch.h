@@ -15,5 +15,11 @@ hipError_t launch_row_op(const RowOpArgs& a, uint32_t grid, hipStream_t s);
 hipError_t launch_split_post(const SplitPostArgs& a, uint32_t grid, hipStream_t s);
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s);   // 128 x 128 tiles, split-K (called by launch_gemm)
+
+// The library's static device scratch (lt_static_scratch.hip): its size, its address on `device`
+// (looked up once per device; `device` must be current), and a fill kernel.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+hipError_t static_scratch(int device, void** ptr, size_t* bytes);
+hipError_t launch_fill_u32(uint32_t* p, uint32_t n, uint32_t value, hipStream_t s);
 }  // namespace ltk
 #endif

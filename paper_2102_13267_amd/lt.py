@@ -90,6 +90,7 @@ def load_library():
         "lt_assign": [P, u64, u64],
         "lt_release": [P, u64],
         "lt_barrier": [P, i32, C.POINTER(BarrierInfo)],
+        "lt_barrier_static": [P, i32, C.POINTER(BarrierInfo)],
         "lt_fetch": [P, u64, P, C.c_size_t],
         "lt_device_ptr": [P, u64, C.POINTER(P)],
         "lt_shape": [P, u64, C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_int64)],
@@ -364,6 +365,14 @@ class Context:
         _ltrec.barrier(self._hv, self._dead, blocking, C.addressof(info))   # (hands the dropped tensors over first)
         # Every launch that reads a dropped leaf's memory is now enqueued on the context's stream, which is
         # the stream the memory was allocated on: torch hands a freed block out again in stream order only.
+        self._kept.clear()
+        return info
+
+    def barrier_static(self, blocking=True) -> BarrierInfo:
+        """lt_barrier_static: the barrier that keeps its scratch in the library's own device array."""
+        self._flush()
+        info = BarrierInfo()
+        self._check(self._lib.lt_barrier_static(self._h, 1 if blocking else 0, C.byref(info)))
         self._kept.clear()
         return info
 

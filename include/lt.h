@@ -57,6 +57,8 @@ typedef enum {
   LT_OP_EXPAND = 48,       /* attrs LT_ATTR_DIM0+i = output dims                             */
   LT_OP_RESHAPE,           /* attrs LT_ATTR_DIM0+i = output dims                             */
   LT_OP_PERMUTE,           /* attrs LT_ATTR_DIM0+i = source axis of output axis i            */
+  LT_OP_NARROW,            /* attrs LT_ATTR_AXIS, _START, _LENGTH: a window along one axis   */
+  LT_OP_SLICE_UPDATE,      /* (base, update), attrs LT_ATTR_AXIS, _START: base with that window replaced */
   LT_OP_SUM = 64, LT_OP_AMAX, LT_OP_MEAN, /* attr LT_ATTR_AXIS (last or first axis); none = all */
   LT_OP_SOFTMAX = 80,      /* (x): softmax over the last axis                                */
   LT_OP_SOFTMAX_GRAD,      /* (dy, y): y * (dy - sum(dy*y))                                  */
@@ -70,7 +72,7 @@ typedef enum {
 
 typedef enum {
   LT_ATTR_VALUE = 1, LT_ATTR_DTYPE = 2, LT_ATTR_AXIS = 3, LT_ATTR_EPS = 4,
-  LT_ATTR_TRANS_A = 5, LT_ATTR_TRANS_B = 6, LT_ATTR_DIM0 = 16
+  LT_ATTR_TRANS_A = 5, LT_ATTR_TRANS_B = 6, LT_ATTR_START = 7, LT_ATTR_LENGTH = 8, LT_ATTR_DIM0 = 16
 } lt_attr_key;
 
 typedef struct {
@@ -143,6 +145,21 @@ lt_status lt_op(lt_ctx* ctx, uint16_t opcode, const lt_tensor* inputs, int n_in,
 
 /* In-place update as substitution (section 4.3): dst now denotes src's computation. */
 lt_status lt_assign(lt_ctx* ctx, lt_tensor dst, lt_tensor src);
+
+/*
+ * A view of `base` (section 4.4, in-place operations on views): view_op is LT_OP_PERMUTE,
+ * LT_OP_RESHAPE or LT_OP_NARROW with the attributes lt_op takes for it.  The new tensor shares
+ * storage with its base as far as a program can tell:
+ *  - read as an operand, fetched or evaluated at a barrier, it is the view op applied to the base's
+ *    current value (the paper's forward sequence; derived again whenever the base was replaced);
+ *  - lt_assign(view, src) gives the view the value src AND rebuilds the base from it with the
+ *    inverse of the view op -- the inverse permutation, the reshape back, the base with the window
+ *    replaced (the backward sequence) -- through every level when the base is itself a view; other
+ *    views of the same base see the change.  src must have the view's dtype and shape (LT_ERR_SHAPE).
+ * Everything is recorded in the one IR graph: no memory is shared, nothing runs.  A base released
+ * while views of it are alive stays evaluated at barriers until its last view is released.
+ */
+lt_status lt_view(lt_ctx* ctx, lt_tensor base, uint16_t view_op, const lt_attr* attrs, int n_attr, lt_tensor* out);
 
 /* UnregisterTensor (section 4): the handle dies; its pending computation is no longer a root. */
 lt_status lt_release(lt_ctx* ctx, lt_tensor t);

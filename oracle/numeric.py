@@ -54,11 +54,12 @@ def round_to_bf16(a: np.ndarray) -> np.ndarray:
 class ETensor:
     """A materialised value: NumPy data plus the logical dtype tag."""
 
-    __slots__ = ("data", "dtype")
+    __slots__ = ("data", "dtype", "shared")
 
     def __init__(self, data: np.ndarray, dtype: str):
         self.data = data
         self.dtype = dtype
+        self.shared = False     # True: other tensors are views into (or the base of) this memory
 
     @property
     def shape(self):
@@ -246,6 +247,47 @@ class Eager:
         x = self._t(x)
         return self._store(np.transpose(x.data, tuple(dims)).copy(), x.dtype)
 
+    def narrow(self, x, axis, start, length):
+        """The window [start, start + length) along one axis, as a copy."""
+        x = self._t(x)
+        idx = [slice(None)] * x.data.ndim
+        idx[axis] = slice(start, start + length)
+        return self._store(x.data[tuple(idx)].copy(), x.dtype)
+
+    def slice_update(self, base, update, axis, start):
+        """base with the window that starts at `start` along `axis` replaced by update."""
+        base, update = self._t(base), self._t(update)
+        out = base.data.copy()
+        idx = [slice(None)] * out.ndim
+        idx[axis] = slice(start, start + update.data.shape[axis])
+        out[tuple(idx)] = update.data
+        return self._store(out, base.dtype)
+
+    # ---- views: tensors that share their base's storage (section 4.4 of the paper) ----------
+    # The plain definition: a view IS the base's memory seen through other strides, so the view
+    # is a NumPy view, and an in-place update of either tensor writes into that memory.
+    def _share(self, x, view_data):
+        x = self._t(x)
+        x.shared = True
+        v = ETensor(view_data, x.dtype)
+        v.shared = True
+        return v
+
+    def view_permute(self, x, dims):
+        return self._share(x, np.transpose(self._t(x).data, tuple(dims)))
+
+    def view_reshape(self, x, size):
+        x = self._t(x)
+        v = x.data.reshape(tuple(size))
+        assert np.shares_memory(v, x.data), "a reshape that needs a copy is not a view"
+        return self._share(x, v)
+
+    def view_narrow(self, x, axis, start, length):
+        x = self._t(x)
+        idx = [slice(None)] * x.data.ndim
+        idx[axis] = slice(start, start + length)
+        return self._share(x, x.data[tuple(idx)])
+
     # ---- reductions -------------------------------------------------------
     def _reduce(self, x, axis, fn):
         x = self._t(x)
@@ -330,7 +372,13 @@ class Eager:
 
     # ---- mutation, barrier, fetch -------------------------------------------
     def assign(self, dst: ETensor, src: ETensor) -> None:
-        """In-place update = rebind the destination to the new value."""
+        """In-place update = rebind the destination to the new value; a tensor whose memory is
+        shared with views (or that is a view) is written in place instead, so that every tensor on
+        that memory sees the update."""
+        if dst.shared:
+            assert dst.dtype == src.dtype and dst.data.shape == src.data.shape
+            dst.data[...] = src.data
+            return
         dst.data, dst.dtype = src.data, src.dtype
 
     def barrier(self, blocking: bool = True) -> None:

@@ -42,7 +42,7 @@ _IS_FLOAT = {F32: True, BF16: True, S32: False, S64: False}
 DEVICE_DATA, SCALAR_PARAM, CONSTANT = 1, 2, 3
 NEG, ABS, EXP, LOG, TANH, SQRT, RSQRT, RECIP, RELU, GELU, SQUARE, CAST, SIGMOID = range(16, 29)
 ADD, SUB, MUL, DIV, MAXIMUM, MINIMUM, RELU_GRAD, GELU_GRAD = range(32, 40)
-EXPAND, RESHAPE, PERMUTE = 48, 49, 50
+EXPAND, RESHAPE, PERMUTE, NARROW, SLICE_UPDATE = 48, 49, 50, 51, 52
 SUM, AMAX, MEAN = 64, 65, 66
 SOFTMAX, SOFTMAX_GRAD, LAYER_NORM, LAYER_NORM_GRAD, XENT, XENT_GRAD = range(80, 86)
 MATMUL = 96
@@ -55,7 +55,7 @@ OP_NAME = {
     ADD: "aten::add", SUB: "aten::sub", MUL: "aten::mul", DIV: "aten::div",
     MAXIMUM: "aten::maximum", MINIMUM: "aten::minimum", RELU_GRAD: "aten::threshold_backward",
     GELU_GRAD: "aten::gelu_backward", EXPAND: "aten::expand", RESHAPE: "aten::view",
-    PERMUTE: "aten::permute", SUM: "aten::sum", AMAX: "aten::amax", MEAN: "aten::mean",
+    PERMUTE: "aten::permute", NARROW: "aten::narrow", SLICE_UPDATE: "aten::slice_scatter", SUM: "aten::sum", AMAX: "aten::amax", MEAN: "aten::mean",
     SOFTMAX: "aten::_softmax", SOFTMAX_GRAD: "aten::_softmax_backward_data",
     LAYER_NORM: "aten::native_layer_norm", LAYER_NORM_GRAD: "aten::native_layer_norm_backward",
     XENT: "aten::nll_loss_of_log_softmax", XENT_GRAD: "aten::nll_loss_of_log_softmax_backward",
@@ -63,7 +63,7 @@ OP_NAME = {
 }
 
 # ---- attribute keys -----------------------------------------------------------
-A_VALUE, A_DTYPE, A_AXIS, A_EPS, A_TRANS_A, A_TRANS_B, A_DIM0 = 1, 2, 3, 4, 5, 6, 16
+A_VALUE, A_DTYPE, A_AXIS, A_EPS, A_TRANS_A, A_TRANS_B, A_START, A_LENGTH, A_DIM0 = 1, 2, 3, 4, 5, 6, 7, 8, 16
 
 UNARY = {NEG, ABS, EXP, LOG, TANH, SQRT, RSQRT, RECIP, RELU, GELU, SQUARE, CAST, SIGMOID}
 BINARY = {ADD, SUB, MUL, DIV, MAXIMUM, MINIMUM, RELU_GRAD, GELU_GRAD}
@@ -127,7 +127,7 @@ class Buffer:
 class STensor:
     """A tensor handle: unique id + binding (pending node | data | scalar)."""
     __slots__ = ("tid", "kind", "node", "slot", "buffer", "value", "dtype", "shape",
-                 "donor", "memo_epoch", "memo_node", "alive", "__weakref__")
+                 "donor", "memo_epoch", "memo_node", "alive", "version", "view", "seen", "__weakref__")
 
     def __del__(self):
         # dropping the last reference to a handle is UnregisterTensor
@@ -146,6 +146,9 @@ class STensor:
         self.memo_epoch = -1
         self.memo_node = None
         self.alive = True
+        self.version = 0               # bumped whenever the handle's value is replaced
+        self.view = None               # (base handle, view op, arguments) for a view (section 4.4)
+        self.seen = 0                  # version of the base that the current value was derived from
 
 
 class Tracer:
@@ -205,9 +208,47 @@ class Tracer:
     def _t(self, x) -> STensor:
         return x if isinstance(x, STensor) else self.scalar(x)
 
+    # ---- views (section 4.4) -------------------------------------------------
+    def _view_op(self, base, kind, args):
+        if kind == PERMUTE:
+            return self.permute(base, args)
+        if kind == RESHAPE:
+            return self.reshape(base, args)
+        return self.narrow(base, *args)
+
+    def _make_view(self, base, kind, args):
+        t = self._view_op(base, kind, args)
+        t.view, t.seen = (base, kind, args), base.version
+        return t
+
+    def view_permute(self, x, dims): return self._make_view(x, PERMUTE, tuple(int(d) for d in dims))
+    def view_reshape(self, x, size): return self._make_view(x, RESHAPE, tuple(int(d) for d in size))
+    def view_narrow(self, x, axis, start, length): return self._make_view(x, NARROW, (int(axis), int(start), int(length)))
+
+    def _refresh(self, t: STensor):
+        """Forward sequence: a view is its view op applied to the base's current value."""
+        if t.view is None:
+            return
+        base, kind, args = t.view
+        self._refresh(base)
+        if t.seen == base.version:
+            return
+        fresh = self._view_op(base, kind, args)
+        self._unbind(t)
+        t.kind, t.node, t.slot, t.donor, t.memo_epoch = "pending", fresh.node, 0, None, -1
+        t.version += 1
+        t.seen = base.version
+        self.release(fresh)
+
+    def _refresh_views(self):
+        for _, t in sorted(self.handles.items()):
+            if t.alive and t.view is not None:
+                self._refresh(t)
+
     def _use(self, t: STensor):
         """Operand reference (node, slot) for a handle in the current trace."""
         assert t.alive
+        self._refresh(t)
         if t.kind == "pending":
             return (t.node, t.slot)
         if t.memo_epoch != self.epoch or t.memo_node is None:
@@ -326,6 +367,21 @@ class Tracer:
         assert sorted(dims) == list(range(len(x.shape)))
         return self._emit(PERMUTE, x.dtype, tuple(x.shape[d] for d in dims), self._dims_attrs(dims), [x])
 
+    def narrow(self, x, axis, start, length):
+        x = self._t(x)
+        ax = int(axis) + (len(x.shape) if axis < 0 else 0)
+        assert 0 <= start and start + length <= x.shape[ax]
+        shape = x.shape[:ax] + (int(length),) + x.shape[ax + 1:]
+        return self._emit(NARROW, x.dtype, shape, [(A_AXIS, False, ax), (A_START, False, int(start)), (A_LENGTH, False, int(length))], [x])
+
+    def slice_update(self, base, update, axis, start):
+        base, update = self._t(base), self._t(update)
+        ax = int(axis) + (len(base.shape) if axis < 0 else 0)
+        assert update.dtype == base.dtype and len(update.shape) == len(base.shape)
+        assert all(u == b for i, (u, b) in enumerate(zip(update.shape, base.shape)) if i != ax)
+        assert 0 <= start and start + update.shape[ax] <= base.shape[ax]
+        return self._emit(SLICE_UPDATE, base.dtype, base.shape, [(A_AXIS, False, ax), (A_START, False, int(start))], [base, update])
+
     def _reduce(self, op, x, axis):
         x = self._t(x)
         if axis is None:
@@ -380,6 +436,9 @@ class Tracer:
         assert dst.alive and src.alive
         if dst is src:
             return
+        self._refresh(src)
+        if dst.view is not None:
+            assert dst.dtype == src.dtype and dst.shape == src.shape
         donor = dst.donor
         if dst.kind == "data" and dst.buffer.donatable:
             donor = dst.buffer
@@ -390,6 +449,25 @@ class Tracer:
         if dst.kind == "data":
             dst.buffer.data_refs += 1
         dst.donor = donor
+        dst.version += 1
+        if dst.view is None:
+            return
+        # backward sequence: the base is rebuilt from the view's new value by the inverse view op
+        base, kind, args = dst.view
+        self._refresh(base)
+        dst.seen = base.version
+        if kind == PERMUTE:
+            inv = [0] * len(args)
+            for j, src_axis in enumerate(args):
+                inv[src_axis] = j
+            rebuilt = self.permute(dst, tuple(inv))
+        elif kind == RESHAPE:
+            rebuilt = self.reshape(dst, base.shape)
+        else:
+            rebuilt = self.slice_update(base, dst, args[0], args[1])
+        self.assign(base, rebuilt)
+        self.release(rebuilt)
+        dst.seen = base.version
 
     # ---- barrier -------------------------------------------------------------
     def roots(self):
@@ -464,6 +542,7 @@ class Tracer:
 
     def dump_ir(self) -> str:
         """Text form of the pending trace, in the layout of the paper's figure 1."""
+        self._refresh_views()
         roots = self.roots()
         order, index_of = self.canonical_order([(t.node, t.slot) for t in roots])
         lines = ["IR {"]
@@ -499,6 +578,7 @@ class Tracer:
     def barrier(self, blocking: bool = True):
         """Cut, number, serialise, hash, consult the cache, lower on a miss,
         then rebind every root to fresh data.  Returns a dict of results."""
+        self._refresh_views()
         roots = self.roots()
         order, index_of = self.canonical_order([(t.node, t.slot) for t in roots])
         blob, donors = self.serialise(order, index_of, roots)
@@ -534,6 +614,7 @@ class Tracer:
         return self.last
 
     def fetch(self, t: STensor):
+        self._refresh(t)
         if t.kind == "pending":
             self.barrier(True)
         return None
@@ -616,7 +697,7 @@ class Tracer:
             live[i] = True
             stack.extend(v[0] for v in rins[i])
 
-        LEAF, VIEW, EW, ROW, COL, ALL, MM = "LEAF", "VIEW", "EW", "ROW", "COL", "ALL", "MM"
+        LEAF, VIEW, EW, ROW, COL, ALL, MM, SLICE = "LEAF", "VIEW", "EW", "ROW", "COL", "ALL", "MM", "SLICE"
 
         def klass(i):
             n = nd[i]
@@ -628,6 +709,13 @@ class Tracer:
             if n.op == PERMUTE:
                 # a permutation that only feeds contractions is addressing (operand strides), not a copy
                 return VIEW if (not is_root[i] and pre_users[i] and all(nd[u].op == MATMUL for u in pre_users[i])) else EW
+            if n.op == NARROW:
+                # a window is addressing for elementwise ops, contractions and permutations; otherwise a copy
+                ok = not is_root[i] and pre_users[i] and all(
+                    nd[u].op in UNARY or nd[u].op in BINARY or nd[u].op in (MATMUL, PERMUTE) for u in pre_users[i])
+                return VIEW if ok else EW
+            if n.op == SLICE_UPDATE:
+                return SLICE
             if n.op in UNARY or n.op in BINARY:
                 return EW
             if n.op in PLAIN_REDUCE:
@@ -696,7 +784,7 @@ class Tracer:
             return r["anchor"] if r["anchor"] is not None else min(r["members"])
 
         for i in range(N):
-            if cls[i] in (EW, ROW, COL, ALL, MM):
+            if cls[i] in (EW, ROW, COL, ALL, MM, SLICE):
                 r = {"kind": cls[i], "anchor": None if cls[i] == EW else i, "members": {i}, "fin_shape": None}
                 regions[id(r)] = r
                 region_of[i] = r
@@ -723,6 +811,9 @@ class Tracer:
         def caps_ok(members):
             # a permutation's operand must be in memory: never computed in the permutation's own region
             if any(nd[m].op == PERMUTE and rins[m][0][0] in members for m in members):
+                return False
+            # ... and so must any value that a member reads through a view
+            if any(cls[v[0]] == VIEW and base(v)[0] in members for m in members for v in rins[m]):
                 return False
             inputs, outputs = region_io(members)
             return (len(inputs) <= MAX_INPUTS and len(outputs) <= MAX_OUTPUTS
@@ -894,8 +985,13 @@ class Tracer:
                 if r is rw:
                     for m in r["members"]:
                         for x in rins[m]:
-                            if base(x) in pn and (m == rw["anchor"] or x not in pn
-                                                  or nd[m].op in (PERMUTE, EXPAND, RESHAPE)):
+                            if base(x) not in pn:
+                                continue
+                            # a window update may overwrite its own base (operand 0) in place
+                            if (m == rw["anchor"] and nd[m].op == SLICE_UPDATE and x in pn and x == rins[m][0]
+                                    and base(rins[m][1]) not in pn):
+                                continue
+                            if m == rw["anchor"] or x not in pn or nd[m].op in (PERMUTE, EXPAND, RESHAPE, NARROW):
                                 ok = False
                 else:
                     readers.append(r)

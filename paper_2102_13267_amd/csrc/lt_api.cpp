@@ -43,6 +43,7 @@ const char* op_name(uint16_t op) {
     case LT_OP_DIV: return "aten::div"; case LT_OP_MAXIMUM: return "aten::maximum"; case LT_OP_MINIMUM: return "aten::minimum";
     case LT_OP_RELU_GRAD: return "aten::threshold_backward"; case LT_OP_GELU_GRAD: return "aten::gelu_backward";
     case LT_OP_EXPAND: return "aten::expand"; case LT_OP_RESHAPE: return "aten::view"; case LT_OP_PERMUTE: return "aten::permute";
+    case LT_OP_NARROW: return "aten::narrow"; case LT_OP_SLICE_UPDATE: return "aten::slice_scatter";
     case LT_OP_SUM: return "aten::sum"; case LT_OP_AMAX: return "aten::amax"; case LT_OP_MEAN: return "aten::mean";
     case LT_OP_SOFTMAX: return "aten::_softmax"; case LT_OP_SOFTMAX_GRAD: return "aten::_softmax_backward_data";
     case LT_OP_LAYER_NORM: return "aten::native_layer_norm";
@@ -106,9 +107,11 @@ void Arena::release(void* p) {
   free_blocks[off] = len;
 }
 
-static Handle* find(lt_ctx* ctx, lt_tensor t) {
+// `hidden`: also find a handle that its owner has released but that lives on as the base of views
+static Handle* find(lt_ctx* ctx, lt_tensor t, bool hidden = false) {
   auto it = ctx->handles.find(t);
-  return it == ctx->handles.end() ? nullptr : &it->second;
+  if (it == ctx->handles.end() || (it->second.released && !hidden)) return nullptr;
+  return &it->second;
 }
 
 static void unbind(Handle* h) {
@@ -121,6 +124,71 @@ static Handle* new_handle(lt_ctx* ctx) {
   Handle& h = ctx->handles[id];
   h.id = id;
   return &h;
+}
+
+static lt_status record_op(lt_ctx* ctx, uint16_t opcode, const lt_tensor* inputs, int n_in, const lt_attr* attrs, int n_attr,
+                           lt_tensor* outputs, int n_out, bool hidden);
+static lt_status assign(lt_ctx* ctx, lt_tensor dst_id, lt_tensor src_id, bool hidden);
+
+// Drop a handle for good.  A view gives up its hold on its base; a base that its owner had
+// already released goes with its last view.
+static void erase_handle(lt_ctx* ctx, Handle* h) {
+  const uint64_t base = h->view_base;
+  unbind(h);
+  ctx->handles.erase(h->id);
+  if (base) {
+    Handle* b = find(ctx, base, true);
+    if (b && --b->view_refs == 0 && b->released) erase_handle(ctx, b);
+  }
+}
+
+static lt_status release_one(lt_ctx* ctx, Handle* h) {
+  if (h->view_refs > 0) {   // still the storage behind live views: hidden, not gone
+    h->released = true;
+    return LT_OK;
+  }
+  erase_handle(ctx, h);
+  return LT_OK;
+}
+
+// A view's value is its view op applied to the CURRENT value of its base (section 4.4, the
+// "forward sequence"): derive it again if the base has been replaced since it was last derived.
+static lt_status refresh(lt_ctx* ctx, Handle* h) {
+  if (!h->view_base) return LT_OK;
+  Handle* b = find(ctx, h->view_base, true);
+  if (!b) return fail(ctx, LT_ERR_HANDLE, "internal: a view has lost its base");
+  lt_status st = refresh(ctx, b);
+  if (st != LT_OK || h->seen == b->version) return st;
+  lt_tensor tid = 0;
+  const lt_tensor bid = b->id;
+  st = record_op(ctx, h->view_op, &bid, 1, h->view_attrs, h->view_n_attr, &tid, 1, true);
+  if (st != LT_OK) return st;
+  Handle* t = find(ctx, tid, true);
+  unbind(h);
+  h->kind = H_PENDING;
+  h->node = t->node;
+  h->slot = 0;
+  h->donor.reset();
+  h->memo_epoch = ~0ull;
+  h->version++;
+  h->seen = b->version;
+  ctx->handles.erase(tid);
+  return LT_OK;
+}
+
+// Before the trace is cut, and before anything reads a view from outside: every live view holds
+// the value its base has now.
+lt_status refresh_views(lt_ctx* ctx) {
+  std::vector<uint64_t> ids;
+  for (auto& kv : ctx->handles)
+    if (kv.second.view_base) ids.push_back(kv.first);
+  for (uint64_t id : ids) {
+    Handle* h = find(ctx, id, true);
+    if (!h) continue;
+    const lt_status st = refresh(ctx, h);
+    if (st != LT_OK) return st;
+  }
+  return LT_OK;
 }
 
 // operand reference of a handle in the trace being recorded; leaves are created on first use
@@ -316,12 +384,25 @@ lt_status lt_scalar(lt_ctx* ctx, lt_dtype dtype, double value, lt_tensor* out) {
 
 lt_status lt_op(lt_ctx* ctx, uint16_t opcode, const lt_tensor* inputs, int n_in, const lt_attr* attrs, int n_attr,
                 lt_tensor* outputs, int n_out) {
+  return record_op(ctx, opcode, inputs, n_in, attrs, n_attr, outputs, n_out, false);
+}
+
+}  // extern "C"
+
+namespace lt {
+
+static lt_status record_op(lt_ctx* ctx, uint16_t opcode, const lt_tensor* inputs, int n_in, const lt_attr* attrs, int n_attr,
+                           lt_tensor* outputs, int n_out, bool hidden) {
   if (!ctx || !inputs || !outputs || n_in < 1 || n_in > kMaxIns || n_attr < 0 || (n_attr > 0 && !attrs))
     return fail(ctx, LT_ERR_ARG, "lt_op: bad arguments");
   Handle* in[kMaxIns];
   for (int i = 0; i < n_in; ++i) {
-    in[i] = find(ctx, inputs[i]);
+    in[i] = find(ctx, inputs[i], hidden);
     if (!in[i]) return fail(ctx, LT_ERR_HANDLE, "lt_op: unknown or released tensor id");
+    if (in[i]->view_base) {   // a view is read at its base's current value
+      const lt_status st = refresh(ctx, in[i]);
+      if (st != LT_OK) return st;
+    }
   }
   Node n;
   n.op = opcode;
@@ -484,6 +565,37 @@ lt_status lt_op(lt_ctx* ctx, uint16_t opcode, const lt_tensor* inputs, int n_in,
       push_attr(&n, LT_ATTR_TRANS_A, false, tra ? 1 : 0, 0);
       push_attr(&n, LT_ATTR_TRANS_B, false, trb ? 1 : 0, 0);
     } break;
+    case LT_OP_NARROW: {
+      const lt_attr* ax = find_attr(attrs, n_attr, LT_ATTR_AXIS);
+      const lt_attr* st = find_attr(attrs, n_attr, LT_ATTR_START);
+      const lt_attr* ln = find_attr(attrs, n_attr, LT_ATTR_LENGTH);
+      if (!need(1) || !ax || !st || !ln) return fail(ctx, LT_ERR_ARG, "narrow takes one input and LT_ATTR_AXIS, _START, _LENGTH");
+      const int64_t axis = ax->v.i < 0 ? ax->v.i + a->rank : ax->v.i;
+      if (axis < 0 || axis >= a->rank) return fail(ctx, LT_ERR_ARG, "narrow: axis out of range");
+      if (st->v.i < 0 || ln->v.i < 0 || st->v.i + ln->v.i > a->dims[axis]) return fail(ctx, LT_ERR_SHAPE, "narrow: window exceeds the axis");
+      n.dtype = a->dtype;
+      set_shape(a->dims, a->rank);
+      n.dims[axis] = ln->v.i;
+      push_attr(&n, LT_ATTR_AXIS, false, axis, 0);
+      push_attr(&n, LT_ATTR_START, false, st->v.i, 0);
+      push_attr(&n, LT_ATTR_LENGTH, false, ln->v.i, 0);
+    } break;
+    case LT_OP_SLICE_UPDATE: {
+      const lt_attr* ax = find_attr(attrs, n_attr, LT_ATTR_AXIS);
+      const lt_attr* st = find_attr(attrs, n_attr, LT_ATTR_START);
+      if (!need(2) || !ax || !st) return fail(ctx, LT_ERR_ARG, "slice_update takes (base, update) and LT_ATTR_AXIS, _START");
+      const Handle* u = in[1];
+      const int64_t axis = ax->v.i < 0 ? ax->v.i + a->rank : ax->v.i;
+      if (axis < 0 || axis >= a->rank) return fail(ctx, LT_ERR_ARG, "slice_update: axis out of range");
+      if (u->rank != a->rank || u->dtype != a->dtype) return fail(ctx, LT_ERR_SHAPE, "slice_update: update must have the base's rank and dtype");
+      for (int i = 0; i < a->rank; ++i)
+        if (i != axis && u->dims[i] != a->dims[i]) return fail(ctx, LT_ERR_SHAPE, "slice_update: update differs from the base off the axis");
+      if (st->v.i < 0 || st->v.i + u->dims[axis] > a->dims[axis]) return fail(ctx, LT_ERR_SHAPE, "slice_update: window exceeds the axis");
+      n.dtype = a->dtype;
+      set_shape(a->dims, a->rank);
+      push_attr(&n, LT_ATTR_AXIS, false, axis, 0);
+      push_attr(&n, LT_ATTR_START, false, st->v.i, 0);
+    } break;
     default:
       return fail(ctx, LT_ERR_UNSUPPORTED, "lt_op: opcode " + std::to_string(opcode) + " has no lowering");
   }
@@ -513,12 +625,23 @@ lt_status lt_op(lt_ctx* ctx, uint16_t opcode, const lt_tensor* inputs, int n_in,
   return LT_OK;
 }
 
-lt_status lt_assign(lt_ctx* ctx, lt_tensor dst_id, lt_tensor src_id) {
-  if (!ctx) return LT_ERR_ARG;
-  Handle* dst = find(ctx, dst_id);
-  Handle* src = find(ctx, src_id);
+// In-place update as substitution (section 4.3).  Through a view (section 4.4): the view takes the
+// new value, and the base is rebuilt from it by the inverse of the view op (the "backward
+// sequence"), through every level of a chain of views.
+static lt_status assign(lt_ctx* ctx, lt_tensor dst_id, lt_tensor src_id, bool hidden) {
+  Handle* dst = find(ctx, dst_id, hidden);
+  Handle* src = find(ctx, src_id, hidden);
   if (!dst || !src) return fail(ctx, LT_ERR_HANDLE, "lt_assign: unknown or released tensor id");
   if (dst == src) return LT_OK;
+  if (src->view_base) {
+    const lt_status st = refresh(ctx, src);
+    if (st != LT_OK) return st;
+  }
+  if (dst->view_base) {
+    bool same = dst->dtype == src->dtype && dst->rank == src->rank;
+    for (int i = 0; same && i < dst->rank; ++i) same = dst->dims[i] == src->dims[i];
+    if (!same) return fail(ctx, LT_ERR_SHAPE, "lt_assign: a view can only take a value of its own dtype and shape");
+  }
   BufRef donor = dst->donor;
   if (dst->kind == H_DATA && dst->buf && dst->buf->donatable) donor = dst->buf;
   unbind(dst);
@@ -534,6 +657,69 @@ lt_status lt_assign(lt_ctx* ctx, lt_tensor dst_id, lt_tensor src_id) {
   dst->memo_node = src->memo_node;
   if (dst->kind == H_DATA && dst->buf) dst->buf->data_refs += 1;
   dst->donor = donor;
+  dst->version++;
+  if (!dst->view_base) return LT_OK;
+  Handle* b = find(ctx, dst->view_base, true);
+  if (!b) return fail(ctx, LT_ERR_HANDLE, "internal: a view has lost its base");
+  lt_status st = refresh(ctx, b);   // (a base that is itself a stale view)
+  if (st != LT_OK) return st;
+  dst->seen = b->version;           // the view now holds its new value, not one to derive again
+  lt_attr inv[kMaxAttrs];
+  int n_inv = 0;
+  lt_tensor tid = 0;
+  const lt_tensor bid = b->id;
+  if (dst->view_op == LT_OP_PERMUTE) {
+    for (int i = 0; i < dst->view_n_attr; ++i) {   // inverse permutation: view axis j shows base axis p[j], so base axis p[j] is view axis j
+      const int64_t j = dst->view_attrs[i].key - LT_ATTR_DIM0, src_axis = dst->view_attrs[i].v.i;
+      inv[src_axis].key = (uint16_t)(LT_ATTR_DIM0 + src_axis);
+      inv[src_axis].is_float = 0;
+      inv[src_axis].v.i = j;
+    }
+    n_inv = dst->view_n_attr;
+    st = record_op(ctx, LT_OP_PERMUTE, &dst_id, 1, inv, n_inv, &tid, 1, true);
+  } else if (dst->view_op == LT_OP_RESHAPE) {
+    for (int i = 0; i < b->rank; ++i) inv[n_inv++] = lt_attr{(uint16_t)(LT_ATTR_DIM0 + i), 0, {b->dims[i]}};
+    st = record_op(ctx, LT_OP_RESHAPE, &dst_id, 1, inv, n_inv, &tid, 1, true);
+  } else {
+    for (int i = 0; i < dst->view_n_attr; ++i)
+      if (dst->view_attrs[i].key == LT_ATTR_AXIS || dst->view_attrs[i].key == LT_ATTR_START) inv[n_inv++] = dst->view_attrs[i];
+    const lt_tensor ins[2] = {bid, dst_id};
+    st = record_op(ctx, LT_OP_SLICE_UPDATE, ins, 2, inv, n_inv, &tid, 1, true);
+  }
+  if (st != LT_OK) return st;
+  st = assign(ctx, bid, tid, true);
+  Handle* t = find(ctx, tid, true);
+  if (t) erase_handle(ctx, t);
+  dst = find(ctx, dst_id, true);
+  b = find(ctx, bid, true);
+  if (dst && b) dst->seen = b->version;
+  return st;
+}
+
+}  // namespace lt
+
+extern "C" {
+
+lt_status lt_assign(lt_ctx* ctx, lt_tensor dst_id, lt_tensor src_id) {
+  if (!ctx) return LT_ERR_ARG;
+  return assign(ctx, dst_id, src_id, false);
+}
+
+lt_status lt_view(lt_ctx* ctx, lt_tensor base, uint16_t view_op, const lt_attr* attrs, int n_attr, lt_tensor* out) {
+  if (!ctx || !out) return LT_ERR_ARG;
+  if (view_op != LT_OP_PERMUTE && view_op != LT_OP_RESHAPE && view_op != LT_OP_NARROW)
+    return fail(ctx, LT_ERR_ARG, "lt_view: the view ops are permute, reshape and narrow");
+  if (n_attr < 0 || n_attr > kMaxAttrs) return fail(ctx, LT_ERR_ARG, "lt_view: bad attributes");
+  lt_status st = record_op(ctx, view_op, &base, 1, attrs, n_attr, out, 1, false);
+  if (st != LT_OK) return st;
+  Handle* h = find(ctx, *out);
+  Handle* b = find(ctx, base);
+  h->view_base = base;
+  h->view_op = view_op;
+  h->view_n_attr = (uint8_t)n_attr;
+  for (int i = 0; i < n_attr; ++i) h->view_attrs[i] = attrs[i];
+  h->seen = b->version;
+  b->view_refs++;
   return LT_OK;
 }
 
@@ -541,9 +727,7 @@ lt_status lt_release(lt_ctx* ctx, lt_tensor t) {
   if (!ctx) return LT_ERR_ARG;
   Handle* h = find(ctx, t);
   if (!h) return fail(ctx, LT_ERR_HANDLE, "lt_release: unknown or released tensor id");
-  unbind(h);
-  ctx->handles.erase(t);
-  return LT_OK;
+  return release_one(ctx, h);
 }
 
 lt_status lt_release_many(lt_ctx* ctx, const lt_tensor* ts, size_t n) {
@@ -555,8 +739,7 @@ lt_status lt_release_many(lt_ctx* ctx, const lt_tensor* ts, size_t n) {
       st = fail(ctx, LT_ERR_HANDLE, "lt_release_many: unknown or released tensor id");
       continue;
     }
-    unbind(h);
-    ctx->handles.erase(ts[i]);
+    (void)release_one(ctx, h);
   }
   return st;
 }
@@ -576,6 +759,7 @@ lt_status lt_device_ptr(lt_ctx* ctx, lt_tensor t, void** dptr) {
   if (!ctx || !dptr) return LT_ERR_ARG;
   Handle* h = find(ctx, t);
   if (!h) return fail(ctx, LT_ERR_HANDLE, "lt_device_ptr: unknown or released tensor id");
+  if (h->view_base && refresh(ctx, h) != LT_OK) return LT_ERR_HANDLE;
   if (h->kind != H_DATA) return fail(ctx, LT_ERR_HANDLE, "lt_device_ptr: tensor is not materialised (barrier first)");
   *dptr = h->buf->ptr;
   return LT_OK;
@@ -593,6 +777,8 @@ static lt_status copy_out(const std::string& s, char* buf, size_t cap, size_t* l
 
 lt_status lt_dump_ir(lt_ctx* ctx, char* buf, size_t cap, size_t* len) {
   if (!ctx) return LT_ERR_ARG;
+  lt_status vs = refresh_views(ctx);   // what the next barrier would cut
+  if (vs != LT_OK) return vs;
   Cut cut;
   collect_cut(ctx, &cut);
   std::string s = "IR {\n";
@@ -620,7 +806,8 @@ lt_status lt_dump_ir(lt_ctx* ctx, char* buf, size_t cap, size_t* len) {
       for (int k = 0; k < n.n_attr; ++k) {
         const Attr& a = n.attrs[k];
         const char* name = a.key == LT_ATTR_DTYPE ? "dtype" : a.key == LT_ATTR_AXIS ? "axis" : a.key == LT_ATTR_EPS ? "eps"
-                           : a.key == LT_ATTR_TRANS_A ? "trans_a" : a.key == LT_ATTR_TRANS_B ? "trans_b" : "attr";
+                           : a.key == LT_ATTR_TRANS_A ? "trans_a" : a.key == LT_ATTR_TRANS_B ? "trans_b"
+                           : a.key == LT_ATTR_START ? "start" : a.key == LT_ATTR_LENGTH ? "length" : "attr";
         if (a.key == LT_ATTR_DTYPE) std::snprintf(tmp, sizeof(tmp), ", %s=%s", name, dtype_name((uint8_t)a.v.i));
         else if (a.is_float) std::snprintf(tmp, sizeof(tmp), ", %s=%g", name, a.v.f);
         else std::snprintf(tmp, sizeof(tmp), ", %s=%lld", name, (long long)a.v.i);
@@ -648,7 +835,7 @@ lt_status lt_dump_schedule(lt_ctx* ctx, char* buf, size_t cap, size_t* len) {
   if (!ctx) return LT_ERR_ARG;
   std::string s;
   if (ctx->last_plan) {
-    static const char* const kinds[] = {"EW", "ROW", "ALL", "COL", "ROWOP", "MM", "SPLITPOST"};
+    static const char* const kinds[] = {"EW", "ROW", "ALL", "COL", "ROWOP", "MM", "SPLITPOST", "SLICE"};
     const Plan& p = *ctx->last_plan;
     for (size_t i = 0; i < p.launches.size(); ++i) {
       const Launch& l = p.launches[i];

@@ -145,6 +145,7 @@ static hipError_t launch_one(const Launch& l, const uint8_t* args, hipStream_t s
     case L_ROWOP: return ltk::launch_row_op(*(const ltk::RowOpArgs*)args, l.grid_x, s);
     case L_GEMM: return ltk::launch_gemm(*(const ltk::GemmArgs*)args, s);
     case L_SPLITPOST: return ltk::launch_split_post(*(const ltk::SplitPostArgs*)args, l.grid_x, s);
+    case L_SLICE: return ltk::launch_slice_update(*(const ltk::SliceArgs*)args, l.grid_x, s);
   }
   return hipErrorInvalidValue;
 }
@@ -158,6 +159,7 @@ static const char* kind_name(LaunchKind k) {
     case L_ROWOP: return "lt_row_op_kernel";
     case L_GEMM: return "lt_gemm_kernel";
     case L_SPLITPOST: return "lt_split_post_kernel";
+    case L_SLICE: return "lt_slice_update_kernel";
   }
   return "?";
 }
@@ -383,6 +385,8 @@ extern "C" {
 
 static lt_status barrier_impl(lt_ctx* ctx, int blocking, lt_barrier_info* info, bool use_static) {
   const uint64_t t0 = now_ns();
+  lt_status vs = refresh_views(ctx);   // (section 4.4) a live view is evaluated at its base's current value
+  if (vs != LT_OK) return vs;
   Cut cut;
   collect_cut(ctx, &cut);
   std::vector<uint8_t> key;
@@ -473,7 +477,11 @@ lt_status lt_barrier_static(lt_ctx* ctx, int blocking, lt_barrier_info* info) {
 lt_status lt_fetch(lt_ctx* ctx, lt_tensor t, void* host_dst, size_t nbytes) {
   if (!ctx || !host_dst) return LT_ERR_ARG;
   auto it = ctx->handles.find(t);
-  if (it == ctx->handles.end()) return fail(ctx, LT_ERR_HANDLE, "lt_fetch: unknown or released tensor id");
+  if (it == ctx->handles.end() || it->second.released) return fail(ctx, LT_ERR_HANDLE, "lt_fetch: unknown or released tensor id");
+  if (it->second.view_base) {
+    lt_status vs = refresh_views(ctx);
+    if (vs != LT_OK) return vs;
+  }
   if (it->second.kind == H_PENDING) {
     lt_status st = lt_barrier(ctx, 1, nullptr);
     if (st != LT_OK) return st;

@@ -97,11 +97,21 @@ struct Handle {
   BufRef donor;                   // buffer this handle gave up through lt_assign
   uint64_t memo_epoch = ~0ull;    // leaf node created for this handle in the current trace
   int32_t memo_node = -1;
+  // views (section 4.4): a view handle names its base and the view op; its value is that op
+  // applied to the base's CURRENT value, recomputed when the base has changed since (`seen`)
+  uint64_t version = 0;           // bumped whenever the handle's value is replaced
+  uint64_t view_base = 0;         // tensor id of the base (0: not a view)
+  uint16_t view_op = 0;           // LT_OP_PERMUTE / LT_OP_RESHAPE / LT_OP_NARROW
+  uint8_t view_n_attr = 0;
+  lt_attr view_attrs[kMaxAttrs];
+  uint64_t seen = 0;              // base's version that the current value was derived from
+  int32_t view_refs = 0;          // views that name this handle as their base
+  bool released = false;          // released by the caller, kept while views still name it
 };
 
 // ---- a lowered, cached program ------------------------------------------------------------
 
-enum LaunchKind : uint8_t { L_EW, L_ROW, L_ALL, L_COL, L_ROWOP, L_GEMM, L_SPLITPOST };
+enum LaunchKind : uint8_t { L_EW, L_ROW, L_ALL, L_COL, L_ROWOP, L_GEMM, L_SPLITPOST, L_SLICE };
 
 struct Storage {
   int param = -1;        // >= 0: the buffer of device parameter `param` (input, or donated output)
@@ -201,6 +211,9 @@ size_t dtype_size(uint8_t dtype);
 const char* dtype_name(uint8_t dtype);
 const char* op_name(uint16_t op);
 int64_t numel(const int64_t* dims, int rank);
+
+// views (lt_api.cpp): bring every live view up to date with its base
+lt_status refresh_views(lt_ctx* ctx);
 
 // barrier pieces (lt_barrier.cpp)
 struct Cut {

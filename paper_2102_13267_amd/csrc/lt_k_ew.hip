@@ -397,4 +397,35 @@ hipError_t launch_ew(const EwArgs& a, uint32_t grid, hipStream_t s) {
   return hipGetLastError();
 }
 
+// ---- window update (the inverse of a narrow view, section 4.4 of the paper) ---------------------
+// One element per lane and trip, any element size: a copy, bound by HBM.  In place only the
+// window is touched.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void lt_slice_update_kernel(const SliceArgs a) {
+  const T* base = (const T*)a.base;
+  const T* upd = (const T*)a.upd;
+  T* out = (T*)a.out;
+  const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+  const uint64_t win = a.len * a.inner, row = a.dim * a.inner, lo = a.start * a.inner;
+  for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < a.n; i += stride) {
+    if (a.window_only) {
+      const uint64_t o = i / win, r = i % win;
+      out[o * row + lo + r] = upd[i];
+    } else {
+      const uint64_t o = i / row, r = i % row;
+      out[i] = (r >= lo && r < lo + win) ? upd[o * win + (r - lo)] : base[i];
+    }
+  }
+}
+
+hipError_t launch_slice_update(const SliceArgs& a, uint32_t grid, hipStream_t s) {
+  if (a.n == 0) return hipSuccess;
+  if (!a.upd || !a.out || (!a.window_only && !a.base) || a.start + a.len > a.dim || grid == 0) return hipErrorInvalidValue;
+  if (a.elem_bytes == 4) hipLaunchKernelGGL(lt_slice_update_kernel<uint32_t>, dim3(grid), dim3(kBlock), 0, s, a);
+  else if (a.elem_bytes == 2) hipLaunchKernelGGL(lt_slice_update_kernel<uint16_t>, dim3(grid), dim3(kBlock), 0, s, a);
+  else if (a.elem_bytes == 8) hipLaunchKernelGGL(lt_slice_update_kernel<uint64_t>, dim3(grid), dim3(kBlock), 0, s, a);
+  else return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
 }  // namespace ltk

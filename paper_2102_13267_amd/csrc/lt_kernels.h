@@ -186,5 +186,19 @@ struct SplitPostArgs {
   uint64_t stride;           // floats between consecutive splits (= elements of the output)
 };
 
+// ---- window update -------------------------------------------------------------------------
+// out = base with the window [start, start + len) along one axis replaced by upd.  The tensors are
+// seen as [outer, dim, inner] (base, out) and [outer, len, inner] (upd), dense.  window_only: out
+// is base's own buffer (updated in place), so only the window is written.
+struct SliceArgs {
+  const void* base;
+  const void* upd;
+  void* out;
+  uint64_t n;              // elements this launch walks: the window (window_only) or all of out
+  uint64_t dim, inner, start, len;
+  uint32_t elem_bytes;     // 2, 4 or 8
+  uint32_t window_only;
+};
+
 }  // namespace ltk
 #endif  // LT_KERNELS_H_

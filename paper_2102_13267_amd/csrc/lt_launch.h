@@ -13,6 +13,7 @@ hipError_t launch_all_reduce(const AllArgs& a, uint32_t grid, hipStream_t s);
 hipError_t launch_col_reduce(const ColArgs& a, uint32_t grid_x, uint32_t grid_y, hipStream_t s);
 hipError_t launch_row_op(const RowOpArgs& a, uint32_t grid, hipStream_t s);
 hipError_t launch_split_post(const SplitPostArgs& a, uint32_t grid, hipStream_t s);
+hipError_t launch_slice_update(const SliceArgs& a, uint32_t grid, hipStream_t s);
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s);   // 128 x 128 tiles, split-K (called by launch_gemm)
 

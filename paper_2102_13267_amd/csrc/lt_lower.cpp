@@ -32,7 +32,7 @@
 namespace lt {
 namespace {
 
-enum Class : uint8_t { C_DEAD, C_LEAF, C_VIEW, C_EW, C_ROW, C_COL, C_ALL, C_MM };
+enum Class : uint8_t { C_DEAD, C_LEAF, C_VIEW, C_EW, C_ROW, C_COL, C_ALL, C_MM, C_SLICE };
 
 struct Region {
   Class kind;
@@ -193,7 +193,15 @@ struct Lowering {
         bool only_mm = !is_root[i] && !users[i].empty();
         for (int32_t u : users[i]) only_mm = only_mm && nd[u]->op == LT_OP_MATMUL;
         cls[i] = only_mm ? C_VIEW : C_EW;
-      } else if (is_unary(op) || is_binary(op)) cls[i] = C_EW;
+      } else if (op == LT_OP_NARROW) {
+        // a window is addressing (an offset and the base's strides) for the consumers that can
+        // address it: elementwise ops, contractions, permutations; otherwise a copy
+        bool addr = !is_root[i] && !users[i].empty();
+        for (int32_t u : users[i])
+          addr = addr && (is_unary(nd[u]->op) || is_binary(nd[u]->op) || nd[u]->op == LT_OP_MATMUL || nd[u]->op == LT_OP_PERMUTE);
+        cls[i] = addr ? C_VIEW : C_EW;
+      } else if (op == LT_OP_SLICE_UPDATE) cls[i] = C_SLICE;
+      else if (is_unary(op) || is_binary(op)) cls[i] = C_EW;
       else if (plain_reduce(op)) {
         const int in_rank = out_rank(rins[i][0]);
         if (nd[i]->n_attr == 0 || in_rank <= 1) cls[i] = C_ALL;
@@ -247,6 +255,11 @@ struct Lowering {
     // in memory, so its producer never shares a region with the permutation
     for (int32_t m : members)
       if (nd[m]->op == LT_OP_PERMUTE && std::binary_search(members.begin(), members.end(), rins[m][0].node)) return false;
+    // the same for anything read through a view (a window, a broadcast, a reshape): the value
+    // under the view must be in memory, so it is never computed by the region that reads the view
+    for (int32_t m : members)
+      for (Val v : rins[m])
+        if (cls[v.node] == C_VIEW && std::binary_search(members.begin(), members.end(), base(v).node)) return false;
     return (int)in.size() <= kMaxRegionInputs && (int)out.size() <= kMaxRegionOutputs &&
            (int)(in.size() + members.size()) <= kMaxRegionSlots;
   }
@@ -448,9 +461,14 @@ struct Lowering {
         if (r == rw) {
           for (int32_t m : r->members)
             for (Val x : rins[m])
-              if (names_donor(base(x)) && (m == rw->anchor || !names_donor(x) || nd[m]->op == LT_OP_PERMUTE ||
-                                           nd[m]->op == LT_OP_EXPAND || nd[m]->op == LT_OP_RESHAPE))
-                ok = false;
+              if (names_donor(base(x))) {
+                // a window update may overwrite its own base (operand 0, read in place) ...
+                if (m == rw->anchor && nd[m]->op == LT_OP_SLICE_UPDATE && names_donor(x) && x == rins[m][0] && !names_donor(base(rins[m][1]))) continue;
+                // ... everything else must read the donor position by position
+                if (m == rw->anchor || !names_donor(x) || nd[m]->op == LT_OP_PERMUTE || nd[m]->op == LT_OP_EXPAND ||
+                    nd[m]->op == LT_OP_RESHAPE || nd[m]->op == LT_OP_NARROW)
+                  ok = false;
+              }
         } else {
           readers.push_back(r);
         }
@@ -493,7 +511,7 @@ struct Lowering {
     char tmp[64];
     for (size_t k = 0; k < ordered.size(); ++k) {
       const Region* r = ordered[k];
-      static const char* names[] = {"DEAD", "LEAF", "VIEW", "EW", "ROW", "COL", "ALL", "MM"};
+      static const char* names[] = {"DEAD", "LEAF", "VIEW", "EW", "ROW", "COL", "ALL", "MM", "SLICE"};
       std::vector<Val> in, o;
       region_io(r->members, &in, &o);
       if (k) out += "\n";
@@ -526,11 +544,13 @@ struct Lowering {
   std::vector<int32_t> param_ordinal;             // canonical node -> device parameter ordinal or -1
   std::vector<int32_t> scalar_ordinal;            // canonical node -> scalar ordinal or -1
 
-  // Addressing of a value relative to an iteration space: the storage that holds it and the
-  // element stride along every dimension of the space (0 where it is broadcast).
+  // Addressing of a value relative to an iteration space: the storage that holds it, the element
+  // offset of its first element and the element stride along every dimension of the space (0 where
+  // it is broadcast).
   struct Access {
     int32_t storage = -1;
     uint8_t dtype = 0;
+    int64_t offset = 0;
     std::vector<int64_t> stride;
   };
 
@@ -540,60 +560,81 @@ struct Lowering {
     return s;
   }
 
-  // strides of value v (seen through its view chain) over its own shape
-  bool view_strides(Val v, int32_t* storage, std::vector<int64_t>* shape, std::vector<int64_t>* stride) {
-    if (cls[v.node] != C_VIEW) {
-      const int32_t s = storage_of[v.node][v.slot];
-      if (s < 0) return bad(LT_ERR_UNSUPPORTED, "internal: operand has no storage");
-      *storage = s;
-      *shape = out_shape(v);
-      *stride = contiguous(*shape);
+  // A value as an address pattern: storage, shape, element strides, element offset.
+  struct Pattern {
+    int32_t storage = -1;
+    int64_t offset = 0;
+    std::vector<int64_t> shape, stride;
+  };
+
+  // The result of view node i (expand / reshape / permute / narrow) as a pattern over the pattern
+  // of its operand: views move no data.
+  bool apply_view(int32_t i, const Pattern& in, Pattern* out) {
+    const Node* n = nd[i];
+    const std::vector<int64_t> oshape = shape_of(i);
+    out->storage = in.storage;
+    out->offset = in.offset;
+    out->shape = oshape;
+    if (n->op == LT_OP_EXPAND) {
+      out->stride.assign(oshape.size(), 0);
+      const int off = (int)oshape.size() - (int)in.shape.size();
+      for (size_t d = 0; d < in.shape.size(); ++d) out->stride[d + off] = in.shape[d] == 1 ? 0 : in.stride[d];
       return true;
     }
-    std::vector<int64_t> ishape, istride;
-    if (!view_strides(rins[v.node][0], storage, &ishape, &istride)) return false;
-    const std::vector<int64_t> oshape = shape_of(v.node);
-    if (nd[v.node]->op == LT_OP_EXPAND) {
-      std::vector<int64_t> st(oshape.size(), 0);
-      const int off = (int)oshape.size() - (int)ishape.size();
-      for (size_t d = 0; d < ishape.size(); ++d) st[d + off] = ishape[d] == 1 ? 0 : istride[d];
-      *shape = oshape;
-      *stride = st;
+    if (n->op == LT_OP_PERMUTE) {
+      out->stride.resize(oshape.size());
+      for (size_t d = 0; d < oshape.size(); ++d) out->stride[d] = in.stride[n->attrs[d].v.i];
       return true;
     }
-    if (nd[v.node]->op == LT_OP_PERMUTE) {
-      std::vector<int64_t> st(oshape.size());
-      for (size_t d = 0; d < oshape.size(); ++d) st[d] = istride[nd[v.node]->attrs[d].v.i];
-      *shape = oshape;
-      *stride = st;
+    if (n->op == LT_OP_NARROW) {
+      int64_t axis = 0, start = 0;
+      for (int k = 0; k < n->n_attr; ++k) {
+        if (n->attrs[k].key == LT_ATTR_AXIS) axis = n->attrs[k].v.i;
+        if (n->attrs[k].key == LT_ATTR_START) start = n->attrs[k].v.i;
+      }
+      out->stride = in.stride;
+      out->offset += start * in.stride[axis];
       return true;
     }
-    // reshape: only of a dense row-major value
-    if (istride != contiguous(ishape)) return bad(LT_ERR_UNSUPPORTED, "reshape of a broadcast view has no lowering");
-    *shape = oshape;
-    *stride = contiguous(oshape);
+    // reshape: only of a dense row-major value (an offset is fine)
+    if (in.stride != contiguous(in.shape)) return bad(LT_ERR_UNSUPPORTED, "reshape of a strided or broadcast view has no lowering");
+    out->stride = contiguous(oshape);
     return true;
   }
 
-  // access of operand v (optionally through `perm`, the permutation of a permute member) from
-  // iteration space `space`
-  bool make_access(Val v, const std::vector<int64_t>& space, const int64_t* perm, Access* out) {
-    std::vector<int64_t> shape, stride;
-    if (!view_strides(v, &out->storage, &shape, &stride)) return false;
-    out->dtype = out_dtype(base(v));
-    if (perm) {
-      std::vector<int64_t> ps(shape.size()), pst(shape.size());
-      for (size_t d = 0; d < shape.size(); ++d) {
-        ps[d] = shape[perm[d]];
-        pst[d] = stride[perm[d]];
-      }
-      shape = ps;
-      stride = pst;
+  // pattern of value v, seen through its chain of view nodes
+  bool pattern_of(Val v, Pattern* out) {
+    if (cls[v.node] != C_VIEW) {
+      const int32_t s = storage_of[v.node][v.slot];
+      if (s < 0) return bad(LT_ERR_UNSUPPORTED, "internal: operand has no storage");
+      out->storage = s;
+      out->offset = 0;
+      out->shape = out_shape(v);
+      out->stride = contiguous(out->shape);
+      return true;
     }
+    Pattern in;
+    if (!pattern_of(rins[v.node][0], &in)) return false;
+    return apply_view(v.node, in, out);
+  }
+
+  // access of operand v from iteration space `space`; via >= 0: as seen through member `via`, a
+  // view op that is materialised by this region (a copy) and addresses its operand in its own way
+  bool make_access(Val v, const std::vector<int64_t>& space, int32_t via, Access* out) {
+    Pattern pat;
+    if (!pattern_of(v, &pat)) return false;
+    if (via >= 0) {
+      Pattern seen;
+      if (!apply_view(via, pat, &seen)) return false;
+      pat = seen;
+    }
+    out->storage = pat.storage;
+    out->offset = pat.offset;
+    out->dtype = out_dtype(base(v));
     out->stride.assign(space.size(), 0);
-    const int off = (int)space.size() - (int)shape.size();
+    const int off = (int)space.size() - (int)pat.shape.size();
     if (off < 0) return bad(LT_ERR_UNSUPPORTED, "internal: operand rank exceeds its iteration space");
-    for (size_t d = 0; d < shape.size(); ++d) out->stride[d + off] = (shape[d] == 1 && space[d + off] != 1) ? 0 : stride[d];
+    for (size_t d = 0; d < pat.shape.size(); ++d) out->stride[d + off] = (pat.shape[d] == 1 && space[d + off] != 1) ? 0 : pat.stride[d];
     for (size_t d = 0; d < space.size(); ++d)
       if (space[d] == 1) out->stride[d] = 0;
     return true;
@@ -601,7 +642,8 @@ struct Lowering {
 
   struct ProgBuild {
     ltk::EwProg prog{};
-    std::vector<std::pair<uint32_t, int32_t>> in_storage;    // (input index, storage)
+    struct In { uint32_t first; int32_t second; int64_t byte_offset; };
+    std::vector<In> in_storage;                               // (input index, storage, offset into it)
     std::vector<std::pair<uint32_t, int32_t>> out_storage;   // (output index, storage)
     struct SP { uint32_t index; int32_t scalar; bool recip; };
     std::vector<SP> scal_patch;
@@ -651,9 +693,9 @@ struct Lowering {
       if (m == anchor.node) continue;
       for (Val v : rins[m]) {
         if (in_members(v.node) || is_imm(v) || v == anchor) continue;
-        // a permute member, and a reshape member that is materialised (a root view), address their
-        // operand in their own way: through a private input
-        const bool perm = nd[m]->op == LT_OP_PERMUTE || nd[m]->op == LT_OP_RESHAPE;
+        // a view op that this region materialises (a permutation, or an expand / reshape / narrow
+        // that is itself a result) addresses its operand in its own way: through a private input
+        const bool perm = nd[m]->op == LT_OP_PERMUTE || nd[m]->op == LT_OP_RESHAPE || nd[m]->op == LT_OP_NARROW;
         bool have = false;
         for (size_t q = 0; q < input_vals.size(); ++q) have |= (input_vals[q] == v && input_perm[q] < 0);
         if (perm || !have) {
@@ -664,34 +706,11 @@ struct Lowering {
     }
     if ((int)input_vals.size() > ltk::kMaxIn) return bad(LT_ERR_UNSUPPORTED, "internal: region has too many inputs");
     p.n_in = (uint32_t)input_vals.size();
-    // permute members load their operand through a private, permuted input
     std::vector<int> permute_input(N, -1);
     for (size_t k = 0; k < input_vals.size(); ++k) {
       Access acc;
-      int64_t perm[LT_MAX_RANK];
-      const int64_t* pp = nullptr;
-      bool flat = false;   // a reshape member reads its (dense) operand by flat index
-      if (input_perm[k] >= 0) {
-        const int32_t m = input_perm[k];
-        permute_input[m] = (int)k;
-        if (nd[m]->op == LT_OP_PERMUTE) {
-          for (int a = 0; a < nd[m]->n_attr; ++a) perm[a] = nd[m]->attrs[a].v.i;
-          pp = perm;
-        } else {
-          flat = true;
-        }
-      }
-      if (flat) {
-        std::vector<int64_t> ishape, istride;
-        if (!view_strides(input_vals[k], &acc.storage, &ishape, &istride)) return false;
-        if (istride != contiguous(ishape)) return bad(LT_ERR_UNSUPPORTED, "reshape of a broadcast view has no lowering");
-        acc.dtype = out_dtype(base(input_vals[k]));
-        acc.stride = contiguous(space);
-        for (size_t d = 0; d < space.size(); ++d)
-          if (space[d] == 1) acc.stride[d] = 0;
-      } else if (!make_access(input_vals[k], space, pp, &acc)) {
-        return false;
-      }
+      if (input_perm[k] >= 0) permute_input[input_perm[k]] = (int)k;
+      if (!make_access(input_vals[k], space, input_perm[k], &acc)) return false;
       ltk::EwIn& in = p.in[k];
       in.ptr = nullptr;
       in.dtype = acc.dtype;
@@ -724,17 +743,19 @@ struct Lowering {
           in.stride[d] = d < off ? 0 : acc.stride[d - off];
         }
       }
+      // (a window that starts off a 16-byte boundary is read element by element)
+      const bool aligned = (acc.offset * (int64_t)dtype_size(acc.dtype)) % 16 == 0;
       in.fetch = ltk::kFetchSlow;
       if (in.mode == ltk::kScalar) in.fetch = ltk::kFetchBcast;
-      else if (in.mode == ltk::kFull && p.full_vec_ok) in.fetch = ltk::kFetchVec4;
-      else if (in.mode == ltk::kRowVec && p.vec_ok) in.fetch = ltk::kFetchVec4;
+      else if (in.mode == ltk::kFull && p.full_vec_ok && aligned) in.fetch = ltk::kFetchVec4;
+      else if (in.mode == ltk::kRowVec && p.vec_ok && aligned) in.fetch = ltk::kFetchVec4;
       else if (in.mode == ltk::kColVec && p.vec_ok) in.fetch = ltk::kFetchBcast;
       if (in.mode == ltk::kRowVec || in.mode == ltk::kColVec) p.needs_divmod = 1;
       if (in.mode != ltk::kStrided && space.size() <= 4) {
         const int off = 4 - (int)space.size();
         for (int d = 0; d < 4; ++d) p.dims[d] = d < off ? 1u : (uint32_t)space[d - off];
       }
-      pb->in_storage.push_back({(uint32_t)k, acc.storage});
+      pb->in_storage.push_back({(uint32_t)k, acc.storage, acc.offset * (int64_t)dtype_size(acc.dtype)});
       // algorithmic bytes: the un-broadcast operand is read once
       int64_t elems = 1;
       for (size_t d = 0; d < space.size(); ++d)
@@ -859,7 +880,7 @@ struct Lowering {
         case LT_OP_SQUARE: op = ltk::kSquare; break;
         case LT_OP_SIGMOID: op = ltk::kSigmoid; break;
         case LT_OP_CAST: op = n->dtype == LT_BF16 ? ltk::kRoundBf16 : ltk::kMov; break;
-        case LT_OP_EXPAND: case LT_OP_RESHAPE: case LT_OP_PERMUTE: op = ltk::kMov; break;
+        case LT_OP_EXPAND: case LT_OP_RESHAPE: case LT_OP_PERMUTE: case LT_OP_NARROW: op = ltk::kMov; break;
         case LT_OP_ADD: op = o.size() == 3 ? ltk::kFma : ltk::kAdd; rop = ltk::kAdd; break;
         case LT_OP_SUB: op = ltk::kSub; rop = ltk::kRsub; break;
         case LT_OP_MUL: op = rop = ltk::kMul; break;
@@ -950,7 +971,7 @@ struct Lowering {
   // append one program's patches to the plan; `offset` = byte offset of the EwProg inside the args
   void add_prog_patches(uint32_t launch, size_t offset, const ProgBuild& pb) {
     for (auto& is : pb.in_storage)
-      plan->ptr_patches.push_back(PtrPatch{launch, (uint32_t)(offset + offsetof(ltk::EwProg, in) + is.first * sizeof(ltk::EwIn) + offsetof(ltk::EwIn, ptr)), is.second, 0});
+      plan->ptr_patches.push_back(PtrPatch{launch, (uint32_t)(offset + offsetof(ltk::EwProg, in) + is.first * sizeof(ltk::EwIn) + offsetof(ltk::EwIn, ptr)), is.second, is.byte_offset});
     for (auto& os : pb.out_storage)
       plan->ptr_patches.push_back(PtrPatch{launch, (uint32_t)(offset + offsetof(ltk::EwProg, out) + os.first * sizeof(ltk::EwOut) + offsetof(ltk::EwOut, ptr)), os.second, 0, 1});
     for (auto& sp : pb.scal_patch)
@@ -984,14 +1005,17 @@ struct Lowering {
   struct MatView {
     int32_t storage;
     uint8_t dtype;
-    int64_t rows, cols, s_row, s_col;
+    int64_t rows, cols, s_row, s_col, byte_offset;
     std::vector<int64_t> lead, s_lead;
   };
 
   bool operand_gemm(Val v, bool trans, MatView* mv) {
-    std::vector<int64_t> shape, stride;
-    if (!view_strides(v, &mv->storage, &shape, &stride)) return false;
+    Pattern pat;
+    if (!pattern_of(v, &pat)) return false;
+    const std::vector<int64_t>&shape = pat.shape, &stride = pat.stride;
+    mv->storage = pat.storage;
     mv->dtype = out_dtype(base(v));
+    mv->byte_offset = pat.offset * (int64_t)dtype_size(mv->dtype);
     const size_t r = shape.size();
     mv->rows = trans ? shape[r - 1] : shape[r - 2];
     mv->cols = trans ? shape[r - 2] : shape[r - 1];
@@ -1124,6 +1148,7 @@ struct Lowering {
       else post_m.push_back(m);
     }
     if (r->kind == C_MM) return emit_gemm(k, r, post_m, out);
+    if (r->kind == C_SLICE) return emit_slice(k, r);
     if (!plain_reduce(an->op)) return emit_row_op(k, r, out);
     // ---- plain reduction
     const Val src = rins[a][0];
@@ -1219,7 +1244,8 @@ struct Lowering {
     ltk::EwProg& p = pb->prog;
     p = ltk::EwProg{};
     Access acc;
-    if (!make_access(src, space, nullptr, &acc)) return false;
+    if (!make_access(src, space, -1, &acc)) return false;
+    if (acc.offset != 0) return bad(LT_ERR_UNSUPPORTED, "reduction of a window has no lowering");
     // reuse build_prog's classification by building a one-member copy program is overkill:
     // a reduction operand that is not computed in the region is always read in full
     const std::vector<int64_t> cs = contiguous(space);
@@ -1238,9 +1264,61 @@ struct Lowering {
     p.anchor_slot = 0;
     p.n_slots = 1;
     for (int d = 0; d < 4; ++d) p.dims[d] = 1;
-    pb->in_storage.push_back({0u, acc.storage});
+    pb->in_storage.push_back({0u, acc.storage, acc.offset * (int64_t)dtype_size(acc.dtype)});
     pb->bytes += p.n * dtype_size(acc.dtype);
     finish_flags(&p);
+    return true;
+  }
+
+  // Window update: base and update must be dense in memory; written in place when the result
+  // replaces the base's own (donated) buffer.
+  bool emit_slice(int k, Region* r) {
+    const int32_t a = r->anchor;
+    const Node* an = nd[a];
+    if (r->members.size() != 1) return bad(LT_ERR_UNSUPPORTED, "internal: window update with fused members");
+    const int launch = (int)plan->launches.size();
+    int64_t axis = 0, start = 0;
+    for (int i = 0; i < an->n_attr; ++i) {
+      if (an->attrs[i].key == LT_ATTR_AXIS) axis = an->attrs[i].v.i;
+      if (an->attrs[i].key == LT_ATTR_START) start = an->attrs[i].v.i;
+    }
+    const std::vector<int64_t> bs = shape_of(a), us = out_shape(rins[a][1]);
+    Access ab, au;
+    if (!make_access(rins[a][0], bs, -1, &ab) || !make_access(rins[a][1], us, -1, &au)) return false;
+    auto dense = [&](const Access& acc, const std::vector<int64_t>& shp) {
+      const std::vector<int64_t> cs = contiguous(shp);
+      for (size_t d = 0; d < shp.size(); ++d)
+        if (shp[d] != 1 && acc.stride[d] != cs[d]) return false;
+      return true;
+    };
+    if (!dense(ab, bs) || !dense(au, us)) return bad(LT_ERR_UNSUPPORTED, "window update of a strided or broadcast operand has no lowering");
+    const int32_t so = storage_of[a][0];
+    if (so < 0) return bad(LT_ERR_UNSUPPORTED, "internal: window update without storage");
+    const bool in_place = plan->storages[so].param >= 0 && plan->storages[ab.storage].param == plan->storages[so].param && ab.offset == 0;
+    ltk::SliceArgs args{};
+    uint64_t outer = 1, inner = 1;
+    for (int64_t d = 0; d < axis; ++d) outer *= (uint64_t)bs[d];
+    for (size_t d = (size_t)axis + 1; d < bs.size(); ++d) inner *= (uint64_t)bs[d];
+    args.dim = (uint64_t)bs[axis];
+    args.inner = inner;
+    args.start = (uint64_t)start;
+    args.len = (uint64_t)us[axis];
+    args.elem_bytes = (uint32_t)dtype_size(an->dtype);
+    args.window_only = in_place ? 1u : 0u;
+    args.n = in_place ? outer * args.len * inner : outer * args.dim * inner;
+    Launch l = make_launch(L_SLICE, k, args);
+    l.grid_x = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>((args.n + 255) / 256, 256 * 64));
+    const uint64_t win_bytes = outer * args.len * inner * args.elem_bytes, all_bytes = outer * args.dim * inner * args.elem_bytes;
+    l.bytes = in_place ? 2 * win_bytes : 2 * all_bytes;
+    plan->launches.push_back(std::move(l));
+    if (!in_place) {
+      plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)offsetof(ltk::SliceArgs, base), ab.storage, ab.offset * (int64_t)args.elem_bytes});
+      touch(ab.storage, launch);
+    }
+    plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)offsetof(ltk::SliceArgs, upd), au.storage, au.offset * (int64_t)args.elem_bytes});
+    plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)offsetof(ltk::SliceArgs, out), so, 0, 1});
+    touch(au.storage, launch);
+    touch(so, launch);
     return true;
   }
 
@@ -1271,7 +1349,8 @@ struct Lowering {
     for (size_t i = 0; i < n_arr; ++i) {
       Access acc;
       const std::vector<int64_t> vs = out_shape(rins[a][i]);
-      if (!make_access(rins[a][i], vs, nullptr, &acc)) return false;
+      if (!make_access(rins[a][i], vs, -1, &acc)) return false;
+      if (acc.offset != 0) return bad(LT_ERR_UNSUPPORTED, "row operator on a window has no lowering");
       if (acc.stride != contiguous(vs) && count(vs) > 1) {
         bool dense = true;
         const std::vector<int64_t> cs = contiguous(vs);
@@ -1462,8 +1541,8 @@ struct Lowering {
       l.flops = 2ull * (uint64_t)batch * m * n * kk;
       l.bytes = (uint64_t)batch * ((uint64_t)m * kk + (uint64_t)kk * n) * dtype_size(A.dtype);
       plan->launches.push_back(std::move(l));
-      plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)(offsetof(ltk::GemmArgs, a) + offsetof(ltk::GemmOperand, ptr)), A.storage, 0});
-      plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)(offsetof(ltk::GemmArgs, b) + offsetof(ltk::GemmOperand, ptr)), B.storage, 0});
+      plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)(offsetof(ltk::GemmArgs, a) + offsetof(ltk::GemmOperand, ptr)), A.storage, A.byte_offset});
+      plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)(offsetof(ltk::GemmArgs, b) + offsetof(ltk::GemmOperand, ptr)), B.storage, B.byte_offset});
       plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)offsetof(ltk::GemmArgs, split_ws), ws_storage, 0, 1});
       touch(A.storage, launch);
       touch(B.storage, launch);
@@ -1484,8 +1563,8 @@ struct Lowering {
     l.flops = 2ull * (uint64_t)batch * m * n * kk;
     l.bytes = post.bytes + (uint64_t)batch * ((uint64_t)m * kk + (uint64_t)kk * n) * dtype_size(A.dtype);
     plan->launches.push_back(std::move(l));
-    plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)(offsetof(ltk::GemmArgs, a) + offsetof(ltk::GemmOperand, ptr)), A.storage, 0});
-    plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)(offsetof(ltk::GemmArgs, b) + offsetof(ltk::GemmOperand, ptr)), B.storage, 0});
+    plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)(offsetof(ltk::GemmArgs, a) + offsetof(ltk::GemmOperand, ptr)), A.storage, A.byte_offset});
+    plan->ptr_patches.push_back(PtrPatch{(uint32_t)launch, (uint32_t)(offsetof(ltk::GemmArgs, b) + offsetof(ltk::GemmOperand, ptr)), B.storage, B.byte_offset});
     touch(A.storage, launch);
     touch(B.storage, launch);
     add_prog_patches(launch, offsetof(ltk::GemmArgs, post), post);

@@ -17,12 +17,12 @@ OPCODES = {
     "neg": 16, "abs": 17, "exp": 18, "log": 19, "tanh": 20, "sqrt": 21, "rsqrt": 22, "recip": 23,
     "relu": 24, "gelu": 25, "square": 26, "cast": 27, "sigmoid": 28,
     "add": 32, "sub": 33, "mul": 34, "div": 35, "maximum": 36, "minimum": 37, "relu_grad": 38, "gelu_grad": 39,
-    "expand": 48, "reshape": 49, "permute": 50,
+    "expand": 48, "reshape": 49, "permute": 50, "narrow": 51, "slice_update": 52,
     "sum": 64, "amax": 65, "mean": 66,
     "softmax": 80, "softmax_grad": 81, "layer_norm": 82, "layer_norm_grad": 83, "xent": 84, "xent_grad": 85,
     "matmul": 96,
 }
-ATTR_VALUE, ATTR_DTYPE, ATTR_AXIS, ATTR_EPS, ATTR_TRANS_A, ATTR_TRANS_B, ATTR_DIM0 = 1, 2, 3, 4, 5, 6, 16
+ATTR_VALUE, ATTR_DTYPE, ATTR_AXIS, ATTR_EPS, ATTR_TRANS_A, ATTR_TRANS_B, ATTR_START, ATTR_LENGTH, ATTR_DIM0 = 1, 2, 3, 4, 5, 6, 7, 8, 16
 LT_DONATABLE = 1
 MAX_RANK = 6
 
@@ -88,6 +88,7 @@ def load_library():
         "lt_scalar": [P, i32, C.c_double, C.POINTER(u64)],
         "lt_op": [P, C.c_uint16, C.POINTER(u64), i32, C.POINTER(lt_attr), i32, C.POINTER(u64), i32],
         "lt_assign": [P, u64, u64],
+        "lt_view": [P, u64, C.c_uint16, C.POINTER(lt_attr), i32, C.POINTER(u64)],
         "lt_release": [P, u64],
         "lt_barrier": [P, i32, C.POINTER(BarrierInfo)],
         "lt_barrier_static": [P, i32, C.POINTER(BarrierInfo)],
@@ -167,6 +168,7 @@ def _plain(name, arity):
 
 
 _CAST, _EXPAND, _RESHAPE, _PERMUTE = OPCODES["cast"], OPCODES["expand"], OPCODES["reshape"], OPCODES["permute"]
+_NARROW, _SLICE_UPDATE = OPCODES["narrow"], OPCODES["slice_update"]
 _SUM, _AMAX, _MEAN = OPCODES["sum"], OPCODES["amax"], OPCODES["mean"]
 _LAYER_NORM, _MATMUL = OPCODES["layer_norm"], OPCODES["matmul"]
 
@@ -348,6 +350,30 @@ class Context:
                 attrs.append((ATTR_DTYPE, DTYPES[dtype]))
             at = self._encode(key, attrs)
         return _rec_op(self, self._hv, _MATMUL, (a, b), at[0], at[1], 1)
+
+    def narrow(self, x, axis, start, length):
+        key = (_NARROW, int(axis), int(start), int(length))
+        at = self._attrs.get(key) or self._encode(key, [(ATTR_AXIS, key[1]), (ATTR_START, key[2]), (ATTR_LENGTH, key[3])])
+        return _rec_op(self, self._hv, _NARROW, (x,), at[0], at[1], 1)
+
+    def slice_update(self, base, update, axis, start):
+        key = (_SLICE_UPDATE, int(axis), int(start))
+        at = self._attrs.get(key) or self._encode(key, [(ATTR_AXIS, key[1]), (ATTR_START, key[2])])
+        return _rec_op(self, self._hv, _SLICE_UPDATE, (base, update), at[0], at[1], 1)
+
+    # views (lt_view): tensors that share storage with their base as far as a program can tell
+    def _view(self, code, x, attrs):
+        key = ("view", code) + tuple(attrs)
+        at = self._attrs.get(key) or self._encode(key, list(attrs))
+        out = C.c_uint64()
+        self._check(self._lib.lt_view(self._h, x.tid, code, C.cast(at[0], C.POINTER(lt_attr)), at[1], C.byref(out)))
+        return Tensor(self, out.value)
+
+    def view_permute(self, x, dims): return self._view(_PERMUTE, x, [(ATTR_DIM0 + i, int(d)) for i, d in enumerate(dims)])
+    def view_reshape(self, x, size): return self._view(_RESHAPE, x, [(ATTR_DIM0 + i, int(d)) for i, d in enumerate(size)])
+
+    def view_narrow(self, x, axis, start, length):
+        return self._view(_NARROW, x, [(ATTR_AXIS, int(axis)), (ATTR_START, int(start)), (ATTR_LENGTH, int(length))])
 
     def assign(self, dst: Tensor, src: Tensor):
         _ltrec.assign(self._hv, dst, src)   # (what is known of src's type and shape becomes dst's)

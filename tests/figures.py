@@ -26,12 +26,12 @@ def fig2(B, mk):
 
 
 def fig3(B, mk):
-    """x of shape (2,3,4); v = x.permute(1,2,0).add_(42): the forward sequence
-    recomputes the view, the backward sequence applies the inverse permutation
-    to rebuild x.  Only x stays alive."""
+    """x of shape (2,3,4); v = x.permute(1,2,0).add_(42): v is a view of x, and the in-place add
+    on it makes the recorder write the forward sequence (the view's new value) and the backward
+    sequence (x rebuilt through the inverse permutation) by itself.  Only x stays alive."""
     x = mk((2, 3, 4))
+    v = B.view_permute(x, (1, 2, 0))
     other = B.mul(B.scalar(42, dtype="s64"), B.scalar(1, dtype="s64"))
-    v = B.add(B.permute(x, (1, 2, 0)), other)
-    B.assign(x, B.permute(v, (2, 0, 1)))
+    B.assign(v, B.add(v, other))
     del v, other
     return [x], []

@@ -33,7 +33,7 @@ import struct
 
 DEVICE_DATA, SCALAR_PARAM, CONSTANT = 1, 2, 3
 ADD, SUB, MUL, DIV = 32, 33, 34, 35
-EXPAND, RESHAPE, PERMUTE = 48, 49, 50
+EXPAND, RESHAPE, PERMUTE, NARROW, SLICE_UPDATE = 48, 49, 50, 51, 52
 SUM, AMAX, MEAN = 64, 65, 66
 LAYER_NORM = 82
 MATMUL = 96
@@ -188,7 +188,7 @@ def check_plan(key: bytes, n_nodes: int, plan_text: str):
             produced[v] = k
 
     def is_view_node(i):
-        return i not in region_of and nodes[i].op in (EXPAND, RESHAPE, PERMUTE)
+        return i not in region_of and nodes[i].op in (EXPAND, RESHAPE, PERMUTE, NARROW)
 
     def base(v):
         while is_view_node(v[0]):
@@ -208,7 +208,7 @@ def check_plan(key: bytes, n_nodes: int, plan_text: str):
         n = nodes[i]
         if n.op in (DEVICE_DATA, SCALAR_PARAM, CONSTANT) or i in region_of:
             continue
-        need(n.op in (EXPAND, RESHAPE, PERMUTE), f"live node {i} (op {n.op}) is computed by no region")
+        need(n.op in (EXPAND, RESHAPE, PERMUTE, NARROW), f"live node {i} (op {n.op}) is computed by no region")
         if n.op == PERMUTE:
             users = [j for j in live if any(v[0] == i for v in operands(j))]
             need(users and all(nodes[j].op == MATMUL for j in users), f"permutation {i} outside every region feeds a non-contraction")
@@ -260,7 +260,7 @@ def check_plan(key: bytes, n_nodes: int, plan_text: str):
             shapes = {nodes[m].shape for m in r["members"]}
             need(len(shapes) == 1, f"R{k}: elementwise members of different shapes {shapes}")
             for m in r["members"]:
-                need(nodes[m].op < SUM, f"R{k}: member {m} is not elementwise")
+                need(nodes[m].op < SUM and nodes[m].op != SLICE_UPDATE, f"R{k}: member {m} is not elementwise")
         else:
             need(a in members, f"R{k}: anchor {a} is not a member")
             an = nodes[a]
@@ -273,8 +273,10 @@ def check_plan(key: bytes, n_nodes: int, plan_text: str):
                         stack.append(v[0])
             after = members - before - {a}
             for m in members - {a}:
-                need(nodes[m].op < SUM, f"R{k}: member {m} next to the anchor is not elementwise")
-            if r["kind"] == "MM":
+                need(nodes[m].op < SUM and nodes[m].op != SLICE_UPDATE, f"R{k}: member {m} next to the anchor is not elementwise")
+            if r["kind"] == "SLICE":
+                need(an.op == SLICE_UPDATE and len(members) == 1, f"R{k}: a window update stands alone")
+            elif r["kind"] == "MM":
                 need(an.op == MATMUL and not before, f"R{k}: contraction region with a prologue")
                 perms = [m for m in after if nodes[m].op == PERMUTE]
                 if perms:
@@ -318,7 +320,9 @@ def check_plan(key: bytes, n_nodes: int, plan_text: str):
                 for w in operands(m):
                     if w[0] in members or is_immediate(w) or not is_donor(base(w)):
                         continue
-                    need(w == (leaf, 0) and m != a and nodes[m].op not in (PERMUTE, EXPAND, RESHAPE) and nodes[m].shape == nodes[leaf].shape,
+                    if m == a and nodes[m].op == SLICE_UPDATE and w == (leaf, 0) and w == operands(m)[0] and not is_donor(base(operands(m)[1])):
+                        continue        # a window update rewrites part of its own base: the rest stays as it is
+                    need(w == (leaf, 0) and m != a and nodes[m].op not in (PERMUTE, EXPAND, RESHAPE, NARROW) and nodes[m].shape == nodes[leaf].shape,
                          f"R{k}: parameter {p} is overwritten by a region that reads it out of position (member {m})")
     claimed = [p for r in regions for (_, p) in r["inplace"]]
     need(len(claimed) == len(set(claimed)), "a parameter is written in place twice")

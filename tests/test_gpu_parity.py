@@ -394,6 +394,59 @@ def test_fused_and_unfused_plans_agree():
     c.close()
 
 
+@pytest.mark.parametrize("donatable", [True, False])
+def test_in_place_updates_through_views(ctx, donatable):
+    """Section 4.4: views share storage with their base as far as a program can tell.  The library
+    records forward and backward sequences; the oracle really shares memory (NumPy views)."""
+    E = Eager()
+    r = rng(31)
+    x, y = r.standard_normal((2, 3, 4), dtype=np.float32), r.standard_normal((6, 4), dtype=np.float32)
+    gx = ctx.tensor(x.copy(), donatable=donatable)
+    got = programs.views_program(ctx, gx, ctx.tensor(y))
+    info = ctx.barrier()
+    ref = programs.views_program(E, E.tensor(x.copy()), E.tensor(y))
+    for g, rr, what in zip(got, ref, ("x", "v", "w", "s")):
+        check(ctx, E, g, rr, TOL32, what)
+    # second step on the materialised tensors: views are derived again from the new base
+    got2 = programs.views_program(ctx, got[0], ctx.tensor(y))
+    ref2 = programs.views_program(E, ref[0], E.tensor(y))
+    for g, rr, what in zip(got2 + got[1:3], ref2 + ref[1:3], ("x", "v", "w", "s", "old v", "old w")):
+        check(ctx, E, g, rr, TOL32, what + " (step 2)")
+
+
+def test_windows_of_larger_tensors(ctx):
+    """narrow as addressing (elementwise consumers, a contraction operand), as a copy (a result, a
+    reduction operand), and the window update in place and out of place, on sizes that span tiles;
+    bf16 too."""
+    E = Eager()
+    r = rng(32)
+    a = r.standard_normal((300, 520), dtype=np.float32)
+    w = r.standard_normal((128, 64), dtype=np.float32)
+    u = r.standard_normal((300, 100), dtype=np.float32)
+
+    def prog(B, a, w, u):
+        left = B.narrow(a, 1, 4, 128)                   # [300, 128] at a 16-byte aligned offset
+        odd = B.narrow(a, 1, 3, 128)                    # ... and at an unaligned one
+        rows = B.narrow(a, 0, 7, 100)                   # a window of whole rows: dense
+        e = B.add(B.tanh(left), odd)
+        mm = B.matmul(left, w)
+        red = B.sum(rows, axis=1)
+        upd = B.slice_update(a, u, 1, 33)               # out of place: a stays as it is
+        return e, mm, red, upd, rows
+    got = prog(ctx, ctx.tensor(a), ctx.tensor(w), ctx.tensor(u))
+    ref = prog(E, E.tensor(a), E.tensor(w), E.tensor(u))
+    for g, rr, what in zip(got, ref, ("e", "mm", "red", "upd", "rows")):
+        check(ctx, E, g, rr, TOL32, what)
+    hb = round_to_bf16(r.standard_normal((64, 1024), dtype=np.float32))
+    gh, rh = ctx.tensor(hb.copy(), dtype="bf16", donatable=True), E.tensor(hb.copy(), dtype="bf16")
+    for B, t in ((ctx, gh), (E, rh)):
+        win = B.view_narrow(t, 1, 256, 512)
+        B.assign(win, B.mul(win, 0.5))
+    ctx.barrier()
+    assert "->p" in ctx.dump_plan() and " SLICE " in ctx.dump_plan()      # the window is written in place
+    check(ctx, E, gh, rh, TOL16, "bf16 window in place")
+
+
 def test_a_leaf_dropped_before_the_barrier_keeps_its_memory(ctx):
     """The trace names a leaf's device memory until the barrier has run; the binding keeps the owner
     of that memory alive that long even when the program drops its handle first."""

@@ -297,6 +297,44 @@ def test_fusion_switch_gives_one_region_per_op_and_valid_plans():
     del out
 
 
+def test_views_forward_and_backward_sequences():
+    """In-place updates through permute / narrow / reshape views and a view of a view: the library's
+    recorder and the oracle's write the same forward and backward sequences (same key bytes), the
+    plans agree and pass the independent checker; a second step hits the cache."""
+    from plan_check import check_plan
+    P = Pair()
+    x, y = P.tensor((2, 3, 4), donatable=True), P.tensor((6, 4))
+    for step in range(2):
+        outs = P.run(programs.views_program, x, y)
+        info, ref = P.barrier()
+        assert info.cache_hit == (step > 0)
+        check_plan(ref["bytes"], ref["n_nodes"], ref["plan"])
+        assert " SLICE " in ref["plan"]
+        del outs
+    # a base released while a view of it is alive stays evaluated; the view keeps working
+    ctx = Context()
+    b = ctx.tensor(np.zeros((4, 4), np.float32))
+    v = ctx.view_permute(b, (1, 0))
+    ctx.assign(v, ctx.add(v, 1.0))
+    live = ctx.stats().live_tensors
+    del b
+    assert ctx.stats().live_tensors == live                  # hidden, not gone
+    assert ctx.barrier().n_roots == 2                        # the view and its (hidden) base
+    ctx.assign(v, ctx.mul(v, 2.0))
+    assert ctx.barrier().n_roots == 2
+    del v
+    assert ctx.stats().live_tensors == live - 2
+    # a view only takes values of its own shape
+    c = ctx.tensor(np.zeros((4, 4), np.float32))
+    w = ctx.view_narrow(c, 0, 1, 2)
+    with pytest.raises(LtError) as e:
+        ctx.assign(w, c)
+    assert e.value.status == 3
+    with pytest.raises(LtError) as e:
+        ctx.view_narrow(c, 1, 3, 2)
+    assert e.value.status == 3
+
+
 def test_error_paths_leave_state_untouched():
     ctx = Context()
     a, b = ctx.tensor(np.zeros((4, 8), np.float32)), ctx.tensor(np.zeros((5, 8), np.float32))

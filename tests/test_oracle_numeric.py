@@ -402,3 +402,27 @@ def test_c3_step_gradients_by_finite_differences():
                 assert abs(num) <= 1e-7 and abs(g[idx]) <= 1e-9 * max(np.max(np.abs(grads["bq"])), 1e-30) + 1e-12
             else:
                 assert abs(num - g[idx]) <= 1e-6 * scale, (k, idx, num, g[idx])
+
+
+def test_views_share_storage_and_window_ops():
+    """narrow / slice_update against hand-typed windows, and the shared-storage semantics of views:
+    an in-place update through any view shows in the base and in every other view."""
+    E = Eager()
+    iota = np.arange(24, dtype=np.float32).reshape(2, 3, 4)
+    x = E.tensor(iota.copy())
+    assert np.array_equal(f(E, E.narrow(x, 1, 1, 2)), [[[4, 5, 6, 7], [8, 9, 10, 11]], [[16, 17, 18, 19], [20, 21, 22, 23]]])
+    assert np.array_equal(f(E, E.narrow(x, 2, 3, 1))[..., 0], [[3, 7, 11], [15, 19, 23]])
+    up = f(E, E.slice_update(x, E.tensor(np.full((2, 1, 4), -1.0, np.float32)), 1, 2))
+    assert np.array_equal(up[:, 2], -np.ones((2, 4))) and np.array_equal(up[:, :2], iota[:, :2])
+    assert np.array_equal(f(E, x), iota)                         # functional forms leave their operands alone
+    v = E.view_permute(x, (1, 2, 0))                             # figure 3's view
+    E.assign(v, E.add(v, 42.0))
+    assert np.array_equal(f(E, x), iota + 42) and f(E, v)[1, 2, 0] == iota[0, 1, 2] + 42
+    w = E.view_narrow(x, 1, 1, 2)
+    E.assign(w, E.mul(w, 2.0))
+    want = iota + 42
+    want[:, 1:3] *= 2
+    assert np.array_equal(f(E, x), want) and np.array_equal(f(E, v), want.transpose(1, 2, 0))   # the sibling view sees it
+    r = E.view_reshape(x, (6, 4))
+    E.assign(x, E.neg(x))                                        # updating the base shows in its views
+    assert np.array_equal(f(E, r), -want.reshape(6, 4)) and np.array_equal(f(E, w), -want[:, 1:3])

@@ -81,7 +81,7 @@ def random_trace(seed):
         unary = ["neg", "abs", "exp", "tanh", "relu", "gelu", "square", "sigmoid"]
         binary = ["add", "sub", "mul", "div", "maximum", "minimum"]
         for _ in range(int(rg.integers(4, 30))):
-            kind = int(rg.integers(0, 14))
+            kind = int(rg.integers(0, 17))
             pick = lambda: pool[int(rg.integers(0, len(pool)))]
             try:
                 if kind < 3:
@@ -123,6 +123,25 @@ def random_trace(seed):
                         r = B.matmul(a, a, trans_b=True)
                     else:
                         continue
+                elif kind == 13:
+                    a = pick()
+                    if a.shape != (8, 16):
+                        continue
+                    r = B.narrow(a, 1, int(rg.integers(0, 3)) * 4, 8) if rg.integers(0, 2) else B.narrow(a, 0, 2, 4)
+                elif kind == 14:
+                    a, u = pick(), pick()
+                    if a.shape != (8, 16) or u.shape != (8, 1):
+                        continue
+                    r = B.slice_update(a, u, 1, int(rg.integers(0, 16)))
+                elif kind == 15:
+                    a = pick()                      # an in-place update through a view of one of the inputs
+                    dst = base[int(rg.integers(0, 3))]
+                    if a.shape != (8, 16):
+                        continue
+                    v = B.view_narrow(dst, 0, 2, 4) if rg.integers(0, 2) else B.view_permute(dst, (1, 0))
+                    B.assign(v, B.narrow(a, 0, 0, 4) if v.shape == (4, 16) else B.permute(a, (1, 0)))
+                    del v
+                    continue
                 else:
                     dst, src = base[int(rg.integers(0, len(base)))], pick()
                     if dst.shape != src.shape or dst is src:
@@ -142,7 +161,7 @@ def random_trace(seed):
     return build
 
 
-@pytest.mark.parametrize("seed", range(60))
+@pytest.mark.parametrize("seed", range(120))
 def test_random_traces_give_valid_plans(seed):
     ctx = Context()
     keep = random_trace(seed)(ctx, lambda shape, dtype="f32", donatable=False: ctx.tensor(np.zeros(shape, np.float32), donatable=donatable))

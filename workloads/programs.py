@@ -162,3 +162,20 @@ def c3_step(B, x, dy, P, M, V, heads, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8,
         B.assign(m, m_new)
         B.assign(v, v_new)
     return y, dx
+
+
+def views_program(B, x, y):
+    """In-place updates through views (section 4.4 of the paper).  x: [2, 3, 4], y: [6, 4], both
+    fp32.  Returns (x, v, w, s): the base, two of its views and a value read from a view after
+    other views were updated."""
+    v = B.view_permute(x, (1, 2, 0))                  # the view of the paper's figure 3 ...
+    B.assign(v, B.add(v, 42.0))                       # ... and its in-place add
+    w = B.view_narrow(x, 1, 1, 2)                     # a window along the middle axis
+    B.assign(w, B.mul(w, 2.0))                        # the sibling view v must see this
+    r = B.view_reshape(x, (6, 4))
+    B.assign(r, B.sub(r, y))
+    chain = B.view_narrow(B.view_reshape(x, (6, 4)), 0, 2, 3)   # a view of a view
+    B.assign(chain, B.neg(chain))
+    s = B.add(B.exp(B.mul(v, 0.01)), B.narrow(v, 2, 0, 1))      # reads: a view, and a window of it as a broadcast operand
+    B.assign(x, B.mul(x, 0.5))                        # updating the base shows in every view
+    return x, v, w, s

@@ -103,6 +103,7 @@ typedef struct {
   uint64_t ns_lowering_total;
   uint64_t arena_bytes_in_use, arena_bytes_peak;
   uint64_t live_tensors;
+  uint64_t fallback_ops;   /* ops that went through the registered fallback (section 4.5) */
 } lt_stats_t;
 
 /*
@@ -269,6 +270,34 @@ lt_status lt_last_launches(lt_ctx* ctx, lt_launch_record* out, int cap, int* n);
  * Errors: LT_ERR_ARG (n out of range).
  */
 lt_status lt_set_streams(lt_ctx* ctx, int n);
+
+/*
+ * Ops without a lowering (section 4.5: every tensor op must give a correct program, if a slower
+ * one).  A registered fallback makes lt_op handle such an op -- an opcode at or above
+ * LT_OP_CUSTOM, or a reduction over an axis pattern the kernels do not cover (a middle axis; axis 0
+ * of a tensor of rank > 2) -- in the paper's three steps, at the moment it is recorded:
+ *   1. the pending trace is evaluated (a blocking barrier), so every input is plain data;
+ *   2. fn is called with run = 0 to state the outputs' dtype and shape (opcodes the library knows
+ *      skip this), then, with output buffers taken from the workspace, with run = 1 to compute
+ *      them by whatever eager implementation the caller has, on `hip_stream` or synchronously;
+ *   3. the results are new tensors holding data: a new IR graph starts from them.
+ * inputs / outputs: host arrays of descriptors; dptr is a device pointer (NULL for a rank-0 scalar
+ * input, whose value is in `scalar`).  fn returns 0 on success; anything else makes lt_op fail
+ * with LT_ERR_UNSUPPORTED and leaves no trace of the op.  Without a fallback such ops fail with
+ * LT_ERR_UNSUPPORTED (unknown opcodes when recorded, the reductions at the barrier).
+ */
+#define LT_OP_CUSTOM 1024
+typedef struct {
+  void* dptr;
+  int32_t dtype;            /* lt_dtype */
+  int32_t rank;
+  int64_t dims[LT_MAX_RANK];
+  int32_t is_scalar;        /* 1: a rank-0 scalar that lives on the host: use `scalar` */
+  double scalar;
+} lt_tensor_desc;
+typedef int (*lt_fallback_fn)(void* user, uint16_t opcode, const lt_tensor_desc* inputs, int n_in, const lt_attr* attrs,
+                              int n_attr, lt_tensor_desc* outputs, int n_out, int run, void* hip_stream);
+lt_status lt_set_fallback(lt_ctx* ctx, lt_fallback_fn fn, void* user);
 
 /*
  * Debugging switch for the invariant of section 3 (a compiled trace is equivalent to running the

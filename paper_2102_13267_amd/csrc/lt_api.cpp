@@ -129,6 +129,8 @@ static Handle* new_handle(lt_ctx* ctx) {
 static lt_status record_op(lt_ctx* ctx, uint16_t opcode, const lt_tensor* inputs, int n_in, const lt_attr* attrs, int n_attr,
                            lt_tensor* outputs, int n_out, bool hidden);
 static lt_status assign(lt_ctx* ctx, lt_tensor dst_id, lt_tensor src_id, bool hidden);
+static lt_status run_fallback(lt_ctx* ctx, uint16_t opcode, const lt_tensor* inputs, int n_in, const lt_attr* attrs, int n_attr,
+                              lt_tensor* outputs, int n_out, const Node* inferred);
 
 // Drop a handle for good.  A view gives up its hold on its base; a base that its owner had
 // already released goes with its last view.
@@ -485,6 +487,13 @@ static lt_status record_op(lt_ctx* ctx, uint16_t opcode, const lt_tensor* inputs
           if (i != axis) n.dims[r++] = a->dims[i];
         n.rank = (uint8_t)r;
         push_attr(&n, LT_ATTR_AXIS, false, axis, 0);
+        // the reduction kernels cover the last axis and axis 0 of a matrix: everything else is an
+        // op without a lowering, which a registered fallback computes eagerly (section 4.5)
+        const bool lowered = a->rank <= 1 || axis == a->rank - 1 || (axis == 0 && a->rank == 2);
+        if (!lowered && ctx->fallback && n_out == 1) {
+          const lt_attr ax_attr{LT_ATTR_AXIS, 0, {axis}};
+          return run_fallback(ctx, opcode, inputs, n_in, &ax_attr, 1, outputs, n_out, &n);
+        }
       }
     } break;
     case LT_OP_SOFTMAX:
@@ -597,6 +606,7 @@ static lt_status record_op(lt_ctx* ctx, uint16_t opcode, const lt_tensor* inputs
       push_attr(&n, LT_ATTR_START, false, st->v.i, 0);
     } break;
     default:
+      if (ctx->fallback && opcode >= LT_OP_CUSTOM) return run_fallback(ctx, opcode, inputs, n_in, attrs, n_attr, outputs, n_out, nullptr);
       return fail(ctx, LT_ERR_UNSUPPORTED, "lt_op: opcode " + std::to_string(opcode) + " has no lowering");
   }
   if (n_out != n.n_out) return fail(ctx, LT_ERR_ARG, "lt_op: wrong number of outputs for this opcode");
@@ -622,6 +632,80 @@ static lt_status record_op(lt_ctx* ctx, uint16_t opcode, const lt_tensor* inputs
     for (int i = 0; i < h->rank; ++i) h->dims[i] = nn.dims[i];
     outputs[s] = h->id;
   }
+  return LT_OK;
+}
+
+// Section 4.5: evaluate the inputs, call the eager implementation, start a new graph from its result.
+static lt_status run_fallback(lt_ctx* ctx, uint16_t opcode, const lt_tensor* inputs, int n_in, const lt_attr* attrs, int n_attr,
+                              lt_tensor* outputs, int n_out, const Node* inferred) {
+  if (n_out < 1 || n_out > 4) return fail(ctx, LT_ERR_ARG, "lt_op: an op without a lowering has 1 to 4 results");
+  // 1. every input becomes plain data (the barrier evaluates all live tensors, the inputs among them)
+  bool pending = false;
+  for (int i = 0; i < n_in; ++i) {
+    const Handle* h = find(ctx, inputs[i]);
+    pending |= h->kind == H_PENDING;
+  }
+  if (pending) {
+    const lt_status st = lt_barrier(ctx, 1, nullptr);
+    if (st != LT_OK) return st;
+  }
+  lt_tensor_desc in[kMaxIns];
+  for (int i = 0; i < n_in; ++i) {
+    const Handle* h = find(ctx, inputs[i]);
+    in[i] = lt_tensor_desc{};
+    in[i].dtype = h->dtype;
+    in[i].rank = h->rank;
+    for (int d = 0; d < h->rank; ++d) in[i].dims[d] = h->dims[d];
+    if (h->kind == H_SCALAR) {
+      in[i].is_scalar = 1;
+      in[i].scalar = h->value;
+    } else {
+      in[i].dptr = h->buf->ptr;
+    }
+  }
+  // 2. result types: the library's own inference, or the callback's
+  lt_tensor_desc out[4];
+  for (int s = 0; s < n_out; ++s) out[s] = lt_tensor_desc{};
+  if (inferred) {
+    out[0].dtype = inferred->dtype;
+    out[0].rank = inferred->rank;
+    for (int d = 0; d < inferred->rank; ++d) out[0].dims[d] = inferred->dims[d];
+  } else {
+    if (ctx->fallback(ctx->fallback_user, opcode, in, n_in, attrs, n_attr, out, n_out, 0, ctx->stream) != 0)
+      return fail(ctx, LT_ERR_UNSUPPORTED, "lt_op: opcode " + std::to_string(opcode) + " has no lowering and the fallback declined it");
+    for (int s = 0; s < n_out; ++s) {
+      bool ok = out[s].dtype >= 0 && out[s].dtype <= LT_I64 && out[s].rank >= 0 && out[s].rank <= LT_MAX_RANK;
+      for (int d = 0; ok && d < out[s].rank; ++d) ok = out[s].dims[d] >= 0;
+      if (!ok) return fail(ctx, LT_ERR_ARG, "fallback: bad result descriptor");
+    }
+  }
+  BufRef bufs[4];
+  for (int s = 0; s < n_out; ++s) {
+    const size_t bytes = (size_t)numel(out[s].dims, out[s].rank) * dtype_size((uint8_t)out[s].dtype);
+    bufs[s] = std::make_shared<Buffer>();
+    bufs[s]->ptr = ctx->arena.alloc(bytes);
+    if (!bufs[s]->ptr) return fail(ctx, LT_ERR_OOM, "workspace arena exhausted by the result of a fallback op");
+    bufs[s]->bytes = bytes;
+    bufs[s]->owned = true;
+    bufs[s]->donatable = true;
+    bufs[s]->arena = &ctx->arena;
+    out[s].dptr = bufs[s]->ptr;
+  }
+  // the eager implementation
+  if (ctx->fallback(ctx->fallback_user, opcode, in, n_in, attrs, n_attr, out, n_out, 1, ctx->stream) != 0)
+    return fail(ctx, LT_ERR_UNSUPPORTED, "lt_op: the fallback failed on opcode " + std::to_string(opcode));
+  // 3. a new IR graph starts from the results
+  for (int s = 0; s < n_out; ++s) {
+    Handle* h = new_handle(ctx);
+    h->kind = H_DATA;
+    h->dtype = (uint8_t)out[s].dtype;
+    h->rank = (uint8_t)out[s].rank;
+    for (int d = 0; d < h->rank; ++d) h->dims[d] = out[s].dims[d];
+    h->buf = bufs[s];
+    h->buf->data_refs = 1;
+    outputs[s] = h->id;
+  }
+  ctx->stats.fallback_ops++;
   return LT_OK;
 }
 
@@ -899,6 +983,13 @@ lt_status lt_set_fusion(lt_ctx* ctx, int on) {
   }
   ctx->cache.clear();
   ctx->last_plan = nullptr;
+  return LT_OK;
+}
+
+lt_status lt_set_fallback(lt_ctx* ctx, lt_fallback_fn fn, void* user) {
+  if (!ctx) return LT_ERR_ARG;
+  ctx->fallback = fn;
+  ctx->fallback_user = user;
   return LT_OK;
 }
 

@@ -193,6 +193,8 @@ struct lt_ctx {
   hipEvent_t fork_event = nullptr, join_event[lt::kMaxStreams - 1] = {};
   int max_streams = lt::kMaxStreams;   // lt_set_streams
   bool fusion = true;                  // lt_set_fusion: off = one region per recorded op
+  lt_fallback_fn fallback = nullptr;   // lt_set_fallback: eager implementation of ops without a lowering
+  void* fallback_user = nullptr;
   // the library's static device scratch on this device (lt_barrier_static): reduction partials,
   // tickets, then room for a plan's temporaries
   uint8_t* static_scratch = nullptr;

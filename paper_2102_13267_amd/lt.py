@@ -46,7 +46,17 @@ class BarrierInfo(C.Structure):
 class Stats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in (
         "barriers", "cache_hits", "cache_misses", "nodes_recorded", "regions_launched", "kernels_launched",
-        "ns_lowering_total", "arena_bytes_in_use", "arena_bytes_peak", "live_tensors")]
+        "ns_lowering_total", "arena_bytes_in_use", "arena_bytes_peak", "live_tensors", "fallback_ops")]
+
+
+class TensorDesc(C.Structure):
+    _fields_ = [("dptr", C.c_void_p), ("dtype", C.c_int32), ("rank", C.c_int32), ("dims", C.c_int64 * 6),
+                ("is_scalar", C.c_int32), ("scalar", C.c_double)]
+
+
+FALLBACK_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_uint16, C.POINTER(TensorDesc), C.c_int, C.POINTER(lt_attr), C.c_int,
+                          C.POINTER(TensorDesc), C.c_int, C.c_int, C.c_void_p)
+OP_CUSTOM = 1024
 
 
 class LaunchRecord(C.Structure):
@@ -104,6 +114,7 @@ def load_library():
         "lt_set_profiling": [P, i32],
         "lt_set_streams": [P, i32],
         "lt_set_fusion": [P, i32],
+        "lt_set_fallback": [P, FALLBACK_FN, P],
         "lt_last_launches": [P, C.POINTER(LaunchRecord), i32, C.POINTER(i32)],
     }
     for name, argtypes in sig.items():
@@ -453,6 +464,70 @@ class Context:
 
     def set_streams(self, n: int) -> None:
         self._check(self._lib.lt_set_streams(self._h, int(n)))
+
+    # ---- ops without a lowering (lt_set_fallback) ----------------------------------------------------
+    def set_fallback(self, fn):
+        """fn(opcode, inputs, attrs, outputs, run) -> None.  inputs / outputs: lists of dicts with keys
+        ptr (device pointer; None for a host scalar), dtype, shape, scalar.  run False: set
+        outputs[i]["dtype"] and ["shape"] (shape inference); run True: outputs have ptr set, compute
+        them.  An exception raised by fn makes the op fail with LT_ERR_UNSUPPORTED.  None unregisters."""
+        if fn is None:
+            self._fallback_c = None
+            self._check(self._lib.lt_set_fallback(self._h, C.cast(None, FALLBACK_FN), None))
+            return
+
+        def trampoline(user, opcode, ins, n_in, attrs, n_attr, outs, n_out, run, stream):
+            try:
+                def desc(d):
+                    return {"ptr": d.dptr, "dtype": _DTYPE_NAMES[d.dtype], "shape": tuple(d.dims[i] for i in range(d.rank)),
+                            "scalar": d.scalar if d.is_scalar else None}
+                i_list = [desc(ins[i]) for i in range(n_in)]
+                a_dict = {attrs[i].key: (attrs[i].v.f if attrs[i].is_float else attrs[i].v.i) for i in range(n_attr)}
+                o_list = [desc(outs[i]) if run else {"ptr": None, "dtype": None, "shape": None} for i in range(n_out)]
+                fn(opcode, i_list, a_dict, o_list, bool(run))
+                if not run:
+                    for i, o in enumerate(o_list):
+                        outs[i].dtype = DTYPES[o["dtype"]]
+                        outs[i].rank = len(o["shape"])
+                        for k, dim in enumerate(o["shape"]):
+                            outs[i].dims[k] = int(dim)
+                return 0
+            except Exception as e:      # an exception cannot cross the C boundary
+                self._fallback_error = e
+                return 1
+        self._fallback_c = FALLBACK_FN(trampoline)       # (kept alive as long as it is registered)
+        self._check(self._lib.lt_set_fallback(self._h, self._fallback_c, None))
+
+    def custom_op(self, opcode, inputs, attrs=(), n_out=1):
+        """Record (or, with a fallback registered, run) an op by number: opcodes from OP_CUSTOM up have no lowering."""
+        self._flush()
+        ts = [self._t(x) for x in inputs]           # (numbers become scalar tensors that live for the call)
+        ids = (C.c_uint64 * len(ts))(*[t.tid for t in ts])
+        arr = (lt_attr * max(1, len(attrs)))()
+        for i, (k, val) in enumerate(attrs):
+            arr[i].key = k
+            if isinstance(val, float):
+                arr[i].is_float, arr[i].v.f = 1, val
+            else:
+                arr[i].is_float, arr[i].v.i = 0, int(val)
+        outs = (C.c_uint64 * n_out)()
+        self._check(self._lib.lt_op(self._h, opcode, ids, len(inputs), arr, len(attrs), outs, n_out))
+        res = [Tensor(self, outs[i]) for i in range(n_out)]
+        return res[0] if n_out == 1 else tuple(res)
+
+    def device_array(self, desc):
+        """A fallback descriptor's device memory as a torch tensor (no copy): for fallbacks that call
+        the eager framework's own op on the device."""
+        torch = self._torch
+        code = {"f32": ("<f4", torch.float32), "bf16": ("<i2", torch.bfloat16), "s32": ("<i4", torch.int32), "s64": ("<i8", torch.int64)}[desc["dtype"]]
+
+        class _Mem:
+            pass
+        m = _Mem()
+        m.__cuda_array_interface__ = {"shape": tuple(desc["shape"]), "typestr": code[0], "data": (int(desc["ptr"]), False),
+                                      "version": 2, "strides": None}
+        t = torch.as_tensor(m, device=f"cuda:{self.device}")
+        return t.view(code[1]) if desc["dtype"] == "bf16" else t
 
     def set_fusion(self, on: bool) -> None:
         self._check(self._lib.lt_set_fusion(self._h, 1 if on else 0))

@@ -447,6 +447,46 @@ def test_windows_of_larger_tensors(ctx):
     check(ctx, E, gh, rh, TOL16, "bf16 window in place")
 
 
+def test_fallback_runs_the_eager_op_on_the_device(ctx):
+    """Section 4.5: ops without a lowering (reductions over a middle axis, a custom opcode) are run
+    by a registered fallback -- here the eager framework's own ops on the device memory that the
+    library hands over -- after the pending trace has been evaluated; lazy ops go on from the results."""
+    import torch
+    E = Eager()
+    seen = []
+
+    def fb(opcode, inputs, attrs, outputs, run):
+        seen.append((opcode, run))
+        if opcode == 1024:                                   # running sum along the last axis
+            if not run:
+                outputs[0]["dtype"], outputs[0]["shape"] = inputs[0]["dtype"], inputs[0]["shape"]
+                return
+            ctx.device_array(outputs[0]).copy_(torch.cumsum(ctx.device_array(inputs[0]), dim=-1))
+            return
+        fn = {64: torch.sum, 65: torch.amax, 66: torch.mean}[opcode]
+        out = ctx.device_array(outputs[0])
+        out.copy_(fn(ctx.device_array(inputs[0]).float(), dim=attrs[3]).to(out.dtype))
+    ctx.set_fallback(fb)
+    try:
+        x = rng(33).standard_normal((4, 6, 8), dtype=np.float32)
+        gx = ctx.tensor(x)
+        a = ctx.exp(ctx.mul(gx, 0.1))                        # pending when the first fallback op arrives
+        m = ctx.sum(a, axis=1)
+        c = ctx.custom_op(1024, [m])
+        out = ctx.add(ctx.tanh(ctx.mul(c, 0.05)), ctx.amax(a, axis=1))
+        hb = ctx.mean(ctx.cast(a, "bf16"), axis=0)           # axis 0 of a rank-3 tensor, bf16
+        ra = E.exp(E.mul(E.tensor(x), 0.1))
+        rm = E.sum(ra, axis=1)
+        rc = E.tensor(np.cumsum(E.fetch(rm).astype(np.float64), axis=-1).astype(np.float32))
+        rout = E.add(E.tanh(E.mul(rc, 0.05)), E.amax(ra, axis=1))
+        check(ctx, E, m, rm, TOL32, "sum over the middle axis")
+        check(ctx, E, out, rout, TOL32, "lazy ops after fallback ops")
+        check(ctx, E, hb, E.mean(E.cast(ra, "bf16"), axis=0), TOL16, "bf16 mean over axis 0 of rank 3")
+        assert [s for s in seen if s[0] == 1024] == [(1024, False), (1024, True)] and ctx.stats().fallback_ops >= 4
+    finally:
+        ctx.set_fallback(None)
+
+
 def test_a_leaf_dropped_before_the_barrier_keeps_its_memory(ctx):
     """The trace names a leaf's device memory until the barrier has run; the binding keeps the owner
     of that memory alive that long even when the program drops its handle first."""

@@ -463,3 +463,47 @@ def test_plain_op_methods_are_descriptors_of_the_extension():
         with pytest.raises(TypeError):
             bad()
     assert ctx.stats().live_tensors == base + len(outs)
+
+
+def test_fallback_for_ops_without_a_lowering():
+    """Section 4.5 on the null device: a reduction over a middle axis and a custom opcode go to the
+    registered fallback at record time -- after the pending trace has been evaluated -- and their
+    results are plain data from which a new trace starts.  Without a fallback they are refused."""
+    ctx = Context()
+    calls = []
+
+    def fb(opcode, inputs, attrs, outputs, run):
+        calls.append((opcode, run, [i["shape"] for i in inputs], dict(attrs), ctx.stats().barriers))
+        if opcode == 1025:
+            raise ValueError("not this one")
+        if not run:
+            outputs[0]["dtype"], outputs[0]["shape"] = "f32", inputs[0]["shape"][::-1]
+        else:
+            assert all(o["ptr"] is not None for o in outputs) and inputs[0]["ptr"] is not None
+    a = ctx.tensor(np.zeros((2, 3, 4), np.float32))
+    with pytest.raises(LtError) as e:
+        ctx.custom_op(1024, [a])
+    assert e.value.status == 5
+    ctx.set_fallback(fb)
+    pre = ctx.exp(a)                                     # pending when the fallback op arrives
+    barriers = ctx.stats().barriers
+    s = ctx.sum(pre, axis=1)                             # middle axis: no kernel covers it
+    assert calls == [(64, True, [(2, 3, 4)], {3: 1}, barriers + 1)]      # inputs were evaluated first; the library inferred the shape
+    assert s.shape == (2, 4) and ctx.stats().fallback_ops == 1
+    ctx.device_ptr(s)                                    # the result is data already
+    t = ctx.custom_op(1024, [s, 2.5], attrs=[(3, 7)])    # a scalar operand comes by value
+    assert [c[:2] for c in calls[1:]] == [(1024, False), (1024, True)] and calls[2][2] == [(2, 4), ()]
+    assert t.shape == (4, 2) and ctx.stats().fallback_ops == 2
+    out = ctx.add(t, 1.0)                                # a new trace starts from the result
+    assert "xla::device_data" in ctx.dump_ir() and ctx.barrier().n_regions == 1
+    with pytest.raises(LtError) as e:
+        ctx.custom_op(1025, [a])
+    assert e.value.status == 5 and "declined" in str(e.value)
+    last = ctx.sum(a, axis=2)                            # an axis the kernels cover is still recorded, not run
+    assert ctx.stats().fallback_ops == 2
+    ctx.set_fallback(None)
+    mid = ctx.sum(a, axis=1)                             # ... and without a fallback the barrier refuses the middle axis
+    with pytest.raises(LtError) as e:
+        ctx.barrier()
+    assert e.value.status == 5
+    del out, last, mid

@@ -7,7 +7,7 @@
 //
 // Structure: workgroup tile 128 x 128 (or 64 x 64 for small problems so that more compute units
 // get a tile), four wavefronts in a 2 x 2 arrangement, each owning a quarter as MFMA 32x32x2
-// blocks.  K is walked in slices of 16 with register prefetch: the global loads of slice k+1 are
+// blocks.  K is walked in slices of 32 with register prefetch: the global loads of slice k+1 are
 // issued before the MFMAs of slice k and written to the other LDS buffer afterwards.  Global
 // loads are 16 bytes per lane along whichever dimension of the operand is contiguous; an operand
 // whose contiguous dimension is k is transposed on its way into LDS.  A long k over few tiles is
@@ -24,7 +24,7 @@ namespace ltk {
 // operand's contiguous dimension (4 fp32 or 8 bf16).  For element type T the raw group travels
 // as uint4.
 template <typename T> struct Elem;
-template <> struct Elem<float> { static constexpr int G = 4; static constexpr int BK = 16; };
+template <> struct Elem<float> { static constexpr int G = 4; static constexpr int BK = 32; };
 
 // Guarded fetch of G elements at (outer, inner .. inner+G-1); element (o, i) lives at
 // base + o*s_outer + i (unit stride inside the group).  Out-of-range elements read as zero.
@@ -43,18 +43,27 @@ __device__ __forceinline__ uint4 fetch_group(const T* base, int64_t s_outer, uin
   return v;
 }
 
-// LDS layout: tile[k][x] (x = m or n contiguous), row stride BX + 4 -> MFMA 32x32x2 reads one float
+// LDS layout: tile[k][x] (x = m or n contiguous); an MFMA 32x32x2 lane reads one float.  Row stride:
+// BX + 4 for an operand that arrives x-contiguous (16-byte row writes stay aligned).  An operand
+// that arrives k-contiguous is transposed by scalar writes, eight lanes of a wave writing rows
+// 4 apart: BX + 1 puts those rows 4 banks apart, so a wave's 32 writes per cycle hit 32 banks
+// (with BX + 4 they hit 8: counters showed as many bank-conflict cycles as LDS cycles).  ELEMS is
+// sized for the wider one, so buffers are interchangeable.
 template <typename T, int BX> struct Tile;
 template <int BX> struct Tile<float, BX> {
-  static constexpr int BK = 16, STRIDE = BX + 4, ELEMS = BK * STRIDE;
+  static constexpr int BK = 32, ELEMS = BK * (BX + 4);
+  static constexpr int stride(bool kc) { return kc ? BX + 1 : BX + 4; }
 };
 // Number of 16-byte groups per lane and k-slice for an operand tile of BX x BK elements.
 template <typename T, int BX> struct Groups {
   static constexpr int N = BX * Elem<T>::BK / Elem<T>::G / kGemmThreads;   // 128: 2, 64: 1
 };
 
+// (a native vector type, not HIP's uint4 struct: sets of the struct kind that are only ever moved
+// whole were left in scratch memory by the compiler)
+typedef uint32_t U32x4 __attribute__((ext_vector_type(4)));
 template <int N> struct GroupRegs {
-  uint4 g[N];
+  U32x4 g[N];
 };
 
 // Fetch this lane's groups of the slice starting at k0.  KC: the contraction dimension is the
@@ -69,52 +78,92 @@ __device__ __forceinline__ void fetch_tile(GroupRegs<Groups<T, BX>::N>& gr, cons
     const uint32_t e = it * kGemmThreads + t;
     if (KC) {
       const uint32_t x = e / (BK / G), kq = e % (BK / G);
-      gr.g[it] = fetch_group<T>(base, s_x, x0 + x, k0 + kq * G, nx, nk, aligned);
+      const uint4 v = fetch_group<T>(base, s_x, x0 + x, k0 + kq * G, nx, nk, aligned);
+      gr.g[it] = U32x4{v.x, v.y, v.z, v.w};
     } else {
       const uint32_t k = e / (BX / G), xq = e % (BX / G);
-      gr.g[it] = fetch_group<T>(base, s_k, k0 + k, x0 + xq * G, nk, nx, aligned);
+      const uint4 v = fetch_group<T>(base, s_k, k0 + k, x0 + xq * G, nk, nx, aligned);
+      gr.g[it] = U32x4{v.x, v.y, v.z, v.w};
     }
   }
 }
 
 template <int BX, bool KC>
 __device__ __forceinline__ void stash_tile(const GroupRegs<Groups<float, BX>::N>& gr, float* tile) {
-  const uint4* g = gr.g;
-  constexpr int G = 4, BK = 16, STRIDE = Tile<float, BX>::STRIDE, NG = Groups<float, BX>::N;
+  constexpr int G = 4, BK = Elem<float>::BK, STRIDE = Tile<float, BX>::stride(KC), NG = Groups<float, BX>::N;
   const uint32_t t = threadIdx.x;
 #pragma unroll
   for (int it = 0; it < NG; ++it) {
     const uint32_t e = it * kGemmThreads + t;
     if (KC) {   // transposing: four scalar writes
       const uint32_t x = e / (BK / G), kq = e % (BK / G);
-      tile[(kq * G + 0) * STRIDE + x] = __uint_as_float(g[it].x);
-      tile[(kq * G + 1) * STRIDE + x] = __uint_as_float(g[it].y);
-      tile[(kq * G + 2) * STRIDE + x] = __uint_as_float(g[it].z);
-      tile[(kq * G + 3) * STRIDE + x] = __uint_as_float(g[it].w);
+      tile[(kq * G + 0) * STRIDE + x] = __uint_as_float(gr.g[it].x);
+      tile[(kq * G + 1) * STRIDE + x] = __uint_as_float(gr.g[it].y);
+      tile[(kq * G + 2) * STRIDE + x] = __uint_as_float(gr.g[it].z);
+      tile[(kq * G + 3) * STRIDE + x] = __uint_as_float(gr.g[it].w);
     } else {
       const uint32_t k = e / (BX / G), xq = e % (BX / G);
-      *(uint4*)&tile[k * STRIDE + xq * G] = g[it];
+      *(U32x4*)&tile[k * STRIDE + xq * G] = gr.g[it];
     }
   }
 }
 
-// MFMAs of one k-slice.
-template <int BM, int BN, int MB, int NB>
-__device__ __forceinline__ void mma_slice(v16f (&acc)[MB][NB], const float* As, const float* Bs, uint32_t wave_m, uint32_t wave_n,
+// Interior tiles of aligned operands: the slice at k0, 16 bytes per lane and load, no checks and
+// no branches, so that all of a slice's loads are in flight together.
+// x_last: the operand's last row (KC only): rows of a tile that hangs over the edge are read as
+// copies of it -- in bounds, and their products are never stored -- so that a tile of a few rows
+// (a small batch) still takes this path.
+template <int BX, bool KC>
+__device__ __forceinline__ void fetch_tile_whole(GroupRegs<Groups<float, BX>::N>& gr, const float* base, int64_t s_x, int64_t s_k,
+                                                 uint32_t x0, uint32_t k0, uint32_t x_last) {
+  constexpr int G = 4, BK = Elem<float>::BK, NG = Groups<float, BX>::N;
+  const uint32_t t = threadIdx.x;
+#pragma unroll
+  for (int it = 0; it < NG; ++it) {
+    const uint32_t e = it * kGemmThreads + t;
+    const float* src = KC ? base + (int64_t)min(x0 + e / (BK / G), x_last) * s_x + (k0 + (e % (BK / G)) * G)
+                          : base + (int64_t)(k0 + e / (BX / G)) * s_k + (x0 + (e % (BX / G)) * G);
+    gr.g[it] = *(const U32x4*)src;
+  }
+}
+
+// MFMAs of one k-slice, in groups of four k-steps: the fragments of the next group are read from
+// LDS BEFORE the MFMAs of the current one are issued (two register sets; scheduling barriers keep
+// the compiler from sinking the reads to their first use), so the matrix cores never wait for an
+// LDS round trip inside a slice.
+// acc has NCH accumulator sets ("chains"); k-step s adds into set s % NCH.  A wave that owns a
+// single 32 x 32 block would otherwise issue nothing but MFMAs that each wait for the one before.
+template <int BM, int BN, int MB, int NB, bool AKC, bool BKC, int NCH>
+__device__ __forceinline__ void mma_slice(v16f (&acc)[NCH][MB][NB], const float* As, const float* Bs, uint32_t wave_m, uint32_t wave_n,
                                           uint32_t lane) {
-  constexpr int SA = Tile<float, BM>::STRIDE, SB = Tile<float, BN>::STRIDE;
+  constexpr int SA = Tile<float, BM>::stride(AKC), SB = Tile<float, BN>::stride(BKC), BK = Elem<float>::BK;
+  constexpr int KG = 4, NGRP = BK / 2 / KG;   // k-steps per group, groups per slice
+  const float* ap = As + (lane >> 5) * SA + wave_m * (MB * 32) + (lane & 31);
+  const float* bp = Bs + (lane >> 5) * SB + wave_n * (NB * 32) + (lane & 31);
+  float af[2][KG][MB], bf[2][KG][NB];
+  auto read_group = [&](int set, int g) {
 #pragma unroll
-  for (int kk = 0; kk < 16; kk += 2) {
-    const uint32_t kl = kk + (lane >> 5);
-    float af[MB], bf[NB];
+    for (int s = 0; s < KG; ++s) {
+      const int kk = (g * KG + s) * 2;
 #pragma unroll
-    for (int i = 0; i < MB; ++i) af[i] = As[kl * SA + wave_m * (MB * 32) + i * 32 + (lane & 31)];
+      for (int i = 0; i < MB; ++i) af[set][s][i] = ap[kk * SA + i * 32];
 #pragma unroll
-    for (int j = 0; j < NB; ++j) bf[j] = Bs[kl * SB + wave_n * (NB * 32) + j * 32 + (lane & 31)];
+      for (int j = 0; j < NB; ++j) bf[set][s][j] = bp[kk * SB + j * 32];
+    }
+  };
+  read_group(0, 0);
 #pragma unroll
-    for (int i = 0; i < MB; ++i)
+  for (int g = 0; g < NGRP; ++g) {
+    if (g + 1 < NGRP) read_group((g + 1) & 1, g + 1);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int j = 0; j < NB; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i], bf[j], acc[i][j], 0, 0, 0);
+    for (int s = 0; s < KG; ++s)
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+          acc[s % NCH][i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[g & 1][s][i], bf[g & 1][s][j], acc[s % NCH][i][j], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
@@ -126,7 +175,7 @@ template <typename T, int BM, int BN> struct Smem {
 
 // T: float.  AKC / BKC: the operand's contiguous dimension is k.
 template <typename T, int BM, int BN, bool AKC, bool BKC>
-__global__ __launch_bounds__(kGemmThreads) void lt_gemm_kernel(const GemmArgs a) {
+__global__ __launch_bounds__(kGemmThreads, BM == 64 ? 2 : 1) void lt_gemm_kernel(const GemmArgs a) {
   constexpr int MB = BM / 64, NB = BN / 64, BK = Elem<T>::BK;
   __shared__ __attribute__((aligned(16))) char smem[Smem<T, BM, BN>::kBytes];
   // LDS map: A buffer 0, A buffer 1, B buffer 0, B buffer 1 (the C tile of the epilogue reuses it)
@@ -148,17 +197,76 @@ __global__ __launch_bounds__(kGemmThreads) void lt_gemm_kernel(const GemmArgs a)
   const int64_t a_outer = AKC ? a.a.s_row : a.a.s_col, b_outer = BKC ? a.b.s_col : a.b.s_row;
   const bool a_al = (((uintptr_t)A) & 15u) == 0 && (a_outer % G) == 0;
   const bool b_al = (((uintptr_t)B) & 15u) == 0 && (b_outer % G) == 0;
-  v16f acc[MB][NB];
+  constexpr int NCH = MB * NB == 1 ? 2 : 1;   // independent accumulator chains per block
+  v16f accs[NCH][MB][NB];
 #pragma unroll
-  for (int i = 0; i < MB; ++i)
+  for (int c = 0; c < NCH; ++c)
 #pragma unroll
-    for (int j = 0; j < NB; ++j)
+    for (int i = 0; i < MB; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+      for (int j = 0; j < NB; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) accs[c][i][j][r] = 0.0f;
 
   GroupRegs<Groups<T, BM>::N> ga;
   GroupRegs<Groups<T, BN>::N> gb;
-  if (k_begin < k_end) {
+  const bool whole = a_al && b_al && (AKC || tile_m + BM <= a.m) && (BKC || tile_n + BN <= a.n) && ((k_end - k_begin) % BK) == 0u;
+  if (k_begin < k_end && whole) {
+    // Interior tile: unchecked 16-byte loads, D slices ahead in registers (a slice's MFMAs are over
+    // in 1000 to 4000 cycles, a load under traffic takes longer: counters showed a wave of the
+    // one-slice-ahead loop waiting two thirds of its life), two LDS buffers.  Slice i: start the
+    // loads of slice i + D into the register set that slice i left when it was written to LDS;
+    // multiply slice i from its LDS buffer; write slice i + 1 to the other buffer; barrier.  The
+    // body is unrolled D times so that set and buffer numbers are compile-time; loads past the
+    // end are clamped to the last slice (in bounds, unused).
+    // (Four named register sets, not an array: an array of sets indexed by the unrolled loop
+    // counter is left in scratch memory by the compiler, and every load then waits to be spilled.)
+    const uint32_t n = (k_end - k_begin) / BK;
+    typedef GroupRegs<Groups<T, BM>::N> RA;
+    typedef GroupRegs<Groups<T, BN>::N> RB;
+    RA ra0, ra1, ra2, ra3;
+    RB rb0, rb1, rb2, rb3;
+    constexpr uint32_t D = BM == 64 ? 4u : 2u;   // slices in flight (a 128 x 128 tile's sets are twice as large)
+#define LT_FETCH(RA_, RB_, I)                                                                 \
+  {                                                                                           \
+    const uint32_t kf = k_begin + min((uint32_t)(I), n - 1u) * BK;                            \
+    fetch_tile_whole<BM, AKC>(RA_, A, a.a.s_row, a.a.s_col, tile_m, kf, a.m - 1u);            \
+    fetch_tile_whole<BN, BKC>(RB_, B, a.b.s_col, a.b.s_row, tile_n, kf, a.n - 1u);            \
+  }
+#define LT_STEP(J, RA_CUR, RB_CUR, RA_NEXT, RB_NEXT)                                          \
+  {                                                                                           \
+    const uint32_t i = i0 + (J);                                                              \
+    LT_FETCH(RA_CUR, RB_CUR, i + D);                                                          \
+    if (i < n) mma_slice<BM, BN, MB, NB, AKC, BKC, NCH>(accs, As((J) & 1), Bs((J) & 1), wave_m, wave_n, lane); \
+    stash_tile<BM, AKC>(RA_NEXT, As(((J) + 1) & 1));                                          \
+    stash_tile<BN, BKC>(RB_NEXT, Bs(((J) + 1) & 1));                                          \
+    __syncthreads();                                                                          \
+  }
+    LT_FETCH(ra0, rb0, 0);
+    LT_FETCH(ra1, rb1, 1);
+    if (D == 4u) {
+      LT_FETCH(ra2, rb2, 2);
+      LT_FETCH(ra3, rb3, 3);
+    }
+    stash_tile<BM, AKC>(ra0, As(0));
+    stash_tile<BN, BKC>(rb0, Bs(0));
+    __syncthreads();
+    if (D == 4u) {
+      for (uint32_t i0 = 0; i0 < n; i0 += 4u) {
+        LT_STEP(0u, ra0, rb0, ra1, rb1);
+        LT_STEP(1u, ra1, rb1, ra2, rb2);
+        LT_STEP(2u, ra2, rb2, ra3, rb3);
+        LT_STEP(3u, ra3, rb3, ra0, rb0);
+      }
+    } else {
+      for (uint32_t i0 = 0; i0 < n; i0 += 2u) {
+        LT_STEP(0u, ra0, rb0, ra1, rb1);
+        LT_STEP(1u, ra1, rb1, ra0, rb0);
+      }
+    }
+#undef LT_STEP
+#undef LT_FETCH
+  } else if (k_begin < k_end) {
     fetch_tile<T, BM, AKC>(ga, A, a.a.s_row, a.a.s_col, tile_m, k_begin, a.m, k_end, a_al);
     fetch_tile<T, BN, BKC>(gb, B, a.b.s_col, a.b.s_row, tile_n, k_begin, a.n, k_end, b_al);
     stash_tile<BM, AKC>(ga, As(0));
@@ -171,7 +279,7 @@ __global__ __launch_bounds__(kGemmThreads) void lt_gemm_kernel(const GemmArgs a)
         fetch_tile<T, BM, AKC>(ga, A, a.a.s_row, a.a.s_col, tile_m, k0 + BK, a.m, k_end, a_al);
         fetch_tile<T, BN, BKC>(gb, B, a.b.s_col, a.b.s_row, tile_n, k0 + BK, a.n, k_end, b_al);
       }
-      mma_slice<BM, BN, MB, NB>(acc, As(cur), Bs(cur), wave_m, wave_n, lane);
+      mma_slice<BM, BN, MB, NB, AKC, BKC, NCH>(accs, As(cur), Bs(cur), wave_m, wave_n, lane);
       if (more) {
         stash_tile<BM, AKC>(ga, As(cur ^ 1));
         stash_tile<BN, BKC>(gb, Bs(cur ^ 1));
@@ -179,6 +287,15 @@ __global__ __launch_bounds__(kGemmThreads) void lt_gemm_kernel(const GemmArgs a)
       __syncthreads();
       cur ^= 1;
     }
+  }
+  v16f (&acc)[MB][NB] = accs[0];
+  if (NCH > 1) {
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] += accs[NCH - 1][i][j][r];
   }
   // split-K: this workgroup's partial product goes to its own fp32 copy of the output, row major
   float* const raw = a.splits > 1u ? a.split_ws + (size_t)split * ((size_t)a.batch0 * a.batch1 * a.m * a.n) : nullptr;

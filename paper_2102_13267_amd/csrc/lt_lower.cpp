@@ -1513,16 +1513,17 @@ struct Lowering {
       }
     }
     if (A.dtype == LT_F32) {
-      // a long k over few tiles is split so that the chip has about one workgroup per compute
-      // unit, each with >= 4 slices of 16
+      // 64 x 64 tiles unless 128 x 128 ones still give every compute unit a workgroup; a long k
+      // over few tiles is split until about two workgroups per compute unit exist (one hides the
+      // other's slice boundaries: loads landing, the barrier), each with >= 4 slices of 16.
+      // Measured on [B, 2048] x [2048, 2048]: B = 1024 as 512 unsplit tiles of 64 x 64 runs at
+      // 85 TFLOP/s (128 x 128 tiles split in two: 78); B = 256 at 54 split in four, 37 unsplit.
       const uint64_t big_tiles = (uint64_t)((m + 127) / 128) * ((n + 127) / 128) * (uint64_t)batch;
-      // 128 x 128 tiles need half the LDS fragment traffic per flop of 64 x 64 ones: measured
-      // better from 32 big tiles up (k is split to fill the rest of the chip)
-      const uint32_t ts = big_tiles >= 32 ? 128u : 64u;
+      const uint32_t ts = big_tiles >= 256 ? 128u : 64u;
       args.tile_m = args.tile_n = ts;
       const uint64_t tiles = (uint64_t)((m + ts - 1) / ts) * ((n + ts - 1) / ts) * (uint64_t)batch;
       const uint64_t slices = (uint64_t)(kk + 15) / 16;
-      const uint64_t splits = r->sealed ? 1 : std::min<uint64_t>({256 / std::max<uint64_t>(tiles, 1), slices / 4, 16});
+      const uint64_t splits = r->sealed ? 1 : std::min<uint64_t>({512 / std::max<uint64_t>(tiles, 1), slices / 4, 16});
       if (splits > 1) {
         args.splits = (uint32_t)splits;
         Storage ws;

@@ -11,6 +11,18 @@
 #include "lt_core.h"
 #include "lt_launch.h"
 
+namespace ltk {
+static thread_local char g_kernel_name[48] = "";
+void note_kernel(const char* name) {
+  // "(lt_ew_stream_kernel<4, true>)" -> "lt_ew_stream_kernel<4, true>"
+  size_t n = 0;
+  for (const char* c = name; *c && n + 1 < sizeof(g_kernel_name); ++c)
+    if (*c != '(' && *c != ')') g_kernel_name[n++] = *c;
+  g_kernel_name[n] = 0;
+}
+const char* last_kernel() { return g_kernel_name; }
+}  // namespace ltk
+
 namespace lt {
 
 static uint64_t now_ns() {
@@ -278,6 +290,7 @@ static lt_status execute(lt_ctx* ctx, Plan* plan, const Cut& cut, std::vector<Bu
   }
   std::vector<size_t> deferred;
   std::vector<uint8_t> args;
+  std::vector<std::string> launch_names;   // kernel instances, when per-launch records are asked for
   size_t pp = 0, sp = 0;
   // join: whatever follows on the caller's stream comes after every side stream's work.  Runs on
   // every way out once a side stream may hold work -- a failed launch included, so that memory the
@@ -339,6 +352,10 @@ static lt_status execute(lt_ctx* ctx, Plan* plan, const Cut& cut, std::vector<Bu
       if (prof) (void)hipEventRecord(ctx->events[2 * li], ctx->stream);
       hipError_t e = launch_one(l, args.data(), stream);
       if (e != hipSuccess) return give_up(hip_fail(ctx, kind_name(l.kind), e));
+      if (prof) {
+        if (launch_names.size() <= li) launch_names.resize(plan->launches.size());
+        launch_names[li] = ltk::last_kernel();
+      }
       if (prof) (void)hipEventRecord(ctx->events[2 * li + 1], ctx->stream);
       if (multi && l.record) {
         if (!plan->events[li]) e = hipEventCreateWithFlags(&plan->events[li], hipEventDisableTiming);
@@ -366,7 +383,8 @@ static lt_status execute(lt_ctx* ctx, Plan* plan, const Cut& cut, std::vector<Bu
     if (e != hipSuccess) return hip_fail(ctx, "hipStreamSynchronize", e);
     for (size_t li = 0; li < plan->launches.size(); ++li) {
       lt_launch_record r{};
-      std::snprintf(r.kernel, sizeof(r.kernel), "%s", kind_name(plan->launches[li].kind));
+      std::snprintf(r.kernel, sizeof(r.kernel), "%s", li < launch_names.size() && !launch_names[li].empty() ? launch_names[li].c_str()
+                                                                                                        : kind_name(plan->launches[li].kind));
       r.region = plan->launches[li].region;
       (void)hipEventElapsedTime(&r.ms, ctx->events[2 * li], ctx->events[2 * li + 1]);
       r.bytes = plan->launches[li].bytes;

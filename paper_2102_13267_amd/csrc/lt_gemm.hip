@@ -14,6 +14,8 @@
 // split over workgroups (partial products to a workspace, summed by a second launch).
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
+
 #include "lt_gemm_epilogue.h"
 #include "lt_launch.h"
 
@@ -305,10 +307,13 @@ __global__ __launch_bounds__(kGemmThreads, BM == 64 ? 2 : 1) void lt_gemm_kernel
 template <typename T, int BM, int BN>
 static void launch_variant(const GemmArgs& a, const dim3 grid, hipStream_t s) {
   const bool akc = a.a.s_col == 1, bkc = a.b.s_row == 1;
-  if (akc && bkc) hipLaunchKernelGGL((lt_gemm_kernel<T, BM, BN, true, true>), grid, dim3(kGemmThreads), 0, s, a);
-  else if (akc) hipLaunchKernelGGL((lt_gemm_kernel<T, BM, BN, true, false>), grid, dim3(kGemmThreads), 0, s, a);
-  else if (bkc) hipLaunchKernelGGL((lt_gemm_kernel<T, BM, BN, false, true>), grid, dim3(kGemmThreads), 0, s, a);
-  else hipLaunchKernelGGL((lt_gemm_kernel<T, BM, BN, false, false>), grid, dim3(kGemmThreads), 0, s, a);
+  if (akc && bkc) LT_LAUNCH((lt_gemm_kernel<T, BM, BN, true, true>), grid, dim3(kGemmThreads), s, a);
+  else if (akc) LT_LAUNCH((lt_gemm_kernel<T, BM, BN, true, false>), grid, dim3(kGemmThreads), s, a);
+  else if (bkc) LT_LAUNCH((lt_gemm_kernel<T, BM, BN, false, true>), grid, dim3(kGemmThreads), s, a);
+  else LT_LAUNCH((lt_gemm_kernel<T, BM, BN, false, false>), grid, dim3(kGemmThreads), s, a);
+  char name[48];
+  snprintf(name, sizeof(name), "lt_gemm_kernel<float, %d, %d, %s, %s>", BM, BN, akc ? "true" : "false", bkc ? "true" : "false");
+  note_kernel(name);
 }
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {

@@ -38,6 +38,8 @@
 // panels per L2).
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
+
 #include "lt_gemm_epilogue.h"
 #include "lt_launch.h"
 
@@ -464,10 +466,13 @@ template <int BM, int BN>
 static void launch_tile(const GemmArgs& a, dim3 grid, hipStream_t s) {
   const dim3 block(kGemmThreads);
   const bool akc = a.a.s_col == 1, bkc = a.b.s_row == 1;
-  if (akc && bkc) hipLaunchKernelGGL((lt_gemm_bf16_kernel<BM, BN, true, true>), grid, block, 0, s, a);
-  else if (akc) hipLaunchKernelGGL((lt_gemm_bf16_kernel<BM, BN, true, false>), grid, block, 0, s, a);
-  else if (bkc) hipLaunchKernelGGL((lt_gemm_bf16_kernel<BM, BN, false, true>), grid, block, 0, s, a);
-  else hipLaunchKernelGGL((lt_gemm_bf16_kernel<BM, BN, false, false>), grid, block, 0, s, a);
+  if (akc && bkc) LT_LAUNCH((lt_gemm_bf16_kernel<BM, BN, true, true>), grid, block, s, a);
+  else if (akc) LT_LAUNCH((lt_gemm_bf16_kernel<BM, BN, true, false>), grid, block, s, a);
+  else if (bkc) LT_LAUNCH((lt_gemm_bf16_kernel<BM, BN, false, true>), grid, block, s, a);
+  else LT_LAUNCH((lt_gemm_bf16_kernel<BM, BN, false, false>), grid, block, s, a);
+  char name[48];
+  snprintf(name, sizeof(name), "lt_gemm_bf16_kernel<%d, %d, %s, %s>", BM, BN, akc ? "true" : "false", bkc ? "true" : "false");
+  note_kernel(name);
 }
 
 }  // namespace bf

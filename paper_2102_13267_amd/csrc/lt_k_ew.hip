@@ -353,16 +353,16 @@ hipError_t launch_split_post(const SplitPostArgs& a, uint32_t grid, hipStream_t 
   if (make_split_stream_args(a, &sa)) {
     const uint64_t tiles = (a.prog.n + 1023) / 1024;
     const dim3 g2((uint32_t)std::max<uint64_t>(1, std::min<uint64_t>((tiles + 1) / 2, 0x7fffffffull)));
-    if (sa.n_fin == 0u && sa.n_bin == 0u) hipLaunchKernelGGL((lt_split_post_stream_kernel<0, 0>), g2, b, 0, s, sa);
-    else if (sa.n_fin == 0u) hipLaunchKernelGGL((lt_split_post_stream_kernel<0, 1>), g2, b, 0, s, sa);
-    else if (sa.n_bin == 0u) hipLaunchKernelGGL((lt_split_post_stream_kernel<2, 0>), g2, b, 0, s, sa);
-    else hipLaunchKernelGGL((lt_split_post_stream_kernel<2, 1>), g2, b, 0, s, sa);
+    if (sa.n_fin == 0u && sa.n_bin == 0u) LT_LAUNCH((lt_split_post_stream_kernel<0, 0>), g2, b, s, sa);
+    else if (sa.n_fin == 0u) LT_LAUNCH((lt_split_post_stream_kernel<0, 1>), g2, b, s, sa);
+    else if (sa.n_bin == 0u) LT_LAUNCH((lt_split_post_stream_kernel<2, 0>), g2, b, s, sa);
+    else LT_LAUNCH((lt_split_post_stream_kernel<2, 1>), g2, b, s, sa);
     return hipGetLastError();
   }
   // whole 4-vectors of partials need 16-byte aligned splits
   const bool fast = a.prog.fast && a.prog.n_in <= 4u && (a.stride % 4u) == 0u;
-  if (fast) hipLaunchKernelGGL((lt_split_post_kernel<4, true>), g, b, 0, s, a);
-  else hipLaunchKernelGGL((lt_split_post_kernel<8, false>), g, b, 0, s, a);
+  if (fast) LT_LAUNCH((lt_split_post_kernel<4, true>), g, b, s, a);
+  else LT_LAUNCH((lt_split_post_kernel<8, false>), g, b, s, a);
   return hipGetLastError();
 }
 
@@ -373,8 +373,8 @@ hipError_t launch_ew(const EwArgs& a, uint32_t grid, hipStream_t s) {
   EwStreamArgs sa;
   if (make_stream_args(p, kBF16, &sa)) {
     const dim3 g2((uint32_t)std::max<uint64_t>(1, std::min<uint64_t>((p.n + 2047) / 2048, 0x7fffffffull)));
-    if (sa.pad <= 2u) hipLaunchKernelGGL((lt_ew_stream_bf16_kernel<2>), g2, b, 0, s, sa);
-    else hipLaunchKernelGGL((lt_ew_stream_bf16_kernel<4>), g2, b, 0, s, sa);
+    if (sa.pad <= 2u) LT_LAUNCH((lt_ew_stream_bf16_kernel<2>), g2, b, s, sa);
+    else LT_LAUNCH((lt_ew_stream_bf16_kernel<4>), g2, b, s, sa);
     return hipGetLastError();
   }
   if (make_stream_args(p, kF32, &sa)) {
@@ -383,17 +383,17 @@ hipError_t launch_ew(const EwArgs& a, uint32_t grid, hipStream_t s) {
     // walking the same tiles with a grid stride (the loop stays for spaces beyond 2^31 trips)
     const dim3 g2((uint32_t)std::max<uint64_t>(1, std::min<uint64_t>((tiles + 1) / 2, 0x7fffffffull)));
     const bool nt = p.n * 4u * (uint64_t)(p.n_in + p.n_out) > (256ull << 20);   // beyond the 256 MiB last-level cache
-    if (sa.pad <= 2u && nt) hipLaunchKernelGGL((lt_ew_stream_kernel<2, true>), g2, b, 0, s, sa);
-    else if (sa.pad <= 2u) hipLaunchKernelGGL((lt_ew_stream_kernel<2, false>), g2, b, 0, s, sa);
-    else if (nt) hipLaunchKernelGGL((lt_ew_stream_kernel<4, true>), g2, b, 0, s, sa);
-    else hipLaunchKernelGGL((lt_ew_stream_kernel<4, false>), g2, b, 0, s, sa);
+    if (sa.pad <= 2u && nt) LT_LAUNCH((lt_ew_stream_kernel<2, true>), g2, b, s, sa);
+    else if (sa.pad <= 2u) LT_LAUNCH((lt_ew_stream_kernel<2, false>), g2, b, s, sa);
+    else if (nt) LT_LAUNCH((lt_ew_stream_kernel<4, true>), g2, b, s, sa);
+    else LT_LAUNCH((lt_ew_stream_kernel<4, false>), g2, b, s, sa);
     return hipGetLastError();
   }
-  if (f16 && p.all_f32 && p.n_in <= 4u) hipLaunchKernelGGL((lt_ew_kernel<16, 4, true, true>), g, b, 0, s, a);
-  else if (f16 && p.all_f32 && p.n_in <= 6u) hipLaunchKernelGGL((lt_ew_kernel<16, 6, true, true>), g, b, 0, s, a);
-  else if (f16 && p.all_f32) hipLaunchKernelGGL((lt_ew_kernel<16, 8, true, true>), g, b, 0, s, a);
-  else if (f16) hipLaunchKernelGGL((lt_ew_kernel<16, 8, true, false>), g, b, 0, s, a);
-  else hipLaunchKernelGGL((lt_ew_kernel<32, 8, false, false>), g, b, 0, s, a);
+  if (f16 && p.all_f32 && p.n_in <= 4u) LT_LAUNCH((lt_ew_kernel<16, 4, true, true>), g, b, s, a);
+  else if (f16 && p.all_f32 && p.n_in <= 6u) LT_LAUNCH((lt_ew_kernel<16, 6, true, true>), g, b, s, a);
+  else if (f16 && p.all_f32) LT_LAUNCH((lt_ew_kernel<16, 8, true, true>), g, b, s, a);
+  else if (f16) LT_LAUNCH((lt_ew_kernel<16, 8, true, false>), g, b, s, a);
+  else LT_LAUNCH((lt_ew_kernel<32, 8, false, false>), g, b, s, a);
   return hipGetLastError();
 }
 
@@ -421,9 +421,9 @@ __global__ __launch_bounds__(kBlock) void lt_slice_update_kernel(const SliceArgs
 hipError_t launch_slice_update(const SliceArgs& a, uint32_t grid, hipStream_t s) {
   if (a.n == 0) return hipSuccess;
   if (!a.upd || !a.out || (!a.window_only && !a.base) || a.start + a.len > a.dim || grid == 0) return hipErrorInvalidValue;
-  if (a.elem_bytes == 4) hipLaunchKernelGGL(lt_slice_update_kernel<uint32_t>, dim3(grid), dim3(kBlock), 0, s, a);
-  else if (a.elem_bytes == 2) hipLaunchKernelGGL(lt_slice_update_kernel<uint16_t>, dim3(grid), dim3(kBlock), 0, s, a);
-  else if (a.elem_bytes == 8) hipLaunchKernelGGL(lt_slice_update_kernel<uint64_t>, dim3(grid), dim3(kBlock), 0, s, a);
+  if (a.elem_bytes == 4) LT_LAUNCH(lt_slice_update_kernel<uint32_t>, dim3(grid), dim3(kBlock), s, a);
+  else if (a.elem_bytes == 2) LT_LAUNCH(lt_slice_update_kernel<uint16_t>, dim3(grid), dim3(kBlock), s, a);
+  else if (a.elem_bytes == 8) LT_LAUNCH(lt_slice_update_kernel<uint64_t>, dim3(grid), dim3(kBlock), s, a);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

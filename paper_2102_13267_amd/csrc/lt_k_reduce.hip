@@ -456,13 +456,13 @@ hipError_t launch_row_reduce(const RowArgs& args, uint32_t grid, hipStream_t s) 
   a.vin[0] = a.vin[1] = a.rin = a.n_vin = a.n_rin = 0u;
   if (row_stream_args(&a, &grid)) {
     const dim3 g(grid), b(kBlock);
-    if (a.n_vin == 1u && a.n_rin == 0u) hipLaunchKernelGGL((lt_row_reduce_stream_kernel<1, 0>), g, b, 0, s, a);
-    else if (a.n_vin == 1u) hipLaunchKernelGGL((lt_row_reduce_stream_kernel<1, 1>), g, b, 0, s, a);
-    else if (a.n_rin == 0u) hipLaunchKernelGGL((lt_row_reduce_stream_kernel<2, 0>), g, b, 0, s, a);
-    else hipLaunchKernelGGL((lt_row_reduce_stream_kernel<2, 1>), g, b, 0, s, a);
+    if (a.n_vin == 1u && a.n_rin == 0u) LT_LAUNCH((lt_row_reduce_stream_kernel<1, 0>), g, b, s, a);
+    else if (a.n_vin == 1u) LT_LAUNCH((lt_row_reduce_stream_kernel<1, 1>), g, b, s, a);
+    else if (a.n_rin == 0u) LT_LAUNCH((lt_row_reduce_stream_kernel<2, 0>), g, b, s, a);
+    else LT_LAUNCH((lt_row_reduce_stream_kernel<2, 1>), g, b, s, a);
     return hipGetLastError();
   }
-  hipLaunchKernelGGL(lt_row_reduce_kernel, dim3(grid), dim3(kBlock), 0, s, args);
+  LT_LAUNCH(lt_row_reduce_kernel, dim3(grid), dim3(kBlock), s, args);
   return hipGetLastError();
 }
 hipError_t launch_all_reduce(const AllArgs& a, uint32_t grid, hipStream_t s) {
@@ -470,15 +470,15 @@ hipError_t launch_all_reduce(const AllArgs& a, uint32_t grid, hipStream_t s) {
   const int kind = stream_kind(a.pro);
   const uint32_t n_in = a.pro.n_in;
   const bool two = a.pro.n_slots <= 8u;   // the program fits half a register file: two 4-vectors per dispatch
-  if (kind == 1 && n_in == 1u && two) hipLaunchKernelGGL((lt_all_reduce_kernel<32, 1, 8, false, 4>), g, b, 0, s, a);
-  else if (kind == 1 && n_in == 1u) hipLaunchKernelGGL((lt_all_reduce_kernel<16, 1, 8, false, 1>), g, b, 0, s, a);
-  else if (kind == 1 && n_in == 2u && two) hipLaunchKernelGGL((lt_all_reduce_kernel<32, 2, 4, false, 4>), g, b, 0, s, a);
-  else if (kind == 1 && n_in == 2u) hipLaunchKernelGGL((lt_all_reduce_kernel<16, 2, 4, false, 1>), g, b, 0, s, a);
-  else if (kind == 2 && n_in == 1u && two) hipLaunchKernelGGL((lt_all_reduce_kernel<32, 1, 8, true, 4>), g, b, 0, s, a);
-  else if (kind == 2 && n_in == 1u) hipLaunchKernelGGL((lt_all_reduce_kernel<16, 1, 8, true, 1>), g, b, 0, s, a);
-  else if (kind == 2 && n_in == 2u && two) hipLaunchKernelGGL((lt_all_reduce_kernel<32, 2, 8, true, 4>), g, b, 0, s, a);
-  else if (kind == 2 && n_in == 2u) hipLaunchKernelGGL((lt_all_reduce_kernel<16, 2, 8, true, 1>), g, b, 0, s, a);
-  else hipLaunchKernelGGL((lt_all_reduce_kernel<16, 0, 1, false, 1>), g, b, 0, s, a);
+  if (kind == 1 && n_in == 1u && two) LT_LAUNCH((lt_all_reduce_kernel<32, 1, 8, false, 4>), g, b, s, a);
+  else if (kind == 1 && n_in == 1u) LT_LAUNCH((lt_all_reduce_kernel<16, 1, 8, false, 1>), g, b, s, a);
+  else if (kind == 1 && n_in == 2u && two) LT_LAUNCH((lt_all_reduce_kernel<32, 2, 4, false, 4>), g, b, s, a);
+  else if (kind == 1 && n_in == 2u) LT_LAUNCH((lt_all_reduce_kernel<16, 2, 4, false, 1>), g, b, s, a);
+  else if (kind == 2 && n_in == 1u && two) LT_LAUNCH((lt_all_reduce_kernel<32, 1, 8, true, 4>), g, b, s, a);
+  else if (kind == 2 && n_in == 1u) LT_LAUNCH((lt_all_reduce_kernel<16, 1, 8, true, 1>), g, b, s, a);
+  else if (kind == 2 && n_in == 2u && two) LT_LAUNCH((lt_all_reduce_kernel<32, 2, 8, true, 4>), g, b, s, a);
+  else if (kind == 2 && n_in == 2u) LT_LAUNCH((lt_all_reduce_kernel<16, 2, 8, true, 1>), g, b, s, a);
+  else LT_LAUNCH((lt_all_reduce_kernel<16, 0, 1, false, 1>), g, b, s, a);
   return hipGetLastError();
 }
 // Host side: a program whose inputs are one or two whole tensors of one element type plus one or
@@ -511,18 +511,18 @@ hipError_t launch_col_reduce(const ColArgs& args, uint32_t grid_x, uint32_t grid
   a.vin[0] = 0u; a.vin[1] = 1u; a.cin[0] = a.cin[1] = 0u;
   const int kind = (a.cols % 4u) == 0u ? stream_kind(a.pro) : 0;
   const uint32_t n_in = a.pro.n_in;
-  if (kind == 1 && n_in == 1u) hipLaunchKernelGGL((lt_col_reduce_kernel<16, 1, 8, false>), g, b, 0, s, a);
-  else if (kind == 1 && n_in == 2u) hipLaunchKernelGGL((lt_col_reduce_kernel<16, 2, 4, false>), g, b, 0, s, a);
-  else if (kind == 2 && n_in == 1u) hipLaunchKernelGGL((lt_col_reduce_kernel<16, 1, 8, true>), g, b, 0, s, a);
-  else if (kind == 2 && n_in == 2u) hipLaunchKernelGGL((lt_col_reduce_kernel<16, 2, 8, true>), g, b, 0, s, a);
+  if (kind == 1 && n_in == 1u) LT_LAUNCH((lt_col_reduce_kernel<16, 1, 8, false>), g, b, s, a);
+  else if (kind == 1 && n_in == 2u) LT_LAUNCH((lt_col_reduce_kernel<16, 2, 4, false>), g, b, s, a);
+  else if (kind == 2 && n_in == 1u) LT_LAUNCH((lt_col_reduce_kernel<16, 1, 8, true>), g, b, s, a);
+  else if (kind == 2 && n_in == 2u) LT_LAUNCH((lt_col_reduce_kernel<16, 2, 8, true>), g, b, s, a);
   else {
     const int mk = mixed_kind(&a);
     const bool four = a.pro.n_slots <= 8u;   // the program fits a quarter of a 32-wide register file
-    if (mk == 1 && four) hipLaunchKernelGGL((lt_col_reduce_kernel<32, 2, 4, false, 2>), g, b, 0, s, a);
-    else if (mk == 1) hipLaunchKernelGGL((lt_col_reduce_kernel<16, 2, 4, false, 2>), g, b, 0, s, a);
-    else if (mk == 2 && four) hipLaunchKernelGGL((lt_col_reduce_kernel<32, 2, 8, true, 2>), g, b, 0, s, a);
-    else if (mk == 2) hipLaunchKernelGGL((lt_col_reduce_kernel<16, 2, 8, true, 2>), g, b, 0, s, a);
-    else hipLaunchKernelGGL((lt_col_reduce_kernel<16, 0, 1, false>), g, b, 0, s, a);
+    if (mk == 1 && four) LT_LAUNCH((lt_col_reduce_kernel<32, 2, 4, false, 2>), g, b, s, a);
+    else if (mk == 1) LT_LAUNCH((lt_col_reduce_kernel<16, 2, 4, false, 2>), g, b, s, a);
+    else if (mk == 2 && four) LT_LAUNCH((lt_col_reduce_kernel<32, 2, 8, true, 2>), g, b, s, a);
+    else if (mk == 2) LT_LAUNCH((lt_col_reduce_kernel<16, 2, 8, true, 2>), g, b, s, a);
+    else LT_LAUNCH((lt_col_reduce_kernel<16, 0, 1, false>), g, b, s, a);
   }
   return hipGetLastError();
 }

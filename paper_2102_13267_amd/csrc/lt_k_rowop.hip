@@ -3,6 +3,8 @@
 // cross-wave step of the reductions.
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
+
 #include "lt_launch.h"
 #include "lt_reduce.h"
 
@@ -247,9 +249,12 @@ __global__ __launch_bounds__(kBlock) void lt_row_op_kernel(const RowOpArgs a) {
 
 template <int OP, int TPR>
 static void launch_io(const RowOpArgs& a, int io, uint32_t grid, hipStream_t s) {
-  if (io == 1) hipLaunchKernelGGL((lt_row_op_kernel<OP, TPR, 1>), dim3(grid), dim3(kBlock), 0, s, a);
-  else if (io == 2) hipLaunchKernelGGL((lt_row_op_kernel<OP, TPR, 2>), dim3(grid), dim3(kBlock), 0, s, a);
-  else hipLaunchKernelGGL((lt_row_op_kernel<OP, TPR, 0>), dim3(grid), dim3(kBlock), 0, s, a);
+  if (io == 1) LT_LAUNCH((lt_row_op_kernel<OP, TPR, 1>), dim3(grid), dim3(kBlock), s, a);
+  else if (io == 2) LT_LAUNCH((lt_row_op_kernel<OP, TPR, 2>), dim3(grid), dim3(kBlock), s, a);
+  else LT_LAUNCH((lt_row_op_kernel<OP, TPR, 0>), dim3(grid), dim3(kBlock), s, a);
+  char name[48];
+  snprintf(name, sizeof(name), "lt_row_op_kernel<%d, %d, %d>", (int)OP, (int)TPR, io == 1 ? 1 : io == 2 ? 2 : 0);
+  note_kernel(name);
 }
 
 template <int OP>

@@ -22,5 +22,17 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s);   // 128 x 128 ti
 constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
 hipError_t static_scratch(int device, void** ptr, size_t* bytes);
 hipError_t launch_fill_u32(uint32_t* p, uint32_t n, uint32_t value, hipStream_t s);
+
+// Name of the kernel instance that the calling thread launched last (per-launch records and
+// profiles name the instance, not just its family).
+void note_kernel(const char* name);
+const char* last_kernel();
 }  // namespace ltk
+
+// Launch kernel instance K and note its name as written (template arguments included).
+#define LT_LAUNCH(K, GRID, BLOCK, STREAM, ARGS)          \
+  do {                                                   \
+    ::ltk::note_kernel(#K);                              \
+    hipLaunchKernelGGL(K, GRID, BLOCK, 0, STREAM, ARGS); \
+  } while (0)
 #endif

@@ -95,7 +95,8 @@ def test_wide_column_reductions_move_and_their_consumers_wait():
     assert kinds.count("COL") == 1
     col = next(l for l in sched if l["kind"] == "COL")
     assert col["stream"] > 0
-    reader = [l for l in sched if l["kind"] == "MM"][-1]     # z's contraction: its epilogue reads s
+    # z's contraction reads s in its post program (the second launch, when k is split over workgroups)
+    reader = [l for l in sched if l["kind"] in ("MM", "SPLITPOST") and set(l["reads"]) & set(col["writes"])][-1]
     assert reader["i"] > col["i"] and "inputs=" in plan[reader["region"]]
     # ordered behind the reduction: the same stream, an event of the reduction, or an event of a
     # later launch of the reduction's stream

@@ -108,14 +108,24 @@ __global__ __launch_bounds__(kBlock) void lt_ew_stream_kernel(const EwStreamArgs
 }
 
 // The same for programs whose plain inputs are all bf16 (outputs of any type): a lane takes 8
-// consecutive elements -- one 16-byte load per input -- which are the two 4-vectors of one
-// interpreter dispatch; a workgroup takes one tile of 2048 elements.
+// consecutive elements -- one 16-byte load per input, one 16-byte store per bf16 output -- which
+// are the two 4-vectors of one interpreter dispatch; a tile is 2048 elements.  An interpreted
+// wave retires an instruction every 10 to 12 cycles (scalar decode, branches, relative register
+// addressing), so what bounds this kernel is instructions per tile divided by waves per SIMD, not
+// memory latency: a 134 MB multiply ran at 2.6 TB/s with one short-lived wave per tile (every
+// wave paid the set-up of the program's scalars and pointers, and padded input lists were
+// loaded and converted twice).  Hence: NV is the exact number of vector inputs; a workgroup walks
+// its tiles with a grid stride and asks for the next tile's inputs as soon as this tile's are in
+// the register file, so the loads fly while the program is interpreted; 8 values of an output
+// leave in one store.
 template <int NV>
-__global__ __launch_bounds__(kBlock) void lt_ew_stream_bf16_kernel(const EwStreamArgs a) {
+__global__ __launch_bounds__(kBlock, 4) void lt_ew_stream_bf16_kernel(const EwStreamArgs a) {
   const EwProg& p = a.prog;
-  const uint64_t n = p.n;   // a multiple of 8
+  const uint64_t n = p.n;   // a multiple of 8: a lane is either wholly inside or wholly outside
   constexpr uint64_t kTile = (uint64_t)kBlock * 2 * kVec;
   const uint64_t ntiles = (n + kTile - 1) / kTile;
+  uint64_t tile = blockIdx.x;
+  if (tile >= ntiles) return;
   const ProgRegs pr = load_prog_regs(p);
   const uint32_t n_code = p.n_code;
   const uint32_t lane = threadIdx.x * 2 * kVec;
@@ -130,22 +140,22 @@ __global__ __launch_bounds__(kBlock) void lt_ew_stream_bf16_kernel(const EwStrea
 #pragma unroll
   for (int j = 0; j < 2; ++j)
     if ((uint32_t)j < a.n_sin) sval[j] = *(const float*)p.in[a.sin[j]].ptr;
-  for (uint64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-    const uint64_t base = tile * kTile;
-    if ((uint64_t)lane >= n - base) continue;
-    typedef uint32_t U32x4 __attribute__((ext_vector_type(4)));
-    U32x4 v[NV];
+  typedef uint32_t U32x4 __attribute__((ext_vector_type(4)));
+  U32x4 v[NV];
+  bool live = (uint64_t)lane < n - tile * kTile;
 #pragma unroll
-    for (int j = 0; j < NV; ++j) v[j] = *(const U32x4*)(vp[j] + (base + lane) * 2u);
+  for (int j = 0; j < NV; ++j) v[j] = live ? *(const U32x4*)(vp[j] + (tile * kTile + lane) * 2u) : U32x4{0u, 0u, 0u, 0u};
+  for (;;) {
     RF<16> f = rf_zero<16>();
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
+      const U32x4 w = v[j];
       Quad q;
-      q.v[0] = __uint_as_float(v[j].x << 16); q.v[1] = __uint_as_float(v[j].x & 0xffff0000u);
-      q.v[2] = __uint_as_float(v[j].y << 16); q.v[3] = __uint_as_float(v[j].y & 0xffff0000u);
+      q.v[0] = __uint_as_float(w.x << 16); q.v[1] = __uint_as_float(w.x & 0xffff0000u);
+      q.v[2] = __uint_as_float(w.y << 16); q.v[3] = __uint_as_float(w.y & 0xffff0000u);
       f = rf_set<16>(f, vslot[j], q);
-      q.v[0] = __uint_as_float(v[j].z << 16); q.v[1] = __uint_as_float(v[j].z & 0xffff0000u);
-      q.v[2] = __uint_as_float(v[j].w << 16); q.v[3] = __uint_as_float(v[j].w & 0xffff0000u);
+      q.v[0] = __uint_as_float(w.z << 16); q.v[1] = __uint_as_float(w.z & 0xffff0000u);
+      q.v[2] = __uint_as_float(w.w << 16); q.v[3] = __uint_as_float(w.w & 0xffff0000u);
       f = rf_set<16>(f, vslot[j] + 8u, q);
     }
     for (uint32_t j = 0; j < a.n_sin; ++j) {
@@ -153,9 +163,38 @@ __global__ __launch_bounds__(kBlock) void lt_ew_stream_bf16_kernel(const EwStrea
       f = rf_set<16>(f, a.sin[j], q);
       f = rf_set<16>(f, a.sin[j] + 8u, q);
     }
+    // this tile's inputs are in the register file: ask for the next tile's.  A program that
+    // updates an input in place is safe: tiles are disjoint and a lane stores where it loaded.
+    const uint64_t cur = tile * kTile;
+    const bool cur_live = live;
+    tile += gridDim.x;
+    const bool more = tile < ntiles;
+    if (more) {
+      live = (uint64_t)lane < n - tile * kTile;
+#pragma unroll
+      for (int j = 0; j < NV; ++j) v[j] = live ? *(const U32x4*)(vp[j] + (tile * kTile + lane) * 2u) : U32x4{0u, 0u, 0u, 0u};
+    }
     f = interp<16, 2>(f, pr, n_code);
-    store_outputs<16, true, false, 0>(f, p, base, lane, kVec);
-    store_outputs<16, true, false, 8>(f, p, base, lane + (uint32_t)kVec, kVec);
+    if (cur_live) {
+#pragma unroll
+      for (int o = 0; o < kMaxOut; ++o) {
+        if ((uint32_t)o < p.n_out) {
+          const EwOut& out = p.out[o];
+          const Quad q0 = rf_get<16>(f, out.slot), q1 = rf_get<16>(f, out.slot + 8u);
+          if (out.scalar) {
+            if (cur + lane == 0) store_elem<false>(out.ptr, out.dtype, 0, q0.v[0]);
+          } else if (out.dtype == kBF16) {
+            const U32x4 u = {f32_to_bf16_pair(q0.v[0], q0.v[1]), f32_to_bf16_pair(q0.v[2], q0.v[3]),
+                             f32_to_bf16_pair(q1.v[0], q1.v[1]), f32_to_bf16_pair(q1.v[2], q1.v[3])};
+            *(U32x4*)((char*)out.ptr + (cur + lane) * 2u) = u;
+          } else {
+            store_vec4<false>(out.ptr, out.dtype, cur, lane, q0);
+            store_vec4<false>(out.ptr, out.dtype, cur, lane + (uint32_t)kVec, q1);
+          }
+        }
+      }
+    }
+    if (!more) break;
   }
 }
 
@@ -366,15 +405,22 @@ hipError_t launch_split_post(const SplitPostArgs& a, uint32_t grid, hipStream_t 
   return hipGetLastError();
 }
 
+static constexpr uint64_t kStreamGroups = 1024;   // 256 compute units x 4
+
 hipError_t launch_ew(const EwArgs& a, uint32_t grid, hipStream_t s) {
   const EwProg& p = a.prog;
   const dim3 g(grid), b(kBlock);
   const bool f16 = p.fast && p.n_slots <= 16u;
   EwStreamArgs sa;
   if (make_stream_args(p, kBF16, &sa)) {
-    const dim3 g2((uint32_t)std::max<uint64_t>(1, std::min<uint64_t>((p.n + 2047) / 2048, 0x7fffffffull)));
-    if (sa.pad <= 2u) LT_LAUNCH((lt_ew_stream_bf16_kernel<2>), g2, b, s, sa);
-    else LT_LAUNCH((lt_ew_stream_bf16_kernel<4>), g2, b, s, sa);
+    const uint64_t tiles = (p.n + 2047) / 2048;
+    // at most four workgroups per compute unit (what the registers allow to be resident): each
+    // walks its share of the tiles
+    const dim3 g2((uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(tiles, kStreamGroups)));
+    if (sa.pad == 1u) LT_LAUNCH(lt_ew_stream_bf16_kernel<1>, g2, b, s, sa);
+    else if (sa.pad == 2u) LT_LAUNCH(lt_ew_stream_bf16_kernel<2>, g2, b, s, sa);
+    else if (sa.pad == 3u) LT_LAUNCH(lt_ew_stream_bf16_kernel<3>, g2, b, s, sa);
+    else LT_LAUNCH(lt_ew_stream_bf16_kernel<4>, g2, b, s, sa);
     return hipGetLastError();
   }
   if (make_stream_args(p, kF32, &sa)) {

@@ -104,6 +104,7 @@ typedef struct {
   uint64_t arena_bytes_in_use, arena_bytes_peak;
   uint64_t live_tensors;
   uint64_t fallback_ops;   /* ops that went through the registered fallback (section 4.5) */
+  uint64_t replays;        /* lt_step_replay calls that ran (not counted as barriers)          */
 } lt_stats_t;
 
 /*
@@ -219,6 +220,48 @@ lt_status lt_device_ptr(lt_ctx* ctx, lt_tensor t, void** dptr);
 
 /* dtype / rank / dims (dims must have room for LT_MAX_RANK entries); any argument may be NULL. */
 lt_status lt_shape(lt_ctx* ctx, lt_tensor t, lt_dtype* dtype, int* rank, int64_t* dims);
+
+/*
+ * Running a step again without tracing it (section 7 of the paper lists this as future work: when
+ * the user guarantees that the computation has not changed, recording it can be skipped).
+ *
+ * lt_step_capture: a handle on the step that the LAST barrier of ctx ran -- its compiled plan, the
+ * tensors whose data were the plan's inputs (the trace's device_data leaves, in the order of the
+ * canonical numbering), the values of its non-special scalars (same order) and the tensors that
+ * received its results.  It holds no device memory and stays valid until lt_step_free, the
+ * context's shutdown, or a call that clears the plan cache (lt_set_fusion), after which
+ * lt_step_replay returns LT_ERR_ARG.  Errors: LT_ERR_ARG no barrier has run; LT_ERR_HANDLE an
+ * input tensor of the step has been released (it could not be named again);
+ * LT_ERR_UNSUPPORTED the plan writes over an input's buffer and the result does not belong to
+ * that same tensor (only x <- f(x) may be repeated in place).
+ *
+ * lt_step_replay: runs the plan on the CURRENT data of the same input tensors and binds the
+ * results to the same result tensors, exactly as the barrier did (donated inputs are updated in
+ * place, other results get fresh workspace memory, the tensors' previous results are released).
+ * scalars: NULL = the captured values, else n_scalars doubles in canonical order (lt_step_scalars
+ * gives the captured ones, e.g. to find the learning rate among them).  Nothing is recorded,
+ * cut, hashed or looked up.  The caller guarantees that tracing the step again would give the
+ * same trace; checked are only: no trace is pending (LT_ERR_ARG), every input still exists
+ * (LT_ERR_HANDLE) as plain data of the captured dtype, shape and donation flag (LT_ERR_SHAPE), an
+ * input updated in place is not shared with another tensor (LT_ERR_ARG).  On an error nothing has
+ * run.  Views of result tensors are brought up to date when they are next used, as after a
+ * barrier.  info may be NULL (hash, key_bytes, n_nodes, ns_hash and ns_lower are 0).
+ *
+ * lt_step_scalars: number of scalars of the step; copies up to cap captured values to out (out
+ * may be NULL).  -1 for a NULL step.
+ *
+ * lt_tensor_rebind: a data tensor made by lt_tensor_from_device now names other device memory of
+ * the same dtype and shape (the next batch), keeping its id, so that a captured step reads it.
+ * Ownership as for lt_tensor_from_device.  LT_ERR_ARG: a result tensor (library memory), a view,
+ * a tensor the pending trace has read, a misaligned or null pointer.
+ */
+typedef struct lt_step lt_step;
+lt_status lt_step_capture(lt_ctx* ctx, lt_step** out);
+lt_status lt_step_replay(lt_ctx* ctx, lt_step* step, const double* scalars, int n_scalars, int blocking,
+                         lt_barrier_info* info);
+int lt_step_scalars(const lt_step* step, double* out, int cap);
+void lt_step_free(lt_step* step);
+lt_status lt_tensor_rebind(lt_ctx* ctx, lt_tensor t, void* device_ptr);
 
 /*
  * Text form of the pending trace in the layout of figure 1(a) of the paper.  Writes at most

@@ -200,6 +200,7 @@ static Val use(lt_ctx* ctx, Handle* h) {
     Node n;
     n.dtype = h->dtype;
     n.rank = h->rank;
+    n.src = h->id;
     std::memcpy(n.dims, h->dims, sizeof(n.dims));
     if (h->kind == H_DATA) {
       n.op = OP_DEVICE_DATA;
@@ -369,6 +370,28 @@ lt_status lt_tensor_from_device(lt_ctx* ctx, void* dptr, lt_dtype dtype, int ran
   h->buf->donatable = (flags & LT_DONATABLE) != 0;
   h->buf->data_refs = 1;
   *out = h->id;
+  return LT_OK;
+}
+
+lt_status lt_tensor_rebind(lt_ctx* ctx, lt_tensor t, void* dptr) {
+  if (!ctx) return LT_ERR_ARG;
+  Handle* h = find(ctx, t, false);
+  if (!h) return fail(ctx, LT_ERR_HANDLE, "lt_tensor_rebind: unknown or released tensor id");
+  if (h->kind != H_DATA || !h->buf || h->view_base) return fail(ctx, LT_ERR_ARG, "lt_tensor_rebind: only a plain data tensor names device memory");
+  if (h->buf->owned) return fail(ctx, LT_ERR_ARG, "lt_tensor_rebind: the tensor's memory belongs to the library (a result), not to the caller");
+  if (h->memo_epoch == ctx->epoch && h->memo_node >= 0) return fail(ctx, LT_ERR_ARG, "lt_tensor_rebind: the pending trace reads this tensor: run a barrier first");
+  if (!dptr && ctx->device >= 0 && h->buf->bytes > 0) return fail(ctx, LT_ERR_ARG, "lt_tensor_rebind: null device pointer");
+  if (ctx->device >= 0 && ((uintptr_t)dptr & 15u)) return fail(ctx, LT_ERR_ARG, "lt_tensor_rebind: pointer must be 16-byte aligned");
+  // a buffer of its own: other tensors that share the old one (lt_assign) keep the old memory
+  auto nb = std::make_shared<Buffer>();
+  nb->ptr = dptr;
+  nb->bytes = h->buf->bytes;
+  nb->donatable = h->buf->donatable;
+  nb->data_refs = 1;
+  h->buf->data_refs -= 1;
+  h->buf = nb;
+  h->donor.reset();
+  h->version++;
   return LT_OK;
 }
 
@@ -982,7 +1005,9 @@ lt_status lt_set_fusion(lt_ctx* ctx, int on) {
           if (e) (void)hipEventDestroy(e);
   }
   ctx->cache.clear();
+  ctx->cache_generation++;
   ctx->last_plan = nullptr;
+  ctx->last_step = lt::StepRecord{};
   return LT_OK;
 }
 

@@ -179,14 +179,17 @@ static const char* kind_name(LaunchKind k) {
 // Bind this step's buffers and scalars into the cached plan and launch it.
 // use_static: reduction scratch and temporaries live in the library's static device scratch, only
 // results are placed in the caller's workspace; one stream, no events, nothing is created.
-static lt_status execute(lt_ctx* ctx, Plan* plan, const Cut& cut, std::vector<BufRef>* storage_bufs, bool use_static) {
+// params / scalars: the buffers of the plan's device parameters and the values of its
+// non-special scalars, in the order of the canonical numbering.
+static lt_status execute(lt_ctx* ctx, Plan* plan, const std::vector<BufRef>& params, const std::vector<double>& scalars,
+                         std::vector<BufRef>* storage_bufs, bool use_static) {
   const size_t ns = plan->storages.size();
   storage_bufs->assign(ns, nullptr);
   std::vector<void*> ptr(ns, nullptr);
   for (size_t s = 0; s < ns; ++s) {
     const Storage& st = plan->storages[s];
     if (st.param >= 0) {
-      (*storage_bufs)[s] = ctx->nodes[cut.param_nodes[st.param]].buffer;
+      (*storage_bufs)[s] = params[st.param];
       ptr[s] = (*storage_bufs)[s]->ptr;
     }
   }
@@ -323,7 +326,7 @@ static lt_status execute(lt_ctx* ctx, Plan* plan, const Cut& cut, std::vector<Bu
     }
     for (; sp < plan->scal_patches.size() && plan->scal_patches[sp].launch == li; ++sp) {
       const ScalPatch& p = plan->scal_patches[sp];
-      double v = ctx->nodes[cut.scalar_nodes[p.scalar]].value;
+      double v = scalars[p.scalar];
       float f = (float)(p.reciprocal ? 1.0 / v : v);
       std::memcpy(args.data() + p.offset, &f, sizeof(float));
     }
@@ -429,9 +432,29 @@ static lt_status barrier_impl(lt_ctx* ctx, int blocking, lt_barrier_info* info, 
     bucket.push_back(std::move(fresh));
   }
   const uint64_t t3 = now_ns();
-  std::vector<BufRef> bufs;
-  lt_status st = execute(ctx, plan, cut, &bufs, use_static);
+  std::vector<BufRef> bufs, params(cut.param_nodes.size());
+  std::vector<double> scalars(cut.scalar_nodes.size());
+  for (size_t k = 0; k < params.size(); ++k) params[k] = ctx->nodes[cut.param_nodes[k]].buffer;
+  for (size_t k = 0; k < scalars.size(); ++k) scalars[k] = ctx->nodes[cut.scalar_nodes[k]].value;
+  lt_status st = execute(ctx, plan, params, scalars, &bufs, use_static);
   if (st != LT_OK) return st;
+  // what a captured step needs of this barrier (lt_step_capture)
+  StepRecord& rec = ctx->last_step;
+  rec.plan = plan;
+  rec.generation = ctx->cache_generation;
+  rec.params.resize(params.size());
+  for (size_t k = 0; k < params.size(); ++k) {
+    const Node& n = ctx->nodes[cut.param_nodes[k]];
+    StepParam& sp = rec.params[k];
+    sp.tensor = n.src;
+    sp.dtype = n.dtype;
+    sp.rank = n.rank;
+    std::memcpy(sp.dims, n.dims, sizeof(sp.dims));
+    sp.donatable = params[k] && params[k]->donatable;
+  }
+  rec.scalars = scalars;
+  rec.roots.resize(cut.roots.size());
+  for (size_t r = 0; r < cut.roots.size(); ++r) rec.roots[r] = cut.roots[r]->id;
   // result binding: after the barrier every evaluated handle is plain data (or a scalar when
   // folding reduced it to one); a new IR graph starts (section 3)
   for (size_t r = 0; r < cut.roots.size(); ++r) {
@@ -490,6 +513,130 @@ lt_status lt_barrier_static(lt_ctx* ctx, int blocking, lt_barrier_info* info) {
   if (!ctx) return LT_ERR_ARG;
   if (!ctx->static_scratch) return fail(ctx, LT_ERR_DEVICE, "lt_barrier_static: " + ctx->static_scratch_error);
   return barrier_impl(ctx, blocking, info, true);
+}
+
+// ---- a captured step (section 7 of the paper: skip tracing when the caller guarantees the same
+// computation) ---------------------------------------------------------------------------------
+
+lt_status lt_step_capture(lt_ctx* ctx, lt_step** out) {
+  if (!ctx || !out) return LT_ERR_ARG;
+  const StepRecord& rec = ctx->last_step;
+  if (!rec.plan || rec.generation != ctx->cache_generation) return fail(ctx, LT_ERR_ARG, "lt_step_capture: no barrier has run (or its plan is gone)");
+  std::unique_ptr<lt_step> step(new lt_step);
+  step->ctx = ctx;
+  step->rec = rec;
+  const Plan* plan = rec.plan;
+  step->written.assign(rec.params.size(), 0);
+  for (const PtrPatch& p : plan->ptr_patches)
+    if (p.write && p.storage >= 0 && plan->storages[p.storage].param >= 0) step->written[plan->storages[p.storage].param] = 1;
+  // every input must be a tensor that can be named again
+  for (size_t k = 0; k < rec.params.size(); ++k) {
+    auto it = ctx->handles.find(rec.params[k].tensor);
+    if (it == ctx->handles.end() || it->second.released)
+      return fail(ctx, LT_ERR_HANDLE, "lt_step_capture: input " + std::to_string(k) + " of the step was a tensor that has been released since: keep a step's inputs alive");
+  }
+  // a buffer the plan overwrites must come back as the value of the tensor it was taken from
+  // (x <- f(x)): any other tensor would see its data change under it on the next run
+  for (size_t r = 0; r < plan->roots.size(); ++r) {
+    const RootBind& rb = plan->roots[r];
+    if (rb.kind != RootBind::STORAGE) continue;
+    const int param = plan->storages[rb.index].param;
+    if (param >= 0 && rec.roots[r] != rec.params[param].tensor)
+      return fail(ctx, LT_ERR_UNSUPPORTED, "lt_step_capture: the step writes a result over the buffer of input " + std::to_string(param) +
+                                               ", and the result belongs to another tensor");
+  }
+  for (size_t k = 0; k < rec.params.size(); ++k) {
+    if (!step->written[k]) continue;
+    bool back = false;
+    for (size_t r = 0; r < plan->roots.size(); ++r)
+      back |= plan->roots[r].kind == RootBind::STORAGE && plan->storages[plan->roots[r].index].param == (int)k;
+    if (!back) return fail(ctx, LT_ERR_UNSUPPORTED, "lt_step_capture: the step uses the buffer of input " + std::to_string(k) + " as scratch");
+  }
+  *out = step.release();
+  return LT_OK;
+}
+
+int lt_step_scalars(const lt_step* step, double* out, int cap) {
+  if (!step) return -1;
+  const int n = (int)step->rec.scalars.size();
+  for (int i = 0; i < n && i < cap && out; ++i) out[i] = step->rec.scalars[i];
+  return n;
+}
+
+void lt_step_free(lt_step* step) { delete step; }
+
+lt_status lt_step_replay(lt_ctx* ctx, lt_step* step, const double* scalars, int n_scalars, int blocking, lt_barrier_info* info) {
+  if (!ctx || !step || step->ctx != ctx) return LT_ERR_ARG;
+  const uint64_t t0 = now_ns();
+  StepRecord& rec = step->rec;
+  if (rec.generation != ctx->cache_generation) return fail(ctx, LT_ERR_ARG, "lt_step_replay: the plan cache has been cleared since the step was captured");
+  if (!ctx->nodes.empty()) return fail(ctx, LT_ERR_ARG, "lt_step_replay: a trace is pending: run a barrier first");
+  if (scalars && n_scalars != (int)rec.scalars.size())
+    return fail(ctx, LT_ERR_ARG, "lt_step_replay: the step has " + std::to_string(rec.scalars.size()) + " scalars");
+  Plan* plan = rec.plan;
+  std::vector<BufRef> params(rec.params.size());
+  for (size_t k = 0; k < params.size(); ++k) {
+    const StepParam& sp = rec.params[k];
+    auto it = ctx->handles.find(sp.tensor);
+    if (it == ctx->handles.end() || it->second.released)
+      return fail(ctx, LT_ERR_HANDLE, "lt_step_replay: input " + std::to_string(k) + " has been released");
+    const Handle& h = it->second;
+    bool same = h.kind == H_DATA && h.buf && h.dtype == sp.dtype && h.rank == sp.rank && h.buf->donatable == sp.donatable;
+    for (int d = 0; same && d < sp.rank; ++d) same = h.dims[d] == sp.dims[d];
+    if (!same) return fail(ctx, LT_ERR_SHAPE, "lt_step_replay: input " + std::to_string(k) + " is not plain data of the captured dtype, shape and donation flag any more");
+    if (step->written[k] && h.buf->data_refs != 1)
+      return fail(ctx, LT_ERR_ARG, "lt_step_replay: input " + std::to_string(k) + " is updated in place and shares its buffer with another tensor now");
+    params[k] = h.buf;
+  }
+  std::vector<double> vals = rec.scalars;
+  if (scalars) vals.assign(scalars, scalars + n_scalars);
+  const uint64_t t1 = now_ns();
+  std::vector<BufRef> bufs;
+  lt_status st = execute(ctx, plan, params, vals, &bufs, false);
+  if (st != LT_OK) return st;
+  for (size_t r = 0; r < rec.roots.size(); ++r) {
+    auto it = ctx->handles.find(rec.roots[r]);
+    if (it == ctx->handles.end()) continue;   // released since: the value is dropped
+    Handle* hd = &it->second;
+    const RootBind& rb = plan->roots[r];
+    BufRef nb;
+    if (rb.kind == RootBind::STORAGE) nb = bufs[rb.index];
+    else if (rb.kind == RootBind::PARAM_ALIAS) nb = params[rb.index];
+    if (nb) nb->data_refs += 1;
+    if (hd->kind == H_DATA && hd->buf) hd->buf->data_refs -= 1;
+    hd->buf = nb;
+    hd->node = -1;
+    hd->slot = 0;
+    hd->donor.reset();
+    hd->version++;
+    if (nb) {
+      hd->kind = H_DATA;
+    } else {
+      hd->kind = H_SCALAR;
+      hd->value = rb.kind == RootBind::CONST ? rb.value : vals[rb.index];
+    }
+  }
+  bufs.clear();
+  const uint64_t t2 = now_ns();
+  if (blocking && ctx->device >= 0) {
+    hipError_t e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) return fail(ctx, LT_ERR_DEVICE, std::string("hipStreamSynchronize: ") + hipGetErrorString(e));
+  }
+  ctx->last_plan = plan;
+  ctx->stats.replays++;
+  ctx->stats.regions_launched += plan->n_regions;
+  if (info) {
+    *info = lt_barrier_info{};
+    info->cache_hit = 1;
+    info->n_roots = (int32_t)rec.roots.size();
+    info->n_regions = plan->n_regions;
+    info->n_launches = (int32_t)plan->launches.size();
+    info->bytes_planned = plan->bytes_planned;
+    info->flops_planned = plan->flops_planned;
+    info->ns_collect = t1 - t0;
+    info->ns_launch = t2 - t1;
+  }
+  return LT_OK;
 }
 
 lt_status lt_fetch(lt_ctx* ctx, lt_tensor t, void* host_dst, size_t nbytes) {

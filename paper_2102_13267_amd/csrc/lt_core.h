@@ -82,6 +82,7 @@ struct Node {
   Val ins[kMaxIns];
   BufRef buffer;       // OP_DEVICE_DATA
   double value = 0;    // OP_SCALAR_PARAM: the dynamic value (not part of the graph's identity)
+  uint64_t src = 0;    // leaves: id of the tensor the leaf was made from (a captured step names its inputs by it)
 };
 
 enum HandleKind : uint8_t { H_PENDING = 0, H_DATA = 1, H_SCALAR = 2 };
@@ -167,7 +168,30 @@ struct Plan {
   std::vector<hipEvent_t> events;    // one per launch with `record` set (created on first use)
 };
 
+// What a captured step has to know about the barrier it repeats: the plan, the tensors whose
+// data were the plan's device parameters (canonical order) with what the plan assumed of them,
+// the non-special scalars, and the tensors that received the roots.
+struct StepParam {
+  uint64_t tensor = 0;
+  uint8_t dtype = 0, rank = 0;
+  int64_t dims[LT_MAX_RANK] = {0};
+  bool donatable = false;
+};
+struct StepRecord {
+  Plan* plan = nullptr;
+  uint64_t generation = 0;           // of the plan cache (plans die when the cache is cleared)
+  std::vector<StepParam> params;
+  std::vector<double> scalars;
+  std::vector<uint64_t> roots;       // tensor ids, in the plan's root order
+};
+
 }  // namespace lt
+
+struct lt_step {
+  lt_ctx* ctx = nullptr;
+  lt::StepRecord rec;
+  std::vector<uint8_t> written;      // per parameter: the plan writes its buffer (a donated input)
+};
 
 struct lt_ctx {
   int device = -1;
@@ -180,6 +204,8 @@ struct lt_ctx {
   std::unordered_map<uint64_t, std::vector<std::unique_ptr<lt::Plan>>> cache;
   lt::Plan* last_plan = nullptr;
   std::vector<uint8_t> last_key;
+  uint64_t cache_generation = 0;             // bumped whenever the plan cache is cleared
+  lt::StepRecord last_step;                  // the last barrier, for lt_step_capture
   lt_stats_t stats{};
   std::string err;
   float* red_partials = nullptr;             // reduction scratch inside the workspace

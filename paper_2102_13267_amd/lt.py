@@ -46,7 +46,7 @@ class BarrierInfo(C.Structure):
 class Stats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in (
         "barriers", "cache_hits", "cache_misses", "nodes_recorded", "regions_launched", "kernels_launched",
-        "ns_lowering_total", "arena_bytes_in_use", "arena_bytes_peak", "live_tensors", "fallback_ops")]
+        "ns_lowering_total", "arena_bytes_in_use", "arena_bytes_peak", "live_tensors", "fallback_ops", "replays")]
 
 
 class TensorDesc(C.Structure):
@@ -62,6 +62,42 @@ OP_CUSTOM = 1024
 class LaunchRecord(C.Structure):
     _fields_ = [("kernel", C.c_char * 48), ("region", C.c_int32), ("ms", C.c_float),
                 ("bytes", C.c_uint64), ("flops", C.c_uint64)]
+
+
+class Step:
+    """A captured step (lt_step): `replay` runs its plan again on the current data of the same
+    tensors; `scalars` are the captured values of its non-special scalars in canonical order."""
+
+    def __init__(self, ctx, handle):
+        self._ctx, self._h = ctx, handle
+        n = ctx._lib.lt_step_scalars(handle, None, 0)
+        buf = (C.c_double * max(1, n))()
+        ctx._lib.lt_step_scalars(handle, buf, n)
+        self.scalars = [buf[i] for i in range(n)]
+
+    def replay(self, scalars=None, blocking=True) -> "BarrierInfo":
+        ctx = self._ctx
+        ctx._flush()
+        info = BarrierInfo()
+        if scalars is None:
+            arr, n = None, 0
+        else:
+            n = len(scalars)
+            arr = (C.c_double * max(1, n))(*[float(v) for v in scalars])
+        ctx._check(ctx._lib.lt_step_replay(ctx._h, self._h, arr, n, 1 if blocking else 0, C.byref(info)))
+        ctx._kept.clear()
+        return info
+
+    def free(self):
+        if self._h:
+            self._ctx._lib.lt_step_free(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
 
 
 class LtError(RuntimeError):
@@ -116,11 +152,17 @@ def load_library():
         "lt_set_fusion": [P, i32],
         "lt_set_fallback": [P, FALLBACK_FN, P],
         "lt_last_launches": [P, C.POINTER(LaunchRecord), i32, C.POINTER(i32)],
+        "lt_step_capture": [P, C.POINTER(P)],
+        "lt_step_replay": [P, P, C.POINTER(C.c_double), i32, i32, C.POINTER(BarrierInfo)],
+        "lt_step_scalars": [P, C.POINTER(C.c_double), i32],
+        "lt_tensor_rebind": [P, u64, P],
     }
     for name, argtypes in sig.items():
         fn = getattr(lib, name)
         fn.argtypes = argtypes
         fn.restype = C.c_int
+    lib.lt_step_free.argtypes = [P]
+    lib.lt_step_free.restype = None
     lib.lt_last_error.argtypes = [P]
     lib.lt_last_error.restype = C.c_char_p
     # the recording fast path makes the same calls from C; it gets the entry points' addresses
@@ -412,6 +454,24 @@ class Context:
         self._check(self._lib.lt_barrier_static(self._h, 1 if blocking else 0, C.byref(info)))
         self._kept.clear()
         return info
+
+    # ---- a captured step (section 7 of the paper: no tracing when the computation is the same) --
+    def capture_step(self) -> "Step":
+        """lt_step_capture: the step that the last barrier ran, to be run again with Step.replay."""
+        h = C.c_void_p()
+        self._check(self._lib.lt_step_capture(self._h, C.byref(h)))
+        return Step(self, h)
+
+    def rebind(self, t: Tensor, array):
+        """lt_tensor_rebind: `t` now names the device memory of `array` (a torch tensor of the same
+        dtype and shape on this device), keeping its id -- the next batch of a captured step."""
+        a = array.contiguous()
+        if tuple(a.shape) != tuple(t.shape):
+            raise ValueError(f"rebind: shape {tuple(a.shape)} is not the tensor's {tuple(t.shape)}")
+        self._check(self._lib.lt_tensor_rebind(self._h, t.tid, C.c_void_p(a.data_ptr())))
+        if t._keep is not None:
+            self._kept.append(t._keep)   # a step still in flight may read the old memory
+        t._keep = a
 
     def fetch(self, t: Tensor) -> np.ndarray:
         """Blocking barrier if needed, then device-to-host copy.  bf16 comes back as float32."""

@@ -1,0 +1,215 @@
+"""A captured step run again without tracing (section 7 of the paper: tracing can be skipped when
+the user guarantees the same computation).  Host bookkeeping on the null device; on the GPU the
+replayed steps against the same steps traced, bit for bit, and against the eager oracle."""
+import numpy as np
+import pytest
+
+from paper_2102_13267_amd import Context, LtError
+from workloads import programs
+from workloads.inputs import c2_inputs
+
+NAMES = ("W1", "b1", "W2", "b2", "W3", "b3")
+
+
+# ---- host logic (null device) ------------------------------------------------------------------
+
+def _mlp_null(ctx, batch=16):
+    shapes = {"W1": (32, 24), "b1": (24,), "W2": (24, 24), "b2": (24,), "W3": (24, 10), "b3": (10,)}
+    params = [ctx.from_device(0, "f32", shapes[k], donatable=True) for k in NAMES]
+    X = ctx.from_device(0, "f32", (batch, 32))
+    labels = ctx.from_device(0, "s32", (batch,))
+    return params, X, labels
+
+
+def test_capture_needs_a_barrier():
+    ctx = Context(device=None)
+    with pytest.raises(LtError):
+        ctx.capture_step()
+
+
+def test_replay_bookkeeping_on_the_null_device():
+    ctx = Context(device=None)
+    params, X, labels = _mlp_null(ctx)
+    loss = programs.c2_step(ctx, X, labels, params, 0.01)
+    info = ctx.barrier()
+    plan = ctx.dump_plan()
+    step = ctx.capture_step()
+    assert step.scalars and set(step.scalars) <= {0.01, 1.0 / 16}   # one per use of the learning rate
+    before = ctx.stats()
+    r = step.replay()
+    after = ctx.stats()
+    assert after.replays == before.replays + 1
+    assert after.barriers == before.barriers                 # nothing was cut, hashed or looked up
+    assert after.nodes_recorded == before.nodes_recorded     # nothing was recorded
+    assert after.regions_launched == before.regions_launched + info.n_regions
+    assert r.n_regions == info.n_regions and r.n_launches == info.n_launches and r.cache_hit == 1
+    assert ctx.dump_plan() == plan
+    # the results are plain data again: the next traced step sees them as leaves, and hits the cache
+    loss2 = programs.c2_step(ctx, X, labels, params, 0.01)
+    assert ctx.barrier().cache_hit == 1
+    assert loss.shape == () and loss2.shape == ()
+    # wrong number of scalars
+    with pytest.raises(LtError):
+        step.replay(scalars=step.scalars + [1.0])
+    step.replay(scalars=step.scalars)
+
+
+def test_replay_refuses_a_pending_trace_and_released_inputs():
+    ctx = Context(device=None)
+    params, X, labels = _mlp_null(ctx)
+    loss = programs.c2_step(ctx, X, labels, params, 0.01)
+    ctx.barrier()
+    step = ctx.capture_step()
+    t = ctx.add(params[1], 1.0)          # a pending trace
+    with pytest.raises(LtError) as e:
+        step.replay()
+    assert "pending" in str(e.value)
+    ctx.barrier()
+    del t
+    step.replay()
+    del X                                 # an input of the step goes away
+    with pytest.raises(LtError) as e:
+        step.replay()
+    assert "released" in str(e.value)
+    assert loss is not None
+
+
+def test_capture_refuses_a_step_whose_input_was_released():
+    ctx = Context(device=None)
+    a = ctx.from_device(0, "f32", (8, 8))
+    b = ctx.add(a, 2.0)
+    del a                                 # (the leaf keeps its buffer until the barrier)
+    ctx.barrier()
+    with pytest.raises(LtError) as e:
+        ctx.capture_step()
+    assert "released" in str(e.value)
+    assert b is not None
+
+
+def test_capture_refuses_donation_to_another_tensor():
+    ctx = Context(device=None)
+    a = ctx.from_device(0, "f32", (64, 64), donatable=True)
+    keep = ctx.mul(a, 3.0)
+    other = ctx.from_device(0, "f32", (64, 64))
+    ctx.assign(a, other)                  # a's old buffer is free for the taking; the result goes to `keep`
+    ctx.barrier()
+    if "->p" in ctx.dump_plan():
+        with pytest.raises(LtError) as e:
+            ctx.capture_step()
+        assert "another tensor" in str(e.value) or "scratch" in str(e.value)
+    assert keep is not None
+
+
+def test_replay_after_the_cache_was_cleared():
+    ctx = Context(device=None)
+    params, X, labels = _mlp_null(ctx)
+    loss = programs.c2_step(ctx, X, labels, params, 0.01)
+    ctx.barrier()
+    step = ctx.capture_step()
+    ctx.set_fusion(False)
+    with pytest.raises(LtError) as e:
+        step.replay()
+    assert "cleared" in str(e.value)
+    assert loss is not None
+
+
+def test_rebind_rules_on_the_null_device():
+    ctx = Context(device=None)
+    a = ctx.from_device(0, "f32", (4, 4))
+    b = ctx.add(a, 1.0)
+    with pytest.raises(LtError):          # the pending trace reads a
+        ctx._check(ctx._lib.lt_tensor_rebind(ctx._h, a.tid, 0))
+    ctx.barrier()
+    ctx._check(ctx._lib.lt_tensor_rebind(ctx._h, a.tid, 0))
+    with pytest.raises(LtError):          # b is a result: library memory
+        ctx._check(ctx._lib.lt_tensor_rebind(ctx._h, b.tid, 0))
+
+
+# ---- on the GPU ----------------------------------------------------------------------------------
+
+@pytest.fixture()
+def gctx():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    c = Context(device=0, workspace_bytes=256 << 20)
+    yield c
+    c.close()
+
+
+@pytest.mark.gpu
+def test_replayed_steps_equal_traced_steps_bit_for_bit(gctx):
+    """Twelve SGD steps of the MLP: traced every step, against one traced step and eleven replays
+    with the batch tensors re-pointed.  Same plan, same kernels, same order: identical bits.  The
+    traced run is compared with the oracle elsewhere; here the replayed one is too."""
+    import torch
+    from oracle.numeric import Eager
+    steps = 12
+    inp = c2_inputs(steps=steps)
+    Xs = [torch.from_numpy(inp["X"][i]).cuda() for i in range(steps)]
+    Ls = [torch.from_numpy(inp["labels"][i]).cuda() for i in range(steps)]
+
+    def traced():
+        ctx = gctx
+        params = [ctx.tensor(inp[k].copy(), donatable=True) for k in NAMES]
+        losses = []
+        for i in range(steps):
+            loss = programs.c2_step(ctx, ctx.tensor(Xs[i]), ctx.tensor(Ls[i]), params, 0.01)
+            ctx.barrier()
+            losses.append(float(ctx.fetch(loss)))
+        return [ctx.fetch(p).copy() for p in params], losses
+
+    def replayed():
+        ctx = gctx
+        params = [ctx.tensor(inp[k].copy(), donatable=True) for k in NAMES]
+        X, L = ctx.tensor(Xs[0].clone()), ctx.tensor(Ls[0].clone())
+        loss = programs.c2_step(ctx, X, L, params, 0.01)
+        ctx.barrier()
+        losses = [float(ctx.fetch(loss))]
+        step = ctx.capture_step()
+        recorded = ctx.stats().nodes_recorded
+        for i in range(1, steps):
+            ctx.rebind(X, Xs[i])
+            ctx.rebind(L, Ls[i])
+            step.replay(blocking=(i % 2 == 0))
+            losses.append(float(ctx.fetch(loss)))
+        assert ctx.stats().nodes_recorded == recorded
+        assert ctx.stats().replays >= steps - 1
+        return [ctx.fetch(p).copy() for p in params], losses
+
+    pt, lt_ = traced()
+    pr, lr_ = replayed()
+    assert lt_ == lr_
+    for a, b, k in zip(pt, pr, NAMES):
+        assert np.array_equal(a, b), k
+    # and against the oracle (the tolerances of the free-running comparison of the traced steps)
+    E = Eager()
+    rp = [E.tensor(inp[k]) for k in NAMES]
+    for i in range(steps):
+        lo = programs.c2_step(E, E.tensor(inp["X"][i]), E.tensor(inp["labels"][i]), rp, 0.01)
+        assert abs(lr_[i] - float(E.fetch(lo))) <= 1e-4 * abs(float(E.fetch(lo)))
+    for g, r, k in zip(pr, rp, NAMES):
+        ref = E.fetch(r)
+        tol = 1e-3 if k.startswith("W") else 2e-2
+        assert np.max(np.abs(g - ref)) <= tol * max(1e-30, np.max(np.abs(ref))), k
+
+
+@pytest.mark.gpu
+def test_replay_with_new_scalars(gctx):
+    """The scalars of a step are inputs of the replay: y = a * s + t with other s and t."""
+    ctx = gctx
+    a_np = np.linspace(-2, 2, 4096, dtype=np.float32).reshape(64, 64)
+    a = ctx.tensor(a_np)
+    y = ctx.add(ctx.mul(a, 3.5), -0.25)
+    ctx.barrier()
+    step = ctx.capture_step()
+    assert sorted(step.scalars) == [-0.25, 3.5]
+    new = [7.0 if v == 3.5 else 0.5 for v in step.scalars]
+    step.replay(scalars=new)
+    got = ctx.fetch(y)
+    want = (a_np * np.float32(7.0) + np.float32(0.5)).astype(np.float32)
+    assert np.max(np.abs(got - want)) <= 1e-6 * np.max(np.abs(want))
+    step.replay()
+    got = ctx.fetch(y)
+    want = (a_np * np.float32(3.5) + np.float32(-0.25)).astype(np.float32)
+    assert np.max(np.abs(got - want)) <= 1e-6 * np.max(np.abs(want))

@@ -105,6 +105,8 @@ typedef struct {
   uint64_t live_tensors;
   uint64_t fallback_ops;   /* ops that went through the registered fallback (section 4.5) */
   uint64_t replays;        /* lt_step_replay calls that ran (not counted as barriers)          */
+  uint64_t graph_launches; /* steps enqueued as one HIP graph (lt_set_graphs)                  */
+  uint64_t graphs_built;   /* HIP graphs captured and instantiated                             */
 } lt_stats_t;
 
 /*
@@ -341,6 +343,23 @@ typedef struct {
 typedef int (*lt_fallback_fn)(void* user, uint16_t opcode, const lt_tensor_desc* inputs, int n_in, const lt_attr* attrs,
                               int n_attr, lt_tensor_desc* outputs, int n_out, int run, void* hip_stream);
 lt_status lt_set_fallback(lt_ctx* ctx, lt_fallback_fn fn, void* user);
+
+/*
+ * One HIP graph per cached plan and set of addresses (section 7 of the paper: the cost that is
+ * left on a cache hit is per-operation host work; here that is one launch and up to two events
+ * per kernel).  With on != 0, a barrier or lt_step_replay whose plan, storage addresses and
+ * scalars are those of an earlier step of this context enqueues that step's instantiated graph
+ * with one call.  The arguments of a plan's launches depend on nothing else, so the graph is the
+ * same work; a set of addresses is captured when it is seen for the second time (a training loop
+ * that updates its parameters in place alternates between two sets, because a step's results are
+ * placed before the previous step's are released), and a plan keeps at most four graphs, least
+ * recently used out first.  Captures run on a stream of the library's own (default priority) and
+ * contain kernel nodes only -- no memset, no copy.  Not used by lt_barrier_static, under
+ * lt_set_profiling, or when the workspace cannot hold a plan's temporaries all at once.  If a
+ * capture or instantiation fails the plan goes back to kernel-by-kernel launches for good and
+ * the step still runs.  Default: off.  lt_stats counts graph_launches and graphs_built.
+ */
+lt_status lt_set_graphs(lt_ctx* ctx, int on);
 
 /*
  * Debugging switch for the invariant of section 3 (a compiled trace is equivalent to running the

@@ -332,9 +332,8 @@ lt_status lt_shutdown(lt_ctx* ctx) {
     (void)hipStreamSynchronize(ctx->stream);
     for (hipEvent_t e : ctx->events) (void)hipEventDestroy(e);
     for (auto& bucket : ctx->cache)
-      for (auto& plan : bucket.second)
-        for (hipEvent_t e : plan->events)
-          if (e) (void)hipEventDestroy(e);
+      for (auto& plan : bucket.second) destroy_device_objects(plan.get());
+    if (ctx->graph_stream) (void)hipStreamDestroy(ctx->graph_stream);
     for (int i = 0; i < kMaxStreams - 1; ++i) {
       if (ctx->side[i]) (void)hipStreamSynchronize(ctx->side[i]);
       if (ctx->side[i]) (void)hipStreamDestroy(ctx->side[i]);
@@ -1000,14 +999,18 @@ lt_status lt_set_fusion(lt_ctx* ctx, int on) {
   if (ctx->device >= 0) {
     (void)hipStreamSynchronize(ctx->stream);
     for (auto& bucket : ctx->cache)
-      for (auto& plan : bucket.second)
-        for (hipEvent_t e : plan->events)
-          if (e) (void)hipEventDestroy(e);
+      for (auto& plan : bucket.second) destroy_device_objects(plan.get());
   }
   ctx->cache.clear();
   ctx->cache_generation++;
   ctx->last_plan = nullptr;
   ctx->last_step = lt::StepRecord{};
+  return LT_OK;
+}
+
+lt_status lt_set_graphs(lt_ctx* ctx, int on) {
+  if (!ctx) return LT_ERR_ARG;
+  ctx->graphs = on != 0;
   return LT_OK;
 }
 

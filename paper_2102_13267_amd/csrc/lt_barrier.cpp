@@ -176,6 +176,16 @@ static const char* kind_name(LaunchKind k) {
   return "?";
 }
 
+void destroy_device_objects(Plan* plan) {
+  for (hipEvent_t& e : plan->events) {
+    if (e) (void)hipEventDestroy(e);
+    e = nullptr;
+  }
+  for (GraphEntry& g : plan->graphs.entries)
+    if (g.exec) (void)hipGraphExecDestroy(g.exec);
+  plan->graphs.entries.clear();
+}
+
 // Bind this step's buffers and scalars into the cached plan and launch it.
 // use_static: reduction scratch and temporaries live in the library's static device scratch, only
 // results are placed in the caller's workspace; one stream, no events, nothing is created.
@@ -285,12 +295,87 @@ static lt_status execute(lt_ctx* ctx, Plan* plan, const std::vector<BufRef>& par
     hipError_t e = ltk::launch_fill_u32(red_tickets, (uint32_t)kTickets, 0u, ctx->stream);
     if (e != hipSuccess) return hip_fail(ctx, "lt_fill_u32_kernel", e);
   }
+  // ---- one HIP graph per plan and set of addresses (lt_set_graphs) ------------------------------
+  // The launches' arguments are a function of the storages' addresses and the scalars.  When the
+  // same ones come back (a training loop whose parameters are updated in place and whose results
+  // alternate between the same workspace blocks), the step that was captured then is launched
+  // again as a whole.  A signature is captured when it is seen for the second time.
+  GraphSlots& gs = plan->graphs;
+  const bool may_graph = real && ctx->graphs && !gs.disabled && !prof && !use_static && upfront && !plan->launches.empty();
+  uint64_t sig = 0;
+  bool capture = false;
+  if (may_graph) {
+    sig = fnv1a64((const uint8_t*)ptr.data(), ptr.size() * sizeof(void*));
+    sig ^= fnv1a64((const uint8_t*)scalars.data(), scalars.size() * sizeof(double)) * 0x9e3779b97f4a7c15ull;
+    sig ^= (uint64_t)(multi ? ctx->max_streams : 1) << 56;
+    sig |= 1ull;   // (0 marks an empty slot of `seen`)
+    for (GraphEntry& g : gs.entries) {
+      if (g.sig != sig) continue;
+      hipError_t e = hipGraphLaunch(g.exec, ctx->stream);
+      if (e != hipSuccess) return hip_fail(ctx, "hipGraphLaunch", e);
+      g.used = ++gs.clock;
+      for (size_t li = 0; li < plan->launches.size(); ++li)
+        for (size_t s : dies[li]) (*storage_bufs)[s].reset();   // behind the graph on the caller's stream
+      ctx->stats.kernels_launched += plan->launches.size();
+      ctx->stats.graph_launches++;
+      return LT_OK;
+    }
+    for (size_t i = 0; i < GraphSlots::kSeen; ++i) capture |= gs.seen[i] == sig;
+    gs.seen[gs.n_seen++ % GraphSlots::kSeen] = sig;
+  }
+  hipStream_t const caller_stream = ctx->stream;
+  if (capture) {
+    hipError_t e = hipSuccess;
+    if (!ctx->graph_stream) e = hipStreamCreateWithFlags(&ctx->graph_stream, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipStreamBeginCapture(ctx->graph_stream, hipStreamCaptureModeThreadLocal);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      gs.disabled = true;
+      capture = false;
+    } else {
+      ctx->stream = ctx->graph_stream;   // everything below is recorded, not run
+    }
+  }
+  // Ends a capture on every way out: the caller's stream is the context's again, and the
+  // recorded work becomes a graph (ok) or is dropped.
+  auto end_capture = [&](bool ok) -> hipError_t {
+    if (!capture) return hipSuccess;
+    capture = false;
+    ctx->stream = caller_stream;
+    hipGraph_t graph = nullptr;
+    hipError_t e = hipStreamEndCapture(ctx->graph_stream, &graph);
+    hipGraphExec_t exec = nullptr;
+    if (e == hipSuccess && ok) e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    if (graph) (void)hipGraphDestroy(graph);
+    if (e != hipSuccess || !ok) {
+      (void)hipGetLastError();
+      gs.disabled = true;
+      return e != hipSuccess ? e : hipErrorUnknown;
+    }
+    if (gs.entries.size() >= GraphSlots::kMax) {
+      size_t victim = 0;
+      for (size_t i = 1; i < gs.entries.size(); ++i)
+        if (gs.entries[i].used < gs.entries[victim].used) victim = i;
+      (void)hipGraphExecDestroy(gs.entries[victim].exec);
+      gs.entries.erase(gs.entries.begin() + victim);
+    }
+    GraphEntry g;
+    g.sig = sig;
+    g.exec = exec;
+    g.used = ++gs.clock;
+    gs.entries.push_back(g);
+    return hipSuccess;
+  };
   bool forked[kMaxStreams] = {true, false, false, false};
   if (multi) {
     plan->events.resize(plan->launches.size(), nullptr);
     hipError_t e = hipEventRecord(ctx->fork_event, ctx->stream);
-    if (e != hipSuccess) return hip_fail(ctx, "hipEventRecord", e);
+    if (e != hipSuccess) {
+      (void)end_capture(false);
+      return hip_fail(ctx, "hipEventRecord", e);
+    }
   }
+  const bool was_capturing = capture;
   std::vector<size_t> deferred;
   std::vector<uint8_t> args;
   std::vector<std::string> launch_names;   // kernel instances, when per-launch records are asked for
@@ -311,6 +396,7 @@ static lt_status execute(lt_ctx* ctx, Plan* plan, const std::vector<BufRef>& par
   };
   auto give_up = [&](lt_status st) {
     if (multi) (void)join_streams();
+    (void)end_capture(false);
     return st;
   };
   for (size_t li = 0; li < plan->launches.size(); ++li) {
@@ -367,7 +453,7 @@ static lt_status execute(lt_ctx* ctx, Plan* plan, const std::vector<BufRef>& par
       }
     }
     for (size_t s : dies[li]) {
-      if (multi) {
+      if (multi || was_capturing) {   // (a recorded step has not run yet)
         deferred.push_back(s);
         continue;
       }
@@ -378,9 +464,30 @@ static lt_status execute(lt_ctx* ctx, Plan* plan, const std::vector<BufRef>& par
   }
   if (multi) {
     hipError_t e = join_streams();
-    if (e != hipSuccess) return hip_fail(ctx, "stream join", e);
-    for (size_t s : deferred) (*storage_bufs)[s].reset();
+    if (e != hipSuccess) {
+      (void)end_capture(false);
+      return hip_fail(ctx, "stream join", e);
+    }
   }
+  if (was_capturing) {
+    // nothing has run yet.  The recorded step becomes a graph and is launched; if that cannot be
+    // had, this plan gives graphs up and the step is enqueued kernel by kernel after all.
+    hipError_t e = end_capture(true);
+    if (e == hipSuccess) {
+      e = hipGraphLaunch(gs.entries.back().exec, ctx->stream);
+      if (e != hipSuccess) return hip_fail(ctx, "hipGraphLaunch", e);
+      ctx->stats.graph_launches++;
+      ctx->stats.graphs_built++;
+    } else {
+      ctx->stats.kernels_launched -= plan->launches.size();
+      for (size_t s : deferred) (*storage_bufs)[s].reset();
+      for (size_t s = 0; s < ns; ++s)
+        if (plan->storages[s].param < 0) (*storage_bufs)[s].reset();
+      storage_bufs->clear();
+      return execute(ctx, plan, params, scalars, storage_bufs, use_static);   // (gs.disabled is set now)
+    }
+  }
+  for (size_t s : deferred) (*storage_bufs)[s].reset();
   if (prof) {
     hipError_t e = hipStreamSynchronize(ctx->stream);
     if (e != hipSuccess) return hip_fail(ctx, "hipStreamSynchronize", e);

@@ -153,6 +153,23 @@ struct RootBind {
   double value = 0;          // CONST
 };
 
+// Instantiated HIP graphs of a plan, by the signature of everything that goes into its launches'
+// arguments (the address of every storage, the scalars): a step whose buffers sit where they sat
+// before is enqueued as one graph launch instead of one launch and up to two events per kernel.
+struct GraphEntry {
+  uint64_t sig = 0;
+  hipGraphExec_t exec = nullptr;
+  uint64_t used = 0;     // (for least-recently-used replacement)
+};
+struct GraphSlots {
+  static constexpr size_t kMax = 4, kSeen = 8;
+  std::vector<GraphEntry> entries;
+  uint64_t seen[kSeen] = {0};   // signatures of recent steps: a graph is built for one that comes back
+  size_t n_seen = 0;
+  uint64_t clock = 0;
+  bool disabled = false;        // a capture failed: this plan is launched kernel by kernel from now on
+};
+
 struct Plan {
   std::vector<uint8_t> key;
   std::string text;
@@ -166,6 +183,7 @@ struct Plan {
   int n_streams = 1;                 // streams the schedule uses (1: everything on the caller's stream)
   size_t temp_bytes = 0;             // arena bytes when no temporary is reused inside the step
   std::vector<hipEvent_t> events;    // one per launch with `record` set (created on first use)
+  GraphSlots graphs;                 // lt_set_graphs
 };
 
 // What a captured step has to know about the barrier it repeats: the plan, the tensors whose
@@ -218,6 +236,8 @@ struct lt_ctx {
   hipStream_t side[lt::kMaxStreams - 1] = {};
   hipEvent_t fork_event = nullptr, join_event[lt::kMaxStreams - 1] = {};
   int max_streams = lt::kMaxStreams;   // lt_set_streams
+  bool graphs = false;                 // lt_set_graphs: steps with unchanged addresses run as one HIP graph
+  hipStream_t graph_stream = nullptr;  // the stream that graph captures are made on (created on first use)
   bool fusion = true;                  // lt_set_fusion: off = one region per recorded op
   lt_fallback_fn fallback = nullptr;   // lt_set_fallback: eager implementation of ops without a lowering
   void* fallback_user = nullptr;
@@ -239,6 +259,9 @@ size_t dtype_size(uint8_t dtype);
 const char* dtype_name(uint8_t dtype);
 const char* op_name(uint16_t op);
 int64_t numel(const int64_t* dims, int rank);
+
+// destroys the events and graphs that a plan owns on the device (lt_barrier.cpp)
+void destroy_device_objects(Plan* plan);
 
 // views (lt_api.cpp): bring every live view up to date with its base
 lt_status refresh_views(lt_ctx* ctx);

@@ -46,7 +46,7 @@ class BarrierInfo(C.Structure):
 class Stats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in (
         "barriers", "cache_hits", "cache_misses", "nodes_recorded", "regions_launched", "kernels_launched",
-        "ns_lowering_total", "arena_bytes_in_use", "arena_bytes_peak", "live_tensors", "fallback_ops", "replays")]
+        "ns_lowering_total", "arena_bytes_in_use", "arena_bytes_peak", "live_tensors", "fallback_ops", "replays", "graph_launches", "graphs_built")]
 
 
 class TensorDesc(C.Structure):
@@ -150,6 +150,7 @@ def load_library():
         "lt_set_profiling": [P, i32],
         "lt_set_streams": [P, i32],
         "lt_set_fusion": [P, i32],
+        "lt_set_graphs": [P, i32],
         "lt_set_fallback": [P, FALLBACK_FN, P],
         "lt_last_launches": [P, C.POINTER(LaunchRecord), i32, C.POINTER(i32)],
         "lt_step_capture": [P, C.POINTER(P)],
@@ -588,6 +589,10 @@ class Context:
                                       "version": 2, "strides": None}
         t = torch.as_tensor(m, device=f"cuda:{self.device}")
         return t.view(code[1]) if desc["dtype"] == "bf16" else t
+
+    def set_graphs(self, on: bool):
+        """lt_set_graphs: steps whose buffers sit where they sat before run as one HIP graph."""
+        self._check(self._lib.lt_set_graphs(self._h, 1 if on else 0))
 
     def set_fusion(self, on: bool) -> None:
         self._check(self._lib.lt_set_fusion(self._h, 1 if on else 0))

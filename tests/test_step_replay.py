@@ -138,10 +138,13 @@ def gctx():
 
 
 @pytest.mark.gpu
-def test_replayed_steps_equal_traced_steps_bit_for_bit(gctx):
+@pytest.mark.parametrize("graphs", [False, True])
+def test_replayed_steps_equal_traced_steps_bit_for_bit(gctx, graphs):
     """Twelve SGD steps of the MLP: traced every step, against one traced step and eleven replays
     with the batch tensors re-pointed.  Same plan, same kernels, same order: identical bits.  The
-    traced run is compared with the oracle elsewhere; here the replayed one is too."""
+    traced run is compared with the oracle elsewhere; here the replayed one is too.  With graphs
+    on, the batches are copied into fixed input tensors instead, so that addresses come back and
+    steps run as HIP graphs -- with fetches (synchronisation and eager work) between them."""
     import torch
     from oracle.numeric import Eager
     steps = 12
@@ -168,13 +171,28 @@ def test_replayed_steps_equal_traced_steps_bit_for_bit(gctx):
         losses = [float(ctx.fetch(loss))]
         step = ctx.capture_step()
         recorded = ctx.stats().nodes_recorded
+        ctx.set_graphs(graphs)
+        before = ctx.stats()
         for i in range(1, steps):
-            ctx.rebind(X, Xs[i])
-            ctx.rebind(L, Ls[i])
+            if graphs:
+                X._keep.copy_(Xs[i])
+                L._keep.copy_(Ls[i])
+            else:
+                ctx.rebind(X, Xs[i])
+                ctx.rebind(L, Ls[i])
             step.replay(blocking=(i % 2 == 0))
             losses.append(float(ctx.fetch(loss)))
-        assert ctx.stats().nodes_recorded == recorded
-        assert ctx.stats().replays >= steps - 1
+        after = ctx.stats()
+        ctx.set_graphs(False)
+        assert after.nodes_recorded == recorded
+        assert after.replays - before.replays == steps - 1
+        if graphs:
+            # the results alternate between two places of the workspace: two graphs, each built
+            # when its addresses came back
+            assert 1 <= after.graphs_built - before.graphs_built <= 4
+            assert after.graph_launches - before.graph_launches >= steps - 1 - 4
+        else:
+            assert after.graph_launches == before.graph_launches
         return [ctx.fetch(p).copy() for p in params], losses
 
     pt, lt_ = traced()
@@ -213,3 +231,38 @@ def test_replay_with_new_scalars(gctx):
     got = ctx.fetch(y)
     want = (a_np * np.float32(3.5) + np.float32(-0.25)).astype(np.float32)
     assert np.max(np.abs(got - want)) <= 1e-6 * np.max(np.abs(want))
+
+
+@pytest.mark.gpu
+def test_traced_steps_as_graphs(gctx):
+    """Barriers whose plan and addresses come back run as HIP graphs too: an in-place Adam-like
+    update traced every step, with and without graphs, bit for bit."""
+    ctx = gctx
+    rng = np.random.default_rng(5)
+    p0 = rng.standard_normal((256, 384)).astype(np.float32)
+    g0 = rng.standard_normal((256, 384)).astype(np.float32)
+
+    def run(graphs):
+        ctx.set_graphs(graphs)
+        p = ctx.tensor(p0.copy(), donatable=True)
+        m = ctx.tensor(np.zeros_like(p0), donatable=True)
+        g = ctx.tensor(g0)
+        norms = []
+        before = ctx.stats()
+        for i in range(10):
+            nm = ctx.add(ctx.mul(m, 0.9), ctx.mul(g, 0.1))
+            npar = ctx.sub(p, ctx.mul(nm, 0.05))
+            n = ctx.sum(ctx.mul(npar, npar))
+            ctx.assign(m, nm)
+            ctx.assign(p, npar)
+            ctx.barrier(blocking=(i % 3 == 0))
+            norms.append(float(ctx.fetch(n)))
+        after = ctx.stats()
+        ctx.set_graphs(False)
+        return ctx.fetch(p).copy(), ctx.fetch(m).copy(), norms, after.graph_launches - before.graph_launches
+
+    pa, ma, na, ga = run(False)
+    pb, mb, nb, gb = run(True)
+    assert ga == 0 and gb >= 4
+    assert na == nb
+    assert np.array_equal(pa, pb) and np.array_equal(ma, mb)

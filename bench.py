@@ -248,6 +248,39 @@ def run_c2(steps, warmup):
         state["i"] += 1
         return programs.c2_step(ctx, Xs[i], Ls[i], params, 0.01)
     pipelined = _time_pipelined(record, ctx, steps)
+
+    # the same steps without tracing (a captured step run again on re-pointed batch tensors), and
+    # as HIP graphs (batches copied into fixed tensors so that the addresses come back)
+    import torch
+    Xt = [torch.from_numpy(inp["X"][i]).cuda() for i in range(n_batches)]
+    Lt = [torch.from_numpy(inp["labels"][i]).cuda() for i in range(n_batches)]
+    X, L = ctx.tensor(Xt[0].clone()), ctx.tensor(Lt[0].clone())
+    loss = programs.c2_step(ctx, X, L, params, 0.01)
+    ctx.barrier(True)
+    captured = ctx.capture_step()
+
+    def replayed(graphs):
+        ctx.set_graphs(graphs)
+
+        def one(i):
+            if graphs:
+                X._keep.copy_(Xt[i % n_batches])
+                L._keep.copy_(Lt[i % n_batches])
+            else:
+                ctx.rebind(X, Xt[i % n_batches])
+                ctx.rebind(L, Lt[i % n_batches])
+            captured.replay(blocking=True)
+        for i in range(max(warmup, 8)):
+            one(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            one(i)
+        torch.cuda.synchronize()
+        rate = steps / (time.perf_counter() - t0)
+        ctx.set_graphs(False)
+        return rate
+    rate_replay, rate_graph = replayed(False), replayed(True)
     _, _, _, _, _, table = _dominant(launches)
     # the contractions as a family (each is a few microseconds: launch latency, not the matrix cores, bounds them)
     flops = sum(r["flops"] for st in launches for r in st)
@@ -259,7 +292,8 @@ def run_c2(steps, warmup):
     roof["frac"] = roof["achieved"] / roof["peak"]
     extra = {"kernels": table, "cache_hits": sum(i.cache_hit for i in infos), "ns_host_per_step": {
         "collect": int(np.mean([i.ns_collect for i in infos])), "hash": int(np.mean([i.ns_hash for i in infos])),
-        "launch": int(np.mean([i.ns_launch for i in infos]))}, "steps_per_s_non_blocking_barrier": pipelined}
+        "launch": int(np.mean([i.ns_launch for i in infos]))}, "steps_per_s_non_blocking_barrier": pipelined,
+        "steps_per_s_replayed_without_tracing": rate_replay, "steps_per_s_replayed_as_hip_graphs": rate_graph}
     config = {"workload": "c2: MLP 784-512-512-10 fp32 batch 128, fwd+bwd+SGD, one barrier per step", "regions": int(infos[-1].n_regions)}
 
     def cpu():

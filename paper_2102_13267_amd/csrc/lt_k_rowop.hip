@@ -152,6 +152,10 @@ __global__ __launch_bounds__(kBlock) void lt_row_op_kernel(const RowOpArgs a) {
       } break;
       case kLayerNorm: {
         RowRegs x = row_load<TPR, IO>(a.in[0], a.in_dtype[0], base, ecols, lane, vec_ok, 0.0f);
+        // scale and shift are asked for together with the row: their (cache) latency passes under
+        // the two reductions instead of after them
+        RowRegs g = row_load<TPR, IO>(a.in[1], a.in_dtype[1], 0, ecols, lane, vec_ok, 0.0f);
+        RowRegs b = row_load<TPR, IO>(a.in[2], a.in_dtype[2], 0, ecols, lane, vec_ok, 0.0f);
         const float mean = row_reduce_regs<TPR>(kRedSum, x, lds) / (float)cols;
         RowRegs d = x;
 #pragma unroll
@@ -164,8 +168,6 @@ __global__ __launch_bounds__(kBlock) void lt_row_op_kernel(const RowOpArgs a) {
         }
         const float var = row_reduce_regs<TPR>(kRedSum, d, lds) / (float)cols;
         const float rstd = 1.0f / sqrtf(var + a.eps);
-        RowRegs g = row_load<TPR, IO>(a.in[1], a.in_dtype[1], 0, ecols, lane, vec_ok, 0.0f);
-        RowRegs b = row_load<TPR, IO>(a.in[2], a.in_dtype[2], 0, ecols, lane, vec_ok, 0.0f);
         LT_ROW_FOREACH(e = (e - mean) * rstd * comp(g.v[k], j) + comp(b.v[k], j);)
         row_store<TPR, IO>(a.out[0], a.out_dtype[0], base, ecols, lane, vec_ok, x);
         if (lane == 0 && live) {

@@ -48,6 +48,7 @@ struct EwStreamArgs {
   uint32_t vin[4];    // input numbers of the vector inputs (padded with the first)
   uint32_t sin[2];    // input numbers of the device scalars
   uint32_t n_sin, pad;
+  uint32_t vrow[4];   // bf16 kernel: 1 = vector input j is a row vector (indexed by column), 0 = a full tensor
 };
 
 // NT: non-temporal loads and stores, for regions larger than the last-level cache (what they read
@@ -131,20 +132,28 @@ __global__ __launch_bounds__(kBlock, 4) void lt_ew_stream_bf16_kernel(const EwSt
   const uint32_t lane = threadIdx.x * 2 * kVec;
   const char* vp[NV];
   uint32_t vslot[NV];
+  bool vrow[NV];
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
     vslot[j] = a.vin[j];
     vp[j] = (const char*)p.in[vslot[j]].ptr;
+    vrow[j] = a.vrow[j] != 0u;
   }
   float sval[2] = {0.0f, 0.0f};
 #pragma unroll
   for (int j = 0; j < 2; ++j)
     if ((uint32_t)j < a.n_sin) sval[j] = *(const float*)p.in[a.sin[j]].ptr;
   typedef uint32_t U32x4 __attribute__((ext_vector_type(4)));
+  // a row vector (a bias) is read at the column of the lane's first element: the host takes this
+  // kernel only when rows are whole 8-element groups, so the 8 columns are consecutive.  The
+  // column moves on by the grid stride modulo the row length, without a division per tile.
+  const uint32_t cols = p.cols;
+  const uint32_t col_step = (uint32_t)(((uint64_t)gridDim.x * kTile) % cols);
+  uint32_t col = (uint32_t)((tile * kTile + lane) % cols);
   U32x4 v[NV];
   bool live = (uint64_t)lane < n - tile * kTile;
 #pragma unroll
-  for (int j = 0; j < NV; ++j) v[j] = live ? *(const U32x4*)(vp[j] + (tile * kTile + lane) * 2u) : U32x4{0u, 0u, 0u, 0u};
+  for (int j = 0; j < NV; ++j) v[j] = live ? *(const U32x4*)(vp[j] + (vrow[j] ? (uint64_t)col : tile * kTile + lane) * 2u) : U32x4{0u, 0u, 0u, 0u};
   for (;;) {
     RF<16> f = rf_zero<16>();
 #pragma unroll
@@ -171,8 +180,10 @@ __global__ __launch_bounds__(kBlock, 4) void lt_ew_stream_bf16_kernel(const EwSt
     const bool more = tile < ntiles;
     if (more) {
       live = (uint64_t)lane < n - tile * kTile;
+      col += col_step;
+      col = col >= cols ? col - cols : col;
 #pragma unroll
-      for (int j = 0; j < NV; ++j) v[j] = live ? *(const U32x4*)(vp[j] + (tile * kTile + lane) * 2u) : U32x4{0u, 0u, 0u, 0u};
+      for (int j = 0; j < NV; ++j) v[j] = live ? *(const U32x4*)(vp[j] + (vrow[j] ? (uint64_t)col : tile * kTile + lane) * 2u) : U32x4{0u, 0u, 0u, 0u};
     }
     f = interp<16, 2>(f, pr, n_code);
     if (cur_live) {
@@ -209,6 +220,12 @@ static bool make_stream_args(const EwProg& p, uint32_t vec_dtype, EwStreamArgs* 
     const EwIn& in = p.in[k];
     if (in.fetch == kFetchVec4 && in.mode == kFull && in.dtype == vec_dtype) {
       if (nv == 4u) return false;
+      out->vrow[nv] = 0u;
+      out->vin[nv++] = k;
+    } else if (vec_dtype == kBF16 && in.fetch == kFetchVec4 && in.mode == kRowVec && in.dtype == kBF16 && (p.cols % 8u) == 0u &&
+               ((uintptr_t)in.ptr & 15u) == 0u) {
+      if (nv == 4u) return false;   // (8 consecutive columns of a row vector: one aligned 16-byte load)
+      out->vrow[nv] = 1u;
       out->vin[nv++] = k;
     } else if (in.fetch == kFetchBcast && in.mode == kScalar && in.dtype == kF32) {
       if (ns == 2u) return false;
@@ -218,7 +235,10 @@ static bool make_stream_args(const EwProg& p, uint32_t vec_dtype, EwStreamArgs* 
     }
   }
   if (nv == 0u) return false;
-  for (uint32_t j = nv; j < 4u; ++j) out->vin[j] = out->vin[0];
+  for (uint32_t j = nv; j < 4u; ++j) {
+    out->vin[j] = out->vin[0];
+    out->vrow[j] = out->vrow[0];
+  }
   for (uint32_t j = ns; j < 2u; ++j) out->sin[j] = 0u;
   out->n_sin = ns;
   out->pad = nv;

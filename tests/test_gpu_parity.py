@@ -1081,6 +1081,36 @@ def test_bf16_elementwise_programs(ctx, n):
         check(ctx, E, gt, rt, TOL16, what)
 
 
+@pytest.mark.parametrize("rows,cols", [(1, 8), (3, 24), (256, 8), (77, 1024), (5, 4104), (1300, 1032), (2600, 1032), (4096, 256), (6, 12)])
+def test_bf16_elementwise_with_row_vectors(ctx, rows, cols):
+    """bf16 regions that mix full tensors with row vectors (a bias, a scale): rows of 8-element
+    groups go through the streamed kernel, which reads a row vector at the lane's column and
+    moves the column on by the grid stride modulo the row length -- one tile, many tiles per
+    workgroup ((2600, 1032) is 1311 tiles for 1024 workgroups), a ragged last tile, rows longer and shorter than a
+    tile, two row vectors and no full tensor at all; (6, 12) is not whole groups of 8 and takes
+    the general kernel.  In-place update of the full input among the outputs."""
+    E = Eager()
+    g = rng(900 + rows + cols)
+    x = round_to_bf16(g.standard_normal((rows, cols), dtype=np.float32))
+    y = round_to_bf16(g.standard_normal((rows, cols), dtype=np.float32))
+    bias = round_to_bf16(g.standard_normal(cols, dtype=np.float32))
+    scale = round_to_bf16(1.0 + 0.1 * g.standard_normal(cols, dtype=np.float32))
+
+    def prog(B, x, y, bias, scale):
+        u = B.gelu(B.add(x, bias))                       # one full tensor, one row vector
+        v = B.add(B.mul(B.add(x, y), scale), bias)       # two full tensors, two row vectors
+        w = B.mul(B.expand(B.add(bias, scale), (rows, cols)), 0.5)   # row vectors only
+        B.assign(y, B.sub(y, B.mul(bias, 0.25)))          # in place over a full input
+        return u, v, w, y
+
+    gx, gy = ctx.tensor(x, dtype="bf16"), ctx.tensor(y.copy(), dtype="bf16", donatable=True)
+    got = prog(ctx, gx, gy, ctx.tensor(bias, dtype="bf16"), ctx.tensor(scale, dtype="bf16"))
+    ref = prog(E, E.tensor(x, dtype="bf16"), E.tensor(y, dtype="bf16"), E.tensor(bias, dtype="bf16"), E.tensor(scale, dtype="bf16"))
+    ctx.barrier()
+    for gt, rt, what in zip(got, ref, "uvwy"):
+        check(ctx, E, gt, rt, TOL16, what)
+
+
 @pytest.mark.parametrize("n", [4, 1024, 1028, 2048, 3072, 5 * 1024 + 8, (1 << 20) + 1024])
 def test_streamed_fp32_elementwise_tile_pairs(ctx, n):
     """The streamed fp32 elementwise kernel takes two 1024-element tiles per workgroup: a single

@@ -1203,8 +1203,10 @@ def test_random_traces_numeric(ctx, shape, trials):
         assert len(got) == len(ref)
         ctx.barrier()
         for k, (a, b) in enumerate(zip(got, ref)):
-            err = rel_err(ctx.fetch(a), E.fetch(b))
-            assert err <= 2e-5, (shape, trial, k, err)
+            ga, rb = ctx.fetch(a), E.fetch(b)
+            err = rel_err(ga, rb)
+            note(ga, rb, TOL32, err)
+            assert err <= TOL32, (shape, trial, k, err)
         del got, ref, lt, et
 
 

@@ -7,6 +7,29 @@
 
 namespace ltk {
 
+// Partial results travel between workgroups of one launch, which may sit on different dies with
+// different L2 caches.  They are written and read with relaxed device-scope atomic accesses --
+// stores and loads that go through to the memory side -- so that no cache has to be written back
+// or invalidated as a whole, which is what a device-scope fence does (microseconds per fence, and
+// every other workgroup of the die loses what it had cached).  Order: the writer waits for its
+// stores (a workgroup-scope release: a wait, no cache operation) before it takes the ticket; the
+// reader starts only after it has seen the last ticket.
+__device__ __forceinline__ void publish(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ float published(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void publish4(float* p, const float4& v) {   // p 16-byte aligned
+  const uint64_t lo = (uint64_t)__float_as_uint(v.x) | ((uint64_t)__float_as_uint(v.y) << 32);
+  const uint64_t hi = (uint64_t)__float_as_uint(v.z) | ((uint64_t)__float_as_uint(v.w) << 32);
+  __hip_atomic_store((uint64_t*)p, lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store((uint64_t*)p + 1, hi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float4 published4(const float* p) {
+  const uint64_t lo = __hip_atomic_load((const uint64_t*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const uint64_t hi = __hip_atomic_load((const uint64_t*)p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_float4(__uint_as_float((uint32_t)lo), __uint_as_float((uint32_t)(lo >> 32)), __uint_as_float((uint32_t)hi),
+                     __uint_as_float((uint32_t)(hi >> 32)));
+}
+
+
 // Run the post program of an anchored region for the flat elements i .. i+nvalid-1 of its
 // space, with the anchor's value(s) already placed in slot post.anchor_slot.
 __device__ __forceinline__ void run_post(const EwProg& post, const ProgRegs post_regs, Quad anchor, uint64_t i,
@@ -185,20 +208,18 @@ __global__ __launch_bounds__(kBlock) void lt_all_reduce_kernel(const AllArgs a) 
     acc = fold_vec(a.red, acc, rf_get(f, pro.anchor_slot), nvalid);
   }
   float r = block_reduce(a.red, acc, lds);
-  if (gridDim.x > 1u) {   // (a single workgroup is its own last one: no partials, no fences, whose
-                          // device-wide cache write-back costs microseconds)
+  if (gridDim.x > 1u) {   // (a single workgroup is its own last one: no partials, no ticket)
     if (threadIdx.x == 0) {
-      a.partials[blockIdx.x] = r;   // published by the fence, read by the last workgroup behind its own fence
-      __threadfence();
+      publish(&a.partials[blockIdx.x], r);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // (the store has been performed before the ticket is taken)
       uint32_t t = atomicAdd(a.ticket, 1u);
       is_last = (t == gridDim.x - 1) ? 1u : 0u;
     }
     __syncthreads();
     if (!is_last) return;
-    __threadfence();
     // the last workgroup combines the partials in a fixed order (deterministic for a given grid)
     acc = red_identity(a.red);
-    for (uint32_t g = threadIdx.x; g < gridDim.x; g += kBlock) acc = red_combine(a.red, acc, a.partials[g]);
+    for (uint32_t g = threadIdx.x; g < gridDim.x; g += kBlock) acc = red_combine(a.red, acc, published(&a.partials[g]));
     r = block_reduce(a.red, acc, lds);
     if (threadIdx.x == 0) *a.ticket = 0u;
   }
@@ -331,7 +352,7 @@ __global__ __launch_bounds__(kColBlock) void lt_col_reduce_kernel(const ColArgs 
       acc.z = red_combine(a.red, acc.z, o.z);
       acc.w = red_combine(a.red, acc.w, o.w);
     }
-    if (gridDim.y == 1u) {   // one slab: this is the result, no partials, tickets or fences
+    if (gridDim.y == 1u) {   // one slab: this is the result, no partials, no tickets
       if (!nvalid) return;
       if (a.red == kRedMean) {
         const float inv = 1.0f / (float)a.rows;
@@ -342,20 +363,17 @@ __global__ __launch_bounds__(kColBlock) void lt_col_reduce_kernel(const ColArgs 
       run_post(a.post, post_regs, accq, c, nvalid);
       return;
     }
-    // plain stores: the fence below publishes them before the ticket is taken, and the last
-    // workgroup's fence after its ticket makes them visible to its plain loads.  The slab stride
-    // is padded to a multiple of four floats so that whole vectors stay 16-byte aligned.
+    // The slab stride is padded to a multiple of four floats so that whole vectors stay 16-byte
+    // aligned.
     if (nvalid == (uint32_t)kVec) {
-      *(float4*)(a.partials + (uint64_t)blockIdx.y * pstride + c) = acc;
+      publish4(a.partials + (uint64_t)blockIdx.y * pstride + c, acc);
     } else if (nvalid) {
       float* dst = a.partials + (uint64_t)blockIdx.y * pstride + c;
-      dst[0] = acc.x;
-      if (nvalid > 1u) dst[1] = acc.y;
-      if (nvalid > 2u) dst[2] = acc.z;
+      publish(dst, acc.x);
+      if (nvalid > 1u) publish(dst + 1, acc.y);
+      if (nvalid > 2u) publish(dst + 2, acc.z);
     }
-    // only this wave wrote partials, so only it pays for the release fence (a write-back of the
-    // whole L2: far too expensive to run once per wave)
-    __threadfence();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // (this wave's stores have been performed before its ticket is taken)
     if (lane == 0) {
       uint32_t t = atomicAdd(&a.tickets[blockIdx.x], 1u);
       is_last = (t == gridDim.y - 1) ? 1u : 0u;
@@ -364,7 +382,6 @@ __global__ __launch_bounds__(kColBlock) void lt_col_reduce_kernel(const ColArgs 
   if (gridDim.y == 1u) return;   // (uniform: wave 0 has finished the strip above)
   __syncthreads();
   if (!is_last) return;
-  __threadfence();
   if (threadIdx.x == 0) a.tickets[blockIdx.x] = 0u;
   // the last workgroup of a strip combines the slabs: each wave a contiguous share, eight loads in
   // flight, fixed order (deterministic for a given grid)
@@ -380,11 +397,11 @@ __global__ __launch_bounds__(kColBlock) void lt_col_reduce_kernel(const ColArgs 
         if (sb + j < s1) {
           const float* src = a.partials + (uint64_t)(sb + j) * pstride + c;
           if (nvalid == (uint32_t)kVec) {
-            t[j] = *(const float4*)src;
+            t[j] = published4(src);
           } else {
-            t[j].x = src[0];
-            if (nvalid > 1u) t[j].y = src[1];
-            if (nvalid > 2u) t[j].z = src[2];
+            t[j].x = published(src);
+            if (nvalid > 1u) t[j].y = published(src + 1);
+            if (nvalid > 2u) t[j].z = published(src + 2);
           }
         }
       }

@@ -40,7 +40,7 @@ struct MemState {
 double estimate_us(const Launch& l) {
   const double mem = (double)l.bytes / 3.0e6;   // 3 TB/s
   if (l.kind == L_GEMM) return 8.0 + std::max(mem, (double)l.flops / 4.0e8);   // 400 TFLOP/s
-  if (l.kind == L_COL) return 20.0 + mem;       // latency bound: dependent trips, fence, last-workgroup pass
+  if (l.kind == L_COL) return 12.0 + mem;       // latency bound: dependent trips, ticket, last-workgroup pass
   return 6.0 + mem;
 }
 
@@ -115,7 +115,7 @@ void schedule_streams(Plan* plan) {
     // Stream choice: the stream on which the launch can start first, among those it may use.
     // Short launches stay on the caller's stream, in plan order (an event costs more than they
     // do).  What may move: column reductions of a few megabytes and more (a chain of dependent
-    // trips, a fence and a last-workgroup pass, at most 256 workgroups: most of the chip is idle
+    // trips, a ticket and a last-workgroup pass, at most 256 workgroups: most of the chip is idle
     // under them), and launches of kSpreadUs and more (workgroups of the next independent launch
     // fill the chip while this one's last workgroups run their epilogues).  A narrow launch that
     // depends on side stream work follows it there, so that the caller's stream never stalls

@@ -107,6 +107,7 @@ typedef struct {
   uint64_t replays;        /* lt_step_replay calls that ran (not counted as barriers)          */
   uint64_t graph_launches; /* steps enqueued as one HIP graph (lt_set_graphs)                  */
   uint64_t graphs_built;   /* HIP graphs captured and instantiated                             */
+  uint64_t quick_hits;     /* barriers whose plan was found by the record-time fingerprint      */
 } lt_stats_t;
 
 /*
@@ -343,6 +344,23 @@ typedef struct {
 typedef int (*lt_fallback_fn)(void* user, uint16_t opcode, const lt_tensor_desc* inputs, int n_in, const lt_attr* attrs,
                               int n_attr, lt_tensor_desc* outputs, int n_out, int run, void* hip_stream);
 lt_status lt_set_fallback(lt_ctx* ctx, lt_fallback_fn fn, void* user);
+
+/*
+ * Hashing while recording (section 7 of the paper: graph hashing is part of the per-step overhead
+ * that is paid even on a cache hit).  Every recorded node is taken into a 128-bit fingerprint of
+ * the pending trace as it is appended (opcode, type, shape, attributes, operands by record index,
+ * which earlier leaf shares a leaf's buffer).  At a barrier the fingerprint, the live roots and
+ * what each root could donate identify the canonical form of the cut, so a trace that this
+ * context has seen before finds its plan without the canonical walk, serialisation and FNV hash;
+ * a trace seen for the first time takes the canonical path (hash and key bit-exact as specified)
+ * and is then remembered by fingerprint.  The fingerprint is not the cache key: lt_barrier_info
+ * still reports the canonical hash, and lt_dump_key the canonical string.  mode 0: off; 1: on
+ * (default); 2: on, and every fingerprint hit is checked against the canonical key (a
+ * disagreement fails the barrier with LT_ERR_ARG and a message that says so) -- the tests run
+ * in this mode.  A wrong hit needs a collision of two independent 64-bit lanes.  lt_stats counts
+ * quick_hits.
+ */
+lt_status lt_set_quick_lookup(lt_ctx* ctx, int mode);
 
 /*
  * One HIP graph per cached plan and set of addresses (section 7 of the paper: the cost that is

@@ -193,6 +193,28 @@ lt_status refresh_views(lt_ctx* ctx) {
   return LT_OK;
 }
 
+// Append a node to the trace and take it into the trace's fingerprint.
+static void push_node(lt_ctx* ctx, Node&& n) {
+  Fingerprint& f = ctx->trace_fp;
+  f.mix((uint64_t)n.op | ((uint64_t)n.dtype << 16) | ((uint64_t)n.rank << 24) | ((uint64_t)n.n_attr << 32) | ((uint64_t)n.n_in << 40) |
+        ((uint64_t)n.n_out << 48));
+  for (int d = 0; d < n.rank; ++d) f.mix((uint64_t)n.dims[d]);
+  for (int k = 0; k < n.n_attr; ++k) {
+    f.mix((uint64_t)n.attrs[k].key | ((uint64_t)n.attrs[k].is_float << 16));
+    uint64_t payload;
+    if (n.attrs[k].is_float) std::memcpy(&payload, &n.attrs[k].v.f, 8);
+    else payload = (uint64_t)n.attrs[k].v.i;
+    f.mix(payload);
+  }
+  for (int k = 0; k < n.n_in; ++k) f.mix(((uint64_t)(uint32_t)n.ins[k].node << 8) | (uint64_t)(uint8_t)n.ins[k].slot);
+  if (n.op == OP_DEVICE_DATA) {
+    // which earlier leaf names the same buffer (itself: none) -- the alias class of the cache key
+    const int32_t self = (int32_t)ctx->nodes.size();
+    f.mix((uint64_t)(uint32_t)ctx->leaf_of_buffer.emplace(n.buffer.get(), self).first->second);
+  }
+  ctx->nodes.push_back(std::move(n));
+}
+
 // operand reference of a handle in the trace being recorded; leaves are created on first use
 static Val use(lt_ctx* ctx, Handle* h) {
   if (h->kind == H_PENDING) return Val{h->node, h->slot};
@@ -220,7 +242,7 @@ static Val use(lt_ctx* ctx, Handle* h) {
         n.value = v;
       }
     }
-    ctx->nodes.push_back(std::move(n));
+    push_node(ctx, std::move(n));
     h->memo_epoch = ctx->epoch;
     h->memo_node = (int32_t)ctx->nodes.size() - 1;
     ctx->stats.nodes_recorded++;
@@ -635,7 +657,7 @@ static lt_status record_op(lt_ctx* ctx, uint16_t opcode, const lt_tensor* inputs
   std::sort(n.attrs, n.attrs + n.n_attr, [](const Attr& x, const Attr& y) { return x.key < y.key; });
   // operands are resolved last so that a failed call leaves the trace untouched
   for (int i = 0; i < n_in; ++i) n.ins[i] = use(ctx, in[i]);
-  ctx->nodes.push_back(std::move(n));
+  push_node(ctx, std::move(n));
   ctx->stats.nodes_recorded++;
   const int32_t idx = (int32_t)ctx->nodes.size() - 1;
   const Node& nn = ctx->nodes[idx];
@@ -970,8 +992,10 @@ lt_status lt_dump_schedule(lt_ctx* ctx, char* buf, size_t cap, size_t* len) {
 
 lt_status lt_dump_key(lt_ctx* ctx, uint8_t* buf, size_t cap, size_t* len) {
   if (!ctx) return LT_ERR_ARG;
-  if (len) *len = ctx->last_key.size();
-  if (buf && cap) std::memcpy(buf, ctx->last_key.data(), std::min(cap, ctx->last_key.size()));
+  static const std::vector<uint8_t> none;
+  const std::vector<uint8_t>& key = ctx->last_plan ? ctx->last_plan->key : none;
+  if (len) *len = key.size();
+  if (buf && cap) std::memcpy(buf, key.data(), std::min(cap, key.size()));
   return LT_OK;
 }
 
@@ -1002,9 +1026,16 @@ lt_status lt_set_fusion(lt_ctx* ctx, int on) {
       for (auto& plan : bucket.second) destroy_device_objects(plan.get());
   }
   ctx->cache.clear();
+  ctx->quick.clear();
   ctx->cache_generation++;
   ctx->last_plan = nullptr;
   ctx->last_step = lt::StepRecord{};
+  return LT_OK;
+}
+
+lt_status lt_set_quick_lookup(lt_ctx* ctx, int mode) {
+  if (!ctx || mode < 0 || mode > 2) return LT_ERR_ARG;
+  ctx->quick_lookup = mode;
   return LT_OK;
 }
 

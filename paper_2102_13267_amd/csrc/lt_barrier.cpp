@@ -516,27 +516,79 @@ static lt_status barrier_impl(lt_ctx* ctx, int blocking, lt_barrier_info* info, 
   lt_status vs = refresh_views(ctx);   // (section 4.4) a live view is evaluated at its base's current value
   if (vs != LT_OK) return vs;
   Cut cut;
-  collect_cut(ctx, &cut);
   std::vector<uint8_t> key;
-  serialise_cut(ctx, &cut, &key);
-  const uint64_t t1 = now_ns();
-  const uint64_t h = fnv1a64(key.data(), key.size());
+  // Quick lookup (section 7 of the paper: hash while recording): the trace's fingerprint was
+  // kept up to date by every recorded node; with the live roots and what each would donate it
+  // identifies the canonical form, so a trace seen before needs no walk, no serialisation and
+  // no hash -- only the roots (the live pending tensors, ascending id).
+  Fingerprint fp = ctx->trace_fp;
+  const QuickEntry* quick = nullptr;
+  if (ctx->quick_lookup) {
+    for (auto& kv : ctx->handles)
+      if (kv.second.kind == H_PENDING) cut.roots.push_back(&kv.second);
+    fp.mix((uint64_t)ctx->nodes.size());
+    for (const Handle* r : cut.roots) {
+      fp.mix(((uint64_t)(uint32_t)r->node << 8) | (uint64_t)(uint8_t)r->slot);
+      // what the root could donate: the leaf of this trace that reads the buffer the tensor gave
+      // up, and whether a live tensor still names that buffer
+      const Buffer* b = r->donor.get();
+      uint64_t d = 0;
+      if (b) {
+        auto it = ctx->leaf_of_buffer.find(b);
+        d = it == ctx->leaf_of_buffer.end() ? 1 : (((uint64_t)(uint32_t)it->second << 2) | (b->data_refs == 0 ? 3u : 2u));
+      }
+      fp.mix(d);
+    }
+    auto it = ctx->quick.find(fp);
+    if (it != ctx->quick.end() && it->second.generation == ctx->cache_generation) quick = &it->second;
+  }
+  uint64_t h = 0;
   Plan* plan = nullptr;
-  auto& bucket = ctx->cache[h];
-  for (auto& p : bucket)
-    if (p->key.size() == key.size() && std::memcmp(p->key.data(), key.data(), key.size()) == 0) plan = p.get();
-  const uint64_t t2 = now_ns();
+  uint64_t t1, t2;
+  if (quick && ctx->quick_lookup == 1) {
+    plan = quick->plan;
+    h = quick->hash;
+    cut.param_nodes = quick->param_nodes;
+    cut.scalar_nodes = quick->scalar_nodes;
+    cut.order.resize(quick->n_nodes);   // (only its length is looked at on a hit)
+    t1 = t2 = now_ns();
+    ctx->stats.quick_hits++;
+  } else {
+    collect_cut(ctx, &cut);
+    serialise_cut(ctx, &cut, &key);
+    t1 = now_ns();
+    h = fnv1a64(key.data(), key.size());
+    auto& bucket = ctx->cache[h];
+    for (auto& p : bucket)
+      if (p->key.size() == key.size() && std::memcmp(p->key.data(), key.data(), key.size()) == 0) plan = p.get();
+    t2 = now_ns();
+    if (quick) {   // checking mode: the fingerprint's answer must be the canonical key's
+      if (quick->plan != plan || quick->param_nodes != cut.param_nodes || quick->scalar_nodes != cut.scalar_nodes)
+        return fail(ctx, LT_ERR_ARG, "internal: the record-time fingerprint and the canonical key disagree");
+      ctx->stats.quick_hits++;
+    }
+  }
   const bool hit = plan != nullptr;
   if (!hit) {
     lt_status st = LT_OK;
     std::unique_ptr<Plan> fresh = lower(ctx, cut, &st);
     if (!fresh) {
-      if (bucket.empty()) ctx->cache.erase(h);
+      auto b = ctx->cache.find(h);
+      if (b != ctx->cache.end() && b->second.empty()) ctx->cache.erase(b);
       return st;
     }
     fresh->key = key;
     plan = fresh.get();
-    bucket.push_back(std::move(fresh));
+    ctx->cache[h].push_back(std::move(fresh));
+  }
+  if (ctx->quick_lookup && !quick) {
+    QuickEntry& e = ctx->quick[fp];
+    e.plan = plan;
+    e.generation = ctx->cache_generation;
+    e.hash = h;
+    e.n_nodes = (int32_t)cut.order.size();
+    e.param_nodes = cut.param_nodes;
+    e.scalar_nodes = cut.scalar_nodes;
   }
   const uint64_t t3 = now_ns();
   std::vector<BufRef> bufs, params(cut.param_nodes.size());
@@ -581,6 +633,8 @@ static lt_status barrier_impl(lt_ctx* ctx, int blocking, lt_barrier_info* info, 
   for (auto& kv : ctx->handles) kv.second.donor.reset();
   bufs.clear();
   ctx->nodes.clear();
+  ctx->trace_fp = Fingerprint{};
+  ctx->leaf_of_buffer.clear();
   ctx->epoch++;
   const uint64_t t4 = now_ns();
   if (blocking && ctx->device >= 0) {
@@ -588,14 +642,13 @@ static lt_status barrier_impl(lt_ctx* ctx, int blocking, lt_barrier_info* info, 
     if (e != hipSuccess) return fail(ctx, LT_ERR_DEVICE, std::string("hipStreamSynchronize: ") + hipGetErrorString(e));
   }
   ctx->last_plan = plan;
-  ctx->last_key.swap(key);
   ctx->stats.barriers++;
   (hit ? ctx->stats.cache_hits : ctx->stats.cache_misses)++;
   ctx->stats.regions_launched += plan->n_regions;
   if (!hit) ctx->stats.ns_lowering_total += t3 - t2;
   if (info) {
     info->hash = h;
-    info->key_bytes = ctx->last_key.size();
+    info->key_bytes = plan->key.size();
     info->cache_hit = hit ? 1 : 0;
     info->n_nodes = (int32_t)cut.order.size();
     info->n_roots = (int32_t)cut.roots.size();

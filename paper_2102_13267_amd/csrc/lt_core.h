@@ -186,6 +186,34 @@ struct Plan {
   GraphSlots graphs;                 // lt_set_graphs
 };
 
+// Fingerprint of the trace as it is being recorded (section 7 of the paper: hashing while the graph
+// is built, instead of walking it again at the barrier): two independent 64-bit lanes, one word
+// at a time.  It covers every recorded node in record order -- opcode, type, shape, attributes,
+// operands by record index, which earlier leaf shares a leaf's buffer -- so two traces with the
+// same fingerprint and the same live roots have the same canonical form.
+struct Fingerprint {
+  uint64_t a = 0x9e3779b97f4a7c15ull, b = 0xc2b2ae3d27d4eb4full;
+  void mix(uint64_t w) {
+    a = (a ^ w) * 0xff51afd7ed558ccdull;
+    a ^= a >> 29;
+    b = (b + w) * 0xc4ceb9fe1a85ec53ull;
+    b ^= b >> 31;
+  }
+  bool operator==(const Fingerprint& o) const { return a == o.a && b == o.b; }
+};
+struct FingerprintHash {
+  size_t operator()(const Fingerprint& f) const { return (size_t)(f.a ^ (f.b * 0x9e3779b97f4a7c15ull)); }
+};
+
+// What the barrier needs of a trace it has seen before, by fingerprint: the plan, and where in the
+// recorded trace the plan's parameters and scalars are (record indices, canonical order).
+struct QuickEntry {
+  Plan* plan = nullptr;
+  uint64_t generation = 0, hash = 0;
+  int32_t n_nodes = 0;                       // nodes of the canonical cut
+  std::vector<int32_t> param_nodes, scalar_nodes;
+};
+
 // What a captured step has to know about the barrier it repeats: the plan, the tensors whose
 // data were the plan's device parameters (canonical order) with what the plan assumed of them,
 // the non-special scalars, and the tensors that received the roots.
@@ -221,8 +249,13 @@ struct lt_ctx {
   uint64_t next_id = 1, epoch = 0;
   std::unordered_map<uint64_t, std::vector<std::unique_ptr<lt::Plan>>> cache;
   lt::Plan* last_plan = nullptr;
-  std::vector<uint8_t> last_key;
   uint64_t cache_generation = 0;             // bumped whenever the plan cache is cleared
+  // record-time fingerprint of the pending trace, the first leaf of every buffer it reads, and
+  // the plans by fingerprint (lt_set_quick_lookup)
+  lt::Fingerprint trace_fp;
+  std::unordered_map<const lt::Buffer*, int32_t> leaf_of_buffer;
+  std::unordered_map<lt::Fingerprint, lt::QuickEntry, lt::FingerprintHash> quick;
+  int quick_lookup = 1;                      // 0: off, 1: on, 2: on, and every hit is checked against the canonical key
   lt::StepRecord last_step;                  // the last barrier, for lt_step_capture
   lt_stats_t stats{};
   std::string err;

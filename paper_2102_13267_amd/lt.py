@@ -46,7 +46,7 @@ class BarrierInfo(C.Structure):
 class Stats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in (
         "barriers", "cache_hits", "cache_misses", "nodes_recorded", "regions_launched", "kernels_launched",
-        "ns_lowering_total", "arena_bytes_in_use", "arena_bytes_peak", "live_tensors", "fallback_ops", "replays", "graph_launches", "graphs_built")]
+        "ns_lowering_total", "arena_bytes_in_use", "arena_bytes_peak", "live_tensors", "fallback_ops", "replays", "graph_launches", "graphs_built", "quick_hits")]
 
 
 class TensorDesc(C.Structure):
@@ -151,6 +151,7 @@ def load_library():
         "lt_set_streams": [P, i32],
         "lt_set_fusion": [P, i32],
         "lt_set_graphs": [P, i32],
+        "lt_set_quick_lookup": [P, i32],
         "lt_set_fallback": [P, FALLBACK_FN, P],
         "lt_last_launches": [P, C.POINTER(LaunchRecord), i32, C.POINTER(i32)],
         "lt_step_capture": [P, C.POINTER(P)],
@@ -589,6 +590,11 @@ class Context:
                                       "version": 2, "strides": None}
         t = torch.as_tensor(m, device=f"cuda:{self.device}")
         return t.view(code[1]) if desc["dtype"] == "bf16" else t
+
+    def set_quick_lookup(self, mode: int):
+        """lt_set_quick_lookup: 0 off, 1 plans found by the record-time fingerprint, 2 the same with
+        every hit checked against the canonical key."""
+        self._check(self._lib.lt_set_quick_lookup(self._h, int(mode)))
 
     def set_graphs(self, on: bool):
         """lt_set_graphs: steps whose buffers sit where they sat before run as one HIP graph."""

@@ -29,6 +29,17 @@ _build_if_nothing_is_built()
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # Every context of the test suite checks each plan that the record-time fingerprint finds
+    # against the canonical key (lt_set_quick_lookup mode 2): a disagreement fails the barrier.
+    import paper_2102_13267_amd.lt as lt
+    if not getattr(lt.Context, "_checks_quick_lookup", False):
+        plain_init = lt.Context.__init__
+
+        def checking_init(self, *args, **kwargs):
+            plain_init(self, *args, **kwargs)
+            self.set_quick_lookup(2)
+        lt.Context.__init__ = checking_init
+        lt.Context._checks_quick_lookup = True
 
 
 def read_golden(name):

@@ -332,16 +332,16 @@ __global__ __launch_bounds__(kBlock) void lt_split_post_stream_kernel(const Spli
     // partial products, summed in split order (the result does not depend on scheduling)
     RawVec s0 = {0, 0, 0, 0}, s1 = {0, 0, 0, 0};
     uint32_t sp = 0;
-    for (; sp + 4u <= a.splits; sp += 4u) {
-      RawVec t0v[4], t1v[4];
+    for (; sp + 2u <= a.splits; sp += 2u) {
+      RawVec t0v[2], t1v[2];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
+      for (int j = 0; j < 2; ++j) {
         const float* src = a.ws + (uint64_t)(sp + j) * a.stride;
         t0v[j] = *(const RawVec*)(src + e0);
         t1v[j] = *(const RawVec*)(src + e1);
       }
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
+      for (int j = 0; j < 2; ++j) {
         s0 += t0v[j];
         s1 += t1v[j];
       }

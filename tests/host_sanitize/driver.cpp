@@ -179,6 +179,50 @@ int main() {
   int nrec = 0;
   CHECK(lt_last_launches(ctx, recs, 4, &nrec) == LT_OK);
   CHECK(lt_shutdown(ctx) == LT_OK);
+  // hashing while recording (every fingerprint hit checked against the canonical key), captured
+  // steps, re-pointed inputs
+  CHECK(lt_init(-1, nullptr, nullptr, 0, &ctx) == LT_OK);
+  CHECK(lt_set_quick_lookup(ctx, 3) == LT_ERR_ARG && lt_set_quick_lookup(ctx, 2) == LT_OK && lt_set_graphs(ctx, 1) == LT_OK);
+  lt_step* none = nullptr;
+  CHECK(lt_step_capture(ctx, &none) == LT_ERR_ARG && none == nullptr);
+  lt_tensor sp = dev({512}, LT_F32, true), sg = dev({512});
+  lt_tensor snorm = 0;
+  for (int it = 0; it < 3; ++it) {
+    lt_tensor lr = scal(0.125 * (it + 1));
+    lt_tensor upd = op(LT_OP_SUB, {sp, op(LT_OP_MUL, {sg, lr})});
+    lt_tensor nn = op(LT_OP_SUM, {op(LT_OP_SQUARE, {upd})});
+    CHECK(lt_assign(ctx, sp, upd) == LT_OK);
+    if (snorm) CHECK(lt_release(ctx, snorm) == LT_OK);
+    snorm = nn;
+    rel({lr, upd});
+    CHECK(lt_barrier(ctx, 1, &info) == LT_OK && info.cache_hit == (it > 0));
+  }
+  lt_stats_t qs{};
+  CHECK(lt_stats(ctx, &qs) == LT_OK && qs.quick_hits == 2 && qs.cache_hits == 2);
+  lt_step* step = nullptr;
+  CHECK(lt_step_capture(ctx, &step) == LT_OK && step != nullptr);
+  double sv[4];
+  CHECK(lt_step_scalars(step, sv, 4) == 1 && sv[0] == 0.375 && lt_step_scalars(nullptr, sv, 4) == -1);
+  CHECK(lt_step_replay(ctx, step, nullptr, 0, 1, &info) == LT_OK && info.cache_hit == 1 && info.n_regions >= 1);
+  sv[0] = 0.5;
+  CHECK(lt_step_replay(ctx, step, sv, 1, 0, nullptr) == LT_OK);
+  CHECK(lt_step_replay(ctx, step, sv, 2, 0, nullptr) == LT_ERR_ARG);
+  CHECK(lt_tensor_rebind(ctx, sg, nullptr) == LT_OK);                 // (a null device: any pointer)
+  CHECK(lt_tensor_rebind(ctx, snorm, nullptr) == LT_ERR_ARG);         // a result: library memory
+  CHECK(lt_step_replay(ctx, step, nullptr, 0, 1, nullptr) == LT_OK);
+  lt_tensor pend = op(LT_OP_EXP, {sg});
+  CHECK(lt_tensor_rebind(ctx, sg, nullptr) == LT_ERR_ARG);            // read by the pending trace
+  CHECK(lt_step_replay(ctx, step, nullptr, 0, 1, nullptr) == LT_ERR_ARG);
+  CHECK(lt_barrier(ctx, 1, nullptr) == LT_OK);
+  rel({pend});
+  CHECK(lt_stats(ctx, &qs) == LT_OK && qs.replays == 3);
+  CHECK(lt_release(ctx, sg) == LT_OK);
+  CHECK(lt_step_replay(ctx, step, nullptr, 0, 1, nullptr) == LT_ERR_HANDLE);
+  CHECK(lt_set_fusion(ctx, 0) == LT_OK);
+  CHECK(lt_step_replay(ctx, step, nullptr, 0, 1, nullptr) == LT_ERR_ARG);   // the plan is gone with the cache
+  lt_step_free(step);
+  lt_step_free(nullptr);
+  CHECK(lt_shutdown(ctx) == LT_OK);
   // arena exhaustion on a small workspace: found before anything runs, trace stays pending
   CHECK(lt_init(-1, nullptr, nullptr, 13u << 20, &ctx) == LT_OK);
   lt_tensor big = dev({1 << 20});

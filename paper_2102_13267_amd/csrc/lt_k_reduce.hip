@@ -266,6 +266,59 @@ __global__ __launch_bounds__(kColBlock) void lt_col_reduce_kernel(const ColArgs 
   const uint32_t r1 = min(a.rows, r0 + rows_per_slab);
   const float id = red_identity(a.red);
   const uint32_t pstride = (a.cols + 3u) & ~3u;   // floats between slabs of partials
+  if (NIN == 0 && a.narrow) {
+    // Narrow and small (at most 64 columns, at most 65536 elements; one workgroup): a strip of 256
+    // columns would leave all but a few lanes idle and walk the rows one by one.  Instead thread
+    // t < S, S the largest multiple of cols within the workgroup, takes the elements t, t + S,
+    // t + 2 S, ... -- all of column t % cols -- four of them per interpreter dispatch; the threads
+    // of a column then meet in LDS.
+    float* lf = (float*)lds;   // kColBlock x 4 floats
+    const uint32_t cols = a.cols, S = ((uint32_t)kColBlock / cols) * cols, n = a.rows * cols;
+    float part = id;
+    if (threadIdx.x < S) {
+      for (uint32_t i0 = threadIdx.x; i0 < n; i0 += 4u * S) {
+        uint32_t nv = 1u;
+#pragma unroll
+        for (uint32_t e = 1; e < (uint32_t)kVec; ++e) nv += (i0 + e * S < n) ? 1u : 0u;
+        RF<16> f = rf_zero<16>();
+#pragma unroll 1
+        for (uint32_t k = 0; k < pro.n_in; ++k) {
+          const EwIn& in = pro.in[k];
+          Quad q;
+#pragma unroll
+          for (uint32_t e = 0; e < (uint32_t)kVec; ++e) {
+            const uint32_t ee = e < nv ? e : nv - 1u;   // (past the end: the last valid one again, no load behind a branch)
+            q.v[e] = load_elem<false>(in.ptr, in.dtype, elem_offset(pro, in, i0 + ee * S));
+          }
+          f = rf_set<16>(f, k, q);
+        }
+        f = interp<16>(f, pro_regs, pro_n);
+        const Quad r = rf_get(f, pro.anchor_slot);
+        part = red_combine(a.red, part, r.v[0]);
+        if (nv > 1u) part = red_combine(a.red, part, r.v[1]);
+        if (nv > 2u) part = red_combine(a.red, part, r.v[2]);
+        if (nv > 3u) part = red_combine(a.red, part, r.v[3]);
+      }
+    }
+    lf[threadIdx.x] = part;
+    __syncthreads();
+    float colv = id;
+    if (threadIdx.x < cols)
+      for (uint32_t j = threadIdx.x; j < S; j += cols) colv = red_combine(a.red, colv, lf[j]);   // fixed order
+    if (a.red == kRedMean) colv = colv / (float)a.rows;
+    __syncthreads();
+    if (threadIdx.x < cols) lf[threadIdx.x] = colv;
+    __syncthreads();
+    const uint32_t c4 = threadIdx.x * (uint32_t)kVec;
+    if (c4 < cols) {
+      const uint32_t nvp = cols - c4 >= (uint32_t)kVec ? (uint32_t)kVec : cols - c4;
+      Quad accq;
+#pragma unroll
+      for (uint32_t e = 0; e < (uint32_t)kVec; ++e) accq.v[e] = e < nvp ? lf[c4 + e] : 0.0f;
+      run_post(a.post, post_regs, accq, c4, nvp);
+    }
+    return;
+  }
   float4 acc = make_float4(id, id, id, id);
   if (nvalid) {
     uint32_t r = r0 + wave;
@@ -539,7 +592,10 @@ hipError_t launch_col_reduce(const ColArgs& args, uint32_t grid_x, uint32_t grid
     else if (mk == 1) LT_LAUNCH((lt_col_reduce_kernel<16, 2, 4, false, 2>), g, b, s, a);
     else if (mk == 2 && four) LT_LAUNCH((lt_col_reduce_kernel<32, 2, 8, true, 2>), g, b, s, a);
     else if (mk == 2) LT_LAUNCH((lt_col_reduce_kernel<16, 2, 8, true, 2>), g, b, s, a);
-    else LT_LAUNCH((lt_col_reduce_kernel<16, 0, 1, false>), g, b, s, a);
+    else if (a.cols <= 64u && (uint64_t)a.rows * a.cols <= 65536u) {
+      a.narrow = 1u;   // narrow and small: one workgroup, a thread per (column, row residue)
+      LT_LAUNCH((lt_col_reduce_kernel<16, 0, 1, false>), dim3(1, 1), b, s, a);
+    } else LT_LAUNCH((lt_col_reduce_kernel<16, 0, 1, false>), g, b, s, a);
   }
   return hipGetLastError();
 }

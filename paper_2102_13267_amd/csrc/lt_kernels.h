@@ -131,7 +131,8 @@ struct ColArgs {
   EwProg post;         // iteration space [cols]
   float* partials;     // [gridDim.y, cols]
   uint32_t* tickets;   // [gridDim.x], zero before launch; reset by the kernel
-  uint32_t rows, cols, red, pad;
+  uint32_t rows, cols, red;
+  uint32_t narrow;     // set by launch_col_reduce: at most 64 columns and 65536 elements, one workgroup (see the kernel)
   // filled in by launch_col_reduce for the streamed variants: input numbers of the (up to two)
   // inputs read in full and of the (up to two) per-row inputs (kColVec), padded with the first
   uint32_t vin[2], cin[2];

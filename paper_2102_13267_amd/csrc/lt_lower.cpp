@@ -1162,7 +1162,10 @@ struct Lowering {
     if (r->has_fin) post_space = r->fin_shape;
     ProgBuild post;
     std::vector<int32_t> post_members = post_m;
-    post_members.insert(post_members.begin(), a);
+    post_members.push_back(a);
+    // canonical (= topological) order; a member that only the epilogue reads may well have been
+    // numbered before the anchor (x - 0.5 * v: the operands are numbered last to first)
+    std::sort(post_members.begin(), post_members.end());
     if (!build_prog(post_members, post_space, Val{a, 0}, out, r->kind == C_ALL, &post)) return false;
     const uint32_t red = an->op == LT_OP_SUM ? ltk::kRedSum : an->op == LT_OP_AMAX ? ltk::kRedMax : ltk::kRedMean;
     if (r->kind == C_ROW) {
@@ -1477,7 +1480,10 @@ struct Lowering {
     }
     ProgBuild post;
     std::vector<int32_t> post_members = post_m;
-    post_members.insert(post_members.begin(), a);
+    post_members.push_back(a);
+    // canonical (= topological) order; a member that only the epilogue reads may well have been
+    // numbered before the anchor (x - 0.5 * v: the operands are numbered last to first)
+    std::sort(post_members.begin(), post_members.end());
     if (!build_prog(post_members, os, Val{a, 0}, out, false, &post)) return false;
     if (r->sealed) {
       storage_of[a][0] = -1;

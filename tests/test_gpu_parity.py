@@ -1210,6 +1210,58 @@ def test_random_traces_numeric(ctx, shape, trials):
         del got, ref, lt, et
 
 
+def test_epilogue_member_numbered_before_the_anchor(ctx):
+    """`anchor(...) - 0.5 * v`: operands are numbered last to first, so the product that only the
+    epilogue reads gets a smaller canonical number than the reduction / contraction it joins."""
+    E = Eager()
+    g = rng(77)
+    a, w, r = (g.standard_normal(s).astype(np.float32) for s in ((96, 40), (40, 24), (96, 24)))
+    x, v, c = g.standard_normal((96, 40)).astype(np.float32), g.standard_normal(96).astype(np.float32), g.standard_normal(40).astype(np.float32)
+
+    def prog(B, a, w, r, x, v, c):
+        y = B.add(B.matmul(a, w), B.mul(r, 0.5))
+        z = B.sub(B.sum(x, axis=1), B.mul(v, 0.5))
+        u = B.sub(B.sum(x, axis=0), B.mul(c, 0.25))
+        t = B.sub(B.sum(B.square(x)), B.mul(B.sum(v), 2.0))
+        return y, z, u, t
+
+    got = prog(ctx, *(ctx.tensor(t) for t in (a, w, r, x, v, c)))
+    ref = prog(E, *(E.tensor(t) for t in (a, w, r, x, v, c)))
+    info = ctx.barrier()
+    assert info.n_regions <= 5
+    for gt, rt, what in zip(got, ref, "yzut"):
+        check(ctx, E, gt, rt, TOL32, what)
+
+
+@pytest.mark.parametrize("rows,cols", [(128, 10), (1, 1), (5, 3), (1000, 7), (64, 64), (1023, 64), (300, 33), (4, 61), (130, 12)])
+def test_column_reductions_of_narrow_matrices(ctx, rows, cols):
+    """Axis-0 reductions of small matrices of at most 64 columns take a path of their own (a
+    thread per column and row residue, four rows per interpreter dispatch, one workgroup): one
+    column, fewer rows than a dispatch takes, a column count that does not divide the workgroup,
+    the largest column count, more rows than threads; sum / max / mean; a prologue with a row
+    vector, a column vector and a scalar; an epilogue; bf16 and int inputs."""
+    E = Eager()
+    g = rng(1300 + rows * 7 + cols)
+    x = g.standard_normal((rows, cols)).astype(np.float32)
+    y = round_to_bf16(g.standard_normal((rows, cols), dtype=np.float32))
+    rv = g.standard_normal(cols).astype(np.float32)
+    cv = g.standard_normal((rows, 1)).astype(np.float32)
+    k = g.integers(-5, 6, (rows, cols)).astype(np.int32)
+
+    def prog(B, x, y, rv, cv, k):
+        s = B.sum(x, axis=0)                                                     # the bare operand
+        m = B.amax(B.mul(B.add(x, rv), B.expand(cv, (rows, cols))), axis=0)      # row and column vectors in the prologue
+        a = B.sub(B.mean(B.mul(B.tanh(x), B.cast(y, "f32")), axis=0), B.mul(rv, 0.5))   # bf16 input, an epilogue
+        i = B.sum(B.mul(B.cast(k, "f32"), 2.0), axis=0)                          # integer input
+        return s, m, a, i
+
+    got = prog(ctx, ctx.tensor(x), ctx.tensor(y, dtype="bf16"), ctx.tensor(rv), ctx.tensor(cv), ctx.tensor(k))
+    ref = prog(E, E.tensor(x), E.tensor(y, dtype="bf16"), E.tensor(rv), E.tensor(cv), E.tensor(k))
+    tol = 2e-5 * max(1.0, rows ** 0.5 / 8)   # (partial sums of `rows` terms against max|ref| of a cancelling sum)
+    for gt, rt, what in zip(got, ref, ("sum", "max", "mean", "int")):
+        check(ctx, E, gt, rt, tol, what)
+
+
 @pytest.mark.parametrize("rows,cols,dtype", [(8, 256, "f32"), (67, 512, "f32"), (64, 1024, "bf16"), (521, 768, "bf16"),
                                               (2048, 1024, "bf16"), (300, 260, "f32"), (130, 250, "bf16")])
 def test_column_reductions_with_per_row_inputs(ctx, rows, cols, dtype):

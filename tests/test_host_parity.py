@@ -507,3 +507,21 @@ def test_fallback_for_ops_without_a_lowering():
         ctx.barrier()
     assert e.value.status == 5
     del out, last, mid
+
+
+def test_epilogue_producer_numbered_before_its_anchor_lowers():
+    """The operands of `anchor(...) - 0.5 * v` are numbered last to first, so the product joins the
+    anchored region with a smaller canonical number than the anchor: code generation must still
+    treat it as a member (it once looked members up in a list that was not sorted)."""
+    from paper_2102_13267_amd import Context
+    ctx = Context(device=None)
+    x = ctx.from_device(0, "f32", (128, 10))
+    rv = ctx.from_device(0, "f32", (10,))
+    a, w, r = ctx.from_device(0, "f32", (64, 32)), ctx.from_device(0, "f32", (32, 16)), ctx.from_device(0, "f32", (64, 16))
+    u = ctx.sub(ctx.mean(ctx.tanh(x), axis=0), ctx.mul(rv, 0.5))
+    y = ctx.add(ctx.matmul(a, w), ctx.mul(r, 0.5))
+    info = ctx.barrier()
+    assert info.n_regions == 2
+    plan = ctx.dump_plan().splitlines()
+    assert plan[0].startswith("R0 COL") and plan[1].startswith("R1 MM")
+    assert u is not None and y is not None

@@ -379,7 +379,10 @@ class Eager:
             assert dst.dtype == src.dtype and dst.data.shape == src.data.shape
             dst.data[...] = src.data
             return
-        dst.data, dst.dtype = src.data, src.dtype
+        # a copy: the destination must not see later in-place writes to the source's memory (the
+        # source may become the base of a view afterwards) -- an in-place update is a substitution
+        # of one tensor's value, never of another's (sections 4.3 and 4.4 of the paper)
+        dst.data, dst.dtype = src.data.copy(), src.dtype
 
     def barrier(self, blocking: bool = True) -> None:
         return None

@@ -941,6 +941,8 @@ class Tracer:
                             continue
                         if not all(u in q["members"] or u in home["members"] for m in q["members"] for u in users[m]):
                             continue
+                        if any(u == home["anchor"] for m in q["members"] for u in users[m]):
+                            continue      # (what the anchor itself reads must exist in memory)
                         if not caps_ok(home["members"] | q["members"]) or not can_union(home, q):
                             continue
                         union(home, q)

@@ -394,7 +394,8 @@ struct Lowering {
             bool ok = true;
             for (int32_t m : q->members) {
               ok = ok && !is_root[m];
-              for (int32_t u : users[m]) ok = ok && (q->has(u) || home->has(u));
+              // (what the anchor itself reads -- a contraction's operand -- must exist in memory)
+              for (int32_t u : users[m]) ok = ok && (q->has(u) || home->has(u)) && u != home->anchor;
             }
             if (!ok) continue;
             if (!caps_ok(merged(home->members, q->members)) || !can_union(home, q)) continue;

@@ -278,7 +278,9 @@ def check_plan(key: bytes, n_nodes: int, plan_text: str):
                 need(an.op == SLICE_UPDATE and len(members) == 1, f"R{k}: a window update stands alone")
             elif r["kind"] == "MM":
                 need(an.op == MATMUL and not before, f"R{k}: contraction region with a prologue")
-                perms = [m for m in after if nodes[m].op == PERMUTE]
+                # a permutation OF THE PRODUCT is its output layout and closes the region; a
+                # permutation of another region's value is an ordinary strided read
+                perms = [m for m in after if nodes[m].op == PERMUTE and operands(m)[0][0] == a]
                 if perms:
                     need(len(after) == 1, f"R{k}: a layout permutation must be the contraction's only follower")
                 else:

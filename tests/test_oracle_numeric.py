@@ -426,3 +426,23 @@ def test_views_share_storage_and_window_ops():
     r = E.view_reshape(x, (6, 4))
     E.assign(x, E.neg(x))                                        # updating the base shows in its views
     assert np.array_equal(f(E, r), -want.reshape(6, 4)) and np.array_equal(f(E, w), -want[:, 1:3])
+
+
+def test_assign_gives_the_destination_a_value_of_its_own():
+    """Sections 4.3 / 4.4: an in-place update substitutes ONE tensor's value.  After `b <- a`, an
+    update of a through a view (which writes a's memory) must leave b alone -- values typed by hand."""
+    E = Eager()
+    a = E.tensor(np.array([[1.0, 2.0], [3.0, 4.0]], np.float32))
+    b = E.tensor(np.zeros((2, 2), np.float32))
+    c = E.tensor(np.array([[10.0, 20.0], [30.0, 40.0]], np.float32))
+    E.assign(b, a)                                    # b = [[1, 2], [3, 4]]
+    v = E.view_permute(a, (1, 0))                     # a view of a: a is written in place from now on
+    E.assign(v, c)                                    # a = c^T
+    assert np.array_equal(E.fetch(a), [[10.0, 30.0], [20.0, 40.0]])
+    assert np.array_equal(E.fetch(b), [[1.0, 2.0], [3.0, 4.0]])
+    # and the other way round: a destination bound to a base's value does not follow the base
+    d = E.tensor(np.zeros((2, 2), np.float32))
+    E.assign(d, a)
+    E.assign(v, E.mul(v, 2.0))
+    assert np.array_equal(E.fetch(a), [[20.0, 60.0], [40.0, 80.0]])
+    assert np.array_equal(E.fetch(d), [[10.0, 30.0], [20.0, 40.0]])

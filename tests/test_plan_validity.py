@@ -161,14 +161,15 @@ def random_trace(seed):
     return build
 
 
-@pytest.mark.parametrize("seed", range(120))
+@pytest.mark.parametrize("seed", range(400))
 def test_random_traces_give_valid_plans(seed):
     ctx = Context()
     keep = random_trace(seed)(ctx, lambda shape, dtype="f32", donatable=False: ctx.tensor(np.zeros(shape, np.float32), donatable=donatable))
     try:
         key, n, plan = lib_plan(ctx)
     except Exception as e:
-        if type(e).__name__ == "LtError" and e.status == 5:
+        # (an "internal: ..." message is a mistake of the lowering, never a reason to skip)
+        if type(e).__name__ == "LtError" and e.status == 5 and "internal" not in str(e):
             pytest.skip("the trace has an op pattern without a lowering: " + str(e))
         raise
     check_plan(key, n, plan)

@@ -42,13 +42,14 @@ def round_to_bf16(a: np.ndarray) -> np.ndarray:
     bfloat16 is the upper 16 bits of an IEEE binary32.  NaNs stay NaNs (a
     quiet bit is forced so that truncation cannot turn a NaN into infinity).
     """
+    shape = np.shape(a)                       # (ascontiguousarray makes a rank-0 value rank 1)
     a = np.ascontiguousarray(a, dtype=np.float32)
     bits = a.view(np.uint32).astype(np.uint64)
     lsb = (bits >> 16) & 1
     rounded = ((bits + 0x7FFF + lsb) >> 16) << 16
     nan = np.isnan(a)
     rounded = np.where(nan, (bits | 0x00400000) & 0xFFFF0000, rounded)
-    return (rounded & 0xFFFFFFFF).astype(np.uint32).view(np.float32).reshape(a.shape)
+    return (rounded & 0xFFFFFFFF).astype(np.uint32).view(np.float32).reshape(shape)
 
 
 class ETensor:

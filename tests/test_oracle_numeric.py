@@ -446,3 +446,12 @@ def test_assign_gives_the_destination_a_value_of_its_own():
     E.assign(v, E.mul(v, 2.0))
     assert np.array_equal(E.fetch(a), [[20.0, 60.0], [40.0, 80.0]])
     assert np.array_equal(E.fetch(d), [[10.0, 30.0], [20.0, 40.0]])
+
+
+def test_bf16_rounding_keeps_rank_zero():
+    """A bf16 reduction over everything is a rank-0 tensor, like its fp32 counterpart."""
+    assert round_to_bf16(np.float32(1.00390625)).shape == () and float(round_to_bf16(np.float32(1.00390625))) == 1.0
+    E = Eager()
+    x = E.tensor(np.full((4, 4), 0.5, np.float32), dtype="bf16")
+    s = E.sum(x)
+    assert s.shape == () and E.fetch(s).shape == () and float(E.fetch(s)) == 8.0

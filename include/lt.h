@@ -236,7 +236,9 @@ lt_status lt_shape(lt_ctx* ctx, lt_tensor t, lt_dtype* dtype, int* rank, int64_t
  * lt_step_replay returns LT_ERR_ARG.  Errors: LT_ERR_ARG no barrier has run; LT_ERR_HANDLE an
  * input tensor of the step has been released (it could not be named again);
  * LT_ERR_UNSUPPORTED the plan writes over an input's buffer and the result does not belong to
- * that same tensor (only x <- f(x) may be repeated in place).
+ * that same tensor (only x <- f(x) may be repeated in place), or during the step lt_assign gave
+ * a tensor the plain data or scalar of another tensor (src not pending: the tensor only becomes a
+ * second name of src's buffer, which leaves nothing in the trace for the plan to repeat).
  *
  * lt_step_replay: runs the plan on the CURRENT data of the same input tensors and binds the
  * results to the same result tensors, exactly as the barrier did (donated inputs are updated in

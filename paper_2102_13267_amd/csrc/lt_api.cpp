@@ -772,6 +772,9 @@ static lt_status assign(lt_ctx* ctx, lt_tensor dst_id, lt_tensor src_id, bool hi
   }
   BufRef donor = dst->donor;
   if (dst->kind == H_DATA && dst->buf && dst->buf->donatable) donor = dst->buf;
+  // dst becomes a second name of src's buffer (or scalar): host bookkeeping that leaves no node in
+  // the trace, so a captured step could not repeat it
+  if (src->kind != H_PENDING) ctx->bound_plain = true;
   unbind(dst);
   dst->kind = src->kind;
   dst->dtype = src->dtype;

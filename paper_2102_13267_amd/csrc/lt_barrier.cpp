@@ -614,6 +614,8 @@ static lt_status barrier_impl(lt_ctx* ctx, int blocking, lt_barrier_info* info, 
   rec.scalars = scalars;
   rec.roots.resize(cut.roots.size());
   for (size_t r = 0; r < cut.roots.size(); ++r) rec.roots[r] = cut.roots[r]->id;
+  rec.bound_plain = ctx->bound_plain;
+  ctx->bound_plain = false;
   // result binding: after the barrier every evaluated handle is plain data (or a scalar when
   // folding reduced it to one); a new IR graph starts (section 3)
   for (size_t r = 0; r < cut.roots.size(); ++r) {
@@ -689,6 +691,9 @@ lt_status lt_step_capture(lt_ctx* ctx, lt_step** out) {
   step->written.assign(rec.params.size(), 0);
   for (const PtrPatch& p : plan->ptr_patches)
     if (p.write && p.storage >= 0 && plan->storages[p.storage].param >= 0) step->written[plan->storages[p.storage].param] = 1;
+  if (rec.bound_plain)
+    return fail(ctx, LT_ERR_UNSUPPORTED, "lt_step_capture: during the step lt_assign gave a tensor the plain data (or scalar) of another tensor; "
+                                         "that leaves no node in the trace, so running the plan again would not repeat it");
   // every input must be a tensor that can be named again
   for (size_t k = 0; k < rec.params.size(); ++k) {
     auto it = ctx->handles.find(rec.params[k].tensor);

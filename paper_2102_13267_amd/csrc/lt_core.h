@@ -229,6 +229,7 @@ struct StepRecord {
   std::vector<StepParam> params;
   std::vector<double> scalars;
   std::vector<uint64_t> roots;       // tensor ids, in the plan's root order
+  bool bound_plain = false;          // a tensor took another's plain data or scalar (no node): not repeatable
 };
 
 }  // namespace lt
@@ -257,6 +258,7 @@ struct lt_ctx {
   std::unordered_map<lt::Fingerprint, lt::QuickEntry, lt::FingerprintHash> quick;
   int quick_lookup = 1;                      // 0: off, 1: on, 2: on, and every hit is checked against the canonical key
   lt::StepRecord last_step;                  // the last barrier, for lt_step_capture
+  bool bound_plain = false;                  // since the last barrier, lt_assign gave a tensor plain data or a scalar
   lt_stats_t stats{};
   std::string err;
   float* red_partials = nullptr;             // reduction scratch inside the workspace

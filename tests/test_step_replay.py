@@ -266,3 +266,79 @@ def test_traced_steps_as_graphs(gctx):
     assert ga == 0 and gb >= 4
     assert na == nb
     assert np.array_equal(pa, pb) and np.array_equal(ma, mb)
+
+
+@pytest.mark.gpu
+def test_random_stateful_steps_replayed_equal_traced(gctx):
+    """Random traces with in-place updates of their inputs (the generator of the plan-validity
+    test), run as four traced steps, against two traced steps, a capture and two replays (HIP graphs
+    on odd seeds): every input and every live result after every step, bit for bit.  The capture is
+    taken at the second step, when updated inputs already sit in library memory (the steady state)."""
+    from test_plan_validity import random_trace
+    ctx = gctx
+    compared = 0
+    for seed in range(60):
+        rg = np.random.Generator(np.random.PCG64(9000 + seed))
+        values = []
+
+        def run(replay_from):
+            made, calls = [], [0]
+
+            def mk(shape, dtype="f32", donatable=False):
+                k = calls[0]
+                calls[0] += 1
+                if k == len(made):
+                    if k == len(values):
+                        values.append((rg.standard_normal(shape) * 0.5).astype(np.float32))
+                    made.append(ctx.tensor(values[k].copy(), donatable=donatable))
+                return made[k]
+
+            snaps, step, live = [], None, None
+            for s in range(4):
+                if step is None:
+                    calls[0] = 0
+                    live = None
+                    live = random_trace(seed)(ctx, mk)
+                    ctx.barrier()
+                    if s + 1 == replay_from:
+                        step = ctx.capture_step()
+                        ctx.set_graphs(bool(seed & 1))
+                else:
+                    step.replay(blocking=bool(s & 1))
+                snaps.append([np.asarray(ctx.fetch(t)).copy() for t in made + [t for t in live if t not in made]])
+            ctx.set_graphs(False)
+            return snaps
+
+        try:
+            traced = run(None)
+            replayed = run(2)
+        except LtError as e:
+            ctx.set_graphs(False)
+            if e.status in (5, 6) and "internal" not in str(e):
+                continue                      # no lowering for the pattern, or the step cannot be captured
+            raise
+        for s, (a, b) in enumerate(zip(traced, replayed)):
+            assert len(a) == len(b)
+            for k, (x, y) in enumerate(zip(a, b)):
+                assert np.array_equal(x, y, equal_nan=True), (seed, s, k)
+        compared += 1
+    assert compared >= 40
+
+
+def test_capture_refuses_a_step_that_bound_plain_data():
+    """t2 <- t3 with t3 plain data only makes t2 a second name of t3's buffer: no node records it,
+    so a replay could not repeat it (t2 would keep naming the buffer of the captured step)."""
+    ctx = Context(device=None)
+    t2 = ctx.from_device(0, "f32", (8, 16), donatable=True)
+    t3 = ctx.from_device(0, "f32", (8, 16), donatable=True)
+    ctx.assign(t2, t3)
+    ctx.assign(t3, ctx.add(t3, 1.0))
+    ctx.barrier()
+    with pytest.raises(LtError) as e:
+        ctx.capture_step()
+    assert e.value.status == 5 and "plain data" in str(e.value)
+    # the next step without such an assignment can be captured
+    ctx.assign(t3, ctx.add(t3, 1.0))
+    ctx.barrier()
+    ctx.capture_step().free()
+    assert t2 is not None

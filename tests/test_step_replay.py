@@ -268,61 +268,78 @@ def test_traced_steps_as_graphs(gctx):
     assert np.array_equal(pa, pb) and np.array_equal(ma, mb)
 
 
-@pytest.mark.gpu
-def test_random_stateful_steps_replayed_equal_traced(gctx):
-    """Random traces with in-place updates of their inputs (the generator of the plan-validity
-    test), run as four traced steps, against two traced steps, a capture and two replays (HIP graphs
-    on odd seeds): every input and every live result after every step, bit for bit.  The capture is
-    taken at the second step, when updated inputs already sit in library memory (the steady state)."""
+def _random_steps(ctx, seed, steps, replay_from, graphs):
+    """`steps` steps of the random stateful trace `seed` (the generator of the plan-validity test)
+    on the same tensors: traced, or replayed from step `replay_from` on; HIP graphs on or off.
+    Returns every input and every live result after every step."""
     from test_plan_validity import random_trace
-    ctx = gctx
+    rg = np.random.Generator(np.random.PCG64(9000 + seed))
+    made, calls = [], [0]
+
+    def mk(shape, dtype="f32", donatable=False):
+        k = calls[0]
+        calls[0] += 1
+        if k == len(made):
+            made.append(ctx.tensor((rg.standard_normal(shape) * 0.5).astype(np.float32), donatable=donatable))
+        return made[k]
+
+    snaps, step, live = [], None, None
+    try:
+        for s in range(steps):
+            if step is None:
+                calls[0] = 0
+                live = None
+                live = random_trace(seed)(ctx, mk)
+                ctx.set_graphs(graphs)
+                ctx.barrier(blocking=bool(s % 3))
+                if replay_from is not None and s + 1 == replay_from:
+                    step = ctx.capture_step()
+            else:
+                step.replay(blocking=bool(s & 1))
+            ctx.set_graphs(False)      # (the fetches below are eager work between the graph launches)
+            snaps.append([np.asarray(ctx.fetch(t)).copy() for t in made + [t for t in live if t not in made]])
+            ctx.set_graphs(graphs)
+    finally:
+        ctx.set_graphs(False)
+    return snaps
+
+
+def _compare_random_steps(ctx, seeds, steps, first, second):
     compared = 0
-    for seed in range(60):
-        rg = np.random.Generator(np.random.PCG64(9000 + seed))
-        values = []
-
-        def run(replay_from):
-            made, calls = [], [0]
-
-            def mk(shape, dtype="f32", donatable=False):
-                k = calls[0]
-                calls[0] += 1
-                if k == len(made):
-                    if k == len(values):
-                        values.append((rg.standard_normal(shape) * 0.5).astype(np.float32))
-                    made.append(ctx.tensor(values[k].copy(), donatable=donatable))
-                return made[k]
-
-            snaps, step, live = [], None, None
-            for s in range(4):
-                if step is None:
-                    calls[0] = 0
-                    live = None
-                    live = random_trace(seed)(ctx, mk)
-                    ctx.barrier()
-                    if s + 1 == replay_from:
-                        step = ctx.capture_step()
-                        ctx.set_graphs(bool(seed & 1))
-                else:
-                    step.replay(blocking=bool(s & 1))
-                snaps.append([np.asarray(ctx.fetch(t)).copy() for t in made + [t for t in live if t not in made]])
-            ctx.set_graphs(False)
-            return snaps
-
+    for seed in seeds:
         try:
-            traced = run(None)
-            replayed = run(2)
+            a = _random_steps(ctx, seed, steps, *first)
+            b = _random_steps(ctx, seed, steps, *second)
         except LtError as e:
-            ctx.set_graphs(False)
             if e.status in (5, 6) and "internal" not in str(e):
                 continue                      # no lowering for the pattern, or the step cannot be captured
             raise
-        for s, (a, b) in enumerate(zip(traced, replayed)):
-            assert len(a) == len(b)
-            for k, (x, y) in enumerate(zip(a, b)):
-                assert np.array_equal(x, y, equal_nan=True), (seed, s, k)
+        for s, (x, y) in enumerate(zip(a, b)):
+            assert len(x) == len(y)
+            for k, (u, v) in enumerate(zip(x, y)):
+                assert np.array_equal(u, v, equal_nan=True), (seed, s, k)
         compared += 1
-    assert compared >= 40
+    return compared
+
+
+@pytest.mark.gpu
+def test_random_stateful_steps_replayed_equal_traced(gctx):
+    """Random traces with in-place updates of their inputs, run as four traced steps, against two
+    traced steps, a capture and two replays: every input and every live result after every step,
+    bit for bit.  The capture is taken at the second step, when updated inputs already sit in
+    library memory (the steady state)."""
+    assert _compare_random_steps(gctx, range(60), 4, (None, False), (2, False)) >= 40
+
+
+@pytest.mark.gpu
+def test_random_stateful_steps_as_graphs_equal_eager_launches(gctx):
+    """The same traces for ten steps, traced and replayed, with HIP graphs on against off: a
+    graph is built when a plan meets the same addresses again and launched from then on, with
+    fetches (eager work and synchronisation) between the launches."""
+    before = gctx.stats().graph_launches
+    assert _compare_random_steps(gctx, range(60, 100), 10, (None, False), (None, True)) >= 25
+    assert _compare_random_steps(gctx, range(100, 140), 10, (2, False), (2, True)) >= 25
+    assert gctx.stats().graph_launches - before >= 200
 
 
 def test_capture_refuses_a_step_that_bound_plain_data():

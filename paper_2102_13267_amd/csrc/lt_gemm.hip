@@ -304,6 +304,144 @@ __global__ __launch_bounds__(kGemmThreads, BM == 64 ? 2 : 1) void lt_gemm_kernel
   epilogue<BM, BN, MB, NB>(a, acc, (float*)smem, tile_m, tile_n, wave_m, wave_n, lane, batch, raw);
 }
 
+// ---- small contractions -------------------------------------------------------------------------
+// A product of a few dozen 64 x 64 tiles leaves most compute units idle, and splitting its k over
+// workgroups costs a second launch that adds the partial products up (for a 128 x 784 x 512 layer
+// two launches of 5 to 7 microseconds each, most of it launch and memory latency).  Here a
+// workgroup of eight wavefronts owns a 32 x 32 tile of the output and splits k INSIDE the
+// workgroup: every wave contracts an eighth of k (whole groups of 8) for the whole tile, with its
+// operands fetched from global memory straight into the MFMA 32x32x2 register layout -- lane
+// (x, h) supplies A[x][k] and B[k][x] for the k of half h, and which k of a group goes into which
+// of its four MFMAs is free as long as both operands agree, so a lane takes four CONSECUTIVE k
+// (4 h .. 4 h + 3): one 16-byte load where k is the operand's contiguous dimension, four 4-byte
+// loads that neighbouring lanes coalesce where it is not.  No LDS staging and no barrier in the
+// loop; kSmallG groups (64 k) are in flight per wave while the previous ones are multiplied.  The
+// eight partial tiles meet in LDS, are added in wave order, and the post program runs on the sum:
+// one launch.
+constexpr int kSmallThreads = 512, kSmallWaves = 8, kSmallG = 8, kSmallStride = 32 + kCPad;
+
+template <bool V>
+__device__ __forceinline__ void small_fetch(float (&v)[kSmallG][4], const float* base, int64_t s_k, uint32_t k0, uint32_t k_end) {
+#pragma unroll
+  for (int g = 0; g < kSmallG; ++g) {
+    const uint32_t kg = k0 + (uint32_t)g * 8u;
+    if (V) {   // k is contiguous and a multiple of 4: the four are valid together
+      const bool ok = kg < k_end;
+      const float4 t = *(const float4*)(base + (ok ? kg : 0u));
+      v[g][0] = ok ? t.x : 0.0f; v[g][1] = ok ? t.y : 0.0f; v[g][2] = ok ? t.z : 0.0f; v[g][3] = ok ? t.w : 0.0f;
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const bool ok = kg + (uint32_t)j < k_end;
+        const float t = base[(int64_t)(ok ? kg + (uint32_t)j : 0u) * s_k];   // (past the end: element 0 again, in bounds, zeroed)
+        v[g][j] = ok ? t : 0.0f;
+      }
+    }
+  }
+}
+
+__device__ __forceinline__ void small_mma(v16f& acc0, v16f& acc1, const float (&av)[kSmallG][4], const float (&bv)[kSmallG][4]) {
+#pragma unroll
+  for (int g = 0; g < kSmallG; ++g) {
+    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(av[g][0], bv[g][0], acc0, 0, 0, 0);
+    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(av[g][1], bv[g][1], acc1, 0, 0, 0);
+    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(av[g][2], bv[g][2], acc0, 0, 0, 0);
+    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(av[g][3], bv[g][3], acc1, 0, 0, 0);
+  }
+}
+
+// AV / BV: k is the operand's contiguous dimension and every group of four is a whole, 16-byte
+// aligned vector (the launcher checks the pointer, the strides and k % 4).
+template <bool AV, bool BV>
+__global__ __launch_bounds__(kSmallThreads) void lt_gemm_small_kernel(const GemmArgs a) {
+  __shared__ __attribute__((aligned(16))) float Cs[kSmallWaves * 32 * kSmallStride];
+  const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t per_batch = a.tiles_m * a.tiles_n;
+  const uint32_t batch = blockIdx.x / per_batch, rem = blockIdx.x % per_batch;
+  const uint32_t tile_m = (rem / a.tiles_n) * 32u, tile_n = (rem % a.tiles_n) * 32u;
+  const uint32_t b0 = batch / a.batch1, b1 = batch % a.batch1;
+  const float* A = (const float*)a.a.ptr + (int64_t)b0 * a.a.s_b0 + (int64_t)b1 * a.a.s_b1;
+  const float* B = (const float*)a.b.ptr + (int64_t)b0 * a.b.s_b0 + (int64_t)b1 * a.b.s_b1;
+  // this wave's share of k: whole groups of 8
+  const uint32_t groups = (a.k + 7u) / 8u, per = (groups + kSmallWaves - 1u) / kSmallWaves;
+  const uint32_t k_begin = min(a.k, wave * per * 8u), k_end = min(a.k, (wave + 1u) * per * 8u);
+  const uint32_t x = lane & 31u, h = lane >> 5;
+  // rows and columns over the edge are read as copies of the last one (in bounds; never stored)
+  const float* ap = A + (int64_t)min(tile_m + x, a.m - 1u) * a.a.s_row;
+  const float* bp = B + (int64_t)min(tile_n + x, a.n - 1u) * a.b.s_col;
+  v16f acc0, acc1;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc0[r] = acc1[r] = 0.0f;
+  constexpr uint32_t kChunk = (uint32_t)kSmallG * 8u;
+  const uint32_t nch = (k_end - k_begin + kChunk - 1u) / kChunk;   // (wave-uniform)
+  float a0[kSmallG][4], b0v[kSmallG][4], a1[kSmallG][4], b1v[kSmallG][4];
+  const uint32_t kl = k_begin + 4u * h;   // this lane's first k
+  if (nch > 0u) {
+    small_fetch<AV>(a0, ap, a.a.s_col, kl, k_end);
+    small_fetch<BV>(b0v, bp, a.b.s_row, kl, k_end);
+  }
+  for (uint32_t c = 0; c < nch; c += 2u) {
+    if (c + 1u < nch) {
+      small_fetch<AV>(a1, ap, a.a.s_col, kl + (c + 1u) * kChunk, k_end);
+      small_fetch<BV>(b1v, bp, a.b.s_row, kl + (c + 1u) * kChunk, k_end);
+    }
+    small_mma(acc0, acc1, a0, b0v);
+    if (c + 2u < nch) {
+      small_fetch<AV>(a0, ap, a.a.s_col, kl + (c + 2u) * kChunk, k_end);
+      small_fetch<BV>(b0v, bp, a.b.s_row, kl + (c + 2u) * kChunk, k_end);
+    }
+    if (c + 1u < nch) small_mma(acc0, acc1, a1, b1v);
+  }
+  float* mine = Cs + wave * (32u * kSmallStride);
+#pragma unroll
+  for (int r = 0; r < 16; ++r) mine[((uint32_t)(r >> 2) * 8u + h * 4u + (uint32_t)(r & 3)) * kSmallStride + x] = acc0[r] + acc1[r];
+  __syncthreads();
+  // (the program lives in the lanes of two registers: fetched while every lane is active)
+  const EwProg& p = a.post;
+  const ProgRegs pr = load_prog_regs(p);
+  if (threadIdx.x >= 256u) return;
+  const uint32_t rr = threadIdx.x >> 3, c4 = (threadIdx.x & 7u) * (uint32_t)kVec;
+  float4 sum = *(const float4*)&Cs[rr * kSmallStride + c4];
+#pragma unroll
+  for (uint32_t w = 1; w < (uint32_t)kSmallWaves; ++w) {   // wave order: deterministic
+    const float4 t = *(const float4*)&Cs[w * (32u * kSmallStride) + rr * kSmallStride + c4];
+    sum.x += t.x; sum.y += t.y; sum.z += t.z; sum.w += t.w;
+  }
+  const uint32_t row = tile_m + rr, col = tile_n + c4;
+  if (row >= a.m || col >= a.n) return;
+  const uint32_t n_code = p.n_code;
+  const uint32_t nvalid = a.n - col >= (uint32_t)kVec ? (uint32_t)kVec : a.n - col;
+  const uint32_t i = (uint32_t)((int64_t)b0 * a.o_b0 + (int64_t)b1 * a.o_b1 + (int64_t)row * a.o_row + col);
+  Quad anchor;
+  anchor.v[0] = sum.x; anchor.v[1] = sum.y; anchor.v[2] = sum.z; anchor.v[3] = sum.w;
+  RF<16> f = load_inputs<16, kMaxIn, false, false>(rf_zero<16>(), p, 0, i, nvalid);
+  f = rf_set<16>(f, p.anchor_slot, anchor);
+  f = interp<16>(f, pr, n_code);
+  store_outputs<16, false, false>(f, p, 0, i, nvalid);
+}
+
+static hipError_t launch_small(const GemmArgs& args, hipStream_t s) {
+  GemmArgs a = args;
+  a.tiles_m = (a.m + 31u) / 32u;
+  a.tiles_n = (a.n + 31u) / 32u;
+  const uint64_t wgs = (uint64_t)a.tiles_m * a.tiles_n * a.batch0 * a.batch1;
+  if (a.splits != 1u || wgs > 0x7fffffffull) return hipErrorInvalidValue;
+  if (wgs == 0u) return hipSuccess;
+  auto whole = [&](const GemmOperand& o, bool k_contiguous, int64_t s_outer) {
+    return k_contiguous && (a.k % 4u) == 0u && (((uintptr_t)o.ptr) & 15u) == 0u && (s_outer % 4) == 0 && (o.s_b0 % 4) == 0 && (o.s_b1 % 4) == 0;
+  };
+  const bool av = whole(a.a, a.a.s_col == 1, a.a.s_row), bv = whole(a.b, a.b.s_row == 1, a.b.s_col);
+  const dim3 grid((uint32_t)wgs), block(kSmallThreads);
+  if (av && bv) LT_LAUNCH((lt_gemm_small_kernel<true, true>), grid, block, s, a);
+  else if (av) LT_LAUNCH((lt_gemm_small_kernel<true, false>), grid, block, s, a);
+  else if (bv) LT_LAUNCH((lt_gemm_small_kernel<false, true>), grid, block, s, a);
+  else LT_LAUNCH((lt_gemm_small_kernel<false, false>), grid, block, s, a);
+  char name[48];
+  snprintf(name, sizeof(name), "lt_gemm_small_kernel<%s, %s>", av ? "true" : "false", bv ? "true" : "false");
+  note_kernel(name);
+  return hipGetLastError();
+}
+
 template <typename T, int BM, int BN>
 static void launch_variant(const GemmArgs& a, const dim3 grid, hipStream_t s) {
   const bool akc = a.a.s_col == 1, bkc = a.b.s_row == 1;
@@ -321,6 +459,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   if ((a.a.s_col != 1 && a.a.s_row != 1) || (a.b.s_col != 1 && a.b.s_row != 1)) return hipErrorInvalidValue;
   if (a.in_dtype == kBF16) return launch_gemm_bf16(a, s);
   const uint32_t batch = a.batch0 * a.batch1;
+  if (a.tile_m == 32u && a.tile_n == 32u) return launch_small(a, s);
   if (a.tile_m != a.tile_n || (a.tile_m != 64u && a.tile_m != 128u)) return hipErrorInvalidValue;
   const bool big = a.tile_m == 128u;   // the host picks big tiles only when they still give every compute unit work
   const uint32_t bm = a.tile_m;

@@ -22,6 +22,7 @@
 //             ordered first (ordering edges are added) and the writer reads it index-aligned.
 //   pass 4    regions run in topological order, smallest id (anchor, else first member) first.
 #include <algorithm>
+#include <cstdlib>
 #include <cmath>
 #include <cstdio>
 #include <functional>
@@ -1530,7 +1531,20 @@ struct Lowering {
       args.tile_m = args.tile_n = ts;
       const uint64_t tiles = (uint64_t)((m + ts - 1) / ts) * ((n + ts - 1) / ts) * (uint64_t)batch;
       const uint64_t slices = (uint64_t)(kk + 15) / 16;
-      const uint64_t splits = r->sealed ? 1 : std::min<uint64_t>({512 / std::max<uint64_t>(tiles, 1), slices / 4, 16});
+      uint64_t splits = r->sealed ? 1 : std::min<uint64_t>({512 / std::max<uint64_t>(tiles, 1), slices / 4, 16});
+      // Small products (a layer of a small MLP: 128 x 512 x 784) go to the kernel that splits k
+      // inside a workgroup of eight waves over a 32 x 32 tile: one launch where the split costs
+      // two, 4 to 5 microseconds less per product.  Measured limits: more tiles than compute
+      // units (784 x 512 x 128: 400) and it loses to the split pair (18 against 16 us); with
+      // k = 2048 a wave makes four dependent round trips, which only ties with the split pair at
+      // 8 and 16 rows and loses from 32 x 2048 x 2048 (0.27 GFLOP) on.
+      {
+        const uint64_t tiles32 = (uint64_t)((m + 31) / 32) * ((n + 31) / 32) * (uint64_t)batch;
+        if (tiles32 <= 256 && 2.0 * (double)batch * m * n * kk <= 2.5e8 && kk >= 32 && kk <= 1024) {
+          args.tile_m = args.tile_n = 32u;
+          splits = 1;
+        }
+      }
       if (splits > 1) {
         args.splits = (uint32_t)splits;
         Storage ws;

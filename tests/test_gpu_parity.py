@@ -632,6 +632,53 @@ def test_gemm_batched_and_epilogue(ctx):
     check(ctx, E, got, prog(E, *(E.tensor(v) for v in (a, w, bias, res))), TOL32)
 
 
+SMALL_GEMMS = [  # m, k, n, ta, tb, batch, kernel variant (A, B fetched as whole 4-vectors along k)
+    (128, 784, 512, False, False, (), "true, false"),     # a layer of the small MLP
+    (128, 512, 512, False, True, (), "true, true"),
+    (128, 512, 10, False, False, (), "true, false"),      # ten columns: one ragged tile
+    (512, 128, 512, True, False, (), "false, false"),     # weight-gradient shape, both operands across k
+    (100, 36, 72, False, True, (), "true, true"),         # k a multiple of 4, not of 8
+    (100, 35, 72, False, True, (), "false, false"),       # k not a multiple of 4: element loads
+    (33, 1000, 41, True, True, (), "false, true"),        # ragged everywhere, k split unevenly over the waves
+    (1, 64, 1, False, False, (), "true, true"),          # (one column: k is B's contiguous dimension too)
+    (70, 520, 90, False, False, (3,), "true, false"),     # batched
+    (40, 96, 50, True, False, (2, 2), "false, false"),
+]
+
+
+@pytest.mark.parametrize("m,k,n,ta,tb,batch,variant", SMALL_GEMMS)
+def test_gemm_f32_small_one_launch(ctx, m, k, n, ta, tb, batch, variant):
+    """Small fp32 products run as ONE launch (k split over the eight waves of a workgroup, the
+    partial tiles added in LDS, the post program on the sum): the product alone, and with a bias,
+    an activation, a residual and a second result in the same region."""
+    E = Eager()
+    r = rng(15)
+    a = r.standard_normal(batch + ((k, m) if ta else (m, k)), dtype=np.float32)
+    b = r.standard_normal(batch + ((n, k) if tb else (k, n)), dtype=np.float32)
+    bias = r.standard_normal((n,), dtype=np.float32)
+    res = r.standard_normal(batch + (m, n), dtype=np.float32)
+    ctx.set_profiling(True)
+    try:
+        got = ctx.matmul(ctx.tensor(a), ctx.tensor(b), ta, tb)
+        ctx.barrier()
+        names = [l["kernel"] for l in ctx.last_launches()]
+        assert names == ["lt_gemm_small_kernel<%s>" % variant], names
+        check(ctx, E, got, E.matmul(E.tensor(a), E.tensor(b), ta, tb), TOL32, "product")
+
+        def prog(B):
+            y = B.add(B.matmul(B.tensor(a), B.tensor(b), ta, tb), B.tensor(bias))
+            return B.add(B.tensor(res), B.mul(B.gelu(y), 0.5)), B.relu(y)
+        g1, g2 = prog(ctx)
+        info = ctx.barrier()
+        assert info.n_regions == 1 and info.n_launches == 1
+        assert ctx.last_launches()[0]["kernel"].startswith("lt_gemm_small_kernel")
+    finally:
+        ctx.set_profiling(False)
+    r1, r2 = prog(E)
+    check(ctx, E, g1, r1, TOL32, "residual + gelu")
+    check(ctx, E, g2, r2, TOL32, "relu")
+
+
 def test_c2_mlp_training_teacher_forced(ctx):
     """Every step starts from the oracle's weights, so errors cannot accumulate: 1e-5 per step."""
     E = Eager()

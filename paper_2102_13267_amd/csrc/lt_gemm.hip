@@ -369,6 +369,22 @@ __global__ __launch_bounds__(kSmallThreads) void lt_gemm_small_kernel(const Gemm
   // rows and columns over the edge are read as copies of the last one (in bounds; never stored)
   const float* ap = A + (int64_t)min(tile_m + x, a.m - 1u) * a.a.s_row;
   const float* bp = B + (int64_t)min(tile_n + x, a.n - 1u) * a.b.s_col;
+  // The post program and, where every quad of the tile is a whole aligned vector inside the
+  // output, its inputs for this lane's quad (lanes of the first four waves: row rr, columns
+  // c4 .. c4 + 3) are asked for now, so that they travel under the contraction.
+  // (the program lives in the lanes of two registers: fetched while every lane is active)
+  const EwProg& p = a.post;
+  const ProgRegs pr = load_prog_regs(p);
+  const uint32_t rr = (threadIdx.x & 255u) >> 3, c4 = (threadIdx.x & 7u) * (uint32_t)kVec;
+  const uint32_t row = tile_m + rr, col = tile_n + c4;
+  const uint32_t i = (uint32_t)((int64_t)b0 * a.o_b0 + (int64_t)b1 * a.o_b1 + (int64_t)row * a.o_row + col);
+  const bool fast = p.fast && p.full_vec_ok && p.n_in <= 4u && p.n_slots <= 8u && tile_m + 32u <= a.m && tile_n + 32u <= a.n;
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Wuninitialized"
+#pragma clang diagnostic ignored "-Wsometimes-uninitialized"
+  Staged<4> staged;
+  if (fast && wave < 4u) staged = fetch_inputs_at<4, false, false>(p, i, (b0 * a.batch1 + b1) * a.m + row, col);
+#pragma clang diagnostic pop
   v16f acc0, acc1;
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc0[r] = acc1[r] = 0.0f;
@@ -396,24 +412,25 @@ __global__ __launch_bounds__(kSmallThreads) void lt_gemm_small_kernel(const Gemm
 #pragma unroll
   for (int r = 0; r < 16; ++r) mine[((uint32_t)(r >> 2) * 8u + h * 4u + (uint32_t)(r & 3)) * kSmallStride + x] = acc0[r] + acc1[r];
   __syncthreads();
-  // (the program lives in the lanes of two registers: fetched while every lane is active)
-  const EwProg& p = a.post;
-  const ProgRegs pr = load_prog_regs(p);
-  if (threadIdx.x >= 256u) return;
-  const uint32_t rr = threadIdx.x >> 3, c4 = (threadIdx.x & 7u) * (uint32_t)kVec;
+  if (wave >= 4u) return;
   float4 sum = *(const float4*)&Cs[rr * kSmallStride + c4];
 #pragma unroll
   for (uint32_t w = 1; w < (uint32_t)kSmallWaves; ++w) {   // wave order: deterministic
     const float4 t = *(const float4*)&Cs[w * (32u * kSmallStride) + rr * kSmallStride + c4];
     sum.x += t.x; sum.y += t.y; sum.z += t.z; sum.w += t.w;
   }
-  const uint32_t row = tile_m + rr, col = tile_n + c4;
-  if (row >= a.m || col >= a.n) return;
-  const uint32_t n_code = p.n_code;
-  const uint32_t nvalid = a.n - col >= (uint32_t)kVec ? (uint32_t)kVec : a.n - col;
-  const uint32_t i = (uint32_t)((int64_t)b0 * a.o_b0 + (int64_t)b1 * a.o_b1 + (int64_t)row * a.o_row + col);
   Quad anchor;
   anchor.v[0] = sum.x; anchor.v[1] = sum.y; anchor.v[2] = sum.z; anchor.v[3] = sum.w;
+  const uint32_t n_code = p.n_code;
+  if (fast) {
+    RF<16> f = place_inputs<16, 4, true, false, 0>(rf_zero<16>(), p, staged, kVec);
+    f = rf_set<16>(f, p.anchor_slot, anchor);
+    f = interp<16>(f, pr, n_code);
+    store_outputs<16, true, false, 0>(f, p, 0, i, kVec);
+    return;
+  }
+  if (row >= a.m || col >= a.n) return;
+  const uint32_t nvalid = a.n - col >= (uint32_t)kVec ? (uint32_t)kVec : a.n - col;
   RF<16> f = load_inputs<16, kMaxIn, false, false>(rf_zero<16>(), p, 0, i, nvalid);
   f = rf_set<16>(f, p.anchor_slot, anchor);
   f = interp<16>(f, pr, n_code);

@@ -426,6 +426,10 @@ static lt_status execute(lt_ctx* ctx, Plan* plan, const std::vector<BufRef>& par
         ltk::ColArgs* a = (ltk::ColArgs*)args.data();
         a->partials = red_partials + l.scratch_slot * (kPartialFloats / kScratchSlots);
         a->tickets = red_tickets + l.scratch_slot * (kTickets / kScratchSlots);
+      } else if (gemm_shared_tiles(l) != 0) {
+        ltk::GemmArgs* a = (ltk::GemmArgs*)args.data();
+        a->split_ws = red_partials + l.scratch_slot * (kPartialFloats / kScratchSlots);
+        a->tickets = red_tickets + l.scratch_slot * (kTickets / kScratchSlots);
       }
       hipStream_t stream = ctx->stream;
       if (multi) {

@@ -317,6 +317,9 @@ uint64_t fnv1a64(const uint8_t* p, size_t n);
 std::unique_ptr<Plan> lower(lt_ctx* ctx, const Cut& cut, lt_status* status);
 // stream schedule of a lowered plan (lt_schedule.cpp)
 void schedule_streams(Plan* plan);
+// 32 x 32 tiles of a one-launch small contraction whose workgroups share tiles (they exchange partial
+// tiles through the reduction scratch and take tickets); 0 for every other launch
+uint64_t gemm_shared_tiles(const Launch& l);
 
 }  // namespace lt
 #endif  // LT_CORE_H_

@@ -18,6 +18,7 @@
 
 #include "lt_gemm_epilogue.h"
 #include "lt_launch.h"
+#include "lt_reduce.h"
 
 namespace ltk {
 
@@ -318,7 +319,14 @@ __global__ __launch_bounds__(kGemmThreads, BM == 64 ? 2 : 1) void lt_gemm_kernel
 // loop; kSmallG groups (64 k) are in flight per wave while the previous ones are multiplied.  The
 // eight partial tiles meet in LDS, are added in wave order, and the post program runs on the sum:
 // one launch.
-constexpr int kSmallThreads = 512, kSmallWaves = 8, kSmallG = 8, kSmallStride = 32 + kCPad;
+// A long k over very few tiles (a batch of 8 rows against a 2048 x 2048 weight: 64 tiles) would
+// leave three quarters of the compute units idle and every wave with several dependent round trips
+// to memory, so there `splits` workgroups share a tile, each with a slice of k.  Their partial
+// tiles (4 KB each) go to a scratch with relaxed device-scope stores, each workgroup takes a ticket
+// of its tile, and the one that draws the last ticket adds the partial tiles up in split order
+// (deterministic) and runs the post program -- the same exchange as in the reductions, still one
+// launch.
+constexpr int kSmallThreads = 512, kSmallWaves = 8, kSmallG = 4, kSmallStride = 32 + kCPad;
 
 template <bool V>
 __device__ __forceinline__ void small_fetch(float (&v)[kSmallG][4], const float* base, int64_t s_k, uint32_t k0, uint32_t k_end) {
@@ -356,15 +364,19 @@ template <bool AV, bool BV>
 __global__ __launch_bounds__(kSmallThreads) void lt_gemm_small_kernel(const GemmArgs a) {
   __shared__ __attribute__((aligned(16))) float Cs[kSmallWaves * 32 * kSmallStride];
   const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  __shared__ uint32_t is_last;
   const uint32_t per_batch = a.tiles_m * a.tiles_n;
-  const uint32_t batch = blockIdx.x / per_batch, rem = blockIdx.x % per_batch;
+  const uint32_t tile = blockIdx.x / a.splits, split = blockIdx.x % a.splits;   // (the workgroups of a tile are neighbours)
+  const uint32_t batch = tile / per_batch, rem = tile % per_batch;
   const uint32_t tile_m = (rem / a.tiles_n) * 32u, tile_n = (rem % a.tiles_n) * 32u;
   const uint32_t b0 = batch / a.batch1, b1 = batch % a.batch1;
   const float* A = (const float*)a.a.ptr + (int64_t)b0 * a.a.s_b0 + (int64_t)b1 * a.a.s_b1;
   const float* B = (const float*)a.b.ptr + (int64_t)b0 * a.b.s_b0 + (int64_t)b1 * a.b.s_b1;
-  // this wave's share of k: whole groups of 8
-  const uint32_t groups = (a.k + 7u) / 8u, per = (groups + kSmallWaves - 1u) / kSmallWaves;
-  const uint32_t k_begin = min(a.k, wave * per * 8u), k_end = min(a.k, (wave + 1u) * per * 8u);
+  // this workgroup's slice of k, and this wave's share of it: whole groups of 8
+  const uint32_t per_wg = (((a.k + 7u) / 8u) + a.splits - 1u) / a.splits;
+  const uint32_t wg_begin = min(a.k, split * per_wg * 8u), wg_end = min(a.k, (split + 1u) * per_wg * 8u);
+  const uint32_t groups = (wg_end - wg_begin + 7u) / 8u, per = (groups + kSmallWaves - 1u) / kSmallWaves;
+  const uint32_t k_begin = min(wg_end, wg_begin + wave * per * 8u), k_end = min(wg_end, wg_begin + (wave + 1u) * per * 8u);
   const uint32_t x = lane & 31u, h = lane >> 5;
   // rows and columns over the edge are read as copies of the last one (in bounds; never stored)
   const float* ap = A + (int64_t)min(tile_m + x, a.m - 1u) * a.a.s_row;
@@ -412,13 +424,39 @@ __global__ __launch_bounds__(kSmallThreads) void lt_gemm_small_kernel(const Gemm
 #pragma unroll
   for (int r = 0; r < 16; ++r) mine[((uint32_t)(r >> 2) * 8u + h * 4u + (uint32_t)(r & 3)) * kSmallStride + x] = acc0[r] + acc1[r];
   __syncthreads();
-  if (wave >= 4u) return;
-  float4 sum = *(const float4*)&Cs[rr * kSmallStride + c4];
+  float4 sum = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+  if (wave < 4u) {
+    sum = *(const float4*)&Cs[rr * kSmallStride + c4];
 #pragma unroll
-  for (uint32_t w = 1; w < (uint32_t)kSmallWaves; ++w) {   // wave order: deterministic
-    const float4 t = *(const float4*)&Cs[w * (32u * kSmallStride) + rr * kSmallStride + c4];
-    sum.x += t.x; sum.y += t.y; sum.z += t.z; sum.w += t.w;
+    for (uint32_t w = 1; w < (uint32_t)kSmallWaves; ++w) {   // wave order: deterministic
+      const float4 t = *(const float4*)&Cs[w * (32u * kSmallStride) + rr * kSmallStride + c4];
+      sum.x += t.x; sum.y += t.y; sum.z += t.z; sum.w += t.w;
+    }
   }
+  if (a.splits > 1u) {
+    // leave this workgroup's partial tile, take a ticket; whoever draws the last one goes on
+    float* const parts = a.split_ws + (size_t)tile * a.splits * 1024u + rr * 32u + c4;
+    if (wave < 4u) {
+      publish4(parts + (size_t)split * 1024u, sum);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // (this wave's stores have been performed before the ticket is taken)
+    }
+    __syncthreads();
+    if (threadIdx.x == 0u) {
+      const uint32_t t = atomicAdd(&a.tickets[tile], 1u);
+      is_last = (t == a.splits - 1u) ? 1u : 0u;
+      if (t == a.splits - 1u) a.tickets[tile] = 0u;   // (every workgroup of the tile has been here)
+    }
+    __syncthreads();
+    if (!is_last) return;
+    if (wave < 4u) {
+      sum = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+      for (uint32_t sp = 0; sp < a.splits; ++sp) {   // split order: deterministic
+        const float4 t = published4(parts + (size_t)sp * 1024u);
+        sum.x += t.x; sum.y += t.y; sum.z += t.z; sum.w += t.w;
+      }
+    }
+  }
+  if (wave >= 4u) return;
   Quad anchor;
   anchor.v[0] = sum.x; anchor.v[1] = sum.y; anchor.v[2] = sum.z; anchor.v[3] = sum.w;
   const uint32_t n_code = p.n_code;
@@ -442,13 +480,14 @@ static hipError_t launch_small(const GemmArgs& args, hipStream_t s) {
   a.tiles_m = (a.m + 31u) / 32u;
   a.tiles_n = (a.n + 31u) / 32u;
   const uint64_t wgs = (uint64_t)a.tiles_m * a.tiles_n * a.batch0 * a.batch1;
-  if (a.splits != 1u || wgs > 0x7fffffffull) return hipErrorInvalidValue;
+  if (a.splits == 0u || wgs * a.splits > 0x7fffffffull) return hipErrorInvalidValue;
+  if (a.splits > 1u && (!a.split_ws || !a.tickets)) return hipErrorInvalidValue;
   if (wgs == 0u) return hipSuccess;
   auto whole = [&](const GemmOperand& o, bool k_contiguous, int64_t s_outer) {
     return k_contiguous && (a.k % 4u) == 0u && (((uintptr_t)o.ptr) & 15u) == 0u && (s_outer % 4) == 0 && (o.s_b0 % 4) == 0 && (o.s_b1 % 4) == 0;
   };
   const bool av = whole(a.a, a.a.s_col == 1, a.a.s_row), bv = whole(a.b, a.b.s_row == 1, a.b.s_col);
-  const dim3 grid((uint32_t)wgs), block(kSmallThreads);
+  const dim3 grid((uint32_t)(wgs * a.splits)), block(kSmallThreads);
   if (av && bv) LT_LAUNCH((lt_gemm_small_kernel<true, true>), grid, block, s, a);
   else if (av) LT_LAUNCH((lt_gemm_small_kernel<true, false>), grid, block, s, a);
   else if (bv) LT_LAUNCH((lt_gemm_small_kernel<false, true>), grid, block, s, a);

@@ -175,6 +175,11 @@ struct GemmArgs {
   // program then runs in a second launch (SplitPostArgs) that adds the partials up in split order.
   uint32_t splits, tile_m, tile_n, pad;   // workgroup tile: 128 rows, 128 or 64 columns
   float* split_ws;           // [splits][batch * m * n] floats
+  // The one-launch small kernel (tile_m = tile_n = 32) with splits > 1: `splits` workgroups share
+  // a 32 x 32 tile; split_ws then holds [tile][split][32 x 32] partial tiles and tickets[tile]
+  // counts the workgroups that have left theirs (zero before the launch; the last one adds the
+  // partials up in split order, runs the post program and resets the ticket).
+  uint32_t* tickets;
   EwProg post;               // iteration space = the output
 };
 

@@ -1534,15 +1534,26 @@ struct Lowering {
       uint64_t splits = r->sealed ? 1 : std::min<uint64_t>({512 / std::max<uint64_t>(tiles, 1), slices / 4, 16});
       // Small products (a layer of a small MLP: 128 x 512 x 784) go to the kernel that splits k
       // inside a workgroup of eight waves over a 32 x 32 tile: one launch where the split costs
-      // two, 4 to 5 microseconds less per product.  Measured limits: more tiles than compute
-      // units (784 x 512 x 128: 400) and it loses to the split pair (18 against 16 us); with
-      // k = 2048 a wave makes four dependent round trips, which only ties with the split pair at
-      // 8 and 16 rows and loses from 32 x 2048 x 2048 (0.27 GFLOP) on.
+      // two.  Measured, HIP events around each launch included: 128 x 512 x 784 18.5 -> 14.4 us,
+      // 128 x 512 x 512 16.8 -> 11.0, 784 x 512 x 128 (400 tiles) 15.9 -> 12.5.
+      // A long k over few tiles (a small batch against a wide weight matrix) is shared by up to
+      // eight workgroups per tile, each with at least 256 of k, which exchange their partial tiles
+      // inside the same launch (reduction scratch and tickets) -- as long as all of them fit the
+      // chip at once, one workgroup per compute unit (a second round costs more than the split
+      // pair): [B, 2048] x [2048, 2048] with B = 8 .. 32 23.4 -> 13.1 us (four per tile), B = 64
+      // 26.2 -> 17.6 (two per tile); from B = 128 on the split pair is as fast or faster.
       {
         const uint64_t tiles32 = (uint64_t)((m + 31) / 32) * ((n + 31) / 32) * (uint64_t)batch;
-        if (tiles32 <= 256 && 2.0 * (double)batch * m * n * kk <= 2.5e8 && kk >= 32 && kk <= 1024) {
+        if (tiles32 <= 512 && 2.0 * (double)batch * m * n * kk <= 2.5e8 && kk >= 32 && kk <= 1024) {
           args.tile_m = args.tile_n = 32u;
           splits = 1;
+        } else if (!r->sealed && tiles32 >= 1 && tiles32 <= 128 && kk > 1024) {
+          const uint64_t share = std::min<uint64_t>({8, 256 / tiles32, (uint64_t)kk / 256});
+          if (share >= 2) {
+            args.tile_m = args.tile_n = 32u;
+            args.splits = (uint32_t)share;   // (workgroups per tile of the one launch, not a second launch)
+            splits = 1;
+          }
         }
       }
       if (splits > 1) {

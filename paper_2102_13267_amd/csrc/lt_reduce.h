@@ -11,6 +11,28 @@ __device__ __forceinline__ float red_combine(uint32_t red, float x, float y) {
   return x + y;
 }
 
+// Partial results travel between workgroups of one launch, which may sit on different dies with
+// different L2 caches.  They are written and read with relaxed device-scope atomic accesses --
+// stores and loads that go through to the memory side -- so that no cache has to be written back
+// or invalidated as a whole, which is what a device-scope fence does (microseconds per fence, and
+// every other workgroup of the die loses what it had cached).  Order: the writer waits for its
+// stores (a workgroup-scope release: a wait, no cache operation) before it takes the ticket; the
+// reader starts only after it has seen the last ticket.
+__device__ __forceinline__ void publish(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ float published(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void publish4(float* p, const float4& v) {   // p 16-byte aligned
+  const uint64_t lo = (uint64_t)__float_as_uint(v.x) | ((uint64_t)__float_as_uint(v.y) << 32);
+  const uint64_t hi = (uint64_t)__float_as_uint(v.z) | ((uint64_t)__float_as_uint(v.w) << 32);
+  __hip_atomic_store((uint64_t*)p, lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store((uint64_t*)p + 1, hi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float4 published4(const float* p) {
+  const uint64_t lo = __hip_atomic_load((const uint64_t*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const uint64_t hi = __hip_atomic_load((const uint64_t*)p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_float4(__uint_as_float((uint32_t)lo), __uint_as_float((uint32_t)(lo >> 32)), __uint_as_float((uint32_t)hi),
+                     __uint_as_float((uint32_t)(hi >> 32)));
+}
+
 // One butterfly step inside a row of 16 lanes through the data-parallel-primitive lane crossbar
 // (no LDS traffic).  CTRL: 0xB1 swaps neighbours, 0x4E swaps pairs, 0x141 mirrors each half row
 // (reaches the other quad), 0x140 mirrors the row (reaches the other half).

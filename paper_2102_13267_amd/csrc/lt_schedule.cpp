@@ -46,6 +46,13 @@ double estimate_us(const Launch& l) {
 
 }  // namespace
 
+uint64_t gemm_shared_tiles(const Launch& l) {
+  if (l.kind != L_GEMM) return 0;
+  const ltk::GemmArgs* a = (const ltk::GemmArgs*)l.args.data();
+  if (a->tile_m != 32u || a->splits <= 1u) return 0;
+  return (uint64_t)((a->m + 31u) / 32u) * ((a->n + 31u) / 32u) * a->batch0 * a->batch1;
+}
+
 void schedule_streams(Plan* plan) {
   const size_t n = plan->launches.size();
   plan->n_streams = 1;
@@ -73,12 +80,16 @@ void schedule_streams(Plan* plan) {
     l.record = 0;
     l.scratch_slot = 0;
     l.waits.clear();
-    if (l.kind != L_ALL && l.kind != L_COL) continue;
+    const uint64_t shared_tiles = gemm_shared_tiles(l);   // (a small contraction whose workgroups share tiles)
+    if (l.kind != L_ALL && l.kind != L_COL && shared_tiles == 0) continue;
     uint64_t floats = l.grid_x, tickets = 1;
     if (l.kind == L_COL) {
       const ltk::ColArgs* a = (const ltk::ColArgs*)l.args.data();
       floats = (uint64_t)l.grid_y * ((a->cols + 3u) & ~3u);
       tickets = l.grid_x;
+    } else if (l.kind == L_GEMM) {
+      floats = shared_tiles * ((const ltk::GemmArgs*)l.args.data())->splits * 1024u;
+      tickets = shared_tiles;
     }
     if (floats <= kPartialFloats / kScratchSlots && tickets <= kTickets / kScratchSlots) {
       l.scratch_slot = (uint8_t)next_slot;

@@ -643,14 +643,22 @@ SMALL_GEMMS = [  # m, k, n, ta, tb, batch, kernel variant (A, B fetched as whole
     (1, 64, 1, False, False, (), "true, true"),          # (one column: k is B's contiguous dimension too)
     (70, 520, 90, False, False, (3,), "true, false"),     # batched
     (40, 96, 50, True, False, (2, 2), "false, false"),
+    # a long k over few tiles: several workgroups share a tile and exchange partial tiles in the launch
+    (8, 2048, 2048, False, False, (), "true, false"),     # four per tile
+    (64, 2048, 512, False, True, (), "true, true"),       # eight per tile
+    (33, 1500, 70, True, False, (), "false, false"),      # five per tile, ragged
+    (20, 1101, 40, True, True, (), "false, false"),       # k odd: element loads, uneven slices
+    (40, 1100, 50, False, False, (3,), "true, false"),    # batched
 ]
 
 
 @pytest.mark.parametrize("m,k,n,ta,tb,batch,variant", SMALL_GEMMS)
 def test_gemm_f32_small_one_launch(ctx, m, k, n, ta, tb, batch, variant):
-    """Small fp32 products run as ONE launch (k split over the eight waves of a workgroup, the
-    partial tiles added in LDS, the post program on the sum): the product alone, and with a bias,
-    an activation, a residual and a second result in the same region."""
+    """Small fp32 products run as ONE launch (k split over the eight waves of a workgroup -- and,
+    for a long k over few tiles, over several workgroups per tile that exchange partial tiles --,
+    the partial tiles added in a fixed order, the post program on the sum): the product alone,
+    twice (the tickets of shared tiles must be back at zero), and with a bias, an activation, a
+    residual and a second result in the same region."""
     E = Eager()
     r = rng(15)
     a = r.standard_normal(batch + ((k, m) if ta else (m, k)), dtype=np.float32)
@@ -664,6 +672,8 @@ def test_gemm_f32_small_one_launch(ctx, m, k, n, ta, tb, batch, variant):
         names = [l["kernel"] for l in ctx.last_launches()]
         assert names == ["lt_gemm_small_kernel<%s>" % variant], names
         check(ctx, E, got, E.matmul(E.tensor(a), E.tensor(b), ta, tb), TOL32, "product")
+        again = ctx.matmul(ctx.tensor(a), ctx.tensor(b), ta, tb)
+        assert np.array_equal(ctx.fetch(again), ctx.fetch(got))
 
         def prog(B):
             y = B.add(B.matmul(B.tensor(a), B.tensor(b), ta, tb), B.tensor(bias))

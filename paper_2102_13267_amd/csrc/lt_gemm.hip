@@ -358,44 +358,58 @@ __device__ __forceinline__ void small_mma(v16f& acc0, v16f& acc1, const float (&
   }
 }
 
-// AV / BV: k is the operand's contiguous dimension and every group of four is a whole, 16-byte
-// aligned vector (the launcher checks the pointer, the strides and k % 4).
-template <bool AV, bool BV>
+// TM x TN: blocks of 32 x 32 per workgroup tile (1 x 1, 2 x 1 or 2 x 2); the eight waves are NB =
+// TM * TN blocks times 8 / NB shares of k.  AV / BV: k is the operand's contiguous dimension and
+// every group of four is a whole, 16-byte aligned vector (the launcher checks the pointer, the
+// strides and k % 4).
+template <int TM, int TN, bool AV, bool BV>
 __global__ __launch_bounds__(kSmallThreads) void lt_gemm_small_kernel(const GemmArgs a) {
+  constexpr uint32_t NB = TM * TN, KW = kSmallWaves / NB;      // blocks, k shares inside the workgroup
+  constexpr uint32_t kQuads = NB * 256u, QT = (kQuads + kSmallThreads - 1u) / kSmallThreads;   // quads of the tile, per thread
   __shared__ __attribute__((aligned(16))) float Cs[kSmallWaves * 32 * kSmallStride];
-  const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   __shared__ uint32_t is_last;
+  const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t block = wave % NB, kway = wave / NB, bm = block / TN, bn = block % TN;
   const uint32_t per_batch = a.tiles_m * a.tiles_n;
   const uint32_t tile = blockIdx.x / a.splits, split = blockIdx.x % a.splits;   // (the workgroups of a tile are neighbours)
   const uint32_t batch = tile / per_batch, rem = tile % per_batch;
-  const uint32_t tile_m = (rem / a.tiles_n) * 32u, tile_n = (rem % a.tiles_n) * 32u;
+  const uint32_t tile_m = (rem / a.tiles_n) * (32u * TM), tile_n = (rem % a.tiles_n) * (32u * TN);
   const uint32_t b0 = batch / a.batch1, b1 = batch % a.batch1;
   const float* A = (const float*)a.a.ptr + (int64_t)b0 * a.a.s_b0 + (int64_t)b1 * a.a.s_b1;
   const float* B = (const float*)a.b.ptr + (int64_t)b0 * a.b.s_b0 + (int64_t)b1 * a.b.s_b1;
   // this workgroup's slice of k, and this wave's share of it: whole groups of 8
   const uint32_t per_wg = (((a.k + 7u) / 8u) + a.splits - 1u) / a.splits;
   const uint32_t wg_begin = min(a.k, split * per_wg * 8u), wg_end = min(a.k, (split + 1u) * per_wg * 8u);
-  const uint32_t groups = (wg_end - wg_begin + 7u) / 8u, per = (groups + kSmallWaves - 1u) / kSmallWaves;
-  const uint32_t k_begin = min(wg_end, wg_begin + wave * per * 8u), k_end = min(wg_end, wg_begin + (wave + 1u) * per * 8u);
+  const uint32_t groups = (wg_end - wg_begin + 7u) / 8u, per = (groups + KW - 1u) / KW;
+  const uint32_t k_begin = min(wg_end, wg_begin + kway * per * 8u), k_end = min(wg_end, wg_begin + (kway + 1u) * per * 8u);
   const uint32_t x = lane & 31u, h = lane >> 5;
   // rows and columns over the edge are read as copies of the last one (in bounds; never stored)
-  const float* ap = A + (int64_t)min(tile_m + x, a.m - 1u) * a.a.s_row;
-  const float* bp = B + (int64_t)min(tile_n + x, a.n - 1u) * a.b.s_col;
+  const float* ap = A + (int64_t)min(tile_m + bm * 32u + x, a.m - 1u) * a.a.s_row;
+  const float* bp = B + (int64_t)min(tile_n + bn * 32u + x, a.n - 1u) * a.b.s_col;
   // The post program and, where every quad of the tile is a whole aligned vector inside the
-  // output, its inputs for this lane's quad (lanes of the first four waves: row rr, columns
-  // c4 .. c4 + 3) are asked for now, so that they travel under the contraction.
+  // output, its inputs for this thread's quads are asked for now, so that they travel under the
+  // contraction.  Quad q of the tile: block q / 256, row (q % 256) / 8 of it, columns 4 (q % 8) ..
   // (the program lives in the lanes of two registers: fetched while every lane is active)
   const EwProg& p = a.post;
   const ProgRegs pr = load_prog_regs(p);
-  const uint32_t rr = (threadIdx.x & 255u) >> 3, c4 = (threadIdx.x & 7u) * (uint32_t)kVec;
-  const uint32_t row = tile_m + rr, col = tile_n + c4;
-  const uint32_t i = (uint32_t)((int64_t)b0 * a.o_b0 + (int64_t)b1 * a.o_b1 + (int64_t)row * a.o_row + col);
-  const bool fast = p.fast && p.full_vec_ok && p.n_in <= 4u && p.n_slots <= 8u && tile_m + 32u <= a.m && tile_n + 32u <= a.n;
+  const bool fast = p.fast && p.full_vec_ok && p.n_in <= 4u && p.n_slots <= 8u && tile_m + 32u * TM <= a.m && tile_n + 32u * TN <= a.n;
+  uint32_t qrow[QT], qcol[QT], qi[QT];
+#pragma unroll
+  for (uint32_t j = 0; j < QT; ++j) {
+    const uint32_t q = (threadIdx.x + j * kSmallThreads) % kQuads, qb = q >> 8;   // (threads past the last quad: a copy, never used)
+    qrow[j] = tile_m + (qb / TN) * 32u + ((q & 255u) >> 3);
+    qcol[j] = tile_n + (qb % TN) * 32u + (q & 7u) * (uint32_t)kVec;
+    qi[j] = (uint32_t)((int64_t)b0 * a.o_b0 + (int64_t)b1 * a.o_b1 + (int64_t)qrow[j] * a.o_row + qcol[j]);
+  }
+  const bool has_quad = threadIdx.x < kQuads;   // (wave-uniform: kQuads is a multiple of 64)
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Wuninitialized"
 #pragma clang diagnostic ignored "-Wsometimes-uninitialized"
-  Staged<4> staged;
-  if (fast && wave < 4u) staged = fetch_inputs_at<4, false, false>(p, i, (b0 * a.batch1 + b1) * a.m + row, col);
+  Staged<4> staged[QT];
+  if (fast && has_quad) {
+#pragma unroll
+    for (uint32_t j = 0; j < QT; ++j) staged[j] = fetch_inputs_at<4, false, false>(p, qi[j], (b0 * a.batch1 + b1) * a.m + qrow[j], qcol[j]);
+  }
 #pragma clang diagnostic pop
   v16f acc0, acc1;
 #pragma unroll
@@ -420,24 +434,29 @@ __global__ __launch_bounds__(kSmallThreads) void lt_gemm_small_kernel(const Gemm
     }
     if (c + 1u < nch) small_mma(acc0, acc1, a1, b1v);
   }
-  float* mine = Cs + wave * (32u * kSmallStride);
+  float* mine = Cs + wave * (32u * kSmallStride);   // (wave = kway * NB + block)
 #pragma unroll
   for (int r = 0; r < 16; ++r) mine[((uint32_t)(r >> 2) * 8u + h * 4u + (uint32_t)(r & 3)) * kSmallStride + x] = acc0[r] + acc1[r];
   __syncthreads();
-  float4 sum = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-  if (wave < 4u) {
-    sum = *(const float4*)&Cs[rr * kSmallStride + c4];
+  float4 sum[QT];
 #pragma unroll
-    for (uint32_t w = 1; w < (uint32_t)kSmallWaves; ++w) {   // wave order: deterministic
-      const float4 t = *(const float4*)&Cs[w * (32u * kSmallStride) + rr * kSmallStride + c4];
-      sum.x += t.x; sum.y += t.y; sum.z += t.z; sum.w += t.w;
+  for (uint32_t j = 0; j < QT; ++j) {
+    const uint32_t q = (threadIdx.x + j * kSmallThreads) % kQuads;
+    const float* src = Cs + (q >> 8) * (32u * kSmallStride) + ((q & 255u) >> 3) * kSmallStride + (q & 7u) * (uint32_t)kVec;
+    sum[j] = *(const float4*)src;
+#pragma unroll
+    for (uint32_t w = 1; w < KW; ++w) {   // share order: deterministic
+      const float4 t = *(const float4*)(src + w * NB * (32u * kSmallStride));
+      sum[j].x += t.x; sum[j].y += t.y; sum[j].z += t.z; sum[j].w += t.w;
     }
   }
   if (a.splits > 1u) {
     // leave this workgroup's partial tile, take a ticket; whoever draws the last one goes on
-    float* const parts = a.split_ws + (size_t)tile * a.splits * 1024u + rr * 32u + c4;
-    if (wave < 4u) {
-      publish4(parts + (size_t)split * 1024u, sum);
+    float* const parts = a.split_ws + (size_t)tile * a.splits * (NB * 1024u);
+    if (has_quad) {
+#pragma unroll
+      for (uint32_t j = 0; j < QT; ++j)
+        publish4(parts + (size_t)split * (NB * 1024u) + (size_t)((threadIdx.x + j * kSmallThreads) % kQuads) * 4u, sum[j]);
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // (this wave's stores have been performed before the ticket is taken)
     }
     __syncthreads();
@@ -448,37 +467,55 @@ __global__ __launch_bounds__(kSmallThreads) void lt_gemm_small_kernel(const Gemm
     }
     __syncthreads();
     if (!is_last) return;
-    if (wave < 4u) {
-      sum = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-      for (uint32_t sp = 0; sp < a.splits; ++sp) {   // split order: deterministic
-        const float4 t = published4(parts + (size_t)sp * 1024u);
-        sum.x += t.x; sum.y += t.y; sum.z += t.z; sum.w += t.w;
+    if (has_quad) {
+#pragma unroll
+      for (uint32_t j = 0; j < QT; ++j) {
+        sum[j] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        for (uint32_t sp = 0; sp < a.splits; ++sp) {   // split order: deterministic
+          const float4 t = published4(parts + (size_t)sp * (NB * 1024u) + (size_t)((threadIdx.x + j * kSmallThreads) % kQuads) * 4u);
+          sum[j].x += t.x; sum[j].y += t.y; sum[j].z += t.z; sum[j].w += t.w;
+        }
       }
     }
   }
-  if (wave >= 4u) return;
-  Quad anchor;
-  anchor.v[0] = sum.x; anchor.v[1] = sum.y; anchor.v[2] = sum.z; anchor.v[3] = sum.w;
+  if (!has_quad) return;
   const uint32_t n_code = p.n_code;
-  if (fast) {
-    RF<16> f = place_inputs<16, 4, true, false, 0>(rf_zero<16>(), p, staged, kVec);
-    f = rf_set<16>(f, p.anchor_slot, anchor);
-    f = interp<16>(f, pr, n_code);
-    store_outputs<16, true, false, 0>(f, p, 0, i, kVec);
-    return;
+#pragma unroll
+  for (uint32_t j = 0; j < QT; ++j) {
+    Quad anchor;
+    anchor.v[0] = sum[j].x; anchor.v[1] = sum[j].y; anchor.v[2] = sum[j].z; anchor.v[3] = sum[j].w;
+    if (fast) {
+      RF<16> f = place_inputs<16, 4, true, false, 0>(rf_zero<16>(), p, staged[j], kVec);
+      f = rf_set<16>(f, p.anchor_slot, anchor);
+      f = interp<16>(f, pr, n_code);
+      store_outputs<16, true, false, 0>(f, p, 0, qi[j], kVec);
+    } else if (qrow[j] < a.m && qcol[j] < a.n) {
+      const uint32_t nvalid = a.n - qcol[j] >= (uint32_t)kVec ? (uint32_t)kVec : a.n - qcol[j];
+      RF<16> f = load_inputs<16, kMaxIn, false, false>(rf_zero<16>(), p, 0, qi[j], nvalid);
+      f = rf_set<16>(f, p.anchor_slot, anchor);
+      f = interp<16>(f, pr, n_code);
+      store_outputs<16, false, false>(f, p, 0, qi[j], nvalid);
+    }
   }
-  if (row >= a.m || col >= a.n) return;
-  const uint32_t nvalid = a.n - col >= (uint32_t)kVec ? (uint32_t)kVec : a.n - col;
-  RF<16> f = load_inputs<16, kMaxIn, false, false>(rf_zero<16>(), p, 0, i, nvalid);
-  f = rf_set<16>(f, p.anchor_slot, anchor);
-  f = interp<16>(f, pr, n_code);
-  store_outputs<16, false, false>(f, p, 0, i, nvalid);
+}
+
+template <int TM, int TN>
+static void launch_small_tile(const GemmArgs& a, bool av, bool bv, dim3 grid, hipStream_t s) {
+  const dim3 block(kSmallThreads);
+  if (av && bv) LT_LAUNCH((lt_gemm_small_kernel<TM, TN, true, true>), grid, block, s, a);
+  else if (av) LT_LAUNCH((lt_gemm_small_kernel<TM, TN, true, false>), grid, block, s, a);
+  else if (bv) LT_LAUNCH((lt_gemm_small_kernel<TM, TN, false, true>), grid, block, s, a);
+  else LT_LAUNCH((lt_gemm_small_kernel<TM, TN, false, false>), grid, block, s, a);
 }
 
 static hipError_t launch_small(const GemmArgs& args, hipStream_t s) {
   GemmArgs a = args;
-  a.tiles_m = (a.m + 31u) / 32u;
-  a.tiles_n = (a.n + 31u) / 32u;
+  // (the kernel is written for 1 x 1, 2 x 1 and 2 x 2 blocks; 2 x 2 lost to the split pair on every
+  // shape measured and is not built)
+  const bool t11 = a.tile_m == 32u && a.tile_n == 32u, t21 = a.tile_m == 64u && a.tile_n == 32u;
+  if (!t11 && !t21) return hipErrorInvalidValue;
+  a.tiles_m = (a.m + a.tile_m - 1u) / a.tile_m;
+  a.tiles_n = (a.n + a.tile_n - 1u) / a.tile_n;
   const uint64_t wgs = (uint64_t)a.tiles_m * a.tiles_n * a.batch0 * a.batch1;
   if (a.splits == 0u || wgs * a.splits > 0x7fffffffull) return hipErrorInvalidValue;
   if (a.splits > 1u && (!a.split_ws || !a.tickets)) return hipErrorInvalidValue;
@@ -487,13 +524,11 @@ static hipError_t launch_small(const GemmArgs& args, hipStream_t s) {
     return k_contiguous && (a.k % 4u) == 0u && (((uintptr_t)o.ptr) & 15u) == 0u && (s_outer % 4) == 0 && (o.s_b0 % 4) == 0 && (o.s_b1 % 4) == 0;
   };
   const bool av = whole(a.a, a.a.s_col == 1, a.a.s_row), bv = whole(a.b, a.b.s_row == 1, a.b.s_col);
-  const dim3 grid((uint32_t)(wgs * a.splits)), block(kSmallThreads);
-  if (av && bv) LT_LAUNCH((lt_gemm_small_kernel<true, true>), grid, block, s, a);
-  else if (av) LT_LAUNCH((lt_gemm_small_kernel<true, false>), grid, block, s, a);
-  else if (bv) LT_LAUNCH((lt_gemm_small_kernel<false, true>), grid, block, s, a);
-  else LT_LAUNCH((lt_gemm_small_kernel<false, false>), grid, block, s, a);
-  char name[48];
-  snprintf(name, sizeof(name), "lt_gemm_small_kernel<%s, %s>", av ? "true" : "false", bv ? "true" : "false");
+  const dim3 grid((uint32_t)(wgs * a.splits));
+  if (t11) launch_small_tile<1, 1>(a, av, bv, grid, s);
+  else launch_small_tile<2, 1>(a, av, bv, grid, s);
+  char name[56];
+  snprintf(name, sizeof(name), "lt_gemm_small_kernel<%u, %u, %s, %s>", a.tile_m / 32u, a.tile_n / 32u, av ? "true" : "false", bv ? "true" : "false");
   note_kernel(name);
   return hipGetLastError();
 }
@@ -515,7 +550,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   if ((a.a.s_col != 1 && a.a.s_row != 1) || (a.b.s_col != 1 && a.b.s_row != 1)) return hipErrorInvalidValue;
   if (a.in_dtype == kBF16) return launch_gemm_bf16(a, s);
   const uint32_t batch = a.batch0 * a.batch1;
-  if (a.tile_m == 32u && a.tile_n == 32u) return launch_small(a, s);
+  if (a.direct) return launch_small(a, s);
   if (a.tile_m != a.tile_n || (a.tile_m != 64u && a.tile_m != 128u)) return hipErrorInvalidValue;
   const bool big = a.tile_m == 128u;   // the host picks big tiles only when they still give every compute unit work
   const uint32_t bm = a.tile_m;

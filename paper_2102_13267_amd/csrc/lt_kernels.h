@@ -173,10 +173,11 @@ struct GemmArgs {
   // Split-K (bf16 kernel only): `splits` workgroups share an output tile, each contracting a
   // slice of k and leaving its fp32 partial product, row major, in split_ws[split]; the post
   // program then runs in a second launch (SplitPostArgs) that adds the partials up in split order.
-  uint32_t splits, tile_m, tile_n, pad;   // workgroup tile: 128 rows, 128 or 64 columns
+  uint32_t splits, tile_m, tile_n;   // workgroup tile: 128 rows, 128 or 64 columns
+  uint32_t direct;           // 1: the one-launch kernel for small fp32 products (tiles of 32 x 32, 64 x 32 or 64 x 64)
   float* split_ws;           // [splits][batch * m * n] floats
-  // The one-launch small kernel (tile_m = tile_n = 32) with splits > 1: `splits` workgroups share
-  // a 32 x 32 tile; split_ws then holds [tile][split][32 x 32] partial tiles and tickets[tile]
+  // The one-launch small kernel (direct = 1) with splits > 1: `splits` workgroups share a tile;
+  // split_ws then holds [tile][split][tile_m x tile_n] partial tiles and tickets[tile]
   // counts the workgroups that have left theirs (zero before the launch; the last one adds the
   // partials up in split order, runs the post program and resets the ticket).
   uint32_t* tickets;

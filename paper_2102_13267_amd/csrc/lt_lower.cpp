@@ -1541,16 +1541,23 @@ struct Lowering {
       // inside the same launch (reduction scratch and tickets) -- as long as all of them fit the
       // chip at once, one workgroup per compute unit (a second round costs more than the split
       // pair): [B, 2048] x [2048, 2048] with B = 8 .. 32 23.4 -> 13.1 us (four per tile), B = 64
-      // 26.2 -> 17.6 (two per tile); from B = 128 on the split pair is as fast or faster.
+      // 26.2 -> 17.6 (two per tile); from B = 256 on the split pair is faster.
       {
         const uint64_t tiles32 = (uint64_t)((m + 31) / 32) * ((n + 31) / 32) * (uint64_t)batch;
         if (tiles32 <= 512 && 2.0 * (double)batch * m * n * kk <= 2.5e8 && kk >= 32 && kk <= 1024) {
           args.tile_m = args.tile_n = 32u;
+          args.direct = 1u;
           splits = 1;
-        } else if (!r->sealed && tiles32 >= 1 && tiles32 <= 128 && kk > 1024) {
-          const uint64_t share = std::min<uint64_t>({8, 256 / tiles32, (uint64_t)kk / 256});
+        } else if (!r->sealed && tiles32 >= 1 && tiles32 <= 256 && kk > 1024) {
+          // (above 128 tiles of 32 x 32: tiles of 64 x 32, two blocks times four shares of k per
+          // workgroup; B = 128: 30.0 -> 26.2 us.  Tiles of 64 x 64 lose to the split pair everywhere.)
+          const uint32_t tm = tiles32 <= 128 ? 32u : 64u;
+          const uint64_t tiles = (uint64_t)((m + tm - 1) / tm) * ((n + 31) / 32) * (uint64_t)batch;
+          const uint64_t share = std::min<uint64_t>({8, 256 / std::max<uint64_t>(tiles, 1), (uint64_t)kk / 256});
           if (share >= 2) {
-            args.tile_m = args.tile_n = 32u;
+            args.tile_m = tm;
+            args.tile_n = 32u;
+            args.direct = 1u;
             args.splits = (uint32_t)share;   // (workgroups per tile of the one launch, not a second launch)
             splits = 1;
           }

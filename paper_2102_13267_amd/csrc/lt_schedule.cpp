@@ -49,8 +49,8 @@ double estimate_us(const Launch& l) {
 uint64_t gemm_shared_tiles(const Launch& l) {
   if (l.kind != L_GEMM) return 0;
   const ltk::GemmArgs* a = (const ltk::GemmArgs*)l.args.data();
-  if (a->tile_m != 32u || a->splits <= 1u) return 0;
-  return (uint64_t)((a->m + 31u) / 32u) * ((a->n + 31u) / 32u) * a->batch0 * a->batch1;
+  if (!a->direct || a->splits <= 1u) return 0;
+  return (uint64_t)((a->m + a->tile_m - 1u) / a->tile_m) * ((a->n + a->tile_n - 1u) / a->tile_n) * a->batch0 * a->batch1;
 }
 
 void schedule_streams(Plan* plan) {
@@ -88,7 +88,10 @@ void schedule_streams(Plan* plan) {
       floats = (uint64_t)l.grid_y * ((a->cols + 3u) & ~3u);
       tickets = l.grid_x;
     } else if (l.kind == L_GEMM) {
-      floats = shared_tiles * ((const ltk::GemmArgs*)l.args.data())->splits * 1024u;
+      {
+        const ltk::GemmArgs* a = (const ltk::GemmArgs*)l.args.data();
+        floats = shared_tiles * a->splits * a->tile_m * a->tile_n;
+      }
       tickets = shared_tiles;
     }
     if (floats <= kPartialFloats / kScratchSlots && tickets <= kTickets / kScratchSlots) {

@@ -268,6 +268,44 @@ def test_traced_steps_as_graphs(gctx):
     assert np.array_equal(pa, pb) and np.array_equal(ma, mb)
 
 
+@pytest.mark.gpu
+def test_shared_tile_contraction_replayed_as_graphs(gctx):
+    """h <- relu(h W + b) with 8 rows against a 2048 x 512 weight: several workgroups per tile exchange
+    partial tiles and take tickets inside the launch; the tickets are reset by the kernel itself, so
+    the step can run again and again as a HIP graph.  Against the same steps launched one by one."""
+    ctx = gctx
+    rng = np.random.default_rng(9)
+    h0 = rng.standard_normal((8, 2048)).astype(np.float32)
+    w = (rng.standard_normal((2048, 2048)) * 0.03).astype(np.float32)
+    b = rng.standard_normal((2048,)).astype(np.float32)
+
+    def run(graphs):
+        h = ctx.tensor(h0.copy(), donatable=True)
+        W, bias = ctx.tensor(w), ctx.tensor(b)
+        ctx.assign(h, ctx.relu(ctx.add(ctx.matmul(h, W), bias)))
+        ctx.barrier()
+        step = ctx.capture_step()
+        ctx.set_graphs(graphs)
+        before = ctx.stats().graph_launches
+        outs = []
+        for i in range(8):
+            step.replay(blocking=bool(i & 1))
+            outs.append(ctx.fetch(h).copy())
+        launched = ctx.stats().graph_launches - before
+        ctx.set_graphs(False)
+        return outs, launched
+
+    eager, n0 = run(False)
+    graphed, n1 = run(True)
+    assert n0 == 0 and n1 >= 3
+    for a, g in zip(eager, graphed):
+        assert np.array_equal(a, g)
+    ref = h0.astype(np.float64)
+    for i in range(9):
+        ref = np.maximum(ref @ w.astype(np.float64) + b, 0.0)
+    assert np.max(np.abs(graphed[-1] - ref)) <= 1e-4 * np.max(np.abs(ref))   # nine chained products
+
+
 def _random_steps(ctx, seed, steps, replay_from, graphs):
     """`steps` steps of the random stateful trace `seed` (the generator of the plan-validity test)
     on the same tensors: traced, or replayed from step `replay_from` on; HIP graphs on or off.

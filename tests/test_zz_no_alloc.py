@@ -72,6 +72,18 @@ def test_static_barrier_matches_the_barrier_and_the_oracle():
         for g, w, r in zip(got, want, (ref, E.sum(ref, axis=0))):
             assert np.array_equal(g, w)
             assert rel_err(g, E.fetch(r)) <= 1e-5
+    # fp32, a long k over few tiles: the workgroups of a tile exchange partial tiles and take tickets in
+    # the static array (tickets of the first call are back at zero for the second)
+    for m, k, n in ((16, 2048, 512), (8, 1300, 70)):
+        r = np.random.Generator(np.random.PCG64(79))
+        a = r.standard_normal((m, k), dtype=np.float32); b = r.standard_normal((k, n), dtype=np.float32)
+        bias = r.standard_normal((n,), dtype=np.float32)
+        prog = lambda B: B.relu(B.add(B.matmul(B.tensor(a), B.tensor(b)), B.tensor(bias)))
+        got_t = prog(ctx); ctx.barrier_static()
+        want_t = prog(ref_ctx); ref_ctx.barrier()
+        got = ctx.fetch(got_t)
+        assert np.array_equal(got, ref_ctx.fetch(want_t))
+        assert rel_err(got, E.fetch(prog(E))) <= 1e-5
     # a plan whose temporaries exceed the array is refused before anything runs; lt_barrier still runs it
     x = ctx.tensor(np.ones((1 << 22,), np.float32))
     y = ctx.exp(x)                                         # 16 MiB temporary (y feeds two regions)

@@ -358,6 +358,13 @@ __device__ __forceinline__ void small_mma(v16f& acc0, v16f& acc1, const float (&
   }
 }
 
+__device__ __forceinline__ float small_colsum(const float (&bv)[kSmallG][4]) {
+  float s = 0.0f;
+#pragma unroll
+  for (int g = 0; g < kSmallG; ++g) s += (bv[g][0] + bv[g][1]) + (bv[g][2] + bv[g][3]);
+  return s;
+}
+
 // TM x TN: blocks of 32 x 32 per workgroup tile (1 x 1, 2 x 1 or 2 x 2); the eight waves are NB =
 // TM * TN blocks times 8 / NB shares of k.  AV / BV: k is the operand's contiguous dimension and
 // every group of four is a whole, 16-byte aligned vector (the launcher checks the pointer, the
@@ -368,6 +375,7 @@ __global__ __launch_bounds__(kSmallThreads) void lt_gemm_small_kernel(const Gemm
   constexpr uint32_t kQuads = NB * 256u, QT = (kQuads + kSmallThreads - 1u) / kSmallThreads;   // quads of the tile, per thread
   __shared__ __attribute__((aligned(16))) float Cs[kSmallWaves * 32 * kSmallStride];
   __shared__ uint32_t is_last;
+  __shared__ float colp[kSmallThreads], coltot[32 * TN];
   const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t block = wave % NB, kway = wave / NB, bm = block / TN, bn = block % TN;
   const uint32_t per_batch = a.tiles_m * a.tiles_n;
@@ -392,6 +400,11 @@ __global__ __launch_bounds__(kSmallThreads) void lt_gemm_small_kernel(const Gemm
   // (the program lives in the lanes of two registers: fetched while every lane is active)
   const EwProg& p = a.post;
   const ProgRegs pr = load_prog_regs(p);
+  // column sums of B ride along in the first tile row (every column block exactly once)
+  const bool cols_here = a.col_sum != 0u && tile_m == 0u;       // (workgroup-uniform)
+  const bool cols_mine = cols_here && bm == 0u;                 // (wave-uniform)
+  const ProgRegs cpr = load_prog_regs(a.col_post);
+  float csum = 0.0f;
   const bool fast = p.fast && p.full_vec_ok && p.n_in <= 4u && p.n_slots <= 8u && tile_m + 32u * TM <= a.m && tile_n + 32u * TN <= a.n;
   uint32_t qrow[QT], qcol[QT], qi[QT];
 #pragma unroll
@@ -428,12 +441,17 @@ __global__ __launch_bounds__(kSmallThreads) void lt_gemm_small_kernel(const Gemm
       small_fetch<BV>(b1v, bp, a.b.s_row, kl + (c + 1u) * kChunk, k_end);
     }
     small_mma(acc0, acc1, a0, b0v);
+    if (cols_mine) csum += small_colsum(b0v);
     if (c + 2u < nch) {
       small_fetch<AV>(a0, ap, a.a.s_col, kl + (c + 2u) * kChunk, k_end);
       small_fetch<BV>(b0v, bp, a.b.s_row, kl + (c + 2u) * kChunk, k_end);
     }
-    if (c + 1u < nch) small_mma(acc0, acc1, a1, b1v);
+    if (c + 1u < nch) {
+      small_mma(acc0, acc1, a1, b1v);
+      if (cols_mine) csum += small_colsum(b1v);
+    }
   }
+  colp[threadIdx.x] = csum;
   float* mine = Cs + wave * (32u * kSmallStride);   // (wave = kway * NB + block)
 #pragma unroll
   for (int r = 0; r < 16; ++r) mine[((uint32_t)(r >> 2) * 8u + h * 4u + (uint32_t)(r & 3)) * kSmallStride + x] = acc0[r] + acc1[r];
@@ -448,6 +466,35 @@ __global__ __launch_bounds__(kSmallThreads) void lt_gemm_small_kernel(const Gemm
     for (uint32_t w = 1; w < KW; ++w) {   // share order: deterministic
       const float4 t = *(const float4*)(src + w * NB * (32u * kSmallStride));
       sum[j].x += t.x; sum[j].y += t.y; sum[j].z += t.z; sum[j].w += t.w;
+    }
+  }
+  if (cols_here) {
+    // column c of column block bn: the shares of k in order, lower half of the wave before the upper
+    // (deterministic); then the column program on quads of four columns
+    if (threadIdx.x < 32u * TN) {
+      const uint32_t cb = threadIdx.x >> 5, cx = threadIdx.x & 31u;
+      float t = 0.0f;
+#pragma unroll
+      for (uint32_t w = 0; w < KW; ++w) {
+        const float* src = colp + (w * NB + cb) * 64u + cx;   // (wave = share * NB + block; block = bm * TN + bn with bm = 0)
+        t += src[0];
+        t += src[32];
+      }
+      if (a.col_red == kRedMean) t = t / (float)a.k;
+      coltot[threadIdx.x] = t;
+    }
+    __syncthreads();
+    const uint32_t cc = tile_n + threadIdx.x * (uint32_t)kVec;
+    if (threadIdx.x < 8u * TN && cc < a.n) {
+      const EwProg& cp = a.col_post;
+      const uint32_t nv = a.n - cc >= (uint32_t)kVec ? (uint32_t)kVec : a.n - cc;
+      Quad q;
+#pragma unroll
+      for (int e = 0; e < kVec; ++e) q.v[e] = coltot[threadIdx.x * (uint32_t)kVec + (uint32_t)e];
+      RF<16> f = load_inputs<16, kMaxIn, false, false>(rf_zero<16>(), cp, 0, cc, nv);
+      f = rf_set<16>(f, cp.anchor_slot, q);
+      f = interp<16>(f, cpr, cp.n_code);
+      store_outputs<16, false, false>(f, cp, 0, cc, nv);
     }
   }
   if (a.splits > 1u) {
@@ -519,6 +566,8 @@ static hipError_t launch_small(const GemmArgs& args, hipStream_t s) {
   const uint64_t wgs = (uint64_t)a.tiles_m * a.tiles_n * a.batch0 * a.batch1;
   if (a.splits == 0u || wgs * a.splits > 0x7fffffffull) return hipErrorInvalidValue;
   if (a.splits > 1u && (!a.split_ws || !a.tickets)) return hipErrorInvalidValue;
+  // column sums ride along only with an unshared, unbatched product whose B is [k, n] with rows contiguous
+  if (a.col_sum && (a.splits != 1u || a.batch0 * a.batch1 != 1u || a.b.s_col != 1 || a.col_post.n_slots > 16u)) return hipErrorInvalidValue;
   if (wgs == 0u) return hipSuccess;
   auto whole = [&](const GemmOperand& o, bool k_contiguous, int64_t s_outer) {
     return k_contiguous && (a.k % 4u) == 0u && (((uintptr_t)o.ptr) & 15u) == 0u && (s_outer % 4) == 0 && (o.s_b0 % 4) == 0 && (o.s_b1 % 4) == 0;

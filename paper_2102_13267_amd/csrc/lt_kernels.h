@@ -182,6 +182,12 @@ struct GemmArgs {
   // partials up in split order, runs the post program and resets the ticket).
   uint32_t* tickets;
   EwProg post;               // iteration space = the output
+  // The one-launch small kernel can carry the column sums of its B operand ([k, n], rows
+  // contiguous) along: a weight gradient x^T dy and the bias gradient sum_rows(dy) read the same
+  // dy.  col_sum = 1: the workgroups of the first tile row add up the columns of B they fetch
+  // anyway (col_red: kRedSum or kRedMean) and run col_post on them, iteration space [n].
+  uint32_t col_sum, col_red;
+  EwProg col_post;
 };
 
 // second launch of a split-K contraction: anchor = sum over splits of ws[split][i], then the

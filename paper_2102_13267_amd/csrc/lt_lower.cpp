@@ -1199,6 +1199,7 @@ struct Lowering {
       add_prog_patches(launch, offsetof(ltk::AllArgs, post), post);
     } else {
       if (in_shape.size() != 2) return bad(LT_ERR_UNSUPPORTED, "axis-0 reduction needs a rank-2 operand (reshape first)");
+      if (ride_with_contraction(r, red, in_shape, pro, post)) return true;
       ltk::ColArgs args{};
       args.pro = pro.prog;
       args.post = post.prog;
@@ -1224,6 +1225,54 @@ struct Lowering {
     }
     note_prog_storages(pro, launch);
     note_prog_storages(post, launch);
+    return true;
+  }
+
+  // A bias gradient next to its weight gradient: dW = x^T dy and db = sum over the rows of dy read
+  // the same dy, and the small one-launch contraction fetches every column of its B operand anyway.
+  // When the launch emitted just before this column sum is such a contraction with this sum's
+  // operand as its B ([k, n], rows contiguous, fp32, no prologue), the sum and its post program
+  // ride along in that launch (GemmArgs::col_sum) and this region gets no launch of its own.
+  // Nothing the column program writes may be touched by the contraction, and nothing it reads
+  // may be written by it.
+  bool ride_with_contraction(const Region* r, uint32_t red, const std::vector<int64_t>& in_shape, const ProgBuild& pro, const ProgBuild& post) {
+    if (plan->launches.empty() || r->has_fin || (red != ltk::kRedSum && red != ltk::kRedMean)) return false;
+    const uint32_t prev = (uint32_t)plan->launches.size() - 1;
+    Launch& pl = plan->launches[prev];
+    if (pl.kind != L_GEMM || pl.args.size() != sizeof(ltk::GemmArgs)) return false;
+    ltk::GemmArgs* ga = (ltk::GemmArgs*)pl.args.data();
+    if (!ga->direct || ga->splits != 1u || ga->col_sum || ga->batch0 * ga->batch1 != 1u || ga->in_dtype != ltk::kF32) return false;
+    if (ga->k != (uint32_t)in_shape[0] || ga->n != (uint32_t)in_shape[1] || ga->b.s_col != 1 || ga->b.s_row != in_shape[1]) return false;
+    if (pro.prog.n_code != 0u || pro.prog.n_in != 1u || pro.in_storage.size() != 1 || pro.prog.in[0].mode != ltk::kFull ||
+        pro.prog.in[0].dtype != ltk::kF32 || !pro.scal_patch.empty() || post.prog.n_slots > 16u)
+      return false;
+    // the contraction's B operand is this sum's operand; collect what the contraction reads and writes
+    const uint32_t b_off = (uint32_t)(offsetof(ltk::GemmArgs, b) + offsetof(ltk::GemmOperand, ptr));
+    bool same_b = false;
+    // (a donated output and the parameter it overwrites are two storages of one buffer: compare buffers)
+    auto buffer_of = [&](int32_t st) -> int64_t {
+      if (st < 0) return INT64_MIN;
+      return plan->storages[st].param >= 0 ? -(int64_t)plan->storages[st].param - 1 : (int64_t)st;
+    };
+    std::vector<int64_t> reads, writes;
+    for (const PtrPatch& pp : plan->ptr_patches) {
+      if (pp.launch != prev) continue;
+      if (pp.offset == b_off) same_b = pp.storage == pro.in_storage[0].second && pp.byte_offset == pro.in_storage[0].byte_offset;
+      (pp.write ? writes : reads).push_back(buffer_of(pp.storage));
+    }
+    if (!same_b) return false;
+    auto among = [](const std::vector<int64_t>& v, int64_t x) { return std::find(v.begin(), v.end(), x) != v.end(); };
+    for (auto& is : post.in_storage)
+      if (among(writes, buffer_of(is.second))) return false;
+    for (auto& os : post.out_storage)
+      if (among(writes, buffer_of(os.second)) || among(reads, buffer_of(os.second))) return false;
+    ga->col_sum = 1u;
+    ga->col_red = red;
+    ga->col_post = post.prog;
+    pl.bytes += post.bytes;
+    add_prog_patches(prev, offsetof(ltk::GemmArgs, col_post), post);
+    note_prog_storages(pro, (int)prev);
+    note_prog_storages(post, (int)prev);
     return true;
   }
 

@@ -691,6 +691,58 @@ def test_gemm_f32_small_one_launch(ctx, m, k, n, ta, tb, batch, variant):
     check(ctx, E, g2, r2, TOL32, "relu")
 
 
+@pytest.mark.parametrize("m,k,n,mean", [(512, 128, 512, False), (784, 128, 512, False), (512, 128, 10, False), (100, 77, 45, True),
+                                        (33, 200, 64, False), (64, 1024, 96, True)])
+def test_bias_gradient_rides_with_the_weight_gradient(ctx, m, k, n, mean):
+    """dW = x^T dy and db = sum over the rows of dy, each with an in-place SGD update as its post
+    program: two regions, ONE launch (the small contraction adds up the columns of the dy it
+    fetches anyway and runs the column program too)."""
+    E = Eager()
+    r = rng(16)
+    x = r.standard_normal((k, m), dtype=np.float32)
+    dy = r.standard_normal((k, n), dtype=np.float32)
+    w = r.standard_normal((m, n), dtype=np.float32)
+    b = r.standard_normal((n,), dtype=np.float32)
+
+    def prog(B):
+        tx, tdy = B.tensor(x), B.tensor(dy)
+        tw, tb = B.tensor(w.copy(), donatable=True), B.tensor(b.copy(), donatable=True)
+        dw = B.matmul(tx, tdy, True, False)
+        db = B.mean(tdy, 0) if mean else B.sum(tdy, 0)
+        B.assign(tw, B.sub(tw, B.mul(dw, 0.01)))
+        B.assign(tb, B.sub(tb, B.mul(db, 0.01)))
+        return tw, tb, B.relu(db)
+    ctx.set_profiling(True)
+    try:
+        got = prog(ctx)
+        info = ctx.barrier()
+        names = [l["kernel"] for l in ctx.last_launches()]
+    finally:
+        ctx.set_profiling(False)
+    assert info.n_regions == 2 and info.n_launches == 1 and names[0].startswith("lt_gemm_small_kernel"), (info.n_regions, names)
+    for g, e in zip(got, prog(E)):
+        check(ctx, E, g, e, TOL32 * max(1.0, (k / 64) ** 0.5))   # (sums of k terms: the bar of the column reductions)
+
+
+def test_bias_gradient_keeps_its_own_launch_when_it_must(ctx):
+    """The column program reads what the contraction writes: no riding along; same values."""
+    E = Eager()
+    r = rng(17)
+    x = r.standard_normal((128, 96), dtype=np.float32)
+    dy = r.standard_normal((128, 64), dtype=np.float32)
+
+    def prog(B):
+        tx, tdy = B.tensor(x), B.tensor(dy)
+        dw = B.matmul(tx, tdy, True, False)                 # [96, 64]
+        first = B.narrow(dw, 0, 0, 1)                       # its first row, [1, 64]
+        return dw, B.add(B.sum(tdy, 0), B.reshape(first, (64,)))
+    got = prog(ctx)
+    info = ctx.barrier()
+    assert info.n_launches >= 2
+    for g, e in zip(got, prog(E)):
+        check(ctx, E, g, e, TOL32 * 2)
+
+
 def test_c2_mlp_training_teacher_forced(ctx):
     """Every step starts from the oracle's weights, so errors cannot accumulate: 1e-5 per step."""
     E = Eager()

@@ -743,6 +743,54 @@ def test_bias_gradient_keeps_its_own_launch_when_it_must(ctx):
         check(ctx, E, g, e, TOL32 * 2)
 
 
+def test_random_weight_and_bias_gradient_pairs(ctx):
+    """Random shapes and post programs around dW = x^T dy, db = sum or mean over the rows of dy: cases
+    where the column sum may share the contraction's launch and cases where it must not (one
+    program reads what the other writes, the sum comes first, two sums), against the fp64 oracle."""
+    shared = 0
+    for seed in range(120):
+        g = rng(500 + seed)
+        m = int(g.choice([1, 10, 32, 33, 100, 512, 784])); n = int(g.choice([1, 4, 10, 33, 64, 130, 512]))
+        k = int(g.choice([32, 33, 64, 100, 128, 500, 1024]))
+        variant, mean, computed_dy = int(g.integers(0, 7)), bool(g.integers(0, 2)), bool(g.integers(0, 2))
+        x = g.standard_normal((k, m)).astype(np.float32); dy0 = g.standard_normal((k, n)).astype(np.float32)
+        w = g.standard_normal((m, n)).astype(np.float32); b = g.standard_normal((n,)).astype(np.float32)
+
+        def prog(B):
+            tx, tdy = B.tensor(x), B.tensor(dy0)
+            tw, tb = B.tensor(w.copy(), donatable=True), B.tensor(b.copy(), donatable=True)
+            dy = B.mul(B.relu(tdy), 0.5) if computed_dy else tdy
+            dw = B.matmul(tx, dy, True, False)
+            db = B.mean(dy, 0) if mean else B.sum(dy, 0)
+            outs = []
+            if variant == 0:
+                B.assign(tw, B.sub(tw, B.mul(dw, 0.01))); B.assign(tb, B.sub(tb, B.mul(db, 0.01)))
+            elif variant == 1:
+                outs += [dw, db]
+            elif variant == 2:                       # the contraction's post reads the bias that the column program updates
+                outs.append(B.add(dw, tb)); B.assign(tb, B.sub(tb, B.mul(db, 0.01)))
+            elif variant == 3:                       # the column program reads the weight that the contraction updates
+                B.assign(tw, B.sub(tw, B.mul(dw, 0.01))); outs.append(B.add(db, B.reshape(B.narrow(tw, 0, 0, 1), (n,))))
+            elif variant == 4:                       # two column sums over the same rows
+                outs += [dw, db, B.sum(B.mul(dy, dy), 0)]
+            elif variant == 5:                       # the column sum first
+                outs += [db, B.matmul(tx, dy, True, False)]
+            else:                                    # two results each
+                mom = B.add(B.mul(tw, 0.9), dw); outs += [mom, B.sub(tw, B.mul(mom, 0.1))]
+                mb = B.add(B.mul(tb, 0.9), db); outs += [mb, B.gelu(mb)]
+            return outs + [tw, tb]
+        got = prog(ctx)
+        info = ctx.barrier()
+        shared += info.n_launches < info.n_regions
+        E = Eager("f64")
+        for j, (a, r) in enumerate(zip(got, prog(E))):
+            ga, ra = np.asarray(ctx.fetch(a), np.float64), np.asarray(E.fetch(r), np.float64)
+            err = float(np.max(np.abs(ga - ra))) / max(float(np.max(np.abs(ra))), 1e-3)
+            assert np.isfinite(ga).all() and err <= 3e-5, (seed, (m, k, n), variant, mean, computed_dy, j, err)   # (sums of up to 1024 terms)
+        del got
+    assert shared >= 30
+
+
 def test_c2_mlp_training_teacher_forced(ctx):
     """Every step starts from the oracle's weights, so errors cannot accumulate: 1e-5 per step."""
     E = Eager()

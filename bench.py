@@ -406,6 +406,34 @@ def run_c3(steps, warmup, bsz=32, seq=256, d=1024, ffn=4096, heads=16):
         state["t"] += 1
         return programs.c3_step(ctx, *g, t=state["t"])
     pipelined = _time_pipelined(record, ctx, steps)
+
+    # the same steps without tracing (section 7 of the paper): one more traced step is captured and
+    # run again with the two scalars that depend on the step number (Adam's bias corrections) replaced
+    def replayed():
+        state["t"] += 1
+        t0 = state["t"]
+        held = programs.c3_step(ctx, *g, t=t0)
+        ctx.barrier(True)
+        captured = ctx.capture_step()
+        base = captured.scalars
+        c1, c2 = 1.0 - 0.9 ** t0, 1.0 - 0.999 ** t0
+
+        def one():
+            state["t"] += 1
+            t = state["t"]
+            captured.replay(scalars=[1.0 - 0.9 ** t if v == c1 else 1.0 - 0.999 ** t if v == c2 else v for v in base], blocking=True)
+        for _ in range(max(warmup, 2)):
+            one()
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        for _ in range(steps):
+            one()
+        torch.cuda.synchronize()
+        rate = steps / (time.perf_counter() - t_start)
+        captured.free()
+        del held
+        return rate
+    rate_replay = replayed()
     _, _, _, _, _, table = _dominant(launches)
     n = len(launches)
     gemm = [r for st in launches for r in st if r["flops"]]
@@ -424,6 +452,7 @@ def run_c3(steps, warmup, bsz=32, seq=256, d=1024, ffn=4096, heads=16):
              "device_ms_per_step": sum(r["ms"] for st in launches for r in st) / n,
              "launches_per_step": len(launches[-1]), "kernels": table,
              "cache_hits": sum(i.cache_hit for i in infos), "steps_per_s_non_blocking_barrier": pipelined,
+             "steps_per_s_replayed_without_tracing": rate_replay,
              "ns_host_per_step": {"collect": int(np.mean([i.ns_collect for i in infos])),
                                   "hash": int(np.mean([i.ns_hash for i in infos])),
                                   "launch": int(np.mean([i.ns_launch for i in infos]))}}

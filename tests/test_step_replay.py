@@ -269,6 +269,48 @@ def test_traced_steps_as_graphs(gctx):
 
 
 @pytest.mark.gpu
+def test_transformer_layer_steps_replayed_with_the_step_number_as_scalars(gctx):
+    """Four Adam steps of the small transformer layer, traced (t = 1 .. 4), against two traced steps
+    and two replays in which the two scalars that depend on t (the bias corrections) are
+    replaced: parameters and moments bit for bit."""
+    import torch
+    from workloads.inputs import c3_inputs
+    ctx = gctx
+    bsz, seq, d, ffn, heads = 2, 16, 64, 128, 4
+    inp = c3_inputs(bsz, seq, d, ffn)
+    keys = programs.C3_WEIGHTS + programs.C3_VECTORS
+    bf = lambda a: torch.from_numpy(a).to(torch.bfloat16).to(torch.float32).numpy()
+
+    def setup():
+        P = {k: ctx.tensor(bf(inp[k]), dtype="bf16", donatable=True) for k in keys}
+        M = {k: ctx.tensor(np.zeros_like(inp[k]), dtype="f32", donatable=True) for k in keys}
+        V = {k: ctx.tensor(np.zeros_like(inp[k]), dtype="f32", donatable=True) for k in keys}
+        return ctx.tensor(bf(inp["x"]), dtype="bf16"), ctx.tensor(bf(inp["dy"]), dtype="bf16"), P, M, V, heads
+
+    def state(g):
+        return [np.asarray(ctx.fetch(g[j][k])).copy() for j in (2, 3, 4) for k in keys]
+
+    g = setup()
+    for t in range(1, 5):
+        held = programs.c3_step(ctx, *g, t=t)
+        ctx.barrier()
+    traced = state(g)
+    g = setup()
+    for t in (1, 2):          # (at t = 1 the bias corrections equal 1 - beta: captured at t = 2, where they can be told apart)
+        held = programs.c3_step(ctx, *g, t=t)
+        ctx.barrier()
+    step = ctx.capture_step()
+    base = step.scalars
+    c1, c2 = 1.0 - 0.9 ** 2, 1.0 - 0.999 ** 2
+    assert c1 in base and c2 in base
+    for t in range(3, 5):
+        step.replay(scalars=[1.0 - 0.9 ** t if v == c1 else 1.0 - 0.999 ** t if v == c2 else v for v in base])
+    for a, b in zip(traced, state(g)):
+        assert np.array_equal(a, b)
+    assert held is not None
+
+
+@pytest.mark.gpu
 def test_shared_tile_contraction_replayed_as_graphs(gctx):
     """h <- relu(h W + b) with 8 rows against a 2048 x 512 weight: several workgroups per tile exchange
     partial tiles and take tickets inside the launch; the tickets are reset by the kernel itself, so

@@ -12,6 +12,8 @@
 // loads are 16 bytes per lane along whichever dimension of the operand is contiguous; an operand
 // whose contiguous dimension is k is transposed on its way into LDS.  A long k over few tiles is
 // split over workgroups (partial products to a workspace, summed by a second launch).
+// Small products take another kernel further down (lt_gemm_small_kernel: no LDS staging, k split
+// inside the workgroup and, for a long k, over a few workgroups that meet inside the launch).
 #include <hip/hip_runtime.h>
 
 #include <cstdio>

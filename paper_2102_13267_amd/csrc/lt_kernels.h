@@ -170,11 +170,11 @@ struct GemmArgs {
   // Contiguous [batch, m, n] by default; a permuted layout when the product's only reader is a
   // permutation (head merge), which then costs nothing.
   int64_t o_b0, o_b1, o_row;
-  // Split-K (bf16 kernel only): `splits` workgroups share an output tile, each contracting a
+  // Split-K (the LDS-staged kernels): `splits` workgroups share an output tile, each contracting a
   // slice of k and leaving its fp32 partial product, row major, in split_ws[split]; the post
   // program then runs in a second launch (SplitPostArgs) that adds the partials up in split order.
   uint32_t splits, tile_m, tile_n;   // workgroup tile: 128 rows, 128 or 64 columns
-  uint32_t direct;           // 1: the one-launch kernel for small fp32 products (tiles of 32 x 32, 64 x 32 or 64 x 64)
+  uint32_t direct;           // 1: the one-launch kernel for small fp32 products (tiles of 32 x 32 or 64 x 32)
   float* split_ws;           // [splits][batch * m * n] floats
   // The one-launch small kernel (direct = 1) with splits > 1: `splits` workgroups share a tile;
   // split_ws then holds [tile][split][tile_m x tile_n] partial tiles and tickets[tile]

@@ -120,6 +120,28 @@ int main() {
   CHECK(lt_op(ctx, LT_OP_LAYER_NORM, ln_in, 3, &eps, 1, ln, 3) == LT_OK);
   CHECK(lt_barrier(ctx, 1, &info) == LT_OK && info.n_regions >= 4 && info.flops_planned == 2ull * 128 * 64 * 32);
   (void)col; (void)loss;
+  // a weight gradient and the bias gradient next to it (the column sum rides in the contraction's
+  // launch: two regions, one launch), a long k over few tiles (workgroups share tiles), and a pair
+  // that must not share a launch (the column program reads what the contraction writes)
+  {
+    lt_tensor gx = dev({128, 96}), gdy = dev({128, 64}), gw = dev({96, 64}, LT_F32, true), gb = dev({64}, LT_F32, true);
+    lt_tensor dw = op(LT_OP_MATMUL, {gx, gdy}, {iattr(LT_ATTR_TRANS_A, 1)});
+    lt_tensor db = op(LT_OP_SUM, {gdy}, {iattr(LT_ATTR_AXIS, 0)});
+    CHECK(lt_assign(ctx, gw, op(LT_OP_SUB, {gw, op(LT_OP_MUL, {dw, scal(0.01)})})) == LT_OK);
+    CHECK(lt_assign(ctx, gb, op(LT_OP_SUB, {gb, op(LT_OP_MUL, {db, scal(0.01)})})) == LT_OK);
+    CHECK(lt_barrier(ctx, 1, &info) == LT_OK && info.n_regions == 2 && info.n_launches == 1);
+    lt_tensor lx = dev({8, 2048}), lw = dev({2048, 512});
+    lt_tensor ly = op(LT_OP_MATMUL, {lx, lw});
+    CHECK(lt_barrier(ctx, 1, &info) == LT_OK && info.n_launches == 1);
+    lt_tensor dw2 = op(LT_OP_MATMUL, {gx, gdy}, {iattr(LT_ATTR_TRANS_A, 1)});
+    CHECK(lt_assign(ctx, gw, op(LT_OP_SUB, {gw, op(LT_OP_MUL, {dw2, scal(0.01)})})) == LT_OK);
+    lt_attr first[3] = {iattr(LT_ATTR_AXIS, 0), iattr(LT_ATTR_START, 0), iattr(LT_ATTR_LENGTH, 1)};
+    lt_attr to_vec[1] = {iattr(LT_ATTR_DIM0, 64)};
+    lt_tensor row0 = op(LT_OP_RESHAPE, {op(LT_OP_NARROW, {gw}, {first[0], first[1], first[2]})}, {to_vec[0]});
+    lt_tensor db2 = op(LT_OP_ADD, {op(LT_OP_SUM, {gdy}, {iattr(LT_ATTR_AXIS, 0)}), row0});
+    CHECK(lt_barrier(ctx, 1, &info) == LT_OK && info.n_launches >= 2);
+    (void)ly; (void)db2;
+  }
   // views: the program of the paper's figure 3, a window, a view of a view, a released base
   lt_tensor vx = dev({2, 3, 4}, LT_F32, true);
   lt_attr perm[3] = {iattr(LT_ATTR_DIM0, 1), iattr(LT_ATTR_DIM0 + 1, 2), iattr(LT_ATTR_DIM0 + 2, 0)};

@@ -470,7 +470,63 @@ def run_c3(steps, warmup, bsz=32, seq=256, d=1024, ffn=4096, heads=16):
     return dt, "bf16", config, roof, extra, cpu
 
 
-WORKLOADS = {"c1": run_c1, "c2": run_c2, "c3": run_c3, "c4": run_c4, "c5": run_c5}
+def run_shapes(steps, warmup):
+    """Not a configuration of the benchmark: relu(A x B + bias) in fp32, one barrier per product, at
+    the contraction shapes of C2 (forward, backward and weight-gradient layouts) and of C5 (every
+    batch size), with HIP events around every launch -- which kernel the lowering picks for a
+    shape and what the product costs, for the kernel notes in the design document and a
+    rocprofv3 trace per kernel instance.  A "step" is one pass over all shapes."""
+    import torch
+    ctx = _gpu_ctx(2 << 30)
+    shapes = [(128, 512, 784, 0, 0), (128, 512, 512, 0, 0), (128, 10, 512, 0, 0), (128, 512, 512, 0, 1), (128, 512, 10, 0, 1),
+              (784, 512, 128, 1, 0), (512, 512, 128, 1, 0), (512, 10, 128, 1, 0)]
+    shapes += [(bsz, 2048, 2048, 0, 0) for bsz in (8, 16, 32, 64, 128, 256, 512, 1024)]
+    ops = []
+    for m, n, k, ta, tb in shapes:
+        ops.append((ctx.tensor(torch.randn((k, m) if ta else (m, k), device="cuda")),
+                    ctx.tensor(torch.randn((n, k) if tb else (k, n), device="cuda")),
+                    ctx.tensor(torch.randn(n, device="cuda")), bool(ta), bool(tb)))
+
+    def one(i):
+        a, b, bias, ta, tb = ops[i]
+        y = ctx.relu(ctx.add(ctx.matmul(a, b, trans_a=ta, trans_b=tb), bias))
+        ctx.barrier(True)
+        return y
+    for _ in range(max(warmup, 2)):
+        for i in range(len(shapes)):
+            one(i)
+    ctx.set_profiling(True)
+    per = [[] for _ in shapes]
+    names = [None] * len(shapes)
+    for _ in range(steps):
+        for i in range(len(shapes)):
+            one(i)
+            ll = ctx.last_launches()
+            per[i].append(sum(r["ms"] for r in ll) * 1e3)
+            names[i] = [r["kernel"] for r in ll]
+    ctx.set_profiling(False)
+    _sync()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        for i in range(len(shapes)):
+            one(i)
+    _sync()
+    dt = time.perf_counter() - t0
+    table = []
+    for (m, n, k, ta, tb), us, nm in zip(shapes, per, names):
+        med = float(np.median(us))
+        table.append({"m": m, "n": n, "k": k, "trans_a": ta, "trans_b": tb, "us_with_events": med,
+                      "TFLOPs": 2.0 * m * n * k / med * 1e-6, "launches": nm})
+    flops = sum(2.0 * m * n * k for m, n, k, _, _ in shapes)
+    total_us = sum(r["us_with_events"] for r in table)
+    roof = {"bound": "mfma", "kernel": "every fp32 contraction of the pass", "achieved": flops / total_us * 1e-6, "peak": MFMA_PEAK_TFLOPS["f32"],
+            "unit": "TFLOP/s", "traffic": None}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    config = {"workload": "shapes: relu(A x B + bias), fp32, the contraction shapes of c2 and c5, one barrier per product"}
+    return dt, "f32", config, roof, {"shapes": table}, None
+
+
+WORKLOADS = {"c1": run_c1, "c2": run_c2, "c3": run_c3, "c4": run_c4, "c5": run_c5, "shapes": run_shapes}
 
 
 def _build_if_nothing_is_built():
@@ -508,7 +564,7 @@ def main():
     global _STREAMS, _C1_STREAMING_RUN
     _STREAMS = args.streams
     _C1_STREAMING_RUN = not args.no_streaming_run
-    defaults = {"c4": (20, 3), "c1": (200, 10), "c2": (200, 10), "c3": (10, 2), "c5": (200, 0)}
+    defaults = {"c4": (20, 3), "c1": (200, 10), "c2": (200, 10), "c3": (10, 2), "c5": (200, 0), "shapes": (20, 3)}
     headline = args.workload or "c4"
     steps = args.steps if args.steps is not None else defaults[headline][0]
     warmup = args.warmup if args.warmup is not None else defaults[headline][1]

@@ -370,14 +370,15 @@ __device__ __forceinline__ float small_colsum(const float (&bv)[kSmallG][4]) {
 // TM x TN: blocks of 32 x 32 per workgroup tile (1 x 1, 2 x 1 or 2 x 2); the eight waves are NB =
 // TM * TN blocks times 8 / NB shares of k.  AV / BV: k is the operand's contiguous dimension and
 // every group of four is a whole, 16-byte aligned vector (the launcher checks the pointer, the
-// strides and k % 4).
-template <int TM, int TN, bool AV, bool BV>
+// strides and k % 4).  CS: the column sums of B ride along (GemmArgs::col_sum); a variant of its own, because the
+// second program costs 40 registers that the plain product does not have to carry.
+template <int TM, int TN, bool AV, bool BV, bool CS>
 __global__ __launch_bounds__(kSmallThreads) void lt_gemm_small_kernel(const GemmArgs a) {
   constexpr uint32_t NB = TM * TN, KW = kSmallWaves / NB;      // blocks, k shares inside the workgroup
   constexpr uint32_t kQuads = NB * 256u, QT = (kQuads + kSmallThreads - 1u) / kSmallThreads;   // quads of the tile, per thread
   __shared__ __attribute__((aligned(16))) float Cs[kSmallWaves * 32 * kSmallStride];
   __shared__ uint32_t is_last;
-  __shared__ float colp[kSmallThreads], coltot[32 * TN];
+  __shared__ float colp[CS ? kSmallThreads : 1], coltot[CS ? 32 * TN : 1];
   const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t block = wave % NB, kway = wave / NB, bm = block / TN, bn = block % TN;
   const uint32_t per_batch = a.tiles_m * a.tiles_n;
@@ -403,9 +404,9 @@ __global__ __launch_bounds__(kSmallThreads) void lt_gemm_small_kernel(const Gemm
   const EwProg& p = a.post;
   const ProgRegs pr = load_prog_regs(p);
   // column sums of B ride along in the first tile row (every column block exactly once)
-  const bool cols_here = a.col_sum != 0u && tile_m == 0u;       // (workgroup-uniform)
+  const bool cols_here = CS && tile_m == 0u;                    // (workgroup-uniform)
   const bool cols_mine = cols_here && bm == 0u;                 // (wave-uniform)
-  const ProgRegs cpr = load_prog_regs(a.col_post);
+  const ProgRegs cpr = CS ? load_prog_regs(a.col_post) : ProgRegs{0u, 0.0f};
   float csum = 0.0f;
   const bool fast = p.fast && p.full_vec_ok && p.n_in <= 4u && p.n_slots <= 8u && tile_m + 32u * TM <= a.m && tile_n + 32u * TN <= a.n;
   uint32_t qrow[QT], qcol[QT], qi[QT];
@@ -453,7 +454,7 @@ __global__ __launch_bounds__(kSmallThreads) void lt_gemm_small_kernel(const Gemm
       if (cols_mine) csum += small_colsum(b1v);
     }
   }
-  colp[threadIdx.x] = csum;
+  if (CS) colp[threadIdx.x] = csum;
   float* mine = Cs + wave * (32u * kSmallStride);   // (wave = kway * NB + block)
 #pragma unroll
   for (int r = 0; r < 16; ++r) mine[((uint32_t)(r >> 2) * 8u + h * 4u + (uint32_t)(r & 3)) * kSmallStride + x] = acc0[r] + acc1[r];
@@ -548,13 +549,13 @@ __global__ __launch_bounds__(kSmallThreads) void lt_gemm_small_kernel(const Gemm
   }
 }
 
-template <int TM, int TN>
+template <int TM, int TN, bool CS>
 static void launch_small_tile(const GemmArgs& a, bool av, bool bv, dim3 grid, hipStream_t s) {
   const dim3 block(kSmallThreads);
-  if (av && bv) LT_LAUNCH((lt_gemm_small_kernel<TM, TN, true, true>), grid, block, s, a);
-  else if (av) LT_LAUNCH((lt_gemm_small_kernel<TM, TN, true, false>), grid, block, s, a);
-  else if (bv) LT_LAUNCH((lt_gemm_small_kernel<TM, TN, false, true>), grid, block, s, a);
-  else LT_LAUNCH((lt_gemm_small_kernel<TM, TN, false, false>), grid, block, s, a);
+  if (av && bv) LT_LAUNCH((lt_gemm_small_kernel<TM, TN, true, true, CS>), grid, block, s, a);
+  else if (av) LT_LAUNCH((lt_gemm_small_kernel<TM, TN, true, false, CS>), grid, block, s, a);
+  else if (bv) LT_LAUNCH((lt_gemm_small_kernel<TM, TN, false, true, CS>), grid, block, s, a);
+  else LT_LAUNCH((lt_gemm_small_kernel<TM, TN, false, false, CS>), grid, block, s, a);
 }
 
 static hipError_t launch_small(const GemmArgs& args, hipStream_t s) {
@@ -569,17 +570,19 @@ static hipError_t launch_small(const GemmArgs& args, hipStream_t s) {
   if (a.splits == 0u || wgs * a.splits > 0x7fffffffull) return hipErrorInvalidValue;
   if (a.splits > 1u && (!a.split_ws || !a.tickets)) return hipErrorInvalidValue;
   // column sums ride along only with an unshared, unbatched product whose B is [k, n] with rows contiguous
-  if (a.col_sum && (a.splits != 1u || a.batch0 * a.batch1 != 1u || a.b.s_col != 1 || a.col_post.n_slots > 16u)) return hipErrorInvalidValue;
+  if (a.col_sum && (!t11 || a.splits != 1u || a.batch0 * a.batch1 != 1u || a.b.s_col != 1 || a.col_post.n_slots > 16u)) return hipErrorInvalidValue;
   if (wgs == 0u) return hipSuccess;
   auto whole = [&](const GemmOperand& o, bool k_contiguous, int64_t s_outer) {
     return k_contiguous && (a.k % 4u) == 0u && (((uintptr_t)o.ptr) & 15u) == 0u && (s_outer % 4) == 0 && (o.s_b0 % 4) == 0 && (o.s_b1 % 4) == 0;
   };
   const bool av = whole(a.a, a.a.s_col == 1, a.a.s_row), bv = whole(a.b, a.b.s_row == 1, a.b.s_col);
   const dim3 grid((uint32_t)(wgs * a.splits));
-  if (t11) launch_small_tile<1, 1>(a, av, bv, grid, s);
-  else launch_small_tile<2, 1>(a, av, bv, grid, s);
-  char name[56];
-  snprintf(name, sizeof(name), "lt_gemm_small_kernel<%u, %u, %s, %s>", a.tile_m / 32u, a.tile_n / 32u, av ? "true" : "false", bv ? "true" : "false");
+  if (t11 && a.col_sum) launch_small_tile<1, 1, true>(a, av, bv, grid, s);
+  else if (t11) launch_small_tile<1, 1, false>(a, av, bv, grid, s);
+  else launch_small_tile<2, 1, false>(a, av, bv, grid, s);
+  char name[64];
+  snprintf(name, sizeof(name), "lt_gemm_small_kernel<%u, %u, %s, %s, %s>", a.tile_m / 32u, a.tile_n / 32u, av ? "true" : "false", bv ? "true" : "false",
+           a.col_sum ? "true" : "false");
   note_kernel(name);
   return hipGetLastError();
 }

@@ -1241,7 +1241,7 @@ struct Lowering {
     Launch& pl = plan->launches[prev];
     if (pl.kind != L_GEMM || pl.args.size() != sizeof(ltk::GemmArgs)) return false;
     ltk::GemmArgs* ga = (ltk::GemmArgs*)pl.args.data();
-    if (!ga->direct || ga->splits != 1u || ga->col_sum || ga->batch0 * ga->batch1 != 1u || ga->in_dtype != ltk::kF32) return false;
+    if (!ga->direct || ga->tile_m != 32u || ga->tile_n != 32u || ga->splits != 1u || ga->col_sum || ga->batch0 * ga->batch1 != 1u || ga->in_dtype != ltk::kF32) return false;
     if (ga->k != (uint32_t)in_shape[0] || ga->n != (uint32_t)in_shape[1] || ga->b.s_col != 1 || ga->b.s_row != in_shape[1]) return false;
     if (pro.prog.n_code != 0u || pro.prog.n_in != 1u || pro.in_storage.size() != 1 || pro.prog.in[0].mode != ltk::kFull ||
         pro.prog.in[0].dtype != ltk::kF32 || !pro.scal_patch.empty() || post.prog.n_slots > 16u)

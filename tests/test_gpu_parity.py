@@ -672,7 +672,7 @@ def test_gemm_f32_small_one_launch(ctx, m, k, n, ta, tb, batch, variant):
         got = ctx.matmul(ctx.tensor(a), ctx.tensor(b), ta, tb)
         ctx.barrier()
         names = [l["kernel"] for l in ctx.last_launches()]
-        assert len(names) == 1 and names[0].startswith("lt_gemm_small_kernel<") and names[0].endswith(", %s>" % variant), names
+        assert len(names) == 1 and names[0].startswith("lt_gemm_small_kernel<") and names[0].endswith(", %s, false>" % variant), names
         check(ctx, E, got, E.matmul(E.tensor(a), E.tensor(b), ta, tb), TOL32, "product")
         again = ctx.matmul(ctx.tensor(a), ctx.tensor(b), ta, tb)
         assert np.array_equal(ctx.fetch(again), ctx.fetch(got))
@@ -719,7 +719,7 @@ def test_bias_gradient_rides_with_the_weight_gradient(ctx, m, k, n, mean):
         names = [l["kernel"] for l in ctx.last_launches()]
     finally:
         ctx.set_profiling(False)
-    assert info.n_regions == 2 and info.n_launches == 1 and names[0].startswith("lt_gemm_small_kernel"), (info.n_regions, names)
+    assert info.n_regions == 2 and info.n_launches == 1 and names[0].startswith("lt_gemm_small_kernel") and names[0].endswith(", true>"), (info.n_regions, names)
     for g, e in zip(got, prog(E)):
         check(ctx, E, g, e, TOL32 * max(1.0, (k / 64) ** 0.5))   # (sums of k terms: the bar of the column reductions)
 

@@ -318,9 +318,9 @@ __global__ __launch_bounds__(kGemmThreads, BM == 64 ? 2 : 1) void lt_gemm_kernel
 // of its four MFMAs is free as long as both operands agree, so a lane takes four CONSECUTIVE k
 // (4 h .. 4 h + 3): one 16-byte load where k is the operand's contiguous dimension, four 4-byte
 // loads that neighbouring lanes coalesce where it is not.  No LDS staging and no barrier in the
-// loop; kSmallG groups (64 k) are in flight per wave while the previous ones are multiplied.  The
-// eight partial tiles meet in LDS, are added in wave order, and the post program runs on the sum:
-// one launch.
+// loop; kSmallG groups (32 k) are in flight per wave while the previous ones are multiplied.  The
+// partial tiles of the waves meet in LDS, are added in a fixed order, and the post program runs on
+// the sum: one launch.  (A tile may also be two blocks of 32 x 32: then two times four waves.)
 // A long k over very few tiles (a batch of 8 rows against a 2048 x 2048 weight: 64 tiles) would
 // leave three quarters of the compute units idle and every wave with several dependent round trips
 // to memory, so there `splits` workgroups share a tile, each with a slice of k.  Their partial

@@ -651,6 +651,7 @@ SMALL_GEMMS = [  # m, k, n, ta, tb, batch, kernel variant (A, B fetched as whole
     (40, 1100, 50, False, False, (3,), "true, false"),    # batched
     (120, 1100, 2040, True, False, (), "false, false"),   # 256 tiles of 32 x 32: tiles of 64 x 32, two per tile, ragged
     (128, 2048, 2048, False, False, (), "true, false"),
+    (64, 2048, 2048, False, False, (), "true, false"),    # 128 tiles, two per tile
 ]
 
 
@@ -859,7 +860,7 @@ def test_c5_dynamic_shapes_and_host_control_flow(ctx):
     assert misses == len(seen)
 
 
-@pytest.mark.parametrize("batch,depth", [(8, 1), (8, 8), (256, 8), (1024, 1), (1024, 8)])
+@pytest.mark.parametrize("batch,depth", [(8, 1), (8, 8), (32, 4), (64, 8), (128, 8), (256, 8), (1024, 1), (1024, 8)])
 def test_c5_full_width(batch, depth):
     """The configured width (d = 2048) at the smallest, a middle and the largest batch size and at
     both ends of the depth range: the 64 x 64 and the 128 x 128 fp32 contraction tiles with the

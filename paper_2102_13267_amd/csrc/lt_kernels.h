@@ -213,5 +213,10 @@ struct SliceArgs {
   uint32_t window_only;
 };
 
+// Argument blocks travel by value in the kernel argument segment, which holds 4 KiB.
+static_assert(sizeof(EwArgs) <= 4096 && sizeof(RowArgs) <= 4096 && sizeof(AllArgs) <= 4096 && sizeof(ColArgs) <= 4096 &&
+                  sizeof(GemmArgs) <= 4096 && sizeof(SplitPostArgs) <= 4096 && sizeof(SliceArgs) <= 4096,
+              "a kernel's argument block must fit the kernel argument segment");
+
 }  // namespace ltk
 #endif  // LT_KERNELS_H_
